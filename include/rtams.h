@@ -1,0 +1,178 @@
+/*
+ * rtams.h - C ABI of the MI355X block-based inverted-list (IVF-Flat) index with
+ * real-time insertion, after arXiv 2408.02937 ("A Real-Time Adaptive
+ * Multi-Stream GPU System for Online Approximate Nearest Neighborhood Search").
+ *
+ * Conventions that hold for every entry point
+ * -------------------------------------------
+ * Pointers named d_* are DEVICE pointers (gfx950 HBM); everything else is host
+ * memory.  `hip_stream` is a hipStream_t passed as void* (NULL = the default
+ * stream).  add / search / rearrange / set_centroids only ENQUEUE work on that
+ * stream and return; inputs must stay alive, and outputs are valid, once the
+ * caller has synchronised the stream.  The library owns no device memory: the
+ * block pool and the search scratch are the caller's (section "Memory Block
+ * Based Real-time Vector Insertion Algorithm": one central pool, pre-split
+ * into blocks; section "Stream-Cached Multi-Stream Execution", consideration
+ * 1: no allocation or release while serving).  After rtams_create no entry
+ * point allocates or frees device memory.
+ * Every function returns RTAMS_OK or a negative rtams_status; nothing throws
+ * or aborts across this boundary.  rtams_last_error() gives a thread-local
+ * description of the last failure on the calling thread.
+ */
+#ifndef RTAMS_H
+#define RTAMS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rtams_index rtams_index; /* opaque, host side */
+
+enum rtams_metric {
+  RTAMS_L2 = 0, /* squared Euclidean distance, smaller is better */
+  RTAMS_IP = 1  /* inner product, larger is better */
+};
+
+enum rtams_status {
+  RTAMS_OK = 0,
+  RTAMS_EINVAL = -1,  /* bad argument */
+  RTAMS_ESTATE = -2,  /* centroids not set yet */
+  RTAMS_EPOOL = -3,   /* the block pool cannot hold the blocks this call may need */
+  RTAMS_EBUSY = -4,   /* every stream resource is in flight: request rejected */
+  RTAMS_EHIP = -5,    /* a HIP runtime call failed */
+  RTAMS_ESCRATCH = -6 /* a search needed more candidate scratch than one resource holds */
+};
+
+typedef struct rtams_config {
+  int32_t d;          /* vector dimension, multiple of 4 */
+  int32_t nlist;      /* number of inverted lists / centroids */
+  int32_t metric;     /* rtams_metric */
+  int32_t block_vecs; /* T_m: vectors per memory block, multiple of 64 */
+  int64_t rearrange_threshold; /* T_m' of Exceed(): vectors appended to a list since its
+                                  last rearrangement; <= 0 never triggers */
+  void *d_pool;       /* device memory carved into control data, tables and blocks */
+  size_t pool_bytes;
+  void *d_scratch;    /* device memory split evenly over the stream resources */
+  size_t scratch_bytes;
+  int32_t n_resources;   /* search requests that may be in flight at once (paper: 32) */
+  int32_t max_batch;     /* largest nq of one rtams_search call */
+  int32_t max_k;         /* largest k, at most 1024 */
+  int32_t max_nprobe;    /* largest nprobe, at most 1024 and at most nlist */
+  int32_t max_add_batch; /* vectors handled per internal insertion round; larger adds are
+                            split into rounds on the same stream */
+} rtams_config;
+
+typedef struct rtams_stats {
+  int64_t ntotal;           /* vectors visible to searches */
+  int64_t blocks_total;     /* |P| */
+  int64_t blocks_handed_out;/* cur_P: blocks the bump pointer has passed */
+  int64_t blocks_free;      /* blocks on the free list */
+  int64_t blocks_in_use;    /* blocks_handed_out - blocks_free */
+  int64_t block_bytes;      /* stride of one block: header + ids + vectors */
+  int64_t pool_bytes;
+  int64_t meta_bytes;       /* control data, centroids and tables in front of the blocks */
+  double utilisation;       /* blocks_in_use / blocks_total; the paper alerts above 0.9 */
+  int64_t lists_exceeding;  /* lists for which Exceed() currently holds */
+  int64_t table_entries_used, table_entries_total;
+} rtams_stats;
+
+/* Bytes of pool needed for `blocks` blocks under this configuration (d_pool and
+ * pool_bytes of cfg are ignored).  0 on bad arguments. */
+size_t rtams_pool_bytes_for(const rtams_config *cfg, int64_t blocks);
+
+/* Bytes of scratch one stream resource needs so that a search of max_batch
+ * queries may score `candidates_per_query` list entries per query. */
+size_t rtams_scratch_bytes_for(const rtams_config *cfg, int64_t candidates_per_query);
+
+/* Creates the index over caller-owned device memory (both regions 256-byte
+ * aligned).  Lays out the pool, clears its control data, creates the stream
+ * resources.  Synchronous. EINVAL when a size does not fit (rtams_last_error()
+ * says which). */
+int rtams_create(const rtams_config *cfg, rtams_index **out);
+
+/* Waits for the work this index enqueued, releases host resources.  The
+ * caller's device memory is left as it is. */
+int rtams_destroy(rtams_index *ix);
+
+/* Copies the centroids ([nlist][d] row-major fp32, device) into the pool.
+ * The paper takes them from k-means over the offline set (Insertion
+ * algorithm, inputs); producing them is the caller's business.  May be called
+ * once, before the first add. */
+int rtams_set_centroids(rtams_index *ix, const float *d_centroids, void *hip_stream);
+
+/* Insertion algorithm of the paper: nearest centroid of each vector, atomic
+ * reservation of the next slot of that list (did -> block did / T_m, offset
+ * did % T_m), lock-free opening and linking of the blocks that do not exist
+ * yet, in-place fill in the interleaved layout, and the Exceed() test.
+ * d_vecs [n][d] row-major fp32; d_ids [n] int64 or NULL (then the ids are
+ * ntotal .. ntotal+n-1 at the time of the call).  The batch becomes visible to
+ * searches as a whole, after its last vector is written.  All adds (and
+ * rearrangements) are ordered one after another: the paper's single data
+ * stream; a call on another stream than the previous one is ordered behind it
+ * with an event.  EPOOL (nothing enqueued) when the pool might overflow. */
+int rtams_add(rtams_index *ix, int64_t n, const float *d_vecs, const int64_t *d_ids,
+              void *hip_stream);
+
+/* Batched search (paper, introduction: the lists of the nprobe clusters most
+ * relevant to the query are scanned, the top-k returned; exact distances).
+ * d_queries [nq][d]; d_out_dist [nq][k] fp32 (squared L2, or inner product);
+ * d_out_ids [nq][k] int64.  Rows are ordered best first, ties by ascending id;
+ * missing results are id -1 with +inf (L2) / -inf (IP).  Takes one stream
+ * resource (scratch slice) for the duration of the request, Multi Stream
+ * Execution algorithm; EBUSY (nothing enqueued) when none is free.  Any number
+ * of host threads may search concurrently, each on its own stream.  A search
+ * sees whole insertion batches only. */
+int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k, int32_t nprobe,
+                 float *d_out_dist, int64_t *d_out_ids, void *hip_stream);
+
+/* Rearrangement algorithm of the paper: makes the blocks of `list` physically
+ * contiguous behind its first block by exchanging blocks with their physical
+ * neighbours; list == -1 handles every list for which Exceed() holds.
+ * Ordered with add on the data stream; searches keep running and see either
+ * placement, never a mixture. */
+int rtams_rearrange(rtams_index *ix, int32_t list, void *hip_stream);
+
+/* ---- introspection and test hooks; these synchronise the data stream ---- */
+
+int rtams_ntotal(rtams_index *ix, int64_t *out);
+int rtams_list_size(rtams_index *ix, int32_t list, int64_t *out);
+/* blocks of the list, physical runs ("header jumps" + 1, 0 for an empty list) and
+ * vectors appended since its last rearrangement */
+int rtams_list_info(rtams_index *ix, int32_t list, int64_t *blocks, int64_t *runs,
+                    int64_t *online);
+/* Logical content of one list in list order: d_ids [cap] and d_vecs [cap][d]
+ * row-major (either may be NULL); *n_out = list length; EINVAL if cap is too small. */
+int rtams_list_export(rtams_index *ix, int32_t list, int64_t cap, int64_t *d_ids, float *d_vecs,
+                      int64_t *n_out, void *hip_stream);
+/* Physical block numbers of the list's chain, in logical order (host array). */
+int rtams_list_chain(rtams_index *ix, int32_t list, int64_t cap, int32_t *chain, int64_t *n_out);
+/* Visible length of every list at once (host array [nlist]). */
+int rtams_list_sizes(rtams_index *ix, int64_t *out);
+int rtams_pool_stats(rtams_index *ix, rtams_stats *out);
+/* Device-side check of the block structure (chain lengths, header links, table
+ * against headers, no block owned twice, free list disjoint from chains).
+ * Returns RTAMS_OK or RTAMS_EINVAL with the violation in rtams_last_error(). */
+int rtams_validate(rtams_index *ix, void *hip_stream);
+/* Probed lists of each query, best first (d_out [nq][nprobe] int32, device). */
+int rtams_probe(rtams_index *ix, int64_t nq, const float *d_queries, int32_t nprobe,
+                int32_t *d_out, void *hip_stream);
+/* Nearest centroid of each vector (d_out [n] int32, device), nothing inserted. */
+int rtams_assign(rtams_index *ix, int64_t n, const float *d_vecs, int32_t *d_out,
+                 void *hip_stream);
+
+/* Sticky asynchronous error raised by a kernel (pool overflow, scratch
+ * overflow); RTAMS_OK if none.  Does not synchronise. */
+int rtams_poll_error(rtams_index *ix);
+const char *rtams_last_error(void);
+/* Launch-shape knobs ("restrict the number of blocks and threads per kernel",
+ * Stream-Cached Multi-Stream Execution, consideration 2).  key: "scan_max_workgroups",
+ * "scan_split_target".  EINVAL for an unknown key. */
+int rtams_set_param(rtams_index *ix, const char *key, int64_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RTAMS_H */

@@ -1,0 +1,156 @@
+// Coarse quantizer: score of every (vector, centroid) pair in the one fixed
+// arithmetic that decides list membership and probe choice (IEEE double, one
+// fused multiply-add per dimension, dimensions in ascending order), so that the
+// integer decisions are reproducible bit for bit.  Insertion algorithm of the
+// paper, step "k <- min(c, y_i)", and the first stage of search.
+#include "rtams_launch.h"
+
+namespace rtams {
+
+constexpr int kCoarseThreads = 256;
+
+int coarse_vt(int d) { return d <= 1024 ? 8 : 4; }
+
+// How many workgroups share the centroids of one vector tile, so that a small
+// batch still spreads over the chip.
+int coarse_splits(const Dev &D, int64_t n, size_t part_cap) {
+  int vt = coarse_vt(D.d);
+  int64_t tiles = (n + vt - 1) / vt;
+  int max_s = (D.nlist + kCoarseThreads - 1) / kCoarseThreads;
+  int64_t want = (1024 + tiles - 1) / tiles;
+  int64_t s = want < 1 ? 1 : want;
+  if (s > max_s) s = max_s;
+  if (part_cap && (size_t)(s * n) > part_cap) s = (int64_t)(part_cap / (size_t)n);
+  if (s < 1) s = 1;
+  return (int)s;
+}
+
+// is score a better than b, ties to the lower index
+__device__ inline bool better_pair(int metric, double a, int ia, double b, int ib) {
+  if (a != b) return metric == 0 ? (a < b) : (a > b);
+  return ia < ib;
+}
+
+// One workgroup: VT vectors (converted to double in LDS) against a range of
+// centroids, one centroid row per thread at a time.  ARGMIN selects the
+// epilogue: the best centroid of the range per vector, or all scores.
+template <int METRIC, int VT, bool ARGMIN>
+__global__ __launch_bounds__(kCoarseThreads) void k_coarse(
+    Dev D, int64_t n, const float *__restrict__ Y, int splits, double *__restrict__ scores,
+    double *__restrict__ pscore, int32_t *__restrict__ pidx, unsigned long long *cursor_to_clear) {
+  extern __shared__ double ylds[];  // [VT][d]
+  __shared__ double red_s[kCoarseThreads];
+  __shared__ int red_i[kCoarseThreads];
+  const int d = D.d, d4 = D.d4;
+  const int64_t v0 = (int64_t)blockIdx.x * VT;
+  const int split = blockIdx.y;
+  if (cursor_to_clear && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *cursor_to_clear = 0ull;
+
+  for (int t = threadIdx.x; t < VT * d; t += kCoarseThreads) {
+    int v = t / d, j = t - v * d;
+    int64_t row = v0 + v;
+    ylds[t] = row < n ? (double)Y[row * d + j] : 0.0;
+  }
+  __syncthreads();
+
+  // centroid range of this split, in units of one row per thread
+  const int per = ((D.nlist + splits - 1) / splits + kCoarseThreads - 1) / kCoarseThreads * kCoarseThreads;
+  const int c_begin = split * per;
+  const int c_end = min(D.nlist, c_begin + per);
+
+  double best_s[VT];
+  int best_i[VT];
+#pragma unroll
+  for (int v = 0; v < VT; ++v) { best_s[v] = 0.0; best_i[v] = -1; }
+
+  const float4 *C4 = reinterpret_cast<const float4 *>(D.centroids);
+  for (int c = c_begin + threadIdx.x; c < c_end; c += kCoarseThreads) {
+    double acc[VT];
+#pragma unroll
+    for (int v = 0; v < VT; ++v) acc[v] = 0.0;
+    const float4 *row = C4 + (size_t)c * d4;
+    for (int j4 = 0; j4 < d4; ++j4) {
+      float4 cv = row[j4];
+      double c0 = (double)cv.x, c1 = (double)cv.y, c2 = (double)cv.z, c3 = (double)cv.w;
+#pragma unroll
+      for (int v = 0; v < VT; ++v) {
+        const double *y = ylds + v * d + 4 * j4;
+        if (METRIC == 0) {
+          double t0 = y[0] - c0; acc[v] = __builtin_fma(t0, t0, acc[v]);
+          double t1 = y[1] - c1; acc[v] = __builtin_fma(t1, t1, acc[v]);
+          double t2 = y[2] - c2; acc[v] = __builtin_fma(t2, t2, acc[v]);
+          double t3 = y[3] - c3; acc[v] = __builtin_fma(t3, t3, acc[v]);
+        } else {
+          acc[v] = __builtin_fma(y[0], c0, acc[v]);
+          acc[v] = __builtin_fma(y[1], c1, acc[v]);
+          acc[v] = __builtin_fma(y[2], c2, acc[v]);
+          acc[v] = __builtin_fma(y[3], c3, acc[v]);
+        }
+      }
+    }
+    if (ARGMIN) {
+#pragma unroll
+      for (int v = 0; v < VT; ++v)
+        if (best_i[v] < 0 || better_pair(METRIC, acc[v], c, best_s[v], best_i[v])) {
+          best_s[v] = acc[v]; best_i[v] = c;
+        }
+    } else {
+#pragma unroll
+      for (int v = 0; v < VT; ++v)
+        if (v0 + v < n) scores[(size_t)(v0 + v) * D.nlist + c] = acc[v];
+    }
+  }
+
+  if (ARGMIN) {
+#pragma unroll
+    for (int v = 0; v < VT; ++v) {
+      __syncthreads();
+      red_s[threadIdx.x] = best_s[v];
+      red_i[threadIdx.x] = best_i[v];
+      __syncthreads();
+      for (int w = kCoarseThreads / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) {
+          int ib = red_i[threadIdx.x + w];
+          double sb = red_s[threadIdx.x + w];
+          int ia = red_i[threadIdx.x];
+          if (ib >= 0 && (ia < 0 || better_pair(METRIC, sb, ib, red_s[threadIdx.x], ia))) {
+            red_s[threadIdx.x] = sb; red_i[threadIdx.x] = ib;
+          }
+        }
+        __syncthreads();
+      }
+      if (threadIdx.x == 0 && v0 + v < n) {
+        pscore[(size_t)(v0 + v) * splits + split] = red_s[0];
+        pidx[(size_t)(v0 + v) * splits + split] = red_i[0];
+      }
+    }
+  }
+}
+
+template <bool ARGMIN>
+static void launch_coarse(const Dev &D, int64_t n, const float *Y, int splits, double *scores,
+                          double *pscore, int32_t *pidx, unsigned long long *cursor, hipStream_t s) {
+  if (n <= 0) return;
+  int vt = coarse_vt(D.d);
+  dim3 grid((unsigned)((n + vt - 1) / vt), (unsigned)splits);
+  size_t lds = (size_t)vt * D.d * sizeof(double);
+#define RTAMS_GO(M, V) \
+  hipLaunchKernelGGL((k_coarse<M, V, ARGMIN>), grid, dim3(kCoarseThreads), lds, s, D, n, Y, splits, \
+                     scores, pscore, pidx, cursor)
+  if (D.metric == 0) { if (vt == 8) RTAMS_GO(0, 8); else RTAMS_GO(0, 4); }
+  else               { if (vt == 8) RTAMS_GO(1, 8); else RTAMS_GO(1, 4); }
+#undef RTAMS_GO
+}
+
+void launch_coarse_scores(const Dev &D, int64_t n, const float *Y, double *scores,
+                          unsigned long long *cursor_to_clear, hipStream_t s) {
+  int splits = coarse_splits(D, n, 0);
+  launch_coarse<false>(D, n, Y, splits, scores, nullptr, nullptr, cursor_to_clear, s);
+}
+
+void launch_coarse_argmin(const Dev &D, int64_t n, const float *Y, int splits, double *pscore,
+                          int32_t *pidx, hipStream_t s) {
+  launch_coarse<true>(D, n, Y, splits, nullptr, pscore, pidx, nullptr, s);
+}
+
+}  // namespace rtams

@@ -1,0 +1,137 @@
+// Introspection kernels: export of a list in logical order, chain copy, chain
+// statistics and a structural check of the block pool.
+#include "rtams_launch.h"
+
+namespace rtams {
+
+// thread (position, chunk): un-interleaves one float4 of one vector
+__global__ __launch_bounds__(256) void k_export(Dev D, int list, int64_t n, int64_t *__restrict__ ids,
+                                                float *__restrict__ vecs) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n * D.d4) return;
+  int64_t pos = t / D.d4;
+  int c = (int)(t - pos * D.d4);
+  uint32_t mid = (uint32_t)(pos / D.T_m), moff = (uint32_t)(pos % D.T_m);
+  uint32_t b = (uint32_t)*table_entry(D, list, mid);
+  if (vecs) reinterpret_cast<float4 *>(vecs)[pos * D.d4 + c] = block_vecs(D, b)[vec_chunk_index(D, moff, c)];
+  if (ids && c == 0) ids[pos] = block_ids(D, b)[moff];
+}
+
+__global__ void k_chain_copy(Dev D, int list, int32_t *__restrict__ out) {
+  uint32_t nb = D.nblk[list];
+  for (uint32_t t = blockIdx.x * blockDim.x + threadIdx.x; t < nb; t += gridDim.x * blockDim.x)
+    out[t] = *table_entry(D, list, t);
+}
+
+// out4 = {blocks, physical runs, vectors since the last rearrangement, visible length}
+__global__ void k_list_info(Dev D, int list, int32_t *out4) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  uint32_t len = D.visible_len[list];
+  uint32_t nb = (len + D.T_m - 1) / D.T_m;
+  int runs = nb > 0 ? 1 : 0;
+  int32_t prev = nb > 0 ? *table_entry(D, list, 0) : -1;
+  for (uint32_t t = 1; t < nb; ++t) {
+    int32_t b = *table_entry(D, list, t);
+    if (b != prev + 1) ++runs;
+    prev = b;
+  }
+  out4[0] = (int32_t)nb;
+  out4[1] = runs;
+  out4[2] = (int32_t)D.online[list];
+  out4[3] = (int32_t)len;
+}
+
+// ---- structural check.  result2 = {code, argument}; code 0 = consistent.
+enum {
+  V_OK = 0,
+  V_LEN_MISMATCH = 1,    // reserved != visible at rest
+  V_NBLK = 2,            // blocks in chain != ceil(len / T_m)
+  V_RANGE = 3,           // table entry outside the handed-out range
+  V_OWNER = 4,           // header owner / seq disagree with the table
+  V_LINK = 5,            // prev / next disagree with the table
+  V_SIZE = 6,            // header size disagrees with the list length
+  V_TWICE = 7,           // block reachable twice (two chains, or chain and free stack)
+  V_COUNT = 8,           // blocks in chains + free stack != cur_P
+  V_NTOTAL = 9           // sum of list lengths != ntotal
+};
+
+__device__ inline void report(int32_t *result2, int code, int arg) {
+  if (atomicCAS(&result2[0], 0, code) == 0) result2[1] = arg;
+}
+
+__global__ void k_validate_clear(Dev D, int32_t *result2, unsigned long long *sums) {
+  uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t == 0) { result2[0] = 0; result2[1] = 0; sums[0] = 0; sums[1] = 0; }
+  for (uint32_t b = t; b < D.nblocks; b += gridDim.x * blockDim.x) D.mark[b] = 0;
+}
+
+__global__ void k_validate_lists(Dev D, int32_t *result2, unsigned long long *sums) {
+  int list = blockIdx.x * blockDim.x + threadIdx.x;
+  if (list >= D.nlist) return;
+  const uint32_t T = (uint32_t)D.T_m;
+  uint32_t len = D.visible_len[list];
+  if (D.reserved_len[list] != len) report(result2, V_LEN_MISMATCH, list);
+  uint32_t nb = D.nblk[list];
+  if (nb != (len + T - 1) / T) { report(result2, V_NBLK, list); return; }
+  uint32_t cur = D.ctrl->cur_P;
+  int32_t prev = -1;
+  for (uint32_t t = 0; t < nb; ++t) {
+    int32_t b = *table_entry(D, list, t);
+    if (b < 0 || (uint32_t)b >= cur || (uint32_t)b >= D.nblocks) { report(result2, V_RANGE, list); return; }
+    const BlockHeader *h = block_header(D, (uint32_t)b);
+    if (h->owner != list || h->seq != (int32_t)t || h->capacity != (int32_t)T) report(result2, V_OWNER, list);
+    if (h->prev != prev) report(result2, V_LINK, list);
+    int32_t nxt = t + 1 < nb ? *table_entry(D, list, t + 1) : -1;
+    if (h->next != nxt) report(result2, V_LINK, list);
+    uint32_t sz = len - t * T < T ? len - t * T : T;
+    if (h->size != (int32_t)sz) report(result2, V_SIZE, list);
+    if (atomicAdd(&D.mark[b], 1) != 0) report(result2, V_TWICE, b);
+    prev = b;
+  }
+  atomicAdd(&sums[0], (unsigned long long)nb);
+  atomicAdd(&sums[1], (unsigned long long)len);
+}
+
+__global__ void k_validate_free(Dev D, int32_t *result2, unsigned long long *sums) {
+  int ft = D.ctrl->free_top;
+  uint32_t cur = D.ctrl->cur_P;
+  for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < ft; t += gridDim.x * blockDim.x) {
+    int32_t b = D.free_stack[t];
+    if (b < 0 || (uint32_t)b >= cur) { report(result2, V_RANGE, -1); continue; }
+    if (atomicAdd(&D.mark[b], 1) != 0) report(result2, V_TWICE, b);
+  }
+}
+
+__global__ void k_validate_totals(Dev D, int32_t *result2, unsigned long long *sums) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  int ft = D.ctrl->free_top;
+  if (sums[0] + (unsigned long long)(ft > 0 ? ft : 0) != D.ctrl->cur_P) report(result2, V_COUNT, 0);
+  if (sums[1] != D.ctrl->ntotal) report(result2, V_NTOTAL, 0);
+}
+
+void launch_export(const Dev &D, int list, int64_t n, int64_t *ids, float *vecs, hipStream_t s) {
+  if (n <= 0) return;
+  int64_t threads = n * D.d4;
+  hipLaunchKernelGGL(k_export, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, D, list, n,
+                     ids, vecs);
+}
+
+void launch_chain_copy(const Dev &D, int list, int32_t *out, hipStream_t s) {
+  hipLaunchKernelGGL(k_chain_copy, dim3(64), dim3(256), 0, s, D, list, out);
+}
+
+void launch_list_info(const Dev &D, int list, int32_t *out4, hipStream_t s) {
+  hipLaunchKernelGGL(k_list_info, dim3(1), dim3(64), 0, s, D, list, out4);
+}
+
+// result2 is followed in memory by two 64-bit sums (16 bytes further on)
+void launch_validate(const Dev &D, int32_t *result2, hipStream_t s) {
+  unsigned long long *sums = reinterpret_cast<unsigned long long *>(result2 + 4);
+  hipLaunchKernelGGL(k_validate_clear, dim3(256), dim3(256), 0, s, D, result2, sums);
+  hipLaunchKernelGGL(k_validate_lists, dim3((unsigned)((D.nlist + 255) / 256)), dim3(256), 0, s, D,
+                     result2, sums);
+  hipLaunchKernelGGL(k_validate_free, dim3(64), dim3(256), 0, s, D, result2, sums);
+  hipLaunchKernelGGL(k_validate_totals, dim3(1), dim3(64), 0, s, D, result2, sums);
+}
+
+}  // namespace rtams

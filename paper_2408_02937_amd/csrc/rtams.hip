@@ -1,0 +1,609 @@
+// Host side of the C ABI declared in include/rtams.h: pool layout, stream
+// resources, and the enqueue-only entry points.
+#include "../../include/rtams.h"
+
+#include <atomic>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+
+#include "rtams_launch.h"
+
+using namespace rtams;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                  \
+  do {                                                                                 \
+    hipError_t e_ = (expr);                                                            \
+    if (e_ != hipSuccess)                                                              \
+      return fail(RTAMS_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_));          \
+  } while (0)
+
+inline size_t up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Byte offsets of everything in front of the blocks.
+struct Layout {
+  size_t ctrl, hook, centroids, reserved_len, visible_len, online, nblk, exceed, seg_dir;
+  size_t ins_assign, ins_did, ins_pscore, ins_pidx, part_cap;
+  size_t fixed_end;          // end of the part that does not depend on the block count
+  size_t slab, free_stack, mark, blocks;
+  size_t block_stride;
+  uint32_t ids_off, vec_off;
+  uint64_t slab_cap;
+  int64_t nblocks;
+  size_t total;
+};
+
+constexpr size_t kAlign = 256;
+constexpr size_t kHookBytes = 256;
+
+bool config_ok(const rtams_config *c, bool need_memory) {
+  if (!c) return fail(RTAMS_EINVAL, "config is NULL"), false;
+  if (c->d <= 0 || c->d % 4 != 0 || c->d > 2048)
+    return fail(RTAMS_EINVAL, "d must be a multiple of 4 in 4..2048, got %d", c->d), false;
+  if (c->nlist <= 0) return fail(RTAMS_EINVAL, "nlist must be positive"), false;
+  if (c->metric != RTAMS_L2 && c->metric != RTAMS_IP) return fail(RTAMS_EINVAL, "unknown metric"), false;
+  if (c->block_vecs <= 0 || c->block_vecs % kWave != 0)
+    return fail(RTAMS_EINVAL, "block_vecs must be a positive multiple of 64, got %d", c->block_vecs), false;
+  if (c->n_resources < 1 || c->n_resources > 256)
+    return fail(RTAMS_EINVAL, "n_resources must be in 1..256"), false;
+  if (c->max_batch < 1) return fail(RTAMS_EINVAL, "max_batch must be positive"), false;
+  if (c->max_k < 1 || c->max_k > kMaxK) return fail(RTAMS_EINVAL, "max_k must be in 1..%d", kMaxK), false;
+  if (c->max_nprobe < 1 || c->max_nprobe > kMaxNprobe || c->max_nprobe > c->nlist)
+    return fail(RTAMS_EINVAL, "max_nprobe must be in 1..min(nlist, %d)", kMaxNprobe), false;
+  if (c->max_add_batch < 1) return fail(RTAMS_EINVAL, "max_add_batch must be positive"), false;
+  if (need_memory) {
+    if (!c->d_pool || !c->d_scratch) return fail(RTAMS_EINVAL, "pool and scratch must be given"), false;
+    if (((uintptr_t)c->d_pool | (uintptr_t)c->d_scratch) % kAlign)
+      return fail(RTAMS_EINVAL, "pool and scratch must be %zu-byte aligned", kAlign), false;
+  }
+  return true;
+}
+
+// Fixed part first; then, given a byte budget (blocks < 0) or a block count, the rest.
+void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L) {
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = up(o + bytes, kAlign); return at; };
+  const size_t nl = (size_t)c->nlist;
+  L->ctrl = take(sizeof(Ctrl));
+  L->hook = take(kHookBytes);
+  L->centroids = take(nl * c->d * sizeof(float));
+  L->reserved_len = take(nl * 4);
+  L->visible_len = take(nl * 4);
+  L->online = take(nl * 4);
+  L->nblk = take(nl * 4);
+  L->exceed = take(nl);
+  L->seg_dir = take(nl * kTableSegs * 4);
+  L->part_cap = (size_t)c->max_add_batch * 2 > 65536 ? (size_t)c->max_add_batch * 2 : 65536;
+  L->ins_assign = take((size_t)c->max_add_batch * 4);
+  L->ins_did = take((size_t)c->max_add_batch * 4);
+  L->ins_pscore = take(L->part_cap * 8);
+  L->ins_pidx = take(L->part_cap * 4);
+  L->fixed_end = o;
+  L->ids_off = kHeaderBytes;
+  L->vec_off = kHeaderBytes + (uint32_t)c->block_vecs * 8u;
+  L->block_stride = up((size_t)L->vec_off + (size_t)c->block_vecs * c->d * 4, kAlign);
+  if (blocks < 0) {
+    // per block: the block itself, 2 table entries, a free-stack entry and a mark
+    size_t slack = 4 * kAlign + nl * kTableBase * 4;
+    size_t per = L->block_stride + 16;
+    blocks = pool_bytes > o + slack ? (int64_t)((pool_bytes - o - slack) / per) : 0;
+    if (blocks > 0x7fffffff) blocks = 0x7fffffff;
+  }
+  L->nblocks = blocks;
+  L->slab_cap = 2ull * (uint64_t)blocks + (uint64_t)nl * kTableBase;
+  L->slab = take((size_t)L->slab_cap * 4);
+  L->free_stack = take((size_t)blocks * 4);
+  L->mark = take((size_t)blocks * 4);
+  L->blocks = o;
+  L->total = o + (size_t)blocks * L->block_stride;
+}
+
+struct ScratchLayout {
+  size_t scores, probe_list, probe_len, probe_off, qbase, qtotal, cursor, cand, fixed;
+};
+
+void lay_out_scratch(const rtams_config *c, ScratchLayout *S) {
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = up(o + bytes, kAlign); return at; };
+  size_t mb = (size_t)c->max_batch, mp = (size_t)c->max_nprobe;
+  S->scores = take(mb * c->nlist * 8);
+  S->probe_list = take(mb * mp * 4);
+  S->probe_len = take(mb * mp * 4);
+  S->probe_off = take(mb * mp * 4);
+  S->qbase = take(mb * 8);
+  S->qtotal = take(mb * 4);
+  S->cursor = take(8);
+  S->cand = o;
+  S->fixed = o;
+}
+
+enum { RES_FREE = 0, RES_BUSY = 1, RES_PENDING = 2 };
+
+struct Resource {
+  std::atomic<int> state{RES_FREE};
+  hipEvent_t done = nullptr;
+  SearchScratch s{};
+};
+
+}  // namespace
+
+struct rtams_index {
+  rtams_config cfg{};
+  Layout lay{};
+  Dev dev{};
+  InsertScratch ins{};
+  HostMirror *mirror = nullptr;
+  char *hook = nullptr;  // device scratch of the introspection calls
+  Resource *res = nullptr;
+  int n_res = 0;
+  bool has_centroids = false;
+  std::mutex data_mutex;  // add / rearrange / hooks: the single data stream of the paper
+  hipStream_t data_stream = nullptr;
+  bool have_data_stream = false;
+  hipEvent_t data_done = nullptr;
+  int64_t ntotal_host = 0;   // vectors handed to add so far
+  int64_t avail_lb = 0;      // lower bound of the blocks still available in the pool
+  std::atomic<int64_t> scan_split_target{2048};
+  std::atomic<int64_t> scan_max_workgroups{0};
+};
+
+namespace {
+
+int sync_data(rtams_index *ix) {
+  if (ix->have_data_stream) HIP_TRY(hipStreamSynchronize(ix->data_stream));
+  return RTAMS_OK;
+}
+
+// Orders this call behind the previous work of the data stream.
+int enter_data_stream(rtams_index *ix, hipStream_t s) {
+  if (ix->have_data_stream && ix->data_stream != s) HIP_TRY(hipStreamWaitEvent(s, ix->data_done, 0));
+  ix->data_stream = s;
+  ix->have_data_stream = true;
+  return RTAMS_OK;
+}
+
+int leave_data_stream(rtams_index *ix, hipStream_t s) {
+  HIP_TRY(hipEventRecord(ix->data_done, s));
+  return RTAMS_OK;
+}
+
+int acquire(rtams_index *ix) {
+  for (int r = 0; r < ix->n_res; ++r) {
+    int st = ix->res[r].state.load(std::memory_order_acquire);
+    if (st == RES_FREE) {
+      if (ix->res[r].state.compare_exchange_strong(st, RES_BUSY, std::memory_order_acq_rel)) return r;
+    } else if (st == RES_PENDING) {
+      if (hipEventQuery(ix->res[r].done) == hipSuccess &&
+          ix->res[r].state.compare_exchange_strong(st, RES_BUSY, std::memory_order_acq_rel))
+        return r;
+    }
+  }
+  (void)hipGetLastError();  // hipEventQuery leaves hipErrorNotReady behind
+  return -1;
+}
+
+int read_ctrl(rtams_index *ix, Ctrl *out) {
+  HIP_TRY(hipMemcpy(out, ix->dev.ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost));
+  return RTAMS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *rtams_last_error(void) { return g_err; }
+
+size_t rtams_pool_bytes_for(const rtams_config *cfg, int64_t blocks) {
+  if (!config_ok(cfg, false) || blocks < 0) return 0;
+  Layout L;
+  lay_out(cfg, blocks, 0, &L);
+  return up(L.total + 4 * kAlign + (size_t)cfg->nlist * kTableBase * 4, kAlign);
+}
+
+size_t rtams_scratch_bytes_for(const rtams_config *cfg, int64_t candidates_per_query) {
+  if (!config_ok(cfg, false) || candidates_per_query < 0) return 0;
+  ScratchLayout S;
+  lay_out_scratch(cfg, &S);
+  return up(S.fixed + (size_t)cfg->max_batch * (size_t)candidates_per_query * 4, kAlign);
+}
+
+int rtams_create(const rtams_config *cfg, rtams_index **out) {
+  if (!out) return fail(RTAMS_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (!config_ok(cfg, true)) return RTAMS_EINVAL;
+  Layout L;
+  lay_out(cfg, -1, cfg->pool_bytes, &L);
+  if (L.nblocks < 1 || L.total > cfg->pool_bytes)
+    return fail(RTAMS_EINVAL, "pool of %zu bytes holds no block (control data needs %zu, a block %zu)",
+                cfg->pool_bytes, L.fixed_end, L.block_stride);
+  ScratchLayout SL;
+  lay_out_scratch(cfg, &SL);
+  size_t slice = cfg->scratch_bytes / (size_t)cfg->n_resources / kAlign * kAlign;
+  if (slice < SL.fixed + kAlign)
+    return fail(RTAMS_EINVAL, "scratch slice of %zu bytes is smaller than its fixed part %zu", slice,
+                SL.fixed + kAlign);
+
+  rtams_index *ix = new (std::nothrow) rtams_index();
+  if (!ix) return fail(RTAMS_EINVAL, "out of host memory");
+  ix->cfg = *cfg;
+  ix->lay = L;
+  char *base = static_cast<char *>(cfg->d_pool);
+  Dev &D = ix->dev;
+  D.d = cfg->d; D.nlist = cfg->nlist; D.metric = cfg->metric; D.T_m = cfg->block_vecs;
+  D.d4 = cfg->d / 4;
+  D.groups_per_block = cfg->block_vecs / kWave;
+  D.nblocks = (uint32_t)L.nblocks;
+  D.slab_cap = (uint32_t)(L.slab_cap > 0xffffffffull ? 0xffffffffull : L.slab_cap);
+  D.T_mp = cfg->rearrange_threshold;
+  D.block_stride = L.block_stride;
+  D.ids_off = L.ids_off; D.vec_off = L.vec_off;
+  D.blocks = base + L.blocks;
+  D.ctrl = reinterpret_cast<Ctrl *>(base + L.ctrl);
+  D.centroids = reinterpret_cast<float *>(base + L.centroids);
+  D.reserved_len = reinterpret_cast<uint32_t *>(base + L.reserved_len);
+  D.visible_len = reinterpret_cast<uint32_t *>(base + L.visible_len);
+  D.online = reinterpret_cast<uint32_t *>(base + L.online);
+  D.nblk = reinterpret_cast<uint32_t *>(base + L.nblk);
+  D.exceed = reinterpret_cast<uint8_t *>(base + L.exceed);
+  D.seg_dir = reinterpret_cast<int32_t *>(base + L.seg_dir);
+  D.slab = reinterpret_cast<int32_t *>(base + L.slab);
+  D.free_stack = reinterpret_cast<int32_t *>(base + L.free_stack);
+  D.mark = reinterpret_cast<int32_t *>(base + L.mark);
+  ix->hook = base + L.hook;
+  ix->ins.assign = reinterpret_cast<int32_t *>(base + L.ins_assign);
+  ix->ins.did = reinterpret_cast<uint32_t *>(base + L.ins_did);
+  ix->ins.pscore = reinterpret_cast<double *>(base + L.ins_pscore);
+  ix->ins.pidx = reinterpret_cast<int32_t *>(base + L.ins_pidx);
+  ix->ins.part_cap = L.part_cap;
+  ix->avail_lb = L.nblocks;
+
+  auto bail = [&](int code) { rtams_destroy(ix); return code; };
+  // control data: everything in front of the blocks starts at zero, table directory at -1
+  if (hipMemset(base, 0, L.blocks) != hipSuccess) return bail(fail(RTAMS_EHIP, "hipMemset of control data failed"));
+  if (hipMemset(D.seg_dir, 0xff, (size_t)cfg->nlist * kTableSegs * 4) != hipSuccess)
+    return bail(fail(RTAMS_EHIP, "hipMemset of the table directory failed"));
+  void *hm = nullptr;
+  if (hipHostMalloc(&hm, sizeof(HostMirror), hipHostMallocMapped) != hipSuccess)
+    return bail(fail(RTAMS_EHIP, "hipHostMalloc failed"));
+  ix->mirror = static_cast<HostMirror *>(hm);
+  memset(hm, 0, sizeof(HostMirror));
+  void *dm = nullptr;
+  if (hipHostGetDevicePointer(&dm, hm, 0) != hipSuccess) return bail(fail(RTAMS_EHIP, "hipHostGetDevicePointer failed"));
+  D.mirror = static_cast<HostMirror *>(dm);
+  if (hipEventCreateWithFlags(&ix->data_done, hipEventDisableTiming) != hipSuccess)
+    return bail(fail(RTAMS_EHIP, "hipEventCreate failed"));
+
+  ix->res = new (std::nothrow) Resource[cfg->n_resources];
+  if (!ix->res) return bail(fail(RTAMS_EINVAL, "out of host memory"));
+  ix->n_res = cfg->n_resources;
+  char *sb = static_cast<char *>(cfg->d_scratch);
+  for (int r = 0; r < ix->n_res; ++r) {
+    char *p = sb + (size_t)r * slice;
+    SearchScratch &S = ix->res[r].s;
+    S.scores = reinterpret_cast<double *>(p + SL.scores);
+    S.probe_list = reinterpret_cast<int32_t *>(p + SL.probe_list);
+    S.probe_len = reinterpret_cast<uint32_t *>(p + SL.probe_len);
+    S.probe_off = reinterpret_cast<uint32_t *>(p + SL.probe_off);
+    S.qbase = reinterpret_cast<unsigned long long *>(p + SL.qbase);
+    S.qtotal = reinterpret_cast<uint32_t *>(p + SL.qtotal);
+    S.cursor = reinterpret_cast<unsigned long long *>(p + SL.cursor);
+    S.cand = reinterpret_cast<float *>(p + SL.cand);
+    S.cand_cap = (slice - SL.fixed) / 4;
+    if (hipEventCreateWithFlags(&ix->res[r].done, hipEventDisableTiming) != hipSuccess)
+      return bail(fail(RTAMS_EHIP, "hipEventCreate failed"));
+  }
+  if (hipDeviceSynchronize() != hipSuccess) return bail(fail(RTAMS_EHIP, "hipDeviceSynchronize failed"));
+  *out = ix;
+  return RTAMS_OK;
+}
+
+int rtams_destroy(rtams_index *ix) {
+  if (!ix) return RTAMS_OK;
+  if (ix->have_data_stream) (void)hipStreamSynchronize(ix->data_stream);
+  for (int r = 0; r < ix->n_res; ++r)
+    if (ix->res[r].done) { (void)hipEventSynchronize(ix->res[r].done); (void)hipEventDestroy(ix->res[r].done); }
+  delete[] ix->res;
+  if (ix->data_done) (void)hipEventDestroy(ix->data_done);
+  if (ix->mirror) (void)hipHostFree((void *)ix->mirror);
+  delete ix;
+  return RTAMS_OK;
+}
+
+int rtams_set_centroids(rtams_index *ix, const float *d_centroids, void *hip_stream) {
+  if (!ix || !d_centroids) return fail(RTAMS_EINVAL, "NULL argument");
+  std::lock_guard<std::mutex> g(ix->data_mutex);
+  if (ix->ntotal_host > 0) return fail(RTAMS_ESTATE, "centroids cannot change once vectors are in");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  int rc = enter_data_stream(ix, s);
+  if (rc) return rc;
+  HIP_TRY(hipMemcpyAsync(ix->dev.centroids, d_centroids, (size_t)ix->cfg.nlist * ix->cfg.d * 4,
+                         hipMemcpyDeviceToDevice, s));
+  ix->has_centroids = true;
+  return leave_data_stream(ix, s);
+}
+
+int rtams_add(rtams_index *ix, int64_t n, const float *d_vecs, const int64_t *d_ids, void *hip_stream) {
+  if (!ix || n < 0 || (n > 0 && !d_vecs)) return fail(RTAMS_EINVAL, "bad argument to add");
+  if (!ix->has_centroids) return fail(RTAMS_ESTATE, "add before set_centroids");
+  if (n == 0) return RTAMS_OK;
+  std::lock_guard<std::mutex> g(ix->data_mutex);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const Dev &D = ix->dev;
+  if (ix->mirror->error == RTAMS_EPOOL) return fail(RTAMS_EPOOL, "the pool overflowed earlier; index is read-only");
+
+  // Upper bound of the blocks this batch can open: one partly filled block per
+  // touched list plus the full ones.
+  int64_t need = (n < D.nlist ? n : D.nlist) + n / D.T_m;
+  if (need > ix->avail_lb) {  // tighten the bound from the device's own counters
+    int rc = sync_data(ix);
+    if (rc) return rc;
+    Ctrl c;
+    if ((rc = read_ctrl(ix, &c))) return rc;
+    ix->avail_lb = (int64_t)D.nblocks - (int64_t)c.cur_P + (c.free_top > 0 ? c.free_top : 0);
+    if (need > ix->avail_lb)
+      return fail(RTAMS_EPOOL, "add of %lld vectors may need %lld blocks, %lld left in the pool",
+                  (long long)n, (long long)need, (long long)ix->avail_lb);
+  }
+  int rc = enter_data_stream(ix, s);
+  if (rc) return rc;
+  const int64_t round = ix->cfg.max_add_batch;
+  for (int64_t o = 0; o < n; o += round) {
+    int64_t m = n - o < round ? n - o : round;
+    const float *Y = d_vecs + (size_t)o * D.d;
+    int splits = coarse_splits(D, m, ix->ins.part_cap);
+    launch_coarse_argmin(D, m, Y, splits, ix->ins.pscore, ix->ins.pidx, s);
+    launch_reserve(D, m, splits, ix->ins, true, nullptr, s);
+    launch_open(D, s);
+    launch_fill(D, m, Y, d_ids ? d_ids + o : nullptr, ix->ntotal_host + o, ix->ins, s);
+    launch_publish(D, s);
+  }
+  HIP_TRY(hipGetLastError());
+  ix->avail_lb -= need;
+  ix->ntotal_host += n;
+  return leave_data_stream(ix, s);
+}
+
+int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k, int32_t nprobe,
+                 float *d_out_dist, int64_t *d_out_ids, void *hip_stream) {
+  if (!ix || nq < 0) return fail(RTAMS_EINVAL, "bad argument to search");
+  if (nq > ix->cfg.max_batch) return fail(RTAMS_EINVAL, "nq %lld exceeds max_batch %d", (long long)nq, ix->cfg.max_batch);
+  if (k < 1 || k > ix->cfg.max_k) return fail(RTAMS_EINVAL, "k %d outside 1..max_k %d", k, ix->cfg.max_k);
+  if (nprobe < 1 || nprobe > ix->cfg.max_nprobe)
+    return fail(RTAMS_EINVAL, "nprobe %d outside 1..max_nprobe %d", nprobe, ix->cfg.max_nprobe);
+  if (!ix->has_centroids) return fail(RTAMS_ESTATE, "search before set_centroids");
+  if (nq == 0) return RTAMS_OK;
+  if (!d_queries || !d_out_dist || !d_out_ids) return fail(RTAMS_EINVAL, "NULL buffer");
+  int r = acquire(ix);
+  if (r < 0) return fail(RTAMS_EBUSY, "all %d stream resources are in flight", ix->n_res);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const Dev &D = ix->dev;
+  const SearchScratch &S = ix->res[r].s;
+  launch_coarse_scores(D, nq, d_queries, S.scores, S.cursor, s);
+  launch_probe_plan(D, nq, nprobe, ix->cfg.max_nprobe, S, nullptr, s);
+  // spread a small batch over the chip: split each (query, list) pair into several workgroups
+  int64_t pairs = nq * nprobe;
+  int64_t target = ix->scan_split_target.load(std::memory_order_relaxed);
+  int64_t splits = (target + pairs - 1) / pairs;
+  uint32_t max_len = ix->mirror->max_len;
+  int64_t max_groups = ((int64_t)max_len + kWave * 4 - 1) / (kWave * 4);
+  if (splits > max_groups) splits = max_groups;
+  if (splits > 64) splits = 64;
+  int64_t cap = ix->scan_max_workgroups.load(std::memory_order_relaxed);
+  if (cap > 0 && pairs * splits > cap) splits = cap / pairs;
+  if (splits < 1) splits = 1;
+  launch_scan(D, nq, nprobe, ix->cfg.max_nprobe, d_queries, (int)splits, S, s);
+  launch_select(D, nq, k, nprobe, ix->cfg.max_nprobe, S, d_out_dist, d_out_ids, s);
+  hipError_t e = hipGetLastError();
+  hipError_t e2 = hipEventRecord(ix->res[r].done, s);
+  ix->res[r].state.store(RES_PENDING, std::memory_order_release);
+  if (e != hipSuccess || e2 != hipSuccess)
+    return fail(RTAMS_EHIP, "search launch failed: %s", hipGetErrorString(e != hipSuccess ? e : e2));
+  return RTAMS_OK;
+}
+
+int rtams_rearrange(rtams_index *ix, int32_t list, void *hip_stream) {
+  (void)hip_stream;
+  if (!ix || list < -1 || list >= ix->cfg.nlist) return fail(RTAMS_EINVAL, "bad list");
+  return fail(RTAMS_EINVAL, "rearrange is not built yet");
+}
+
+int rtams_probe(rtams_index *ix, int64_t nq, const float *d_queries, int32_t nprobe, int32_t *d_out,
+                void *hip_stream) {
+  if (!ix || nq < 0 || nq > ix->cfg.max_batch || nprobe < 1 || nprobe > ix->cfg.max_nprobe)
+    return fail(RTAMS_EINVAL, "bad argument to probe");
+  if (!ix->has_centroids) return fail(RTAMS_ESTATE, "probe before set_centroids");
+  if (nq == 0) return RTAMS_OK;
+  if (!d_queries || !d_out) return fail(RTAMS_EINVAL, "NULL buffer");
+  int r = acquire(ix);
+  if (r < 0) return fail(RTAMS_EBUSY, "all %d stream resources are in flight", ix->n_res);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const SearchScratch &S = ix->res[r].s;
+  launch_coarse_scores(ix->dev, nq, d_queries, S.scores, S.cursor, s);
+  launch_probe_plan(ix->dev, nq, nprobe, ix->cfg.max_nprobe, S, d_out, s);
+  hipError_t e = hipGetLastError();
+  hipError_t e2 = hipEventRecord(ix->res[r].done, s);
+  ix->res[r].state.store(RES_PENDING, std::memory_order_release);
+  if (e != hipSuccess || e2 != hipSuccess) return fail(RTAMS_EHIP, "probe launch failed");
+  return RTAMS_OK;
+}
+
+int rtams_assign(rtams_index *ix, int64_t n, const float *d_vecs, int32_t *d_out, void *hip_stream) {
+  if (!ix || n < 0) return fail(RTAMS_EINVAL, "bad argument to assign");
+  if (!ix->has_centroids) return fail(RTAMS_ESTATE, "assign before set_centroids");
+  if (n == 0) return RTAMS_OK;
+  if (!d_vecs || !d_out) return fail(RTAMS_EINVAL, "NULL buffer");
+  std::lock_guard<std::mutex> g(ix->data_mutex);  // shares the insertion scratch
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  int rc = enter_data_stream(ix, s);
+  if (rc) return rc;
+  const int64_t round = ix->cfg.max_add_batch;
+  for (int64_t o = 0; o < n; o += round) {
+    int64_t m = n - o < round ? n - o : round;
+    int splits = coarse_splits(ix->dev, m, ix->ins.part_cap);
+    launch_coarse_argmin(ix->dev, m, d_vecs + (size_t)o * ix->dev.d, splits, ix->ins.pscore, ix->ins.pidx, s);
+    launch_reserve(ix->dev, m, splits, ix->ins, false, d_out + o, s);
+  }
+  HIP_TRY(hipGetLastError());
+  return leave_data_stream(ix, s);
+}
+
+// ------------------------------------------------------------ introspection
+
+int rtams_ntotal(rtams_index *ix, int64_t *out) {
+  if (!ix || !out) return fail(RTAMS_EINVAL, "NULL argument");
+  std::lock_guard<std::mutex> g(ix->data_mutex);
+  int rc = sync_data(ix);
+  if (rc) return rc;
+  Ctrl c;
+  if ((rc = read_ctrl(ix, &c))) return rc;
+  *out = (int64_t)c.ntotal;
+  return RTAMS_OK;
+}
+
+int rtams_list_sizes(rtams_index *ix, int64_t *out) {
+  if (!ix || !out) return fail(RTAMS_EINVAL, "NULL argument");
+  std::lock_guard<std::mutex> g(ix->data_mutex);
+  int rc = sync_data(ix);
+  if (rc) return rc;
+  uint32_t *tmp = new (std::nothrow) uint32_t[ix->cfg.nlist];
+  if (!tmp) return fail(RTAMS_EINVAL, "out of host memory");
+  hipError_t e = hipMemcpy(tmp, ix->dev.visible_len, (size_t)ix->cfg.nlist * 4, hipMemcpyDeviceToHost);
+  for (int k = 0; k < ix->cfg.nlist; ++k) out[k] = tmp[k];
+  delete[] tmp;
+  if (e != hipSuccess) return fail(RTAMS_EHIP, "hipMemcpy failed: %s", hipGetErrorString(e));
+  return RTAMS_OK;
+}
+
+int rtams_list_size(rtams_index *ix, int32_t list, int64_t *out) {
+  if (!ix || !out || list < 0 || list >= ix->cfg.nlist) return fail(RTAMS_EINVAL, "bad argument");
+  std::lock_guard<std::mutex> g(ix->data_mutex);
+  int rc = sync_data(ix);
+  if (rc) return rc;
+  uint32_t v = 0;
+  HIP_TRY(hipMemcpy(&v, ix->dev.visible_len + list, 4, hipMemcpyDeviceToHost));
+  *out = v;
+  return RTAMS_OK;
+}
+
+int rtams_list_info(rtams_index *ix, int32_t list, int64_t *blocks, int64_t *runs, int64_t *online) {
+  if (!ix || list < 0 || list >= ix->cfg.nlist) return fail(RTAMS_EINVAL, "bad argument");
+  std::lock_guard<std::mutex> g(ix->data_mutex);
+  int rc = sync_data(ix);
+  if (rc) return rc;
+  int32_t *d4 = reinterpret_cast<int32_t *>(ix->hook);
+  launch_list_info(ix->dev, list, d4, nullptr);
+  int32_t h[4];
+  HIP_TRY(hipMemcpy(h, d4, sizeof(h), hipMemcpyDeviceToHost));
+  if (blocks) *blocks = h[0];
+  if (runs) *runs = h[1];
+  if (online) *online = h[2];
+  return RTAMS_OK;
+}
+
+int rtams_list_export(rtams_index *ix, int32_t list, int64_t cap, int64_t *d_ids, float *d_vecs,
+                      int64_t *n_out, void *hip_stream) {
+  if (!ix || list < 0 || list >= ix->cfg.nlist || cap < 0) return fail(RTAMS_EINVAL, "bad argument");
+  std::lock_guard<std::mutex> g(ix->data_mutex);
+  int rc = sync_data(ix);
+  if (rc) return rc;
+  uint32_t len = 0;
+  HIP_TRY(hipMemcpy(&len, ix->dev.visible_len + list, 4, hipMemcpyDeviceToHost));
+  if (n_out) *n_out = len;
+  if ((int64_t)len > cap) return fail(RTAMS_EINVAL, "list %d holds %u vectors, cap is %lld", list, len, (long long)cap);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  launch_export(ix->dev, list, len, d_ids, d_vecs, s);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipStreamSynchronize(s));
+  return RTAMS_OK;
+}
+
+int rtams_list_chain(rtams_index *ix, int32_t list, int64_t cap, int32_t *chain, int64_t *n_out) {
+  if (!ix || list < 0 || list >= ix->cfg.nlist || cap < 0) return fail(RTAMS_EINVAL, "bad argument");
+  std::lock_guard<std::mutex> g(ix->data_mutex);
+  int rc = sync_data(ix);
+  if (rc) return rc;
+  uint32_t nb = 0;
+  HIP_TRY(hipMemcpy(&nb, ix->dev.nblk + list, 4, hipMemcpyDeviceToHost));
+  if (n_out) *n_out = nb;
+  if ((int64_t)nb > cap) return fail(RTAMS_EINVAL, "chain of %u blocks, cap is %lld", nb, (long long)cap);
+  if (nb == 0) return RTAMS_OK;
+  if (!chain) return fail(RTAMS_EINVAL, "NULL chain");
+  launch_chain_copy(ix->dev, list, ix->dev.mark, nullptr);  // the validation marks double as staging
+  HIP_TRY(hipMemcpy(chain, ix->dev.mark, (size_t)nb * 4, hipMemcpyDeviceToHost));
+  return RTAMS_OK;
+}
+
+int rtams_pool_stats(rtams_index *ix, rtams_stats *out) {
+  if (!ix || !out) return fail(RTAMS_EINVAL, "NULL argument");
+  std::lock_guard<std::mutex> g(ix->data_mutex);
+  int rc = sync_data(ix);
+  if (rc) return rc;
+  Ctrl c;
+  if ((rc = read_ctrl(ix, &c))) return rc;
+  memset(out, 0, sizeof(*out));
+  out->ntotal = (int64_t)c.ntotal;
+  out->blocks_total = ix->dev.nblocks;
+  out->blocks_handed_out = c.cur_P;
+  out->blocks_free = c.free_top > 0 ? c.free_top : 0;
+  out->blocks_in_use = out->blocks_handed_out - out->blocks_free;
+  out->block_bytes = (int64_t)ix->lay.block_stride;
+  out->pool_bytes = (int64_t)ix->cfg.pool_bytes;
+  out->meta_bytes = (int64_t)ix->lay.blocks;
+  out->utilisation = (double)out->blocks_in_use / (double)out->blocks_total;
+  out->lists_exceeding = c.exceed_lists;
+  out->table_entries_used = c.slab_cur;
+  out->table_entries_total = (int64_t)ix->lay.slab_cap;
+  ix->avail_lb = out->blocks_total - out->blocks_in_use;
+  return RTAMS_OK;
+}
+
+int rtams_validate(rtams_index *ix, void *hip_stream) {
+  if (!ix) return fail(RTAMS_EINVAL, "NULL argument");
+  std::lock_guard<std::mutex> g(ix->data_mutex);
+  int rc = sync_data(ix);
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  int32_t *res = reinterpret_cast<int32_t *>(ix->hook + 64);
+  launch_validate(ix->dev, res, s);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipStreamSynchronize(s));
+  int32_t h[2];
+  HIP_TRY(hipMemcpy(h, res, sizeof(h), hipMemcpyDeviceToHost));
+  static const char *what[] = {"consistent", "reserved length differs from visible length",
+                               "chain length is not ceil(len / T_m)", "table entry out of range",
+                               "header owner/seq/capacity disagrees with the table",
+                               "header prev/next disagrees with the table",
+                               "header size disagrees with the list length", "block reachable twice",
+                               "blocks in chains + free stack != cur_P", "sum of list lengths != ntotal"};
+  if (h[0] != 0)
+    return fail(RTAMS_EINVAL, "validate: %s (argument %d)", h[0] >= 1 && h[0] <= 9 ? what[h[0]] : "unknown", h[1]);
+  return RTAMS_OK;
+}
+
+int rtams_poll_error(rtams_index *ix) {
+  if (!ix) return RTAMS_EINVAL;
+  return ix->mirror->error;
+}
+
+int rtams_set_param(rtams_index *ix, const char *key, int64_t value) {
+  if (!ix || !key) return fail(RTAMS_EINVAL, "NULL argument");
+  if (!strcmp(key, "scan_split_target")) { ix->scan_split_target = value; return RTAMS_OK; }
+  if (!strcmp(key, "scan_max_workgroups")) { ix->scan_max_workgroups = value; return RTAMS_OK; }
+  return fail(RTAMS_EINVAL, "unknown parameter %s", key);
+}
+
+}  // extern "C"

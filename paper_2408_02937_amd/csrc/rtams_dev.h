@@ -1,0 +1,120 @@
+// Device-side view of the pool: layout constants, block format, block table.
+// Internal to the library; nothing here is part of the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rtams {
+
+constexpr int kWave = 64;            // gfx950 wavefront
+constexpr int kHeaderBytes = 128;    // block header, padded so ids and vectors stay line aligned
+constexpr int kTableBase = 32;       // entries of a list's first block-table segment
+constexpr int kTableSegs = 20;       // segment s holds kTableBase << s entries
+constexpr int kMaxK = 1024;
+constexpr int kMaxNprobe = 1024;
+
+// Header of a memory block ("mh" of the paper: previous / next header and block
+// info), followed inside the block by the id list "ml" and the vectors "mv".
+struct BlockHeader {
+  int32_t prev;      // physical block before this one in the chain, -1 at the head
+  int32_t next;      // physical block after this one, -1 at the tail
+  int32_t owner;     // list that owns the block, -1 when free
+  int32_t seq;       // position in the owner's chain
+  int32_t capacity;  // T_m
+  int32_t size;      // vectors visible in this block
+  int32_t pad[26];
+};
+static_assert(sizeof(BlockHeader) == kHeaderBytes, "header size");
+
+// Control words shared by all kernels (one cache line each for the hot ones).
+struct Ctrl {
+  uint32_t cur_P;            // bump pointer of the central pool
+  uint32_t pad0[31];
+  int32_t free_top;          // number of entries on the free stack
+  uint32_t pad1[31];
+  uint32_t slab_cur;         // bump pointer of the block-table slab
+  uint32_t pad2[31];
+  int32_t error;             // sticky rtams_status raised by a kernel
+  uint32_t exceed_lists;     // lists for which Exceed() holds
+  unsigned long long ntotal; // vectors visible
+  uint32_t max_len;          // longest visible list
+  uint32_t rearr_count;      // moves planned by the running rearrangement
+  uint32_t pad3[26];
+};
+
+// Words the device writes straight into pinned host memory, so the host can
+// read them without synchronising.
+struct HostMirror {
+  volatile int32_t error;
+  volatile uint32_t exceed_lists;
+  volatile uint32_t max_len;
+  volatile uint32_t pad;
+};
+
+struct Dev {
+  int32_t d, nlist, metric, T_m;
+  int32_t d4;               // d / 4
+  int32_t groups_per_block; // T_m / 64
+  uint32_t nblocks;         // |P|
+  uint32_t slab_cap;        // entries in the table slab
+  int64_t T_mp;             // rearrangement threshold
+  uint64_t block_stride;    // bytes
+  uint32_t ids_off;         // byte offset of the id list inside a block
+  uint32_t vec_off;         // byte offset of the vectors inside a block
+  char *blocks;
+  Ctrl *ctrl;
+  HostMirror *mirror;       // pinned host memory, device-visible
+  float *centroids;         // [nlist][d]
+  uint32_t *reserved_len;   // [nlist] next free position (atomicAdd target)
+  uint32_t *visible_len;    // [nlist] length searches may read
+  uint32_t *online;         // [nlist] vectors since the last rearrangement
+  uint32_t *nblk;           // [nlist] blocks in the chain
+  uint8_t *exceed;          // [nlist] Exceed() holds
+  int32_t *seg_dir;         // [nlist][kTableSegs] slab offset of each table segment, -1 unset
+  int32_t *slab;            // block-table entries
+  int32_t *free_stack;      // [nblocks]
+  int32_t *mark;            // [nblocks] scratch for validation
+};
+
+// ---- block table: a growable array per list, made of doubling segments ----
+__host__ __device__ inline int table_seg(uint32_t i) {
+  uint32_t v = i / kTableBase + 1;
+#if defined(__HIP_DEVICE_COMPILE__)
+  return 31 - __clz((int)v);
+#else
+  int s = 0;
+  while (v >>= 1) ++s;
+  return s;
+#endif
+}
+__host__ __device__ inline uint32_t table_seg_first(int s) {
+  return (uint32_t)kTableBase * ((1u << s) - 1u);
+}
+
+__device__ inline int32_t *table_entry(const Dev &D, int list, uint32_t i) {
+  int s = table_seg(i);
+  int32_t off = D.seg_dir[(size_t)list * kTableSegs + s];
+  return D.slab + off + (i - table_seg_first(s));
+}
+
+__device__ inline BlockHeader *block_header(const Dev &D, uint32_t b) {
+  return reinterpret_cast<BlockHeader *>(D.blocks + (size_t)b * D.block_stride);
+}
+__device__ inline int64_t *block_ids(const Dev &D, uint32_t b) {
+  return reinterpret_cast<int64_t *>(D.blocks + (size_t)b * D.block_stride + D.ids_off);
+}
+__device__ inline float4 *block_vecs(const Dev &D, uint32_t b) {
+  return reinterpret_cast<float4 *>(D.blocks + (size_t)b * D.block_stride + D.vec_off);
+}
+
+// Interleaved vector layout inside a block (the paper's equation for "mv",
+// re-derived for 64-wide wavefronts): vectors are taken in groups of 64; inside
+// a group, chunk c (dimensions 4c..4c+3) of the 64 vectors is contiguous, one
+// float4 per vector.  A wavefront reading chunk c of a group loads 1 KiB of
+// consecutive memory, lane = vector.
+__device__ inline size_t vec_chunk_index(const Dev &D, uint32_t moff, int c) {
+  uint32_t group = moff / kWave, lane = moff % kWave;
+  return ((size_t)group * D.d4 + c) * kWave + lane;
+}
+
+}  // namespace rtams

@@ -1,0 +1,62 @@
+// Host-callable launchers of the kernels, one translation unit per group.
+// Internal to the library.
+#pragma once
+#include "rtams_dev.h"
+
+namespace rtams {
+
+// Per-request scratch of one stream resource (device pointers into its slice).
+struct SearchScratch {
+  double *scores;       // [max_batch][nlist] coarse scores
+  int32_t *probe_list;  // [max_batch][max_nprobe]
+  uint32_t *probe_len;  // [max_batch][max_nprobe] list lengths as seen by this request
+  uint32_t *probe_off;  // [max_batch][max_nprobe] start of the list inside the query's candidates
+  unsigned long long *qbase;  // [max_batch] start of the query's candidates in cand
+  uint32_t *qtotal;     // [max_batch] candidates of the query
+  unsigned long long *cursor; // bump pointer into cand
+  float *cand;          // candidate scores
+  unsigned long long cand_cap;
+};
+
+// Scratch of the insertion path (lives in the pool's control region).
+struct InsertScratch {
+  int32_t *assign;   // [max_add_batch] list of each vector
+  uint32_t *did;     // [max_add_batch] position inside the list
+  double *pscore;    // [part_cap] best score per (vector, centroid split)
+  int32_t *pidx;     // [part_cap]
+  size_t part_cap;
+};
+
+// coarse.hip ---------------------------------------------------------------
+int coarse_vt(int d);                      // vectors per workgroup for this dimension
+int coarse_splits(const Dev &D, int64_t n, size_t part_cap);
+// full score matrix scores[n][nlist]
+void launch_coarse_scores(const Dev &D, int64_t n, const float *Y, double *scores,
+                          unsigned long long *cursor_to_clear, hipStream_t s);
+// per (vector, split) best centroid
+void launch_coarse_argmin(const Dev &D, int64_t n, const float *Y, int splits, double *pscore,
+                          int32_t *pidx, hipStream_t s);
+
+// insert.hip -----------------------------------------------------------------
+void launch_reserve(const Dev &D, int64_t n, int splits, const InsertScratch &S, bool reserve,
+                    int32_t *assign_out, hipStream_t s);
+void launch_open(const Dev &D, hipStream_t s);
+void launch_fill(const Dev &D, int64_t n, const float *Y, const int64_t *ids, int64_t id_base,
+                 const InsertScratch &S, hipStream_t s);
+void launch_publish(const Dev &D, hipStream_t s);
+
+// search.hip -----------------------------------------------------------------
+void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const SearchScratch &S,
+                       int32_t *probe_out, hipStream_t s);
+void launch_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const float *Q, int splits,
+                 const SearchScratch &S, hipStream_t s);
+void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
+                   const SearchScratch &S, float *out_dist, int64_t *out_ids, hipStream_t s);
+
+// maint.hip ------------------------------------------------------------------
+void launch_export(const Dev &D, int list, int64_t n, int64_t *ids, float *vecs, hipStream_t s);
+void launch_chain_copy(const Dev &D, int list, int32_t *out, hipStream_t s);
+void launch_list_info(const Dev &D, int list, int32_t *out4, hipStream_t s);
+void launch_validate(const Dev &D, int32_t *result2, hipStream_t s);
+
+}  // namespace rtams

@@ -1,0 +1,354 @@
+// Search path: probe selection and plan, list scan, top-k selection.
+// (Paper, introduction: "the vector lists belonging to the most relevant
+// clusters to the query are computed, and the final top-k vectors are
+// retrieved"; distances are exact, so the result is the textbook IVF-Flat one.)
+#include "rtams_launch.h"
+
+namespace rtams {
+
+constexpr int kSelThreads = 256;
+
+// ------------------------------------------------------------------ key maps
+// Monotone maps from scores to unsigned keys: a smaller key is a better score.
+__device__ inline uint64_t key_of_double(double x) {
+  uint64_t b = (uint64_t)__double_as_longlong(x);
+  return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+}
+__device__ inline uint32_t key_of_float(float x) {
+  uint32_t b = __float_as_uint(x);
+  return (b >> 31) ? ~b : (b | 0x80000000u);
+}
+
+// ------------------------------------------------- workgroup radix selection
+// Finds the threshold of the k smallest keys among the valid items 0..n-1.
+// fn(i, key) returns false for items that do not take part.  On return T is
+// the k-th smallest key, `need` how many items with key == T belong to the k
+// smallest, c_eq how many items have key == T.  Requires 1 <= k <= #valid.
+struct SelectResult {
+  uint64_t T;
+  uint32_t need, c_eq;
+};
+
+template <int BITS, typename Fn>
+__device__ SelectResult wg_radix_select(int n, uint32_t k, Fn fn, uint32_t *hist, uint32_t *bc) {
+  uint64_t prefix = 0, mask = 0;
+  uint32_t need = k, c_eq = 0;
+  for (int shift = BITS - 8; shift >= 0; shift -= 8) {
+    for (int b = threadIdx.x; b < 256; b += kSelThreads) hist[b] = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < n; i += kSelThreads) {
+      uint64_t key;
+      if (!fn(i, key)) continue;
+      if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x < kWave) {  // first wavefront: which bin holds the need-th item
+      int l = threadIdx.x;
+      uint32_t h0 = hist[4 * l], h1 = hist[4 * l + 1], h2 = hist[4 * l + 2], h3 = hist[4 * l + 3];
+      uint32_t sum = h0 + h1 + h2 + h3, incl = sum;
+      for (int o = 1; o < kWave; o <<= 1) {
+        uint32_t t = __shfl_up(incl, o);
+        if (l >= o) incl += t;
+      }
+      uint32_t excl = incl - sum;
+      if (excl < need && need <= incl) {  // exactly one lane
+        uint32_t cum = excl;
+        int dg;
+        uint32_t hh;
+        if (cum + h0 >= need) { dg = 0; hh = h0; }
+        else { cum += h0;
+          if (cum + h1 >= need) { dg = 1; hh = h1; }
+          else { cum += h1;
+            if (cum + h2 >= need) { dg = 2; hh = h2; }
+            else { cum += h2; dg = 3; hh = h3; } } }
+        bc[0] = (uint32_t)(4 * l + dg);
+        bc[1] = cum;
+        bc[2] = hh;
+      }
+    }
+    __syncthreads();
+    uint32_t dg = bc[0];
+    need -= bc[1];
+    c_eq = bc[2];
+    prefix |= (uint64_t)dg << shift;
+    mask |= (uint64_t)255u << shift;
+    __syncthreads();
+  }
+  return {prefix, need, c_eq};
+}
+
+// Bitonic sort of m (power of two) entries in LDS by (k1, k2) ascending; pay is
+// carried along.
+__device__ inline void wg_bitonic_sort(int m, uint64_t *k1, uint64_t *k2, uint32_t *pay) {
+  for (int size = 2; size <= m; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      __syncthreads();
+      for (int t = threadIdx.x; t < m / 2; t += kSelThreads) {
+        int i = 2 * t - (t & (stride - 1));
+        int j = i + stride;
+        bool up = (i & size) == 0;
+        uint64_t a1 = k1[i], a2 = k2[i], b1 = k1[j], b2 = k2[j];
+        bool a_gt_b = a1 != b1 ? a1 > b1 : a2 > b2;
+        if (a_gt_b == up) {
+          k1[i] = b1; k2[i] = b2; k1[j] = a1; k2[j] = a2;
+          uint32_t p = pay[i]; pay[i] = pay[j]; pay[j] = p;
+        }
+      }
+    }
+  }
+  __syncthreads();
+}
+
+__device__ inline int next_pow2(int v) {
+  int m = 1;
+  while (m < v) m <<= 1;
+  return m;
+}
+
+// ------------------------------------------------------------ probe and plan
+// One workgroup per query: the nprobe best centroids by (score, index), best
+// first; then the plan of the scan: the visible length of each probed list is
+// read ONCE here, so that scan and selection agree on it whatever an insertion
+// publishes meanwhile, and the query gets its slice of the candidate array.
+__global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, int max_nprobe,
+                                                            SearchScratch S, int32_t *probe_out) {
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t bc[4];
+  __shared__ uint32_t cnt[2];
+  __shared__ uint64_t k1[kMaxNprobe];
+  __shared__ uint64_t k2[kMaxNprobe];
+  __shared__ uint32_t pay[kMaxNprobe];
+  const int q = blockIdx.x;
+  const int n = D.nlist;
+  const double *sc = S.scores + (size_t)q * n;
+  const int metric = D.metric;
+  auto key1 = [&](int i) -> uint64_t {
+    double x = sc[i];
+    x = (metric == 0 ? x : -x) + 0.0;  // +0.0 folds -0 into +0
+    return key_of_double(x);
+  };
+
+  SelectResult r1{~0ull, 0, 0}, r2{~0ull, 0, 0};
+  const bool all = nprobe >= n;
+  if (!all) {
+    r1 = wg_radix_select<64>(n, (uint32_t)nprobe, [&](int i, uint64_t &k) { k = key1(i); return true; },
+                             hist, bc);
+    if (r1.c_eq > r1.need)  // ties at the boundary go to the lower index
+      r2 = wg_radix_select<32>(n, r1.need,
+                               [&](int i, uint64_t &k) { k = (uint32_t)i; return key1(i) == r1.T; },
+                               hist, bc);
+  }
+  if (threadIdx.x == 0) cnt[0] = 0;
+  __syncthreads();
+  for (int i = threadIdx.x; i < n; i += kSelThreads) {
+    uint64_t k = key1(i);
+    bool take = all || k < r1.T || (k == r1.T && (r1.c_eq <= r1.need || (uint64_t)i <= r2.T));
+    if (take) {
+      uint32_t p = atomicAdd(&cnt[0], 1u);
+      k1[p] = k; k2[p] = (uint64_t)i; pay[p] = (uint32_t)i;
+    }
+  }
+  __syncthreads();
+  const int m = next_pow2(nprobe);
+  for (int p = nprobe + threadIdx.x; p < m; p += kSelThreads) { k1[p] = ~0ull; k2[p] = ~0ull; pay[p] = 0; }
+  wg_bitonic_sort(m, k1, k2, pay);
+
+  // plan
+  int32_t *pl = S.probe_list + (size_t)q * max_nprobe;
+  uint32_t *plen = S.probe_len + (size_t)q * max_nprobe;
+  uint32_t *poff = S.probe_off + (size_t)q * max_nprobe;
+  for (int p = threadIdx.x; p < nprobe; p += kSelThreads) {
+    int list = (int)pay[p];
+    pl[p] = list;
+    if (probe_out) probe_out[(size_t)q * nprobe + p] = list;
+    uint32_t len = __hip_atomic_load(&D.visible_len[list], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+    plen[p] = len;
+    pay[p] = len;  // reuse as lengths for the prefix sum below
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned long long tot = 0;
+    for (int p = 0; p < nprobe; ++p) {
+      uint32_t len = pay[p];
+      poff[p] = (uint32_t)tot;
+      tot += len;
+    }
+    unsigned long long base = 0;
+    if (tot > 0xFFFFFFFFull) tot = ~0ull;  // cannot be indexed: treated as overflow below
+    if (tot != ~0ull) base = atomicAdd(S.cursor, tot);
+    if (tot == ~0ull || base + tot > S.cand_cap) {  // not enough candidate scratch for this query
+      atomicCAS(&D.ctrl->error, 0, -6);
+      D.mirror->error = -6;
+      tot = 0;
+      for (int p = 0; p < nprobe; ++p) { plen[p] = 0; poff[p] = 0; }
+    }
+    S.qbase[q] = base;
+    S.qtotal[q] = (uint32_t)tot;
+  }
+}
+
+// ------------------------------------------------------------------ list scan
+// Workgroup (pair, split): pair = (query, probed list).  Each wavefront takes
+// groups of 64 vectors of the list; lane = vector.  Per chunk of 4 dimensions a
+// wavefront loads 1 KiB of consecutive memory (one float4 per lane) and every
+// lane accumulates the score of its own vector against the query, whose values
+// are uniform over the wavefront.  Scores go to the query's candidate slice.
+template <int METRIC>
+__global__ __launch_bounds__(256) void k_scan(Dev D, int nprobe, int max_nprobe,
+                                              const float *__restrict__ Q, SearchScratch S) {
+  const int pair = blockIdx.x;
+  const int q = pair / nprobe, p = pair - q * nprobe;
+  const uint32_t len = S.probe_len[(size_t)q * max_nprobe + p];
+  if (len == 0) return;
+  const int list = S.probe_list[(size_t)q * max_nprobe + p];
+  float *out = S.cand + S.qbase[q] + S.probe_off[(size_t)q * max_nprobe + p];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int waves = blockDim.x / kWave;
+  const uint32_t ngroups = (len + kWave - 1) / kWave;
+  const int d4 = D.d4;
+  const float4 *__restrict__ q4 = reinterpret_cast<const float4 *>(Q + (size_t)q * D.d);
+  const uint32_t gpb = (uint32_t)D.groups_per_block;
+
+  for (uint32_t g = blockIdx.y * waves + wave; g < ngroups; g += gridDim.y * waves) {
+    const uint32_t bi = g / gpb, sub = g - bi * gpb;
+    const uint32_t b = (uint32_t)*table_entry(D, list, bi);
+    const float4 *__restrict__ x4 = block_vecs(D, b) + (size_t)sub * d4 * kWave + lane;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+#pragma unroll 8
+    for (int c = 0; c < d4; ++c) {
+      float4 x = x4[(size_t)c * kWave];
+      float4 y = q4[c];
+      if (METRIC == 0) {
+        float t0 = x.x - y.x, t1 = x.y - y.y, t2 = x.z - y.z, t3 = x.w - y.w;
+        a0 = fmaf(t0, t0, a0); a1 = fmaf(t1, t1, a1); a2 = fmaf(t2, t2, a2); a3 = fmaf(t3, t3, a3);
+      } else {
+        a0 = fmaf(x.x, y.x, a0); a1 = fmaf(x.y, y.y, a1); a2 = fmaf(x.z, y.z, a2); a3 = fmaf(x.w, y.w, a3);
+      }
+    }
+    const uint32_t v = g * kWave + lane;
+    if (v < len) out[v] = (a0 + a1) + (a2 + a3);
+  }
+}
+
+// ------------------------------------------------------------ top-k selection
+// One workgroup per query over its candidate slice: the k best by (score, id).
+__global__ __launch_bounds__(kSelThreads) void k_select(Dev D, int k, int nprobe, int max_nprobe,
+                                                        SearchScratch S, float *__restrict__ out_dist,
+                                                        int64_t *__restrict__ out_ids) {
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t bc[4];
+  __shared__ uint32_t cnt[2];
+  __shared__ uint32_t offs[kMaxNprobe];
+  __shared__ int32_t lists[kMaxNprobe];
+  __shared__ uint64_t k1[kMaxK];
+  __shared__ uint64_t k2[kMaxK];
+  __shared__ uint32_t pay[kMaxK];
+  const int q = blockIdx.x;
+  const int n = (int)S.qtotal[q];
+  const float *cand = S.cand + S.qbase[q];
+  const int metric = D.metric;
+  for (int p = threadIdx.x; p < nprobe; p += kSelThreads) {
+    offs[p] = S.probe_off[(size_t)q * max_nprobe + p];
+    lists[p] = S.probe_list[(size_t)q * max_nprobe + p];
+  }
+  if (threadIdx.x == 0) cnt[0] = cnt[1] = 0;
+  __syncthreads();
+
+  auto key1 = [&](int i) -> uint32_t {
+    float x = cand[i];
+    x = (metric == 0 ? x : -x) + 0.0f;
+    return key_of_float(x);
+  };
+  // candidate i -> id: which probed list (last offset <= i), which position, which block
+  auto id_of = [&](int i) -> int64_t {
+    int lo = 0, hi = nprobe - 1;
+    while (lo < hi) {
+      int mid = (lo + hi + 1) >> 1;
+      if (offs[mid] <= (uint32_t)i) lo = mid; else hi = mid - 1;
+    }
+    uint32_t pos = (uint32_t)i - offs[lo];
+    uint32_t b = (uint32_t)*table_entry(D, lists[lo], pos / (uint32_t)D.T_m);
+    return block_ids(D, b)[pos % (uint32_t)D.T_m];
+  };
+  auto key_of_id = [](int64_t id) -> uint64_t { return (uint64_t)id ^ 0x8000000000000000ull; };
+
+  const int kk = k < n ? k : n;  // results that exist
+  SelectResult r1{~0ull, 0, 0}, r2{~0ull, 0, 0};
+  const bool all = n <= k;
+  if (!all) {
+    r1 = wg_radix_select<32>(n, (uint32_t)k, [&](int i, uint64_t &key) { key = key1(i); return true; },
+                             hist, bc);
+    if (r1.c_eq > r1.need)  // ties at the boundary go to the lower id
+      r2 = wg_radix_select<64>(n, r1.need,
+                               [&](int i, uint64_t &key) {
+                                 if (key1(i) != (uint32_t)r1.T) return false;
+                                 key = key_of_id(id_of(i));
+                                 return true;
+                               },
+                               hist, bc);
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < n; i += kSelThreads) {
+    uint32_t key = key1(i);
+    bool take = all || key < (uint32_t)r1.T;
+    int64_t id = 0;
+    bool have_id = false;
+    if (!take && key == (uint32_t)r1.T) {
+      if (r1.c_eq <= r1.need) take = true;
+      else {
+        id = id_of(i); have_id = true;
+        uint64_t ik = key_of_id(id);
+        if (ik < r2.T) take = true;
+        else if (ik == r2.T) take = atomicAdd(&cnt[1], 1u) < r2.need;  // identical (score, id) pairs
+      }
+    }
+    if (take) {
+      if (!have_id) id = id_of(i);
+      uint32_t p = atomicAdd(&cnt[0], 1u);
+      k1[p] = key; k2[p] = key_of_id(id); pay[p] = (uint32_t)i;
+    }
+  }
+  __syncthreads();
+  const int m = next_pow2(kk > 0 ? kk : 1);
+  for (int p = kk + threadIdx.x; p < m; p += kSelThreads) { k1[p] = ~0ull; k2[p] = ~0ull; pay[p] = 0; }
+  wg_bitonic_sort(m, k1, k2, pay);
+  for (int r = threadIdx.x; r < k; r += kSelThreads) {
+    size_t o = (size_t)q * k + r;
+    if (r < kk) {
+      out_dist[o] = cand[pay[r]];
+      out_ids[o] = (int64_t)(k2[r] ^ 0x8000000000000000ull);
+    } else {
+      out_dist[o] = metric == 0 ? __builtin_inff() : -__builtin_inff();
+      out_ids[o] = -1;
+    }
+  }
+}
+
+// ---------------------------------------------------------------- launchers
+
+void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const SearchScratch &S,
+                       int32_t *probe_out, hipStream_t s) {
+  if (nq <= 0) return;
+  hipLaunchKernelGGL(k_probe_plan, dim3((unsigned)nq), dim3(kSelThreads), 0, s, D, nprobe, max_nprobe,
+                     S, probe_out);
+}
+
+void launch_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const float *Q, int splits,
+                 const SearchScratch &S, hipStream_t s) {
+  if (nq <= 0) return;
+  dim3 grid((unsigned)(nq * nprobe), (unsigned)splits);
+  if (D.metric == 0)
+    hipLaunchKernelGGL(k_scan<0>, grid, dim3(256), 0, s, D, nprobe, max_nprobe, Q, S);
+  else
+    hipLaunchKernelGGL(k_scan<1>, grid, dim3(256), 0, s, D, nprobe, max_nprobe, Q, S);
+}
+
+void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
+                   const SearchScratch &S, float *out_dist, int64_t *out_ids, hipStream_t s) {
+  if (nq <= 0) return;
+  hipLaunchKernelGGL(k_select, dim3((unsigned)nq), dim3(kSelThreads), 0, s, D, k, nprobe, max_nprobe,
+                     S, out_dist, out_ids);
+}
+
+}  // namespace rtams

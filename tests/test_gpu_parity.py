@@ -1,0 +1,178 @@
+"""HIP path against the CPU oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2408_02937_amd import rtams, synth
+from tests.gpu_common import assert_lists_equal, dev, make_pair
+from tests.helpers import assert_topk_matches
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-4  # relative tolerance on fp32 distances (stated target of the build)
+
+
+def workloads():
+    return {
+        "tiny-l2": synth.config(1),
+        "byte-l2": synth.byte_valued_l2("byte-small", 21, n_base=30_000, n_centres=40, nlist=96,
+                                        block_vecs=128, n_queries=300, n_inserts=3_000, insert_batch=64,
+                                        nprobe=12, k=100),
+        "unit-ip": synth.unit_ip("ip-small", 22, d=96, n_base=40_000, n_centres=300, nlist=128,
+                                 block_vecs=256, n_queries=300, n_inserts=2_048, insert_batch=512,
+                                 nprobe=16, k=10),
+        "zipf-l2": synth.skewed_l2("zipf-small", 23, d=64, n_base=60_000, nlist=256, block_vecs=64,
+                                   n_queries=256, n_inserts=4_096, insert_batch=1024, nprobe=16, k=50),
+    }
+
+
+@pytest.fixture(scope="module", params=list(workloads().keys()))
+def loaded(request):
+    """Base set bulk-loaded in one add, then the insert stream in its batches."""
+    w = workloads()[request.param]
+    print(f"[case] workload={w.name} seed={w.seed}", flush=True)
+    g, o = make_pair(w)
+    g.add(dev(w.base))
+    o.add(w.base)
+    bounds = [len(w.base)]
+    for b in range(0, len(w.inserts), w.insert_batch):
+        chunk = w.inserts[b:b + w.insert_batch]
+        g.add(dev(chunk))
+        o.add(chunk)
+        bounds.append(bounds[-1] + len(chunk))
+    torch.cuda.synchronize()
+    assert g.poll_error() == 0
+    yield w, g, o, np.array(bounds[:-1])
+    g.close()
+
+
+def test_assignment_is_bit_exact(loaded):
+    w, g, o, _ = loaded
+    y = np.concatenate([w.inserts, w.queries])
+    got = g.assign(dev(y)).cpu().numpy()
+    assert np.array_equal(got, o.assign(y))
+
+
+def test_list_contents_and_block_structure(loaded):
+    w, g, o, bounds = loaded
+    g.validate()
+    assert_lists_equal(g, o, bounds)
+
+
+def test_probe_selection_is_bit_exact(loaded):
+    w, g, o, _ = loaded
+    for nprobe in (1, w.nprobe, min(w.nlist, 64)):
+        got = g.probe(dev(w.queries[:256]), nprobe).cpu().numpy()
+        assert np.array_equal(got, o.probe(w.queries[:256], nprobe)), f"nprobe={nprobe}"
+
+
+@pytest.mark.parametrize("batch", [1, 7, 256])
+def test_search_matches_oracle(loaded, batch):
+    w, g, o, _ = loaded
+    q = w.queries[:batch]
+    d, i = g.search(dev(q), w.k, w.nprobe)
+    torch.cuda.synchronize()
+    assert g.poll_error() == 0
+    rd, ri = o.search(q, w.k, w.nprobe)
+    assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6,
+                        what=f"{w.name} batch {batch}")
+
+
+def test_search_all_lists_and_large_k(loaded):
+    w, g, o, _ = loaded
+    nprobe = min(w.nlist, 64)
+    q = w.queries[:32]
+    d, i = g.search(dev(q), 128, nprobe)
+    torch.cuda.synchronize()
+    rd, ri = o.search(q, 128, nprobe)
+    assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6)
+
+
+def test_integer_valued_distances_are_exact():
+    """Byte-valued data: every partial sum is an integer below 2^24, so fp32 is
+    exact and ids (ties by id included) and distances must equal the oracle's."""
+    w = workloads()["byte-l2"]
+    g, o = make_pair(w)
+    base = np.concatenate([w.base, w.base[:500]])      # duplicates: exact ties
+    g.add(dev(base)); o.add(base)
+    q = w.queries[:256]
+    d, i = g.search(dev(q), w.k, w.nprobe)
+    torch.cuda.synchronize()
+    rd, ri = o.search(q, w.k, w.nprobe)
+    assert np.array_equal(i.cpu().numpy(), ri)
+    assert np.array_equal(d.cpu().numpy().astype(np.float64), rd)
+    d, i = g.search(dev(base[7:8]), 2, w.nprobe)      # both copies of a duplicated row, lower id first
+    assert i.cpu().numpy()[0].tolist() == [7, len(w.base) + 7] and d.cpu().numpy()[0].tolist() == [0.0, 0.0]
+    g.close()
+
+
+def test_caller_ids_and_ragged_tail():
+    """Caller-supplied ids; list lengths that end inside a 64-vector group and
+    inside a block; a batch that opens several blocks for one list."""
+    rng = np.random.default_rng(5)
+    d, nlist, T = 8, 3, 64
+    C = np.eye(nlist, d, dtype=np.float32) * 4
+    w = synth.Workload("ragged", "l2", d, nlist, T, 3, 10, np.zeros((0, d), np.float32), C,
+                       np.zeros((0, d), np.float32), np.zeros((0, d), np.float32), 1, 0)
+    g, o = make_pair(w, pool_blocks=64, candidates_per_query=2000)
+    sizes = [1, 63, 64, 65, 200, 1]
+    next_id = 10_000
+    for s, n in enumerate(sizes):
+        comp = rng.integers(0, nlist, size=n) if s != 4 else np.zeros(n, dtype=np.int64)
+        y = (C[comp] + 0.3 * rng.standard_normal((n, d))).astype(np.float32)
+        ids = np.arange(next_id, next_id + n, dtype=np.int64)[::-1].copy()   # descending on purpose
+        next_id += n
+        g.add(dev(y), dev(ids)); o.add(y, ids)
+    g.validate()
+    assert_lists_equal(g, o)
+    q = (C[rng.integers(0, nlist, size=40)] + 0.3 * rng.standard_normal((40, d))).astype(np.float32)
+    for nprobe in (1, 3):
+        dd, ii = g.search(dev(q), 10, nprobe)
+        rd, ri = o.search(q, 10, nprobe)
+        assert_topk_matches("l2", dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6)
+    g.close()
+
+
+def test_empty_index_short_lists_and_errors():
+    d, nlist = 4, 4
+    C = np.eye(4, dtype=np.float32)
+    w = synth.Workload("empty", "ip", d, nlist, 64, 4, 3, np.zeros((0, d), np.float32), C,
+                       np.zeros((0, d), np.float32), np.zeros((0, d), np.float32), 1, 0)
+    g = rtams.Index(d, nlist, "ip", 64, pool_blocks=8, max_batch=4, max_k=8, max_nprobe=4,
+                    candidates_per_query=256, n_resources=2)
+    q = dev(np.ones((1, d), np.float32))
+    with pytest.raises(rtams.RtamsError) as e:
+        g.search(q, 3, 4)
+    assert e.value.code == rtams.ESTATE
+    g.set_centroids(dev(C))
+    dd, ii = g.search(q, 3, 4)                                   # nothing inserted yet
+    assert ii.cpu().numpy().tolist() == [[-1, -1, -1]] and np.all(np.isneginf(dd.cpu().numpy()))
+    g.add(dev(C[:2]))
+    dd, ii = g.search(dev(np.array([[1, 0, 0, 0]], np.float32)), 3, 4)
+    assert ii.cpu().numpy().tolist() == [[0, 1, -1]]
+    assert dd.cpu().numpy()[0, :2].tolist() == [1.0, 0.0] and np.isneginf(dd.cpu().numpy()[0, 2])
+    for bad in (dict(k=9, nprobe=1), dict(k=1, nprobe=5), dict(k=0, nprobe=1)):
+        with pytest.raises(rtams.RtamsError) as e:
+            g.search(q, bad["k"], bad["nprobe"])
+        assert e.value.code == rtams.EINVAL
+    with pytest.raises(rtams.RtamsError) as e:
+        g.search(dev(np.ones((5, d), np.float32)), 1, 1)        # nq > max_batch
+    assert e.value.code == rtams.EINVAL
+    g.close()
+
+
+def test_pool_exhaustion_is_refused_before_anything_is_enqueued():
+    d, nlist, T = 4, 2, 64
+    C = np.eye(2, 4, dtype=np.float32)
+    g = rtams.Index(d, nlist, "ip", T, pool_blocks=3, max_batch=4, max_k=8, max_nprobe=2,
+                    candidates_per_query=1024, n_resources=2)
+    g.set_centroids(dev(C))
+    total = g.pool_stats().blocks_total
+    g.add(dev(np.repeat(C[:1], T * (total - 2), axis=0)))       # all but two blocks
+    with pytest.raises(rtams.RtamsError) as e:
+        g.add(dev(np.repeat(C[1:], 2 * T + 1, axis=0)))         # needs three
+    assert e.value.code == rtams.EPOOL
+    st = g.pool_stats()
+    assert st.ntotal == T * (total - 2) and st.blocks_in_use == total - 2 and g.poll_error() == 0
+    g.validate()
+    g.close()

@@ -1,0 +1,64 @@
+"""CPU-only checks of the HIP library's boundary: it loads, exports every symbol the
+header declares, and its host-side argument checks work without a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2408_02937_amd import rtams
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "rtams.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rtams_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = rtams.lib()
+    declared = header_symbols()
+    assert declared == sorted(rtams.SYMBOLS)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def cfg(**kw):
+    base = dict(d=32, nlist=64, metric=0, block_vecs=64, rearrange_threshold=0, n_resources=4,
+                max_batch=16, max_k=10, max_nprobe=8, max_add_batch=1024)
+    base.update(kw)
+    return rtams.Config(**base)
+
+
+def test_pool_size_arithmetic():
+    L = rtams.lib()
+    c = cfg()
+    one = L.rtams_pool_bytes_for(C.byref(c), 1)
+    many = L.rtams_pool_bytes_for(C.byref(c), 1001)
+    stride = (many - one) // 1000
+    # a block is header + T_m ids + T_m vectors, padded to 256 bytes, plus 16 bytes of tables
+    payload = 128 + 64 * 8 + 64 * 32 * 4
+    padded = (payload + 255) // 256 * 256
+    assert abs(stride - (padded + 16)) <= 1          # alignment of the tables rounds the quotient
+    assert L.rtams_scratch_bytes_for(C.byref(c), 1000) - L.rtams_scratch_bytes_for(C.byref(c), 0) \
+        in range(16 * 1000 * 4, 16 * 1000 * 4 + 257)
+
+
+@pytest.mark.parametrize("bad", [dict(d=30), dict(d=0), dict(block_vecs=100), dict(nlist=0), dict(metric=7),
+                                 dict(max_k=2000), dict(max_nprobe=65), dict(n_resources=0)])
+def test_bad_configurations_are_refused_on_the_host(bad):
+    L = rtams.lib()
+    c = cfg(**bad)
+    assert L.rtams_pool_bytes_for(C.byref(c), 10) == 0
+    h = C.c_void_p()
+    assert L.rtams_create(C.byref(c), C.byref(h)) == rtams.EINVAL and not h.value
+    assert len(L.rtams_last_error()) > 0
+
+
+def test_create_needs_memory():
+    L = rtams.lib()
+    h = C.c_void_p()
+    assert L.rtams_create(C.byref(cfg()), C.byref(h)) == rtams.EINVAL
+    assert b"pool and scratch" in L.rtams_last_error()
