@@ -1,0 +1,263 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: one
+insertion batch on the data stream (assignment, slot reservation, block
+opening, fill, publication) and, concurrently, one search batch on a pooled
+search stream (coarse scores, probe selection, list scan, top-k).  The
+workload is configuration 2 of the benchmark spec (byte-valued L2, d=128, 1M base
+vectors, nlist=1024, nprobe=32, k=100, block of 128 vectors, inserts in batches
+of 64), with every input resident in HBM before the timed region starts.
+
+Prints ONE JSON line; see the design doc for the meaning of each field.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import threading
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def percentile(xs, p):
+    return float(np.percentile(np.asarray(xs, dtype=np.float64), p)) if len(xs) else float("nan")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--batch", type=int, default=256, help="queries per search batch")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrinks base/query/insert counts")
+    ap.add_argument("--search-streams", type=int, default=4)
+    ap.add_argument("--latency-iters", type=int, default=300)
+    ap.add_argument("--cpu-queries", type=int, default=1024, help="queries of the oracle sample; 0 skips it")
+    ap.add_argument("--no-extras", action="store_true", help="only the timed steps (for profiler runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (see DESIGN.md, sharding)",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2408_02937_amd import rtams, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    t_gen = time.perf_counter()
+    w = synth.config(2, scale=args.scale)
+    t_gen = time.perf_counter() - t_gen
+    B, k, nprobe, ib = args.batch, w.k, w.nprobe, w.insert_batch
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    base, cents, queries, inserts = map(to_dev, (w.base, w.centroids, w.queries, w.inserts))
+    n_all = len(w.base) + len(w.inserts) * 2
+    pool_blocks = n_all // w.block_vecs + 2 * w.nlist + 64
+    g = rtams.Index(w.d, w.nlist, w.metric, w.block_vecs, pool_blocks=pool_blocks, n_resources=8,
+                    max_batch=max(B, 256), max_k=128, max_nprobe=64, max_add_batch=65536,
+                    candidates_per_query=65536)
+    data_stream = torch.cuda.Stream(dev)
+    search_streams = [torch.cuda.Stream(dev) for _ in range(args.search_streams)]
+    g.set_centroids(cents, stream=data_stream)
+
+    # ---- bulk load of the base set through add (one format for offline and online data)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    g.add(base, stream=data_stream)
+    torch.cuda.synchronize()
+    bulk_s = time.perf_counter() - t0
+
+    nq_batches = len(w.queries) // B
+    q_batches = [queries[i * B:(i + 1) * B] for i in range(nq_batches)]
+    n_ins_batches = len(w.inserts) // ib
+    ins_batches = [inserts[i * ib:(i + 1) * ib] for i in range(n_ins_batches)]
+    outs = [(torch.empty((B, k), dtype=torch.float32, device=dev),
+             torch.empty((B, k), dtype=torch.int64, device=dev)) for _ in search_streams]
+    ins_cursor = [0]
+
+    def next_insert():
+        b = ins_batches[ins_cursor[0] % n_ins_batches]
+        ins_cursor[0] += 1
+        return b
+
+    def submit_search(i, q):
+        s = i % len(search_streams)
+        while True:
+            try:
+                g.search(q, k, nprobe, outs[s][0], outs[s][1], stream=search_streams[s])
+                return
+            except rtams.RtamsError as e:
+                if e.code != rtams.EBUSY:
+                    raise
+                search_streams[(s + 1) % len(search_streams)].synchronize()
+
+    def step(i):
+        g.add(next_insert(), stream=data_stream)
+        submit_search(i, q_batches[i % nq_batches])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    g.scan_time(reset=True)
+    g.set_param("profile_scan", 1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    g.set_param("profile_scan", 0)
+    scan_ms, scan_n = g.scan_time(reset=True)
+    assert g.poll_error() == 0, "a kernel raised an error during the timed steps"
+    qps = args.steps * B / elapsed
+
+    # ---- algorithmic bytes of the scan kernel per launch (what the method must read)
+    sizes = g.list_sizes()
+    pair_bytes, union_bytes = [], []
+    for i in range(min(args.steps, nq_batches)):
+        pl = g.probe(q_batches[(args.warmup + i) % nq_batches], nprobe).cpu().numpy()
+        ln = sizes[pl]
+        per_list = lambda l: l * w.d * 4 + ((l + w.block_vecs - 1) // w.block_vecs) * 4
+        pair_bytes.append(int(per_list(ln).sum()))
+        union_bytes.append(int(per_list(sizes[np.unique(pl)]).sum()))
+    pair_b, union_b = float(np.mean(pair_bytes)), float(np.mean(union_bytes))
+    scan_avg_ms = scan_ms / max(scan_n, 1)
+    achieved = pair_b / (scan_avg_ms * 1e-3) / 1e9 if scan_n else float("nan")
+
+    result = {
+        "metric": "search QPS under concurrent insertion",
+        "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "n_base": len(w.base), "d": w.d, "nlist": w.nlist,
+                   "block_vecs": w.block_vecs, "metric": w.metric, "query_batch": B, "nprobe": nprobe,
+                   "k": k, "insert_batch": ib, "search_streams": args.search_streams, "seed": w.seed},
+        "roofline": {"bound": "hbm", "kernel": "k_scan", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": pair_b, "union_bytes_per_launch": union_b,
+                     "union_frac": union_b / (scan_avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if scan_n else None,
+                     "avg_launch_ms": scan_avg_ms, "launches_timed": scan_n},
+        "inserts_per_s_in_step": args.steps * ib / elapsed,
+        "bulk_load_vectors_per_s": len(w.base) / bulk_s,
+    }
+
+    if not args.no_extras:
+        result.update(extras(args, g, w, torch, rtams, q_batches, queries, ins_batches, data_stream,
+                             search_streams, dev))
+        if args.cpu_queries > 0:
+            result["cpu_baseline"] = cpu_baseline(args, w)
+    print(json.dumps(result))
+    g.close()
+    return 0
+
+
+def extras(args, g, w, torch, rtams, q_batches, queries, ins_batches, data_stream, search_streams, dev):
+    """Latency of one search request (closed loop, one in flight) with and
+    without the insertion stream running at the configured rate; saturated
+    insertion rate."""
+    k, nprobe, ib = w.k, w.nprobe, w.insert_batch
+    s = search_streams[0]
+    out = {}
+
+    def latencies(bs, iters):
+        od = torch.empty((bs, k), dtype=torch.float32, device=dev)
+        oi = torch.empty((bs, k), dtype=torch.int64, device=dev)
+        lat = []
+        nb = len(queries) // bs
+        for i in range(iters + 10):
+            q = queries[(i % nb) * bs:(i % nb + 1) * bs]
+            t0 = time.perf_counter()
+            g.search(q, k, nprobe, od, oi, stream=s)
+            s.synchronize()
+            if i >= 10:
+                lat.append((time.perf_counter() - t0) * 1e3)
+        return lat
+
+    rate = 10_000.0  # vectors per second of the configured insertion stream
+    stop = threading.Event()
+    sent = [0]
+
+    def inserter():
+        period = ib / rate
+        nxt = time.perf_counter()
+        i = 0
+        while not stop.is_set():
+            g.add(ins_batches[i % len(ins_batches)], stream=data_stream)
+            i += 1
+            sent[0] += ib
+            nxt += period
+            dt = nxt - time.perf_counter()
+            if dt > 0:
+                time.sleep(dt)
+
+    per_batch = {}
+    for bs in (1, 32, 256):
+        iters = args.latency_iters
+        alone = latencies(bs, iters)
+        stop.clear()
+        sent[0] = 0
+        th = threading.Thread(target=inserter)
+        t0 = time.perf_counter()
+        th.start()
+        loaded = latencies(bs, iters)
+        stop.set()
+        th.join()
+        data_stream.synchronize()
+        dt = time.perf_counter() - t0
+        per_batch[str(bs)] = {
+            "search_only": {"qps": bs / (np.mean(alone) * 1e-3), "p50_ms": percentile(alone, 50),
+                            "p99_ms": percentile(alone, 99)},
+            "with_inserts": {"qps": bs / (np.mean(loaded) * 1e-3), "p50_ms": percentile(loaded, 50),
+                             "p99_ms": percentile(loaded, 99), "inserts_per_s": sent[0] / dt},
+            "p99_ratio": percentile(loaded, 99) / percentile(alone, 99),
+        }
+    out["latency_by_query_batch"] = per_batch
+
+    # saturated insertion: batches back to back on the data stream
+    torch.cuda.synchronize()
+    n = 300
+    t0 = time.perf_counter()
+    for i in range(n):
+        g.add(ins_batches[i % len(ins_batches)], stream=data_stream)
+    data_stream.synchronize()
+    out["inserts_per_s_saturated"] = n * ib / (time.perf_counter() - t0)
+    st = g.pool_stats()
+    out["pool"] = {"blocks_in_use": st.blocks_in_use, "blocks_total": st.blocks_total,
+                   "utilisation": st.utilisation, "ntotal": st.ntotal}
+    return out
+
+
+def cpu_baseline(args, w):
+    """The CPU oracle, as it stands, on the host cores of this machine: the same
+    index (built by the oracle itself) and a bounded sample of the queries."""
+    from oracle import oracle as orc
+    o = orc.OracleIndex(w.d, w.nlist, w.metric, w.block_vecs,
+                        pool_blocks=len(w.base) // w.block_vecs + 2 * w.nlist + 64)
+    o.set_centroids(w.centroids)
+    t0 = time.perf_counter()
+    o.add(w.base)
+    t_add = time.perf_counter() - t0
+    n = min(args.cpu_queries, len(w.queries))
+    t0 = time.perf_counter()
+    o.search(w.queries[:n], w.k, w.nprobe)
+    t_search = time.perf_counter() - t0
+    return {"value": n / t_search, "unit": "queries/s", "cores": orc.threads(), "kind": "oracle",
+            "sample": f"first {n} queries of the workload against the full {len(w.base)}-vector index, "
+                      f"nprobe {w.nprobe}, k {w.k}; search only ({t_search:.1f} s)",
+            "bulk_load_vectors_per_s": len(w.base) / t_add}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -167,9 +167,15 @@ int rtams_assign(rtams_index *ix, int64_t n, const float *d_vecs, int32_t *d_out
  * overflow); RTAMS_OK if none.  Does not synchronise. */
 int rtams_poll_error(rtams_index *ix);
 const char *rtams_last_error(void);
+/* Measured duration of the list-scan kernel: with the parameter "profile_scan"
+ * set to 1, every search brackets its scan launch with two HIP events on the
+ * caller's stream; this call adds up the pairs of the requests that have
+ * finished (ms_sum in milliseconds, launches = how many) and optionally resets
+ * the sums.  Does not synchronise. */
+int rtams_scan_time(rtams_index *ix, double *ms_sum, int64_t *launches, int reset);
 /* Launch-shape knobs ("restrict the number of blocks and threads per kernel",
  * Stream-Cached Multi-Stream Execution, consideration 2).  key: "scan_max_workgroups",
- * "scan_split_target".  EINVAL for an unknown key. */
+ * "scan_split_target", and "profile_scan" (see rtams_scan_time).  EINVAL for an unknown key. */
 int rtams_set_param(rtams_index *ix, const char *key, int64_t value);
 
 #ifdef __cplusplus

@@ -58,10 +58,12 @@ __global__ __launch_bounds__(kCoarseThreads) void k_coarse(
   const int c_begin = split * per;
   const int c_end = min(D.nlist, c_begin + per);
 
+  // running best per vector; the sentinel loses against every real score
+  const double worst = METRIC == 0 ? __builtin_inf() : -__builtin_inf();
   double best_s[VT];
   int best_i[VT];
 #pragma unroll
-  for (int v = 0; v < VT; ++v) { best_s[v] = 0.0; best_i[v] = -1; }
+  for (int v = 0; v < VT; ++v) { best_s[v] = worst; best_i[v] = 0x7fffffff; }
 
   const float4 *C4 = reinterpret_cast<const float4 *>(D.centroids);
   for (int c = c_begin + threadIdx.x; c < c_end; c += kCoarseThreads) {
@@ -90,10 +92,11 @@ __global__ __launch_bounds__(kCoarseThreads) void k_coarse(
     }
     if (ARGMIN) {
 #pragma unroll
-      for (int v = 0; v < VT; ++v)
-        if (best_i[v] < 0 || better_pair(METRIC, acc[v], c, best_s[v], best_i[v])) {
-          best_s[v] = acc[v]; best_i[v] = c;
-        }
+      for (int v = 0; v < VT; ++v) {
+        const bool take = better_pair(METRIC, acc[v], c, best_s[v], best_i[v]);
+        best_s[v] = take ? acc[v] : best_s[v];
+        best_i[v] = take ? c : best_i[v];
+      }
     } else {
 #pragma unroll
       for (int v = 0; v < VT; ++v)
@@ -110,18 +113,17 @@ __global__ __launch_bounds__(kCoarseThreads) void k_coarse(
       __syncthreads();
       for (int w = kCoarseThreads / 2; w > 0; w >>= 1) {
         if ((int)threadIdx.x < w) {
-          int ib = red_i[threadIdx.x + w];
-          double sb = red_s[threadIdx.x + w];
-          int ia = red_i[threadIdx.x];
-          if (ib >= 0 && (ia < 0 || better_pair(METRIC, sb, ib, red_s[threadIdx.x], ia))) {
-            red_s[threadIdx.x] = sb; red_i[threadIdx.x] = ib;
-          }
+          const int ib = red_i[threadIdx.x + w], ia = red_i[threadIdx.x];
+          const double sb = red_s[threadIdx.x + w], sa = red_s[threadIdx.x];
+          const bool take = better_pair(METRIC, sb, ib, sa, ia);
+          red_s[threadIdx.x] = take ? sb : sa;
+          red_i[threadIdx.x] = take ? ib : ia;
         }
         __syncthreads();
       }
       if (threadIdx.x == 0 && v0 + v < n) {
         pscore[(size_t)(v0 + v) * splits + split] = red_s[0];
-        pidx[(size_t)(v0 + v) * splits + split] = red_i[0];
+        pidx[(size_t)(v0 + v) * splits + split] = red_i[0] == 0x7fffffff ? -1 : red_i[0];
       }
     }
   }

@@ -136,6 +136,8 @@ enum { RES_FREE = 0, RES_BUSY = 1, RES_PENDING = 2 };
 struct Resource {
   std::atomic<int> state{RES_FREE};
   hipEvent_t done = nullptr;
+  hipEvent_t t0 = nullptr, t1 = nullptr;  // around the scan kernel when profiling is on
+  bool timed = false;
   SearchScratch s{};
 };
 
@@ -159,6 +161,10 @@ struct rtams_index {
   int64_t avail_lb = 0;      // lower bound of the blocks still available in the pool
   std::atomic<int64_t> scan_split_target{2048};
   std::atomic<int64_t> scan_max_workgroups{0};
+  std::atomic<int64_t> profile_scan{0};
+  std::mutex prof_mutex;
+  double scan_ms = 0.0;      // sum of measured scan-kernel durations
+  int64_t scan_launches = 0;
 };
 
 namespace {
@@ -181,6 +187,23 @@ int leave_data_stream(rtams_index *ix, hipStream_t s) {
   return RTAMS_OK;
 }
 
+// The owner of a resource (state BUSY) collects the scan timing of its last request.
+void harvest(rtams_index *ix, Resource &R) {
+  if (!R.timed) return;
+  R.timed = false;
+  float ms = 0.f;
+  if (hipEventElapsedTime(&ms, R.t0, R.t1) == hipSuccess) {
+    std::lock_guard<std::mutex> g(ix->prof_mutex);
+    ix->scan_ms += ms;
+    ix->scan_launches += 1;
+  } else {
+    (void)hipGetLastError();
+  }
+}
+
+// Lock-free hand-out of stream resources: a slot is FREE, BUSY (being filled by
+// a host thread) or PENDING (its request is on the GPU; the next taker checks
+// the completion event).
 int acquire(rtams_index *ix) {
   for (int r = 0; r < ix->n_res; ++r) {
     int st = ix->res[r].state.load(std::memory_order_acquire);
@@ -188,8 +211,10 @@ int acquire(rtams_index *ix) {
       if (ix->res[r].state.compare_exchange_strong(st, RES_BUSY, std::memory_order_acq_rel)) return r;
     } else if (st == RES_PENDING) {
       if (hipEventQuery(ix->res[r].done) == hipSuccess &&
-          ix->res[r].state.compare_exchange_strong(st, RES_BUSY, std::memory_order_acq_rel))
+          ix->res[r].state.compare_exchange_strong(st, RES_BUSY, std::memory_order_acq_rel)) {
+        harvest(ix, ix->res[r]);
         return r;
+      }
     }
   }
   (void)hipGetLastError();  // hipEventQuery leaves hipErrorNotReady behind
@@ -303,7 +328,8 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
     S.cursor = reinterpret_cast<unsigned long long *>(p + SL.cursor);
     S.cand = reinterpret_cast<float *>(p + SL.cand);
     S.cand_cap = (slice - SL.fixed) / 4;
-    if (hipEventCreateWithFlags(&ix->res[r].done, hipEventDisableTiming) != hipSuccess)
+    if (hipEventCreateWithFlags(&ix->res[r].done, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreate(&ix->res[r].t0) != hipSuccess || hipEventCreate(&ix->res[r].t1) != hipSuccess)
       return bail(fail(RTAMS_EHIP, "hipEventCreate failed"));
   }
   if (hipDeviceSynchronize() != hipSuccess) return bail(fail(RTAMS_EHIP, "hipDeviceSynchronize failed"));
@@ -315,7 +341,12 @@ int rtams_destroy(rtams_index *ix) {
   if (!ix) return RTAMS_OK;
   if (ix->have_data_stream) (void)hipStreamSynchronize(ix->data_stream);
   for (int r = 0; r < ix->n_res; ++r)
-    if (ix->res[r].done) { (void)hipEventSynchronize(ix->res[r].done); (void)hipEventDestroy(ix->res[r].done); }
+    if (ix->res[r].done) {
+      (void)hipEventSynchronize(ix->res[r].done);
+      (void)hipEventDestroy(ix->res[r].done);
+      if (ix->res[r].t0) (void)hipEventDestroy(ix->res[r].t0);
+      if (ix->res[r].t1) (void)hipEventDestroy(ix->res[r].t1);
+    }
   delete[] ix->res;
   if (ix->data_done) (void)hipEventDestroy(ix->data_done);
   if (ix->mirror) (void)hipHostFree((void *)ix->mirror);
@@ -405,7 +436,10 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   int64_t cap = ix->scan_max_workgroups.load(std::memory_order_relaxed);
   if (cap > 0 && pairs * splits > cap) splits = cap / pairs;
   if (splits < 1) splits = 1;
+  const bool timed = ix->profile_scan.load(std::memory_order_relaxed) != 0;
+  if (timed) (void)hipEventRecord(ix->res[r].t0, s);
   launch_scan(D, nq, nprobe, ix->cfg.max_nprobe, d_queries, (int)splits, S, s);
+  if (timed) { (void)hipEventRecord(ix->res[r].t1, s); ix->res[r].timed = true; }
   launch_select(D, nq, k, nprobe, ix->cfg.max_nprobe, S, d_out_dist, d_out_ids, s);
   hipError_t e = hipGetLastError();
   hipError_t e2 = hipEventRecord(ix->res[r].done, s);
@@ -599,8 +633,28 @@ int rtams_poll_error(rtams_index *ix) {
   return ix->mirror->error;
 }
 
+int rtams_scan_time(rtams_index *ix, double *ms_sum, int64_t *launches, int reset) {
+  if (!ix) return fail(RTAMS_EINVAL, "NULL argument");
+  for (int r = 0; r < ix->n_res; ++r) {  // collect from requests that have finished
+    int st = RES_PENDING;
+    if (ix->res[r].state.load(std::memory_order_acquire) == RES_PENDING &&
+        hipEventQuery(ix->res[r].done) == hipSuccess &&
+        ix->res[r].state.compare_exchange_strong(st, RES_BUSY, std::memory_order_acq_rel)) {
+      harvest(ix, ix->res[r]);
+      ix->res[r].state.store(RES_FREE, std::memory_order_release);
+    }
+  }
+  (void)hipGetLastError();
+  std::lock_guard<std::mutex> g(ix->prof_mutex);
+  if (ms_sum) *ms_sum = ix->scan_ms;
+  if (launches) *launches = ix->scan_launches;
+  if (reset) { ix->scan_ms = 0.0; ix->scan_launches = 0; }
+  return RTAMS_OK;
+}
+
 int rtams_set_param(rtams_index *ix, const char *key, int64_t value) {
   if (!ix || !key) return fail(RTAMS_EINVAL, "NULL argument");
+  if (!strcmp(key, "profile_scan")) { ix->profile_scan = value; return RTAMS_OK; }
   if (!strcmp(key, "scan_split_target")) { ix->scan_split_target = value; return RTAMS_OK; }
   if (!strcmp(key, "scan_max_workgroups")) { ix->scan_max_workgroups = value; return RTAMS_OK; }
   return fail(RTAMS_EINVAL, "unknown parameter %s", key);

@@ -27,7 +27,7 @@ SYMBOLS = [
     "rtams_set_centroids", "rtams_add", "rtams_search", "rtams_rearrange", "rtams_ntotal",
     "rtams_list_size", "rtams_list_info", "rtams_list_export", "rtams_list_chain",
     "rtams_list_sizes", "rtams_pool_stats", "rtams_validate", "rtams_probe", "rtams_assign",
-    "rtams_poll_error", "rtams_last_error", "rtams_set_param",
+    "rtams_poll_error", "rtams_last_error", "rtams_set_param", "rtams_scan_time",
 ]
 
 
@@ -90,6 +90,7 @@ def lib():
         L.rtams_poll_error.argtypes = [vp]
         L.rtams_last_error.restype = C.c_char_p
         L.rtams_set_param.argtypes = [vp, C.c_char_p, i64]
+        L.rtams_scan_time.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), C.c_int]
         _lib = L
     return _lib
 
@@ -256,6 +257,11 @@ class Index:
 
     def poll_error(self) -> int:
         return lib().rtams_poll_error(self._h)
+
+    def scan_time(self, reset: bool = False) -> Tuple[float, int]:
+        ms, n = C.c_double(), C.c_int64()
+        _chk(lib().rtams_scan_time(self._h, C.byref(ms), C.byref(n), int(reset)), "rtams_scan_time")
+        return ms.value, n.value
 
     def set_param(self, key: str, value: int) -> None:
         _chk(lib().rtams_set_param(self._h, key.encode(), value), "rtams_set_param")

@@ -106,6 +106,30 @@ def test_integer_valued_distances_are_exact():
     g.close()
 
 
+@pytest.mark.parametrize("metric", ["l2", "ip"])
+def test_many_lists_assignment_and_probes(metric):
+    """More centroids than one pass of a workgroup covers: each thread of the
+    coarse kernel walks several centroid rows (nlist 16384, as in the largest
+    configuration), for a big insertion batch and for a query batch."""
+    rng = np.random.default_rng(31)
+    d, nlist = 8, 16384
+    C = rng.standard_normal((nlist, d), dtype=np.float32)
+    w = synth.Workload("many-lists", metric, d, nlist, 64, 64, 10, np.zeros((0, d), np.float32), C,
+                       np.zeros((0, d), np.float32), np.zeros((0, d), np.float32), 1, 0)
+    g, o = make_pair(w, pool_blocks=20000, candidates_per_query=4096)
+    y = rng.standard_normal((20000, d), dtype=np.float32)
+    assert np.array_equal(g.assign(dev(y)).cpu().numpy(), o.assign(y))
+    for nq in (3, 256):
+        assert np.array_equal(g.probe(dev(y[:nq]), 64).cpu().numpy(), o.probe(y[:nq], 64))
+    g.add(dev(y)); o.add(y)
+    g.validate()
+    assert np.array_equal(g.list_sizes(), o.list_sizes())
+    dd, ii = g.search(dev(y[:256]), 10, 64)
+    rd, ri = o.search(y[:256], 10, 64)
+    assert_topk_matches(metric, dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6)
+    g.close()
+
+
 def test_caller_ids_and_ragged_tail():
     """Caller-supplied ids; list lengths that end inside a 64-vector group and
     inside a block; a batch that opens several blocks for one list."""
