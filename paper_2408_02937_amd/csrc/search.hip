@@ -233,17 +233,83 @@ __global__ __launch_bounds__(256) void k_scan(Dev D, int nprobe, int max_nprobe,
 
 // ------------------------------------------------------------ top-k selection
 // One workgroup per query over its candidate slice: the k best by (score, id).
+//
+// The slice holds tens of thousands of scores of which k survive, so the exact
+// selection runs on a filtered subset kept in LDS: the k-th best score of the
+// first probed lists (the shortest prefix of them with at least k entries) is
+// an upper bound of the final k-th best; one pass over the slice keeps what is
+// not worse than that bound.  If more survive than LDS holds, the selection
+// falls back to working on the whole slice in place.
+constexpr int kSurvivorCap = 4096;
+
+struct SelectShared {
+  uint32_t hist[256];
+  uint32_t bc[4];
+  uint32_t cnt[2];
+  uint64_t k1[kMaxK];
+  uint64_t k2[kMaxK];
+  uint32_t pay[kMaxK];
+};
+
+// Exact top-k among `count` items given by key(j) (32-bit score key) and
+// item(j) (candidate index, for the id lookup).  Leaves the winners sorted in
+// sh.k1 (score key), sh.k2 (id key), sh.pay (candidate index); returns how many.
+template <typename KeyFn, typename ItemFn, typename IdFn>
+__device__ int select_topk(int count, int k, KeyFn key, ItemFn item, IdFn id_of, SelectShared &sh) {
+  auto key_of_id = [](int64_t id) -> uint64_t { return (uint64_t)id ^ 0x8000000000000000ull; };
+  const int kk = k < count ? k : count;
+  SelectResult r1{~0ull, 0, 0}, r2{~0ull, 0, 0};
+  const bool all = count <= k;
+  if (!all) {
+    r1 = wg_radix_select<32>(count, (uint32_t)k, [&](int j, uint64_t &kv) { kv = key(j); return true; },
+                             sh.hist, sh.bc);
+    if (r1.c_eq > r1.need)  // ties at the boundary go to the lower id
+      r2 = wg_radix_select<64>(count, r1.need,
+                               [&](int j, uint64_t &kv) {
+                                 if (key(j) != (uint32_t)r1.T) return false;
+                                 kv = key_of_id(id_of(item(j)));
+                                 return true;
+                               },
+                               sh.hist, sh.bc);
+  }
+  if (threadIdx.x == 0) sh.cnt[0] = sh.cnt[1] = 0;
+  __syncthreads();
+  for (int j = threadIdx.x; j < count; j += kSelThreads) {
+    uint32_t kv = key(j);
+    bool take = all || kv < (uint32_t)r1.T;
+    int64_t id = 0;
+    bool have_id = false;
+    if (!take && kv == (uint32_t)r1.T) {
+      if (r1.c_eq <= r1.need) take = true;
+      else {
+        id = id_of(item(j)); have_id = true;
+        uint64_t ik = key_of_id(id);
+        if (ik < r2.T) take = true;
+        else if (ik == r2.T) take = atomicAdd(&sh.cnt[1], 1u) < r2.need;  // identical (score, id) pairs
+      }
+    }
+    if (take) {
+      if (!have_id) id = id_of(item(j));
+      uint32_t p = atomicAdd(&sh.cnt[0], 1u);
+      sh.k1[p] = kv; sh.k2[p] = key_of_id(id); sh.pay[p] = (uint32_t)item(j);
+    }
+  }
+  __syncthreads();
+  const int m = next_pow2(kk > 0 ? kk : 1);
+  for (int p = kk + threadIdx.x; p < m; p += kSelThreads) { sh.k1[p] = ~0ull; sh.k2[p] = ~0ull; sh.pay[p] = 0; }
+  wg_bitonic_sort(m, sh.k1, sh.k2, sh.pay);
+  return kk;
+}
+
 __global__ __launch_bounds__(kSelThreads) void k_select(Dev D, int k, int nprobe, int max_nprobe,
                                                         SearchScratch S, float *__restrict__ out_dist,
                                                         int64_t *__restrict__ out_ids) {
-  __shared__ uint32_t hist[256];
-  __shared__ uint32_t bc[4];
-  __shared__ uint32_t cnt[2];
+  __shared__ SelectShared sh;
   __shared__ uint32_t offs[kMaxNprobe];
   __shared__ int32_t lists[kMaxNprobe];
-  __shared__ uint64_t k1[kMaxK];
-  __shared__ uint64_t k2[kMaxK];
-  __shared__ uint32_t pay[kMaxK];
+  __shared__ uint32_t skey[kSurvivorCap];
+  __shared__ uint32_t sidx[kSurvivorCap];
+  __shared__ uint32_t scount;
   const int q = blockIdx.x;
   const int n = (int)S.qtotal[q];
   const float *cand = S.cand + S.qbase[q];
@@ -252,7 +318,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Dev D, int k, int nprobe
     offs[p] = S.probe_off[(size_t)q * max_nprobe + p];
     lists[p] = S.probe_list[(size_t)q * max_nprobe + p];
   }
-  if (threadIdx.x == 0) cnt[0] = cnt[1] = 0;
+  if (threadIdx.x == 0) scount = 0;
   __syncthreads();
 
   auto key1 = [&](int i) -> uint32_t {
@@ -271,53 +337,38 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Dev D, int k, int nprobe
     uint32_t b = (uint32_t)*table_entry(D, lists[lo], pos / (uint32_t)D.T_m);
     return block_ids(D, b)[pos % (uint32_t)D.T_m];
   };
-  auto key_of_id = [](int64_t id) -> uint64_t { return (uint64_t)id ^ 0x8000000000000000ull; };
 
-  const int kk = k < n ? k : n;  // results that exist
-  SelectResult r1{~0ull, 0, 0}, r2{~0ull, 0, 0};
-  const bool all = n <= k;
-  if (!all) {
-    r1 = wg_radix_select<32>(n, (uint32_t)k, [&](int i, uint64_t &key) { key = key1(i); return true; },
-                             hist, bc);
-    if (r1.c_eq > r1.need)  // ties at the boundary go to the lower id
-      r2 = wg_radix_select<64>(n, r1.need,
-                               [&](int i, uint64_t &key) {
-                                 if (key1(i) != (uint32_t)r1.T) return false;
-                                 key = key_of_id(id_of(i));
-                                 return true;
-                               },
-                               hist, bc);
-  }
-  __syncthreads();
-  for (int i = threadIdx.x; i < n; i += kSelThreads) {
-    uint32_t key = key1(i);
-    bool take = all || key < (uint32_t)r1.T;
-    int64_t id = 0;
-    bool have_id = false;
-    if (!take && key == (uint32_t)r1.T) {
-      if (r1.c_eq <= r1.need) take = true;
-      else {
-        id = id_of(i); have_id = true;
-        uint64_t ik = key_of_id(id);
-        if (ik < r2.T) take = true;
-        else if (ik == r2.T) take = atomicAdd(&cnt[1], 1u) < r2.need;  // identical (score, id) pairs
+  int kk;
+  bool in_lds = false;
+  if (n > k && n > kSurvivorCap) {
+    // shortest prefix of the probed lists holding at least k candidates
+    int m0 = n;
+    for (int p = 1; p < nprobe; ++p)
+      if (offs[p] >= (uint32_t)k) { m0 = (int)offs[p]; break; }
+    SelectResult r0 = wg_radix_select<32>(
+        m0, (uint32_t)k, [&](int i, uint64_t &kv) { kv = key1(i); return true; }, sh.hist, sh.bc);
+    const uint32_t bound = (uint32_t)r0.T;
+    for (int i = threadIdx.x; i < n; i += kSelThreads) {
+      uint32_t kv = key1(i);
+      if (kv <= bound) {
+        uint32_t pos = atomicAdd(&scount, 1u);
+        if (pos < (uint32_t)kSurvivorCap) { skey[pos] = kv; sidx[pos] = (uint32_t)i; }
       }
     }
-    if (take) {
-      if (!have_id) id = id_of(i);
-      uint32_t p = atomicAdd(&cnt[0], 1u);
-      k1[p] = key; k2[p] = key_of_id(id); pay[p] = (uint32_t)i;
-    }
+    __syncthreads();
+    in_lds = scount <= (uint32_t)kSurvivorCap;
   }
-  __syncthreads();
-  const int m = next_pow2(kk > 0 ? kk : 1);
-  for (int p = kk + threadIdx.x; p < m; p += kSelThreads) { k1[p] = ~0ull; k2[p] = ~0ull; pay[p] = 0; }
-  wg_bitonic_sort(m, k1, k2, pay);
+  if (in_lds)
+    kk = select_topk((int)scount, k, [&](int j) { return skey[j]; }, [&](int j) { return (int)sidx[j]; },
+                     id_of, sh);
+  else
+    kk = select_topk(n, k, key1, [](int j) { return j; }, id_of, sh);
+
   for (int r = threadIdx.x; r < k; r += kSelThreads) {
     size_t o = (size_t)q * k + r;
     if (r < kk) {
-      out_dist[o] = cand[pay[r]];
-      out_ids[o] = (int64_t)(k2[r] ^ 0x8000000000000000ull);
+      out_dist[o] = cand[sh.pay[r]];
+      out_ids[o] = (int64_t)(sh.k2[r] ^ 0x8000000000000000ull);
     } else {
       out_dist[o] = metric == 0 ? __builtin_inff() : -__builtin_inff();
       out_ids[o] = -1;

@@ -130,6 +130,28 @@ def test_many_lists_assignment_and_probes(metric):
     g.close()
 
 
+def test_massive_ties_fall_back_to_in_place_selection():
+    """Thousands of identical vectors: every candidate ties at the k-th score, more
+    than the selection keeps in LDS, so the lowest ids must win."""
+    rng = np.random.default_rng(9)
+    d, nlist = 16, 4
+    C = rng.standard_normal((nlist, d), dtype=np.float32)
+    w = synth.Workload("ties", "l2", d, nlist, 64, 4, 100, np.zeros((0, d), np.float32), C,
+                       np.zeros((0, d), np.float32), np.zeros((0, d), np.float32), 1, 0)
+    g, o = make_pair(w, pool_blocks=400, candidates_per_query=20000)
+    same = np.repeat(C[1:2] + np.float32(0.25), 9000, axis=0)
+    other = (C[rng.integers(0, nlist, 3000)] + rng.standard_normal((3000, d))).astype(np.float32)
+    ids = rng.permutation(12000).astype(np.int64)
+    y = np.concatenate([same, other])
+    g.add(dev(y), dev(ids)); o.add(y, ids)
+    q = np.concatenate([C[1:2] + np.float32(0.25), other[:7]])
+    dd, ii = g.search(dev(q), 100, 4)
+    rd, ri = o.search(q, 100, 4)
+    assert np.array_equal(ii.cpu().numpy()[0], ri[0]) and np.all(dd.cpu().numpy()[0] == 0.0)
+    assert_topk_matches("l2", dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6)
+    g.close()
+
+
 def test_caller_ids_and_ragged_tail():
     """Caller-supplied ids; list lengths that end inside a 64-vector group and
     inside a block; a batch that opens several blocks for one list."""
