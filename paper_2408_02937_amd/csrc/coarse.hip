@@ -37,14 +37,21 @@ __device__ inline bool better_pair(int metric, double a, int ia, double b, int i
 template <int METRIC, int VT, bool ARGMIN>
 __global__ __launch_bounds__(kCoarseThreads) void k_coarse(
     Dev D, int64_t n, const float *__restrict__ Y, int splits, double *__restrict__ scores,
-    double *__restrict__ pscore, int32_t *__restrict__ pidx, unsigned long long *cursor_to_clear) {
+    double *__restrict__ pscore, int32_t *__restrict__ pidx, unsigned long long *cursor_to_clear,
+    uint32_t *__restrict__ zero, int zero_n) {
   extern __shared__ double ylds[];  // [VT][d]
   __shared__ double red_s[kCoarseThreads];
   __shared__ int red_i[kCoarseThreads];
   const int d = D.d, d4 = D.d4;
   const int64_t v0 = (int64_t)blockIdx.x * VT;
   const int split = blockIdx.y;
+  // per-request counters of the search plan start from zero (no memset node on the stream)
   if (cursor_to_clear && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *cursor_to_clear = 0ull;
+  if (zero) {
+    const int nthreads = gridDim.x * gridDim.y * kCoarseThreads;
+    for (int i = (blockIdx.y * gridDim.x + blockIdx.x) * kCoarseThreads + threadIdx.x; i < zero_n; i += nthreads)
+      zero[i] = 0u;
+  }
 
   for (int t = threadIdx.x; t < VT * d; t += kCoarseThreads) {
     int v = t / d, j = t - v * d;
@@ -131,28 +138,29 @@ __global__ __launch_bounds__(kCoarseThreads) void k_coarse(
 
 template <bool ARGMIN>
 static void launch_coarse(const Dev &D, int64_t n, const float *Y, int splits, double *scores,
-                          double *pscore, int32_t *pidx, unsigned long long *cursor, hipStream_t s) {
+                          double *pscore, int32_t *pidx, unsigned long long *cursor, uint32_t *zero,
+                          int zero_n, hipStream_t s) {
   if (n <= 0) return;
   int vt = coarse_vt(D.d);
   dim3 grid((unsigned)((n + vt - 1) / vt), (unsigned)splits);
   size_t lds = (size_t)vt * D.d * sizeof(double);
 #define RTAMS_GO(M, V) \
   hipLaunchKernelGGL((k_coarse<M, V, ARGMIN>), grid, dim3(kCoarseThreads), lds, s, D, n, Y, splits, \
-                     scores, pscore, pidx, cursor)
+                     scores, pscore, pidx, cursor, zero, zero_n)
   if (D.metric == 0) { if (vt == 8) RTAMS_GO(0, 8); else RTAMS_GO(0, 4); }
   else               { if (vt == 8) RTAMS_GO(1, 8); else RTAMS_GO(1, 4); }
 #undef RTAMS_GO
 }
 
 void launch_coarse_scores(const Dev &D, int64_t n, const float *Y, double *scores,
-                          unsigned long long *cursor_to_clear, hipStream_t s) {
+                          unsigned long long *cursor_to_clear, uint32_t *zero, int zero_n, hipStream_t s) {
   int splits = coarse_splits(D, n, 0);
-  launch_coarse<false>(D, n, Y, splits, scores, nullptr, nullptr, cursor_to_clear, s);
+  launch_coarse<false>(D, n, Y, splits, scores, nullptr, nullptr, cursor_to_clear, zero, zero_n, s);
 }
 
 void launch_coarse_argmin(const Dev &D, int64_t n, const float *Y, int splits, double *pscore,
                           int32_t *pidx, hipStream_t s) {
-  launch_coarse<true>(D, n, Y, splits, nullptr, pscore, pidx, nullptr, s);
+  launch_coarse<true>(D, n, Y, splits, nullptr, pscore, pidx, nullptr, nullptr, 0, s);
 }
 
 }  // namespace rtams

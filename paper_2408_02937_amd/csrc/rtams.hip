@@ -60,7 +60,8 @@ bool config_ok(const rtams_config *c, bool need_memory) {
     return fail(RTAMS_EINVAL, "block_vecs must be a positive multiple of 64, got %d", c->block_vecs), false;
   if (c->n_resources < 1 || c->n_resources > 256)
     return fail(RTAMS_EINVAL, "n_resources must be in 1..256"), false;
-  if (c->max_batch < 1) return fail(RTAMS_EINVAL, "max_batch must be positive"), false;
+  if (c->max_batch < 1 || c->max_batch > (1 << 20))
+    return fail(RTAMS_EINVAL, "max_batch must be in 1..1048576"), false;
   if (c->max_k < 1 || c->max_k > kMaxK) return fail(RTAMS_EINVAL, "max_k must be in 1..%d", kMaxK), false;
   if (c->max_nprobe < 1 || c->max_nprobe > kMaxNprobe || c->max_nprobe > c->nlist)
     return fail(RTAMS_EINVAL, "max_nprobe must be in 1..min(nlist, %d)", kMaxNprobe), false;
@@ -114,6 +115,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
 
 struct ScratchLayout {
   size_t scores, probe_list, probe_len, probe_off, qbase, qtotal, cursor, cand, fixed;
+  size_t list_cnt, pair_slot, grouped, tile_desc, ntiles;
 };
 
 void lay_out_scratch(const rtams_config *c, ScratchLayout *S) {
@@ -127,6 +129,11 @@ void lay_out_scratch(const rtams_config *c, ScratchLayout *S) {
   S->qbase = take(mb * 8);
   S->qtotal = take(mb * 4);
   S->cursor = take(8);
+  S->list_cnt = take((size_t)c->nlist * 4 + 4);
+  S->pair_slot = take(mb * mp * 4);
+  S->grouped = take(mb * mp * 4);
+  S->tile_desc = take(mb * mp * 16);
+  S->ntiles = take(4);
   S->cand = o;
   S->fixed = o;
 }
@@ -326,6 +333,11 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
     S.qbase = reinterpret_cast<unsigned long long *>(p + SL.qbase);
     S.qtotal = reinterpret_cast<uint32_t *>(p + SL.qtotal);
     S.cursor = reinterpret_cast<unsigned long long *>(p + SL.cursor);
+    S.list_cnt = reinterpret_cast<uint32_t *>(p + SL.list_cnt);
+    S.pair_slot = reinterpret_cast<uint32_t *>(p + SL.pair_slot);
+    S.grouped = reinterpret_cast<uint32_t *>(p + SL.grouped);
+    S.tile_desc = reinterpret_cast<uint4 *>(p + SL.tile_desc);
+    S.ntiles = reinterpret_cast<uint32_t *>(p + SL.ntiles);
     S.cand = reinterpret_cast<float *>(p + SL.cand);
     S.cand_cap = (slice - SL.fixed) / 4;
     if (hipEventCreateWithFlags(&ix->res[r].done, hipEventDisableTiming) != hipSuccess ||
@@ -423,10 +435,11 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const Dev &D = ix->dev;
   const SearchScratch &S = ix->res[r].s;
-  launch_coarse_scores(D, nq, d_queries, S.scores, S.cursor, s);
+  launch_coarse_scores(D, nq, d_queries, S.scores, S.cursor, S.list_cnt, D.nlist, s);
   launch_probe_plan(D, nq, nprobe, ix->cfg.max_nprobe, S, nullptr, s);
-  // spread a small batch over the chip: split each (query, list) pair into several workgroups
-  int64_t pairs = nq * nprobe;
+  launch_group(D, nq, nprobe, ix->cfg.max_nprobe, S, s);
+  // spread a small batch over the chip: split each tile (list x up to 8 queries) over several workgroups
+  int64_t pairs = scan_tiles_upper_bound(D, nq, nprobe);
   int64_t target = ix->scan_split_target.load(std::memory_order_relaxed);
   int64_t splits = (target + pairs - 1) / pairs;
   uint32_t max_len = ix->mirror->max_len;
@@ -466,7 +479,7 @@ int rtams_probe(rtams_index *ix, int64_t nq, const float *d_queries, int32_t npr
   if (r < 0) return fail(RTAMS_EBUSY, "all %d stream resources are in flight", ix->n_res);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const SearchScratch &S = ix->res[r].s;
-  launch_coarse_scores(ix->dev, nq, d_queries, S.scores, S.cursor, s);
+  launch_coarse_scores(ix->dev, nq, d_queries, S.scores, S.cursor, S.list_cnt, ix->dev.nlist, s);
   launch_probe_plan(ix->dev, nq, nprobe, ix->cfg.max_nprobe, S, d_out, s);
   hipError_t e = hipGetLastError();
   hipError_t e2 = hipEventRecord(ix->res[r].done, s);

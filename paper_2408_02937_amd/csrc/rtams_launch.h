@@ -14,9 +14,16 @@ struct SearchScratch {
   unsigned long long *qbase;  // [max_batch] start of the query's candidates in cand
   uint32_t *qtotal;     // [max_batch] candidates of the query
   unsigned long long *cursor; // bump pointer into cand
+  uint32_t *list_cnt;   // [nlist] queries probing each list, then start of the list's pair group
+  uint32_t *pair_slot;  // [max_batch][max_nprobe] rank of the pair among the pairs of its list
+  uint32_t *grouped;    // [max_batch * max_nprobe] pairs (query << 10 | probe) grouped by list
+  uint4 *tile_desc;     // [max_batch * max_nprobe] {list, first pair, pairs, 0} per scan tile
+  uint32_t *ntiles;     // number of scan tiles of this request
   float *cand;          // candidate scores
   unsigned long long cand_cap;
 };
+
+constexpr int kScanTileQueries = 8;  // queries that share one pass over a list
 
 // Scratch of the insertion path (lives in the pool's control region).
 struct InsertScratch {
@@ -32,7 +39,7 @@ int coarse_vt(int d);                      // vectors per workgroup for this dim
 int coarse_splits(const Dev &D, int64_t n, size_t part_cap);
 // full score matrix scores[n][nlist]
 void launch_coarse_scores(const Dev &D, int64_t n, const float *Y, double *scores,
-                          unsigned long long *cursor_to_clear, hipStream_t s);
+                          unsigned long long *cursor_to_clear, uint32_t *zero, int zero_n, hipStream_t s);
 // per (vector, split) best centroid
 void launch_coarse_argmin(const Dev &D, int64_t n, const float *Y, int splits, double *pscore,
                           int32_t *pidx, hipStream_t s);
@@ -48,6 +55,9 @@ void launch_publish(const Dev &D, hipStream_t s);
 // search.hip -----------------------------------------------------------------
 void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const SearchScratch &S,
                        int32_t *probe_out, hipStream_t s);
+void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const SearchScratch &S,
+                  hipStream_t s);
+int64_t scan_tiles_upper_bound(const Dev &D, int64_t nq, int nprobe);
 void launch_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const float *Q, int splits,
                  const SearchScratch &S, hipStream_t s);
 void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,

@@ -164,6 +164,8 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
     uint32_t len = __hip_atomic_load(&D.visible_len[list], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
     plen[p] = len;
     pay[p] = len;  // reuse as lengths for the prefix sum below
+    // rank of this pair among the pairs that probe the same list (grouping for the scan)
+    S.pair_slot[(size_t)q * max_nprobe + p] = atomicAdd(&S.list_cnt[list], 1u);
   }
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -187,48 +189,153 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
   }
 }
 
-// ------------------------------------------------------------------ list scan
-// Workgroup (pair, split): pair = (query, probed list).  Each wavefront takes
-// groups of 64 vectors of the list; lane = vector.  Per chunk of 4 dimensions a
-// wavefront loads 1 KiB of consecutive memory (one float4 per lane) and every
-// lane accumulates the score of its own vector against the query, whose values
-// are uniform over the wavefront.  Scores go to the query's candidate slice.
-template <int METRIC>
-__global__ __launch_bounds__(256) void k_scan(Dev D, int nprobe, int max_nprobe,
-                                              const float *__restrict__ Q, SearchScratch S) {
-  const int pair = blockIdx.x;
-  const int q = pair / nprobe, p = pair - q * nprobe;
-  const uint32_t len = S.probe_len[(size_t)q * max_nprobe + p];
-  if (len == 0) return;
-  const int list = S.probe_list[(size_t)q * max_nprobe + p];
-  float *out = S.cand + S.qbase[q] + S.probe_off[(size_t)q * max_nprobe + p];
-  const int lane = threadIdx.x & (kWave - 1);
-  const int wave = threadIdx.x / kWave;
-  const int waves = blockDim.x / kWave;
-  const uint32_t ngroups = (len + kWave - 1) / kWave;
-  const int d4 = D.d4;
-  const float4 *__restrict__ q4 = reinterpret_cast<const float4 *>(Q + (size_t)q * D.d);
-  const uint32_t gpb = (uint32_t)D.groups_per_block;
+// ------------------------------------------------------------ pair grouping
+// The (query, probed list) pairs of a request are grouped by list, so that the
+// scan reads a list once for up to kScanTileQueries queries.  One workgroup:
+// exclusive prefix sums over the lists of the pair counts and of the tile
+// counts, then the tile descriptors and the grouped pair array.
+constexpr int kGroupThreads = 1024;
 
-  for (uint32_t g = blockIdx.y * waves + wave; g < ngroups; g += gridDim.y * waves) {
-    const uint32_t bi = g / gpb, sub = g - bi * gpb;
-    const uint32_t b = (uint32_t)*table_entry(D, list, bi);
-    const float4 *__restrict__ x4 = block_vecs(D, b) + (size_t)sub * d4 * kWave + lane;
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-#pragma unroll 8
+__global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int nprobe, int max_nprobe,
+                                                         SearchScratch S) {
+  __shared__ uint32_t s_pairs[kGroupThreads];
+  __shared__ uint32_t s_tiles[kGroupThreads];
+  const int tid = threadIdx.x;
+  const int per = (D.nlist + kGroupThreads - 1) / kGroupThreads;
+  const int l0 = tid * per, l1 = min(D.nlist, l0 + per);
+  uint32_t np = 0, nt = 0;
+  for (int l = l0; l < l1; ++l) {
+    uint32_t c = S.list_cnt[l];
+    np += c;
+    nt += (c + kScanTileQueries - 1) / kScanTileQueries;
+  }
+  s_pairs[tid] = np;
+  s_tiles[tid] = nt;
+  __syncthreads();
+  for (int o = 1; o < kGroupThreads; o <<= 1) {  // inclusive scan over the threads
+    uint32_t a = tid >= o ? s_pairs[tid - o] : 0u, b = tid >= o ? s_tiles[tid - o] : 0u;
+    __syncthreads();
+    s_pairs[tid] += a;
+    s_tiles[tid] += b;
+    __syncthreads();
+  }
+  uint32_t pstart = s_pairs[tid] - np, tstart = s_tiles[tid] - nt;
+  if (tid == kGroupThreads - 1) *S.ntiles = s_tiles[tid];
+  for (int l = l0; l < l1; ++l) {
+    uint32_t c = S.list_cnt[l];
+    S.list_cnt[l] = pstart;  // from here on: where the list's pairs start
+    for (uint32_t t = 0; t * kScanTileQueries < c; ++t) {
+      uint32_t left = c - t * kScanTileQueries;
+      S.tile_desc[tstart++] = make_uint4((uint32_t)l, pstart + t * kScanTileQueries,
+                                         left < (uint32_t)kScanTileQueries ? left : (uint32_t)kScanTileQueries, 0u);
+    }
+    pstart += c;
+  }
+  __syncthreads();  // list starts written above are read below by other threads of this workgroup
+  for (int idx = tid; idx < nq * nprobe; idx += kGroupThreads) {
+    int q = idx / nprobe, p = idx - q * nprobe;
+    size_t o = (size_t)q * max_nprobe + p;
+    int l = S.probe_list[o];
+    S.grouped[S.list_cnt[l] + S.pair_slot[o]] = ((uint32_t)q << 10) | (uint32_t)p;
+  }
+}
+
+// ------------------------------------------------------------------ list scan
+// A tile is one list together with up to kScanTileQueries of the queries that
+// probe it; a workgroup handles (tile, split).  The tile's queries sit in LDS.
+// Each wavefront takes pairs of groups of 64 vectors of the list, lane = vector
+// (two vectors per lane).  Per chunk of 4 dimensions the wavefront loads 1 KiB
+// of consecutive memory per group (one float4 per lane) ONCE and every lane
+// accumulates the score of its two vectors against each query of the tile; a
+// query chunk is one broadcast LDS read shared by both vectors.  Scores go to
+// each query's candidate slice.
+template <int METRIC>
+__device__ __forceinline__ void accumulate(float &acc, const float4 &x, const float4 &y) {
+  if (METRIC == 0) {
+    const float t0 = x.x - y.x, t1 = x.y - y.y, t2 = x.z - y.z, t3 = x.w - y.w;
+    acc = fmaf(t0, t0, acc); acc = fmaf(t1, t1, acc); acc = fmaf(t2, t2, acc); acc = fmaf(t3, t3, acc);
+  } else {
+    acc = fmaf(x.x, y.x, acc); acc = fmaf(x.y, y.y, acc); acc = fmaf(x.z, y.z, acc); acc = fmaf(x.w, y.w, acc);
+  }
+}
+
+template <int METRIC, int NQ>
+__device__ __forceinline__ void scan_tile(const Dev &D, const SearchScratch &S,
+                                          const float *__restrict__ Q, int max_nprobe, int list,
+                                          uint32_t first, int cnt, uint32_t split, uint32_t nsplits,
+                                          float4 *qs) {
+  const int d4 = D.d4;
+  float *outp[NQ];
+  uint32_t lenq[NQ];
+  uint32_t maxlen = 0;
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    const uint32_t pk = S.grouped[first + (i < cnt ? i : 0)];
+    const uint32_t q = pk >> 10, p = pk & 1023u;
+    const size_t o = (size_t)q * max_nprobe + p;
+    lenq[i] = i < cnt ? S.probe_len[o] : 0u;  // padding queries write nothing
+    outp[i] = S.cand + S.qbase[q] + S.probe_off[o];
+    maxlen = lenq[i] > maxlen ? lenq[i] : maxlen;
+    const float4 *src = reinterpret_cast<const float4 *>(Q + (size_t)q * D.d);
+    for (int c = threadIdx.x; c < d4; c += blockDim.x) qs[i * d4 + c] = src[c];
+  }
+  __syncthreads();
+  const int lane = threadIdx.x & (kWave - 1);
+  const uint32_t wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
+  const uint32_t ngroups = (maxlen + kWave - 1) / kWave;
+  const uint32_t gpb = (uint32_t)D.groups_per_block;
+  const size_t group_stride = (size_t)d4 * kWave;
+  for (uint32_t g0 = 2 * (split * waves + wave); g0 < ngroups; g0 += 2 * nsplits * waves) {
+    const bool two = g0 + 1 < ngroups;  // uniform over the wavefront
+    const uint32_t g1 = two ? g0 + 1 : g0;
+    const uint32_t b0 = (uint32_t)*table_entry(D, list, g0 / gpb);
+    const uint32_t b1 = (uint32_t)*table_entry(D, list, g1 / gpb);
+    const float4 *__restrict__ xa = block_vecs(D, b0) + (size_t)(g0 % gpb) * group_stride + lane;
+    const float4 *__restrict__ xb = block_vecs(D, b1) + (size_t)(g1 % gpb) * group_stride + lane;
+    float acc0[NQ], acc1[NQ];
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) { acc0[i] = 0.f; acc1[i] = 0.f; }
+#pragma unroll 2
     for (int c = 0; c < d4; ++c) {
-      float4 x = x4[(size_t)c * kWave];
-      float4 y = q4[c];
-      if (METRIC == 0) {
-        float t0 = x.x - y.x, t1 = x.y - y.y, t2 = x.z - y.z, t3 = x.w - y.w;
-        a0 = fmaf(t0, t0, a0); a1 = fmaf(t1, t1, a1); a2 = fmaf(t2, t2, a2); a3 = fmaf(t3, t3, a3);
-      } else {
-        a0 = fmaf(x.x, y.x, a0); a1 = fmaf(x.y, y.y, a1); a2 = fmaf(x.z, y.z, a2); a3 = fmaf(x.w, y.w, a3);
+      const float4 x0 = xa[(size_t)c * kWave];
+      const float4 x1 = xb[(size_t)c * kWave];
+#pragma unroll
+      for (int i = 0; i < NQ; ++i) {
+        const float4 y = qs[i * d4 + c];
+        accumulate<METRIC>(acc0[i], x0, y);
+        accumulate<METRIC>(acc1[i], x1, y);
       }
     }
-    const uint32_t v = g * kWave + lane;
-    if (v < len) out[v] = (a0 + a1) + (a2 + a3);
+    const uint32_t v0 = g0 * kWave + lane, v1 = v0 + kWave;
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+      if (v0 < lenq[i]) outp[i][v0] = acc0[i];
+      if (two && v1 < lenq[i]) outp[i][v1] = acc1[i];
+    }
   }
+}
+
+// Workgroups are numbered so that those of one XCD (hardware hands consecutive
+// workgroup ids to the 8 XCDs in turn) work on consecutive tiles: the tiles of
+// one list, and the splits of one tile, then share that XCD's L2.
+constexpr uint32_t kXcds = 8;
+
+template <int METRIC>
+__global__ __launch_bounds__(256) void k_scan(Dev D, int max_nprobe, const float *__restrict__ Q,
+                                              uint32_t nsplits, SearchScratch S) {
+  extern __shared__ float4 qs[];  // [kScanTileQueries][d / 4]
+  const uint32_t work = *S.ntiles * nsplits;
+  const uint32_t per_xcd = (work + kXcds - 1) / kXcds;
+  const uint32_t in_xcd = blockIdx.x / kXcds;
+  const uint32_t logical = (blockIdx.x % kXcds) * per_xcd + in_xcd;
+  if (in_xcd >= per_xcd || logical >= work) return;
+  const uint32_t tile = logical / nsplits, split = logical - tile * nsplits;
+  const uint4 desc = S.tile_desc[tile];
+  const int list = (int)desc.x, cnt = (int)desc.z;
+  if (cnt == 1) scan_tile<METRIC, 1>(D, S, Q, max_nprobe, list, desc.y, cnt, split, nsplits, qs);
+  else if (cnt == 2) scan_tile<METRIC, 2>(D, S, Q, max_nprobe, list, desc.y, cnt, split, nsplits, qs);
+  else if (cnt <= 4) scan_tile<METRIC, 4>(D, S, Q, max_nprobe, list, desc.y, cnt, split, nsplits, qs);
+  else scan_tile<METRIC, 8>(D, S, Q, max_nprobe, list, desc.y, cnt, split, nsplits, qs);
 }
 
 // ------------------------------------------------------------ top-k selection
@@ -385,14 +492,29 @@ void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, con
                      S, probe_out);
 }
 
+void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const SearchScratch &S,
+                  hipStream_t s) {
+  if (nq <= 0) return;
+  hipLaunchKernelGGL(k_group, dim3(1), dim3(kGroupThreads), 0, s, D, (int)nq, nprobe, max_nprobe, S);
+}
+
+// No request has more tiles than this: full tiles plus one partial tile per touched list.
+int64_t scan_tiles_upper_bound(const Dev &D, int64_t nq, int nprobe) {
+  int64_t pairs = nq * nprobe;
+  return pairs / kScanTileQueries + (pairs < D.nlist ? pairs : D.nlist);
+}
+
 void launch_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const float *Q, int splits,
                  const SearchScratch &S, hipStream_t s) {
   if (nq <= 0) return;
-  dim3 grid((unsigned)(nq * nprobe), (unsigned)splits);
+  int64_t wgs = scan_tiles_upper_bound(D, nq, nprobe) * splits;
+  wgs = (wgs + kXcds - 1) / kXcds * kXcds + kXcds;
+  dim3 grid((unsigned)wgs);
+  size_t lds = (size_t)kScanTileQueries * D.d * sizeof(float);
   if (D.metric == 0)
-    hipLaunchKernelGGL(k_scan<0>, grid, dim3(256), 0, s, D, nprobe, max_nprobe, Q, S);
+    hipLaunchKernelGGL(k_scan<0>, grid, dim3(256), lds, s, D, max_nprobe, Q, (uint32_t)splits, S);
   else
-    hipLaunchKernelGGL(k_scan<1>, grid, dim3(256), 0, s, D, nprobe, max_nprobe, Q, S);
+    hipLaunchKernelGGL(k_scan<1>, grid, dim3(256), lds, s, D, max_nprobe, Q, (uint32_t)splits, S);
 }
 
 void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
