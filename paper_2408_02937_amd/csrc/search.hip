@@ -34,12 +34,19 @@ __device__ SelectResult wg_radix_select(int n, uint32_t k, Fn fn, uint32_t *hist
   uint64_t prefix = 0, mask = 0;
   uint32_t need = k, c_eq = 0;
   for (int shift = BITS - 8; shift >= 0; shift -= 8) {
-    for (int b = threadIdx.x; b < 256; b += kSelThreads) hist[b] = 0;
+    for (int b = threadIdx.x; b < 256; b += blockDim.x) hist[b] = 0;
     __syncthreads();
-    for (int i = threadIdx.x; i < n; i += kSelThreads) {
-      uint64_t key;
-      if (!fn(i, key)) continue;
-      if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & 255u], 1u);
+    for (int i0 = threadIdx.x; i0 < n; i0 += 4 * blockDim.x) {  // four independent loads in flight
+      uint64_t key[4];
+      bool ok[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + u * (int)blockDim.x;
+        ok[u] = i < n && fn(i, key[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (ok[u] && (key[u] & mask) == prefix) atomicAdd(&hist[(uint32_t)(key[u] >> shift) & 255u], 1u);
     }
     __syncthreads();
     if (threadIdx.x < kWave) {  // first wavefront: which bin holds the need-th item
@@ -83,7 +90,7 @@ __device__ inline void wg_bitonic_sort(int m, uint64_t *k1, uint64_t *k2, uint32
   for (int size = 2; size <= m; size <<= 1) {
     for (int stride = size >> 1; stride > 0; stride >>= 1) {
       __syncthreads();
-      for (int t = threadIdx.x; t < m / 2; t += kSelThreads) {
+      for (int t = threadIdx.x; t < m / 2; t += blockDim.x) {
         int i = 2 * t - (t & (stride - 1));
         int j = i + stride;
         bool up = (i & size) == 0;
@@ -259,27 +266,38 @@ __device__ __forceinline__ void accumulate(float &acc, const float4 &x, const fl
   }
 }
 
+constexpr int kPrefetch = 2;  // chunks of 4 dimensions kept in flight per group
+
 template <int METRIC, int NQ>
 __device__ __forceinline__ void scan_tile(const Dev &D, const SearchScratch &S,
                                           const float *__restrict__ Q, int max_nprobe, int list,
                                           uint32_t first, int cnt, uint32_t split, uint32_t nsplits,
                                           float4 *qs) {
   const int d4 = D.d4;
-  float *outp[NQ];
-  uint32_t lenq[NQ];
-  uint32_t maxlen = 0;
-#pragma unroll
-  for (int i = 0; i < NQ; ++i) {
+  // per-query facts of the tile live in LDS, out of the inner loop's registers
+  __shared__ uint32_t s_len[kScanTileQueries];
+  __shared__ float *s_out[kScanTileQueries];
+  __shared__ uint32_t s_maxlen;
+  if (threadIdx.x == 0) s_maxlen = 0;
+  __syncthreads();
+  if ((int)threadIdx.x < NQ) {
+    const int i = threadIdx.x;
     const uint32_t pk = S.grouped[first + (i < cnt ? i : 0)];
     const uint32_t q = pk >> 10, p = pk & 1023u;
     const size_t o = (size_t)q * max_nprobe + p;
-    lenq[i] = i < cnt ? S.probe_len[o] : 0u;  // padding queries write nothing
-    outp[i] = S.cand + S.qbase[q] + S.probe_off[o];
-    maxlen = lenq[i] > maxlen ? lenq[i] : maxlen;
-    const float4 *src = reinterpret_cast<const float4 *>(Q + (size_t)q * D.d);
+    const uint32_t len = i < cnt ? S.probe_len[o] : 0u;  // padding queries write nothing
+    s_len[i] = len;
+    s_out[i] = S.cand + S.qbase[q] + S.probe_off[o];
+    atomicMax(&s_maxlen, len);
+  }
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) {
+    const uint32_t pk = S.grouped[first + (i < cnt ? i : 0)];
+    const float4 *src = reinterpret_cast<const float4 *>(Q + (size_t)(pk >> 10) * D.d);
     for (int c = threadIdx.x; c < d4; c += blockDim.x) qs[i * d4 + c] = src[c];
   }
   __syncthreads();
+  const uint32_t maxlen = s_maxlen;
   const int lane = threadIdx.x & (kWave - 1);
   const uint32_t wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
   const uint32_t ngroups = (maxlen + kWave - 1) / kWave;
@@ -295,10 +313,47 @@ __device__ __forceinline__ void scan_tile(const Dev &D, const SearchScratch &S,
     float acc0[NQ], acc1[NQ];
 #pragma unroll
     for (int i = 0; i < NQ; ++i) { acc0[i] = 0.f; acc1[i] = 0.f; }
-#pragma unroll 2
-    for (int c = 0; c < d4; ++c) {
-      const float4 x0 = xa[(size_t)c * kWave];
-      const float4 x1 = xb[(size_t)c * kWave];
+    // Software pipeline over the chunks, two register sets of kPrefetch chunks
+    // each: while one set is being accumulated the loads of the other are in
+    // flight.
+    const int d4_main = d4 & ~(2 * kPrefetch - 1);
+    if (d4_main) {
+      float4 a0[kPrefetch], a1[kPrefetch], b0v[kPrefetch], b1v[kPrefetch];
+      auto load_set = [&](float4 *s0, float4 *s1, int cb) {
+#pragma unroll
+        for (int u = 0; u < kPrefetch; ++u) {
+          s0[u] = xa[(size_t)(cb + u) * kWave];
+          s1[u] = xb[(size_t)(cb + u) * kWave];
+        }
+        __builtin_amdgcn_sched_barrier(0);  // loads are issued here, not sunk towards their use
+      };
+      auto use_set = [&](const float4 *s0, const float4 *s1, int cb) {
+#pragma unroll
+        for (int u = 0; u < kPrefetch; ++u) {
+#pragma unroll
+          for (int i = 0; i < NQ; ++i) {
+            const float4 y = qs[i * d4 + cb + u];
+            accumulate<METRIC>(acc0[i], s0[u], y);
+            accumulate<METRIC>(acc1[i], s1[u], y);
+          }
+          __builtin_amdgcn_sched_barrier(0);  // keep one chunk's temporaries from piling up on the next
+        }
+      };
+      load_set(a0, a1, 0);
+      int c = 0;
+#pragma unroll 1
+      for (; c + 2 * kPrefetch < d4_main; c += 2 * kPrefetch) {
+        load_set(b0v, b1v, c + kPrefetch);
+        use_set(a0, a1, c);
+        load_set(a0, a1, c + 2 * kPrefetch);
+        use_set(b0v, b1v, c + kPrefetch);
+      }
+      load_set(b0v, b1v, c + kPrefetch);
+      use_set(a0, a1, c);
+      use_set(b0v, b1v, c + kPrefetch);
+    }
+    for (int c = d4_main; c < d4; ++c) {  // dimensions beyond the last full double set
+      const float4 x0 = xa[(size_t)c * kWave], x1 = xb[(size_t)c * kWave];
 #pragma unroll
       for (int i = 0; i < NQ; ++i) {
         const float4 y = qs[i * d4 + c];
@@ -309,8 +364,10 @@ __device__ __forceinline__ void scan_tile(const Dev &D, const SearchScratch &S,
     const uint32_t v0 = g0 * kWave + lane, v1 = v0 + kWave;
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
-      if (v0 < lenq[i]) outp[i][v0] = acc0[i];
-      if (two && v1 < lenq[i]) outp[i][v1] = acc1[i];
+      const uint32_t len = s_len[i];
+      float *out = s_out[i];
+      if (v0 < len) out[v0] = acc0[i];
+      if (two && v1 < len) out[v1] = acc1[i];
     }
   }
 }
@@ -348,6 +405,7 @@ __global__ __launch_bounds__(256) void k_scan(Dev D, int max_nprobe, const float
 // not worse than that bound.  If more survive than LDS holds, the selection
 // falls back to working on the whole slice in place.
 constexpr int kSurvivorCap = 4096;
+constexpr int kBoundPrefix = 8192;  // candidates (at least) that the first bound is taken from
 
 struct SelectShared {
   uint32_t hist[256];
@@ -381,7 +439,7 @@ __device__ int select_topk(int count, int k, KeyFn key, ItemFn item, IdFn id_of,
   }
   if (threadIdx.x == 0) sh.cnt[0] = sh.cnt[1] = 0;
   __syncthreads();
-  for (int j = threadIdx.x; j < count; j += kSelThreads) {
+  for (int j = threadIdx.x; j < count; j += blockDim.x) {
     uint32_t kv = key(j);
     bool take = all || kv < (uint32_t)r1.T;
     int64_t id = 0;
@@ -403,12 +461,14 @@ __device__ int select_topk(int count, int k, KeyFn key, ItemFn item, IdFn id_of,
   }
   __syncthreads();
   const int m = next_pow2(kk > 0 ? kk : 1);
-  for (int p = kk + threadIdx.x; p < m; p += kSelThreads) { sh.k1[p] = ~0ull; sh.k2[p] = ~0ull; sh.pay[p] = 0; }
+  for (int p = kk + threadIdx.x; p < m; p += blockDim.x) { sh.k1[p] = ~0ull; sh.k2[p] = ~0ull; sh.pay[p] = 0; }
   wg_bitonic_sort(m, sh.k1, sh.k2, sh.pay);
   return kk;
 }
 
-__global__ __launch_bounds__(kSelThreads) void k_select(Dev D, int k, int nprobe, int max_nprobe,
+constexpr int kTopkThreads = 1024;
+
+__global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprobe, int max_nprobe,
                                                         SearchScratch S, float *__restrict__ out_dist,
                                                         int64_t *__restrict__ out_ids) {
   __shared__ SelectShared sh;
@@ -421,7 +481,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Dev D, int k, int nprobe
   const int n = (int)S.qtotal[q];
   const float *cand = S.cand + S.qbase[q];
   const int metric = D.metric;
-  for (int p = threadIdx.x; p < nprobe; p += kSelThreads) {
+  for (int p = threadIdx.x; p < nprobe; p += kTopkThreads) {
     offs[p] = S.probe_off[(size_t)q * max_nprobe + p];
     lists[p] = S.probe_list[(size_t)q * max_nprobe + p];
   }
@@ -448,18 +508,30 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Dev D, int k, int nprobe
   int kk;
   bool in_lds = false;
   if (n > k && n > kSurvivorCap) {
-    // shortest prefix of the probed lists holding at least k candidates
+    // shortest prefix of the probed lists holding at least max(k, kBoundPrefix) candidates:
+    // the more of the nearest lists it covers, the fewer candidates survive the bound
+    const uint32_t want = (uint32_t)(k > kBoundPrefix ? k : kBoundPrefix);
     int m0 = n;
     for (int p = 1; p < nprobe; ++p)
-      if (offs[p] >= (uint32_t)k) { m0 = (int)offs[p]; break; }
+      if (offs[p] >= want) { m0 = (int)offs[p]; break; }
     SelectResult r0 = wg_radix_select<32>(
         m0, (uint32_t)k, [&](int i, uint64_t &kv) { kv = key1(i); return true; }, sh.hist, sh.bc);
     const uint32_t bound = (uint32_t)r0.T;
-    for (int i = threadIdx.x; i < n; i += kSelThreads) {
-      uint32_t kv = key1(i);
-      if (kv <= bound) {
-        uint32_t pos = atomicAdd(&scount, 1u);
-        if (pos < (uint32_t)kSurvivorCap) { skey[pos] = kv; sidx[pos] = (uint32_t)i; }
+    // one pass over the slice, four independent loads in flight per thread
+    for (int i0 = threadIdx.x; i0 < n; i0 += 4 * kTopkThreads) {
+      uint32_t kv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + u * kTopkThreads;
+        kv[u] = i < n ? key1(i) : 0xffffffffu;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + u * kTopkThreads;
+        if (i < n && kv[u] <= bound) {
+          uint32_t pos = atomicAdd(&scount, 1u);
+          if (pos < (uint32_t)kSurvivorCap) { skey[pos] = kv[u]; sidx[pos] = (uint32_t)i; }
+        }
       }
     }
     __syncthreads();
@@ -471,7 +543,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(Dev D, int k, int nprobe
   else
     kk = select_topk(n, k, key1, [](int j) { return j; }, id_of, sh);
 
-  for (int r = threadIdx.x; r < k; r += kSelThreads) {
+  for (int r = threadIdx.x; r < k; r += kTopkThreads) {
     size_t o = (size_t)q * k + r;
     if (r < kk) {
       out_dist[o] = cand[sh.pay[r]];
@@ -520,7 +592,7 @@ void launch_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const flo
 void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
                    const SearchScratch &S, float *out_dist, int64_t *out_ids, hipStream_t s) {
   if (nq <= 0) return;
-  hipLaunchKernelGGL(k_select, dim3((unsigned)nq), dim3(kSelThreads), 0, s, D, k, nprobe, max_nprobe,
+  hipLaunchKernelGGL(k_select, dim3((unsigned)nq), dim3(kTopkThreads), 0, s, D, k, nprobe, max_nprobe,
                      S, out_dist, out_ids);
 }
 
