@@ -8,6 +8,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <shared_mutex>
 
 #include "rtams_launch.h"
 
@@ -38,6 +39,7 @@ inline size_t up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Layout {
   size_t ctrl, hook, centroids, reserved_len, visible_len, online, nblk, exceed, seg_dir;
   size_t ins_assign, ins_did, ins_pscore, ins_pidx, part_cap;
+  size_t rearr_head, rearr_arrays;
   size_t fixed_end;          // end of the part that does not depend on the block count
   size_t slab, free_stack, mark, blocks;
   size_t block_stride;
@@ -48,6 +50,7 @@ struct Layout {
 };
 
 constexpr size_t kAlign = 256;
+constexpr uint32_t kRearrangeCap = 4096;  // block moves per rearrangement round
 constexpr size_t kHookBytes = 256;
 
 bool config_ok(const rtams_config *c, bool need_memory) {
@@ -93,6 +96,8 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
   L->ins_did = take((size_t)c->max_add_batch * 4);
   L->ins_pscore = take(L->part_cap * 8);
   L->ins_pidx = take(L->part_cap * 4);
+  L->rearr_head = take(sizeof(RearrangeHead));
+  L->rearr_arrays = take((size_t)kRearrangeCap * 4 * 7);
   L->fixed_end = o;
   L->ids_off = kHeaderBytes;
   L->vec_off = kHeaderBytes + (uint32_t)c->block_vecs * 8u;
@@ -155,6 +160,7 @@ struct rtams_index {
   Layout lay{};
   Dev dev{};
   InsertScratch ins{};
+  RearrangeScratch rearr{};
   HostMirror *mirror = nullptr;
   char *hook = nullptr;  // device scratch of the introspection calls
   Resource *res = nullptr;
@@ -164,6 +170,11 @@ struct rtams_index {
   hipStream_t data_stream = nullptr;
   bool have_data_stream = false;
   hipEvent_t data_done = nullptr;
+  // Searches hold this shared while they enqueue; a rearrangement takes it
+  // exclusively for the instant in which it fences the searches in flight.
+  std::shared_mutex fence_mutex;
+  hipEvent_t fence_ev[2] = {nullptr, nullptr};  // table switches of the running rearrangement
+  hipEvent_t fence_cur = nullptr;               // what a new search must wait for, or nullptr
   int64_t ntotal_host = 0;   // vectors handed to add so far
   int64_t avail_lb = 0;      // lower bound of the blocks still available in the pool
   std::atomic<int64_t> scan_split_target{2048};
@@ -235,6 +246,8 @@ int read_ctrl(rtams_index *ix, Ctrl *out) {
 
 }  // namespace
 
+static int rearrange_round(rtams_index *ix, int32_t list, hipStream_t s);
+
 extern "C" {
 
 const char *rtams_last_error(void) { return g_err; }
@@ -301,6 +314,16 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   ix->ins.pscore = reinterpret_cast<double *>(base + L.ins_pscore);
   ix->ins.pidx = reinterpret_cast<int32_t *>(base + L.ins_pidx);
   ix->ins.part_cap = L.part_cap;
+  {
+    uint32_t *a = reinterpret_cast<uint32_t *>(base + L.rearr_arrays);
+    RearrangeScratch &R = ix->rearr;
+    R.head = reinterpret_cast<RearrangeHead *>(base + L.rearr_head);
+    R.cap = kRearrangeCap;
+    R.mv_t = a; R.kind = a + kRearrangeCap; R.vic_rank = a + 2 * kRearrangeCap;
+    R.vic_new = a + 3 * kRearrangeCap; R.old_src = a + 4 * kRearrangeCap;
+    R.vic_list = reinterpret_cast<int32_t *>(a + 5 * kRearrangeCap);
+    R.vic_seq = reinterpret_cast<int32_t *>(a + 6 * kRearrangeCap);
+  }
   ix->avail_lb = L.nblocks;
 
   auto bail = [&](int code) { rtams_destroy(ix); return code; };
@@ -316,7 +339,9 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   void *dm = nullptr;
   if (hipHostGetDevicePointer(&dm, hm, 0) != hipSuccess) return bail(fail(RTAMS_EHIP, "hipHostGetDevicePointer failed"));
   D.mirror = static_cast<HostMirror *>(dm);
-  if (hipEventCreateWithFlags(&ix->data_done, hipEventDisableTiming) != hipSuccess)
+  if (hipEventCreateWithFlags(&ix->data_done, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&ix->fence_ev[0], hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&ix->fence_ev[1], hipEventDisableTiming) != hipSuccess)
     return bail(fail(RTAMS_EHIP, "hipEventCreate failed"));
 
   ix->res = new (std::nothrow) Resource[cfg->n_resources];
@@ -361,6 +386,8 @@ int rtams_destroy(rtams_index *ix) {
     }
   delete[] ix->res;
   if (ix->data_done) (void)hipEventDestroy(ix->data_done);
+  for (hipEvent_t e : ix->fence_ev)
+    if (e) (void)hipEventDestroy(e);
   if (ix->mirror) (void)hipHostFree((void *)ix->mirror);
   delete ix;
   return RTAMS_OK;
@@ -417,6 +444,11 @@ int rtams_add(rtams_index *ix, int64_t n, const float *d_vecs, const int64_t *d_
   HIP_TRY(hipGetLastError());
   ix->avail_lb -= need;
   ix->ntotal_host += n;
+  // Exceed() held for some list when an earlier batch was published (the device
+  // reports it through pinned memory): one rearrangement round behind this batch
+  if (ix->cfg.rearrange_threshold > 0 && ix->mirror->exceed_lists > 0) {
+    if ((rc = rearrange_round(ix, -1, s))) return rc;
+  }
   return leave_data_stream(ix, s);
 }
 
@@ -430,11 +462,14 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   if (!ix->has_centroids) return fail(RTAMS_ESTATE, "search before set_centroids");
   if (nq == 0) return RTAMS_OK;
   if (!d_queries || !d_out_dist || !d_out_ids) return fail(RTAMS_EINVAL, "NULL buffer");
+  std::shared_lock<std::shared_mutex> in_flight(ix->fence_mutex);
   int r = acquire(ix);
   if (r < 0) return fail(RTAMS_EBUSY, "all %d stream resources are in flight", ix->n_res);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const Dev &D = ix->dev;
   const SearchScratch &S = ix->res[r].s;
+  // a rearrangement is switching block tables: start behind its last switch
+  if (ix->fence_cur) (void)hipStreamWaitEvent(s, ix->fence_cur, 0);
   launch_coarse_scores(D, nq, d_queries, S.scores, S.cursor, S.list_cnt, D.nlist, s);
   launch_probe_plan(D, nq, nprobe, ix->cfg.max_nprobe, S, nullptr, s);
   launch_group(D, nq, nprobe, ix->cfg.max_nprobe, S, s);
@@ -462,10 +497,40 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   return RTAMS_OK;
 }
 
+// Grace period: the work enqueued next on the data stream starts only after
+// every search request that is in flight now has finished, and every search
+// enqueued from now on starts behind `ev` (the table switch just enqueued).
+static int fence_searches(rtams_index *ix, hipEvent_t ev, hipStream_t s) {
+  HIP_TRY(hipEventRecord(ev, s));
+  std::unique_lock<std::shared_mutex> g(ix->fence_mutex);
+  ix->fence_cur = ev;
+  for (int r = 0; r < ix->n_res; ++r)
+    if (ix->res[r].state.load(std::memory_order_acquire) == RES_PENDING)
+      HIP_TRY(hipStreamWaitEvent(s, ix->res[r].done, 0));
+  return RTAMS_OK;
+}
+
+static int rearrange_round(rtams_index *ix, int32_t list, hipStream_t s) {
+  const Dev &D = ix->dev;
+  launch_rearr_plan(D, ix->rearr, list, s);
+  launch_rearr_step(D, ix->rearr, 1, s);   // occupants out of the way, their tables switched
+  int rc = fence_searches(ix, ix->fence_ev[0], s);
+  if (rc) return rc;
+  launch_rearr_step(D, ix->rearr, 2, s);   // the list's blocks into place, its table switched
+  if ((rc = fence_searches(ix, ix->fence_ev[1], s))) return rc;
+  launch_rearr_release(D, ix->rearr, s);
+  HIP_TRY(hipGetLastError());
+  return RTAMS_OK;
+}
+
 int rtams_rearrange(rtams_index *ix, int32_t list, void *hip_stream) {
-  (void)hip_stream;
   if (!ix || list < -1 || list >= ix->cfg.nlist) return fail(RTAMS_EINVAL, "bad list");
-  return fail(RTAMS_EINVAL, "rearrange is not built yet");
+  std::lock_guard<std::mutex> g(ix->data_mutex);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  int rc = enter_data_stream(ix, s);
+  if (rc) return rc;
+  if ((rc = rearrange_round(ix, list, s))) return rc;  // blocks in use are the same before and after
+  return leave_data_stream(ix, s);
 }
 
 int rtams_probe(rtams_index *ix, int64_t nq, const float *d_queries, int32_t nprobe, int32_t *d_out,
@@ -475,6 +540,7 @@ int rtams_probe(rtams_index *ix, int64_t nq, const float *d_queries, int32_t npr
   if (!ix->has_centroids) return fail(RTAMS_ESTATE, "probe before set_centroids");
   if (nq == 0) return RTAMS_OK;
   if (!d_queries || !d_out) return fail(RTAMS_EINVAL, "NULL buffer");
+  std::shared_lock<std::shared_mutex> in_flight(ix->fence_mutex);
   int r = acquire(ix);
   if (r < 0) return fail(RTAMS_EBUSY, "all %d stream resources are in flight", ix->n_res);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);

@@ -34,6 +34,25 @@ struct InsertScratch {
   size_t part_cap;
 };
 
+// Scratch of one rearrangement round (lives in the pool's control region).
+struct RearrangeHead {
+  int32_t list;    // list being rearranged, -1 none
+  uint32_t count;  // moves of this round
+  uint32_t nvict;  // occupants that had to be moved out of the way
+  uint32_t done;   // the round reaches the end of the chain
+};
+struct RearrangeScratch {
+  RearrangeHead *head;
+  uint32_t cap;        // moves per round
+  uint32_t *mv_t;      // [cap] chain position of each move, ascending
+  uint32_t *kind;      // [cap] what sits at the target: 0 never handed out, 1 free, 2 a block in use
+  uint32_t *vic_rank;  // [cap] rank among the occupants in use
+  uint32_t *vic_new;   // [cap] block the occupant is copied to
+  uint32_t *old_src;   // [cap] block the list gives up
+  int32_t *vic_list;   // [cap] owner of the occupant
+  int32_t *vic_seq;    // [cap] its position in the owner's chain
+};
+
 // coarse.hip ---------------------------------------------------------------
 int coarse_vt(int d);                      // vectors per workgroup for this dimension
 int coarse_splits(const Dev &D, int64_t n, size_t part_cap);
@@ -62,6 +81,11 @@ void launch_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const flo
                  const SearchScratch &S, hipStream_t s);
 void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
                    const SearchScratch &S, float *out_dist, int64_t *out_ids, hipStream_t s);
+
+// rearrange.hip --------------------------------------------------------------
+void launch_rearr_plan(const Dev &D, const RearrangeScratch &R, int list, hipStream_t s);
+void launch_rearr_step(const Dev &D, const RearrangeScratch &R, int phase, hipStream_t s);
+void launch_rearr_release(const Dev &D, const RearrangeScratch &R, hipStream_t s);
 
 // maint.hip ------------------------------------------------------------------
 void launch_export(const Dev &D, int list, int64_t n, int64_t *ids, float *vecs, hipStream_t s);

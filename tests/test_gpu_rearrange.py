@@ -1,0 +1,150 @@
+"""In-place rearrangement on the GPU: the invariants the paper's Rearrangement
+algorithm must keep (logical content of every list, blocks in use, fewer header
+jumps), the Exceed() trigger, and searches running while blocks move."""
+import threading
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2408_02937_amd import rtams, synth
+from tests.gpu_common import assert_lists_equal, dev, make_pair
+from tests.helpers import assert_topk_matches
+
+pytestmark = pytest.mark.gpu
+
+
+def interleaved(nlist=3, d=8, T=64, rounds=6, seed=3, threshold=0, pool_blocks=200):
+    """Lists grown in turn, one block at a time, so every chain is scattered."""
+    rng = np.random.default_rng(seed)
+    C = (np.eye(nlist, d) * 10).astype(np.float32)
+    w = synth.Workload("interleaved", "l2", d, nlist, T, nlist, 10, np.zeros((0, d), np.float32), C,
+                       np.zeros((0, d), np.float32), np.zeros((0, d), np.float32), 1, seed)
+    g, o = make_pair(w, pool_blocks=pool_blocks, rearrange_threshold=threshold, candidates_per_query=8192)
+    for r in range(rounds):
+        for k in range(nlist):
+            y = (C[k] + 0.5 * rng.standard_normal((T, d))).astype(np.float32)
+            g.add(dev(y)); o.add(y)
+    return w, g, o, rng
+
+
+def runs_of(g, k):
+    return g.list_info(k)[1]
+
+
+def test_rearrange_makes_a_chain_contiguous_and_keeps_every_list():
+    w, g, o, _ = interleaved()
+    g.validate()
+    before = g.pool_stats().blocks_in_use
+    chains = [g.list_chain(k) for k in range(3)]
+    assert all(len(c) == 6 for c in chains) and runs_of(g, 0) == 6   # one jump per block
+    g.rearrange(0)
+    g.validate()
+    c0 = g.list_chain(0)
+    assert runs_of(g, 0) == 1 and np.array_equal(c0, c0[0] + np.arange(6))
+    assert g.pool_stats().blocks_in_use == before
+    assert_lists_equal(g, o)                                  # victims and target keep their content
+    for k in (1, 2):                                          # victims can be compacted afterwards
+        g.rearrange(k)
+        g.validate()
+        assert runs_of(g, k) == 1
+    assert g.pool_stats().blocks_in_use == before
+    assert_lists_equal(g, o)
+    g.add(dev(w.centroids)); o.add(w.centroids)               # the index keeps working
+    g.validate()
+    assert_lists_equal(g, o)
+    g.close()
+
+
+def test_rearrange_into_free_fresh_and_own_blocks():
+    """Targets that were never handed out, targets on the free stack, and targets
+    held by a later block of the same chain."""
+    w, g, o, rng = interleaved(nlist=2, rounds=4, pool_blocks=64)
+    g.rearrange(1)                       # list 1 starts at block 1: its last target is past cur_P
+    g.validate()
+    assert runs_of(g, 1) == 1
+    g.rearrange(0)                       # list 0 now finds free-stack blocks at its targets
+    g.validate()
+    assert runs_of(g, 0) == 1
+    st = g.pool_stats()
+    assert st.blocks_in_use == 8 and st.blocks_free + st.blocks_in_use == st.blocks_handed_out
+    assert_lists_equal(g, o)
+    for r in range(3):                   # grow both again, then compact the one that got scattered
+        for k in (1, 0):
+            y = (w.centroids[k] + 0.5 * rng.standard_normal((64, w.d))).astype(np.float32)
+            g.add(dev(y)); o.add(y)
+    g.rearrange(0); g.rearrange(1); g.rearrange(0)
+    g.validate()
+    assert runs_of(g, 0) == 1
+    assert_lists_equal(g, o)
+    g.close()
+
+
+def test_exceed_triggers_rearrangement_behind_the_batch():
+    """Exceed() is evaluated when a batch is published; the round is enqueued by
+    the next add (or by rearrange(-1)).  The oracle rearranges at once; the logical
+    content must agree at every point, the block structure must stay valid."""
+    w, g, o, rng = interleaved(nlist=3, rounds=2, threshold=200)   # 128 per list so far: no trigger
+    assert g.pool_stats().lists_exceeding == 0 and o.n_rearrange == 0
+    y = (w.centroids[1] + 0.5 * rng.standard_normal((73, w.d))).astype(np.float32)   # 201 > 200
+    g.add(dev(y)); o.add(y)
+    assert g.pool_stats().lists_exceeding == 1 and o.n_rearrange == 1
+    assert runs_of(g, 1) == 3                                      # blocks 1 | 4 | 6 7
+    g.add(dev(w.centroids[:1])); o.add(w.centroids[:1])            # carries the round
+    g.validate()
+    assert g.pool_stats().lists_exceeding == 0 and runs_of(g, 1) == 1
+    assert g.list_info(1)[2] == 0                                  # counter restarts
+    assert_lists_equal(g, o)
+    y = (w.centroids[2] + 0.5 * rng.standard_normal((72, w.d))).astype(np.float32)   # exactly 200: no trigger
+    g.add(dev(y)); o.add(y)
+    assert g.pool_stats().lists_exceeding == 0 and o.n_rearrange == 1
+    g.close()
+
+
+def test_searches_stay_correct_while_blocks_move():
+    w = synth.skewed_l2("zipf-rearr", 41, d=32, n_base=40_000, nlist=32, block_vecs=64, n_queries=256,
+                        n_inserts=64, nprobe=8, k=20)
+    g, o = make_pair(w, pool_blocks=1400, n_resources=8)
+    for b in range(0, len(w.base), 500):                   # many small batches: scattered chains
+        g.add(dev(w.base[b:b + 500])); o.add(w.base[b:b + 500])
+    torch.cuda.synchronize()
+    q = dev(w.queries)
+    rd, ri = o.search(w.queries, w.k, w.nprobe)
+    stop, bad, done = threading.Event(), [], [0]
+    streams = [torch.cuda.Stream() for _ in range(3)]
+
+    def searcher(s):
+        od = torch.empty((256, w.k), dtype=torch.float32, device="cuda:0")
+        oi = torch.empty((256, w.k), dtype=torch.int64, device="cuda:0")
+        while not stop.is_set():
+            try:
+                g.search(q, w.k, w.nprobe, od, oi, stream=s)
+            except rtams.RtamsError as e:
+                if e.code == rtams.EBUSY:
+                    s.synchronize()
+                    continue
+                bad.append(str(e)); return
+            s.synchronize()
+            try:
+                assert_topk_matches("l2", od.cpu().numpy(), oi.cpu().numpy(), rd, ri, rtol=1e-4, atol=1e-6)
+            except AssertionError as e:
+                bad.append(str(e)); return
+            done[0] += 1
+
+    threads = [threading.Thread(target=searcher, args=(s,)) for s in streams]
+    for t in threads:
+        t.start()
+    data = torch.cuda.Stream()
+    order = np.argsort(-g.list_sizes())
+    for rep in range(3):                                   # compacting one list scatters its neighbours
+        for k in order[:12]:
+            g.rearrange(int(k), stream=data)
+        data.synchronize()
+    stop.set()
+    for t in threads:
+        t.join()
+    assert not bad, bad[0]
+    assert done[0] > 0
+    g.validate()
+    assert_lists_equal(g, o)
+    g.close()
