@@ -44,6 +44,8 @@ def main() -> int:
     ap.add_argument("--latency-iters", type=int, default=300)
     ap.add_argument("--cpu-queries", type=int, default=1024, help="queries of the oracle sample; 0 skips it")
     ap.add_argument("--no-extras", action="store_true", help="only the timed steps (for profiler runs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only the plain copy kernel on 1 GiB (yardstick for the traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (see DESIGN.md, sharding)",
@@ -57,6 +59,14 @@ def main() -> int:
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
     dev = torch.device("cuda:0")
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            rtams.copy_plain(dst, src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_per_launch": 1 << 30, "launches": 5}))
+        return 0
     t_gen = time.perf_counter()
     w = synth.config(2, scale=args.scale)
     t_gen = time.perf_counter() - t_gen
@@ -134,7 +144,11 @@ def main() -> int:
         union_bytes.append(int(per_list(sizes[np.unique(pl)]).sum()))
     pair_b, union_b = float(np.mean(pair_bytes)), float(np.mean(union_bytes))
     scan_avg_ms = scan_ms / max(scan_n, 1)
-    achieved = pair_b / (scan_avg_ms * 1e-3) / 1e9 if scan_n else float("nan")
+    # The scan reads a list once for all the queries of the batch that probe it, so
+    # the bytes it must move are those of the UNION of the probed lists; bytes
+    # counted once per (query, list) pair are reported beside it, never credited.
+    achieved = union_b / (scan_avg_ms * 1e-3) / 1e9 if scan_n else float("nan")
+    traffic = measured_traffic(w.name, B)
 
     result = {
         "metric": "search QPS under concurrent insertion",
@@ -145,9 +159,8 @@ def main() -> int:
                    "block_vecs": w.block_vecs, "metric": w.metric, "query_batch": B, "nprobe": nprobe,
                    "k": k, "insert_batch": ib, "search_streams": args.search_streams, "seed": w.seed},
         "roofline": {"bound": "hbm", "kernel": "k_scan", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "bytes_per_launch": pair_b, "union_bytes_per_launch": union_b,
-                     "union_frac": union_b / (scan_avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if scan_n else None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "bytes_per_launch": union_b, "pair_bytes_per_launch": pair_b,
                      "avg_launch_ms": scan_avg_ms, "launches_timed": scan_n},
         "inserts_per_s_in_step": args.steps * ib / elapsed,
         "bulk_load_vectors_per_s": len(w.base) / bulk_s,
@@ -161,6 +174,19 @@ def main() -> int:
     print(json.dumps(result))
     g.close()
     return 0
+
+
+def measured_traffic(workload: str, batch: int):
+    """HBM bytes per scan launch from the committed profiler summary of this
+    workload (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel yardstick), or None."""
+    path = os.path.join(ROOT, "profiles", f"k_scan_{workload}_batch{batch}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
 
 
 def extras(args, g, w, torch, rtams, q_batches, queries, ins_batches, data_stream, search_streams, dev):

@@ -173,9 +173,14 @@ const char *rtams_last_error(void);
  * finished (ms_sum in milliseconds, launches = how many) and optionally resets
  * the sums.  Does not synchronise. */
 int rtams_scan_time(rtams_index *ix, double *ms_sum, int64_t *launches, int reset);
+/* Measurement aid, not part of the method: a plain device-to-device copy kernel
+ * (bytes a multiple of 16).  Profiler counters of HBM traffic are scaled by
+ * what they read for this kernel, whose traffic is known. */
+int rtams_copy_plain(void *d_dst, const void *d_src, size_t bytes, void *hip_stream);
 /* Launch-shape knobs ("restrict the number of blocks and threads per kernel",
- * Stream-Cached Multi-Stream Execution, consideration 2).  key: "scan_max_workgroups",
- * "scan_split_target", and "profile_scan" (see rtams_scan_time).  EINVAL for an unknown key. */
+ * Stream-Cached Multi-Stream Execution, consideration 2).  key: "scan_max_workgroups"
+ * (workgroups of one list-scan launch, default 1024 = 4 per CU), and "profile_scan"
+ * (see rtams_scan_time).  EINVAL for an unknown key. */
 int rtams_set_param(rtams_index *ix, const char *key, int64_t value);
 
 #ifdef __cplusplus

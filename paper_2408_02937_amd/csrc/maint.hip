@@ -109,6 +109,18 @@ __global__ void k_validate_totals(Dev D, int32_t *result2, unsigned long long *s
   if (sums[1] != D.ctrl->ntotal) report(result2, V_NTOTAL, 0);
 }
 
+// plain copy, 16 bytes per thread per step: the yardstick the HBM traffic counters are scaled by
+__global__ __launch_bounds__(256) void k_copy_plain(uint4 *__restrict__ dst, const uint4 *__restrict__ src,
+                                                    size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+void launch_copy_plain(void *dst, const void *src, size_t bytes, hipStream_t s) {
+  hipLaunchKernelGGL(k_copy_plain, dim3(4096), dim3(256), 0, s, static_cast<uint4 *>(dst),
+                     static_cast<const uint4 *>(src), bytes / 16);
+}
+
 void launch_export(const Dev &D, int list, int64_t n, int64_t *ids, float *vecs, hipStream_t s) {
   if (n <= 0) return;
   int64_t threads = n * D.d4;

@@ -120,7 +120,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
 
 struct ScratchLayout {
   size_t scores, probe_list, probe_len, probe_off, qbase, qtotal, cursor, cand, fixed;
-  size_t list_cnt, pair_slot, grouped, tile_desc, ntiles;
+  size_t list_cnt, list_len, pair_slot, grouped, tile_desc, queues, item_cap;
 };
 
 void lay_out_scratch(const rtams_config *c, ScratchLayout *S) {
@@ -134,11 +134,14 @@ void lay_out_scratch(const rtams_config *c, ScratchLayout *S) {
   S->qbase = take(mb * 8);
   S->qtotal = take(mb * 4);
   S->cursor = take(8);
-  S->list_cnt = take((size_t)c->nlist * 4 + 4);
+  // list_cnt and the queue heads are cleared together at the start of every request
+  S->list_cnt = take((size_t)c->nlist * 4);
+  S->queues = take(sizeof(ScanQueues));
+  S->list_len = take((size_t)c->nlist * 4);
   S->pair_slot = take(mb * mp * 4);
   S->grouped = take(mb * mp * 4);
-  S->tile_desc = take(mb * mp * 16);
-  S->ntiles = take(4);
+  S->item_cap = mb * mp * 4 > 65536 ? mb * mp * 4 : 65536;
+  S->tile_desc = take(S->item_cap * 16);
   S->cand = o;
   S->fixed = o;
 }
@@ -177,8 +180,8 @@ struct rtams_index {
   hipEvent_t fence_cur = nullptr;               // what a new search must wait for, or nullptr
   int64_t ntotal_host = 0;   // vectors handed to add so far
   int64_t avail_lb = 0;      // lower bound of the blocks still available in the pool
-  std::atomic<int64_t> scan_split_target{2048};
-  std::atomic<int64_t> scan_max_workgroups{0};
+  std::atomic<int64_t> scan_max_workgroups{1024};  // 4 per CU: leaves room for insertion kernels
+  std::atomic<int64_t> scan_items_per_wave{2};     // work items the plan aims at per wavefront
   std::atomic<int64_t> profile_scan{0};
   std::mutex prof_mutex;
   double scan_ms = 0.0;      // sum of measured scan-kernel durations
@@ -186,6 +189,13 @@ struct rtams_index {
 };
 
 namespace {
+
+// 32-bit words cleared at the start of a request: per-list pair counters and, right
+// behind them in the slice, the scan queues
+int plan_words(const rtams_index *ix) {
+  return (int)(((const char *)ix->res[0].s.queues - (const char *)ix->res[0].s.list_cnt) / 4 +
+               sizeof(ScanQueues) / 4);
+}
 
 int sync_data(rtams_index *ix) {
   if (ix->have_data_stream) HIP_TRY(hipStreamSynchronize(ix->data_stream));
@@ -359,10 +369,12 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
     S.qtotal = reinterpret_cast<uint32_t *>(p + SL.qtotal);
     S.cursor = reinterpret_cast<unsigned long long *>(p + SL.cursor);
     S.list_cnt = reinterpret_cast<uint32_t *>(p + SL.list_cnt);
+    S.list_len = reinterpret_cast<uint32_t *>(p + SL.list_len);
     S.pair_slot = reinterpret_cast<uint32_t *>(p + SL.pair_slot);
     S.grouped = reinterpret_cast<uint32_t *>(p + SL.grouped);
     S.tile_desc = reinterpret_cast<uint4 *>(p + SL.tile_desc);
-    S.ntiles = reinterpret_cast<uint32_t *>(p + SL.ntiles);
+    S.item_cap = (uint32_t)SL.item_cap;
+    S.queues = reinterpret_cast<ScanQueues *>(p + SL.queues);
     S.cand = reinterpret_cast<float *>(p + SL.cand);
     S.cand_cap = (slice - SL.fixed) / 4;
     if (hipEventCreateWithFlags(&ix->res[r].done, hipEventDisableTiming) != hipSuccess ||
@@ -470,23 +482,18 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   const SearchScratch &S = ix->res[r].s;
   // a rearrangement is switching block tables: start behind its last switch
   if (ix->fence_cur) (void)hipStreamWaitEvent(s, ix->fence_cur, 0);
-  launch_coarse_scores(D, nq, d_queries, S.scores, S.cursor, S.list_cnt, D.nlist, s);
+  launch_coarse_scores(D, nq, d_queries, S.scores, S.cursor, S.list_cnt, plan_words(ix), s);
   launch_probe_plan(D, nq, nprobe, ix->cfg.max_nprobe, S, nullptr, s);
-  launch_group(D, nq, nprobe, ix->cfg.max_nprobe, S, s);
-  // spread a small batch over the chip: split each tile (list x up to 8 queries) over several workgroups
-  int64_t pairs = scan_tiles_upper_bound(D, nq, nprobe);
-  int64_t target = ix->scan_split_target.load(std::memory_order_relaxed);
-  int64_t splits = (target + pairs - 1) / pairs;
-  uint32_t max_len = ix->mirror->max_len;
-  int64_t max_groups = ((int64_t)max_len + kWave * 4 - 1) / (kWave * 4);
-  if (splits > max_groups) splits = max_groups;
-  if (splits > 64) splits = 64;
-  int64_t cap = ix->scan_max_workgroups.load(std::memory_order_relaxed);
-  if (cap > 0 && pairs * splits > cap) splits = cap / pairs;
-  if (splits < 1) splits = 1;
+  // The scan runs as a capped number of workgroups whose wavefronts pull work
+  // items from queues, so that one request never takes every CU slot (the
+  // paper's restriction of blocks and threads per kernel).
+  int64_t wgs = ix->scan_max_workgroups.load(std::memory_order_relaxed);
+  if (wgs < 8) wgs = 8;
+  int64_t items = wgs * scan_waves(D) * ix->scan_items_per_wave.load(std::memory_order_relaxed);
+  launch_group(D, nq, nprobe, ix->cfg.max_nprobe, (int)items, S, s);
   const bool timed = ix->profile_scan.load(std::memory_order_relaxed) != 0;
   if (timed) (void)hipEventRecord(ix->res[r].t0, s);
-  launch_scan(D, nq, nprobe, ix->cfg.max_nprobe, d_queries, (int)splits, S, s);
+  launch_scan(D, nq, ix->cfg.max_nprobe, d_queries, (int)wgs, S, s);
   if (timed) { (void)hipEventRecord(ix->res[r].t1, s); ix->res[r].timed = true; }
   launch_select(D, nq, k, nprobe, ix->cfg.max_nprobe, S, d_out_dist, d_out_ids, s);
   hipError_t e = hipGetLastError();
@@ -545,7 +552,7 @@ int rtams_probe(rtams_index *ix, int64_t nq, const float *d_queries, int32_t npr
   if (r < 0) return fail(RTAMS_EBUSY, "all %d stream resources are in flight", ix->n_res);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const SearchScratch &S = ix->res[r].s;
-  launch_coarse_scores(ix->dev, nq, d_queries, S.scores, S.cursor, S.list_cnt, ix->dev.nlist, s);
+  launch_coarse_scores(ix->dev, nq, d_queries, S.scores, S.cursor, S.list_cnt, plan_words(ix), s);
   launch_probe_plan(ix->dev, nq, nprobe, ix->cfg.max_nprobe, S, d_out, s);
   hipError_t e = hipGetLastError();
   hipError_t e2 = hipEventRecord(ix->res[r].done, s);
@@ -731,11 +738,18 @@ int rtams_scan_time(rtams_index *ix, double *ms_sum, int64_t *launches, int rese
   return RTAMS_OK;
 }
 
+int rtams_copy_plain(void *d_dst, const void *d_src, size_t bytes, void *hip_stream) {
+  if (!d_dst || !d_src || bytes % 16) return fail(RTAMS_EINVAL, "copy needs buffers and a multiple of 16 bytes");
+  launch_copy_plain(d_dst, d_src, bytes, static_cast<hipStream_t>(hip_stream));
+  HIP_TRY(hipGetLastError());
+  return RTAMS_OK;
+}
+
 int rtams_set_param(rtams_index *ix, const char *key, int64_t value) {
   if (!ix || !key) return fail(RTAMS_EINVAL, "NULL argument");
   if (!strcmp(key, "profile_scan")) { ix->profile_scan = value; return RTAMS_OK; }
-  if (!strcmp(key, "scan_split_target")) { ix->scan_split_target = value; return RTAMS_OK; }
   if (!strcmp(key, "scan_max_workgroups")) { ix->scan_max_workgroups = value; return RTAMS_OK; }
+  if (!strcmp(key, "scan_items_per_wave")) { ix->scan_items_per_wave = value > 0 ? value : 1; return RTAMS_OK; }
   return fail(RTAMS_EINVAL, "unknown parameter %s", key);
 }
 

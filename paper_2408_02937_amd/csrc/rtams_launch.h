@@ -5,6 +5,15 @@
 
 namespace rtams {
 
+// Work queues of the scan of one request.  The items are ordered by list; each
+// XCD owns a contiguous range of them and hands them out with an atomic counter.
+struct ScanQueues {
+  uint32_t next[8];     // items taken from each queue so far (cleared with the plan counters)
+  uint32_t begin[9];    // queue x holds items begin[x] .. begin[x+1]-1
+  uint32_t seg_groups;  // 64-vector groups per work item
+  uint32_t pad[14];
+};
+
 // Per-request scratch of one stream resource (device pointers into its slice).
 struct SearchScratch {
   double *scores;       // [max_batch][nlist] coarse scores
@@ -15,10 +24,12 @@ struct SearchScratch {
   uint32_t *qtotal;     // [max_batch] candidates of the query
   unsigned long long *cursor; // bump pointer into cand
   uint32_t *list_cnt;   // [nlist] queries probing each list, then start of the list's pair group
+  uint32_t *list_len;   // [nlist] length of each probed list as seen by the grouping step
   uint32_t *pair_slot;  // [max_batch][max_nprobe] rank of the pair among the pairs of its list
   uint32_t *grouped;    // [max_batch * max_nprobe] pairs (query << 10 | probe) grouped by list
-  uint4 *tile_desc;     // [max_batch * max_nprobe] {list, first pair, pairs, 0} per scan tile
-  uint32_t *ntiles;     // number of scan tiles of this request
+  uint4 *tile_desc;     // [item_cap] {list, first pair, pairs, segment} per scan work item
+  uint32_t item_cap;
+  ScanQueues *queues;   // work items of this request, split into one queue per XCD
   float *cand;          // candidate scores
   unsigned long long cand_cap;
 };
@@ -74,10 +85,10 @@ void launch_publish(const Dev &D, hipStream_t s);
 // search.hip -----------------------------------------------------------------
 void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const SearchScratch &S,
                        int32_t *probe_out, hipStream_t s);
-void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const SearchScratch &S,
-                  hipStream_t s);
-int64_t scan_tiles_upper_bound(const Dev &D, int64_t nq, int nprobe);
-void launch_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const float *Q, int splits,
+void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int target_items,
+                  const SearchScratch &S, hipStream_t s);
+int scan_waves(const Dev &D);
+void launch_scan(const Dev &D, int64_t nq, int max_nprobe, const float *Q, int workgroups,
                  const SearchScratch &S, hipStream_t s);
 void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
                    const SearchScratch &S, float *out_dist, int64_t *out_ids, hipStream_t s);
@@ -92,5 +103,6 @@ void launch_export(const Dev &D, int list, int64_t n, int64_t *ids, float *vecs,
 void launch_chain_copy(const Dev &D, int list, int32_t *out, hipStream_t s);
 void launch_list_info(const Dev &D, int list, int32_t *out4, hipStream_t s);
 void launch_validate(const Dev &D, int32_t *result2, hipStream_t s);
+void launch_copy_plain(void *dst, const void *src, size_t bytes, hipStream_t s);
 
 }  // namespace rtams

@@ -199,46 +199,114 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
 // ------------------------------------------------------------ pair grouping
 // The (query, probed list) pairs of a request are grouped by list, so that the
 // scan reads a list once for up to kScanTileQueries queries.  One workgroup:
-// exclusive prefix sums over the lists of the pair counts and of the tile
-// counts, then the tile descriptors and the grouped pair array.
+// prefix sums over the lists of the pair counts, the work-item counts and the
+// work, then the item descriptors, the split of the items over the XCD queues
+// and the grouped pair array.  A work item is (list, query tile, segment of
+// seg_groups 64-vector groups); segments bound the work of one item, so that
+// long lists spread over many workgroups.
 constexpr int kGroupThreads = 1024;
 
+__device__ inline void wg_scan3(uint32_t &a, uint32_t &b, unsigned long long &c, uint32_t *sa,
+                                uint32_t *sb, unsigned long long *sc) {
+  // inclusive scan over the threads of three values at once
+  const int tid = threadIdx.x;
+  __syncthreads();
+  sa[tid] = a; sb[tid] = b; sc[tid] = c;
+  __syncthreads();
+  for (int o = 1; o < kGroupThreads; o <<= 1) {
+    uint32_t xa = tid >= o ? sa[tid - o] : 0u, xb = tid >= o ? sb[tid - o] : 0u;
+    unsigned long long xc = tid >= o ? sc[tid - o] : 0ull;
+    __syncthreads();
+    sa[tid] += xa; sb[tid] += xb; sc[tid] += xc;
+    __syncthreads();
+  }
+  a = sa[tid]; b = sb[tid]; c = sc[tid];
+}
+
 __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int nprobe, int max_nprobe,
-                                                         SearchScratch S) {
-  __shared__ uint32_t s_pairs[kGroupThreads];
-  __shared__ uint32_t s_tiles[kGroupThreads];
+                                                         uint32_t target_items, SearchScratch S) {
+  __shared__ uint32_t s_a[kGroupThreads];
+  __shared__ uint32_t s_b[kGroupThreads];
+  __shared__ unsigned long long s_c[kGroupThreads];
   const int tid = threadIdx.x;
   const int per = (D.nlist + kGroupThreads - 1) / kGroupThreads;
   const int l0 = tid * per, l1 = min(D.nlist, l0 + per);
-  uint32_t np = 0, nt = 0;
-  for (int l = l0; l < l1; ++l) {
-    uint32_t c = S.list_cnt[l];
-    np += c;
-    nt += (c + kScanTileQueries - 1) / kScanTileQueries;
-  }
-  s_pairs[tid] = np;
-  s_tiles[tid] = nt;
-  __syncthreads();
-  for (int o = 1; o < kGroupThreads; o <<= 1) {  // inclusive scan over the threads
-    uint32_t a = tid >= o ? s_pairs[tid - o] : 0u, b = tid >= o ? s_tiles[tid - o] : 0u;
-    __syncthreads();
-    s_pairs[tid] += a;
-    s_tiles[tid] += b;
-    __syncthreads();
-  }
-  uint32_t pstart = s_pairs[tid] - np, tstart = s_tiles[tid] - nt;
-  if (tid == kGroupThreads - 1) *S.ntiles = s_tiles[tid];
-  for (int l = l0; l < l1; ++l) {
-    uint32_t c = S.list_cnt[l];
-    S.list_cnt[l] = pstart;  // from here on: where the list's pairs start
-    for (uint32_t t = 0; t * kScanTileQueries < c; ++t) {
-      uint32_t left = c - t * kScanTileQueries;
-      S.tile_desc[tstart++] = make_uint4((uint32_t)l, pstart + t * kScanTileQueries,
-                                         left < (uint32_t)kScanTileQueries ? left : (uint32_t)kScanTileQueries, 0u);
+  ScanQueues *Qs = S.queues;
+
+  // The visible length of every probed list is read ONCE: an insertion may publish
+  // while this kernel runs, and the passes below must agree on the segment counts.
+  // (Each pair's own snapshot was taken earlier, so it is not longer than this one.)
+  for (int l = l0; l < l1; ++l)
+    S.list_len[l] = S.list_cnt[l]
+                        ? __hip_atomic_load(&D.visible_len[l], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                        : 0u;
+  // segment length: the longest (least per-item overhead) that still yields
+  // `target_items` items for the wavefronts to balance; never so short that the
+  // item array overflows
+  uint32_t seg = 16;
+  bool growing = false;
+  uint32_t np, ni;
+  unsigned long long wk;
+  for (;;) {
+    np = 0; ni = 0; wk = 0;
+    for (int l = l0; l < l1; ++l) {
+      const uint32_t c = S.list_cnt[l];
+      if (!c) continue;
+      const uint32_t groups = (S.list_len[l] + kWave - 1) / kWave;
+      const uint32_t segs = groups ? (groups + seg - 1) / seg : 1u;
+      np += c;
+      ni += (c + kScanTileQueries - 1) / kScanTileQueries * segs;
+      wk += (unsigned long long)c * (groups ? groups : 1u);
     }
-    pstart += c;
+    uint32_t inp = np, ini = ni;
+    unsigned long long iwk = wk;
+    wg_scan3(inp, ini, iwk, s_a, s_b, s_c);
+    const uint32_t total_items = s_b[kGroupThreads - 1];
+    if (!growing && total_items < target_items && seg > 2 && 2ull * total_items <= S.item_cap) {
+      seg /= 2;  // uniform decision: every thread sees the same total
+      continue;
+    }
+    growing = true;
+    if (total_items <= S.item_cap) {
+      const unsigned long long total_work = s_c[kGroupThreads - 1];
+      uint32_t pstart = inp - np, istart = ini - ni;
+      unsigned long long wstart = iwk - wk;
+      if (tid == 0) { Qs->begin[0] = 0; Qs->begin[8] = total_items; Qs->seg_groups = seg; }
+      for (int l = l0; l < l1; ++l) {
+        const uint32_t c = S.list_cnt[l];
+        S.list_cnt[l] = pstart;  // from here on: where the list's pairs start
+        if (!c) continue;
+        const uint32_t groups = (S.list_len[l] + kWave - 1) / kWave;
+        const uint32_t segs = groups ? (groups + seg - 1) / seg : 1u;
+        const unsigned long long w = (unsigned long long)c * (groups ? groups : 1u);
+        // queue boundaries: XCD x starts at the first list whose work prefix reaches x/8 of the total
+        for (uint32_t x = 1; x < 8; ++x) {
+          const unsigned long long cut = total_work * x / 8;
+          if (wstart <= cut && cut < wstart + w) Qs->begin[x] = istart;
+        }
+        for (uint32_t sg = 0; sg < segs; ++sg)  // items of one segment are adjacent: they share its bytes in L2
+          for (uint32_t t = 0; t * kScanTileQueries < c; ++t) {
+            const uint32_t left = c - t * kScanTileQueries;
+            S.tile_desc[istart++] =
+                make_uint4((uint32_t)l, pstart + t * kScanTileQueries,
+                           left < (uint32_t)kScanTileQueries ? left : (uint32_t)kScanTileQueries, sg);
+          }
+        pstart += c;
+        wstart += w;
+      }
+      if (total_work == 0 && tid == 0)
+        for (uint32_t x = 1; x < 8; ++x) Qs->begin[x] = 0;
+      break;
+    }
+    seg *= 2;  // uniform decision: every thread sees the same total
   }
   __syncthreads();  // list starts written above are read below by other threads of this workgroup
+  // a boundary that no list claimed (cut inside a gap of empty lists cannot happen, but
+  // a cut at 0 work can): make the sequence monotone
+  if (tid == 0) {
+    for (uint32_t x = 1; x < 8; ++x)
+      if (Qs->begin[x] < Qs->begin[x - 1]) Qs->begin[x] = Qs->begin[x - 1];
+  }
   for (int idx = tid; idx < nq * nprobe; idx += kGroupThreads) {
     int q = idx / nprobe, p = idx - q * nprobe;
     size_t o = (size_t)q * max_nprobe + p;
@@ -248,14 +316,15 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
 }
 
 // ------------------------------------------------------------------ list scan
-// A tile is one list together with up to kScanTileQueries of the queries that
-// probe it; a workgroup handles (tile, split).  The tile's queries sit in LDS.
-// Each wavefront takes pairs of groups of 64 vectors of the list, lane = vector
-// (two vectors per lane).  Per chunk of 4 dimensions the wavefront loads 1 KiB
-// of consecutive memory per group (one float4 per lane) ONCE and every lane
-// accumulates the score of its two vectors against each query of the tile; a
-// query chunk is one broadcast LDS read shared by both vectors.  Scores go to
-// each query's candidate slice.
+// A work item is one segment of one list together with up to kScanTileQueries
+// of the queries that probe the list.  Every WAVEFRONT works on its own: it
+// takes an item from a queue, copies the item's queries into its slice of LDS,
+// and walks the segment in pairs of groups of 64 vectors, lane = vector (two
+// vectors per lane).  Per chunk of 4 dimensions it loads 1 KiB of consecutive
+// memory per group (one float4 per lane) ONCE and every lane accumulates the
+// score of its two vectors against each query of the item; a query chunk is one
+// broadcast LDS read shared by both vectors.  Scores go to each query's
+// candidate slice.  No workgroup barrier is involved anywhere.
 template <int METRIC>
 __device__ __forceinline__ void accumulate(float &acc, const float4 &x, const float4 &y) {
   if (METRIC == 0) {
@@ -266,44 +335,46 @@ __device__ __forceinline__ void accumulate(float &acc, const float4 &x, const fl
   }
 }
 
-constexpr int kPrefetch = 2;  // chunks of 4 dimensions kept in flight per group
+constexpr int kPrefetch = 2;  // chunks of 4 dimensions per register set of the software pipeline
 
 template <int METRIC, int NQ>
-__device__ __forceinline__ void scan_tile(const Dev &D, const SearchScratch &S,
+__device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
                                           const float *__restrict__ Q, int max_nprobe, int list,
-                                          uint32_t first, int cnt, uint32_t split, uint32_t nsplits,
+                                          uint32_t first, uint32_t g_begin, uint32_t g_count,
                                           float4 *qs) {
   const int d4 = D.d4;
-  // per-query facts of the tile live in LDS, out of the inner loop's registers
-  __shared__ uint32_t s_len[kScanTileQueries];
-  __shared__ float *s_out[kScanTileQueries];
-  __shared__ uint32_t s_maxlen;
-  if (threadIdx.x == 0) s_maxlen = 0;
-  __syncthreads();
-  if ((int)threadIdx.x < NQ) {
-    const int i = threadIdx.x;
-    const uint32_t pk = S.grouped[first + (i < cnt ? i : 0)];
-    const uint32_t q = pk >> 10, p = pk & 1023u;
-    const size_t o = (size_t)q * max_nprobe + p;
-    const uint32_t len = i < cnt ? S.probe_len[o] : 0u;  // padding queries write nothing
-    s_len[i] = len;
-    s_out[i] = S.cand + S.qbase[q] + S.probe_off[o];
-    atomicMax(&s_maxlen, len);
+  const int lane = threadIdx.x & (kWave - 1);
+  // lane i < NQ looks after query i of the item: where it reads and writes, how far its list goes
+  uint32_t my_q = 0, my_len = 0;
+  float *my_out = nullptr;
+  if (lane < NQ) {
+    const uint32_t pk = S.grouped[first + lane];
+    my_q = pk >> 10;
+    const size_t o = (size_t)my_q * max_nprobe + (pk & 1023u);
+    my_len = S.probe_len[o];
+    my_out = S.cand + S.qbase[my_q] + S.probe_off[o];
   }
+  uint32_t maxlen = 0;
 #pragma unroll
   for (int i = 0; i < NQ; ++i) {
-    const uint32_t pk = S.grouped[first + (i < cnt ? i : 0)];
-    const float4 *src = reinterpret_cast<const float4 *>(Q + (size_t)(pk >> 10) * D.d);
-    for (int c = threadIdx.x; c < d4; c += blockDim.x) qs[i * d4 + c] = src[c];
+    const uint32_t q = (uint32_t)__builtin_amdgcn_readlane((int)my_q, i);
+    const uint32_t len = (uint32_t)__builtin_amdgcn_readlane((int)my_len, i);
+    maxlen = len > maxlen ? len : maxlen;
+    const float4 *src = reinterpret_cast<const float4 *>(Q + (size_t)q * D.d);
+    for (int c = lane; c < d4; c += kWave) qs[i * d4 + c] = src[c];
   }
-  __syncthreads();
-  const uint32_t maxlen = s_maxlen;
-  const int lane = threadIdx.x & (kWave - 1);
-  const uint32_t wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
-  const uint32_t ngroups = (maxlen + kWave - 1) / kWave;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+
+  uint32_t ngroups = (maxlen + kWave - 1) / kWave;  // groups any query of the item wants
+  if (ngroups > g_begin + g_count) ngroups = g_begin + g_count;  // ... inside this item's segment
   const uint32_t gpb = (uint32_t)D.groups_per_block;
+  {  // never index the block table past the list's chain, whatever the descriptors say
+    const uint32_t have = D.nblk[list] * gpb;
+    if (ngroups > have) ngroups = have;
+  }
   const size_t group_stride = (size_t)d4 * kWave;
-  for (uint32_t g0 = 2 * (split * waves + wave); g0 < ngroups; g0 += 2 * nsplits * waves) {
+  for (uint32_t g0 = g_begin; g0 < ngroups; g0 += 2) {
     const bool two = g0 + 1 < ngroups;  // uniform over the wavefront
     const uint32_t g1 = two ? g0 + 1 : g0;
     const uint32_t b0 = (uint32_t)*table_entry(D, list, g0 / gpb);
@@ -364,35 +435,61 @@ __device__ __forceinline__ void scan_tile(const Dev &D, const SearchScratch &S,
     const uint32_t v0 = g0 * kWave + lane, v1 = v0 + kWave;
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
-      const uint32_t len = s_len[i];
-      float *out = s_out[i];
+      // readlane yields a signed int: go through uint32_t so the low word is not sign-extended
+      const uint32_t len = (uint32_t)__builtin_amdgcn_readlane((int)my_len, i);
+      const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(uintptr_t)my_out, i);
+      const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uintptr_t)my_out >> 32), i);
+      float *out = reinterpret_cast<float *>((uint64_t)lo | ((uint64_t)hi << 32));
       if (v0 < len) out[v0] = acc0[i];
       if (two && v1 < len) out[v1] = acc1[i];
     }
   }
+  __builtin_amdgcn_wave_barrier();  // the LDS slice is rewritten by the next item
 }
 
-// Workgroups are numbered so that those of one XCD (hardware hands consecutive
-// workgroup ids to the 8 XCDs in turn) work on consecutive tiles: the tiles of
-// one list, and the splits of one tile, then share that XCD's L2.
+// The launch is a fixed number of workgroups of four independent wavefronts.
+// Hardware hands consecutive workgroup ids to the 8 XCDs in turn, so workgroup
+// i runs on XCD i % 8; its wavefronts take items from that XCD's queue (a
+// contiguous range of lists: the tiles of a list and the items of a segment
+// share that XCD's L2) and, once the queue is empty, help the other queues.
+// Every queue counter only grows and every wavefront leaves as soon as all
+// eight queues are past their end.
 constexpr uint32_t kXcds = 8;
 
 template <int METRIC>
 __global__ __launch_bounds__(256) void k_scan(Dev D, int max_nprobe, const float *__restrict__ Q,
-                                              uint32_t nsplits, SearchScratch S) {
-  extern __shared__ float4 qs[];  // [kScanTileQueries][d / 4]
-  const uint32_t work = *S.ntiles * nsplits;
-  const uint32_t per_xcd = (work + kXcds - 1) / kXcds;
-  const uint32_t in_xcd = blockIdx.x / kXcds;
-  const uint32_t logical = (blockIdx.x % kXcds) * per_xcd + in_xcd;
-  if (in_xcd >= per_xcd || logical >= work) return;
-  const uint32_t tile = logical / nsplits, split = logical - tile * nsplits;
-  const uint4 desc = S.tile_desc[tile];
-  const int list = (int)desc.x, cnt = (int)desc.z;
-  if (cnt == 1) scan_tile<METRIC, 1>(D, S, Q, max_nprobe, list, desc.y, cnt, split, nsplits, qs);
-  else if (cnt == 2) scan_tile<METRIC, 2>(D, S, Q, max_nprobe, list, desc.y, cnt, split, nsplits, qs);
-  else if (cnt <= 4) scan_tile<METRIC, 4>(D, S, Q, max_nprobe, list, desc.y, cnt, split, nsplits, qs);
-  else scan_tile<METRIC, 8>(D, S, Q, max_nprobe, list, desc.y, cnt, split, nsplits, qs);
+                                              SearchScratch S) {
+  extern __shared__ float4 qs_all[];  // [wavefronts][kScanTileQueries][d / 4]
+  float4 *qs = qs_all + (size_t)(threadIdx.x / kWave) * kScanTileQueries * D.d4;
+  ScanQueues *Qs = S.queues;
+  const uint32_t seg = Qs->seg_groups;
+  const uint32_t home = blockIdx.x % kXcds;
+  const int lane = threadIdx.x & (kWave - 1);
+  for (uint32_t hop = 0; hop < kXcds; ++hop) {
+    const uint32_t x = (home + hop) % kXcds;
+    const uint32_t begin = Qs->begin[x], end = Qs->begin[x + 1];
+    for (;;) {
+      uint32_t item = 0;
+      if (lane == 0) item = begin + atomicAdd(&Qs->next[x], 1u);
+      item = __builtin_amdgcn_readfirstlane(item);
+      if (item >= end) break;
+      const uint4 desc = S.tile_desc[item];
+      const int list = __builtin_amdgcn_readfirstlane((int)desc.x);
+      const uint32_t first = __builtin_amdgcn_readfirstlane(desc.y);
+      const int cnt = __builtin_amdgcn_readfirstlane((int)desc.z);
+      const uint32_t g_begin = __builtin_amdgcn_readfirstlane(desc.w) * seg;
+      switch (cnt) {
+        case 1: scan_item<METRIC, 1>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+        case 2: scan_item<METRIC, 2>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+        case 3: scan_item<METRIC, 3>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+        case 4: scan_item<METRIC, 4>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+        case 5: scan_item<METRIC, 5>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+        case 6: scan_item<METRIC, 6>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+        case 7: scan_item<METRIC, 7>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+        default: scan_item<METRIC, 8>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+      }
+    }
+  }
 }
 
 // ------------------------------------------------------------ top-k selection
@@ -564,29 +661,29 @@ void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, con
                      S, probe_out);
 }
 
-void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const SearchScratch &S,
-                  hipStream_t s) {
+void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int target_items,
+                  const SearchScratch &S, hipStream_t s) {
   if (nq <= 0) return;
-  hipLaunchKernelGGL(k_group, dim3(1), dim3(kGroupThreads), 0, s, D, (int)nq, nprobe, max_nprobe, S);
+  hipLaunchKernelGGL(k_group, dim3(1), dim3(kGroupThreads), 0, s, D, (int)nq, nprobe, max_nprobe,
+                     (uint32_t)target_items, S);
 }
 
-// No request has more tiles than this: full tiles plus one partial tile per touched list.
-int64_t scan_tiles_upper_bound(const Dev &D, int64_t nq, int nprobe) {
-  int64_t pairs = nq * nprobe;
-  return pairs / kScanTileQueries + (pairs < D.nlist ? pairs : D.nlist);
+// wavefronts per workgroup of the scan: as many (4, 2, 1) as fit their query tiles into 64 KiB of LDS
+int scan_waves(const Dev &D) {
+  size_t per_wave = (size_t)kScanTileQueries * D.d * sizeof(float);
+  return per_wave * 4 <= 65536 ? 4 : per_wave * 2 <= 65536 ? 2 : 1;
 }
 
-void launch_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const float *Q, int splits,
+void launch_scan(const Dev &D, int64_t nq, int max_nprobe, const float *Q, int workgroups,
                  const SearchScratch &S, hipStream_t s) {
   if (nq <= 0) return;
-  int64_t wgs = scan_tiles_upper_bound(D, nq, nprobe) * splits;
-  wgs = (wgs + kXcds - 1) / kXcds * kXcds + kXcds;
-  dim3 grid((unsigned)wgs);
-  size_t lds = (size_t)kScanTileQueries * D.d * sizeof(float);
+  const int waves = scan_waves(D);
+  dim3 grid((unsigned)((workgroups + kXcds - 1) / kXcds * kXcds));
+  size_t lds = (size_t)waves * kScanTileQueries * D.d * sizeof(float);  // one query tile per wavefront
   if (D.metric == 0)
-    hipLaunchKernelGGL(k_scan<0>, grid, dim3(256), lds, s, D, max_nprobe, Q, (uint32_t)splits, S);
+    hipLaunchKernelGGL(k_scan<0>, grid, dim3(waves * kWave), lds, s, D, max_nprobe, Q, S);
   else
-    hipLaunchKernelGGL(k_scan<1>, grid, dim3(256), lds, s, D, max_nprobe, Q, (uint32_t)splits, S);
+    hipLaunchKernelGGL(k_scan<1>, grid, dim3(waves * kWave), lds, s, D, max_nprobe, Q, S);
 }
 
 void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,

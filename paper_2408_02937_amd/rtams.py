@@ -28,6 +28,7 @@ SYMBOLS = [
     "rtams_list_size", "rtams_list_info", "rtams_list_export", "rtams_list_chain",
     "rtams_list_sizes", "rtams_pool_stats", "rtams_validate", "rtams_probe", "rtams_assign",
     "rtams_poll_error", "rtams_last_error", "rtams_set_param", "rtams_scan_time",
+    "rtams_copy_plain",
 ]
 
 
@@ -91,6 +92,7 @@ def lib():
         L.rtams_last_error.restype = C.c_char_p
         L.rtams_set_param.argtypes = [vp, C.c_char_p, i64]
         L.rtams_scan_time.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), C.c_int]
+        L.rtams_copy_plain.argtypes = [vp, vp, C.c_size_t, vp]
         _lib = L
     return _lib
 
@@ -109,6 +111,12 @@ def _dev_f32(t: torch.Tensor, d: int, what: str) -> torch.Tensor:
     if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.dim() == 2 and t.shape[1] == d):
         raise ValueError(f"{what} must be a contiguous float32 CUDA tensor of shape [n][{d}]")
     return t
+
+
+def copy_plain(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    """The library's plain copy kernel (calibration of traffic counters)."""
+    nbytes = src.numel() * src.element_size()
+    _chk(lib().rtams_copy_plain(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream)), "rtams_copy_plain")
 
 
 class Index:
