@@ -178,9 +178,11 @@ int rtams_scan_time(rtams_index *ix, double *ms_sum, int64_t *launches, int rese
  * what they read for this kernel, whose traffic is known. */
 int rtams_copy_plain(void *d_dst, const void *d_src, size_t bytes, void *hip_stream);
 /* Launch-shape knobs ("restrict the number of blocks and threads per kernel",
- * Stream-Cached Multi-Stream Execution, consideration 2).  key: "scan_max_workgroups"
- * (workgroups of one list-scan launch, default 1024 = 4 per CU), and "profile_scan"
- * (see rtams_scan_time).  EINVAL for an unknown key. */
+ * Stream-Cached Multi-Stream Execution, consideration 2).  key: "scan_max_items"
+ * (most work items, i.e. single-wavefront workgroups, one list-scan launch is cut
+ * into; default 16384), "scan_items_per_pair" (items per (query, list) pair a small
+ * request may be cut into; default 8), and "profile_scan" (see rtams_scan_time).
+ * EINVAL for an unknown key. */
 int rtams_set_param(rtams_index *ix, const char *key, int64_t value);
 
 #ifdef __cplusplus

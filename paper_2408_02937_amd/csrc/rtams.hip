@@ -180,8 +180,8 @@ struct rtams_index {
   hipEvent_t fence_cur = nullptr;               // what a new search must wait for, or nullptr
   int64_t ntotal_host = 0;   // vectors handed to add so far
   int64_t avail_lb = 0;      // lower bound of the blocks still available in the pool
-  std::atomic<int64_t> scan_max_workgroups{1024};  // 4 per CU: leaves room for insertion kernels
-  std::atomic<int64_t> scan_items_per_wave{2};     // work items the plan aims at per wavefront
+  std::atomic<int64_t> scan_items_per_pair{8};   // work items the plan may cut per (query, list) pair
+  std::atomic<int64_t> scan_max_items{16384};    // ... and per request
   std::atomic<int64_t> profile_scan{0};
   std::mutex prof_mutex;
   double scan_ms = 0.0;      // sum of measured scan-kernel durations
@@ -484,16 +484,17 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   if (ix->fence_cur) (void)hipStreamWaitEvent(s, ix->fence_cur, 0);
   launch_coarse_scores(D, nq, d_queries, S.scores, S.cursor, S.list_cnt, plan_words(ix), s);
   launch_probe_plan(D, nq, nprobe, ix->cfg.max_nprobe, S, nullptr, s);
-  // The scan runs as a capped number of workgroups whose wavefronts pull work
-  // items from queues, so that one request never takes every CU slot (the
-  // paper's restriction of blocks and threads per kernel).
-  int64_t wgs = ix->scan_max_workgroups.load(std::memory_order_relaxed);
-  if (wgs < 8) wgs = 8;
-  int64_t items = wgs * scan_waves(D) * ix->scan_items_per_wave.load(std::memory_order_relaxed);
-  launch_group(D, nq, nprobe, ix->cfg.max_nprobe, (int)items, S, s);
+  // The scan is cut into work items of bounded size, one single-wavefront workgroup
+  // each; the budget of items grows with the request so that a small batch still
+  // spreads over the chip and a large one is not drowned in per-item overhead.
+  int64_t budget = nq * nprobe * ix->scan_items_per_pair.load(std::memory_order_relaxed);
+  const int64_t cap = ix->scan_max_items.load(std::memory_order_relaxed);
+  if (budget > cap) budget = cap;
+  if (budget < 1024) budget = 1024;
+  launch_group(D, nq, nprobe, ix->cfg.max_nprobe, (int)budget, S, s);
   const bool timed = ix->profile_scan.load(std::memory_order_relaxed) != 0;
   if (timed) (void)hipEventRecord(ix->res[r].t0, s);
-  launch_scan(D, nq, ix->cfg.max_nprobe, d_queries, (int)wgs, S, s);
+  launch_scan(D, nq, ix->cfg.max_nprobe, d_queries, (int)budget, S, s);
   if (timed) { (void)hipEventRecord(ix->res[r].t1, s); ix->res[r].timed = true; }
   launch_select(D, nq, k, nprobe, ix->cfg.max_nprobe, S, d_out_dist, d_out_ids, s);
   hipError_t e = hipGetLastError();
@@ -748,8 +749,8 @@ int rtams_copy_plain(void *d_dst, const void *d_src, size_t bytes, void *hip_str
 int rtams_set_param(rtams_index *ix, const char *key, int64_t value) {
   if (!ix || !key) return fail(RTAMS_EINVAL, "NULL argument");
   if (!strcmp(key, "profile_scan")) { ix->profile_scan = value; return RTAMS_OK; }
-  if (!strcmp(key, "scan_max_workgroups")) { ix->scan_max_workgroups = value; return RTAMS_OK; }
-  if (!strcmp(key, "scan_items_per_wave")) { ix->scan_items_per_wave = value > 0 ? value : 1; return RTAMS_OK; }
+  if (!strcmp(key, "scan_max_items")) { ix->scan_max_items = value > 1024 ? value : 1024; return RTAMS_OK; }
+  if (!strcmp(key, "scan_items_per_pair")) { ix->scan_items_per_pair = value > 0 ? value : 1; return RTAMS_OK; }
   return fail(RTAMS_EINVAL, "unknown parameter %s", key);
 }
 

@@ -5,13 +5,12 @@
 
 namespace rtams {
 
-// Work queues of the scan of one request.  The items are ordered by list; each
-// XCD owns a contiguous range of them and hands them out with an atomic counter.
+// Work items of the scan of one request.  The items are ordered by list; each
+// XCD owns a contiguous range of them.
 struct ScanQueues {
-  uint32_t next[8];     // items taken from each queue so far (cleared with the plan counters)
-  uint32_t begin[9];    // queue x holds items begin[x] .. begin[x+1]-1
+  uint32_t begin[9];    // XCD x owns items begin[x] .. begin[x+1]-1
   uint32_t seg_groups;  // 64-vector groups per work item
-  uint32_t pad[14];
+  uint32_t pad[22];
 };
 
 // Per-request scratch of one stream resource (device pointers into its slice).
@@ -85,10 +84,10 @@ void launch_publish(const Dev &D, hipStream_t s);
 // search.hip -----------------------------------------------------------------
 void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const SearchScratch &S,
                        int32_t *probe_out, hipStream_t s);
-void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int target_items,
+void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int item_budget,
                   const SearchScratch &S, hipStream_t s);
-int scan_waves(const Dev &D);
-void launch_scan(const Dev &D, int64_t nq, int max_nprobe, const float *Q, int workgroups,
+int scan_grid(int item_budget);
+void launch_scan(const Dev &D, int64_t nq, int max_nprobe, const float *Q, int item_budget,
                  const SearchScratch &S, hipStream_t s);
 void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
                    const SearchScratch &S, float *out_dist, int64_t *out_ids, hipStream_t s);

@@ -200,11 +200,14 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
 // The (query, probed list) pairs of a request are grouped by list, so that the
 // scan reads a list once for up to kScanTileQueries queries.  One workgroup:
 // prefix sums over the lists of the pair counts, the work-item counts and the
-// work, then the item descriptors, the split of the items over the XCD queues
-// and the grouped pair array.  A work item is (list, query tile, segment of
+// work, then the item descriptors, the split of the items over the 8 XCDs and
+// the grouped pair array.  A work item is (list, query tile, segment of
 // seg_groups 64-vector groups); segments bound the work of one item, so that
-// long lists spread over many workgroups.
+// long lists spread over many wavefronts.  The segment length is the shortest
+// power of two for which the request has at most `item_budget` items and no XCD
+// more than `max_per_xcd` (the launch of the scan is sized from those two).
 constexpr int kGroupThreads = 1024;
+constexpr int kSegChoices = 8;  // segment lengths 2, 4, ..., 256 groups
 
 __device__ inline void wg_scan3(uint32_t &a, uint32_t &b, unsigned long long &c, uint32_t *sa,
                                 uint32_t *sb, unsigned long long *sc) {
@@ -224,10 +227,13 @@ __device__ inline void wg_scan3(uint32_t &a, uint32_t &b, unsigned long long &c,
 }
 
 __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int nprobe, int max_nprobe,
-                                                         uint32_t target_items, SearchScratch S) {
+                                                         uint32_t item_budget, uint32_t max_per_xcd,
+                                                         SearchScratch S) {
   __shared__ uint32_t s_a[kGroupThreads];
   __shared__ uint32_t s_b[kGroupThreads];
   __shared__ unsigned long long s_c[kGroupThreads];
+  __shared__ uint32_t s_items[kSegChoices];
+  __shared__ uint32_t s_begin[9];
   const int tid = threadIdx.x;
   const int per = (D.nlist + kGroupThreads - 1) / kGroupThreads;
   const int l0 = tid * per, l1 = min(D.nlist, l0 + per);
@@ -236,54 +242,91 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
   // The visible length of every probed list is read ONCE: an insertion may publish
   // while this kernel runs, and the passes below must agree on the segment counts.
   // (Each pair's own snapshot was taken earlier, so it is not longer than this one.)
-  for (int l = l0; l < l1; ++l)
-    S.list_len[l] = S.list_cnt[l]
-                        ? __hip_atomic_load(&D.visible_len[l], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                        : 0u;
-  // segment length: the longest (least per-item overhead) that still yields
-  // `target_items` items for the wavefronts to balance; never so short that the
-  // item array overflows
-  uint32_t seg = 16;
-  bool growing = false;
-  uint32_t np, ni;
-  unsigned long long wk;
-  for (;;) {
-    np = 0; ni = 0; wk = 0;
+  if (tid < kSegChoices) s_items[tid] = 0;
+  __syncthreads();
+  {
+    uint32_t cnt[kSegChoices];
+#pragma unroll
+    for (int e = 0; e < kSegChoices; ++e) cnt[e] = 0;
+    for (int l = l0; l < l1; ++l) {
+      const uint32_t c = S.list_cnt[l];
+      const uint32_t len =
+          c ? __hip_atomic_load(&D.visible_len[l], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+      S.list_len[l] = len;
+      if (!c) continue;
+      const uint32_t groups = (len + kWave - 1) / kWave;
+      const uint32_t tiles = (c + kScanTileQueries - 1) / kScanTileQueries;
+#pragma unroll
+      for (int e = 0; e < kSegChoices; ++e) {
+        const uint32_t sg = 2u << e;
+        cnt[e] += tiles * (groups ? (groups + sg - 1) / sg : 1u);
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < kSegChoices; ++e)
+      if (cnt[e]) atomicAdd(&s_items[e], cnt[e]);
+  }
+  __syncthreads();
+  int choice = kSegChoices - 1;
+  for (int e = 0; e < kSegChoices; ++e)
+    if (s_items[e] <= item_budget && s_items[e] <= S.item_cap) { choice = e; break; }
+
+  for (;; ++choice) {  // uniform: every thread sees the same totals
+    const uint32_t seg = 2u << choice;
+    uint32_t np = 0, ni = 0;
+    unsigned long long wk = 0;
     for (int l = l0; l < l1; ++l) {
       const uint32_t c = S.list_cnt[l];
       if (!c) continue;
       const uint32_t groups = (S.list_len[l] + kWave - 1) / kWave;
-      const uint32_t segs = groups ? (groups + seg - 1) / seg : 1u;
       np += c;
-      ni += (c + kScanTileQueries - 1) / kScanTileQueries * segs;
+      ni += (c + kScanTileQueries - 1) / kScanTileQueries * (groups ? (groups + seg - 1) / seg : 1u);
       wk += (unsigned long long)c * (groups ? groups : 1u);
     }
     uint32_t inp = np, ini = ni;
     unsigned long long iwk = wk;
     wg_scan3(inp, ini, iwk, s_a, s_b, s_c);
     const uint32_t total_items = s_b[kGroupThreads - 1];
-    if (!growing && total_items < target_items && seg > 2 && 2ull * total_items <= S.item_cap) {
-      seg /= 2;  // uniform decision: every thread sees the same total
-      continue;
-    }
-    growing = true;
-    if (total_items <= S.item_cap) {
-      const unsigned long long total_work = s_c[kGroupThreads - 1];
-      uint32_t pstart = inp - np, istart = ini - ni;
-      unsigned long long wstart = iwk - wk;
-      if (tid == 0) { Qs->begin[0] = 0; Qs->begin[8] = total_items; Qs->seg_groups = seg; }
+    const unsigned long long total_work = s_c[kGroupThreads - 1];
+    uint32_t pstart = inp - np, istart = ini - ni;
+    unsigned long long wstart = iwk - wk;
+    // XCD x starts at the list inside which the work prefix passes x/8 of the total
+    if (tid < 9) s_begin[tid] = tid == 8 ? total_items : 0u;
+    __syncthreads();
+    {
+      uint32_t is = istart;
+      unsigned long long ws = wstart;
       for (int l = l0; l < l1; ++l) {
         const uint32_t c = S.list_cnt[l];
-        S.list_cnt[l] = pstart;  // from here on: where the list's pairs start
         if (!c) continue;
         const uint32_t groups = (S.list_len[l] + kWave - 1) / kWave;
-        const uint32_t segs = groups ? (groups + seg - 1) / seg : 1u;
         const unsigned long long w = (unsigned long long)c * (groups ? groups : 1u);
-        // queue boundaries: XCD x starts at the first list whose work prefix reaches x/8 of the total
         for (uint32_t x = 1; x < 8; ++x) {
           const unsigned long long cut = total_work * x / 8;
-          if (wstart <= cut && cut < wstart + w) Qs->begin[x] = istart;
+          if (ws <= cut && cut < ws + w) s_begin[x] = is;
         }
+        is += (c + kScanTileQueries - 1) / kScanTileQueries * (groups ? (groups + seg - 1) / seg : 1u);
+        ws += w;
+      }
+    }
+    __syncthreads();
+    if (tid == 0)  // several cuts may fall into one list: keep the sequence monotone
+      for (uint32_t x = 1; x < 8; ++x)
+        if (s_begin[x] < s_begin[x - 1]) s_begin[x] = s_begin[x - 1];
+    __syncthreads();
+    uint32_t longest = 0;
+    for (uint32_t x = 0; x < 8; ++x) longest = max(longest, s_begin[x + 1] - s_begin[x]);
+    const bool fits = total_items <= S.item_cap && longest <= max_per_xcd;
+    if (!fits && choice + 1 < kSegChoices + 8) continue;  // coarser segments (bounded: lengths are 32 bit)
+    if (tid < 9) Qs->begin[tid] = s_begin[tid];
+    if (tid == 0) Qs->seg_groups = fits ? seg : 0u;  // 0: nothing is scanned (cannot happen with sane sizes)
+    for (int l = l0; l < l1; ++l) {
+      const uint32_t c = S.list_cnt[l];
+      S.list_cnt[l] = pstart;  // from here on: where the list's pairs start
+      if (!c) continue;
+      const uint32_t groups = (S.list_len[l] + kWave - 1) / kWave;
+      const uint32_t segs = groups ? (groups + seg - 1) / seg : 1u;
+      if (fits)
         for (uint32_t sg = 0; sg < segs; ++sg)  // items of one segment are adjacent: they share its bytes in L2
           for (uint32_t t = 0; t * kScanTileQueries < c; ++t) {
             const uint32_t left = c - t * kScanTileQueries;
@@ -291,22 +334,11 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
                 make_uint4((uint32_t)l, pstart + t * kScanTileQueries,
                            left < (uint32_t)kScanTileQueries ? left : (uint32_t)kScanTileQueries, sg);
           }
-        pstart += c;
-        wstart += w;
-      }
-      if (total_work == 0 && tid == 0)
-        for (uint32_t x = 1; x < 8; ++x) Qs->begin[x] = 0;
-      break;
+      pstart += c;
     }
-    seg *= 2;  // uniform decision: every thread sees the same total
+    break;
   }
   __syncthreads();  // list starts written above are read below by other threads of this workgroup
-  // a boundary that no list claimed (cut inside a gap of empty lists cannot happen, but
-  // a cut at 0 work can): make the sequence monotone
-  if (tid == 0) {
-    for (uint32_t x = 1; x < 8; ++x)
-      if (Qs->begin[x] < Qs->begin[x - 1]) Qs->begin[x] = Qs->begin[x - 1];
-  }
   for (int idx = tid; idx < nq * nprobe; idx += kGroupThreads) {
     int q = idx / nprobe, p = idx - q * nprobe;
     size_t o = (size_t)q * max_nprobe + p;
@@ -447,48 +479,39 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
   __builtin_amdgcn_wave_barrier();  // the LDS slice is rewritten by the next item
 }
 
-// The launch is a fixed number of workgroups of four independent wavefronts.
-// Hardware hands consecutive workgroup ids to the 8 XCDs in turn, so workgroup
-// i runs on XCD i % 8; its wavefronts take items from that XCD's queue (a
-// contiguous range of lists: the tiles of a list and the items of a segment
-// share that XCD's L2) and, once the queue is empty, help the other queues.
-// Every queue counter only grows and every wavefront leaves as soon as all
-// eight queues are past their end.
+// One single-wavefront workgroup per work item; the hardware's workgroup
+// dispatcher is the work queue (a new workgroup starts wherever a wavefront slot
+// frees up).  Hardware hands consecutive workgroup ids to the 8 XCDs in turn, so
+// workgroup i runs on XCD i % 8 and takes item i / 8 of that XCD's range of
+// items (a contiguous range of lists: the tiles of a list and the items of a
+// segment share that XCD's L2).  Workgroups past the end of their range leave at
+// once.
 constexpr uint32_t kXcds = 8;
 
 template <int METRIC>
-__global__ __launch_bounds__(256) void k_scan(Dev D, int max_nprobe, const float *__restrict__ Q,
-                                              SearchScratch S) {
-  extern __shared__ float4 qs_all[];  // [wavefronts][kScanTileQueries][d / 4]
-  float4 *qs = qs_all + (size_t)(threadIdx.x / kWave) * kScanTileQueries * D.d4;
-  ScanQueues *Qs = S.queues;
+__global__ __launch_bounds__(kWave) void k_scan(Dev D, int max_nprobe, const float *__restrict__ Q,
+                                                SearchScratch S) {
+  extern __shared__ float4 qs[];  // [kScanTileQueries][d / 4]
+  const ScanQueues *Qs = S.queues;
+  const uint32_t x = blockIdx.x % kXcds;
+  const uint32_t item = Qs->begin[x] + blockIdx.x / kXcds;
+  if (item >= Qs->begin[x + 1]) return;
   const uint32_t seg = Qs->seg_groups;
-  const uint32_t home = blockIdx.x % kXcds;
-  const int lane = threadIdx.x & (kWave - 1);
-  for (uint32_t hop = 0; hop < kXcds; ++hop) {
-    const uint32_t x = (home + hop) % kXcds;
-    const uint32_t begin = Qs->begin[x], end = Qs->begin[x + 1];
-    for (;;) {
-      uint32_t item = 0;
-      if (lane == 0) item = begin + atomicAdd(&Qs->next[x], 1u);
-      item = __builtin_amdgcn_readfirstlane(item);
-      if (item >= end) break;
-      const uint4 desc = S.tile_desc[item];
-      const int list = __builtin_amdgcn_readfirstlane((int)desc.x);
-      const uint32_t first = __builtin_amdgcn_readfirstlane(desc.y);
-      const int cnt = __builtin_amdgcn_readfirstlane((int)desc.z);
-      const uint32_t g_begin = __builtin_amdgcn_readfirstlane(desc.w) * seg;
-      switch (cnt) {
-        case 1: scan_item<METRIC, 1>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-        case 2: scan_item<METRIC, 2>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-        case 3: scan_item<METRIC, 3>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-        case 4: scan_item<METRIC, 4>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-        case 5: scan_item<METRIC, 5>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-        case 6: scan_item<METRIC, 6>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-        case 7: scan_item<METRIC, 7>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-        default: scan_item<METRIC, 8>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-      }
-    }
+  if (seg == 0) return;
+  const uint4 desc = S.tile_desc[item];
+  const int list = __builtin_amdgcn_readfirstlane((int)desc.x);
+  const uint32_t first = (uint32_t)__builtin_amdgcn_readfirstlane((int)desc.y);
+  const int cnt = __builtin_amdgcn_readfirstlane((int)desc.z);
+  const uint32_t g_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)desc.w) * seg;
+  switch (cnt) {
+    case 1: scan_item<METRIC, 1>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 2: scan_item<METRIC, 2>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 3: scan_item<METRIC, 3>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 4: scan_item<METRIC, 4>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 5: scan_item<METRIC, 5>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 6: scan_item<METRIC, 6>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 7: scan_item<METRIC, 7>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    default: scan_item<METRIC, 8>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
   }
 }
 
@@ -661,29 +684,26 @@ void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, con
                      S, probe_out);
 }
 
-void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int target_items,
+void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int item_budget,
                   const SearchScratch &S, hipStream_t s) {
   if (nq <= 0) return;
   hipLaunchKernelGGL(k_group, dim3(1), dim3(kGroupThreads), 0, s, D, (int)nq, nprobe, max_nprobe,
-                     (uint32_t)target_items, S);
+                     (uint32_t)item_budget, (uint32_t)scan_grid(item_budget) / kXcds, S);
 }
 
-// wavefronts per workgroup of the scan: as many (4, 2, 1) as fit their query tiles into 64 KiB of LDS
-int scan_waves(const Dev &D) {
-  size_t per_wave = (size_t)kScanTileQueries * D.d * sizeof(float);
-  return per_wave * 4 <= 65536 ? 4 : per_wave * 2 <= 65536 ? 2 : 1;
-}
+// workgroups of the scan launch for a budget of work items: room for an uneven
+// split of the items over the XCDs
+int scan_grid(int item_budget) { return (item_budget + item_budget / 2 + kXcds - 1) / kXcds * kXcds; }
 
-void launch_scan(const Dev &D, int64_t nq, int max_nprobe, const float *Q, int workgroups,
+void launch_scan(const Dev &D, int64_t nq, int max_nprobe, const float *Q, int item_budget,
                  const SearchScratch &S, hipStream_t s) {
   if (nq <= 0) return;
-  const int waves = scan_waves(D);
-  dim3 grid((unsigned)((workgroups + kXcds - 1) / kXcds * kXcds));
-  size_t lds = (size_t)waves * kScanTileQueries * D.d * sizeof(float);  // one query tile per wavefront
+  dim3 grid((unsigned)scan_grid(item_budget));
+  size_t lds = (size_t)kScanTileQueries * D.d * sizeof(float);
   if (D.metric == 0)
-    hipLaunchKernelGGL(k_scan<0>, grid, dim3(waves * kWave), lds, s, D, max_nprobe, Q, S);
+    hipLaunchKernelGGL(k_scan<0>, grid, dim3(kWave), lds, s, D, max_nprobe, Q, S);
   else
-    hipLaunchKernelGGL(k_scan<1>, grid, dim3(waves * kWave), lds, s, D, max_nprobe, Q, S);
+    hipLaunchKernelGGL(k_scan<1>, grid, dim3(kWave), lds, s, D, max_nprobe, Q, S);
 }
 
 void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
