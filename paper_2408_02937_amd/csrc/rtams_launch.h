@@ -26,7 +26,7 @@ struct SearchScratch {
   uint32_t *list_len;   // [nlist] length of each probed list as seen by the grouping step
   uint32_t *pair_slot;  // [max_batch][max_nprobe] rank of the pair among the pairs of its list
   uint32_t *grouped;    // [max_batch * max_nprobe] pairs (query << 10 | probe) grouped by list
-  uint4 *tile_desc;     // [item_cap] {list, first pair, pairs, segment} per scan work item
+  uint4 *tile_desc;     // [item_cap] {list, first pair of the list, pairs of the list, segment} per item
   uint32_t item_cap;
   ScanQueues *queues;   // work items of this request, split into one queue per XCD
   float *cand;          // candidate scores

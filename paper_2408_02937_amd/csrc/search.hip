@@ -201,11 +201,13 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
 // scan reads a list once for up to kScanTileQueries queries.  One workgroup:
 // prefix sums over the lists of the pair counts, the work-item counts and the
 // work, then the item descriptors, the split of the items over the 8 XCDs and
-// the grouped pair array.  A work item is (list, query tile, segment of
-// seg_groups 64-vector groups); segments bound the work of one item, so that
-// long lists spread over many wavefronts.  The segment length is the shortest
-// power of two for which the request has at most `item_budget` items and no XCD
-// more than `max_per_xcd` (the launch of the scan is sized from those two).
+// the grouped pair array.  A work item is (list, segment of seg_groups
+// 64-vector groups); the wavefront that takes it walks the segment once per
+// tile of kScanTileQueries queries probing the list (the second walk finds the
+// segment in cache).  Segments bound the work of one item, so that long lists
+// spread over many wavefronts.  The segment length is the shortest power of two
+// for which the request has at most `item_budget` items and no XCD more than
+// `max_per_xcd` (the launch of the scan is sized from those two).
 constexpr int kGroupThreads = 1024;
 constexpr int kSegChoices = 8;  // segment lengths 2, 4, ..., 256 groups
 
@@ -255,11 +257,10 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
       S.list_len[l] = len;
       if (!c) continue;
       const uint32_t groups = (len + kWave - 1) / kWave;
-      const uint32_t tiles = (c + kScanTileQueries - 1) / kScanTileQueries;
 #pragma unroll
       for (int e = 0; e < kSegChoices; ++e) {
         const uint32_t sg = 2u << e;
-        cnt[e] += tiles * (groups ? (groups + sg - 1) / sg : 1u);
+        cnt[e] += groups ? (groups + sg - 1) / sg : 1u;
       }
     }
 #pragma unroll
@@ -280,7 +281,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
       if (!c) continue;
       const uint32_t groups = (S.list_len[l] + kWave - 1) / kWave;
       np += c;
-      ni += (c + kScanTileQueries - 1) / kScanTileQueries * (groups ? (groups + seg - 1) / seg : 1u);
+      ni += groups ? (groups + seg - 1) / seg : 1u;
       wk += (unsigned long long)c * (groups ? groups : 1u);
     }
     uint32_t inp = np, ini = ni;
@@ -305,7 +306,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
           const unsigned long long cut = total_work * x / 8;
           if (ws <= cut && cut < ws + w) s_begin[x] = is;
         }
-        is += (c + kScanTileQueries - 1) / kScanTileQueries * (groups ? (groups + seg - 1) / seg : 1u);
+        is += groups ? (groups + seg - 1) / seg : 1u;
         ws += w;
       }
     }
@@ -327,13 +328,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
       const uint32_t groups = (S.list_len[l] + kWave - 1) / kWave;
       const uint32_t segs = groups ? (groups + seg - 1) / seg : 1u;
       if (fits)
-        for (uint32_t sg = 0; sg < segs; ++sg)  // items of one segment are adjacent: they share its bytes in L2
-          for (uint32_t t = 0; t * kScanTileQueries < c; ++t) {
-            const uint32_t left = c - t * kScanTileQueries;
-            S.tile_desc[istart++] =
-                make_uint4((uint32_t)l, pstart + t * kScanTileQueries,
-                           left < (uint32_t)kScanTileQueries ? left : (uint32_t)kScanTileQueries, sg);
-          }
+        for (uint32_t sg = 0; sg < segs; ++sg) S.tile_desc[istart++] = make_uint4((uint32_t)l, pstart, c, sg);
       pstart += c;
     }
     break;
@@ -348,8 +343,8 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
 }
 
 // ------------------------------------------------------------------ list scan
-// A work item is one segment of one list together with up to kScanTileQueries
-// of the queries that probe the list.  Every WAVEFRONT works on its own: it
+// A work item is one segment of one list; it is walked once per tile of up to
+// kScanTileQueries of the queries that probe the list.  Every WAVEFRONT works on its own: it
 // takes an item from a queue, copies the item's queries into its slice of LDS,
 // and walks the segment in pairs of groups of 64 vectors, lane = vector (two
 // vectors per lane).  Per chunk of 4 dimensions it loads 1 KiB of consecutive
@@ -479,39 +474,48 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
   __builtin_amdgcn_wave_barrier();  // the LDS slice is rewritten by the next item
 }
 
-// One single-wavefront workgroup per work item; the hardware's workgroup
-// dispatcher is the work queue (a new workgroup starts wherever a wavefront slot
-// frees up).  Hardware hands consecutive workgroup ids to the 8 XCDs in turn, so
-// workgroup i runs on XCD i % 8 and takes item i / 8 of that XCD's range of
-// items (a contiguous range of lists: the tiles of a list and the items of a
-// segment share that XCD's L2).  Workgroups past the end of their range leave at
-// once.
+// One workgroup per work item (list, segment); the hardware's workgroup
+// dispatcher is the work queue (a new workgroup starts wherever room frees up).
+// The wavefronts of the workgroup take the query tiles of the list in turn and
+// walk the same segment at the same time, each with its own tile of queries in
+// its own slice of LDS: the segment comes from HBM once and the other
+// wavefronts find it in the CU's cache.  There is no barrier between them.
+// Hardware hands consecutive workgroup ids to the 8 XCDs in turn, so workgroup i
+// runs on XCD i % 8 and takes item i / 8 of that XCD's range of items (a
+// contiguous range of lists).  Workgroups past the end of their range, and
+// wavefronts without a tile, leave at once.
 constexpr uint32_t kXcds = 8;
+constexpr int kScanWaves = 4;
 
 template <int METRIC>
-__global__ __launch_bounds__(kWave) void k_scan(Dev D, int max_nprobe, const float *__restrict__ Q,
-                                                SearchScratch S) {
-  extern __shared__ float4 qs[];  // [kScanTileQueries][d / 4]
+__global__ __launch_bounds__(kScanWaves * kWave) void k_scan(Dev D, int max_nprobe,
+                                                             const float *__restrict__ Q, SearchScratch S) {
+  extern __shared__ float4 qs_all[];  // [wavefronts][kScanTileQueries][d / 4]
   const ScanQueues *Qs = S.queues;
   const uint32_t x = blockIdx.x % kXcds;
   const uint32_t item = Qs->begin[x] + blockIdx.x / kXcds;
   if (item >= Qs->begin[x + 1]) return;
   const uint32_t seg = Qs->seg_groups;
   if (seg == 0) return;
+  const uint32_t wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
+  float4 *qs = qs_all + (size_t)wave * kScanTileQueries * D.d4;
   const uint4 desc = S.tile_desc[item];
   const int list = __builtin_amdgcn_readfirstlane((int)desc.x);
   const uint32_t first = (uint32_t)__builtin_amdgcn_readfirstlane((int)desc.y);
-  const int cnt = __builtin_amdgcn_readfirstlane((int)desc.z);
+  const uint32_t pairs = (uint32_t)__builtin_amdgcn_readfirstlane((int)desc.z);
   const uint32_t g_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)desc.w) * seg;
-  switch (cnt) {
-    case 1: scan_item<METRIC, 1>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-    case 2: scan_item<METRIC, 2>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-    case 3: scan_item<METRIC, 3>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-    case 4: scan_item<METRIC, 4>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-    case 5: scan_item<METRIC, 5>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-    case 6: scan_item<METRIC, 6>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-    case 7: scan_item<METRIC, 7>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-    default: scan_item<METRIC, 8>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+  for (uint32_t t = wave * kScanTileQueries; t < pairs; t += waves * kScanTileQueries) {
+    const uint32_t f = first + t;
+    switch (pairs - t) {
+      case 1: scan_item<METRIC, 1>(D, S, Q, max_nprobe, list, f, g_begin, seg, qs); break;
+      case 2: scan_item<METRIC, 2>(D, S, Q, max_nprobe, list, f, g_begin, seg, qs); break;
+      case 3: scan_item<METRIC, 3>(D, S, Q, max_nprobe, list, f, g_begin, seg, qs); break;
+      case 4: scan_item<METRIC, 4>(D, S, Q, max_nprobe, list, f, g_begin, seg, qs); break;
+      case 5: scan_item<METRIC, 5>(D, S, Q, max_nprobe, list, f, g_begin, seg, qs); break;
+      case 6: scan_item<METRIC, 6>(D, S, Q, max_nprobe, list, f, g_begin, seg, qs); break;
+      case 7: scan_item<METRIC, 7>(D, S, Q, max_nprobe, list, f, g_begin, seg, qs); break;
+      default: scan_item<METRIC, 8>(D, S, Q, max_nprobe, list, f, g_begin, seg, qs); break;
+    }
   }
 }
 
@@ -699,11 +703,13 @@ void launch_scan(const Dev &D, int64_t nq, int max_nprobe, const float *Q, int i
                  const SearchScratch &S, hipStream_t s) {
   if (nq <= 0) return;
   dim3 grid((unsigned)scan_grid(item_budget));
-  size_t lds = (size_t)kScanTileQueries * D.d * sizeof(float);
+  // as many wavefronts per workgroup (4, 2, 1) as fit their query tiles into 64 KiB of LDS
+  const size_t per_wave = (size_t)kScanTileQueries * D.d * sizeof(float);
+  const int waves = per_wave * 4 <= 65536 ? 4 : per_wave * 2 <= 65536 ? 2 : 1;
   if (D.metric == 0)
-    hipLaunchKernelGGL(k_scan<0>, grid, dim3(kWave), lds, s, D, max_nprobe, Q, S);
+    hipLaunchKernelGGL(k_scan<0>, grid, dim3(waves * kWave), waves * per_wave, s, D, max_nprobe, Q, S);
   else
-    hipLaunchKernelGGL(k_scan<1>, grid, dim3(kWave), lds, s, D, max_nprobe, Q, S);
+    hipLaunchKernelGGL(k_scan<1>, grid, dim3(waves * kWave), waves * per_wave, s, D, max_nprobe, Q, S);
 }
 
 void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
