@@ -22,34 +22,20 @@ __device__ inline uint32_t key_of_float(float x) {
 // ------------------------------------------------- workgroup radix selection
 // Finds the threshold of the k smallest keys among the valid items 0..n-1.
 // fn(i, key) returns false for items that do not take part.  On return T is
-// the k-th smallest key, `need` how many items with key == T belong to the k
-// smallest, c_eq how many items have key == T.  Requires 1 <= k <= #valid.
+// a threshold such that every key < T belongs to the k smallest and, of the
+// c_eq keys not yet told apart from T, `need` belong to them (when c_eq == need
+// the selection stops early and T is the largest key that group can hold; else
+// T is the k-th smallest key itself and the c_eq keys equal it).  Callers take
+// key < T, and key == T under the tie rule.  Requires 1 <= k <= #valid.
 struct SelectResult {
   uint64_t T;
   uint32_t need, c_eq;
 };
 
-template <int BITS, typename Fn>
-__device__ SelectResult wg_radix_select(int n, uint32_t k, Fn fn, uint32_t *hist, uint32_t *bc) {
-  uint64_t prefix = 0, mask = 0;
-  uint32_t need = k, c_eq = 0;
-  for (int shift = BITS - 8; shift >= 0; shift -= 8) {
-    for (int b = threadIdx.x; b < 256; b += blockDim.x) hist[b] = 0;
-    __syncthreads();
-    for (int i0 = threadIdx.x; i0 < n; i0 += 4 * blockDim.x) {  // four independent loads in flight
-      uint64_t key[4];
-      bool ok[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int i = i0 + u * (int)blockDim.x;
-        ok[u] = i < n && fn(i, key[u]);
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-        if (ok[u] && (key[u] & mask) == prefix) atomicAdd(&hist[(uint32_t)(key[u] >> shift) & 255u], 1u);
-    }
-    __syncthreads();
-    if (threadIdx.x < kWave) {  // first wavefront: which bin holds the need-th item
+// After a histogram pass: the first wavefront finds the bin that holds the
+// need-th smallest item; bc = {bin, items in lower bins, items in the bin}.
+__device__ inline void wg_pick_bin(const uint32_t *hist, uint32_t need, uint32_t *bc) {
+  if (threadIdx.x < kWave) {  // first wavefront: which bin holds the need-th item
       int l = threadIdx.x;
       uint32_t h0 = hist[4 * l], h1 = hist[4 * l + 1], h2 = hist[4 * l + 2], h3 = hist[4 * l + 3];
       uint32_t sum = h0 + h1 + h2 + h3, incl = sum;
@@ -74,31 +60,158 @@ __device__ SelectResult wg_radix_select(int n, uint32_t k, Fn fn, uint32_t *hist
       }
     }
     __syncthreads();
+}
+
+// `each(body)` calls body(key) for every key of the calling thread that takes part.
+template <int BITS, typename Each>
+__device__ SelectResult wg_radix_select_each(uint32_t k, Each each, uint32_t *hist, uint32_t *bc) {
+  // Leading digits on which every key agrees are skipped: scores of one query's
+  // candidates share sign, exponent and often the first mantissa bits, and a
+  // histogram pass in which all lanes hit one LDS word serialises completely.
+  unsigned long long *mm = reinterpret_cast<unsigned long long *>(hist);  // {min, max} for a moment
+  if (threadIdx.x == 0) { mm[0] = ~0ull; mm[1] = 0ull; }
+  __syncthreads();
+  {
+    unsigned long long lo = ~0ull, hi = 0ull;
+    each([&](uint64_t key) { lo = key < lo ? key : lo; hi = key > hi ? key : hi; });
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+      const unsigned long long a = __shfl_xor(lo, o), b = __shfl_xor(hi, o);
+      lo = a < lo ? a : lo;
+      hi = b > hi ? b : hi;
+    }
+    if ((threadIdx.x & (kWave - 1)) == 0) { atomicMin(&mm[0], lo); atomicMax(&mm[1], hi); }
+  }
+  __syncthreads();
+  const uint64_t kmin = mm[0], kmax = mm[1];
+  __syncthreads();  // hist is reused below
+  int first_shift = BITS - 8;
+  uint64_t prefix = 0, mask = 0;
+  {
+    const uint64_t diff = kmin ^ kmax;
+    const int top = diff ? 63 - __clzll((long long)diff) : -1;  // highest bit in which keys differ
+    first_shift = top < 0 ? 0 : (top / 8) * 8;
+    if (first_shift > BITS - 8) first_shift = BITS - 8;
+    if (first_shift + 8 < 64) {
+      mask = ~0ull << (first_shift + 8);
+      if (BITS < 64) mask &= (1ull << BITS) - 1ull;
+    }
+    prefix = kmax & mask;
+  }
+  uint32_t need = k, c_eq = 0;
+  for (int shift = first_shift; shift >= 0; shift -= 8) {
+    for (int b = threadIdx.x; b < 256; b += blockDim.x) hist[b] = 0;
+    __syncthreads();
+    each([&](uint64_t key) {
+      if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & 255u], 1u);
+    });
+    __syncthreads();
+    wg_pick_bin(hist, need, bc);
     uint32_t dg = bc[0];
     need -= bc[1];
     c_eq = bc[2];
     prefix |= (uint64_t)dg << shift;
     mask |= (uint64_t)255u << shift;
     __syncthreads();
+    if (c_eq == need) {  // the whole bin belongs to the k smallest: the lower digits cannot matter
+      if (shift > 0) prefix |= (1ull << shift) - 1ull;  // threshold = largest key of the bin
+      break;
+    }
   }
   return {prefix, need, c_eq};
 }
 
+// The same selection over 32-bit keys that every thread holds in registers:
+// thread t owns kreg[0 .. mine-1].  Nothing is read from memory.
+template <int KR>
+__device__ SelectResult wg_radix_select_regs(const uint32_t (&kreg)[KR], int mine, uint32_t k,
+                                             uint32_t *hist, uint32_t *bc) {
+  if (threadIdx.x == 0) { hist[0] = 0xffffffffu; hist[1] = 0u; }
+  __syncthreads();
+  {
+    uint32_t lo = 0xffffffffu, hi = 0u;
+#pragma unroll
+    for (int u = 0; u < KR; ++u)
+      if (u < mine) { lo = kreg[u] < lo ? kreg[u] : lo; hi = kreg[u] > hi ? kreg[u] : hi; }
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+      const uint32_t a = __shfl_xor(lo, o), b = __shfl_xor(hi, o);
+      lo = a < lo ? a : lo;
+      hi = b > hi ? b : hi;
+    }
+    if ((threadIdx.x & (kWave - 1)) == 0) { atomicMin(&hist[0], lo); atomicMax(&hist[1], hi); }
+  }
+  __syncthreads();
+  const uint32_t kmin = hist[0], kmax = hist[1];
+  __syncthreads();  // hist is reused below
+  const uint32_t diff = kmin ^ kmax;
+  const int top = diff ? 31 - __clz((int)diff) : -1;  // highest bit in which keys differ
+  const int first_shift = top < 0 ? 0 : (top / 8) * 8;
+  uint32_t mask = first_shift + 8 < 32 ? ~0u << (first_shift + 8) : 0u;
+  uint32_t prefix = kmax & mask;
+  uint32_t need = k, c_eq = 0;
+  for (int shift = first_shift; shift >= 0; shift -= 8) {
+    for (int b = threadIdx.x; b < 256; b += blockDim.x) hist[b] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < KR; ++u)
+      if (u < mine && (kreg[u] & mask) == prefix) atomicAdd(&hist[(kreg[u] >> shift) & 255u], 1u);
+    __syncthreads();
+    wg_pick_bin(hist, need, bc);
+    const uint32_t dg = bc[0];
+    need -= bc[1];
+    c_eq = bc[2];
+    prefix |= dg << shift;
+    mask |= 255u << shift;
+    __syncthreads();
+    if (c_eq == need) {
+      if (shift > 0) prefix |= (1u << shift) - 1u;
+      break;
+    }
+  }
+  return {(uint64_t)prefix, need, c_eq};
+}
+
+// Items 0..n-1 given by fn(i, key) (false: the item does not take part); keys are
+// read from memory, four independent loads in flight per thread.
+template <int BITS, typename Fn>
+__device__ SelectResult wg_radix_select(int n, uint32_t k, Fn fn, uint32_t *hist, uint32_t *bc) {
+  auto each = [&](auto body) {
+    for (int i0 = threadIdx.x; i0 < n; i0 += 4 * blockDim.x) {
+      uint64_t key[4];
+      bool ok[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {  // clamped index: the loads are unconditional and issue back to back
+        const int i = i0 + u * (int)blockDim.x;
+        ok[u] = fn(i < n ? i : n - 1, key[u]) && i < n;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (ok[u]) body(key[u]);
+    }
+  };
+  return wg_radix_select_each<BITS>(k, each, hist, bc);
+}
+
 // Bitonic sort of m (power of two) entries in LDS by (k1, k2) ascending; pay is
-// carried along.
+// carried along.  The first wavefront does all of it (LDS operations of one
+// wavefront execute in order, so the steps need no workgroup barrier); the
+// others wait at the end.
 __device__ inline void wg_bitonic_sort(int m, uint64_t *k1, uint64_t *k2, uint32_t *pay) {
-  for (int size = 2; size <= m; size <<= 1) {
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      __syncthreads();
-      for (int t = threadIdx.x; t < m / 2; t += blockDim.x) {
-        int i = 2 * t - (t & (stride - 1));
-        int j = i + stride;
-        bool up = (i & size) == 0;
-        uint64_t a1 = k1[i], a2 = k2[i], b1 = k1[j], b2 = k2[j];
-        bool a_gt_b = a1 != b1 ? a1 > b1 : a2 > b2;
-        if (a_gt_b == up) {
-          k1[i] = b1; k2[i] = b2; k1[j] = a1; k2[j] = a2;
-          uint32_t p = pay[i]; pay[i] = pay[j]; pay[j] = p;
+  __syncthreads();
+  if (threadIdx.x < kWave) {
+    for (int size = 2; size <= m; size <<= 1) {
+      for (int stride = size >> 1; stride > 0; stride >>= 1) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        for (int t = threadIdx.x; t < m / 2; t += kWave) {
+          int i = 2 * t - (t & (stride - 1));
+          int j = i + stride;
+          bool up = (i & size) == 0;
+          uint64_t a1 = k1[i], a2 = k2[i], b1 = k1[j], b2 = k2[j];
+          bool a_gt_b = a1 != b1 ? a1 > b1 : a2 > b2;
+          if (a_gt_b == up) {
+            k1[i] = b1; k2[i] = b2; k1[j] = a1; k2[j] = a2;
+            uint32_t p = pay[i]; pay[i] = pay[j]; pay[j] = p;
+          }
         }
       }
     }
@@ -119,7 +232,7 @@ __device__ inline int next_pow2(int v) {
 // publishes meanwhile, and the query gets its slice of the candidate array.
 __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, int max_nprobe,
                                                             SearchScratch S, int32_t *probe_out) {
-  __shared__ uint32_t hist[256];
+  __shared__ __attribute__((aligned(8))) uint32_t hist[256];  // also holds two 64-bit words for a moment
   __shared__ uint32_t bc[4];
   __shared__ uint32_t cnt[2];
   __shared__ uint64_t k1[kMaxNprobe];
@@ -213,19 +326,31 @@ constexpr int kSegChoices = 8;  // segment lengths 2, 4, ..., 256 groups
 
 __device__ inline void wg_scan3(uint32_t &a, uint32_t &b, unsigned long long &c, uint32_t *sa,
                                 uint32_t *sb, unsigned long long *sc) {
-  // inclusive scan over the threads of three values at once
-  const int tid = threadIdx.x;
-  __syncthreads();
-  sa[tid] = a; sb[tid] = b; sc[tid] = c;
-  __syncthreads();
-  for (int o = 1; o < kGroupThreads; o <<= 1) {
-    uint32_t xa = tid >= o ? sa[tid - o] : 0u, xb = tid >= o ? sb[tid - o] : 0u;
-    unsigned long long xc = tid >= o ? sc[tid - o] : 0ull;
-    __syncthreads();
-    sa[tid] += xa; sb[tid] += xb; sc[tid] += xc;
-    __syncthreads();
+  // inclusive scan over the threads of three values at once: shuffles inside a
+  // wavefront, then the wavefront totals through LDS; sa/sb/sc[kGroupThreads-1]
+  // receive the grand totals
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  constexpr int kWaves = kGroupThreads / kWave;
+  for (int o = 1; o < kWave; o <<= 1) {
+    const uint32_t xa = __shfl_up(a, o), xb = __shfl_up(b, o);
+    const unsigned long long xc = __shfl_up(c, o);
+    if (lane >= o) { a += xa; b += xb; c += xc; }
   }
-  a = sa[tid]; b = sb[tid]; c = sc[tid];
+  __syncthreads();  // earlier readers of the LDS arrays are done
+  if (lane == kWave - 1) { sa[wave] = a; sb[wave] = b; sc[wave] = c; }
+  __syncthreads();
+  uint32_t oa = 0, ob = 0, ta = 0, tb = 0;
+  unsigned long long oc = 0, tc = 0;
+  for (int w = 0; w < kWaves; ++w) {
+    const uint32_t va = sa[w], vb = sb[w];
+    const unsigned long long vc = sc[w];
+    if (w < wave) { oa += va; ob += vb; oc += vc; }
+    ta += va; tb += vb; tc += vc;
+  }
+  a += oa; b += ob; c += oc;
+  __syncthreads();
+  if (tid == kGroupThreads - 1) { sa[tid] = ta; sb[tid] = tb; sc[tid] = tc; }
+  __syncthreads();
 }
 
 __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int nprobe, int max_nprobe,
@@ -263,9 +388,14 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
         cnt[e] += groups ? (groups + sg - 1) / sg : 1u;
       }
     }
+    // totals per choice: shuffles inside the wavefront, one LDS atomic per wavefront
+    // (every lane adding to the same LDS word would serialise)
 #pragma unroll
-    for (int e = 0; e < kSegChoices; ++e)
-      if (cnt[e]) atomicAdd(&s_items[e], cnt[e]);
+    for (int e = 0; e < kSegChoices; ++e) {
+      uint32_t v = cnt[e];
+      for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
+      if ((tid & (kWave - 1)) == 0 && v) atomicAdd(&s_items[e], v);
+    }
   }
   __syncthreads();
   int choice = kSegChoices - 1;
@@ -334,11 +464,30 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
     break;
   }
   __syncthreads();  // list starts written above are read below by other threads of this workgroup
-  for (int idx = tid; idx < nq * nprobe; idx += kGroupThreads) {
-    int q = idx / nprobe, p = idx - q * nprobe;
-    size_t o = (size_t)q * max_nprobe + p;
-    int l = S.probe_list[o];
-    S.grouped[S.list_cnt[l] + S.pair_slot[o]] = ((uint32_t)q << 10) | (uint32_t)p;
+  // scatter of the pairs into their list's group, eight independent chains of loads per thread
+  const int npairs = nq * nprobe;
+  for (int base = tid; base < npairs; base += 8 * kGroupThreads) {
+    int l[8];
+    uint32_t slot[8], pk[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int idx = base + u * kGroupThreads;
+      if (idx < npairs) {
+        const int q = idx / nprobe, p = idx - q * nprobe;
+        const size_t o = (size_t)q * max_nprobe + p;
+        l[u] = S.probe_list[o];
+        slot[u] = S.pair_slot[o];
+        pk[u] = ((uint32_t)q << 10) | (uint32_t)p;
+      } else {
+        l[u] = -1;
+      }
+    }
+    uint32_t start[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) start[u] = l[u] >= 0 ? S.list_cnt[l[u]] : 0u;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (l[u] >= 0) S.grouped[start[u] + slot[u]] = pk[u];
   }
 }
 
@@ -532,7 +681,7 @@ constexpr int kSurvivorCap = 4096;
 constexpr int kBoundPrefix = 8192;  // candidates (at least) that the first bound is taken from
 
 struct SelectShared {
-  uint32_t hist[256];
+  __attribute__((aligned(8))) uint32_t hist[256];  // also holds two 64-bit words for a moment
   uint32_t bc[4];
   uint32_t cnt[2];
   uint64_t k1[kMaxK];
@@ -590,7 +739,8 @@ __device__ int select_topk(int count, int k, KeyFn key, ItemFn item, IdFn id_of,
   return kk;
 }
 
-constexpr int kTopkThreads = 1024;
+constexpr int kTopkThreads = 512;
+constexpr int kKeyRegs = 128; // candidate keys a thread of the selection keeps in registers
 
 __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprobe, int max_nprobe,
                                                         SearchScratch S, float *__restrict__ out_dist,
@@ -638,23 +788,75 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
     int m0 = n;
     for (int p = 1; p < nprobe; ++p)
       if (offs[p] >= want) { m0 = (int)offs[p]; break; }
-    SelectResult r0 = wg_radix_select<32>(
-        m0, (uint32_t)k, [&](int i, uint64_t &kv) { kv = key1(i); return true; }, sh.hist, sh.bc);
-    const uint32_t bound = (uint32_t)r0.T;
-    // one pass over the slice, four independent loads in flight per thread
-    for (int i0 = threadIdx.x; i0 < n; i0 += 4 * kTopkThreads) {
-      uint32_t kv[4];
+    // The bound is the k-th best of a SAMPLE of that prefix (every 4th candidate when
+    // the prefix is long enough): the k-th best of any k or more candidates bounds the
+    // final k-th best, and the sample makes the selection four times cheaper at the
+    // price of a few hundred more survivors.
+    const int stride = m0 >= 4 * (k > 512 ? k : 512) ? 4 : 1;
+    const int ms = (m0 + stride - 1) / stride;  // sample size, >= k
+    if (ms <= kKeyRegs * kTopkThreads) {
+      // the sample fits into registers: read it once (every load in flight at the
+      // same time) and take the bound without touching memory again;
+      // samples tid, tid + T, tid + 2T, ... below ms are this thread's
+      uint32_t kreg[kKeyRegs];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int i = i0 + u * kTopkThreads;
-        kv[u] = i < n ? key1(i) : 0xffffffffu;
+      for (int u = 0; u < kKeyRegs; ++u) {  // clamped index: unconditional loads
+        const int j = (int)threadIdx.x + u * kTopkThreads;
+        kreg[u] = key1((j < ms ? j : ms - 1) * stride);
       }
+      const int mine = ms > (int)threadIdx.x ? (ms - (int)threadIdx.x + kTopkThreads - 1) / kTopkThreads : 0;
+      const SelectResult r0 = wg_radix_select_regs<kKeyRegs>(kreg, mine, (uint32_t)k, sh.hist, sh.bc);
+      uint32_t bound = (uint32_t)r0.T;
+      // one pass over the whole slice, many independent loads in flight per thread;
+      // if more survive than LDS holds, the k-th best of those that were kept is a
+      // tighter bound and the pass is repeated (ties that cannot be told apart end it)
+      constexpr int kInFlight = 24;
+      for (int round = 0; round < 4; ++round) {
+        for (int i0 = (int)threadIdx.x; i0 < n; i0 += kInFlight * kTopkThreads) {
+          uint32_t kv[kInFlight];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int i = i0 + u * kTopkThreads;
-        if (i < n && kv[u] <= bound) {
-          uint32_t pos = atomicAdd(&scount, 1u);
-          if (pos < (uint32_t)kSurvivorCap) { skey[pos] = kv[u]; sidx[pos] = (uint32_t)i; }
+          for (int u = 0; u < kInFlight; ++u) {
+            const int i = i0 + u * kTopkThreads;
+            kv[u] = key1(i < n ? i : n - 1);
+          }
+#pragma unroll
+          for (int u = 0; u < kInFlight; ++u) {
+            const int i = i0 + u * kTopkThreads;
+            if (i < n && kv[u] <= bound) {
+              uint32_t pos = atomicAdd(&scount, 1u);
+              if (pos < (uint32_t)kSurvivorCap) { skey[pos] = kv[u]; sidx[pos] = (uint32_t)i; }
+            }
+          }
+        }
+        __syncthreads();
+        if (scount <= (uint32_t)kSurvivorCap) break;
+        const SelectResult rt = wg_radix_select<32>(
+            kSurvivorCap, (uint32_t)k, [&](int j, uint64_t &kv) { kv = skey[j]; return true; }, sh.hist, sh.bc);
+        if ((uint32_t)rt.T >= bound) break;  // no tighter: left to the in-place selection below
+        bound = (uint32_t)rt.T;
+        __syncthreads();
+        if (threadIdx.x == 0) scount = 0;
+        __syncthreads();
+      }
+    } else {
+      SelectResult r0 = wg_radix_select<32>(
+          m0, (uint32_t)k, [&](int i, uint64_t &kv) { kv = key1(i); return true; }, sh.hist, sh.bc);
+      const uint32_t bound = (uint32_t)r0.T;
+      // one pass over the slice, four independent loads in flight per thread
+      for (int i0 = threadIdx.x; i0 < n; i0 += 4 * kTopkThreads) {
+        uint32_t kv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int i = i0 + u * kTopkThreads;
+          kv[u] = key1(i < n ? i : n - 1);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int i = i0 + u * kTopkThreads;
+          if (i < n && kv[u] <= bound) {
+            uint32_t pos = atomicAdd(&scount, 1u);
+            if (pos < (uint32_t)kSurvivorCap) { skey[pos] = kv[u]; sidx[pos] = (uint32_t)i; }
+          }
         }
       }
     }
