@@ -197,11 +197,14 @@ def extras(args, g, w, torch, rtams, q_batches, queries, ins_batches, data_strea
     s = search_streams[0]
     out = {}
 
-    def latencies(bs, iters):
+    def latencies(bs, iters, timed_scan=False):
         od = torch.empty((bs, k), dtype=torch.float32, device=dev)
         oi = torch.empty((bs, k), dtype=torch.int64, device=dev)
         lat = []
         nb = len(queries) // bs
+        if timed_scan:
+            g.scan_time(reset=True)
+            g.set_param("profile_scan", 1)
         for i in range(iters + 10):
             q = queries[(i % nb) * bs:(i % nb + 1) * bs]
             t0 = time.perf_counter()
@@ -209,7 +212,21 @@ def extras(args, g, w, torch, rtams, q_batches, queries, ins_batches, data_strea
             s.synchronize()
             if i >= 10:
                 lat.append((time.perf_counter() - t0) * 1e3)
+        if timed_scan:
+            g.set_param("profile_scan", 0)
+            ms, cnt = g.scan_time(reset=True)
+            return lat, ms / max(cnt, 1)
         return lat
+
+    def union_bytes(bs, batches):
+        sizes = g.list_sizes()
+        nb = len(queries) // bs
+        tot = []
+        for i in range(batches):
+            pl = g.probe(queries[(i % nb) * bs:(i % nb + 1) * bs], nprobe).cpu().numpy()
+            ln = sizes[np.unique(pl)]
+            tot.append(int((ln * w.d * 4 + ((ln + w.block_vecs - 1) // w.block_vecs) * 4).sum()))
+        return float(np.mean(tot))
 
     rate = 10_000.0  # vectors per second of the configured insertion stream
     stop = threading.Event()
@@ -231,7 +248,8 @@ def extras(args, g, w, torch, rtams, q_batches, queries, ins_batches, data_strea
     per_batch = {}
     for bs in (1, 32, 256):
         iters = args.latency_iters
-        alone = latencies(bs, iters)
+        alone, scan_ms = latencies(bs, iters, timed_scan=True)
+        ub = union_bytes(bs, min(iters, 64))
         stop.clear()
         sent[0] = 0
         th = threading.Thread(target=inserter)
@@ -248,6 +266,10 @@ def extras(args, g, w, torch, rtams, q_batches, queries, ins_batches, data_strea
             "with_inserts": {"qps": bs / (np.mean(loaded) * 1e-3), "p50_ms": percentile(loaded, 50),
                              "p99_ms": percentile(loaded, 99), "inserts_per_s": sent[0] / dt},
             "p99_ratio": percentile(loaded, 99) / percentile(alone, 99),
+            # list scan of one request running alone: union bytes of the probed lists over its duration
+            "scan": {"avg_launch_ms": scan_ms, "bytes_per_launch": ub,
+                     "achieved_GBps": ub / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else None,
+                     "frac_of_hbm_peak": ub / (scan_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if scan_ms > 0 else None},
         }
     out["latency_by_query_batch"] = per_batch
 

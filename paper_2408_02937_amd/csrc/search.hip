@@ -905,9 +905,10 @@ void launch_scan(const Dev &D, int64_t nq, int max_nprobe, const float *Q, int i
                  const SearchScratch &S, hipStream_t s) {
   if (nq <= 0) return;
   dim3 grid((unsigned)scan_grid(item_budget));
-  // as many wavefronts per workgroup (4, 2, 1) as fit their query tiles into 64 KiB of LDS
+  // as many wavefronts per workgroup (8, 4, 2, 1) as fit their query tiles into 64 KiB of LDS
   const size_t per_wave = (size_t)kScanTileQueries * D.d * sizeof(float);
-  const int waves = per_wave * 4 <= 65536 ? 4 : per_wave * 2 <= 65536 ? 2 : 1;
+  int waves = kScanWaves;
+  while (waves > 1 && per_wave * waves > 65536) waves /= 2;
   if (D.metric == 0)
     hipLaunchKernelGGL(k_scan<0>, grid, dim3(waves * kWave), waves * per_wave, s, D, max_nprobe, Q, S);
   else
