@@ -511,13 +511,16 @@ __device__ __forceinline__ void accumulate(float &acc, const float4 &x, const fl
   }
 }
 
-constexpr int kPrefetch = 2;  // chunks of 4 dimensions per register set of the software pipeline
+// Chunks of 4 dimensions per register set of the software pipeline.  Deeper sets for
+// items with few queries were measured: they cost a wavefront of occupancy and gain nothing.
+constexpr int prefetch_chunks(int) { return 2; }
 
 template <int METRIC, int NQ>
 __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
                                           const float *__restrict__ Q, int max_nprobe, int list,
                                           uint32_t first, uint32_t g_begin, uint32_t g_count,
                                           float4 *qs) {
+  constexpr int kPrefetch = prefetch_chunks(NQ);
   const int d4 = D.d4;
   const int lane = threadIdx.x & (kWave - 1);
   // lane i < NQ looks after query i of the item: where it reads and writes, how far its list goes
