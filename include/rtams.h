@@ -179,10 +179,13 @@ int rtams_scan_time(rtams_index *ix, double *ms_sum, int64_t *launches, int rese
 int rtams_copy_plain(void *d_dst, const void *d_src, size_t bytes, void *hip_stream);
 /* Launch-shape knobs ("restrict the number of blocks and threads per kernel",
  * Stream-Cached Multi-Stream Execution, consideration 2).  key: "scan_max_items"
- * (most work items, i.e. single-wavefront workgroups, one list-scan launch is cut
+ * (most work items, one workgroup each, one list-scan launch is cut
  * into; default 16384), "scan_items_per_pair" (items per (query, list) pair a small
- * request may be cut into; default 8), and "profile_scan" (see rtams_scan_time).
- * EINVAL for an unknown key. */
+ * request may be cut into; default 8), "profile_scan" (see rtams_scan_time), and
+ * "use_mfma": whether approximate coarse scores from the matrix cores filter the
+ * centroids before the exact arithmetic decides (0 never, 1 for batches large
+ * enough to repay it (default), 2 for every batch of 32 rows or more; results
+ * are identical in all three).  EINVAL for an unknown key. */
 int rtams_set_param(rtams_index *ix, const char *key, int64_t value);
 
 #ifdef __cplusplus

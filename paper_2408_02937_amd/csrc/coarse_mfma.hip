@@ -1,0 +1,204 @@
+// Coarse quantizer as a dense contraction on the matrix cores, used when a
+// batch is large enough for that to pay (bulk loads, big insertion batches,
+// query batches against many centroids): approximate scores of every (vector,
+// centroid) pair in fp32 with v_mfma_f32_32x32x2_f32.
+//
+// The approximate scores only FILTER.  Which list a vector joins and which
+// lists a query probes are decided by the fixed double-precision arithmetic of
+// coarse.hip on the few centroids the filter cannot tell apart (refinement
+// kernels below and in search.hip), so the decisions stay bit-exact:
+//   approx(i, c) = |c|^2 - 2 <y_i, c>   (L2; |y_i|^2 is the same for every c)
+//   approx(i, c) = - <y_i, c>           (IP)            smaller is better
+// and |approx - exact| <= E_i = 4 (d + 4) 2^-24 (|y_i|^2 + max_c |c|^2), a bound
+// that covers the rounding of the norms, of the dot product in any summation
+// order, and of the final combination.  If m is the smallest approximate score
+// of row i, the exact winner lies among the centroids with approx <= m + 2 E_i.
+#include "rtams_launch.h"
+
+namespace rtams {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kMfmaThreads = 256;  // 4 wavefronts: 2 (rows) x 2 (columns)
+constexpr int kTileM = 64, kTileN = 128, kTileK = 16;
+constexpr int kLdsStride = kTileK + 1;  // odd stride: the 32 rows of an operand hit 32 banks
+
+// ---- centroid norms (fp32) and their maximum, once per set_centroids
+__global__ __launch_bounds__(256) void k_centroid_norms(Dev D) {
+  int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= D.nlist) return;
+  double acc = 0.0;
+  const float *row = D.centroids + (size_t)c * D.d;
+  for (int j = 0; j < D.d; ++j) acc = __builtin_fma((double)row[j], (double)row[j], acc);
+  float n = (float)acc;
+  D.cnorm[c] = n;
+  atomicMax(&D.ctrl->cnorm_max_bits, __float_as_uint(n));  // non-negative floats order like their bits
+}
+
+// ---- approx[i][c] for i < n, c < nlist
+template <int METRIC>
+__global__ __launch_bounds__(kMfmaThreads) void k_coarse_mfma(Dev D, int64_t n, const float *__restrict__ Y,
+                                                              float *__restrict__ approx,
+                                                              unsigned long long *cursor_to_clear,
+                                                              uint32_t *__restrict__ zero, int zero_n) {
+  __shared__ float sA[kTileM * kLdsStride];
+  __shared__ float sB[kTileN * kLdsStride];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int wm = wave & 1, wn = wave >> 1;  // wavefront's place in the 2 x 2 arrangement
+  const int64_t row0 = (int64_t)blockIdx.x * kTileM;
+  const int col0 = blockIdx.y * kTileN;
+  const int d = D.d;
+
+  // per-request counters of the search plan start from zero (no memset node on the stream)
+  if (cursor_to_clear && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *cursor_to_clear = 0ull;
+  if (zero) {
+    const int nthreads = gridDim.x * gridDim.y * kMfmaThreads;
+    for (int i = (blockIdx.y * gridDim.x + blockIdx.x) * kMfmaThreads + tid; i < zero_n; i += nthreads) zero[i] = 0u;
+  }
+
+  floatx16 acc[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
+
+  // staging: thread t loads a float4 (4 consecutive k) of one row
+  const int ld_row = tid / 4, ld_k = (tid % 4) * 4;  // 64 rows x 16 k per pass
+  for (int k0 = 0; k0 < d; k0 += kTileK) {
+    {
+      const int64_t r = row0 + ld_row;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (r < n && k0 + ld_k < d) v = *reinterpret_cast<const float4 *>(Y + r * d + k0 + ld_k);
+      float *dst = sA + ld_row * kLdsStride + ld_k;
+      dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int cr = ld_row + 64 * h, c = col0 + cr;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (c < D.nlist && k0 + ld_k < d)
+        v = *reinterpret_cast<const float4 *>(D.centroids + (size_t)c * d + k0 + ld_k);
+      float *dst = sB + cr * kLdsStride + ld_k;
+      dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+    }
+    __syncthreads();
+    // operand layout of v_mfma_f32_32x32x2_f32: lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32]
+    const float *pa = sA + (wm * 32 + (lane & 31)) * kLdsStride + (lane >> 5);
+    const float *pb = sB + (wn * 64 + (lane & 31)) * kLdsStride + (lane >> 5);
+#pragma unroll
+    for (int kk = 0; kk < kTileK; kk += 2) {
+      const float a = pa[kk];
+      const float b0 = pb[kk], b1 = pb[32 * kLdsStride + kk];
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc[1], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  // result layout: register r of lane l holds row (r / 4) * 8 + (l / 32) * 4 + r % 4, column l % 32
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    const int c = col0 + wn * 64 + b * 32 + (lane & 31);
+    if (c >= D.nlist) continue;
+    const float cn = METRIC == 0 ? D.cnorm[c] : 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int64_t i = row0 + wm * 32 + (r / 4) * 8 + (lane >> 5) * 4 + (r % 4);
+      if (i < n) approx[(size_t)i * D.nlist + c] = METRIC == 0 ? cn - 2.f * acc[b][r] : -acc[b][r];
+    }
+  }
+}
+
+// ---- refinement of the assignment: one wavefront per vector.  Finds the
+// smallest approximate score of the row, gathers the centroids within the
+// error band, scores those in the fixed double arithmetic (one lane each) and
+// takes the best, ties to the lowest index; then takes the next position of the
+// list ("did = atomicAdd(nl_k, 1)").  A band wider than 64 centroids is walked
+// in rounds of 64.
+__device__ inline double exact_score(const Dev &D, const float *__restrict__ y, int c) {
+  const float *row = D.centroids + (size_t)c * D.d;
+  double acc = 0.0;
+  if (D.metric == 0) {
+    for (int j = 0; j < D.d; ++j) {
+      const double t = (double)y[j] - (double)row[j];
+      acc = __builtin_fma(t, t, acc);
+    }
+  } else {
+    for (int j = 0; j < D.d; ++j) acc = __builtin_fma((double)y[j], (double)row[j], acc);
+  }
+  return acc;
+}
+
+__device__ inline float error_band(const Dev &D, float ynorm) {
+  const float cmax = __uint_as_float(D.ctrl->cnorm_max_bits);
+  // 2 E_i with E_i = 4 (d + 4) 2^-24 (|y|^2 + max |c|^2); the norm itself carries a relative
+  // error of at most d 2^-24, covered by the factor 1.01
+  return 8.f * (float)(D.d + 4) * 5.9604645e-8f * (ynorm + cmax) * 1.01f;
+}
+
+__global__ __launch_bounds__(256) void k_assign_refine(Dev D, int64_t n, const float *__restrict__ Y,
+                                                       const float *__restrict__ approx, int reserve,
+                                                       int32_t *__restrict__ assign,
+                                                       uint32_t *__restrict__ did) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t i = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  if (i >= n) return;  // uniform over the wavefront
+  const float *y = Y + i * D.d;
+  const float *row = approx + (size_t)i * D.nlist;
+  float yn = 0.f, m = __builtin_inff();
+  for (int j = lane; j < D.d; j += kWave) yn = fmaf(y[j], y[j], yn);
+  for (int c = lane; c < D.nlist; c += kWave) m = fminf(m, row[c]);
+  for (int o = kWave / 2; o > 0; o >>= 1) {
+    yn += __shfl_xor(yn, o);
+    m = fminf(m, __shfl_xor(m, o));
+  }
+  const float limit = m + error_band(D, yn);
+  const bool l2 = D.metric == 0;
+  double best_s = l2 ? __builtin_inf() : -__builtin_inf();
+  int best_c = 0x7fffffff;
+  for (int c0 = 0; c0 < D.nlist; c0 += kWave) {
+    const int c = c0 + lane;
+    const bool cand = c < D.nlist && row[c] <= limit;
+    if (__ballot(cand) == 0) continue;  // uniform
+    if (cand) {
+      const double s = exact_score(D, y, c);
+      const bool take = s != best_s ? (l2 ? s < best_s : s > best_s) : c < best_c;
+      best_s = take ? s : best_s;
+      best_c = take ? c : best_c;
+    }
+  }
+  for (int o = kWave / 2; o > 0; o >>= 1) {
+    const double s = __shfl_xor(best_s, o);
+    const int c = __shfl_xor(best_c, o);
+    const bool take = s != best_s ? (l2 ? s < best_s : s > best_s) : c < best_c;
+    best_s = take ? s : best_s;
+    best_c = take ? c : best_c;
+  }
+  if (lane == 0) {
+    assign[i] = best_c;
+    if (reserve) did[i] = atomicAdd(&D.reserved_len[best_c], 1u);
+  }
+}
+
+void launch_centroid_norms(const Dev &D, hipStream_t s) {
+  hipLaunchKernelGGL(k_centroid_norms, dim3((unsigned)((D.nlist + 255) / 256)), dim3(256), 0, s, D);
+}
+
+void launch_coarse_mfma(const Dev &D, int64_t n, const float *Y, float *approx,
+                        unsigned long long *cursor_to_clear, uint32_t *zero, int zero_n, hipStream_t s) {
+  if (n <= 0) return;
+  dim3 grid((unsigned)((n + kTileM - 1) / kTileM), (unsigned)((D.nlist + kTileN - 1) / kTileN));
+  if (D.metric == 0)
+    hipLaunchKernelGGL(k_coarse_mfma<0>, grid, dim3(kMfmaThreads), 0, s, D, n, Y, approx, cursor_to_clear, zero, zero_n);
+  else
+    hipLaunchKernelGGL(k_coarse_mfma<1>, grid, dim3(kMfmaThreads), 0, s, D, n, Y, approx, cursor_to_clear, zero, zero_n);
+}
+
+void launch_assign_refine(const Dev &D, int64_t n, const float *Y, const float *approx, bool reserve,
+                          int32_t *assign, uint32_t *did, hipStream_t s) {
+  if (n <= 0) return;
+  unsigned grid = (unsigned)((n + 3) / 4);
+  hipLaunchKernelGGL(k_assign_refine, dim3(grid), dim3(256), 0, s, D, n, Y, approx, reserve ? 1 : 0, assign, did);
+}
+
+}  // namespace rtams

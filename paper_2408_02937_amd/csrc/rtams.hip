@@ -37,7 +37,7 @@ inline size_t up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Byte offsets of everything in front of the blocks.
 struct Layout {
-  size_t ctrl, hook, centroids, reserved_len, visible_len, online, nblk, exceed, seg_dir;
+  size_t ctrl, hook, centroids, cnorm, ins_approx, approx_rows, reserved_len, visible_len, online, nblk, exceed, seg_dir;
   size_t ins_assign, ins_did, ins_pscore, ins_pidx, part_cap;
   size_t rearr_head, rearr_arrays;
   size_t fixed_end;          // end of the part that does not depend on the block count
@@ -85,6 +85,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
   L->ctrl = take(sizeof(Ctrl));
   L->hook = take(kHookBytes);
   L->centroids = take(nl * c->d * sizeof(float));
+  L->cnorm = take(nl * sizeof(float));
   L->reserved_len = take(nl * 4);
   L->visible_len = take(nl * 4);
   L->online = take(nl * 4);
@@ -96,6 +97,13 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
   L->ins_did = take((size_t)c->max_add_batch * 4);
   L->ins_pscore = take(L->part_cap * 8);
   L->ins_pidx = take(L->part_cap * 4);
+  {  // approximate scores of one insertion sub-round: at most 256 MiB, at least 64 rows
+    size_t rows = ((size_t)256 << 20) / (nl * 4);
+    if (rows > (size_t)c->max_add_batch) rows = (size_t)c->max_add_batch;
+    if (rows < 64) rows = 64;
+    L->approx_rows = rows;
+    L->ins_approx = take(rows * nl * 4);
+  }
   L->rearr_head = take(sizeof(RearrangeHead));
   L->rearr_arrays = take((size_t)kRearrangeCap * 4 * 7);
   L->fixed_end = o;
@@ -119,7 +127,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
 }
 
 struct ScratchLayout {
-  size_t scores, probe_list, probe_len, probe_off, qbase, qtotal, cursor, cand, fixed;
+  size_t scores, approx, probe_list, probe_len, probe_off, qbase, qtotal, cursor, cand, fixed;
   size_t list_cnt, list_len, pair_slot, grouped, tile_desc, queues, item_cap;
 };
 
@@ -128,6 +136,7 @@ void lay_out_scratch(const rtams_config *c, ScratchLayout *S) {
   auto take = [&](size_t bytes) { size_t at = o; o = up(o + bytes, kAlign); return at; };
   size_t mb = (size_t)c->max_batch, mp = (size_t)c->max_nprobe;
   S->scores = take(mb * c->nlist * 8);
+  S->approx = take(mb * c->nlist * 4);
   S->probe_list = take(mb * mp * 4);
   S->probe_len = take(mb * mp * 4);
   S->probe_off = take(mb * mp * 4);
@@ -183,6 +192,7 @@ struct rtams_index {
   std::atomic<int64_t> scan_items_per_pair{8};   // work items the plan may cut per (query, list) pair
   std::atomic<int64_t> scan_max_items{16384};    // ... and per request
   std::atomic<int64_t> profile_scan{0};
+  std::atomic<int64_t> use_mfma{1};  // matrix-core filter in front of the exact coarse arithmetic
   std::mutex prof_mutex;
   double scan_ms = 0.0;      // sum of measured scan-kernel durations
   int64_t scan_launches = 0;
@@ -195,6 +205,17 @@ namespace {
 int plan_words(const rtams_index *ix) {
   return (int)(((const char *)ix->res[0].s.queues - (const char *)ix->res[0].s.list_cnt) / 4 +
                sizeof(ScanQueues) / 4);
+}
+
+// Coarse scores of the queries, probe selection and the plan of the scan.
+void coarse_and_plan(rtams_index *ix, int64_t nq, const float *Q, int nprobe, const SearchScratch &S,
+                     int32_t *probe_out, hipStream_t s) {
+  const Dev &D = ix->dev;
+  const int64_t mode = ix->use_mfma.load(std::memory_order_relaxed);  // 0 never, 1 when it pays, 2 from 32 rows
+  const bool mfma = mode == 2 ? nq >= 32 : mode == 1 && mfma_pays_for_search(nq, D.nlist);
+  if (mfma) launch_coarse_mfma(D, nq, Q, S.approx, S.cursor, S.list_cnt, plan_words(ix), s);
+  else launch_coarse_scores(D, nq, Q, S.scores, S.cursor, S.list_cnt, plan_words(ix), s);
+  launch_probe_plan(D, nq, nprobe, ix->cfg.max_nprobe, S, Q, mfma, probe_out, s);
 }
 
 int sync_data(rtams_index *ix) {
@@ -247,6 +268,26 @@ int acquire(rtams_index *ix) {
   }
   (void)hipGetLastError();  // hipEventQuery leaves hipErrorNotReady behind
   return -1;
+}
+
+// Nearest centroid of m vectors (m <= max_add_batch) and, if asked, the slot
+// reservation.  A batch that is a large dense contraction gets approximate
+// scores on the matrix cores, then exact refinement of what they cannot tell
+// apart; smaller batches go through the exact kernel alone.
+void assign_round(rtams_index *ix, int64_t m, const float *Y, bool reserve, int32_t *assign_out, hipStream_t s) {
+  const Dev &D = ix->dev;
+  const int64_t mode = ix->use_mfma.load(std::memory_order_relaxed);  // 0 never, 1 when it pays, 2 from 32 rows
+  if (mode == 2 ? m >= 32 : mode == 1 && mfma_pays_for_assign(m, D.nlist)) {
+    for (int64_t o = 0; o < m; o += ix->ins.approx_rows) {
+      const int64_t mm = m - o < ix->ins.approx_rows ? m - o : ix->ins.approx_rows;
+      launch_coarse_mfma(D, mm, Y + (size_t)o * D.d, ix->ins.approx, nullptr, nullptr, 0, s);
+      launch_assign_refine(D, mm, Y + (size_t)o * D.d, ix->ins.approx, reserve, assign_out + o, ix->ins.did + o, s);
+    }
+  } else {
+    int splits = coarse_splits(D, m, ix->ins.part_cap);
+    launch_coarse_argmin(D, m, Y, splits, ix->ins.pscore, ix->ins.pidx, s);
+    launch_reserve(D, m, splits, ix->ins, reserve, assign_out, s);
+  }
 }
 
 int read_ctrl(rtams_index *ix, Ctrl *out) {
@@ -309,6 +350,7 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   D.blocks = base + L.blocks;
   D.ctrl = reinterpret_cast<Ctrl *>(base + L.ctrl);
   D.centroids = reinterpret_cast<float *>(base + L.centroids);
+  D.cnorm = reinterpret_cast<float *>(base + L.cnorm);
   D.reserved_len = reinterpret_cast<uint32_t *>(base + L.reserved_len);
   D.visible_len = reinterpret_cast<uint32_t *>(base + L.visible_len);
   D.online = reinterpret_cast<uint32_t *>(base + L.online);
@@ -324,6 +366,8 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   ix->ins.pscore = reinterpret_cast<double *>(base + L.ins_pscore);
   ix->ins.pidx = reinterpret_cast<int32_t *>(base + L.ins_pidx);
   ix->ins.part_cap = L.part_cap;
+  ix->ins.approx = reinterpret_cast<float *>(base + L.ins_approx);
+  ix->ins.approx_rows = (int64_t)L.approx_rows;
   {
     uint32_t *a = reinterpret_cast<uint32_t *>(base + L.rearr_arrays);
     RearrangeScratch &R = ix->rearr;
@@ -362,6 +406,7 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
     char *p = sb + (size_t)r * slice;
     SearchScratch &S = ix->res[r].s;
     S.scores = reinterpret_cast<double *>(p + SL.scores);
+    S.approx = reinterpret_cast<float *>(p + SL.approx);
     S.probe_list = reinterpret_cast<int32_t *>(p + SL.probe_list);
     S.probe_len = reinterpret_cast<uint32_t *>(p + SL.probe_len);
     S.probe_off = reinterpret_cast<uint32_t *>(p + SL.probe_off);
@@ -414,6 +459,8 @@ int rtams_set_centroids(rtams_index *ix, const float *d_centroids, void *hip_str
   if (rc) return rc;
   HIP_TRY(hipMemcpyAsync(ix->dev.centroids, d_centroids, (size_t)ix->cfg.nlist * ix->cfg.d * 4,
                          hipMemcpyDeviceToDevice, s));
+  launch_centroid_norms(ix->dev, s);
+  HIP_TRY(hipGetLastError());
   ix->has_centroids = true;
   return leave_data_stream(ix, s);
 }
@@ -446,9 +493,7 @@ int rtams_add(rtams_index *ix, int64_t n, const float *d_vecs, const int64_t *d_
   for (int64_t o = 0; o < n; o += round) {
     int64_t m = n - o < round ? n - o : round;
     const float *Y = d_vecs + (size_t)o * D.d;
-    int splits = coarse_splits(D, m, ix->ins.part_cap);
-    launch_coarse_argmin(D, m, Y, splits, ix->ins.pscore, ix->ins.pidx, s);
-    launch_reserve(D, m, splits, ix->ins, true, nullptr, s);
+    assign_round(ix, m, Y, true, ix->ins.assign, s);
     launch_open(D, s);
     launch_fill(D, m, Y, d_ids ? d_ids + o : nullptr, ix->ntotal_host + o, ix->ins, s);
     launch_publish(D, s);
@@ -482,8 +527,7 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   const SearchScratch &S = ix->res[r].s;
   // a rearrangement is switching block tables: start behind its last switch
   if (ix->fence_cur) (void)hipStreamWaitEvent(s, ix->fence_cur, 0);
-  launch_coarse_scores(D, nq, d_queries, S.scores, S.cursor, S.list_cnt, plan_words(ix), s);
-  launch_probe_plan(D, nq, nprobe, ix->cfg.max_nprobe, S, nullptr, s);
+  coarse_and_plan(ix, nq, d_queries, nprobe, S, nullptr, s);
   // The scan is cut into work items of bounded size, one single-wavefront workgroup
   // each; the budget of items grows with the request so that a small batch still
   // spreads over the chip and a large one is not drowned in per-item overhead.
@@ -553,8 +597,7 @@ int rtams_probe(rtams_index *ix, int64_t nq, const float *d_queries, int32_t npr
   if (r < 0) return fail(RTAMS_EBUSY, "all %d stream resources are in flight", ix->n_res);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const SearchScratch &S = ix->res[r].s;
-  launch_coarse_scores(ix->dev, nq, d_queries, S.scores, S.cursor, S.list_cnt, plan_words(ix), s);
-  launch_probe_plan(ix->dev, nq, nprobe, ix->cfg.max_nprobe, S, d_out, s);
+  coarse_and_plan(ix, nq, d_queries, nprobe, S, d_out, s);
   hipError_t e = hipGetLastError();
   hipError_t e2 = hipEventRecord(ix->res[r].done, s);
   ix->res[r].state.store(RES_PENDING, std::memory_order_release);
@@ -574,9 +617,7 @@ int rtams_assign(rtams_index *ix, int64_t n, const float *d_vecs, int32_t *d_out
   const int64_t round = ix->cfg.max_add_batch;
   for (int64_t o = 0; o < n; o += round) {
     int64_t m = n - o < round ? n - o : round;
-    int splits = coarse_splits(ix->dev, m, ix->ins.part_cap);
-    launch_coarse_argmin(ix->dev, m, d_vecs + (size_t)o * ix->dev.d, splits, ix->ins.pscore, ix->ins.pidx, s);
-    launch_reserve(ix->dev, m, splits, ix->ins, false, d_out + o, s);
+    assign_round(ix, m, d_vecs + (size_t)o * ix->dev.d, false, d_out + o, s);
   }
   HIP_TRY(hipGetLastError());
   return leave_data_stream(ix, s);
@@ -749,6 +790,7 @@ int rtams_copy_plain(void *d_dst, const void *d_src, size_t bytes, void *hip_str
 int rtams_set_param(rtams_index *ix, const char *key, int64_t value) {
   if (!ix || !key) return fail(RTAMS_EINVAL, "NULL argument");
   if (!strcmp(key, "profile_scan")) { ix->profile_scan = value; return RTAMS_OK; }
+  if (!strcmp(key, "use_mfma")) { ix->use_mfma = value; return RTAMS_OK; }
   if (!strcmp(key, "scan_max_items")) { ix->scan_max_items = value > 1024 ? value : 1024; return RTAMS_OK; }
   if (!strcmp(key, "scan_items_per_pair")) { ix->scan_items_per_pair = value > 0 ? value : 1; return RTAMS_OK; }
   return fail(RTAMS_EINVAL, "unknown parameter %s", key);

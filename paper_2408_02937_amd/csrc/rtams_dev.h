@@ -38,7 +38,7 @@ struct Ctrl {
   uint32_t exceed_lists;     // lists for which Exceed() holds
   unsigned long long ntotal; // vectors visible
   uint32_t max_len;          // longest visible list
-  uint32_t rearr_count;      // moves planned by the running rearrangement
+  uint32_t cnorm_max_bits;   // largest squared centroid norm, as float bits
   uint32_t pad3[26];
 };
 
@@ -65,6 +65,7 @@ struct Dev {
   Ctrl *ctrl;
   HostMirror *mirror;       // pinned host memory, device-visible
   float *centroids;         // [nlist][d]
+  float *cnorm;             // [nlist] squared norms of the centroids (fp32)
   uint32_t *reserved_len;   // [nlist] next free position (atomicAdd target)
   uint32_t *visible_len;    // [nlist] length searches may read
   uint32_t *online;         // [nlist] vectors since the last rearrangement

@@ -15,7 +15,8 @@ struct ScanQueues {
 
 // Per-request scratch of one stream resource (device pointers into its slice).
 struct SearchScratch {
-  double *scores;       // [max_batch][nlist] coarse scores
+  double *scores;       // [max_batch][nlist] coarse scores in the fixed double arithmetic
+  float *approx;        // [max_batch][nlist] approximate coarse scores from the matrix cores
   int32_t *probe_list;  // [max_batch][max_nprobe]
   uint32_t *probe_len;  // [max_batch][max_nprobe] list lengths as seen by this request
   uint32_t *probe_off;  // [max_batch][max_nprobe] start of the list inside the query's candidates
@@ -42,6 +43,8 @@ struct InsertScratch {
   double *pscore;    // [part_cap] best score per (vector, centroid split)
   int32_t *pidx;     // [part_cap]
   size_t part_cap;
+  float *approx;     // [approx_rows][nlist] approximate scores of one sub-round
+  int64_t approx_rows;
 };
 
 // Scratch of one rearrangement round (lives in the pool's control region).
@@ -73,6 +76,19 @@ void launch_coarse_scores(const Dev &D, int64_t n, const float *Y, double *score
 void launch_coarse_argmin(const Dev &D, int64_t n, const float *Y, int splits, double *pscore,
                           int32_t *pidx, hipStream_t s);
 
+// coarse_mfma.hip ------------------------------------------------------------
+// When the matrix-core filter runs in front of the exact coarse arithmetic: the
+// batch has to be a dense contraction large enough to repay the extra kernel and
+// the refinement (measured crossovers on MI355X, d = 128: about 2 M (query,
+// centroid) pairs for a search, 4 M pairs and 1024 rows for an assignment).
+inline bool mfma_pays_for_search(int64_t nq, int64_t nlist) { return nq >= 32 && nq * nlist >= (int64_t)2 << 20; }
+inline bool mfma_pays_for_assign(int64_t m, int64_t nlist) { return m >= 1024 && m * nlist >= (int64_t)4 << 20; }
+void launch_centroid_norms(const Dev &D, hipStream_t s);
+void launch_coarse_mfma(const Dev &D, int64_t n, const float *Y, float *approx,
+                        unsigned long long *cursor_to_clear, uint32_t *zero, int zero_n, hipStream_t s);
+void launch_assign_refine(const Dev &D, int64_t n, const float *Y, const float *approx, bool reserve,
+                          int32_t *assign, uint32_t *did, hipStream_t s);
+
 // insert.hip -----------------------------------------------------------------
 void launch_reserve(const Dev &D, int64_t n, int splits, const InsertScratch &S, bool reserve,
                     int32_t *assign_out, hipStream_t s);
@@ -83,7 +99,7 @@ void launch_publish(const Dev &D, hipStream_t s);
 
 // search.hip -----------------------------------------------------------------
 void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const SearchScratch &S,
-                       int32_t *probe_out, hipStream_t s);
+                       const float *Q, bool from_approx, int32_t *probe_out, hipStream_t s);
 void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int item_budget,
                   const SearchScratch &S, hipStream_t s);
 int scan_grid(int item_budget);

@@ -230,26 +230,95 @@ __device__ inline int next_pow2(int v) {
 // first; then the plan of the scan: the visible length of each probed list is
 // read ONCE here, so that scan and selection agree on it whatever an insertion
 // publishes meanwhile, and the query gets its slice of the candidate array.
+// FROM_APPROX: the request's coarse scores are fp32 approximations from the
+// matrix cores (coarse_mfma.hip).  The nprobe-th smallest of them plus the error
+// band bounds every centroid that can be among the exact nprobe best; those
+// candidates are scored in the fixed double arithmetic here and ordered
+// exactly.  If the band holds more candidates than LDS, the whole row is scored
+// exactly instead (what small requests, which skip the matrix cores, always do).
+template <bool FROM_APPROX>
 __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, int max_nprobe,
-                                                            SearchScratch S, int32_t *probe_out) {
+                                                            SearchScratch S, const float *__restrict__ Q,
+                                                            int32_t *probe_out) {
   __shared__ __attribute__((aligned(8))) uint32_t hist[256];  // also holds two 64-bit words for a moment
   __shared__ uint32_t bc[4];
   __shared__ uint32_t cnt[2];
   __shared__ uint64_t k1[kMaxNprobe];
   __shared__ uint64_t k2[kMaxNprobe];
   __shared__ uint32_t pay[kMaxNprobe];
+  __shared__ float s_red[kSelThreads / kWave];
   const int q = blockIdx.x;
   const int n = D.nlist;
-  const double *sc = S.scores + (size_t)q * n;
+  double *sc = S.scores + (size_t)q * n;
   const int metric = D.metric;
-  auto key1 = [&](int i) -> uint64_t {
-    double x = sc[i];
+  auto exact = [&](int c) -> double {  // the fixed arithmetic of coarse.hip
+    const float *y = Q + (size_t)q * D.d, *row = D.centroids + (size_t)c * D.d;
+    double acc = 0.0;
+    if (metric == 0) {
+      for (int j = 0; j < D.d; ++j) {
+        const double t = (double)y[j] - (double)row[j];
+        acc = __builtin_fma(t, t, acc);
+      }
+    } else {
+      for (int j = 0; j < D.d; ++j) acc = __builtin_fma((double)y[j], (double)row[j], acc);
+    }
+    return acc;
+  };
+  auto key_of_score = [&](double x) -> uint64_t {
     x = (metric == 0 ? x : -x) + 0.0;  // +0.0 folds -0 into +0
     return key_of_double(x);
   };
+  bool done = false;  // k1 / k2 / pay hold the nprobe winners, not yet sorted
+  if (FROM_APPROX && nprobe < n) {
+    const float *ap = S.approx + (size_t)q * n;
+    // |y|^2 for the error band
+    float yn = 0.f;
+    for (int j = threadIdx.x; j < D.d; j += kSelThreads) { const float v = Q[(size_t)q * D.d + j]; yn = fmaf(v, v, yn); }
+    for (int o = kWave / 2; o > 0; o >>= 1) yn += __shfl_xor(yn, o);
+    if ((threadIdx.x & (kWave - 1)) == 0) s_red[threadIdx.x / kWave] = yn;
+    __syncthreads();
+    yn = 0.f;
+    for (int w = 0; w < kSelThreads / kWave; ++w) yn += s_red[w];
+    const float cmax = __uint_as_float(D.ctrl->cnorm_max_bits);
+    const float band = 8.f * (float)(D.d + 4) * 5.9604645e-8f * (yn + cmax) * 1.01f;  // 2 E, see coarse_mfma.hip
+    const SelectResult ra = wg_radix_select<32>(
+        n, (uint32_t)nprobe, [&](int i, uint64_t &k) { k = key_of_float(ap[i] + 0.0f); return true; }, hist, bc);
+    const uint32_t tk = (uint32_t)ra.T;  // key of (an upper bound of) the nprobe-th smallest approximation
+    const float t = __uint_as_float((tk & 0x80000000u) ? (tk & 0x7fffffffu) : ~tk);
+    const float limit = t + band;
+    if (threadIdx.x == 0) cnt[0] = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < n; i += kSelThreads)
+      if (ap[i] <= limit) {
+        uint32_t p = atomicAdd(&cnt[0], 1u);
+        if (p < (uint32_t)kMaxNprobe) pay[p] = (uint32_t)i;
+      }
+    __syncthreads();
+    const int nc = (int)cnt[0];
+    if (nc >= nprobe && nc <= kMaxNprobe) {  // (fewer than nprobe: scores that do not compare, e.g. NaN)
+      for (int p = threadIdx.x; p < nc; p += kSelThreads) {
+        const int c = (int)pay[p];
+        k1[p] = key_of_score(exact(c));
+        k2[p] = (uint64_t)c;
+      }
+      const int m = next_pow2(nc);
+      for (int p = nc + threadIdx.x; p < m; p += kSelThreads) { k1[p] = ~0ull; k2[p] = ~0ull; pay[p] = 0; }
+      wg_bitonic_sort(m, k1, k2, pay);  // by (exact score, index): the first nprobe are the answer
+      done = true;
+    } else {
+      for (int i = threadIdx.x; i < n; i += kSelThreads) sc[i] = exact(i);  // the filter did not narrow it: whole row
+      __syncthreads();
+    }
+  }
+  auto key1 = [&](int i) -> uint64_t { return key_of_score(sc[i]); };
 
   SelectResult r1{~0ull, 0, 0}, r2{~0ull, 0, 0};
   const bool all = nprobe >= n;
+  if (!done && FROM_APPROX && all) {  // every list is probed: exact order of the whole row
+    for (int i = threadIdx.x; i < n; i += kSelThreads) sc[i] = exact(i);
+    __syncthreads();
+  }
+  if (!done) {
   if (!all) {
     r1 = wg_radix_select<64>(n, (uint32_t)nprobe, [&](int i, uint64_t &k) { k = key1(i); return true; },
                              hist, bc);
@@ -272,6 +341,12 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
   const int m = next_pow2(nprobe);
   for (int p = nprobe + threadIdx.x; p < m; p += kSelThreads) { k1[p] = ~0ull; k2[p] = ~0ull; pay[p] = 0; }
   wg_bitonic_sort(m, k1, k2, pay);
+  }  // !done
+  if (done) {  // the sort carried no payload: the list index is the second key
+    __syncthreads();
+    for (int p = threadIdx.x; p < nprobe; p += kSelThreads) pay[p] = (uint32_t)k2[p];
+    __syncthreads();
+  }
 
   // plan
   int32_t *pl = S.probe_list + (size_t)q * max_nprobe;
@@ -887,10 +962,14 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
 // ---------------------------------------------------------------- launchers
 
 void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const SearchScratch &S,
-                       int32_t *probe_out, hipStream_t s) {
+                       const float *Q, bool from_approx, int32_t *probe_out, hipStream_t s) {
   if (nq <= 0) return;
-  hipLaunchKernelGGL(k_probe_plan, dim3((unsigned)nq), dim3(kSelThreads), 0, s, D, nprobe, max_nprobe,
-                     S, probe_out);
+  if (from_approx)
+    hipLaunchKernelGGL(k_probe_plan<true>, dim3((unsigned)nq), dim3(kSelThreads), 0, s, D, nprobe, max_nprobe,
+                       S, Q, probe_out);
+  else
+    hipLaunchKernelGGL(k_probe_plan<false>, dim3((unsigned)nq), dim3(kSelThreads), 0, s, D, nprobe, max_nprobe,
+                       S, Q, probe_out);
 }
 
 void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int item_budget,

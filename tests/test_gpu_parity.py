@@ -32,6 +32,7 @@ def loaded(request):
     w = workloads()[request.param]
     print(f"[case] workload={w.name} seed={w.seed}", flush=True)
     g, o = make_pair(w)
+    g.set_param("use_mfma", 2)  # every batch of 32 rows or more goes through the matrix-core filter
     g.add(dev(w.base))
     o.add(w.base)
     bounds = [len(w.base)]
@@ -118,15 +119,64 @@ def test_many_lists_assignment_and_probes(metric):
                        np.zeros((0, d), np.float32), np.zeros((0, d), np.float32), 1, 0)
     g, o = make_pair(w, pool_blocks=20000, candidates_per_query=4096)
     y = rng.standard_normal((20000, d), dtype=np.float32)
-    assert np.array_equal(g.assign(dev(y)).cpu().numpy(), o.assign(y))
-    for nq in (3, 256):
-        assert np.array_equal(g.probe(dev(y[:nq]), 64).cpu().numpy(), o.probe(y[:nq], 64))
+    for filt in (2, 0):  # with and without the matrix-core filter in front of the exact arithmetic
+        g.set_param("use_mfma", filt)
+        assert np.array_equal(g.assign(dev(y)).cpu().numpy(), o.assign(y)), f"filter={filt}"
+        for nq in (3, 256):
+            assert np.array_equal(g.probe(dev(y[:nq]), 64).cpu().numpy(), o.probe(y[:nq], 64)), f"filter={filt}"
+    g.set_param("use_mfma", 1)
     g.add(dev(y)); o.add(y)
     g.validate()
     assert np.array_equal(g.list_sizes(), o.list_sizes())
     dd, ii = g.search(dev(y[:256]), 10, 64)
     rd, ri = o.search(y[:256], 10, 64)
     assert_topk_matches(metric, dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6)
+    g.close()
+
+
+@pytest.mark.parametrize("metric", ["l2", "ip"])
+def test_coarse_filter_cannot_separate_near_duplicate_centroids(metric):
+    """1500 of 2048 centroids differ only in the last bits: the fp32 filter of a
+    large batch cannot tell them apart (more candidates than its refinement
+    holds), so assignment and probe selection must come out of the exact
+    arithmetic alone, ties to the lowest index."""
+    rng = np.random.default_rng(77)
+    d, nlist = 32, 2048
+    C = rng.standard_normal((nlist, d), dtype=np.float32)
+    dup = rng.permutation(nlist)[:1500]
+    C[dup] = C[dup[0]] * (1 + rng.integers(-2, 3, (1500, d)).astype(np.float32) * np.float32(2.0 ** -23))
+    C[dup[100:140]] = C[dup[0]]  # and some exact copies
+    w = synth.Workload("near-dup-centroids", metric, d, nlist, 64, 16, 10, np.zeros((0, d), np.float32), C,
+                       np.zeros((0, d), np.float32), np.zeros((0, d), np.float32), 1, 0)
+    g, o = make_pair(w, pool_blocks=8000, candidates_per_query=8192)
+    g.set_param("use_mfma", 2)
+    y = np.concatenate([C[dup[0]] + 0.05 * rng.standard_normal((3000, d)),
+                        rng.standard_normal((3000, d))]).astype(np.float32)
+    assert np.array_equal(g.assign(dev(y)).cpu().numpy(), o.assign(y))
+    q = np.concatenate([y[:100], y[3000:3100]])
+    for nprobe in (1, 16, 64):
+        assert np.array_equal(g.probe(dev(q), nprobe).cpu().numpy(), o.probe(q, nprobe)), f"nprobe={nprobe}"
+    g.close()
+
+
+def test_coarse_filter_under_cancellation():
+    """Vectors and centroids far from the origin, close to each other: the
+    norm expansion the filter uses loses every significant digit of the
+    distances, its error band covers most centroids, and the decisions must still
+    be those of the exact arithmetic."""
+    rng = np.random.default_rng(78)
+    d, nlist = 64, 512
+    C = (1000.0 + rng.standard_normal((nlist, d))).astype(np.float32)
+    w = synth.Workload("far-from-origin", "l2", d, nlist, 64, 16, 10, np.zeros((0, d), np.float32), C,
+                       np.zeros((0, d), np.float32), np.zeros((0, d), np.float32), 1, 0)
+    g, o = make_pair(w, pool_blocks=4000, candidates_per_query=8192)
+    g.set_param("use_mfma", 2)
+    y = (1000.0 + rng.standard_normal((4096, d))).astype(np.float32)
+    assert np.array_equal(g.assign(dev(y)).cpu().numpy(), o.assign(y))
+    for nprobe in (1, 16, 64):
+        assert np.array_equal(g.probe(dev(y[:256]), nprobe).cpu().numpy(), o.probe(y[:256], nprobe))
+    g.add(dev(y)); o.add(y)
+    assert_lists_equal(g, o)
     g.close()
 
 
