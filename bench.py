@@ -46,6 +46,8 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true", help="only the timed steps (for profiler runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only the plain copy kernel on 1 GiB (yardstick for the traffic counters)")
+    ap.add_argument("--study", choices=["rearrange", "blocksize"],
+                    help="run one of the side studies instead of the benchmark (one JSON line each)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (see DESIGN.md, sharding)",
@@ -66,6 +68,11 @@ def main() -> int:
             rtams.copy_plain(dst, src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_per_launch": 1 << 30, "launches": 5}))
+        return 0
+    if args.study:
+        from paper_2408_02937_amd import studies
+        fn = studies.rearrangement_study if args.study == "rearrange" else studies.block_size_sweep
+        print(json.dumps(fn(scale=args.scale, iters=args.latency_iters)))
         return 0
     t_gen = time.perf_counter()
     w = synth.config(2, scale=args.scale)

@@ -1,0 +1,181 @@
+"""Two measured studies on one GPU, run through `bench.py --study ...`.
+
+* `rearrangement_study`: the analogue of the paper's rearrangement table
+  (Memory Rearrangement, "Experiments on memory rearrangement"): every online
+  vector goes to one list until it holds T_m' of them; search latency before,
+  the cost of rearranging that list, search latency after, and what searches
+  see while the rearrangement runs.
+* `block_size_sweep`: the analogue of the paper's block-size figure ("Effects
+  of memory block size"): latency, scan rate and pad memory as T_m grows.
+
+Both use configuration 2's synthetic data (byte-valued, d = 128, 1 M vectors,
+1024 lists) and go through the same C ABI as everything else.
+"""
+from __future__ import annotations
+
+import threading
+import time
+
+import numpy as np
+import torch
+
+from . import rtams, synth
+
+
+def _p(xs, q):
+    return float(np.percentile(np.asarray(xs, dtype=np.float64), q)) if len(xs) else float("nan")
+
+
+def _to_dev(a, dev):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+
+def _search_latencies(g, queries, bs, k, nprobe, iters, stream, dev):
+    od = torch.empty((bs, k), dtype=torch.float32, device=dev)
+    oi = torch.empty((bs, k), dtype=torch.int64, device=dev)
+    nb = max(len(queries) // bs, 1)
+    lat = []
+    for i in range(iters + 10):
+        q = queries[(i % nb) * bs:(i % nb) * bs + bs]
+        t0 = time.perf_counter()
+        g.search(q, k, nprobe, od, oi, stream=stream)
+        stream.synchronize()
+        if i >= 10:
+            lat.append((time.perf_counter() - t0) * 1e3)
+    return lat
+
+
+def rearrangement_study(scale: float = 1.0, thresholds=(10_000, 50_000, 100_000), iters: int = 200) -> dict:
+    dev = torch.device("cuda:0")
+    w = synth.config(2, scale=scale)
+    rng = np.random.Generator(np.random.PCG64([w.seed, 77]))
+    base, cents, inserts = (_to_dev(a, dev) for a in (w.base, w.centroids, w.inserts))
+    hot = 17 % w.nlist
+    rows = []
+    for thr in thresholds:
+        n_hot = thr + 1  # Exceed() is strict: T_m' vectors do not trigger, one more does
+        # vectors of the hot list: its centroid plus small integer noise (kept byte-valued)
+        hv = np.clip(np.rint(w.centroids[hot][None, :] + 2.0 * rng.standard_normal((n_hot, w.d))), 0, 255)
+        hv = _to_dev(hv.astype(np.float32), dev)
+        n_all = len(w.base) + n_hot + len(w.inserts)
+        spare = 2 * (n_hot // w.block_vecs + 2)
+        g = rtams.Index(w.d, w.nlist, w.metric, w.block_vecs,
+                        pool_blocks=n_all // w.block_vecs + 2 * w.nlist + spare + 64, n_resources=8,
+                        max_batch=256, max_k=128, max_nprobe=64, max_add_batch=65536, candidates_per_query=262144)
+        ds, ss, s2 = torch.cuda.Stream(dev), torch.cuda.Stream(dev), torch.cuda.Stream(dev)
+        g.set_centroids(cents, stream=ds)
+        g.add(base, stream=ds)
+        ds.synchronize()
+        assigned = g.assign(hv[:4096]).cpu().numpy()
+        on_hot = float((assigned == hot).mean())
+        # online phase: a batch into the hot list, a batch of ordinary traffic, in turn
+        ib = w.insert_batch
+        t0 = time.perf_counter()
+        j = 0
+        for o in range(0, n_hot, ib):
+            g.add(hv[o:o + ib], stream=ds)
+            g.add(inserts[(j % (len(inserts) // ib)) * ib:(j % (len(inserts) // ib)) * ib + ib], stream=ds)
+            j += 1
+        ds.synchronize()
+        t_online = time.perf_counter() - t0
+        blocks, runs_before, online = g.list_info(hot)
+        qh = hv[:2000]
+        before = {bs: _search_latencies(g, qh, bs, w.k, w.nprobe, iters, ss, dev) for bs in (1, 10)}
+
+        # searches that run while the list is rearranged
+        during, stop = [], threading.Event()
+
+        def searcher():
+            od = torch.empty((10, w.k), dtype=torch.float32, device=dev)
+            oi = torch.empty((10, w.k), dtype=torch.int64, device=dev)
+            i = 0
+            while not stop.is_set():
+                t = time.perf_counter()
+                g.search(qh[(i % 100) * 10:(i % 100) * 10 + 10], w.k, w.nprobe, od, oi, stream=s2)
+                s2.synchronize()
+                during.append((t, (time.perf_counter() - t) * 1e3))
+                i += 1
+
+        g.rearrange((hot + 1) % w.nlist, stream=ds)  # one-time set-up cost of the first call stays out of the timing
+        ds.synchronize()
+        th = threading.Thread(target=searcher)
+        th.start()
+        time.sleep(0.05)
+        t0 = time.perf_counter()
+        g.rearrange(hot, stream=ds)
+        ds.synchronize()
+        t1 = time.perf_counter()
+        time.sleep(0.02)
+        stop.set()
+        th.join()
+        cost_ms = (t1 - t0) * 1e3
+        overl = [l for (t, l) in during if t + l * 1e-3 >= t0 and t <= t1]
+        quiet = [l for (t, l) in during if t + l * 1e-3 < t0]
+        _, runs_after, _ = g.list_info(hot)
+        after = {bs: _search_latencies(g, qh, bs, w.k, w.nprobe, iters, ss, dev) for bs in (1, 10)}
+        g.validate()
+        assert g.poll_error() == 0
+        rows.append({
+            "threshold": thr, "hot_list": hot, "hot_list_len": int(g.list_sizes()[hot]), "blocks": int(blocks),
+            "share_of_online_vectors_on_hot_list": on_hot, "online_phase_s": t_online,
+            "runs_before": int(runs_before), "runs_after": int(runs_after),
+            "rearrange_cost_ms": cost_ms,
+            "latency_ms": {str(bs): {"before_p50": _p(before[bs], 50), "before_p99": _p(before[bs], 99),
+                                     "after_p50": _p(after[bs], 50), "after_p99": _p(after[bs], 99)}
+                           for bs in (1, 10)},
+            "searches_during_rearrangement": {"count": len(overl), "max_ms": max(overl) if overl else None,
+                                              "quiet_p50_ms": _p(quiet, 50), "quiet_max_ms": max(quiet) if quiet else None},
+        })
+        g.close()
+    return {"study": "rearrangement", "workload": w.name, "block_vecs": w.block_vecs, "rows": rows}
+
+
+def block_size_sweep(scale: float = 1.0, sizes=(64, 128, 256, 512, 1024, 2048), iters: int = 200) -> dict:
+    dev = torch.device("cuda:0")
+    w = synth.config(2, scale=scale)
+    base, cents, queries, inserts = (_to_dev(a, dev) for a in (w.base, w.centroids, w.queries, w.inserts))
+    rows = []
+    for T in sizes:
+        n_all = len(w.base) + 2 * len(w.inserts)
+        g = rtams.Index(w.d, w.nlist, w.metric, T, pool_blocks=n_all // T + 2 * w.nlist + 64, n_resources=8,
+                        max_batch=256, max_k=128, max_nprobe=64, max_add_batch=65536, candidates_per_query=65536)
+        ds, ss = torch.cuda.Stream(dev), torch.cuda.Stream(dev)
+        g.set_centroids(cents, stream=ds)
+        t0 = time.perf_counter()
+        g.add(base, stream=ds)
+        ds.synchronize()
+        bulk_s = time.perf_counter() - t0
+        st = g.pool_stats()
+        row = {"block_vecs": T, "blocks_in_use": st.blocks_in_use,
+               "pad_bytes": int((st.blocks_in_use * T - st.ntotal) * (w.d * 4 + 8)),
+               "pool_bytes": int(st.pool_bytes),
+               "bulk_load_vectors_per_s": len(w.base) / bulk_s, "search": {}}
+        sizes_now = g.list_sizes()
+        for bs in (1, 10, 32, 256):
+            g.scan_time(reset=True)
+            g.set_param("profile_scan", 1)
+            lat = _search_latencies(g, queries, bs, w.k, w.nprobe, iters, ss, dev)
+            g.set_param("profile_scan", 0)
+            ms, cnt = g.scan_time(reset=True)
+            nb = len(queries) // bs
+            ub = []
+            for i in range(min(32, nb)):
+                pl = g.probe(queries[i * bs:(i + 1) * bs], w.nprobe).cpu().numpy()
+                ub.append(int((sizes_now[np.unique(pl)] * w.d * 4).sum()))
+            scan_ms = ms / max(cnt, 1)
+            row["search"][str(bs)] = {"p50_ms": _p(lat, 50), "p99_ms": _p(lat, 99), "scan_ms": scan_ms,
+                                      "scan_GBps": float(np.mean(ub)) / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else None}
+        ib = w.insert_batch
+        lat = []
+        for i in range(iters + 10):
+            t0 = time.perf_counter()
+            g.add(inserts[(i % (len(inserts) // ib)) * ib:(i % (len(inserts) // ib)) * ib + ib], stream=ds)
+            ds.synchronize()
+            if i >= 10:
+                lat.append((time.perf_counter() - t0) * 1e3)
+        row["insert_batch64_p50_ms"] = _p(lat, 50)
+        row["insert_batch64_p99_ms"] = _p(lat, 99)
+        assert g.poll_error() == 0
+        rows.append(row)
+        g.close()
+    return {"study": "block_size", "workload": w.name, "rows": rows}

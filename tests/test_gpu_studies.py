@@ -1,0 +1,26 @@
+"""The two side studies run end to end on a shrunken workload (their numbers
+are not checked here, only that they complete, validate and report sane fields)."""
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+def test_rearrangement_study_small():
+    from paper_2408_02937_amd import studies
+    print("[case] rearrangement study, scale 0.03, thresholds 500 / 2000", flush=True)
+    out = studies.rearrangement_study(scale=0.03, thresholds=(500, 2000), iters=5)
+    for row in out["rows"]:
+        assert row["runs_after"] == 1 and row["runs_before"] >= 1
+        assert row["hot_list_len"] > row["threshold"]
+        assert row["share_of_online_vectors_on_hot_list"] == 1.0
+        assert row["rearrange_cost_ms"] > 0
+
+
+def test_block_size_sweep_small():
+    from paper_2408_02937_amd import studies
+    print("[case] block size sweep, scale 0.03, T_m 64 / 256", flush=True)
+    out = studies.block_size_sweep(scale=0.03, sizes=(64, 256), iters=5)
+    pads = [r["pad_bytes"] for r in out["rows"]]
+    assert pads[1] > pads[0] > 0
+    for r in out["rows"]:
+        assert r["search"]["256"]["scan_ms"] > 0
