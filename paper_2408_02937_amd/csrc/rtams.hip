@@ -190,7 +190,7 @@ struct rtams_index {
   int64_t ntotal_host = 0;   // vectors handed to add so far
   int64_t avail_lb = 0;      // lower bound of the blocks still available in the pool
   std::atomic<int64_t> scan_items_per_pair{8};   // work items the plan may cut per (query, list) pair
-  std::atomic<int64_t> scan_max_items{16384};    // ... and per request
+  std::atomic<int64_t> scan_max_items{32768};    // ... and per request
   std::atomic<int64_t> profile_scan{0};
   std::atomic<int64_t> use_mfma{1};  // matrix-core filter in front of the exact coarse arithmetic
   std::mutex prof_mutex;

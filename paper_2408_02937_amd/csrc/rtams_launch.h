@@ -27,7 +27,7 @@ struct SearchScratch {
   uint32_t *list_len;   // [nlist] length of each probed list as seen by the grouping step
   uint32_t *pair_slot;  // [max_batch][max_nprobe] rank of the pair among the pairs of its list
   uint32_t *grouped;    // [max_batch * max_nprobe] pairs (query << 10 | probe) grouped by list
-  uint4 *tile_desc;     // [item_cap] {list, first pair of the list, pairs of the list, segment} per item
+  uint4 *tile_desc;     // [item_cap] {list, first pair of the tile, pairs of the tile, segment} per item
   uint32_t item_cap;
   ScanQueues *queues;   // work items of this request, split into one queue per XCD
   float *cand;          // candidate scores
@@ -102,7 +102,6 @@ void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, con
                        const float *Q, bool from_approx, int32_t *probe_out, hipStream_t s);
 void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int item_budget,
                   const SearchScratch &S, hipStream_t s);
-int scan_grid(int item_budget);
 void launch_scan(const Dev &D, int64_t nq, int max_nprobe, const float *Q, int item_budget,
                  const SearchScratch &S, hipStream_t s);
 void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,

@@ -390,9 +390,10 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
 // prefix sums over the lists of the pair counts, the work-item counts and the
 // work, then the item descriptors, the split of the items over the 8 XCDs and
 // the grouped pair array.  A work item is (list, segment of seg_groups
-// 64-vector groups); the wavefront that takes it walks the segment once per
-// tile of kScanTileQueries queries probing the list (the second walk finds the
-// segment in cache).  Segments bound the work of one item, so that long lists
+// 64-vector groups, tile of up to kScanTileQueries of the queries probing the
+// list); one wavefront walks it.  The items of one segment follow each other, so
+// they run at the same time on the same CU or on its neighbours and the segment
+// comes from HBM once.  Segments bound the work of one item, so that long lists
 // spread over many wavefronts.  The segment length is the shortest power of two
 // for which the request has at most `item_budget` items and no XCD more than
 // `max_per_xcd` (the launch of the scan is sized from those two).
@@ -436,6 +437,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
   __shared__ unsigned long long s_c[kGroupThreads];
   __shared__ uint32_t s_items[kSegChoices];
   __shared__ uint32_t s_begin[9];
+  __shared__ uint32_t s_istart[kGroupThreads];
   const int tid = threadIdx.x;
   const int per = (D.nlist + kGroupThreads - 1) / kGroupThreads;
   const int l0 = tid * per, l1 = min(D.nlist, l0 + per);
@@ -457,10 +459,11 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
       S.list_len[l] = len;
       if (!c) continue;
       const uint32_t groups = (len + kWave - 1) / kWave;
+      const uint32_t tiles = (c + kScanTileQueries - 1) / kScanTileQueries;
 #pragma unroll
       for (int e = 0; e < kSegChoices; ++e) {
         const uint32_t sg = 2u << e;
-        cnt[e] += groups ? (groups + sg - 1) / sg : 1u;
+        cnt[e] += (groups ? (groups + sg - 1) / sg : 1u) * tiles;
       }
     }
     // totals per choice: shuffles inside the wavefront, one LDS atomic per wavefront
@@ -486,7 +489,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
       if (!c) continue;
       const uint32_t groups = (S.list_len[l] + kWave - 1) / kWave;
       np += c;
-      ni += groups ? (groups + seg - 1) / seg : 1u;
+      ni += (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
       wk += (unsigned long long)c * (groups ? groups : 1u);
     }
     uint32_t inp = np, ini = ni;
@@ -511,7 +514,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
           const unsigned long long cut = total_work * x / 8;
           if (ws <= cut && cut < ws + w) s_begin[x] = is;
         }
-        is += groups ? (groups + seg - 1) / seg : 1u;
+        is += (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
         ws += w;
       }
     }
@@ -526,19 +529,58 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
     if (!fits && choice + 1 < kSegChoices + 8) continue;  // coarser segments (bounded: lengths are 32 bit)
     if (tid < 9) Qs->begin[tid] = s_begin[tid];
     if (tid == 0) Qs->seg_groups = fits ? seg : 0u;  // 0: nothing is scanned (cannot happen with sane sizes)
+    s_istart[tid] = istart;  // where the items of this thread's lists start
     for (int l = l0; l < l1; ++l) {
       const uint32_t c = S.list_cnt[l];
       S.list_cnt[l] = pstart;  // from here on: where the list's pairs start
-      if (!c) continue;
-      const uint32_t groups = (S.list_len[l] + kWave - 1) / kWave;
-      const uint32_t segs = groups ? (groups + seg - 1) / seg : 1u;
-      if (fits)
-        for (uint32_t sg = 0; sg < segs; ++sg) S.tile_desc[istart++] = make_uint4((uint32_t)l, pstart, c, sg);
       pstart += c;
+    }
+    __syncthreads();  // list starts and item starts written above are read below by other threads
+    // Item descriptors: every thread writes an equal share of consecutive items, whatever
+    // lists they belong to (a hot list probed by many queries has hundreds of items, most
+    // lists a dozen).  Item j lies in the lists of the last thread whose items start at or
+    // before j; inside a list the tiles of one segment follow each other, and the tiles are
+    // of (almost) equal size.
+    if (fits) {
+      const uint32_t npairs_all = (uint32_t)(nq * nprobe);
+      const uint32_t share = (total_items + kGroupThreads - 1) / kGroupThreads;
+      uint32_t j = (uint32_t)tid * share;
+      const uint32_t j_end = min(total_items, j + share);
+      while (j < j_end) {
+        const uint32_t j_before = j;
+        int lo = 0, hi = kGroupThreads - 1;
+        while (lo < hi) {
+          const int mid = (lo + hi + 1) >> 1;
+          if (s_istart[mid] <= j) lo = mid; else hi = mid - 1;
+        }
+        uint32_t base = s_istart[lo];
+        const int le = min(D.nlist, lo * per + per);
+        for (int l = lo * per; l < le && j < j_end; ++l) {
+          const uint32_t start = S.list_cnt[l];
+          const uint32_t c = (l + 1 < D.nlist ? S.list_cnt[l + 1] : npairs_all) - start;
+          if (!c) continue;
+          const uint32_t groups = (S.list_len[l] + kWave - 1) / kWave;
+          const uint32_t segs = groups ? (groups + seg - 1) / seg : 1u;
+          const uint32_t tiles = (c + kScanTileQueries - 1) / kScanTileQueries;
+          const uint32_t n = segs * tiles;
+          if (j < base + n) {
+            const uint32_t r = j - base, stop = min(j_end, base + n);
+            uint32_t sg = r / tiles, t = r - sg * tiles;
+            const uint32_t small = c / tiles, extra = c - small * tiles;  // the first `extra` tiles hold one more
+            for (; j < stop; ++j) {
+              const uint32_t p_lo = t * small + min(t, extra);
+              S.tile_desc[j] = make_uint4((uint32_t)l, start + p_lo, small + (t < extra ? 1u : 0u), sg);
+              if (++t == tiles) { t = 0; ++sg; }
+            }
+          }
+          base += n;
+        }
+        // j is now past this thread's share, or at the first item of a list of a later thread
+        if (j == j_before) break;  // cannot happen: the item counts above are the ones the starts were made from
+      }
     }
     break;
   }
-  __syncthreads();  // list starts written above are read below by other threads of this workgroup
   // scatter of the pairs into their list's group, eight independent chains of loads per thread
   const int npairs = nq * nprobe;
   for (int base = tid; base < npairs; base += 8 * kGroupThreads) {
@@ -701,16 +743,14 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
   __builtin_amdgcn_wave_barrier();  // the LDS slice is rewritten by the next item
 }
 
-// One workgroup per work item (list, segment); the hardware's workgroup
-// dispatcher is the work queue (a new workgroup starts wherever room frees up).
-// The wavefronts of the workgroup take the query tiles of the list in turn and
-// walk the same segment at the same time, each with its own tile of queries in
-// its own slice of LDS: the segment comes from HBM once and the other
-// wavefronts find it in the CU's cache.  There is no barrier between them.
-// Hardware hands consecutive workgroup ids to the 8 XCDs in turn, so workgroup i
-// runs on XCD i % 8 and takes item i / 8 of that XCD's range of items (a
-// contiguous range of lists).  Workgroups past the end of their range, and
-// wavefronts without a tile, leave at once.
+// The hardware's workgroup dispatcher is the work queue (a new workgroup starts
+// wherever room frees up).  A workgroup is four wavefronts that take four
+// consecutive work items, one each, and work on their own: own slice of LDS, no
+// barrier.  Consecutive items are mostly the tiles of one segment, or the next
+// segment of the same list.  Hardware hands consecutive workgroup ids to the 8
+// XCDs in turn, so workgroup i runs on XCD i % 8 and takes items 4 (i / 8) ..
+// 4 (i / 8) + 3 of that XCD's range of items (a contiguous range of lists).
+// Wavefronts past the end of their range leave at once.
 constexpr uint32_t kXcds = 8;
 constexpr int kScanWaves = 4;
 
@@ -720,29 +760,27 @@ __global__ __launch_bounds__(kScanWaves * kWave) void k_scan(Dev D, int max_npro
   extern __shared__ float4 qs_all[];  // [wavefronts][kScanTileQueries][d / 4]
   const ScanQueues *Qs = S.queues;
   const uint32_t x = blockIdx.x % kXcds;
-  const uint32_t item = Qs->begin[x] + blockIdx.x / kXcds;
+  const uint32_t wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
+  const uint32_t item = Qs->begin[x] + (blockIdx.x / kXcds) * waves + wave;
   if (item >= Qs->begin[x + 1]) return;
   const uint32_t seg = Qs->seg_groups;
   if (seg == 0) return;
-  const uint32_t wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
   float4 *qs = qs_all + (size_t)wave * kScanTileQueries * D.d4;
   const uint4 desc = S.tile_desc[item];
   const int list = __builtin_amdgcn_readfirstlane((int)desc.x);
   const uint32_t first = (uint32_t)__builtin_amdgcn_readfirstlane((int)desc.y);
   const uint32_t pairs = (uint32_t)__builtin_amdgcn_readfirstlane((int)desc.z);
   const uint32_t g_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)desc.w) * seg;
-  for (uint32_t t = wave * kScanTileQueries; t < pairs; t += waves * kScanTileQueries) {
-    const uint32_t f = first + t;
-    switch (pairs - t) {
-      case 1: scan_item<METRIC, 1>(D, S, Q, max_nprobe, list, f, g_begin, seg, qs); break;
-      case 2: scan_item<METRIC, 2>(D, S, Q, max_nprobe, list, f, g_begin, seg, qs); break;
-      case 3: scan_item<METRIC, 3>(D, S, Q, max_nprobe, list, f, g_begin, seg, qs); break;
-      case 4: scan_item<METRIC, 4>(D, S, Q, max_nprobe, list, f, g_begin, seg, qs); break;
-      case 5: scan_item<METRIC, 5>(D, S, Q, max_nprobe, list, f, g_begin, seg, qs); break;
-      case 6: scan_item<METRIC, 6>(D, S, Q, max_nprobe, list, f, g_begin, seg, qs); break;
-      case 7: scan_item<METRIC, 7>(D, S, Q, max_nprobe, list, f, g_begin, seg, qs); break;
-      default: scan_item<METRIC, 8>(D, S, Q, max_nprobe, list, f, g_begin, seg, qs); break;
-    }
+  switch (pairs) {
+    case 0: break;
+    case 1: scan_item<METRIC, 1>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 2: scan_item<METRIC, 2>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 3: scan_item<METRIC, 3>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 4: scan_item<METRIC, 4>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 5: scan_item<METRIC, 5>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 6: scan_item<METRIC, 6>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 7: scan_item<METRIC, 7>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    default: scan_item<METRIC, 8>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
   }
 }
 
@@ -972,29 +1010,39 @@ void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, con
                        S, Q, probe_out);
 }
 
+// Wavefronts per workgroup of the scan: as many (4, 2, 1) as fit their query tiles into 64 KiB of LDS
+static int scan_waves(const Dev &D) {
+  const size_t per_wave = (size_t)kScanTileQueries * D.d * sizeof(float);
+  int waves = kScanWaves;
+  while (waves > 1 && per_wave * waves > 65536) waves /= 2;
+  return waves;
+}
+
+// workgroups of the scan launch for a budget of work items (one wavefront each):
+// room for an uneven split of the items over the XCDs
+static int scan_grid(const Dev &D, int item_budget) {
+  const int waves = scan_waves(D);
+  const int wgs = (item_budget + item_budget / 2 + waves - 1) / waves;
+  return (wgs + (int)kXcds - 1) / (int)kXcds * (int)kXcds;
+}
+
 void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int item_budget,
                   const SearchScratch &S, hipStream_t s) {
   if (nq <= 0) return;
   hipLaunchKernelGGL(k_group, dim3(1), dim3(kGroupThreads), 0, s, D, (int)nq, nprobe, max_nprobe,
-                     (uint32_t)item_budget, (uint32_t)scan_grid(item_budget) / kXcds, S);
+                     (uint32_t)item_budget, (uint32_t)(scan_grid(D, item_budget) / (int)kXcds * scan_waves(D)), S);
 }
-
-// workgroups of the scan launch for a budget of work items: room for an uneven
-// split of the items over the XCDs
-int scan_grid(int item_budget) { return (item_budget + item_budget / 2 + kXcds - 1) / kXcds * kXcds; }
 
 void launch_scan(const Dev &D, int64_t nq, int max_nprobe, const float *Q, int item_budget,
                  const SearchScratch &S, hipStream_t s) {
   if (nq <= 0) return;
-  dim3 grid((unsigned)scan_grid(item_budget));
-  // as many wavefronts per workgroup (8, 4, 2, 1) as fit their query tiles into 64 KiB of LDS
-  const size_t per_wave = (size_t)kScanTileQueries * D.d * sizeof(float);
-  int waves = kScanWaves;
-  while (waves > 1 && per_wave * waves > 65536) waves /= 2;
+  dim3 grid((unsigned)scan_grid(D, item_budget));
+  const int waves = scan_waves(D);
+  const size_t lds = (size_t)waves * kScanTileQueries * D.d * sizeof(float);
   if (D.metric == 0)
-    hipLaunchKernelGGL(k_scan<0>, grid, dim3(waves * kWave), waves * per_wave, s, D, max_nprobe, Q, S);
+    hipLaunchKernelGGL(k_scan<0>, grid, dim3(waves * kWave), lds, s, D, max_nprobe, Q, S);
   else
-    hipLaunchKernelGGL(k_scan<1>, grid, dim3(waves * kWave), waves * per_wave, s, D, max_nprobe, Q, S);
+    hipLaunchKernelGGL(k_scan<1>, grid, dim3(waves * kWave), lds, s, D, max_nprobe, Q, S);
 }
 
 void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
