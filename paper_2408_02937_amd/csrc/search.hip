@@ -442,6 +442,10 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
   const int per = (D.nlist + kGroupThreads - 1) / kGroupThreads;
   const int l0 = tid * per, l1 = min(D.nlist, l0 + per);
   ScanQueues *Qs = S.queues;
+  // Cost of a list for the split over the XCDs, per group of 64 vectors: reading it once from HBM
+  // (each XCD has its own link to memory) plus the arithmetic of every query that probes it.  On
+  // this chip one group's bytes cost about as much as the arithmetic of 12 queries (L2) or 24 (IP).
+  const uint32_t byte_weight = D.metric == 0 ? 12u : 24u;
 
   // The visible length of every probed list is read ONCE: an insertion may publish
   // while this kernel runs, and the passes below must agree on the segment counts.
@@ -490,7 +494,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
       const uint32_t groups = (S.list_len[l] + kWave - 1) / kWave;
       np += c;
       ni += (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
-      wk += (unsigned long long)c * (groups ? groups : 1u);
+      wk += (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
     }
     uint32_t inp = np, ini = ni;
     unsigned long long iwk = wk;
@@ -509,7 +513,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
         const uint32_t c = S.list_cnt[l];
         if (!c) continue;
         const uint32_t groups = (S.list_len[l] + kWave - 1) / kWave;
-        const unsigned long long w = (unsigned long long)c * (groups ? groups : 1u);
+        const unsigned long long w = (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
         for (uint32_t x = 1; x < 8; ++x) {
           const unsigned long long cut = total_work * x / 8;
           if (ws <= cut && cut < ws + w) s_begin[x] = is;
@@ -618,6 +622,8 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
 // score of its two vectors against each query of the item; a query chunk is one
 // broadcast LDS read shared by both vectors.  Scores go to each query's
 // candidate slice.  No workgroup barrier is involved anywhere.
+typedef __attribute__((address_space(1))) float GlobalFloat;
+
 template <int METRIC>
 __device__ __forceinline__ void accumulate(float &acc, const float4 &x, const float4 &y) {
   if (METRIC == 0) {
@@ -735,7 +741,10 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
       const uint32_t len = (uint32_t)__builtin_amdgcn_readlane((int)my_len, i);
       const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(uintptr_t)my_out, i);
       const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uintptr_t)my_out >> 32), i);
-      float *out = reinterpret_cast<float *>((uint64_t)lo | ((uint64_t)hi << 32));
+      // A pointer rebuilt from integers has no address space: say "global", or the stores become
+      // FLAT operations, and while one of those is pending every wait of the load pipeline above
+      // has to be for ALL outstanding memory operations.
+      GlobalFloat *out = (GlobalFloat *)((uint64_t)lo | ((uint64_t)hi << 32));
       if (v0 < len) out[v0] = acc0[i];
       if (two && v1 < len) out[v1] = acc1[i];
     }
