@@ -84,7 +84,9 @@ typedef struct rtams_stats {
 size_t rtams_pool_bytes_for(const rtams_config *cfg, int64_t blocks);
 
 /* Bytes of scratch one stream resource needs so that a search of max_batch
- * queries may score `candidates_per_query` list entries per query. */
+ * queries may score `candidates_per_query` list entries per query (8 bytes
+ * per entry: key and position of those that survive the pruning bound, with
+ * room for all). */
 size_t rtams_scratch_bytes_for(const rtams_config *cfg, int64_t candidates_per_query);
 
 /* Creates the index over caller-owned device memory (both regions 256-byte

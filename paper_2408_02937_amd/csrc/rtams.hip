@@ -127,7 +127,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
 }
 
 struct ScratchLayout {
-  size_t scores, approx, probe_list, probe_len, probe_off, qbase, qtotal, cursor, cand, fixed;
+  size_t scores, approx, probe_list, probe_len, probe_off, qbase, qtotal, bound, rec_cnt, cursor, cand, fixed;
   size_t list_cnt, list_len, pair_slot, grouped, tile_desc, queues, item_cap;
 };
 
@@ -142,6 +142,8 @@ void lay_out_scratch(const rtams_config *c, ScratchLayout *S) {
   S->probe_off = take(mb * mp * 4);
   S->qbase = take(mb * 8);
   S->qtotal = take(mb * 4);
+  S->bound = take(mb * 4);
+  S->rec_cnt = take(mb * 4);
   S->cursor = take(8);
   // list_cnt and the queue heads are cleared together at the start of every request
   S->list_cnt = take((size_t)c->nlist * 4);
@@ -160,7 +162,7 @@ enum { RES_FREE = 0, RES_BUSY = 1, RES_PENDING = 2 };
 struct Resource {
   std::atomic<int> state{RES_FREE};
   hipEvent_t done = nullptr;
-  hipEvent_t t0 = nullptr, t1 = nullptr;  // around the scan kernel when profiling is on
+  hipEvent_t t0 = nullptr, t1 = nullptr;  // around the grouped scan when profiling is on
   bool timed = false;
   SearchScratch s{};
 };
@@ -314,7 +316,8 @@ size_t rtams_scratch_bytes_for(const rtams_config *cfg, int64_t candidates_per_q
   if (!config_ok(cfg, false) || candidates_per_query < 0) return 0;
   ScratchLayout S;
   lay_out_scratch(cfg, &S);
-  return up(S.fixed + (size_t)cfg->max_batch * (size_t)candidates_per_query * 4, kAlign);
+  // key and position of a surviving candidate: 8 bytes each, room for all of them
+  return up(S.fixed + 2 * up((size_t)cfg->max_batch * (size_t)candidates_per_query * 4, kAlign), kAlign);
 }
 
 int rtams_create(const rtams_config *cfg, rtams_index **out) {
@@ -412,6 +415,8 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
     S.probe_off = reinterpret_cast<uint32_t *>(p + SL.probe_off);
     S.qbase = reinterpret_cast<unsigned long long *>(p + SL.qbase);
     S.qtotal = reinterpret_cast<uint32_t *>(p + SL.qtotal);
+    S.bound = reinterpret_cast<uint32_t *>(p + SL.bound);
+    S.rec_cnt = reinterpret_cast<uint32_t *>(p + SL.rec_cnt);
     S.cursor = reinterpret_cast<unsigned long long *>(p + SL.cursor);
     S.list_cnt = reinterpret_cast<uint32_t *>(p + SL.list_cnt);
     S.list_len = reinterpret_cast<uint32_t *>(p + SL.list_len);
@@ -420,8 +425,10 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
     S.tile_desc = reinterpret_cast<uint4 *>(p + SL.tile_desc);
     S.item_cap = (uint32_t)SL.item_cap;
     S.queues = reinterpret_cast<ScanQueues *>(p + SL.queues);
-    S.cand = reinterpret_cast<float *>(p + SL.cand);
-    S.cand_cap = (slice - SL.fixed) / 4;
+    // the rest of the slice: two arrays of equal length
+    S.cand_cap = (slice - SL.fixed) / (2 * kAlign) * (kAlign / 4);
+    S.rec_key = reinterpret_cast<uint32_t *>(p + SL.cand);
+    S.rec_pos = S.rec_key + S.cand_cap;
     if (hipEventCreateWithFlags(&ix->res[r].done, hipEventDisableTiming) != hipSuccess ||
         hipEventCreate(&ix->res[r].t0) != hipSuccess || hipEventCreate(&ix->res[r].t1) != hipSuccess)
       return bail(fail(RTAMS_EHIP, "hipEventCreate failed"));
@@ -528,14 +535,14 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   // a rearrangement is switching block tables: start behind its last switch
   if (ix->fence_cur) (void)hipStreamWaitEvent(s, ix->fence_cur, 0);
   coarse_and_plan(ix, nq, d_queries, nprobe, S, nullptr, s);
-  // The scan is cut into work items of bounded size, one single-wavefront workgroup
-  // each; the budget of items grows with the request so that a small batch still
+  // The grouped scan is cut into work items of bounded size, one wavefront each;
+  // the budget of items grows with the request so that a small batch still
   // spreads over the chip and a large one is not drowned in per-item overhead.
   int64_t budget = nq * nprobe * ix->scan_items_per_pair.load(std::memory_order_relaxed);
   const int64_t cap = ix->scan_max_items.load(std::memory_order_relaxed);
   if (budget > cap) budget = cap;
   if (budget < 1024) budget = 1024;
-  launch_group(D, nq, nprobe, ix->cfg.max_nprobe, (int)budget, S, s);
+  launch_group(D, nq, nprobe, ix->cfg.max_nprobe, k, d_queries, (int)budget, S, s);
   const bool timed = ix->profile_scan.load(std::memory_order_relaxed) != 0;
   if (timed) (void)hipEventRecord(ix->res[r].t0, s);
   launch_scan(D, nq, ix->cfg.max_nprobe, d_queries, (int)budget, S, s);

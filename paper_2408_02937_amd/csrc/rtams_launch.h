@@ -13,6 +13,10 @@ struct ScanQueues {
   uint32_t pad[22];
 };
 
+// The scan keeps, for every query, only the candidates that are not worse than
+// the query's BOUND (the k-th best score of a sample of its candidates, set
+// before the scan starts): they are appended to the query's survivor records.
+
 // Per-request scratch of one stream resource (device pointers into its slice).
 struct SearchScratch {
   double *scores;       // [max_batch][nlist] coarse scores in the fixed double arithmetic
@@ -20,9 +24,11 @@ struct SearchScratch {
   int32_t *probe_list;  // [max_batch][max_nprobe]
   uint32_t *probe_len;  // [max_batch][max_nprobe] list lengths as seen by this request
   uint32_t *probe_off;  // [max_batch][max_nprobe] start of the list inside the query's candidates
-  unsigned long long *qbase;  // [max_batch] start of the query's candidates in cand
+  unsigned long long *qbase;  // [max_batch] start of the query's slice of rec_key / rec_pos
   uint32_t *qtotal;     // [max_batch] candidates of the query
-  unsigned long long *cursor; // bump pointer into cand
+  uint32_t *bound;      // [max_batch] key of the score the scan compares with
+  uint32_t *rec_cnt;    // [max_batch] survivors recorded so far
+  unsigned long long *cursor; // bump pointer into the survivor records
   uint32_t *list_cnt;   // [nlist] queries probing each list, then start of the list's pair group
   uint32_t *list_len;   // [nlist] length of each probed list as seen by the grouping step
   uint32_t *pair_slot;  // [max_batch][max_nprobe] rank of the pair among the pairs of its list
@@ -30,8 +36,9 @@ struct SearchScratch {
   uint4 *tile_desc;     // [item_cap] {list, first pair of the tile, pairs of the tile, segment} per item
   uint32_t item_cap;
   ScanQueues *queues;   // work items of this request, split into one queue per XCD
-  float *cand;          // candidate scores
-  unsigned long long cand_cap;
+  uint32_t *rec_key;    // survivors: key of the score (smaller is better) ...
+  uint32_t *rec_pos;    // ... and position among the query's candidates
+  unsigned long long cand_cap;  // entries of each of the two arrays
 };
 
 constexpr int kScanTileQueries = 8;  // queries that share one pass over a list
@@ -100,8 +107,10 @@ void launch_publish(const Dev &D, hipStream_t s);
 // search.hip -----------------------------------------------------------------
 void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const SearchScratch &S,
                        const float *Q, bool from_approx, int32_t *probe_out, hipStream_t s);
-void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int item_budget,
-                  const SearchScratch &S, hipStream_t s);
+// One launch does two things side by side: one workgroup groups the pairs by list
+// and cuts the scan into work items; one workgroup per query sets the query's bound.
+void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int k, const float *Q,
+                  int item_budget, const SearchScratch &S, hipStream_t s);
 void launch_scan(const Dev &D, int64_t nq, int max_nprobe, const float *Q, int item_budget,
                  const SearchScratch &S, hipStream_t s);
 void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,

@@ -384,6 +384,106 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
   }
 }
 
+// ------------------------------------------------------------- pruning bound
+// Score of one vector against one query, 4 dimensions at a time, one FMA chain
+// in the order of the dimensions.
+typedef __attribute__((address_space(1))) float GlobalFloat;
+typedef __attribute__((address_space(1))) uint32_t GlobalU32;
+
+template <int METRIC>
+__device__ __forceinline__ void accumulate(float &acc, const float4 &x, const float4 &y) {
+  if (METRIC == 0) {
+    const float t0 = x.x - y.x, t1 = x.y - y.y, t2 = x.z - y.z, t3 = x.w - y.w;
+    acc = fmaf(t0, t0, acc); acc = fmaf(t1, t1, acc); acc = fmaf(t2, t2, acc); acc = fmaf(t3, t3, acc);
+  } else {
+    acc = fmaf(x.x, y.x, acc); acc = fmaf(x.y, y.y, acc); acc = fmaf(x.z, y.z, acc); acc = fmaf(x.w, y.w, acc);
+  }
+}
+
+constexpr int kGroupThreads = 1024;
+constexpr int kSampleMax = 4096;  // candidates the bound of a query is taken from, at most
+
+// The scan writes nothing for a candidate that cannot be among the k best of
+// its query: before it starts, every query gets a BOUND, the k-th best score
+// of a sample of its candidates (the first few groups of its nearest probed
+// lists, where most of its neighbours are).  The k-th best of any k or more
+// candidates cannot be better than the final k-th best, so keeping what is not
+// worse than the bound loses nothing.  One workgroup per query: a wavefront per
+// group of 64 vectors, lane = vector, scores to LDS, radix selection there.
+// These workgroups run beside the one that groups the pairs (same launch): both
+// need only the plan, and the scan needs both.
+template <int METRIC>
+__device__ void sample_scores(const Dev &D, int nprobe, int max_nprobe, int q, uint32_t want_groups,
+                              const float *__restrict__ Q, const SearchScratch &S, const float4 *qv,
+                              uint32_t *skey) {
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int d4 = D.d4;
+  const uint32_t gpb = (uint32_t)D.groups_per_block;
+  const size_t group_stride = (size_t)d4 * kWave;
+  // the sample is the first want_groups groups of the probed lists taken in order, nearest first
+  uint32_t g_first = 0;  // groups of the lists before list p
+  for (int p = 0; p < nprobe && g_first < want_groups; ++p) {  // uniform over the workgroup
+    const size_t o = (size_t)q * max_nprobe + p;
+    const int list = S.probe_list[o];
+    const uint32_t len = S.probe_len[o];
+    uint32_t groups = (len + kWave - 1) / kWave;
+    const uint32_t have = D.nblk[list] * gpb;  // never index the block table past the chain
+    if (groups > have) groups = have;
+    if (groups > want_groups - g_first) groups = want_groups - g_first;
+    for (uint32_t g = (uint32_t)wave; g < groups; g += kGroupThreads / kWave) {
+      const uint32_t b = (uint32_t)*table_entry(D, list, g / gpb);
+      const float4 *__restrict__ x = block_vecs(D, b) + (size_t)(g % gpb) * group_stride + lane;
+      float acc = 0.f;
+      int c = 0;
+      for (; c + 8 <= d4; c += 8) {  // eight loads of 1 KiB in flight per wavefront
+        float4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = x[(size_t)(c + u) * kWave];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) accumulate<METRIC>(acc, v[u], qv[c + u]);
+      }
+      for (; c < d4; ++c) accumulate<METRIC>(acc, x[(size_t)c * kWave], qv[c]);
+      const uint32_t v = g * kWave + lane;
+      skey[(size_t)(g_first + g) * kWave + lane] =
+          v < len ? key_of_float((METRIC == 0 ? acc : -acc) + 0.0f) : 0xFFFFFFFFu;
+    }
+    g_first += groups;
+  }
+  // groups the lists did not have stay at the worst key (set by the caller)
+}
+
+__device__ void sample_bound(const Dev &D, int nprobe, int max_nprobe, int k, const float *__restrict__ Q,
+                             const SearchScratch &S) {
+  __shared__ float4 qv[512];  // the query (d <= 2048)
+  __shared__ uint32_t skey[kSampleMax];
+  __shared__ __attribute__((aligned(8))) uint32_t hist[256];
+  __shared__ uint32_t bc[4];
+  const int q = (int)blockIdx.x - 1;
+  const int tid = threadIdx.x;
+  // sample size: 4 k, at least 512, at most kSampleMax, in whole groups
+  uint32_t want = (uint32_t)k * 4u;
+  want = want < 512u ? 512u : (want > (uint32_t)kSampleMax ? (uint32_t)kSampleMax : want);
+  const uint32_t want_groups = (want + kWave - 1) / kWave;
+  for (int c = tid; c < D.d4; c += kGroupThreads) qv[c] = reinterpret_cast<const float4 *>(Q + (size_t)q * D.d)[c];
+  for (int i = tid; i < (int)(want_groups * kWave); i += kGroupThreads) skey[i] = 0xFFFFFFFFu;
+  __syncthreads();
+  if (D.metric == 0) sample_scores<0>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
+  else sample_scores<1>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
+  __syncthreads();
+  // k-th smallest key of the sample; with fewer than k candidates in it, it is the worst key
+  // and everything is kept
+  uint32_t bound = 0xFFFFFFFFu;
+  if ((uint32_t)k <= want_groups * kWave) {
+    const SelectResult r = wg_radix_select<32>(
+        (int)(want_groups * kWave), (uint32_t)k, [&](int i, uint64_t &kv) { kv = skey[i]; return true; }, hist, bc);
+    bound = (uint32_t)r.T;  // the k-th smallest key, or an upper bound of it that admits the same candidates
+  }
+  if (tid == 0) {
+    S.bound[q] = bound;
+    S.rec_cnt[q] = 0u;
+  }
+}
+
 // ------------------------------------------------------------ pair grouping
 // The (query, probed list) pairs of a request are grouped by list, so that the
 // scan reads a list once for up to kScanTileQueries queries.  One workgroup:
@@ -397,7 +497,6 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
 // spread over many wavefronts.  The segment length is the shortest power of two
 // for which the request has at most `item_budget` items and no XCD more than
 // `max_per_xcd` (the launch of the scan is sized from those two).
-constexpr int kGroupThreads = 1024;
 constexpr int kSegChoices = 8;  // segment lengths 2, 4, ..., 256 groups
 
 __device__ inline void wg_scan3(uint32_t &a, uint32_t &b, unsigned long long &c, uint32_t *sa,
@@ -429,9 +528,14 @@ __device__ inline void wg_scan3(uint32_t &a, uint32_t &b, unsigned long long &c,
   __syncthreads();
 }
 
-__global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int nprobe, int max_nprobe,
+__global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int nprobe, int max_nprobe, int k,
+                                                         const float *__restrict__ Q,
                                                          uint32_t item_budget, uint32_t max_per_xcd,
                                                          SearchScratch S) {
+  if (blockIdx.x > 0) {  // uniform over the workgroup: this one sets the bound of query blockIdx.x - 1
+    sample_bound(D, nprobe, max_nprobe, k, Q, S);
+    return;
+  }
   __shared__ uint32_t s_a[kGroupThreads];
   __shared__ uint32_t s_b[kGroupThreads];
   __shared__ unsigned long long s_c[kGroupThreads];
@@ -441,6 +545,8 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
   const int tid = threadIdx.x;
   const int per = (D.nlist + kGroupThreads - 1) / kGroupThreads;
   const int l0 = tid * per, l1 = min(D.nlist, l0 + per);
+  uint32_t *list_cnt = S.list_cnt, *list_len = S.list_len, *grouped = S.grouped;
+  uint4 *tile_desc = S.tile_desc;
   ScanQueues *Qs = S.queues;
   // Cost of a list for the split over the XCDs, per group of 64 vectors: reading it once from HBM
   // (each XCD has its own link to memory) plus the arithmetic of every query that probes it.  On
@@ -457,10 +563,10 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
 #pragma unroll
     for (int e = 0; e < kSegChoices; ++e) cnt[e] = 0;
     for (int l = l0; l < l1; ++l) {
-      const uint32_t c = S.list_cnt[l];
+      const uint32_t c = list_cnt[l];
       const uint32_t len =
           c ? __hip_atomic_load(&D.visible_len[l], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
-      S.list_len[l] = len;
+      list_len[l] = len;
       if (!c) continue;
       const uint32_t groups = (len + kWave - 1) / kWave;
       const uint32_t tiles = (c + kScanTileQueries - 1) / kScanTileQueries;
@@ -489,9 +595,9 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
     uint32_t np = 0, ni = 0;
     unsigned long long wk = 0;
     for (int l = l0; l < l1; ++l) {
-      const uint32_t c = S.list_cnt[l];
+      const uint32_t c = list_cnt[l];
       if (!c) continue;
-      const uint32_t groups = (S.list_len[l] + kWave - 1) / kWave;
+      const uint32_t groups = (list_len[l] + kWave - 1) / kWave;
       np += c;
       ni += (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
       wk += (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
@@ -499,6 +605,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
     uint32_t inp = np, ini = ni;
     unsigned long long iwk = wk;
     wg_scan3(inp, ini, iwk, s_a, s_b, s_c);
+    const uint32_t total_pairs = s_a[kGroupThreads - 1];
     const uint32_t total_items = s_b[kGroupThreads - 1];
     const unsigned long long total_work = s_c[kGroupThreads - 1];
     uint32_t pstart = inp - np, istart = ini - ni;
@@ -510,9 +617,9 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
       uint32_t is = istart;
       unsigned long long ws = wstart;
       for (int l = l0; l < l1; ++l) {
-        const uint32_t c = S.list_cnt[l];
+        const uint32_t c = list_cnt[l];
         if (!c) continue;
-        const uint32_t groups = (S.list_len[l] + kWave - 1) / kWave;
+        const uint32_t groups = (list_len[l] + kWave - 1) / kWave;
         const unsigned long long w = (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
         for (uint32_t x = 1; x < 8; ++x) {
           const unsigned long long cut = total_work * x / 8;
@@ -535,8 +642,8 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
     if (tid == 0) Qs->seg_groups = fits ? seg : 0u;  // 0: nothing is scanned (cannot happen with sane sizes)
     s_istart[tid] = istart;  // where the items of this thread's lists start
     for (int l = l0; l < l1; ++l) {
-      const uint32_t c = S.list_cnt[l];
-      S.list_cnt[l] = pstart;  // from here on: where the list's pairs start
+      const uint32_t c = list_cnt[l];
+      list_cnt[l] = pstart;  // from here on: where the list's pairs start
       pstart += c;
     }
     __syncthreads();  // list starts and item starts written above are read below by other threads
@@ -546,7 +653,6 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
     // before j; inside a list the tiles of one segment follow each other, and the tiles are
     // of (almost) equal size.
     if (fits) {
-      const uint32_t npairs_all = (uint32_t)(nq * nprobe);
       const uint32_t share = (total_items + kGroupThreads - 1) / kGroupThreads;
       uint32_t j = (uint32_t)tid * share;
       const uint32_t j_end = min(total_items, j + share);
@@ -560,10 +666,10 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
         uint32_t base = s_istart[lo];
         const int le = min(D.nlist, lo * per + per);
         for (int l = lo * per; l < le && j < j_end; ++l) {
-          const uint32_t start = S.list_cnt[l];
-          const uint32_t c = (l + 1 < D.nlist ? S.list_cnt[l + 1] : npairs_all) - start;
+          const uint32_t start = list_cnt[l];
+          const uint32_t c = (l + 1 < D.nlist ? list_cnt[l + 1] : total_pairs) - start;
           if (!c) continue;
-          const uint32_t groups = (S.list_len[l] + kWave - 1) / kWave;
+          const uint32_t groups = (list_len[l] + kWave - 1) / kWave;
           const uint32_t segs = groups ? (groups + seg - 1) / seg : 1u;
           const uint32_t tiles = (c + kScanTileQueries - 1) / kScanTileQueries;
           const uint32_t n = segs * tiles;
@@ -573,7 +679,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
             const uint32_t small = c / tiles, extra = c - small * tiles;  // the first `extra` tiles hold one more
             for (; j < stop; ++j) {
               const uint32_t p_lo = t * small + min(t, extra);
-              S.tile_desc[j] = make_uint4((uint32_t)l, start + p_lo, small + (t < extra ? 1u : 0u), sg);
+              tile_desc[j] = make_uint4((uint32_t)l, start + p_lo, small + (t < extra ? 1u : 0u), sg);
               if (++t == tiles) { t = 0; ++sg; }
             }
           }
@@ -605,10 +711,10 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
     }
     uint32_t start[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) start[u] = l[u] >= 0 ? S.list_cnt[l[u]] : 0u;
+    for (int u = 0; u < 8; ++u) start[u] = l[u] >= 0 ? list_cnt[l[u]] : 0u;
 #pragma unroll
     for (int u = 0; u < 8; ++u)
-      if (l[u] >= 0) S.grouped[start[u] + slot[u]] = pk[u];
+      if (l[u] >= 0) grouped[start[u] + slot[u]] = pk[u];
   }
 }
 
@@ -622,17 +728,6 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
 // score of its two vectors against each query of the item; a query chunk is one
 // broadcast LDS read shared by both vectors.  Scores go to each query's
 // candidate slice.  No workgroup barrier is involved anywhere.
-typedef __attribute__((address_space(1))) float GlobalFloat;
-
-template <int METRIC>
-__device__ __forceinline__ void accumulate(float &acc, const float4 &x, const float4 &y) {
-  if (METRIC == 0) {
-    const float t0 = x.x - y.x, t1 = x.y - y.y, t2 = x.z - y.z, t3 = x.w - y.w;
-    acc = fmaf(t0, t0, acc); acc = fmaf(t1, t1, acc); acc = fmaf(t2, t2, acc); acc = fmaf(t3, t3, acc);
-  } else {
-    acc = fmaf(x.x, y.x, acc); acc = fmaf(x.y, y.y, acc); acc = fmaf(x.z, y.z, acc); acc = fmaf(x.w, y.w, acc);
-  }
-}
 
 // Chunks of 4 dimensions per register set of the software pipeline.  Deeper sets for
 // items with few queries were measured: they cost a wavefront of occupancy and gain nothing.
@@ -646,15 +741,18 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
   constexpr int kPrefetch = prefetch_chunks(NQ);
   const int d4 = D.d4;
   const int lane = threadIdx.x & (kWave - 1);
-  // lane i < NQ looks after query i of the item: where it reads and writes, how far its list goes
-  uint32_t my_q = 0, my_len = 0;
-  float *my_out = nullptr;
+  // lane i < NQ looks after query i of the item: how far its list goes, its bound, where its
+  // survivor records go
+  uint32_t my_q = 0, my_len = 0, my_off = 0, my_bound = 0;
+  uint64_t my_base = 0;  // start of the query's slice of rec_key / rec_pos
   if (lane < NQ) {
     const uint32_t pk = S.grouped[first + lane];
     my_q = pk >> 10;
     const size_t o = (size_t)my_q * max_nprobe + (pk & 1023u);
     my_len = S.probe_len[o];
-    my_out = S.cand + S.qbase[my_q] + S.probe_off[o];
+    my_off = S.probe_off[o];
+    my_base = S.qbase[my_q];
+    my_bound = S.bound[my_q];
   }
   uint32_t maxlen = 0;
 #pragma unroll
@@ -735,18 +833,54 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
       }
     }
     const uint32_t v0 = g0 * kWave + lane, v1 = v0 + kWave;
+    // Only what is not worse than the query's bound is kept: appended to the query's survivor
+    // records, one atomic per query with survivors.  (readlane yields a signed int: go through
+    // uint32_t so the low word is not sign-extended.  A pointer rebuilt from integers has no address
+    // space: say "global", or the stores become FLAT operations, and while one of those is pending
+    // every wait of the load pipeline above has to be for ALL outstanding memory operations.)
+    auto lane_u32 = [](uint32_t v, int i) { return (uint32_t)__builtin_amdgcn_readlane((int)v, i); };
+    auto lane_u64 = [&](uint64_t v, int i) {
+      return (uint64_t)lane_u32((uint32_t)v, i) | ((uint64_t)lane_u32((uint32_t)(v >> 32), i) << 32);
+    };
+    {
+      // survivors of each query in this pair of groups: masks, counts (lane i keeps query i's count)
+      unsigned long long m0[NQ], m1[NQ];
+      uint32_t n_mine = 0;
+      bool any = false;
 #pragma unroll
-    for (int i = 0; i < NQ; ++i) {
-      // readlane yields a signed int: go through uint32_t so the low word is not sign-extended
-      const uint32_t len = (uint32_t)__builtin_amdgcn_readlane((int)my_len, i);
-      const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(uintptr_t)my_out, i);
-      const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uintptr_t)my_out >> 32), i);
-      // A pointer rebuilt from integers has no address space: say "global", or the stores become
-      // FLAT operations, and while one of those is pending every wait of the load pipeline above
-      // has to be for ALL outstanding memory operations.
-      GlobalFloat *out = (GlobalFloat *)((uint64_t)lo | ((uint64_t)hi << 32));
-      if (v0 < len) out[v0] = acc0[i];
-      if (two && v1 < len) out[v1] = acc1[i];
+      for (int i = 0; i < NQ; ++i) {
+        const uint32_t len = lane_u32(my_len, i), bound = lane_u32(my_bound, i);
+        const uint32_t key0 = key_of_float((METRIC == 0 ? acc0[i] : -acc0[i]) + 0.0f);
+        const uint32_t key1 = key_of_float((METRIC == 0 ? acc1[i] : -acc1[i]) + 0.0f);
+        m0[i] = __ballot(v0 < len && key0 <= bound);
+        m1[i] = __ballot(two && v1 < len && key1 <= bound);
+        const uint32_t c = (uint32_t)__popcll(m0[i]) + (uint32_t)__popcll(m1[i]);
+        n_mine = lane == i ? c : n_mine;
+        any = any || c != 0;
+      }
+      if (any) {  // uniform.  One atomic per query with survivors, all of them in one instruction
+        uint32_t base_mine = 0;
+        if (lane < NQ && n_mine) base_mine = atomicAdd(&S.rec_cnt[my_q], n_mine);
+        const unsigned long long below = (1ull << lane) - 1ull;
+#pragma unroll
+        for (int i = 0; i < NQ; ++i) {
+          if ((m0[i] | m1[i]) == 0) continue;  // uniform
+          const uint64_t at = lane_u64(my_base, i) + lane_u32(base_mine, i);
+          const uint32_t off = lane_u32(my_off, i);
+          GlobalU32 *rk = (GlobalU32 *)((uint64_t)(uintptr_t)S.rec_key + 4ull * at);
+          GlobalU32 *rp = (GlobalU32 *)((uint64_t)(uintptr_t)S.rec_pos + 4ull * at);
+          if ((m0[i] >> lane) & 1ull) {
+            const uint32_t slot = (uint32_t)__popcll(m0[i] & below);
+            rk[slot] = key_of_float((METRIC == 0 ? acc0[i] : -acc0[i]) + 0.0f);
+            rp[slot] = off + v0;
+          }
+          if ((m1[i] >> lane) & 1ull) {
+            const uint32_t slot = (uint32_t)__popcll(m0[i]) + (uint32_t)__popcll(m1[i] & below);
+            rk[slot] = key_of_float((METRIC == 0 ? acc1[i] : -acc1[i]) + 0.0f);
+            rp[slot] = off + v1;
+          }
+        }
+      }
     }
   }
   __builtin_amdgcn_wave_barrier();  // the LDS slice is rewritten by the next item
@@ -794,16 +928,14 @@ __global__ __launch_bounds__(kScanWaves * kWave) void k_scan(Dev D, int max_npro
 }
 
 // ------------------------------------------------------------ top-k selection
-// One workgroup per query over its candidate slice: the k best by (score, id).
-//
-// The slice holds tens of thousands of scores of which k survive, so the exact
-// selection runs on a filtered subset kept in LDS: the k-th best score of the
-// first probed lists (the shortest prefix of them with at least k entries) is
-// an upper bound of the final k-th best; one pass over the slice keeps what is
-// not worse than that bound.  If more survive than LDS holds, the selection
-// falls back to working on the whole slice in place.
+// One workgroup per query takes the k best of the query's survivor records
+// (first-list candidates and what the grouped scan appended) by (score, id):
+// exact selection with the id tie-break, then a bitonic sort.  The records
+// number a few hundred as a rule and are worked on in LDS; a list longer than
+// LDS holds (massive ties) is selected from in place.
 constexpr int kSurvivorCap = 4096;
-constexpr int kBoundPrefix = 8192;  // candidates (at least) that the first bound is taken from
+
+constexpr int kTieCap = 1024;  // candidates tied at the k-th score that are told apart in LDS
 
 struct SelectShared {
   __attribute__((aligned(8))) uint32_t hist[256];  // also holds two 64-bit words for a moment
@@ -812,52 +944,78 @@ struct SelectShared {
   uint64_t k1[kMaxK];
   uint64_t k2[kMaxK];
   uint32_t pay[kMaxK];
+  uint64_t tie_id[kTieCap];
+  uint32_t tie_item[kTieCap];
 };
 
 // Exact top-k among `count` items given by key(j) (32-bit score key) and
-// item(j) (candidate index, for the id lookup).  Leaves the winners sorted in
-// sh.k1 (score key), sh.k2 (id key), sh.pay (candidate index); returns how many.
+// item(j) (candidate position, for the id lookup).  Leaves the winners sorted in
+// sh.k1 (score key), sh.k2 (id key), sh.pay (candidate position); returns how
+// many.  Candidates tied at the k-th score are told apart by id: their ids are
+// fetched once and ranked in LDS (with byte-valued data such ties are the rule,
+// a handful per query); only more ties than kTieCap go through a radix
+// selection over the ids.
 template <typename KeyFn, typename ItemFn, typename IdFn>
 __device__ int select_topk(int count, int k, KeyFn key, ItemFn item, IdFn id_of, SelectShared &sh) {
   auto key_of_id = [](int64_t id) -> uint64_t { return (uint64_t)id ^ 0x8000000000000000ull; };
   const int kk = k < count ? k : count;
   SelectResult r1{~0ull, 0, 0}, r2{~0ull, 0, 0};
   const bool all = count <= k;
-  if (!all) {
+  if (!all)
     r1 = wg_radix_select<32>(count, (uint32_t)k, [&](int j, uint64_t &kv) { kv = key(j); return true; },
                              sh.hist, sh.bc);
-    if (r1.c_eq > r1.need)  // ties at the boundary go to the lower id
-      r2 = wg_radix_select<64>(count, r1.need,
-                               [&](int j, uint64_t &kv) {
-                                 if (key(j) != (uint32_t)r1.T) return false;
-                                 kv = key_of_id(id_of(item(j)));
-                                 return true;
-                               },
-                               sh.hist, sh.bc);
-  }
+  const bool tie_break = !all && r1.c_eq > r1.need;  // not all of the candidates tied at the k-th score fit
+  const bool in_lds = tie_break && r1.c_eq <= (uint32_t)kTieCap;
+  if (tie_break && !in_lds)
+    r2 = wg_radix_select<64>(count, r1.need,
+                             [&](int j, uint64_t &kv) {
+                               if (key(j) != (uint32_t)r1.T) return false;
+                               kv = key_of_id(id_of(item(j)));
+                               return true;
+                             },
+                             sh.hist, sh.bc);
   if (threadIdx.x == 0) sh.cnt[0] = sh.cnt[1] = 0;
   __syncthreads();
   for (int j = threadIdx.x; j < count; j += blockDim.x) {
-    uint32_t kv = key(j);
-    bool take = all || kv < (uint32_t)r1.T;
+    const uint32_t kv = key(j);
+    bool take = all || kv < (uint32_t)r1.T || (kv == (uint32_t)r1.T && !tie_break);
     int64_t id = 0;
     bool have_id = false;
     if (!take && kv == (uint32_t)r1.T) {
-      if (r1.c_eq <= r1.need) take = true;
-      else {
+      if (in_lds) {
+        sh.tie_item[atomicAdd(&sh.cnt[1], 1u)] = (uint32_t)item(j);
+      } else {
         id = id_of(item(j)); have_id = true;
-        uint64_t ik = key_of_id(id);
+        const uint64_t ik = key_of_id(id);
         if (ik < r2.T) take = true;
         else if (ik == r2.T) take = atomicAdd(&sh.cnt[1], 1u) < r2.need;  // identical (score, id) pairs
       }
     }
     if (take) {
       if (!have_id) id = id_of(item(j));
-      uint32_t p = atomicAdd(&sh.cnt[0], 1u);
+      const uint32_t p = atomicAdd(&sh.cnt[0], 1u);
       sh.k1[p] = kv; sh.k2[p] = key_of_id(id); sh.pay[p] = (uint32_t)item(j);
     }
   }
   __syncthreads();
+  if (in_lds) {  // uniform over the workgroup
+    const int nt = (int)sh.cnt[1];  // == r1.c_eq
+    for (int t = threadIdx.x; t < nt; t += blockDim.x) sh.tie_id[t] = key_of_id(id_of((int)sh.tie_item[t]));
+    __syncthreads();
+    for (int t = threadIdx.x; t < nt; t += blockDim.x) {
+      const uint64_t mine = sh.tie_id[t];
+      uint32_t rank = 0;
+      for (int u = 0; u < nt; ++u) {
+        const uint64_t other = sh.tie_id[u];
+        rank += (other < mine || (other == mine && u < t)) ? 1u : 0u;
+      }
+      if (rank < r1.need) {
+        const uint32_t p = atomicAdd(&sh.cnt[0], 1u);
+        sh.k1[p] = (uint32_t)r1.T; sh.k2[p] = mine; sh.pay[p] = sh.tie_item[t];
+      }
+    }
+    __syncthreads();
+  }
   const int m = next_pow2(kk > 0 ? kk : 1);
   for (int p = kk + threadIdx.x; p < m; p += blockDim.x) { sh.k1[p] = ~0ull; sh.k2[p] = ~0ull; sh.pay[p] = 0; }
   wg_bitonic_sort(m, sh.k1, sh.k2, sh.pay);
@@ -865,7 +1023,11 @@ __device__ int select_topk(int count, int k, KeyFn key, ItemFn item, IdFn id_of,
 }
 
 constexpr int kTopkThreads = 512;
-constexpr int kKeyRegs = 128; // candidate keys a thread of the selection keeps in registers
+
+__device__ inline float score_of_key(uint32_t key, int metric) {
+  const float x = __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+  return metric == 0 ? x : -x;
+}
 
 __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprobe, int max_nprobe,
                                                         SearchScratch S, float *__restrict__ out_dist,
@@ -877,9 +1039,11 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
   __shared__ uint32_t sidx[kSurvivorCap];
   __shared__ uint32_t scount;
   const int q = blockIdx.x;
-  const int n = (int)S.qtotal[q];
-  const float *cand = S.cand + S.qbase[q];
+  const int n = (int)S.rec_cnt[q];
+  const unsigned long long base = S.qbase[q];
+  const uint32_t *rk = S.rec_key + base, *rp = S.rec_pos + base;
   const int metric = D.metric;
+  const int lane = threadIdx.x & (kWave - 1);
   for (int p = threadIdx.x; p < nprobe; p += kTopkThreads) {
     offs[p] = S.probe_off[(size_t)q * max_nprobe + p];
     lists[p] = S.probe_list[(size_t)q * max_nprobe + p];
@@ -887,12 +1051,83 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
   if (threadIdx.x == 0) scount = 0;
   __syncthreads();
 
-  auto key1 = [&](int i) -> uint32_t {
-    float x = cand[i];
-    x = (metric == 0 ? x : -x) + 0.0f;
-    return key_of_float(x);
-  };
-  // candidate i -> id: which probed list (last offset <= i), which position, which block
+  // The records are taken into LDS in portions that fit whatever they hold.  Once LDS is more
+  // than half full the k-th best of what it holds becomes the limit (it cannot be better than
+  // the final k-th best): what is worse is dropped, and later portions are filtered on the way
+  // in.  Ties that no limit can separate (LDS stays more than half full) are left to the
+  // selection in place below.
+  uint32_t limit = 0xFFFFFFFFu;
+  bool in_lds = true;
+  for (int next = 0; next < n;) {  // every branch here is uniform over the workgroup
+    const int count = (int)scount;
+    const int m = min(n - next, kSurvivorCap - count);
+    constexpr int kInFlight = 8;  // independent loads per thread
+    for (int j0 = 0; j0 < m; j0 += kInFlight * kTopkThreads) {
+      uint32_t kv[kInFlight];
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u) {  // clamped index: the loads are unconditional and issue back to back
+        const int j = j0 + u * kTopkThreads + (int)threadIdx.x;
+        kv[u] = rk[next + (j < m ? j : m - 1)];
+      }
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u) {
+        const int j = j0 + u * kTopkThreads + (int)threadIdx.x;
+        const bool keep = j < m && kv[u] <= limit;
+        const unsigned long long mask = __ballot(keep);
+        if (mask) {  // uniform over the wavefront
+          uint32_t at = 0;
+          if (lane == 0) at = atomicAdd(&scount, (uint32_t)__popcll(mask));
+          at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+          if (keep) {
+            const uint32_t slot = at + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+            skey[slot] = kv[u];
+            sidx[slot] = rp[next + j];
+          }
+        }
+      }
+    }
+    next += m;
+    __syncthreads();
+    if (next >= n) break;
+    const int have = (int)scount;
+    if (have <= kSurvivorCap / 2) continue;
+    // tighten (have > kSurvivorCap / 2 >= k)
+    const SelectResult r = wg_radix_select<32>(
+        have, (uint32_t)k, [&](int j, uint64_t &kv) { kv = skey[j]; return true; }, sh.hist, sh.bc);
+    limit = (uint32_t)r.T;
+    // drop what is worse: everybody reads its entries, then everybody writes the kept ones back
+    constexpr int kMine = kSurvivorCap / kTopkThreads;
+    uint32_t mk[kMine], mi[kMine];
+#pragma unroll
+    for (int u = 0; u < kMine; ++u) {
+      const int j = (int)threadIdx.x + u * kTopkThreads;
+      mk[u] = j < have ? skey[j] : 0xFFFFFFFFu;
+      mi[u] = j < have ? sidx[j] : 0u;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) scount = 0;
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kMine; ++u) {
+      const int j = (int)threadIdx.x + u * kTopkThreads;
+      const bool keep = j < have && mk[u] <= limit;
+      const unsigned long long mask = __ballot(keep);
+      if (mask) {
+        uint32_t at = 0;
+        if (lane == 0) at = atomicAdd(&scount, (uint32_t)__popcll(mask));
+        at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+        if (keep) {
+          const uint32_t slot = at + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+          skey[slot] = mk[u];
+          sidx[slot] = mi[u];
+        }
+      }
+    }
+    __syncthreads();
+    if ((int)scount > kSurvivorCap / 2) { in_lds = false; break; }
+  }
+
+  // candidate position -> id: which probed list (last offset <= position), which place, which block
   auto id_of = [&](int i) -> int64_t {
     int lo = 0, hi = nprobe - 1;
     while (lo < hi) {
@@ -905,99 +1140,16 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
   };
 
   int kk;
-  bool in_lds = false;
-  if (n > k && n > kSurvivorCap) {
-    // shortest prefix of the probed lists holding at least max(k, kBoundPrefix) candidates:
-    // the more of the nearest lists it covers, the fewer candidates survive the bound
-    const uint32_t want = (uint32_t)(k > kBoundPrefix ? k : kBoundPrefix);
-    int m0 = n;
-    for (int p = 1; p < nprobe; ++p)
-      if (offs[p] >= want) { m0 = (int)offs[p]; break; }
-    // The bound is the k-th best of a SAMPLE of that prefix (every 4th candidate when
-    // the prefix is long enough): the k-th best of any k or more candidates bounds the
-    // final k-th best, and the sample makes the selection four times cheaper at the
-    // price of a few hundred more survivors.
-    const int stride = m0 >= 4 * (k > 512 ? k : 512) ? 4 : 1;
-    const int ms = (m0 + stride - 1) / stride;  // sample size, >= k
-    if (ms <= kKeyRegs * kTopkThreads) {
-      // the sample fits into registers: read it once (every load in flight at the
-      // same time) and take the bound without touching memory again;
-      // samples tid, tid + T, tid + 2T, ... below ms are this thread's
-      uint32_t kreg[kKeyRegs];
-#pragma unroll
-      for (int u = 0; u < kKeyRegs; ++u) {  // clamped index: unconditional loads
-        const int j = (int)threadIdx.x + u * kTopkThreads;
-        kreg[u] = key1((j < ms ? j : ms - 1) * stride);
-      }
-      const int mine = ms > (int)threadIdx.x ? (ms - (int)threadIdx.x + kTopkThreads - 1) / kTopkThreads : 0;
-      const SelectResult r0 = wg_radix_select_regs<kKeyRegs>(kreg, mine, (uint32_t)k, sh.hist, sh.bc);
-      uint32_t bound = (uint32_t)r0.T;
-      // one pass over the whole slice, many independent loads in flight per thread;
-      // if more survive than LDS holds, the k-th best of those that were kept is a
-      // tighter bound and the pass is repeated (ties that cannot be told apart end it)
-      constexpr int kInFlight = 24;
-      for (int round = 0; round < 4; ++round) {
-        for (int i0 = (int)threadIdx.x; i0 < n; i0 += kInFlight * kTopkThreads) {
-          uint32_t kv[kInFlight];
-#pragma unroll
-          for (int u = 0; u < kInFlight; ++u) {
-            const int i = i0 + u * kTopkThreads;
-            kv[u] = key1(i < n ? i : n - 1);
-          }
-#pragma unroll
-          for (int u = 0; u < kInFlight; ++u) {
-            const int i = i0 + u * kTopkThreads;
-            if (i < n && kv[u] <= bound) {
-              uint32_t pos = atomicAdd(&scount, 1u);
-              if (pos < (uint32_t)kSurvivorCap) { skey[pos] = kv[u]; sidx[pos] = (uint32_t)i; }
-            }
-          }
-        }
-        __syncthreads();
-        if (scount <= (uint32_t)kSurvivorCap) break;
-        const SelectResult rt = wg_radix_select<32>(
-            kSurvivorCap, (uint32_t)k, [&](int j, uint64_t &kv) { kv = skey[j]; return true; }, sh.hist, sh.bc);
-        if ((uint32_t)rt.T >= bound) break;  // no tighter: left to the in-place selection below
-        bound = (uint32_t)rt.T;
-        __syncthreads();
-        if (threadIdx.x == 0) scount = 0;
-        __syncthreads();
-      }
-    } else {
-      SelectResult r0 = wg_radix_select<32>(
-          m0, (uint32_t)k, [&](int i, uint64_t &kv) { kv = key1(i); return true; }, sh.hist, sh.bc);
-      const uint32_t bound = (uint32_t)r0.T;
-      // one pass over the slice, four independent loads in flight per thread
-      for (int i0 = threadIdx.x; i0 < n; i0 += 4 * kTopkThreads) {
-        uint32_t kv[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int i = i0 + u * kTopkThreads;
-          kv[u] = key1(i < n ? i : n - 1);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int i = i0 + u * kTopkThreads;
-          if (i < n && kv[u] <= bound) {
-            uint32_t pos = atomicAdd(&scount, 1u);
-            if (pos < (uint32_t)kSurvivorCap) { skey[pos] = kv[u]; sidx[pos] = (uint32_t)i; }
-          }
-        }
-      }
-    }
-    __syncthreads();
-    in_lds = scount <= (uint32_t)kSurvivorCap;
-  }
   if (in_lds)
     kk = select_topk((int)scount, k, [&](int j) { return skey[j]; }, [&](int j) { return (int)sidx[j]; },
                      id_of, sh);
   else
-    kk = select_topk(n, k, key1, [](int j) { return j; }, id_of, sh);
+    kk = select_topk(n, k, [&](int j) { return rk[j]; }, [&](int j) { return (int)rp[j]; }, id_of, sh);
 
   for (int r = threadIdx.x; r < k; r += kTopkThreads) {
     size_t o = (size_t)q * k + r;
     if (r < kk) {
-      out_dist[o] = cand[sh.pay[r]];
+      out_dist[o] = score_of_key((uint32_t)sh.k1[r], metric);
       out_ids[o] = (int64_t)(sh.k2[r] ^ 0x8000000000000000ull);
     } else {
       out_dist[o] = metric == 0 ? __builtin_inff() : -__builtin_inff();
@@ -1035,11 +1187,13 @@ static int scan_grid(const Dev &D, int item_budget) {
   return (wgs + (int)kXcds - 1) / (int)kXcds * (int)kXcds;
 }
 
-void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int item_budget,
-                  const SearchScratch &S, hipStream_t s) {
+void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int k, const float *Q,
+                  int item_budget, const SearchScratch &S, hipStream_t s) {
   if (nq <= 0) return;
-  hipLaunchKernelGGL(k_group, dim3(1), dim3(kGroupThreads), 0, s, D, (int)nq, nprobe, max_nprobe,
-                     (uint32_t)item_budget, (uint32_t)(scan_grid(D, item_budget) / (int)kXcds * scan_waves(D)), S);
+  // workgroup 0 groups the pairs, workgroup 1 + q sets the bound of query q
+  hipLaunchKernelGGL(k_group, dim3(1 + (unsigned)nq), dim3(kGroupThreads), 0, s, D, (int)nq, nprobe,
+                     max_nprobe, k, Q, (uint32_t)item_budget,
+                     (uint32_t)(scan_grid(D, item_budget) / (int)kXcds * scan_waves(D)), S);
 }
 
 void launch_scan(const Dev &D, int64_t nq, int max_nprobe, const float *Q, int item_budget,
