@@ -120,56 +120,6 @@ __device__ SelectResult wg_radix_select_each(uint32_t k, Each each, uint32_t *hi
   return {prefix, need, c_eq};
 }
 
-// The same selection over 32-bit keys that every thread holds in registers:
-// thread t owns kreg[0 .. mine-1].  Nothing is read from memory.
-template <int KR>
-__device__ SelectResult wg_radix_select_regs(const uint32_t (&kreg)[KR], int mine, uint32_t k,
-                                             uint32_t *hist, uint32_t *bc) {
-  if (threadIdx.x == 0) { hist[0] = 0xffffffffu; hist[1] = 0u; }
-  __syncthreads();
-  {
-    uint32_t lo = 0xffffffffu, hi = 0u;
-#pragma unroll
-    for (int u = 0; u < KR; ++u)
-      if (u < mine) { lo = kreg[u] < lo ? kreg[u] : lo; hi = kreg[u] > hi ? kreg[u] : hi; }
-    for (int o = kWave / 2; o > 0; o >>= 1) {
-      const uint32_t a = __shfl_xor(lo, o), b = __shfl_xor(hi, o);
-      lo = a < lo ? a : lo;
-      hi = b > hi ? b : hi;
-    }
-    if ((threadIdx.x & (kWave - 1)) == 0) { atomicMin(&hist[0], lo); atomicMax(&hist[1], hi); }
-  }
-  __syncthreads();
-  const uint32_t kmin = hist[0], kmax = hist[1];
-  __syncthreads();  // hist is reused below
-  const uint32_t diff = kmin ^ kmax;
-  const int top = diff ? 31 - __clz((int)diff) : -1;  // highest bit in which keys differ
-  const int first_shift = top < 0 ? 0 : (top / 8) * 8;
-  uint32_t mask = first_shift + 8 < 32 ? ~0u << (first_shift + 8) : 0u;
-  uint32_t prefix = kmax & mask;
-  uint32_t need = k, c_eq = 0;
-  for (int shift = first_shift; shift >= 0; shift -= 8) {
-    for (int b = threadIdx.x; b < 256; b += blockDim.x) hist[b] = 0;
-    __syncthreads();
-#pragma unroll
-    for (int u = 0; u < KR; ++u)
-      if (u < mine && (kreg[u] & mask) == prefix) atomicAdd(&hist[(kreg[u] >> shift) & 255u], 1u);
-    __syncthreads();
-    wg_pick_bin(hist, need, bc);
-    const uint32_t dg = bc[0];
-    need -= bc[1];
-    c_eq = bc[2];
-    prefix |= dg << shift;
-    mask |= 255u << shift;
-    __syncthreads();
-    if (c_eq == need) {
-      if (shift > 0) prefix |= (1u << shift) - 1u;
-      break;
-    }
-  }
-  return {(uint64_t)prefix, need, c_eq};
-}
-
 // Items 0..n-1 given by fn(i, key) (false: the item does not take part); keys are
 // read from memory, four independent loads in flight per thread.
 template <int BITS, typename Fn>
@@ -1051,16 +1001,22 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
   if (threadIdx.x == 0) scount = 0;
   __syncthreads();
 
-  // The records are taken into LDS in portions that fit whatever they hold.  Once LDS is more
-  // than half full the k-th best of what it holds becomes the limit (it cannot be better than
-  // the final k-th best): what is worse is dropped, and later portions are filtered on the way
-  // in.  Ties that no limit can separate (LDS stays more than half full) are left to the
-  // selection in place below.
-  uint32_t limit = 0xFFFFFFFFu;
+  // The records are taken into LDS in portions.  Once LDS is more than half full the k-th best
+  // of what it holds becomes the limit (it cannot be better than the final k-th best): what is
+  // worse is dropped, and later portions are filtered on the way in.  Under a limit only a few
+  // per cent of a portion pass as a rule, so a portion is four times what LDS could take if all
+  // of it passed; should it not fit after all, what it added is dropped, the limit is renewed
+  // and the portion is read again, cut to what fits for certain.  Ties that no limit can
+  // separate (LDS stays more than half full) are left to the selection in place below.
+  uint32_t limit = S.bound[q];
   bool in_lds = true;
+  __shared__ uint32_t s_over;
+  int stretch = 1;  // portions as a multiple of the room in LDS
   for (int next = 0; next < n;) {  // every branch here is uniform over the workgroup
     const int count = (int)scount;
-    const int m = min(n - next, kSurvivorCap - count);
+    const int m = min(n - next, stretch * (kSurvivorCap - count));
+    if (threadIdx.x == 0) s_over = 0;
+    __syncthreads();
     constexpr int kInFlight = 8;  // independent loads per thread
     for (int j0 = 0; j0 < m; j0 += kInFlight * kTopkThreads) {
       uint32_t kv[kInFlight];
@@ -1080,51 +1036,63 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
           at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
           if (keep) {
             const uint32_t slot = at + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-            skey[slot] = kv[u];
-            sidx[slot] = rp[next + j];
+            if (slot < (uint32_t)kSurvivorCap) { skey[slot] = kv[u]; sidx[slot] = rp[next + j]; }
+            else s_over = 1u;
           }
         }
       }
     }
-    next += m;
     __syncthreads();
-    if (next >= n) break;
-    const int have = (int)scount;
-    if (have <= kSurvivorCap / 2) continue;
-    // tighten (have > kSurvivorCap / 2 >= k)
-    const SelectResult r = wg_radix_select<32>(
-        have, (uint32_t)k, [&](int j, uint64_t &kv) { kv = skey[j]; return true; }, sh.hist, sh.bc);
-    limit = (uint32_t)r.T;
-    // drop what is worse: everybody reads its entries, then everybody writes the kept ones back
-    constexpr int kMine = kSurvivorCap / kTopkThreads;
-    uint32_t mk[kMine], mi[kMine];
-#pragma unroll
-    for (int u = 0; u < kMine; ++u) {
-      const int j = (int)threadIdx.x + u * kTopkThreads;
-      mk[u] = j < have ? skey[j] : 0xFFFFFFFFu;
-      mi[u] = j < have ? sidx[j] : 0u;
+    const bool over = s_over != 0;
+    __syncthreads();
+    if (over) {  // did not fit: forget what this portion added; below, the limit is renewed from the rest
+      if (threadIdx.x == 0) scount = (uint32_t)count;
+      __syncthreads();
+    } else {
+      next += m;
+      if (next >= n) break;
     }
-    __syncthreads();
-    if (threadIdx.x == 0) scount = 0;
-    __syncthreads();
+    const int have = (int)scount;
+    if (!over && have <= kSurvivorCap / 2) continue;
+    if (have >= k) {
+      // tighten
+      const SelectResult r = wg_radix_select<32>(
+          have, (uint32_t)k, [&](int j, uint64_t &kv) { kv = skey[j]; return true; }, sh.hist, sh.bc);
+      limit = (uint32_t)r.T;
+      // drop what is worse: everybody reads its entries, then everybody writes the kept ones back
+      constexpr int kMine = kSurvivorCap / kTopkThreads;
+      uint32_t mk[kMine], mi[kMine];
 #pragma unroll
-    for (int u = 0; u < kMine; ++u) {
-      const int j = (int)threadIdx.x + u * kTopkThreads;
-      const bool keep = j < have && mk[u] <= limit;
-      const unsigned long long mask = __ballot(keep);
-      if (mask) {
-        uint32_t at = 0;
-        if (lane == 0) at = atomicAdd(&scount, (uint32_t)__popcll(mask));
-        at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
-        if (keep) {
-          const uint32_t slot = at + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-          skey[slot] = mk[u];
-          sidx[slot] = mi[u];
+      for (int u = 0; u < kMine; ++u) {
+        const int j = (int)threadIdx.x + u * kTopkThreads;
+        mk[u] = j < have ? skey[j] : 0xFFFFFFFFu;
+        mi[u] = j < have ? sidx[j] : 0u;
+      }
+      __syncthreads();
+      if (threadIdx.x == 0) scount = 0;
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < kMine; ++u) {
+        const int j = (int)threadIdx.x + u * kTopkThreads;
+        const bool keep = j < have && mk[u] <= limit;
+        const unsigned long long mask = __ballot(keep);
+        if (mask) {
+          uint32_t at = 0;
+          if (lane == 0) at = atomicAdd(&scount, (uint32_t)__popcll(mask));
+          at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+          if (keep) {
+            const uint32_t slot = at + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+            skey[slot] = mk[u];
+            sidx[slot] = mi[u];
+          }
         }
       }
+      __syncthreads();
+      if ((int)scount > kSurvivorCap / 2) { in_lds = false; break; }
     }
-    __syncthreads();
-    if ((int)scount > kSurvivorCap / 2) { in_lds = false; break; }
+    // from the first limit on, portions may be stretched; a portion that did not fit is read
+    // again unstretched (it fits then, whatever it holds)
+    stretch = over ? 1 : 4;
   }
 
   // candidate position -> id: which probed list (last offset <= position), which place, which block
