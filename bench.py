@@ -280,6 +280,21 @@ def extras(args, g, w, torch, rtams, q_batches, queries, ins_batches, data_strea
         }
     out["latency_by_query_batch"] = per_batch
 
+    # practical ceiling of a streaming read on this chip: the library's plain read kernel over 1 GiB
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).zero_()
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    for _ in range(3):
+        rtams.read_plain(src, sink)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        rtams.read_plain(src, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    out["plain_read_GBps"] = 10 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src
+
     # saturated insertion: batches back to back on the data stream
     torch.cuda.synchronize()
     n = 300

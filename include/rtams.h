@@ -179,6 +179,11 @@ int rtams_scan_time(rtams_index *ix, double *ms_sum, int64_t *launches, int rese
  * (bytes a multiple of 16).  Profiler counters of HBM traffic are scaled by
  * what they read for this kernel, whose traffic is known. */
 int rtams_copy_plain(void *d_dst, const void *d_src, size_t bytes, void *hip_stream);
+/* Measurement aid, not part of the method: a kernel that only reads `bytes`
+ * (a multiple of 16) of device memory; d_sink points to 4 bytes of device
+ * memory it may write.  Its rate is the practical ceiling a streaming read
+ * reaches on the chip, reported beside the list scan's. */
+int rtams_read_plain(const void *d_src, size_t bytes, float *d_sink, void *hip_stream);
 /* Launch-shape knobs ("restrict the number of blocks and threads per kernel",
  * Stream-Cached Multi-Stream Execution, consideration 2).  key: "scan_max_items"
  * (most work items, one workgroup each, one list-scan launch is cut

@@ -116,6 +116,25 @@ __global__ __launch_bounds__(256) void k_copy_plain(uint4 *__restrict__ dst, con
     dst[i] = src[i];
 }
 
+// plain read, four independent 16-byte loads per thread per step: what a kernel that only streams
+// memory in reaches on this chip (the practical ceiling the list scan is compared with).  The
+// sum is stored only if it equals a value it cannot have, so that the loads stay.
+__global__ __launch_bounds__(256) void k_read_plain(const float4 *__restrict__ src, size_t n16, float *sink) {
+  size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 1024;
+  float acc = 0.f;
+  for (; i + 768 < n16; i += stride) {
+    const float4 a = src[i], b = src[i + 256], c = src[i + 512], d = src[i + 768];
+    acc += (a.x + a.y + a.z + a.w) + (b.x + b.y + b.z + b.w) + (c.x + c.y + c.z + c.w) + (d.x + d.y + d.z + d.w);
+  }
+  for (; i < n16; i += 256) acc += src[i].x;
+  if (acc == 1.2345678e-30f) *sink = acc;
+}
+
+void launch_read_plain(const void *src, size_t bytes, float *sink, hipStream_t s) {
+  hipLaunchKernelGGL(k_read_plain, dim3(4096), dim3(256), 0, s, static_cast<const float4 *>(src), bytes / 16, sink);
+}
+
 void launch_copy_plain(void *dst, const void *src, size_t bytes, hipStream_t s) {
   hipLaunchKernelGGL(k_copy_plain, dim3(4096), dim3(256), 0, s, static_cast<uint4 *>(dst),
                      static_cast<const uint4 *>(src), bytes / 16);

@@ -794,6 +794,13 @@ int rtams_copy_plain(void *d_dst, const void *d_src, size_t bytes, void *hip_str
   return RTAMS_OK;
 }
 
+int rtams_read_plain(const void *d_src, size_t bytes, float *d_sink, void *hip_stream) {
+  if (!d_src || !d_sink || bytes % 16) return fail(RTAMS_EINVAL, "read needs buffers and a multiple of 16 bytes");
+  launch_read_plain(d_src, bytes, d_sink, static_cast<hipStream_t>(hip_stream));
+  HIP_TRY(hipGetLastError());
+  return RTAMS_OK;
+}
+
 int rtams_set_param(rtams_index *ix, const char *key, int64_t value) {
   if (!ix || !key) return fail(RTAMS_EINVAL, "NULL argument");
   if (!strcmp(key, "profile_scan")) { ix->profile_scan = value; return RTAMS_OK; }

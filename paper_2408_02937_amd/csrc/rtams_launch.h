@@ -127,5 +127,6 @@ void launch_chain_copy(const Dev &D, int list, int32_t *out, hipStream_t s);
 void launch_list_info(const Dev &D, int list, int32_t *out4, hipStream_t s);
 void launch_validate(const Dev &D, int32_t *result2, hipStream_t s);
 void launch_copy_plain(void *dst, const void *src, size_t bytes, hipStream_t s);
+void launch_read_plain(const void *src, size_t bytes, float *sink, hipStream_t s);
 
 }  // namespace rtams

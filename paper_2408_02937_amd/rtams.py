@@ -28,7 +28,7 @@ SYMBOLS = [
     "rtams_list_size", "rtams_list_info", "rtams_list_export", "rtams_list_chain",
     "rtams_list_sizes", "rtams_pool_stats", "rtams_validate", "rtams_probe", "rtams_assign",
     "rtams_poll_error", "rtams_last_error", "rtams_set_param", "rtams_scan_time",
-    "rtams_copy_plain",
+    "rtams_copy_plain", "rtams_read_plain",
 ]
 
 
@@ -93,6 +93,7 @@ def lib():
         L.rtams_set_param.argtypes = [vp, C.c_char_p, i64]
         L.rtams_scan_time.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), C.c_int]
         L.rtams_copy_plain.argtypes = [vp, vp, C.c_size_t, vp]
+        L.rtams_read_plain.argtypes = [vp, C.c_size_t, vp, vp]
         _lib = L
     return _lib
 
@@ -117,6 +118,12 @@ def copy_plain(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
     """The library's plain copy kernel (calibration of traffic counters)."""
     nbytes = src.numel() * src.element_size()
     _chk(lib().rtams_copy_plain(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream)), "rtams_copy_plain")
+
+
+def read_plain(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    """The library's plain read kernel (practical ceiling of a streaming read)."""
+    nbytes = src.numel() * src.element_size()
+    _chk(lib().rtams_read_plain(src.data_ptr(), nbytes, sink.data_ptr(), _stream_ptr(stream)), "rtams_read_plain")
 
 
 class Index:
