@@ -13,6 +13,12 @@
 // that covers the rounding of the norms, of the dot product in any summation
 // order, and of the final combination.  If m is the smallest approximate score
 // of row i, the exact winner lies among the centroids with approx <= m + 2 E_i.
+//
+// For a search the whole score matrix is written (probe selection needs the
+// nprobe-th smallest of a row).  For an assignment it is not: each workgroup
+// reduces its 64 x 128 tile on the spot to, per row, the tile's smallest score
+// and the (up to kTileCands) columns within the band of it; the refinement reads
+// those few bytes per (row, tile) instead of the matrix, twice.
 #include "rtams_launch.h"
 
 namespace rtams {
@@ -36,13 +42,18 @@ __global__ __launch_bounds__(256) void k_centroid_norms(Dev D) {
 }
 
 // ---- approx[i][c] for i < n, c < nlist
-template <int METRIC>
+template <int METRIC, bool MATRIX>
 __global__ __launch_bounds__(kMfmaThreads) void k_coarse_mfma(Dev D, int64_t n, const float *__restrict__ Y,
-                                                              float *__restrict__ approx,
+                                                              float *__restrict__ approx, TileCands tc,
                                                               unsigned long long *cursor_to_clear,
                                                               uint32_t *__restrict__ zero, int zero_n) {
   __shared__ float sA[kTileM * kLdsStride];
   __shared__ float sB[kTileN * kLdsStride];
+  __shared__ float s_min[kTileM][2];
+  __shared__ float s_norm[kTileM];
+  __shared__ uint32_t s_cnt[kTileM];
+  __shared__ int32_t s_col[kTileM][kTileCands];
+  __shared__ float s_val[kTileM][kTileCands];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int wm = wave & 1, wn = wave >> 1;  // wavefront's place in the 2 x 2 arrangement
   const int64_t row0 = (int64_t)blockIdx.x * kTileM;
@@ -64,11 +75,13 @@ __global__ __launch_bounds__(kMfmaThreads) void k_coarse_mfma(Dev D, int64_t n, 
 
   // staging: thread t loads a float4 (4 consecutive k) of one row
   const int ld_row = tid / 4, ld_k = (tid % 4) * 4;  // 64 rows x 16 k per pass
+  float nsq = 0.f;  // this thread's share of |y_row|^2
   for (int k0 = 0; k0 < d; k0 += kTileK) {
     {
       const int64_t r = row0 + ld_row;
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (r < n && k0 + ld_k < d) v = *reinterpret_cast<const float4 *>(Y + r * d + k0 + ld_k);
+      if (!MATRIX) nsq = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, nsq))));
       float *dst = sA + ld_row * kLdsStride + ld_k;
       dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
     }
@@ -96,25 +109,82 @@ __global__ __launch_bounds__(kMfmaThreads) void k_coarse_mfma(Dev D, int64_t n, 
   }
 
   // result layout: register r of lane l holds row (r / 4) * 8 + (l / 32) * 4 + r % 4, column l % 32
+  if (MATRIX) {
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const int c = col0 + wn * 64 + b * 32 + (lane & 31);
+      if (c >= D.nlist) continue;
+      const float cn = METRIC == 0 ? D.cnorm[c] : 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t i = row0 + wm * 32 + (r / 4) * 8 + (lane >> 5) * 4 + (r % 4);
+        if (i < n) approx[(size_t)i * D.nlist + c] = METRIC == 0 ? cn - 2.f * acc[b][r] : -acc[b][r];
+      }
+    }
+    return;
+  }
+  // The tile is reduced here: per row its smallest score and the columns within the band of it.
+  float val[2][16];
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
     const int c = col0 + wn * 64 + b * 32 + (lane & 31);
-    if (c >= D.nlist) continue;
-    const float cn = METRIC == 0 ? D.cnorm[c] : 0.f;
+    const bool real = c < D.nlist;
+    const float cn = (METRIC == 0 && real) ? D.cnorm[c] : 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int64_t i = row0 + wm * 32 + (r / 4) * 8 + (lane >> 5) * 4 + (r % 4);
-      if (i < n) approx[(size_t)i * D.nlist + c] = METRIC == 0 ? cn - 2.f * acc[b][r] : -acc[b][r];
+    for (int r = 0; r < 16; ++r)
+      val[b][r] = real ? (METRIC == 0 ? cn - 2.f * acc[b][r] : -acc[b][r]) : __builtin_inff();
+  }
+  {  // |y_row|^2: the four threads that staged a row add up their shares
+    float t = nsq;
+    t += __shfl_xor(t, 1);
+    t += __shfl_xor(t, 2);
+    if ((tid & 3) == 0) s_norm[ld_row] = t;
+    if (tid < kTileM) s_cnt[tid] = 0u;
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {  // smallest score of each row over this wavefront's 64 columns
+    float v = fminf(val[0][r], val[1][r]);
+    for (int o = 16; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o));  // stays inside a half of 32 lanes
+    if ((lane & 31) == 0) s_min[wm * 32 + (r / 4) * 8 + (lane >> 5) * 4 + (r % 4)][wn] = v;
+  }
+  __syncthreads();
+  const float cmax = __uint_as_float(D.ctrl->cnorm_max_bits);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int row = wm * 32 + (r / 4) * 8 + (lane >> 5) * 4 + (r % 4);
+    const float tmin = fminf(s_min[row][0], s_min[row][1]);
+    // 2 E of the row, a little wider than the refinement's (1.02 against 1.01), so that what the
+    // refinement asks for is certainly among what is kept here
+    const float band = 8.f * (float)(D.d + 4) * 5.9604645e-8f * (s_norm[row] + cmax) * 1.02f;
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+      if (val[b][r] <= tmin + band) {
+        const uint32_t slot = atomicAdd(&s_cnt[row], 1u);
+        if (slot < (uint32_t)kTileCands) {
+          s_col[row][slot] = col0 + wn * 64 + b * 32 + (lane & 31);
+          s_val[row][slot] = val[b][r];
+        }
+      }
+  }
+  __syncthreads();
+  if (tid < kTileM && row0 + tid < n) {
+    const size_t at = (size_t)(row0 + tid) * tc.tiles + blockIdx.y;
+    tc.tmin[at] = fminf(s_min[tid][0], s_min[tid][1]);
+    tc.cnt[at] = s_cnt[tid];
+#pragma unroll
+    for (int j = 0; j < kTileCands; ++j) {
+      tc.col[at * kTileCands + j] = s_col[tid][j];
+      tc.val[at * kTileCands + j] = s_val[tid][j];
     }
   }
 }
 
-// ---- refinement of the assignment: one wavefront per vector.  Finds the
-// smallest approximate score of the row, gathers the centroids within the
-// error band, scores those in the fixed double arithmetic (one lane each) and
-// takes the best, ties to the lowest index; then takes the next position of the
-// list ("did = atomicAdd(nl_k, 1)").  A band wider than 64 centroids is walked
-// in rounds of 64.
+// ---- refinement of the assignment: one wavefront per vector.  The smallest
+// approximate score of the row is the smallest of its tiles' minima; the
+// centroids within the error band of it (from the tiles' kept columns; from all
+// 128 columns of a tile that had more in the band than it could keep) are
+// scored in the fixed double arithmetic and the best is taken, ties to the
+// lowest index; then the next position of the list ("did = atomicAdd(nl_k, 1)").
 __device__ inline double exact_score(const Dev &D, const float *__restrict__ y, int c) {
   const float *row = D.centroids + (size_t)c * D.d;
   double acc = 0.0;
@@ -137,17 +207,17 @@ __device__ inline float error_band(const Dev &D, float ynorm) {
 }
 
 __global__ __launch_bounds__(256) void k_assign_refine(Dev D, int64_t n, const float *__restrict__ Y,
-                                                       const float *__restrict__ approx, int reserve,
+                                                       TileCands tc, int reserve,
                                                        int32_t *__restrict__ assign,
                                                        uint32_t *__restrict__ did) {
   const int lane = threadIdx.x & (kWave - 1);
   const int64_t i = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
   if (i >= n) return;  // uniform over the wavefront
   const float *y = Y + i * D.d;
-  const float *row = approx + (size_t)i * D.nlist;
+  const float *tmin = tc.tmin + (size_t)i * tc.tiles;
   float yn = 0.f, m = __builtin_inff();
   for (int j = lane; j < D.d; j += kWave) yn = fmaf(y[j], y[j], yn);
-  for (int c = lane; c < D.nlist; c += kWave) m = fminf(m, row[c]);
+  for (int t = lane; t < tc.tiles; t += kWave) m = fminf(m, tmin[t]);
   for (int o = kWave / 2; o > 0; o >>= 1) {
     yn += __shfl_xor(yn, o);
     m = fminf(m, __shfl_xor(m, o));
@@ -156,15 +226,26 @@ __global__ __launch_bounds__(256) void k_assign_refine(Dev D, int64_t n, const f
   const bool l2 = D.metric == 0;
   double best_s = l2 ? __builtin_inf() : -__builtin_inf();
   int best_c = 0x7fffffff;
-  for (int c0 = 0; c0 < D.nlist; c0 += kWave) {
-    const int c = c0 + lane;
-    const bool cand = c < D.nlist && row[c] <= limit;
-    if (__ballot(cand) == 0) continue;  // uniform
-    if (cand) {
-      const double s = exact_score(D, y, c);
-      const bool take = s != best_s ? (l2 ? s < best_s : s > best_s) : c < best_c;
-      best_s = take ? s : best_s;
-      best_c = take ? c : best_c;
+  auto offer = [&](int c) {
+    const double s = exact_score(D, y, c);
+    const bool take = s != best_s ? (l2 ? s < best_s : s > best_s) : c < best_c;
+    best_s = take ? s : best_s;
+    best_c = take ? c : best_c;
+  };
+  for (int t0 = 0; t0 < tc.tiles; t0 += kWave) {
+    const int t = t0 + lane;
+    const size_t at = (size_t)i * tc.tiles + t;
+    const bool near = t < tc.tiles && tmin[t] <= limit;
+    const uint32_t cnt = near ? tc.cnt[at] : 0u;
+    if (near && cnt <= (uint32_t)kTileCands)  // the tile kept all its columns within the band: one lane takes them
+      for (uint32_t j = 0; j < cnt; ++j)
+        if (tc.val[at * kTileCands + j] <= limit) offer(tc.col[at * kTileCands + j]);
+    // a tile with more columns in the band than it could keep: all its columns, shared out over the lanes
+    unsigned long long crowded = __ballot(near && cnt > (uint32_t)kTileCands);
+    while (crowded) {  // uniform
+      const int tt = t0 + __ffsll((long long)crowded) - 1;
+      crowded &= crowded - 1;
+      for (int c = tt * kTileN + lane; c < (tt + 1) * kTileN && c < D.nlist; c += kWave) offer(c);
     }
   }
   for (int o = kWave / 2; o > 0; o >>= 1) {
@@ -188,17 +269,29 @@ void launch_coarse_mfma(const Dev &D, int64_t n, const float *Y, float *approx,
                         unsigned long long *cursor_to_clear, uint32_t *zero, int zero_n, hipStream_t s) {
   if (n <= 0) return;
   dim3 grid((unsigned)((n + kTileM - 1) / kTileM), (unsigned)((D.nlist + kTileN - 1) / kTileN));
+  const TileCands none{};
   if (D.metric == 0)
-    hipLaunchKernelGGL(k_coarse_mfma<0>, grid, dim3(kMfmaThreads), 0, s, D, n, Y, approx, cursor_to_clear, zero, zero_n);
+    hipLaunchKernelGGL((k_coarse_mfma<0, true>), grid, dim3(kMfmaThreads), 0, s, D, n, Y, approx, none, cursor_to_clear, zero, zero_n);
   else
-    hipLaunchKernelGGL(k_coarse_mfma<1>, grid, dim3(kMfmaThreads), 0, s, D, n, Y, approx, cursor_to_clear, zero, zero_n);
+    hipLaunchKernelGGL((k_coarse_mfma<1, true>), grid, dim3(kMfmaThreads), 0, s, D, n, Y, approx, none, cursor_to_clear, zero, zero_n);
 }
 
-void launch_assign_refine(const Dev &D, int64_t n, const float *Y, const float *approx, bool reserve,
+int coarse_tiles(const Dev &D) { return (D.nlist + kTileN - 1) / kTileN; }
+
+void launch_coarse_tiles(const Dev &D, int64_t n, const float *Y, const TileCands &tc, hipStream_t s) {
+  if (n <= 0) return;
+  dim3 grid((unsigned)((n + kTileM - 1) / kTileM), (unsigned)tc.tiles);
+  if (D.metric == 0)
+    hipLaunchKernelGGL((k_coarse_mfma<0, false>), grid, dim3(kMfmaThreads), 0, s, D, n, Y, nullptr, tc, nullptr, nullptr, 0);
+  else
+    hipLaunchKernelGGL((k_coarse_mfma<1, false>), grid, dim3(kMfmaThreads), 0, s, D, n, Y, nullptr, tc, nullptr, nullptr, 0);
+}
+
+void launch_assign_refine(const Dev &D, int64_t n, const float *Y, const TileCands &tc, bool reserve,
                           int32_t *assign, uint32_t *did, hipStream_t s) {
   if (n <= 0) return;
   unsigned grid = (unsigned)((n + 3) / 4);
-  hipLaunchKernelGGL(k_assign_refine, dim3(grid), dim3(256), 0, s, D, n, Y, approx, reserve ? 1 : 0, assign, did);
+  hipLaunchKernelGGL(k_assign_refine, dim3(grid), dim3(256), 0, s, D, n, Y, tc, reserve ? 1 : 0, assign, did);
 }
 
 }  // namespace rtams

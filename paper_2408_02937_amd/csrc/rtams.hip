@@ -37,7 +37,7 @@ inline size_t up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Byte offsets of everything in front of the blocks.
 struct Layout {
-  size_t ctrl, hook, centroids, cnorm, ins_approx, approx_rows, reserved_len, visible_len, online, nblk, exceed, seg_dir;
+  size_t ctrl, hook, centroids, cnorm, tc_min, tc_cnt, tc_col, tc_val, tile_rows, reserved_len, visible_len, online, nblk, exceed, seg_dir;
   size_t ins_assign, ins_did, ins_pscore, ins_pidx, part_cap;
   size_t rearr_head, rearr_arrays;
   size_t fixed_end;          // end of the part that does not depend on the block count
@@ -97,12 +97,16 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
   L->ins_did = take((size_t)c->max_add_batch * 4);
   L->ins_pscore = take(L->part_cap * 8);
   L->ins_pidx = take(L->part_cap * 4);
-  {  // approximate scores of one insertion sub-round: at most 256 MiB, at least 64 rows
-    size_t rows = ((size_t)256 << 20) / (nl * 4);
+  {  // tile digests of one insertion sub-round (40 bytes per row and tile): at most 64 MiB, at least 64 rows
+    const size_t tiles = (nl + 127) / 128;
+    size_t rows = ((size_t)64 << 20) / (tiles * 40);
     if (rows > (size_t)c->max_add_batch) rows = (size_t)c->max_add_batch;
     if (rows < 64) rows = 64;
-    L->approx_rows = rows;
-    L->ins_approx = take(rows * nl * 4);
+    L->tile_rows = rows;
+    L->tc_min = take(rows * tiles * 4);
+    L->tc_cnt = take(rows * tiles * 4);
+    L->tc_col = take(rows * tiles * kTileCands * 4);
+    L->tc_val = take(rows * tiles * kTileCands * 4);
   }
   L->rearr_head = take(sizeof(RearrangeHead));
   L->rearr_arrays = take((size_t)kRearrangeCap * 4 * 7);
@@ -280,10 +284,10 @@ void assign_round(rtams_index *ix, int64_t m, const float *Y, bool reserve, int3
   const Dev &D = ix->dev;
   const int64_t mode = ix->use_mfma.load(std::memory_order_relaxed);  // 0 never, 1 when it pays, 2 from 32 rows
   if (mode == 2 ? m >= 32 : mode == 1 && mfma_pays_for_assign(m, D.nlist)) {
-    for (int64_t o = 0; o < m; o += ix->ins.approx_rows) {
-      const int64_t mm = m - o < ix->ins.approx_rows ? m - o : ix->ins.approx_rows;
-      launch_coarse_mfma(D, mm, Y + (size_t)o * D.d, ix->ins.approx, nullptr, nullptr, 0, s);
-      launch_assign_refine(D, mm, Y + (size_t)o * D.d, ix->ins.approx, reserve, assign_out + o, ix->ins.did + o, s);
+    for (int64_t o = 0; o < m; o += ix->ins.tile_rows) {
+      const int64_t mm = m - o < ix->ins.tile_rows ? m - o : ix->ins.tile_rows;
+      launch_coarse_tiles(D, mm, Y + (size_t)o * D.d, ix->ins.tiles, s);
+      launch_assign_refine(D, mm, Y + (size_t)o * D.d, ix->ins.tiles, reserve, assign_out + o, ix->ins.did + o, s);
     }
   } else {
     int splits = coarse_splits(D, m, ix->ins.part_cap);
@@ -369,8 +373,12 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   ix->ins.pscore = reinterpret_cast<double *>(base + L.ins_pscore);
   ix->ins.pidx = reinterpret_cast<int32_t *>(base + L.ins_pidx);
   ix->ins.part_cap = L.part_cap;
-  ix->ins.approx = reinterpret_cast<float *>(base + L.ins_approx);
-  ix->ins.approx_rows = (int64_t)L.approx_rows;
+  ix->ins.tiles.tiles = (cfg->nlist + 127) / 128;
+  ix->ins.tiles.tmin = reinterpret_cast<float *>(base + L.tc_min);
+  ix->ins.tiles.cnt = reinterpret_cast<uint32_t *>(base + L.tc_cnt);
+  ix->ins.tiles.col = reinterpret_cast<int32_t *>(base + L.tc_col);
+  ix->ins.tiles.val = reinterpret_cast<float *>(base + L.tc_val);
+  ix->ins.tile_rows = (int64_t)L.tile_rows;
   {
     uint32_t *a = reinterpret_cast<uint32_t *>(base + L.rearr_arrays);
     RearrangeScratch &R = ix->rearr;

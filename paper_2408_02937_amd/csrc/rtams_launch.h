@@ -43,6 +43,17 @@ struct SearchScratch {
 
 constexpr int kScanTileQueries = 8;  // queries that share one pass over a list
 
+// What a 64 x 128 tile of approximate coarse scores is reduced to, per row: the
+// tile's smallest score and the columns within the error band of it.
+constexpr int kTileCands = 4;
+struct TileCands {
+  int32_t tiles;   // tiles per row = ceil(nlist / 128)
+  float *tmin;     // [rows][tiles]
+  uint32_t *cnt;   // [rows][tiles] columns within the band (may exceed kTileCands: then all 128 are rescored)
+  int32_t *col;    // [rows][tiles][kTileCands]
+  float *val;      // [rows][tiles][kTileCands]
+};
+
 // Scratch of the insertion path (lives in the pool's control region).
 struct InsertScratch {
   int32_t *assign;   // [max_add_batch] list of each vector
@@ -50,8 +61,8 @@ struct InsertScratch {
   double *pscore;    // [part_cap] best score per (vector, centroid split)
   int32_t *pidx;     // [part_cap]
   size_t part_cap;
-  float *approx;     // [approx_rows][nlist] approximate scores of one sub-round
-  int64_t approx_rows;
+  TileCands tiles;   // per (row, tile of 128 centroids) digest of the approximate scores of one sub-round
+  int64_t tile_rows; // rows one sub-round may hold
 };
 
 // Scratch of one rearrangement round (lives in the pool's control region).
@@ -93,7 +104,9 @@ inline bool mfma_pays_for_assign(int64_t m, int64_t nlist) { return m >= 1024 &&
 void launch_centroid_norms(const Dev &D, hipStream_t s);
 void launch_coarse_mfma(const Dev &D, int64_t n, const float *Y, float *approx,
                         unsigned long long *cursor_to_clear, uint32_t *zero, int zero_n, hipStream_t s);
-void launch_assign_refine(const Dev &D, int64_t n, const float *Y, const float *approx, bool reserve,
+int coarse_tiles(const Dev &D);
+void launch_coarse_tiles(const Dev &D, int64_t n, const float *Y, const TileCands &tc, hipStream_t s);
+void launch_assign_refine(const Dev &D, int64_t n, const float *Y, const TileCands &tc, bool reserve,
                           int32_t *assign, uint32_t *did, hipStream_t s);
 
 // insert.hip -----------------------------------------------------------------
