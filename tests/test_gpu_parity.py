@@ -180,6 +180,55 @@ def test_coarse_filter_under_cancellation():
     g.close()
 
 
+def test_loose_bound_and_worst_first_records():
+    """The pruning bound of a query comes from the head of its nearest list.  Here that head is 600
+    decoys far from the query, so every candidate passes the bound, and the true neighbours sit
+    in another list ordered worst first: the selection has to take tens of thousands of survivor
+    records through LDS, renewing its limit as better ones keep coming."""
+    rng = np.random.default_rng(5)
+    d, nlist, n_near = 16, 8, 30000
+    C = np.zeros((nlist, d), np.float32)
+    C[1, 0] = 2.0
+    C[2:, 1] = 50.0 + np.arange(nlist - 2)  # far away, probed but empty
+    w = synth.Workload("loose-bound", "l2", d, nlist, 64, nlist, 100, np.zeros((0, d), np.float32), C,
+                       np.zeros((0, d), np.float32), np.zeros((0, d), np.float32), 1, 0)
+    g, o = make_pair(w, pool_blocks=1000, candidates_per_query=40000)
+    decoys = np.zeros((600, d), np.float32)
+    decoys[:, 0] = -0.9
+    decoys += 0.01 * rng.standard_normal((600, d)).astype(np.float32)
+    near = 0.001 * rng.standard_normal((n_near, d)).astype(np.float32)
+    near[:, 0] = 1.02 + 0.28 * (1.0 - np.arange(n_near, dtype=np.float32) / n_near)  # worst first
+    for part in (decoys, near):
+        g.add(dev(part)); o.add(part)
+    assert np.array_equal(g.list_sizes(), o.list_sizes()) and g.list_sizes()[0] == 600
+    q = np.zeros((3, d), np.float32)
+    q[:, 0] = (0.95, 0.9, 0.8)
+    for k in (1, 100):
+        dd, ii = g.search(dev(q), k, nlist)
+        rd, ri = o.search(q, k, nlist)
+        assert_topk_matches("l2", dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6)
+    g.close()
+
+
+def test_k_larger_than_a_query_has_candidates():
+    """Fewer candidates than k (and than the bound's sample): everything is kept, the rest of the
+    row is padding."""
+    rng = np.random.default_rng(6)
+    d, nlist = 8, 16
+    C = rng.standard_normal((nlist, d)).astype(np.float32)
+    w = synth.Workload("few-candidates", "ip", d, nlist, 64, 2, 128, np.zeros((0, d), np.float32), C,
+                       np.zeros((0, d), np.float32), np.zeros((0, d), np.float32), 1, 0)
+    g, o = make_pair(w, pool_blocks=200, candidates_per_query=4096)
+    y = rng.standard_normal((700, d)).astype(np.float32)
+    g.add(dev(y)); o.add(y)
+    q = rng.standard_normal((40, d)).astype(np.float32)
+    dd, ii = g.search(dev(q), 128, 2)
+    rd, ri = o.search(q, 128, 2)
+    assert (ri == -1).any()  # some query does run short
+    assert_topk_matches("ip", dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6)
+    g.close()
+
+
 def test_massive_ties_fall_back_to_in_place_selection():
     """Thousands of identical vectors: every candidate ties at the k-th score, more
     than the selection keeps in LDS, so the lowest ids must win."""
