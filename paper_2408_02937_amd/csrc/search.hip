@@ -352,6 +352,10 @@ __device__ __forceinline__ void accumulate(float &acc, const float4 &x, const fl
 
 constexpr int kGroupThreads = 1024;
 constexpr int kSampleMax = 4096;  // candidates the bound of a query is taken from, at most
+#ifndef RTAMS_SAMPLE_DIVISOR
+#define RTAMS_SAMPLE_DIVISOR 4
+#endif
+constexpr int kSampleDivisor = RTAMS_SAMPLE_DIVISOR;
 
 // The scan writes nothing for a candidate that cannot be among the k best of
 // its query: before it starts, every query gets a BOUND, the k-th best score
@@ -410,8 +414,11 @@ __device__ void sample_bound(const Dev &D, int nprobe, int max_nprobe, int k, co
   __shared__ uint32_t bc[4];
   const int q = (int)blockIdx.x - 1;
   const int tid = threadIdx.x;
-  // sample size: 4 k, at least 512, at most kSampleMax, in whole groups
+  // sample size: 4 k, at least 512 and at least a fraction of the nearest list (the longer that
+  // list, the more candidates a given score admits), at most kSampleMax, in whole groups
   uint32_t want = (uint32_t)k * 4u;
+  const uint32_t part = S.probe_len[(size_t)q * max_nprobe] / (uint32_t)kSampleDivisor;
+  want = want < part ? part : want;
   want = want < 512u ? 512u : (want > (uint32_t)kSampleMax ? (uint32_t)kSampleMax : want);
   const uint32_t want_groups = (want + kWave - 1) / kWave;
   for (int c = tid; c < D.d4; c += kGroupThreads) qv[c] = reinterpret_cast<const float4 *>(Q + (size_t)q * D.d)[c];
