@@ -180,6 +180,33 @@ def test_coarse_filter_under_cancellation():
     g.close()
 
 
+@pytest.mark.parametrize("shape", [
+    dict(d=4, nlist=100, block_vecs=64, metric="l2", nprobe=100, k=1, batch=77),
+    dict(d=20, nlist=37, block_vecs=192, metric="ip", nprobe=9, k=1000, batch=5),
+    dict(d=260, nlist=50, block_vecs=128, metric="l2", nprobe=50, k=33, batch=130),
+])
+def test_odd_shapes(shape):
+    """Dimensions that are not a multiple of the scan's pipeline depth, blocks of three groups,
+    list counts that are no power of two, every list probed, k = 1 and k near its maximum."""
+    d, nlist, metric = shape["d"], shape["nlist"], shape["metric"]
+    rng = np.random.default_rng(100 + d)
+    C = rng.standard_normal((nlist, d)).astype(np.float32)
+    w = synth.Workload("odd", metric, d, nlist, shape["block_vecs"], shape["nprobe"], shape["k"],
+                       np.zeros((0, d), np.float32), C, np.zeros((0, d), np.float32),
+                       np.zeros((0, d), np.float32), 1, 0)
+    g, o = make_pair(w, pool_blocks=600, max_k=1024, max_nprobe=128, candidates_per_query=30000)
+    y = (C[rng.integers(0, nlist, 25000)] + 0.3 * rng.standard_normal((25000, d))).astype(np.float32)
+    for b in range(0, len(y), 7000):  # ragged batches
+        g.add(dev(y[b:b + 7000])); o.add(y[b:b + 7000])
+    g.validate()
+    assert_lists_equal(g, o)
+    q = (C[rng.integers(0, nlist, shape["batch"])] + 0.3 * rng.standard_normal((shape["batch"], d))).astype(np.float32)
+    dd, ii = g.search(dev(q), shape["k"], shape["nprobe"])
+    rd, ri = o.search(q, shape["k"], shape["nprobe"])
+    assert_topk_matches(metric, dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-5)
+    g.close()
+
+
 def test_loose_bound_and_worst_first_records():
     """The pruning bound of a query comes from the head of its nearest list.  Here that head is 600
     decoys far from the query, so every candidate passes the bound, and the true neighbours sit
