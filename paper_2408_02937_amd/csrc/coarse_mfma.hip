@@ -186,15 +186,27 @@ __global__ __launch_bounds__(kMfmaThreads) void k_coarse_mfma(Dev D, int64_t n, 
 // scored in the fixed double arithmetic and the best is taken, ties to the
 // lowest index; then the next position of the list ("did = atomicAdd(nl_k, 1)").
 __device__ inline double exact_score(const Dev &D, const float *__restrict__ y, int c) {
-  const float *row = D.centroids + (size_t)c * D.d;
+  // the fixed arithmetic of coarse.hip: one double FMA per dimension, dimensions in order
+  // (loaded four at a time)
+  const float4 *row4 = reinterpret_cast<const float4 *>(D.centroids + (size_t)c * D.d);
+  const float4 *y4 = reinterpret_cast<const float4 *>(y);
   double acc = 0.0;
   if (D.metric == 0) {
-    for (int j = 0; j < D.d; ++j) {
-      const double t = (double)y[j] - (double)row[j];
-      acc = __builtin_fma(t, t, acc);
+    for (int j = 0; j < D.d4; ++j) {
+      const float4 a = y4[j], b = row4[j];
+      double t = (double)a.x - (double)b.x; acc = __builtin_fma(t, t, acc);
+      t = (double)a.y - (double)b.y; acc = __builtin_fma(t, t, acc);
+      t = (double)a.z - (double)b.z; acc = __builtin_fma(t, t, acc);
+      t = (double)a.w - (double)b.w; acc = __builtin_fma(t, t, acc);
     }
   } else {
-    for (int j = 0; j < D.d; ++j) acc = __builtin_fma((double)y[j], (double)row[j], acc);
+    for (int j = 0; j < D.d4; ++j) {
+      const float4 a = y4[j], b = row4[j];
+      acc = __builtin_fma((double)a.x, (double)b.x, acc);
+      acc = __builtin_fma((double)a.y, (double)b.y, acc);
+      acc = __builtin_fma((double)a.z, (double)b.z, acc);
+      acc = __builtin_fma((double)a.w, (double)b.w, acc);
+    }
   }
   return acc;
 }

@@ -131,7 +131,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
 }
 
 struct ScratchLayout {
-  size_t scores, approx, probe_list, probe_len, probe_off, qbase, qtotal, bound, rec_cnt, cursor, cand, fixed;
+  size_t scores, approx, probe_list, probe_len, probe_off, qbase, qtotal, bound, rec_cnt, cursor, records, fixed;
   size_t list_cnt, list_len, pair_slot, grouped, tile_desc, queues, item_cap;
 };
 
@@ -157,7 +157,7 @@ void lay_out_scratch(const rtams_config *c, ScratchLayout *S) {
   S->grouped = take(mb * mp * 4);
   S->item_cap = mb * mp * 4 > 65536 ? mb * mp * 4 : 65536;
   S->tile_desc = take(S->item_cap * 16);
-  S->cand = o;
+  S->records = o;
   S->fixed = o;
 }
 
@@ -435,7 +435,7 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
     S.queues = reinterpret_cast<ScanQueues *>(p + SL.queues);
     // the rest of the slice: two arrays of equal length
     S.cand_cap = (slice - SL.fixed) / (2 * kAlign) * (kAlign / 4);
-    S.rec_key = reinterpret_cast<uint32_t *>(p + SL.cand);
+    S.rec_key = reinterpret_cast<uint32_t *>(p + SL.records);
     S.rec_pos = S.rec_key + S.cand_cap;
     if (hipEventCreateWithFlags(&ix->res[r].done, hipEventDisableTiming) != hipSuccess ||
         hipEventCreate(&ix->res[r].t0) != hipSuccess || hipEventCreate(&ix->res[r].t1) != hipSuccess)
