@@ -43,6 +43,9 @@ def lib():
         L.orc_create.argtypes = [i32, i32, i32, i64, i64, i64]
         L.orc_destroy.argtypes = [vp]
         L.orc_set_centroids.argtypes = [vp, vp]
+        L.orc_set_codebooks.argtypes = [vp, i32, vp]
+        L.orc_pq_encode.argtypes = [vp, i64, vp, vp]
+        L.orc_list_export_codes.argtypes = [vp, i32, vp, vp]
         L.orc_assign.argtypes = [vp, i64, vp, vp]
         L.orc_coarse_scores.argtypes = [vp, vp, vp]
         L.orc_add.argtypes = [vp, i64, vp, vp, vp]
@@ -103,6 +106,27 @@ class OracleIndex:
         c = _f32(centroids)
         assert c.shape == (self.nlist, self.d)
         self._chk(lib().orc_set_centroids(self._h, _ptr(c)), "set_centroids")
+
+    def set_codebooks(self, codebooks) -> None:
+        """codebooks [M][256][d / M]: the lists hold product-quantiser codes from here on."""
+        cb = _f32(codebooks)
+        m = cb.shape[0]
+        assert cb.shape == (m, 256, self.d // m) and self.d % m == 0
+        self.pq_m = m
+        self._chk(lib().orc_set_codebooks(self._h, m, _ptr(cb)), "set_codebooks")
+
+    def pq_encode(self, vecs) -> np.ndarray:
+        y = _f32(vecs).reshape(-1, self.d)
+        out = np.empty((y.shape[0], self.pq_m), dtype=np.uint8)
+        self._chk(lib().orc_pq_encode(self._h, y.shape[0], _ptr(y), _ptr(out)), "pq_encode")
+        return out
+
+    def list_export_codes(self, k: int) -> Tuple[np.ndarray, np.ndarray]:
+        n = self.list_size(k)
+        ids = np.empty(n, dtype=np.int64)
+        codes = np.empty((n, self.pq_m), dtype=np.uint8)
+        lib().orc_list_export_codes(self._h, k, _ptr(ids), _ptr(codes))
+        return ids, codes
 
     def assign(self, vecs) -> np.ndarray:
         y = _f32(vecs)

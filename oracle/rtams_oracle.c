@@ -43,6 +43,22 @@
  *   - Exceed() counts the vectors appended to the list since its last
  *     rearrangement and is a strict ">".
  *
+ * Product-quantised lists (the paper names IVF-PQ beside IVF-Flat as an index
+ * kind whose lists live in the same blocks, without spelling it out; this is
+ * the textbook method, J\'egou et al. 2011, with these readings):
+ *   - the codebooks are given (training is outside the path): M sub-spaces of
+ *     d / M dimensions, 256 entries each;
+ *   - a vector is coded as it is (not its residual to the coarse centroid), so
+ *     one table of sub-distances per query serves all lists;
+ *   - code m of a vector is the entry of codebook m nearest to sub-vector m in
+ *     squared Euclidean distance (for both metrics), computed in the fixed
+ *     arithmetic (double, one fma per dimension, in order), ties to the lowest
+ *     entry: codes are integers both implementations must agree on;
+ *   - the score of a coded vector is the sum over m, in order, of the table
+ *     entry of its code: squared distance (L2) or inner product (IP) between
+ *     the query's sub-vector and the codebook entry, plain double arithmetic.
+ *   orc_set_codebooks / orc_pq_encode / orc_add / orc_search follow that.
+ *
  * Pins (tests/test_oracle_*.py): brute-force exact k-NN when every list is
  * probed; restriction to the probed lists otherwise; membership invariants;
  * closed forms for block counts and slot addresses; the pad-memory figure of
@@ -65,7 +81,8 @@ enum { ORC_OK = 0, ORC_EINVAL = -1, ORC_ESTATE = -2, ORC_EPOOL = -3 };
 typedef struct {
   int64_t n, cap;      /* logical length and capacity of the arrays below   */
   int64_t *ids;        /* [n]                                                */
-  float *x;            /* [n][d] row-major                                   */
+  float *x;            /* [n][d] row-major (flat lists)                      */
+  uint8_t *codes;      /* [n][M] (product-quantised lists)                   */
   int64_t online;      /* vectors appended since the last rearrangement      */
   int32_t *chain;      /* physical block numbers, in logical order           */
   int64_t nchain, chain_cap;
@@ -77,6 +94,8 @@ typedef struct {
   int64_t T_mp;        /* rearrangement threshold in vectors, <= 0: never    */
   float *C;            /* [nlist][d]                                         */
   int has_C;
+  int pq_m;            /* sub-spaces of a product quantiser, 0: flat lists    */
+  float *CB;           /* [M][256][d / M] codebooks                          */
   orc_list *L;
   int64_t npool;       /* |P|: number of blocks in the central pool          */
   int64_t cur_P;       /* blocks 0..cur_P-1 have been handed out at least once */
@@ -153,8 +172,9 @@ orc_index *orc_create(int d, int nlist, int metric, int64_t T_m, int64_t T_mp, i
 void orc_destroy(orc_index *ix) {
   if (!ix) return;
   for (int k = 0; k < ix->nlist; ++k) {
-    free(ix->L[k].ids); free(ix->L[k].x); free(ix->L[k].chain);
+    free(ix->L[k].ids); free(ix->L[k].x); free(ix->L[k].codes); free(ix->L[k].chain);
   }
+  free(ix->CB);
   free(ix->L); free(ix->C); free(ix->free_blocks); free(ix->owner); free(ix->seq); free(ix);
 }
 
@@ -162,6 +182,42 @@ int orc_set_centroids(orc_index *ix, const float *C) {
   if (!ix || !C) return ORC_EINVAL;
   memcpy(ix->C, C, (size_t)ix->nlist * ix->d * sizeof(float));
   ix->has_C = 1;
+  return ORC_OK;
+}
+
+/* Codebooks of a product quantiser: CB [M][256][d / M].  Only before the
+ * first vector is added. */
+int orc_set_codebooks(orc_index *ix, int M, const float *CB) {
+  if (!ix || !CB || M < 1 || ix->d % M != 0) return ORC_EINVAL;
+  if (ix->ntotal > 0) return ORC_ESTATE;
+  free(ix->CB);
+  ix->CB = (float *)malloc((size_t)256 * ix->d * sizeof(float));
+  memcpy(ix->CB, CB, (size_t)256 * ix->d * sizeof(float));
+  ix->pq_m = M;
+  return ORC_OK;
+}
+
+/* Code of sub-vector m: nearest codebook entry, fixed arithmetic, ties low. */
+static uint8_t pq_code(const orc_index *ix, int m, const float *ysub) {
+  const int ds = ix->d / ix->pq_m;
+  const float *cb = ix->CB + (size_t)m * 256 * ds;
+  int best = 0;
+  double bs = coarse_score(ORC_L2, ds, ysub, cb);
+  for (int c = 1; c < 256; ++c) {
+    double s = coarse_score(ORC_L2, ds, ysub, cb + (size_t)c * ds);
+    if (s < bs) { bs = s; best = c; }
+  }
+  return (uint8_t)best;
+}
+
+/* Codes of n vectors: out [n][M]. */
+int orc_pq_encode(const orc_index *ix, int64_t n, const float *Y, uint8_t *out) {
+  if (!ix || ix->pq_m == 0) return ORC_ESTATE;
+  const int M = ix->pq_m, ds = ix->d / M;
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < n; ++i)
+    for (int m = 0; m < M; ++m)
+      out[(size_t)i * M + m] = pq_code(ix, m, Y + (size_t)i * ix->d + (size_t)m * ds);
   return ORC_OK;
 }
 
@@ -249,12 +305,13 @@ int orc_rearrange(orc_index *ix, int k) {
 
 /* ---------------------------------------------------------------- insertion */
 
-static void list_reserve(orc_list *l, int d, int64_t need) {
+static void list_reserve(orc_list *l, int d, int pq_m, int64_t need) {
   if (need <= l->cap) return;
   int64_t cap = l->cap ? l->cap : 16;
   while (cap < need) cap *= 2;
   l->ids = (int64_t *)realloc(l->ids, (size_t)cap * sizeof(int64_t));
-  l->x = (float *)realloc(l->x, (size_t)cap * d * sizeof(float));
+  if (pq_m) l->codes = (uint8_t *)realloc(l->codes, (size_t)cap * pq_m);
+  else l->x = (float *)realloc(l->x, (size_t)cap * d * sizeof(float));
   l->cap = cap;
 }
 
@@ -284,6 +341,11 @@ int orc_add(orc_index *ix, int64_t n, const float *Y, const int64_t *ids, const 
     if (need > (ix->npool - ix->cur_P) + ix->nfree) { free(a); return ORC_EPOOL; }
   }
 
+  uint8_t *codes = NULL;
+  if (ix->pq_m) {
+    codes = (uint8_t *)malloc((size_t)n * ix->pq_m);
+    orc_pq_encode(ix, n, Y, codes);
+  }
   int64_t gid = ix->ntotal;             /* running total: base of the new ids */
   for (int64_t i = 0; i < n; ++i) {
     int k = a[i];
@@ -292,9 +354,9 @@ int orc_add(orc_index *ix, int64_t n, const float *Y, const int64_t *ids, const 
     int64_t mid = did / ix->T_m, moff = did % ix->T_m;
     if (mid >= l->nchain) {             /* the chain has no block for this slot yet */
       /* only the first slot of a block can open it */
-      if (moff != 0) { free(a); return ORC_EINVAL; }
+      if (moff != 0) { free(a); free(codes); return ORC_EINVAL; }
       int32_t b;
-      if (take_block(ix, &b) != ORC_OK) { free(a); return ORC_EPOOL; }
+      if (take_block(ix, &b) != ORC_OK) { free(a); free(codes); return ORC_EPOOL; }
       if (l->nchain == l->chain_cap) {
         l->chain_cap = l->chain_cap ? 2 * l->chain_cap : 4;
         l->chain = (int32_t *)realloc(l->chain, (size_t)l->chain_cap * sizeof(int32_t));
@@ -302,9 +364,10 @@ int orc_add(orc_index *ix, int64_t n, const float *Y, const int64_t *ids, const 
       ix->owner[b] = k; ix->seq[b] = (int32_t)l->nchain;
       l->chain[l->nchain++] = b;        /* link behind the chain's last block */
     }
-    list_reserve(l, ix->d, did + 1);
+    list_reserve(l, ix->d, ix->pq_m, did + 1);
     l->ids[did] = ids ? ids[i] : gid + i;
-    memcpy(l->x + (size_t)did * ix->d, Y + (size_t)i * ix->d, (size_t)ix->d * sizeof(float));
+    if (ix->pq_m) memcpy(l->codes + (size_t)did * ix->pq_m, codes + (size_t)i * ix->pq_m, (size_t)ix->pq_m);
+    else memcpy(l->x + (size_t)did * ix->d, Y + (size_t)i * ix->d, (size_t)ix->d * sizeof(float));
     l->n = did + 1;
     l->online++;
   }
@@ -316,6 +379,7 @@ int orc_add(orc_index *ix, int64_t n, const float *Y, const int64_t *ids, const 
     for (int k = 0; k < ix->nlist; ++k)
       if (ix->L[k].online > ix->T_mp) orc_rearrange(ix, k);
   free(a);
+  free(codes);
   return ORC_OK;
 }
 
@@ -369,14 +433,29 @@ int orc_search(const orc_index *ix, int64_t nq, const float *Q, int k, int nprob
     for (int p = 0; p < nprobe; ++p) total += ix->L[pl[p]].n;
     cand *cs = (cand *)malloc((size_t)(total > 0 ? total : 1) * sizeof(cand));
     int64_t m = 0;
+    double *lut = NULL;  /* [M][256]: query's sub-vector against every codebook entry */
+    if (ix->pq_m) {
+      const int M = ix->pq_m, ds = ix->d / M;
+      lut = (double *)malloc((size_t)M * 256 * sizeof(double));
+      for (int s = 0; s < M; ++s)
+        for (int c = 0; c < 256; ++c)
+          lut[(size_t)s * 256 + c] = fine_score(ix->metric, ds, ix->CB + ((size_t)s * 256 + c) * ds, q + (size_t)s * ds);
+    }
     for (int p = 0; p < nprobe; ++p) {
       const orc_list *l = &ix->L[pl[p]];
       for (int64_t e = 0; e < l->n; ++e) {
-        cs[m].s = fine_score(ix->metric, ix->d, l->x + (size_t)e * ix->d, q);
+        if (ix->pq_m) {
+          double acc = 0.0;
+          for (int s = 0; s < ix->pq_m; ++s) acc = acc + lut[(size_t)s * 256 + l->codes[(size_t)e * ix->pq_m + s]];
+          cs[m].s = acc;
+        } else {
+          cs[m].s = fine_score(ix->metric, ix->d, l->x + (size_t)e * ix->d, q);
+        }
         cs[m].id = l->ids[e];
         ++m;
       }
     }
+    free(lut);
     g_metric_for_sort = ix->metric;
     qsort(cs, (size_t)m, sizeof(cand), cand_cmp);
     for (int r = 0; r < k; ++r) {
@@ -407,6 +486,13 @@ void orc_list_export(const orc_index *ix, int k, int64_t *ids, float *x) {
   const orc_list *l = &ix->L[k];
   if (ids) memcpy(ids, l->ids, (size_t)l->n * sizeof(int64_t));
   if (x) memcpy(x, l->x, (size_t)l->n * ix->d * sizeof(float));
+}
+
+/* Codes of list k in list order: codes [n][M]. */
+void orc_list_export_codes(const orc_index *ix, int k, int64_t *ids, uint8_t *codes) {
+  const orc_list *l = &ix->L[k];
+  if (ids) memcpy(ids, l->ids, (size_t)l->n * sizeof(int64_t));
+  if (codes && ix->pq_m) memcpy(codes, l->codes, (size_t)l->n * ix->pq_m);
 }
 
 void orc_list_chain(const orc_index *ix, int k, int32_t *chain) {
