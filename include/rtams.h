@@ -63,6 +63,9 @@ typedef struct rtams_config {
   int32_t max_nprobe;    /* largest nprobe, at most 1024 and at most nlist */
   int32_t max_add_batch; /* vectors handled per internal insertion round; larger adds are
                             split into rounds on the same stream */
+  int32_t pq_m;          /* 0: the lists hold the vectors (IVF-Flat).  M > 0: they hold
+                            product-quantiser codes, M bytes per vector (IVF-PQ): M a
+                            multiple of 4, at most 64, dividing d */
 } rtams_config;
 
 typedef struct rtams_stats {
@@ -104,6 +107,18 @@ int rtams_destroy(rtams_index *ix);
  * algorithm, inputs); producing them is the caller's business.  May be called
  * once, before the first add. */
 int rtams_set_centroids(rtams_index *ix, const float *d_centroids, void *hip_stream);
+
+/* Product-quantised lists (pq_m > 0 only; the paper names IVF-PQ beside
+ * IVF-Flat as a kind of list its blocks hold, without spelling it out; this is
+ * the textbook method).  d_codebooks [pq_m][256][d / pq_m] fp32, copied into
+ * the pool; training them is outside this library.  A vector is coded as it is
+ * (not its residual to the coarse centroid): code m is the entry of codebook m
+ * nearest to its m-th sub-vector in squared Euclidean distance (both metrics),
+ * ties to the lowest entry.  A search scores a coded vector by the sum over m
+ * of the squared distance (L2) or inner product (IP) between the query's m-th
+ * sub-vector and the entry its code names.  ESTATE once vectors are in, or when
+ * pq_m is 0; add and search return ESTATE until the codebooks are set. */
+int rtams_set_codebooks(rtams_index *ix, const float *d_codebooks, void *hip_stream);
 
 /* Insertion algorithm of the paper: nearest centroid of each vector, atomic
  * reservation of the next slot of that list (did -> block did / T_m, offset
@@ -169,6 +184,12 @@ int rtams_assign(rtams_index *ix, int64_t n, const float *d_vecs, int32_t *d_out
  * overflow); RTAMS_OK if none.  Does not synchronise. */
 int rtams_poll_error(rtams_index *ix);
 const char *rtams_last_error(void);
+/* Codes of a product-quantised list in list order: d_ids [cap] int64 (or NULL),
+ * d_codes [cap][pq_m] bytes (or NULL), *n_out = entries of the list (at most
+ * cap are written).  Synchronises the stream.  ESTATE for flat lists. */
+int rtams_list_export_codes(rtams_index *ix, int32_t list, int64_t cap, int64_t *d_ids, uint8_t *d_codes,
+                            int64_t *n_out, void *hip_stream);
+
 /* Measured duration of the list-scan kernel: with the parameter "profile_scan"
  * set to 1, every search brackets its scan launch with two HIP events on the
  * caller's stream; this call adds up the pairs of the requests that have

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librtams.so")
-SOURCES = ["rtams.hip", "coarse.hip", "coarse_mfma.hip", "insert.hip", "search.hip", "rearrange.hip", "maint.hip"]
+SOURCES = ["rtams.hip", "coarse.hip", "coarse_mfma.hip", "insert.hip", "pq.hip", "search.hip", "rearrange.hip", "maint.hip"]
 HEADERS = ["rtams_dev.h", "rtams_launch.h", os.path.join("..", "..", "include", "rtams.h")]
 
 # packed-fp32 instructions are switched off for every device compilation

@@ -37,7 +37,7 @@ inline size_t up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Byte offsets of everything in front of the blocks.
 struct Layout {
-  size_t ctrl, hook, centroids, cnorm, tc_min, tc_cnt, tc_col, tc_val, tile_rows, reserved_len, visible_len, online, nblk, exceed, seg_dir;
+  size_t ctrl, hook, centroids, cnorm, codebooks, tc_min, tc_cnt, tc_col, tc_val, tile_rows, reserved_len, visible_len, online, nblk, exceed, seg_dir;
   size_t ins_assign, ins_did, ins_pscore, ins_pidx, part_cap;
   size_t rearr_head, rearr_arrays;
   size_t fixed_end;          // end of the part that does not depend on the block count
@@ -58,6 +58,8 @@ bool config_ok(const rtams_config *c, bool need_memory) {
   if (c->d <= 0 || c->d % 4 != 0 || c->d > 2048)
     return fail(RTAMS_EINVAL, "d must be a multiple of 4 in 4..2048, got %d", c->d), false;
   if (c->nlist <= 0) return fail(RTAMS_EINVAL, "nlist must be positive"), false;
+  if (c->pq_m < 0 || (c->pq_m > 0 && (c->pq_m % 4 != 0 || c->pq_m > 64 || c->d % c->pq_m != 0)))
+    return fail(RTAMS_EINVAL, "pq_m must be 0, or a multiple of 4 up to 64 that divides d; got %d", c->pq_m), false;
   if (c->metric != RTAMS_L2 && c->metric != RTAMS_IP) return fail(RTAMS_EINVAL, "unknown metric"), false;
   if (c->block_vecs <= 0 || c->block_vecs % kWave != 0)
     return fail(RTAMS_EINVAL, "block_vecs must be a positive multiple of 64, got %d", c->block_vecs), false;
@@ -86,6 +88,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
   L->hook = take(kHookBytes);
   L->centroids = take(nl * c->d * sizeof(float));
   L->cnorm = take(nl * sizeof(float));
+  L->codebooks = take(c->pq_m > 0 ? (size_t)256 * c->d * sizeof(float) : 0);
   L->reserved_len = take(nl * 4);
   L->visible_len = take(nl * 4);
   L->online = take(nl * 4);
@@ -113,7 +116,8 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
   L->fixed_end = o;
   L->ids_off = kHeaderBytes;
   L->vec_off = kHeaderBytes + (uint32_t)c->block_vecs * 8u;
-  L->block_stride = up((size_t)L->vec_off + (size_t)c->block_vecs * c->d * 4, kAlign);
+  // a vector takes d floats, or pq_m code bytes
+  L->block_stride = up((size_t)L->vec_off + (size_t)c->block_vecs * (c->pq_m > 0 ? (size_t)c->pq_m : (size_t)c->d * 4), kAlign);
   if (blocks < 0) {
     // per block: the block itself, 2 table entries, a free-stack entry and a mark
     size_t slack = 4 * kAlign + nl * kTableBase * 4;
@@ -131,7 +135,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
 }
 
 struct ScratchLayout {
-  size_t scores, approx, probe_list, probe_len, probe_off, qbase, qtotal, bound, rec_cnt, cursor, records, fixed;
+  size_t scores, approx, probe_list, probe_len, probe_off, qbase, qtotal, bound, rec_cnt, cursor, lut, records, fixed;
   size_t list_cnt, list_len, pair_slot, grouped, tile_desc, queues, item_cap;
 };
 
@@ -141,6 +145,7 @@ void lay_out_scratch(const rtams_config *c, ScratchLayout *S) {
   size_t mb = (size_t)c->max_batch, mp = (size_t)c->max_nprobe;
   S->scores = take(mb * c->nlist * 8);
   S->approx = take(mb * c->nlist * 4);
+  S->lut = take(c->pq_m > 0 ? mb * c->pq_m * 256 * 4 : 0);
   S->probe_list = take(mb * mp * 4);
   S->probe_len = take(mb * mp * 4);
   S->probe_off = take(mb * mp * 4);
@@ -198,6 +203,7 @@ struct rtams_index {
   std::atomic<int64_t> scan_items_per_pair{8};   // work items the plan may cut per (query, list) pair
   std::atomic<int64_t> scan_max_items{32768};    // ... and per request
   std::atomic<int64_t> profile_scan{0};
+  bool has_codebooks = false;
   std::atomic<int64_t> use_mfma{1};  // matrix-core filter in front of the exact coarse arithmetic
   std::mutex prof_mutex;
   double scan_ms = 0.0;      // sum of measured scan-kernel durations
@@ -358,6 +364,8 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   D.ctrl = reinterpret_cast<Ctrl *>(base + L.ctrl);
   D.centroids = reinterpret_cast<float *>(base + L.centroids);
   D.cnorm = reinterpret_cast<float *>(base + L.cnorm);
+  D.codebooks = reinterpret_cast<float *>(base + L.codebooks);
+  D.pq_m = cfg->pq_m;
   D.reserved_len = reinterpret_cast<uint32_t *>(base + L.reserved_len);
   D.visible_len = reinterpret_cast<uint32_t *>(base + L.visible_len);
   D.online = reinterpret_cast<uint32_t *>(base + L.online);
@@ -418,6 +426,7 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
     SearchScratch &S = ix->res[r].s;
     S.scores = reinterpret_cast<double *>(p + SL.scores);
     S.approx = reinterpret_cast<float *>(p + SL.approx);
+    S.lut = reinterpret_cast<float *>(p + SL.lut);
     S.probe_list = reinterpret_cast<int32_t *>(p + SL.probe_list);
     S.probe_len = reinterpret_cast<uint32_t *>(p + SL.probe_len);
     S.probe_off = reinterpret_cast<uint32_t *>(p + SL.probe_off);
@@ -480,9 +489,23 @@ int rtams_set_centroids(rtams_index *ix, const float *d_centroids, void *hip_str
   return leave_data_stream(ix, s);
 }
 
+int rtams_set_codebooks(rtams_index *ix, const float *d_codebooks, void *hip_stream) {
+  if (!ix || !d_codebooks) return fail(RTAMS_EINVAL, "NULL argument");
+  if (ix->cfg.pq_m == 0) return fail(RTAMS_ESTATE, "the index holds flat lists (pq_m is 0)");
+  std::lock_guard<std::mutex> g(ix->data_mutex);
+  if (ix->ntotal_host > 0) return fail(RTAMS_ESTATE, "codebooks cannot change once vectors are in");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  int rc = enter_data_stream(ix, s);
+  if (rc) return rc;
+  HIP_TRY(hipMemcpyAsync(ix->dev.codebooks, d_codebooks, (size_t)256 * ix->cfg.d * 4, hipMemcpyDeviceToDevice, s));
+  ix->has_codebooks = true;
+  return leave_data_stream(ix, s);
+}
+
 int rtams_add(rtams_index *ix, int64_t n, const float *d_vecs, const int64_t *d_ids, void *hip_stream) {
   if (!ix || n < 0 || (n > 0 && !d_vecs)) return fail(RTAMS_EINVAL, "bad argument to add");
   if (!ix->has_centroids) return fail(RTAMS_ESTATE, "add before set_centroids");
+  if (ix->cfg.pq_m > 0 && !ix->has_codebooks) return fail(RTAMS_ESTATE, "add before set_codebooks");
   if (n == 0) return RTAMS_OK;
   std::lock_guard<std::mutex> g(ix->data_mutex);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -510,7 +533,8 @@ int rtams_add(rtams_index *ix, int64_t n, const float *d_vecs, const int64_t *d_
     const float *Y = d_vecs + (size_t)o * D.d;
     assign_round(ix, m, Y, true, ix->ins.assign, s);
     launch_open(D, s);
-    launch_fill(D, m, Y, d_ids ? d_ids + o : nullptr, ix->ntotal_host + o, ix->ins, s);
+    if (D.pq_m > 0) launch_pq_fill(D, m, Y, d_ids ? d_ids + o : nullptr, ix->ntotal_host + o, ix->ins, s);
+    else launch_fill(D, m, Y, d_ids ? d_ids + o : nullptr, ix->ntotal_host + o, ix->ins, s);
     launch_publish(D, s);
   }
   HIP_TRY(hipGetLastError());
@@ -532,6 +556,7 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   if (nprobe < 1 || nprobe > ix->cfg.max_nprobe)
     return fail(RTAMS_EINVAL, "nprobe %d outside 1..max_nprobe %d", nprobe, ix->cfg.max_nprobe);
   if (!ix->has_centroids) return fail(RTAMS_ESTATE, "search before set_centroids");
+  if (ix->cfg.pq_m > 0 && !ix->has_codebooks) return fail(RTAMS_ESTATE, "search before set_codebooks");
   if (nq == 0) return RTAMS_OK;
   if (!d_queries || !d_out_dist || !d_out_ids) return fail(RTAMS_EINVAL, "NULL buffer");
   std::shared_lock<std::shared_mutex> in_flight(ix->fence_mutex);
@@ -543,12 +568,15 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   // a rearrangement is switching block tables: start behind its last switch
   if (ix->fence_cur) (void)hipStreamWaitEvent(s, ix->fence_cur, 0);
   coarse_and_plan(ix, nq, d_queries, nprobe, S, nullptr, s);
+  if (D.pq_m > 0) launch_pq_lut(D, nq, d_queries, S.lut, s);
   // The grouped scan is cut into work items of bounded size, one wavefront each;
   // the budget of items grows with the request so that a small batch still
   // spreads over the chip and a large one is not drowned in per-item overhead.
-  int64_t budget = nq * nprobe * ix->scan_items_per_pair.load(std::memory_order_relaxed);
+  // (quantised lists: one item per (query, list) pair as a rule, see the scan over codes)
+  int64_t budget = nq * nprobe * (D.pq_m > 0 ? 1 : ix->scan_items_per_pair.load(std::memory_order_relaxed));
   const int64_t cap = ix->scan_max_items.load(std::memory_order_relaxed);
   if (budget > cap) budget = cap;
+  if (budget < nq * nprobe) budget = nq * nprobe;  // a (query, list) pair is at least one item
   if (budget < 1024) budget = 1024;
   launch_group(D, nq, nprobe, ix->cfg.max_nprobe, k, d_queries, (int)budget, S, s);
   const bool timed = ix->profile_scan.load(std::memory_order_relaxed) != 0;
@@ -701,8 +729,27 @@ int rtams_list_export(rtams_index *ix, int32_t list, int64_t cap, int64_t *d_ids
   HIP_TRY(hipMemcpy(&len, ix->dev.visible_len + list, 4, hipMemcpyDeviceToHost));
   if (n_out) *n_out = len;
   if ((int64_t)len > cap) return fail(RTAMS_EINVAL, "list %d holds %u vectors, cap is %lld", list, len, (long long)cap);
+  if (ix->cfg.pq_m > 0 && d_vecs) return fail(RTAMS_ESTATE, "the lists hold codes: use rtams_list_export_codes");
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   launch_export(ix->dev, list, len, d_ids, d_vecs, s);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipStreamSynchronize(s));
+  return RTAMS_OK;
+}
+
+int rtams_list_export_codes(rtams_index *ix, int32_t list, int64_t cap, int64_t *d_ids, uint8_t *d_codes,
+                            int64_t *n_out, void *hip_stream) {
+  if (!ix || list < 0 || list >= ix->cfg.nlist || cap < 0) return fail(RTAMS_EINVAL, "bad argument");
+  if (ix->cfg.pq_m == 0) return fail(RTAMS_ESTATE, "the index holds flat lists (pq_m is 0)");
+  std::lock_guard<std::mutex> g(ix->data_mutex);
+  int rc = sync_data(ix);
+  if (rc) return rc;
+  uint32_t len = 0;
+  HIP_TRY(hipMemcpy(&len, ix->dev.visible_len + list, 4, hipMemcpyDeviceToHost));
+  if (n_out) *n_out = len;
+  if ((int64_t)len > cap) return fail(RTAMS_EINVAL, "list %d holds %u vectors, cap is %lld", list, len, (long long)cap);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  launch_pq_export(ix->dev, list, len, d_ids, d_codes, s);
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipStreamSynchronize(s));
   return RTAMS_OK;

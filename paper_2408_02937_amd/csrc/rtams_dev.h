@@ -53,6 +53,7 @@ struct HostMirror {
 
 struct Dev {
   int32_t d, nlist, metric, T_m;
+  int32_t pq_m;             // 0: flat lists; M > 0: product-quantiser codes, M bytes per vector
   int32_t d4;               // d / 4
   int32_t groups_per_block; // T_m / 64
   uint32_t nblocks;         // |P|
@@ -66,6 +67,7 @@ struct Dev {
   HostMirror *mirror;       // pinned host memory, device-visible
   float *centroids;         // [nlist][d]
   float *cnorm;             // [nlist] squared norms of the centroids (fp32)
+  float *codebooks;         // [pq_m][256][d / pq_m] (product-quantised lists only)
   uint32_t *reserved_len;   // [nlist] next free position (atomicAdd target)
   uint32_t *visible_len;    // [nlist] length searches may read
   uint32_t *online;         // [nlist] vectors since the last rearrangement
@@ -106,6 +108,16 @@ __device__ inline int64_t *block_ids(const Dev &D, uint32_t b) {
 }
 __device__ inline float4 *block_vecs(const Dev &D, uint32_t b) {
   return reinterpret_cast<float4 *>(D.blocks + (size_t)b * D.block_stride + D.vec_off);
+}
+
+// Product-quantised lists keep the same shape with 4 codes (one 32-bit word) as the chunk:
+// word index of codes 4c..4c+3 of the vector at offset moff.
+__device__ inline uint32_t *block_codes(const Dev &D, uint32_t b) {
+  return reinterpret_cast<uint32_t *>(D.blocks + (size_t)b * D.block_stride + D.vec_off);
+}
+__device__ inline size_t code_word_index(const Dev &D, uint32_t moff, int c) {
+  uint32_t group = moff / kWave, lane = moff % kWave;
+  return ((size_t)group * (D.pq_m / 4) + c) * kWave + lane;
 }
 
 // Interleaved vector layout inside a block (the paper's equation for "mv",

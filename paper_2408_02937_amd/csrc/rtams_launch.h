@@ -36,6 +36,7 @@ struct SearchScratch {
   uint4 *tile_desc;     // [item_cap] {list, first pair of the tile, pairs of the tile, segment} per item
   uint32_t item_cap;
   ScanQueues *queues;   // work items of this request, split into one queue per XCD
+  float *lut;           // [max_batch][pq_m][256] sub-scores of the queries against the codebooks (PQ lists)
   uint32_t *rec_key;    // survivors: key of the score (smaller is better) ...
   uint32_t *rec_pos;    // ... and position among the query's candidates
   unsigned long long cand_cap;  // entries of each of the two arrays
@@ -128,6 +129,12 @@ void launch_scan(const Dev &D, int64_t nq, int max_nprobe, const float *Q, int i
                  const SearchScratch &S, hipStream_t s);
 void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
                    const SearchScratch &S, float *out_dist, int64_t *out_ids, hipStream_t s);
+
+// pq.hip -----------------------------------------------------------------------
+void launch_pq_fill(const Dev &D, int64_t n, const float *Y, const int64_t *ids, int64_t id_base,
+                    const InsertScratch &S, hipStream_t s);
+void launch_pq_lut(const Dev &D, int64_t nq, const float *Q, float *lut, hipStream_t s);
+void launch_pq_export(const Dev &D, int list, int64_t n, int64_t *ids, uint8_t *codes, hipStream_t s);
 
 // rearrange.hip --------------------------------------------------------------
 void launch_rearr_plan(const Dev &D, const RearrangeScratch &R, int list, hipStream_t s);

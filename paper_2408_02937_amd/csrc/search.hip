@@ -406,6 +406,44 @@ __device__ void sample_scores(const Dev &D, int nprobe, int max_nprobe, int q, u
   // groups the lists did not have stay at the worst key (set by the caller)
 }
 
+// The same sample over product-quantiser codes: a vector's score is the sum, in the order of the
+// sub-spaces, of the request's table entries that its codes name (the table stays in global
+// memory here: a few thousand look-ups per query).
+__device__ void pq_sample_scores(const Dev &D, int nprobe, int max_nprobe, int q, uint32_t want_groups,
+                                 const SearchScratch &S, uint32_t *skey) {
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int words = D.pq_m / 4;
+  const float *lut = S.lut + (size_t)q * D.pq_m * 256;
+  const uint32_t gpb = (uint32_t)D.groups_per_block;
+  uint32_t g_first = 0;
+  for (int p = 0; p < nprobe && g_first < want_groups; ++p) {  // uniform over the workgroup
+    const size_t o = (size_t)q * max_nprobe + p;
+    const int list = S.probe_list[o];
+    const uint32_t len = S.probe_len[o];
+    uint32_t groups = (len + kWave - 1) / kWave;
+    const uint32_t have = D.nblk[list] * gpb;  // never index the block table past the chain
+    if (groups > have) groups = have;
+    if (groups > want_groups - g_first) groups = want_groups - g_first;
+    for (uint32_t g = (uint32_t)wave; g < groups; g += kGroupThreads / kWave) {
+      const uint32_t b = (uint32_t)*table_entry(D, list, g / gpb);
+      const uint32_t *__restrict__ x = block_codes(D, b) + (size_t)(g % gpb) * words * kWave + lane;
+      float acc = 0.f;
+      for (int c = 0; c < words; ++c) {
+        const uint32_t w = x[(size_t)c * kWave];
+        const float *t = lut + (size_t)c * 4 * 256;
+        acc += t[w & 255u];
+        acc += t[256 + ((w >> 8) & 255u)];
+        acc += t[512 + ((w >> 16) & 255u)];
+        acc += t[768 + (w >> 24)];
+      }
+      const uint32_t v = g * kWave + lane;
+      skey[(size_t)(g_first + g) * kWave + lane] =
+          v < len ? key_of_float((D.metric == 0 ? acc : -acc) + 0.0f) : 0xFFFFFFFFu;
+    }
+    g_first += groups;
+  }
+}
+
 __device__ void sample_bound(const Dev &D, int nprobe, int max_nprobe, int k, const float *__restrict__ Q,
                              const SearchScratch &S) {
   __shared__ float4 qv[512];  // the query (d <= 2048)
@@ -424,7 +462,8 @@ __device__ void sample_bound(const Dev &D, int nprobe, int max_nprobe, int k, co
   for (int c = tid; c < D.d4; c += kGroupThreads) qv[c] = reinterpret_cast<const float4 *>(Q + (size_t)q * D.d)[c];
   for (int i = tid; i < (int)(want_groups * kWave); i += kGroupThreads) skey[i] = 0xFFFFFFFFu;
   __syncthreads();
-  if (D.metric == 0) sample_scores<0>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
+  if (D.pq_m > 0) pq_sample_scores(D, nprobe, max_nprobe, q, want_groups, S, skey);
+  else if (D.metric == 0) sample_scores<0>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
   else sample_scores<1>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
   __syncthreads();
   // k-th smallest key of the sample; with fewer than k candidates in it, it is the worst key
@@ -447,8 +486,8 @@ __device__ void sample_bound(const Dev &D, int nprobe, int max_nprobe, int k, co
 // prefix sums over the lists of the pair counts, the work-item counts and the
 // work, then the item descriptors, the split of the items over the 8 XCDs and
 // the grouped pair array.  A work item is (list, segment of seg_groups
-// 64-vector groups, tile of up to kScanTileQueries of the queries probing the
-// list); one wavefront walks it.  The items of one segment follow each other, so
+// 64-vector groups, tile of up to tile_q of the queries probing the list: 8 for
+// flat lists, 1 for product-quantised ones); one wavefront walks it.  The items of one segment follow each other, so
 // they run at the same time on the same CU or on its neighbours and the segment
 // comes from HBM once.  Segments bound the work of one item, so that long lists
 // spread over many wavefronts.  The segment length is the shortest power of two
@@ -486,7 +525,7 @@ __device__ inline void wg_scan3(uint32_t &a, uint32_t &b, unsigned long long &c,
 }
 
 __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int nprobe, int max_nprobe, int k,
-                                                         const float *__restrict__ Q,
+                                                         uint32_t tile_q, const float *__restrict__ Q,
                                                          uint32_t item_budget, uint32_t max_per_xcd,
                                                          SearchScratch S) {
   if (blockIdx.x > 0) {  // uniform over the workgroup: this one sets the bound of query blockIdx.x - 1
@@ -526,7 +565,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
       list_len[l] = len;
       if (!c) continue;
       const uint32_t groups = (len + kWave - 1) / kWave;
-      const uint32_t tiles = (c + kScanTileQueries - 1) / kScanTileQueries;
+      const uint32_t tiles = (c + tile_q - 1) / tile_q;
 #pragma unroll
       for (int e = 0; e < kSegChoices; ++e) {
         const uint32_t sg = 2u << e;
@@ -556,7 +595,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
       if (!c) continue;
       const uint32_t groups = (list_len[l] + kWave - 1) / kWave;
       np += c;
-      ni += (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
+      ni += (groups ? (groups + seg - 1) / seg : 1u) * ((c + tile_q - 1) / tile_q);
       wk += (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
     }
     uint32_t inp = np, ini = ni;
@@ -567,7 +606,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
     const unsigned long long total_work = s_c[kGroupThreads - 1];
     uint32_t pstart = inp - np, istart = ini - ni;
     unsigned long long wstart = iwk - wk;
-    // XCD x starts at the list inside which the work prefix passes x/8 of the total
+    // XCD x starts at the item at which the work prefix passes x/8 of the total
     if (tid < 9) s_begin[tid] = tid == 8 ? total_items : 0u;
     __syncthreads();
     {
@@ -578,11 +617,12 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
         if (!c) continue;
         const uint32_t groups = (list_len[l] + kWave - 1) / kWave;
         const unsigned long long w = (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
-        for (uint32_t x = 1; x < 8; ++x) {
+        const uint32_t n = (groups ? (groups + seg - 1) / seg : 1u) * ((c + tile_q - 1) / tile_q);
+        for (uint32_t x = 1; x < 8; ++x) {  // the cut falls inside this list: at the item the same share of it ends at
           const unsigned long long cut = total_work * x / 8;
-          if (ws <= cut && cut < ws + w) s_begin[x] = is;
+          if (ws <= cut && cut < ws + w) s_begin[x] = is + (uint32_t)((cut - ws) * n / w);
         }
-        is += (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
+        is += n;
         ws += w;
       }
     }
@@ -593,10 +633,22 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
     __syncthreads();
     uint32_t longest = 0;
     for (uint32_t x = 0; x < 8; ++x) longest = max(longest, s_begin[x + 1] - s_begin[x]);
+    if (longest > max_per_xcd) {  // uniform.  Items of very unequal cost: give every XCD the same number instead
+      __syncthreads();
+      if (tid < 9) s_begin[tid] = (uint32_t)((unsigned long long)total_items * tid / 8);
+      __syncthreads();
+      longest = (total_items + 7) / 8;
+    }
     const bool fits = total_items <= S.item_cap && longest <= max_per_xcd;
     if (!fits && choice + 1 < kSegChoices + 8) continue;  // coarser segments (bounded: lengths are 32 bit)
     if (tid < 9) Qs->begin[tid] = s_begin[tid];
-    if (tid == 0) Qs->seg_groups = fits ? seg : 0u;  // 0: nothing is scanned (cannot happen with sane sizes)
+    if (tid == 0) {
+      Qs->seg_groups = fits ? seg : 0u;
+      if (!fits) {  // more tiles than the request's item descriptors hold: nothing is scanned, and the caller is told
+        atomicCAS(&D.ctrl->error, 0, -6);
+        D.mirror->error = -6;
+      }
+    }
     s_istart[tid] = istart;  // where the items of this thread's lists start
     for (int l = l0; l < l1; ++l) {
       const uint32_t c = list_cnt[l];
@@ -628,7 +680,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
           if (!c) continue;
           const uint32_t groups = (list_len[l] + kWave - 1) / kWave;
           const uint32_t segs = groups ? (groups + seg - 1) / seg : 1u;
-          const uint32_t tiles = (c + kScanTileQueries - 1) / kScanTileQueries;
+          const uint32_t tiles = (c + tile_q - 1) / tile_q;
           const uint32_t n = segs * tiles;
           if (j < base + n) {
             const uint32_t r = j - base, stop = min(j_end, base + n);
@@ -881,6 +933,92 @@ __global__ __launch_bounds__(kScanWaves * kWave) void k_scan(Dev D, int max_npro
     case 6: scan_item<METRIC, 6>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
     case 7: scan_item<METRIC, 7>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
     default: scan_item<METRIC, 8>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+  }
+}
+
+// ------------------------------------------------- scan of quantised lists
+// Product-quantised lists: a work item is (list, segment, ONE query), a workgroup is one
+// wavefront.  It copies the query's table of sub-scores (M x 256 floats, computed once per
+// request) into LDS and walks the segment two groups of 64 vectors at a time, lane = vector:
+// per word of 4 codes one coalesced 256-byte load per group and four LDS look-ups per vector,
+// added up in the order of the sub-spaces.  Survivors of the query's bound are appended to its
+// records exactly as in the scan of flat lists.  (Segments are longer here: the table is 1 KiB
+// per sub-space, a group of 64 coded vectors 64 bytes per sub-space.)
+__global__ __launch_bounds__(kWave) void k_pq_scan(Dev D, int max_nprobe, SearchScratch S) {
+  extern __shared__ float pq_lut[];  // [M][256]
+  const ScanQueues *Qs = S.queues;
+  const uint32_t x = blockIdx.x % kXcds;
+  const uint32_t item = Qs->begin[x] + blockIdx.x / kXcds;
+  if (item >= Qs->begin[x + 1]) return;
+  const uint32_t seg = Qs->seg_groups;
+  if (seg == 0) return;
+  const int lane = threadIdx.x;
+  const uint4 desc = S.tile_desc[item];
+  const int list = __builtin_amdgcn_readfirstlane((int)desc.x);
+  const uint32_t first = (uint32_t)__builtin_amdgcn_readfirstlane((int)desc.y);
+  if (__builtin_amdgcn_readfirstlane((int)desc.z) == 0) return;
+  const uint32_t g_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)desc.w) * seg;
+  const uint32_t pk = S.grouped[first];
+  const uint32_t q = pk >> 10;
+  const size_t o = (size_t)q * max_nprobe + (pk & 1023u);
+  const uint32_t len = S.probe_len[o], off = S.probe_off[o];
+  const unsigned long long base = S.qbase[q];
+  const uint32_t bound = __hip_atomic_load(&S.bound[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const int M = D.pq_m, words = M / 4;
+  {
+    const float4 *src = reinterpret_cast<const float4 *>(S.lut + (size_t)q * M * 256);
+    float4 *dst = reinterpret_cast<float4 *>(pq_lut);
+    for (int i = lane; i < M * 64; i += kWave) dst[i] = src[i];
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+
+  uint32_t ngroups = (len + kWave - 1) / kWave;
+  if (ngroups > g_begin + seg) ngroups = g_begin + seg;
+  const uint32_t gpb = (uint32_t)D.groups_per_block;
+  {
+    const uint32_t have = D.nblk[list] * gpb;  // never index the block table past the chain
+    if (ngroups > have) ngroups = have;
+  }
+  const int metric = D.metric;
+  for (uint32_t g0 = g_begin; g0 < ngroups; g0 += 2) {
+    const bool two = g0 + 1 < ngroups;  // uniform
+    const uint32_t g1 = two ? g0 + 1 : g0;
+    const uint32_t b0 = (uint32_t)*table_entry(D, list, g0 / gpb);
+    const uint32_t b1 = (uint32_t)*table_entry(D, list, g1 / gpb);
+    const uint32_t *__restrict__ xa = block_codes(D, b0) + (size_t)(g0 % gpb) * words * kWave + lane;
+    const uint32_t *__restrict__ xb = block_codes(D, b1) + (size_t)(g1 % gpb) * words * kWave + lane;
+    float acc0 = 0.f, acc1 = 0.f;
+    for (int c = 0; c < words; ++c) {
+      const uint32_t w0 = xa[(size_t)c * kWave], w1 = xb[(size_t)c * kWave];
+      const float *t = pq_lut + (size_t)c * 4 * 256;
+      acc0 += t[w0 & 255u];                 acc1 += t[w1 & 255u];
+      acc0 += t[256 + ((w0 >> 8) & 255u)];  acc1 += t[256 + ((w1 >> 8) & 255u)];
+      acc0 += t[512 + ((w0 >> 16) & 255u)]; acc1 += t[512 + ((w1 >> 16) & 255u)];
+      acc0 += t[768 + (w0 >> 24)];          acc1 += t[768 + (w1 >> 24)];
+    }
+    const uint32_t v0 = g0 * kWave + lane, v1 = v0 + kWave;
+    const uint32_t key0 = key_of_float((metric == 0 ? acc0 : -acc0) + 0.0f);
+    const uint32_t key1 = key_of_float((metric == 0 ? acc1 : -acc1) + 0.0f);
+    const bool keep0 = v0 < len && key0 <= bound, keep1 = two && v1 < len && key1 <= bound;
+    const unsigned long long m0 = __ballot(keep0), m1 = __ballot(keep1);
+    if (m0 | m1) {  // uniform
+      uint32_t at = 0;
+      if (lane == 0) at = atomicAdd(&S.rec_cnt[q], (uint32_t)__popcll(m0) + (uint32_t)__popcll(m1));
+      at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+      const unsigned long long below = (1ull << lane) - 1ull;
+      uint32_t *rk = S.rec_key + base + at, *rp = S.rec_pos + base + at;
+      if (keep0) {
+        const uint32_t slot = (uint32_t)__popcll(m0 & below);
+        rk[slot] = key0;
+        rp[slot] = off + v0;
+      }
+      if (keep1) {
+        const uint32_t slot = (uint32_t)__popcll(m0) + (uint32_t)__popcll(m1 & below);
+        rk[slot] = key1;
+        rp[slot] = off + v1;
+      }
+    }
   }
 }
 
@@ -1148,6 +1286,7 @@ void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, con
 
 // Wavefronts per workgroup of the scan: as many (4, 2, 1) as fit their query tiles into 64 KiB of LDS
 static int scan_waves(const Dev &D) {
+  if (D.pq_m > 0) return 1;  // a workgroup of the scan over codes is one wavefront
   const size_t per_wave = (size_t)kScanTileQueries * D.d * sizeof(float);
   int waves = kScanWaves;
   while (waves > 1 && per_wave * waves > 65536) waves /= 2;
@@ -1167,7 +1306,7 @@ void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int k, c
   if (nq <= 0) return;
   // workgroup 0 groups the pairs, workgroup 1 + q sets the bound of query q
   hipLaunchKernelGGL(k_group, dim3(1 + (unsigned)nq), dim3(kGroupThreads), 0, s, D, (int)nq, nprobe,
-                     max_nprobe, k, Q, (uint32_t)item_budget,
+                     max_nprobe, k, (uint32_t)(D.pq_m > 0 ? 1 : kScanTileQueries), Q, (uint32_t)item_budget,
                      (uint32_t)(scan_grid(D, item_budget) / (int)kXcds * scan_waves(D)), S);
 }
 
@@ -1175,6 +1314,10 @@ void launch_scan(const Dev &D, int64_t nq, int max_nprobe, const float *Q, int i
                  const SearchScratch &S, hipStream_t s) {
   if (nq <= 0) return;
   dim3 grid((unsigned)scan_grid(D, item_budget));
+  if (D.pq_m > 0) {
+    hipLaunchKernelGGL(k_pq_scan, grid, dim3(kWave), (size_t)D.pq_m * 256 * sizeof(float), s, D, max_nprobe, S);
+    return;
+  }
   const int waves = scan_waves(D);
   const size_t lds = (size_t)waves * kScanTileQueries * D.d * sizeof(float);
   if (D.metric == 0)

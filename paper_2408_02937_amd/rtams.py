@@ -28,7 +28,7 @@ SYMBOLS = [
     "rtams_list_size", "rtams_list_info", "rtams_list_export", "rtams_list_chain",
     "rtams_list_sizes", "rtams_pool_stats", "rtams_validate", "rtams_probe", "rtams_assign",
     "rtams_poll_error", "rtams_last_error", "rtams_set_param", "rtams_scan_time",
-    "rtams_copy_plain", "rtams_read_plain",
+    "rtams_copy_plain", "rtams_read_plain", "rtams_set_codebooks", "rtams_list_export_codes",
 ]
 
 
@@ -38,7 +38,7 @@ class Config(C.Structure):
                 ("d_pool", C.c_void_p), ("pool_bytes", C.c_size_t),
                 ("d_scratch", C.c_void_p), ("scratch_bytes", C.c_size_t),
                 ("n_resources", C.c_int32), ("max_batch", C.c_int32), ("max_k", C.c_int32),
-                ("max_nprobe", C.c_int32), ("max_add_batch", C.c_int32)]
+                ("max_nprobe", C.c_int32), ("max_add_batch", C.c_int32), ("pq_m", C.c_int32)]
 
 
 class Stats(C.Structure):
@@ -75,6 +75,8 @@ def lib():
         L.rtams_create.argtypes = [cp, C.POINTER(vp)]
         L.rtams_destroy.argtypes = [vp]
         L.rtams_set_centroids.argtypes = [vp, vp, vp]
+        L.rtams_set_codebooks.argtypes = [vp, vp, vp]
+        L.rtams_list_export_codes.argtypes = [vp, i32, i64, vp, vp, C.POINTER(i64), vp]
         L.rtams_add.argtypes = [vp, i64, vp, vp, vp]
         L.rtams_search.argtypes = [vp, i64, vp, i32, i32, vp, vp, vp]
         L.rtams_rearrange.argtypes = [vp, i32, vp]
@@ -133,15 +135,15 @@ class Index:
                  pool_blocks: Optional[int] = None, pool_bytes: Optional[int] = None,
                  rearrange_threshold: int = 0, n_resources: int = 8, max_batch: int = 256,
                  max_k: int = 128, max_nprobe: int = 64, max_add_batch: int = 65536,
-                 candidates_per_query: int = 65536, device: str = "cuda:0"):
+                 candidates_per_query: int = 65536, device: str = "cuda:0", pq_m: int = 0):
         L = lib()
-        self.d, self.nlist, self.block_vecs = d, nlist, block_vecs
+        self.d, self.nlist, self.block_vecs, self.pq_m = d, nlist, block_vecs, pq_m
         self.metric = {"l2": L2, "ip": IP}[metric]
         self.device = torch.device(device)
         cfg = Config(d=d, nlist=nlist, metric=self.metric, block_vecs=block_vecs,
                      rearrange_threshold=rearrange_threshold, n_resources=n_resources,
                      max_batch=max_batch, max_k=max_k, max_nprobe=min(max_nprobe, nlist),
-                     max_add_batch=max_add_batch)
+                     max_add_batch=max_add_batch, pq_m=pq_m)
         if pool_bytes is None:
             if pool_blocks is None:
                 raise ValueError("give pool_blocks or pool_bytes")
@@ -179,6 +181,13 @@ class Index:
         if c.shape[0] != self.nlist:
             raise ValueError("centroids must have nlist rows")
         _chk(lib().rtams_set_centroids(self._h, c.data_ptr(), _stream_ptr(stream)), "rtams_set_centroids")
+
+    def set_codebooks(self, codebooks: torch.Tensor, stream=None) -> None:
+        """codebooks [pq_m][256][d / pq_m] float32 on the device."""
+        if (codebooks.dtype != torch.float32 or not codebooks.is_cuda or not codebooks.is_contiguous()
+                or self.pq_m == 0 or tuple(codebooks.shape) != (self.pq_m, 256, self.d // self.pq_m)):
+            raise ValueError("codebooks must be a contiguous float32 CUDA tensor [pq_m][256][d / pq_m]")
+        _chk(lib().rtams_set_codebooks(self._h, codebooks.data_ptr(), _stream_ptr(stream)), "rtams_set_codebooks")
 
     def add(self, vecs: torch.Tensor, ids: Optional[torch.Tensor] = None, stream=None) -> None:
         v = _dev_f32(vecs, self.d, "vecs")
@@ -249,6 +258,15 @@ class Index:
         _chk(lib().rtams_list_export(self._h, lst, n, ids.data_ptr(), vecs.data_ptr(), C.byref(got),
                                      _stream_ptr(stream)), "rtams_list_export")
         return ids[:got.value], vecs[:got.value]
+
+    def list_export_codes(self, lst: int, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+        n = self.list_size(lst)
+        ids = torch.empty(n, dtype=torch.int64, device=self.device)
+        codes = torch.empty((n, max(self.pq_m, 1)), dtype=torch.uint8, device=self.device)
+        got = C.c_int64()
+        _chk(lib().rtams_list_export_codes(self._h, lst, n, ids.data_ptr(), codes.data_ptr(), C.byref(got),
+                                           _stream_ptr(stream)), "rtams_list_export_codes")
+        return ids[:got.value], codes[:got.value]
 
     def list_chain(self, lst: int):
         import numpy as np

@@ -225,3 +225,16 @@ def config(idx: int, scale: float = 1.0) -> Workload:
                          nlist=16384, block_vecs=256, n_queries=s(4_096),
                          n_inserts=s(1_000_000), insert_batch=1024, nprobe=64, k=50)
     raise ValueError(f"no such configuration: {idx}")
+
+
+def codebooks_from_rows(seed: int, rows: np.ndarray, m: int) -> np.ndarray:
+    """Codebooks [m][256][d/m] for product-quantised lists: entry c of sub-space s
+    is sub-vector s of a row drawn by a seeded permutation (256 distinct rows per
+    sub-space).  A stand-in for trained codebooks: training is outside the path."""
+    d = rows.shape[1]
+    ds = d // m
+    out = np.empty((m, 256, ds), dtype=np.float32)
+    for s in range(m):
+        idx = _rng(seed, 200 + s).permutation(rows.shape[0])[:256]
+        out[s] = rows[idx, s * ds:(s + 1) * ds]
+    return out
