@@ -46,7 +46,7 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true", help="only the timed steps (for profiler runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only the plain copy kernel on 1 GiB (yardstick for the traffic counters)")
-    ap.add_argument("--study", choices=["rearrange", "blocksize"],
+    ap.add_argument("--study", choices=["rearrange", "blocksize", "pq"],
                     help="run one of the side studies instead of the benchmark (one JSON line each)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -71,7 +71,8 @@ def main() -> int:
         return 0
     if args.study:
         from paper_2408_02937_amd import studies
-        fn = studies.rearrangement_study if args.study == "rearrange" else studies.block_size_sweep
+        fn = {"rearrange": studies.rearrangement_study, "blocksize": studies.block_size_sweep,
+              "pq": studies.pq_study}[args.study]
         print(json.dumps(fn(scale=args.scale, iters=args.latency_iters)))
         return 0
     t_gen = time.perf_counter()

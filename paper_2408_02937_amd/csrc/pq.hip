@@ -13,41 +13,81 @@
 
 namespace rtams {
 
-// ---- fill: thread (vector i, sub-space m) finds code m of vector i, the entry of codebook m
-// nearest to the sub-vector in squared Euclidean distance, in the fixed arithmetic of the coarse
-// quantizer (double, one FMA per dimension, in order), ties to the lowest entry, and writes the
-// byte to its place; the thread of sub-space 0 also writes the id.
+// ---- fill: one wavefront codes sub-space m of a tile of 8 vectors.  Code m of a vector is the
+// entry of codebook m nearest to its sub-vector in squared Euclidean distance, in the fixed
+// arithmetic of the coarse quantizer (double, one FMA per dimension, in order), ties to the lowest
+// entry.  Lane l holds entries l, l + 64, l + 128, l + 192: it reads each of their coordinates once
+// for the 8 vectors, keeps its best (distance, entry) per vector, and a butterfly over the
+// wavefront leaves the overall best in every lane; lane v then writes the byte of vector v to its
+// place (the wavefront of sub-space 0 also writes the ids).
+constexpr int kFillVecs = 8;
+
 __global__ __launch_bounds__(256) void k_pq_fill(Dev D, int64_t n, const float *__restrict__ Y,
                                                  const int64_t *__restrict__ ids, int64_t id_base,
                                                  const int32_t *__restrict__ assign,
                                                  const uint32_t *__restrict__ did) {
   const int M = D.pq_m, ds = D.d / M;
-  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= n * M) return;
-  const int64_t i = t / M;
-  const int m = (int)(t - i * M);
-  const float *y = Y + i * D.d + (size_t)m * ds;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t w = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int64_t tiles = (n + kFillVecs - 1) / kFillVecs;
+  if (w >= tiles * M) return;  // uniform over the wavefront
+  const int m = (int)(w % M);
+  const int64_t i0 = (w / M) * kFillVecs;
   const float *cb = D.codebooks + (size_t)m * 256 * ds;
-  double best = __builtin_inf();
-  int code = 0;
-  for (int c = 0; c < 256; ++c) {
-    const float *e = cb + (size_t)c * ds;
-    double acc = 0.0;
-    for (int j = 0; j < ds; ++j) {
-      const double u = (double)y[j] - (double)e[j];
-      acc = __builtin_fma(u, u, acc);
-    }
-    const bool take = acc < best;  // strict: ties stay with the lower entry
-    best = take ? acc : best;
-    code = take ? c : code;
+  const float *yrow[kFillVecs];
+#pragma unroll
+  for (int v = 0; v < kFillVecs; ++v) {
+    const int64_t i = i0 + v < n ? i0 + v : n - 1;  // the tail of the last tile repeats the last vector
+    yrow[v] = Y + (size_t)i * D.d + (size_t)m * ds;
   }
+  double acc[kFillVecs][4];
+#pragma unroll
+  for (int v = 0; v < kFillVecs; ++v)
+#pragma unroll
+    for (int u = 0; u < 4; ++u) acc[v][u] = 0.0;
+  for (int j = 0; j < ds; ++j) {
+    double e[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) e[u] = (double)cb[(size_t)(lane + kWave * u) * ds + j];
+#pragma unroll
+    for (int v = 0; v < kFillVecs; ++v) {
+      const double y = (double)yrow[v][j];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const double t = y - e[u];
+        acc[v][u] = __builtin_fma(t, t, acc[v][u]);
+      }
+    }
+  }
+  int mine = 0;  // lane v ends up with the code of vector v
+#pragma unroll
+  for (int v = 0; v < kFillVecs; ++v) {
+    double best = acc[v][0];
+    int code = lane;
+#pragma unroll
+    for (int u = 1; u < 4; ++u) {  // ascending entries: strict "<" keeps the lower one on a tie
+      const bool take = acc[v][u] < best;
+      best = take ? acc[v][u] : best;
+      code = take ? lane + kWave * u : code;
+    }
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+      const double ob = __shfl_xor(best, o);
+      const int oc = __shfl_xor(code, o);
+      const bool take = ob < best || (ob == best && oc < code);
+      best = take ? ob : best;
+      code = take ? oc : code;
+    }
+    if (lane == v) mine = code;
+  }
+  if (lane >= kFillVecs || i0 + lane >= n) return;
+  const int64_t i = i0 + lane;
   const int list = assign[i];
   const uint32_t pos = did[i];
   const uint32_t mid = pos / (uint32_t)D.T_m, moff = pos % (uint32_t)D.T_m;
   if (mid >= D.nblk[list]) return;  // the block could not be opened (pool exhausted)
   const uint32_t b = (uint32_t)*table_entry(D, list, mid);
   uint8_t *bytes = reinterpret_cast<uint8_t *>(block_codes(D, b) + code_word_index(D, moff, m / 4));
-  bytes[m % 4] = (uint8_t)code;
+  bytes[m % 4] = (uint8_t)mine;
   if (m == 0) block_ids(D, b)[moff] = ids ? ids[i] : id_base + i;
 }
 
@@ -85,8 +125,8 @@ __global__ __launch_bounds__(256) void k_pq_export(Dev D, int list, int64_t n, i
 void launch_pq_fill(const Dev &D, int64_t n, const float *Y, const int64_t *ids, int64_t id_base,
                     const InsertScratch &S, hipStream_t s) {
   if (n <= 0) return;
-  const int64_t threads = n * D.pq_m;
-  hipLaunchKernelGGL(k_pq_fill, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, D, n, Y, ids, id_base,
+  const int64_t waves = (n + kFillVecs - 1) / kFillVecs * D.pq_m;
+  hipLaunchKernelGGL(k_pq_fill, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, D, n, Y, ids, id_base,
                      S.assign, S.did);
 }
 

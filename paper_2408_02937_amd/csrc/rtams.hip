@@ -572,8 +572,7 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   // The grouped scan is cut into work items of bounded size, one wavefront each;
   // the budget of items grows with the request so that a small batch still
   // spreads over the chip and a large one is not drowned in per-item overhead.
-  // (quantised lists: one item per (query, list) pair as a rule, see the scan over codes)
-  int64_t budget = nq * nprobe * (D.pq_m > 0 ? 1 : ix->scan_items_per_pair.load(std::memory_order_relaxed));
+  int64_t budget = nq * nprobe * ix->scan_items_per_pair.load(std::memory_order_relaxed);
   const int64_t cap = ix->scan_max_items.load(std::memory_order_relaxed);
   if (budget > cap) budget = cap;
   if (budget < nq * nprobe) budget = nq * nprobe;  // a (query, list) pair is at least one item
@@ -581,7 +580,7 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   launch_group(D, nq, nprobe, ix->cfg.max_nprobe, k, d_queries, (int)budget, S, s);
   const bool timed = ix->profile_scan.load(std::memory_order_relaxed) != 0;
   if (timed) (void)hipEventRecord(ix->res[r].t0, s);
-  launch_scan(D, nq, ix->cfg.max_nprobe, d_queries, (int)budget, S, s);
+  launch_scan(D, nq, nprobe, ix->cfg.max_nprobe, d_queries, (int)budget, S, s);
   if (timed) { (void)hipEventRecord(ix->res[r].t1, s); ix->res[r].timed = true; }
   launch_select(D, nq, k, nprobe, ix->cfg.max_nprobe, S, d_out_dist, d_out_ids, s);
   hipError_t e = hipGetLastError();

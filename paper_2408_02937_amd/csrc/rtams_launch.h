@@ -123,9 +123,10 @@ void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, con
                        const float *Q, bool from_approx, int32_t *probe_out, hipStream_t s);
 // One launch does two things side by side: one workgroup groups the pairs by list
 // and cuts the scan into work items; one workgroup per query sets the query's bound.
+// (Quantised lists are scanned per query: only the bounds are set.)
 void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int k, const float *Q,
                   int item_budget, const SearchScratch &S, hipStream_t s);
-void launch_scan(const Dev &D, int64_t nq, int max_nprobe, const float *Q, int item_budget,
+void launch_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const float *Q, int item_budget,
                  const SearchScratch &S, hipStream_t s);
 void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
                    const SearchScratch &S, float *out_dist, int64_t *out_ids, hipStream_t s);

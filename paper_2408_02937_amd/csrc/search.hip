@@ -444,13 +444,13 @@ __device__ void pq_sample_scores(const Dev &D, int nprobe, int max_nprobe, int q
   }
 }
 
-__device__ void sample_bound(const Dev &D, int nprobe, int max_nprobe, int k, const float *__restrict__ Q,
+template <bool PQ>
+__device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, int k, const float *__restrict__ Q,
                              const SearchScratch &S) {
   __shared__ float4 qv[512];  // the query (d <= 2048)
   __shared__ uint32_t skey[kSampleMax];
   __shared__ __attribute__((aligned(8))) uint32_t hist[256];
   __shared__ uint32_t bc[4];
-  const int q = (int)blockIdx.x - 1;
   const int tid = threadIdx.x;
   // sample size: 4 k, at least 512 and at least a fraction of the nearest list (the longer that
   // list, the more candidates a given score admits), at most kSampleMax, in whole groups
@@ -459,10 +459,11 @@ __device__ void sample_bound(const Dev &D, int nprobe, int max_nprobe, int k, co
   want = want < part ? part : want;
   want = want < 512u ? 512u : (want > (uint32_t)kSampleMax ? (uint32_t)kSampleMax : want);
   const uint32_t want_groups = (want + kWave - 1) / kWave;
-  for (int c = tid; c < D.d4; c += kGroupThreads) qv[c] = reinterpret_cast<const float4 *>(Q + (size_t)q * D.d)[c];
+  if (!PQ)
+    for (int c = tid; c < D.d4; c += kGroupThreads) qv[c] = reinterpret_cast<const float4 *>(Q + (size_t)q * D.d)[c];
   for (int i = tid; i < (int)(want_groups * kWave); i += kGroupThreads) skey[i] = 0xFFFFFFFFu;
   __syncthreads();
-  if (D.pq_m > 0) pq_sample_scores(D, nprobe, max_nprobe, q, want_groups, S, skey);
+  if (PQ) pq_sample_scores(D, nprobe, max_nprobe, q, want_groups, S, skey);
   else if (D.metric == 0) sample_scores<0>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
   else sample_scores<1>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
   __syncthreads();
@@ -486,8 +487,8 @@ __device__ void sample_bound(const Dev &D, int nprobe, int max_nprobe, int k, co
 // prefix sums over the lists of the pair counts, the work-item counts and the
 // work, then the item descriptors, the split of the items over the 8 XCDs and
 // the grouped pair array.  A work item is (list, segment of seg_groups
-// 64-vector groups, tile of up to tile_q of the queries probing the list: 8 for
-// flat lists, 1 for product-quantised ones); one wavefront walks it.  The items of one segment follow each other, so
+// 64-vector groups, tile of up to kScanTileQueries of the queries probing the
+// list); one wavefront walks it.  The items of one segment follow each other, so
 // they run at the same time on the same CU or on its neighbours and the segment
 // comes from HBM once.  Segments bound the work of one item, so that long lists
 // spread over many wavefronts.  The segment length is the shortest power of two
@@ -525,11 +526,11 @@ __device__ inline void wg_scan3(uint32_t &a, uint32_t &b, unsigned long long &c,
 }
 
 __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int nprobe, int max_nprobe, int k,
-                                                         uint32_t tile_q, const float *__restrict__ Q,
+                                                         const float *__restrict__ Q,
                                                          uint32_t item_budget, uint32_t max_per_xcd,
                                                          SearchScratch S) {
   if (blockIdx.x > 0) {  // uniform over the workgroup: this one sets the bound of query blockIdx.x - 1
-    sample_bound(D, nprobe, max_nprobe, k, Q, S);
+    sample_bound<false>(D, (int)blockIdx.x - 1, nprobe, max_nprobe, k, Q, S);
     return;
   }
   __shared__ uint32_t s_a[kGroupThreads];
@@ -565,7 +566,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
       list_len[l] = len;
       if (!c) continue;
       const uint32_t groups = (len + kWave - 1) / kWave;
-      const uint32_t tiles = (c + tile_q - 1) / tile_q;
+      const uint32_t tiles = (c + kScanTileQueries - 1) / kScanTileQueries;
 #pragma unroll
       for (int e = 0; e < kSegChoices; ++e) {
         const uint32_t sg = 2u << e;
@@ -595,7 +596,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
       if (!c) continue;
       const uint32_t groups = (list_len[l] + kWave - 1) / kWave;
       np += c;
-      ni += (groups ? (groups + seg - 1) / seg : 1u) * ((c + tile_q - 1) / tile_q);
+      ni += (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
       wk += (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
     }
     uint32_t inp = np, ini = ni;
@@ -617,7 +618,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
         if (!c) continue;
         const uint32_t groups = (list_len[l] + kWave - 1) / kWave;
         const unsigned long long w = (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
-        const uint32_t n = (groups ? (groups + seg - 1) / seg : 1u) * ((c + tile_q - 1) / tile_q);
+        const uint32_t n = (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
         for (uint32_t x = 1; x < 8; ++x) {  // the cut falls inside this list: at the item the same share of it ends at
           const unsigned long long cut = total_work * x / 8;
           if (ws <= cut && cut < ws + w) s_begin[x] = is + (uint32_t)((cut - ws) * n / w);
@@ -680,7 +681,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
           if (!c) continue;
           const uint32_t groups = (list_len[l] + kWave - 1) / kWave;
           const uint32_t segs = groups ? (groups + seg - 1) / seg : 1u;
-          const uint32_t tiles = (c + tile_q - 1) / tile_q;
+          const uint32_t tiles = (c + kScanTileQueries - 1) / kScanTileQueries;
           const uint32_t n = segs * tiles;
           if (j < base + n) {
             const uint32_t r = j - base, stop = min(j_end, base + n);
@@ -937,89 +938,209 @@ __global__ __launch_bounds__(kScanWaves * kWave) void k_scan(Dev D, int max_npro
 }
 
 // ------------------------------------------------- scan of quantised lists
-// Product-quantised lists: a work item is (list, segment, ONE query), a workgroup is one
-// wavefront.  It copies the query's table of sub-scores (M x 256 floats, computed once per
-// request) into LDS and walks the segment two groups of 64 vectors at a time, lane = vector:
-// per word of 4 codes one coalesced 256-byte load per group and four LDS look-ups per vector,
-// added up in the order of the sub-spaces.  Survivors of the query's bound are appended to its
-// records exactly as in the scan of flat lists.  (Segments are longer here: the table is 1 KiB
-// per sub-space, a group of 64 coded vectors 64 bytes per sub-space.)
-__global__ __launch_bounds__(kWave) void k_pq_scan(Dev D, int max_nprobe, SearchScratch S) {
-  extern __shared__ float pq_lut[];  // [M][256]
-  const ScanQueues *Qs = S.queues;
-  const uint32_t x = blockIdx.x % kXcds;
-  const uint32_t item = Qs->begin[x] + blockIdx.x / kXcds;
-  if (item >= Qs->begin[x + 1]) return;
-  const uint32_t seg = Qs->seg_groups;
-  if (seg == 0) return;
-  const int lane = threadIdx.x;
-  const uint4 desc = S.tile_desc[item];
-  const int list = __builtin_amdgcn_readfirstlane((int)desc.x);
-  const uint32_t first = (uint32_t)__builtin_amdgcn_readfirstlane((int)desc.y);
-  if (__builtin_amdgcn_readfirstlane((int)desc.z) == 0) return;
-  const uint32_t g_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)desc.w) * seg;
-  const uint32_t pk = S.grouped[first];
-  const uint32_t q = pk >> 10;
-  const size_t o = (size_t)q * max_nprobe + (pk & 1023u);
-  const uint32_t len = S.probe_len[o], off = S.probe_off[o];
-  const unsigned long long base = S.qbase[q];
-  const uint32_t bound = __hip_atomic_load(&S.bound[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// Product-quantised lists are scanned per QUERY, not per list: what a query brings to a list is
+// its table of sub-scores (M x 256 floats, 1 KiB per sub-space, computed once per request), far
+// more than the 64 bytes per sub-space of a group of 64 coded vectors, so the table is what has
+// to stay put.  Workgroup (q, part) copies the table of query q into LDS once and its wavefronts
+// walk part `part` of the groups of the query's probed lists, four groups of 64 vectors at a time,
+// lane = vector: per word of 4 codes one coalesced 256-byte load per group and four LDS look-ups
+// per vector, added up in the order of the sub-spaces.  (The codes of a probed list are read by
+// every query that probes it; they are a small fraction of the flat vectors and stay in cache.)
+// Survivors of the query's bound are appended to its records exactly as in the scan of flat lists.
+constexpr int kPqScanWaves = 8;
+
+constexpr int kPqScanThreads = kPqScanWaves * kWave;
+constexpr int kPqUnits = 4;  // groups of 64 vectors a wavefront walks side by side
+constexpr int kPqStage = 128;  // survivors a wavefront collects in LDS before it appends them to the query's records
+
+__device__ inline void pq_flush(const SearchScratch &S, int q, unsigned long long base, const uint32_t *my_key,
+                                const uint32_t *my_pos, uint32_t n, int lane) {
+  uint32_t at = 0;
+  if (lane == 0) at = atomicAdd(&S.rec_cnt[q], n);
+  at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+  uint32_t *rk = S.rec_key + base + at, *rp = S.rec_pos + base + at;
+  for (uint32_t i = (uint32_t)lane; i < n; i += kWave) {
+    rk[i] = my_key[i];
+    rp[i] = my_pos[i];
+  }
+}
+
+__global__ __launch_bounds__(kPqScanThreads) void k_pq_scan(Dev D, int nprobe, int max_nprobe, int parts,
+                                                            SearchScratch S) {
+  extern __shared__ float pq_lut[];            // [M][256]
+  __shared__ uint32_t gstart[kMaxNprobe + 1];  // groups of the query in front of probe p
+  __shared__ uint32_t s_blk[kPqScanThreads];   // per group of the current chunk: its block ...
+  __shared__ uint32_t s_probe[kPqScanThreads]; // ... and the probe it belongs to
+  __shared__ uint32_t s_key[kPqScanWaves][kPqStage];  // survivors not yet written out, per wavefront
+  __shared__ uint32_t s_pos[kPqScanWaves][kPqStage];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int q = blockIdx.x / parts, part = blockIdx.x % parts;
   const int M = D.pq_m, words = M / 4;
+  const uint32_t gpb = (uint32_t)D.groups_per_block;
+  if (wave == 0) {  // running sum of the groups per probe, 64 probes at a time
+    uint32_t carry = 0;
+    for (int p0 = 0; p0 < nprobe; p0 += kWave) {
+      const int p = p0 + lane;
+      uint32_t groups = 0;
+      if (p < nprobe) {
+        const size_t o = (size_t)q * max_nprobe + p;
+        groups = (S.probe_len[o] + kWave - 1) / kWave;
+        const uint32_t have = D.nblk[S.probe_list[o]] * gpb;  // never index the block table past the chain
+        groups = groups > have ? have : groups;
+      }
+      uint32_t incl = groups;
+      for (int d = 1; d < kWave; d <<= 1) {
+        const uint32_t t = __shfl_up(incl, d);
+        if (lane >= d) incl += t;
+      }
+      if (p < nprobe) gstart[p] = carry + incl - groups;
+      carry += __shfl(incl, kWave - 1);
+    }
+    if (lane == 0) gstart[nprobe] = carry;
+  }
+  __syncthreads();
+  const uint32_t total = gstart[nprobe];
+  uint32_t per = (total + (uint32_t)parts - 1) / (uint32_t)parts;
+  const uint32_t u_lo = (uint32_t)part * per, u_hi = min(total, u_lo + per);
+  if (u_lo >= u_hi) return;  // uniform over the workgroup
+  // the query's table: loads issued here, stored to LDS after the first chunk's blocks are resolved
+  constexpr int kLutRegs = 64 * 64 / kPqScanThreads;  // float4 per thread at M = 64
+  float4 lut_reg[kLutRegs];
   {
     const float4 *src = reinterpret_cast<const float4 *>(S.lut + (size_t)q * M * 256);
-    float4 *dst = reinterpret_cast<float4 *>(pq_lut);
-    for (int i = lane; i < M * 64; i += kWave) dst[i] = src[i];
+#pragma unroll
+    for (int r = 0; r < kLutRegs; ++r) {
+      const int i = tid + r * kPqScanThreads;
+      lut_reg[r] = i < M * 64 ? src[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
   }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-
-  uint32_t ngroups = (len + kWave - 1) / kWave;
-  if (ngroups > g_begin + seg) ngroups = g_begin + seg;
-  const uint32_t gpb = (uint32_t)D.groups_per_block;
-  {
-    const uint32_t have = D.nblk[list] * gpb;  // never index the block table past the chain
-    if (ngroups > have) ngroups = have;
-  }
+  const unsigned long long base = S.qbase[q];
+  const uint32_t bound = __hip_atomic_load(&S.bound[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   const int metric = D.metric;
-  for (uint32_t g0 = g_begin; g0 < ngroups; g0 += 2) {
-    const bool two = g0 + 1 < ngroups;  // uniform
-    const uint32_t g1 = two ? g0 + 1 : g0;
-    const uint32_t b0 = (uint32_t)*table_entry(D, list, g0 / gpb);
-    const uint32_t b1 = (uint32_t)*table_entry(D, list, g1 / gpb);
-    const uint32_t *__restrict__ xa = block_codes(D, b0) + (size_t)(g0 % gpb) * words * kWave + lane;
-    const uint32_t *__restrict__ xb = block_codes(D, b1) + (size_t)(g1 % gpb) * words * kWave + lane;
-    float acc0 = 0.f, acc1 = 0.f;
-    for (int c = 0; c < words; ++c) {
-      const uint32_t w0 = xa[(size_t)c * kWave], w1 = xb[(size_t)c * kWave];
-      const float *t = pq_lut + (size_t)c * 4 * 256;
-      acc0 += t[w0 & 255u];                 acc1 += t[w1 & 255u];
-      acc0 += t[256 + ((w0 >> 8) & 255u)];  acc1 += t[256 + ((w1 >> 8) & 255u)];
-      acc0 += t[512 + ((w0 >> 16) & 255u)]; acc1 += t[512 + ((w1 >> 16) & 255u)];
-      acc0 += t[768 + (w0 >> 24)];          acc1 += t[768 + (w1 >> 24)];
-    }
-    const uint32_t v0 = g0 * kWave + lane, v1 = v0 + kWave;
-    const uint32_t key0 = key_of_float((metric == 0 ? acc0 : -acc0) + 0.0f);
-    const uint32_t key1 = key_of_float((metric == 0 ? acc1 : -acc1) + 0.0f);
-    const bool keep0 = v0 < len && key0 <= bound, keep1 = two && v1 < len && key1 <= bound;
-    const unsigned long long m0 = __ballot(keep0), m1 = __ballot(keep1);
-    if (m0 | m1) {  // uniform
-      uint32_t at = 0;
-      if (lane == 0) at = atomicAdd(&S.rec_cnt[q], (uint32_t)__popcll(m0) + (uint32_t)__popcll(m1));
-      at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
-      const unsigned long long below = (1ull << lane) - 1ull;
-      uint32_t *rk = S.rec_key + base + at, *rp = S.rec_pos + base + at;
-      if (keep0) {
-        const uint32_t slot = (uint32_t)__popcll(m0 & below);
-        rk[slot] = key0;
-        rp[slot] = off + v0;
+  uint32_t *my_key = s_key[wave], *my_pos = s_pos[wave];
+  uint32_t staged = 0;  // uniform over the wavefront
+  for (uint32_t c0 = u_lo; c0 < u_hi; c0 += kPqScanThreads) {  // chunks of 512 groups
+    if (c0 != u_lo) __syncthreads();  // the previous chunk has been walked
+    {  // thread t resolves group c0 + t: probe by bisection of the running sums, block from the list's table
+      const uint32_t u = c0 + (uint32_t)tid;
+      if (u < u_hi) {
+        int lo = 0, hi = nprobe - 1;  // last probe whose groups start at or before u
+        while (lo < hi) {
+          const int mid = (lo + hi + 1) >> 1;
+          if (gstart[mid] <= u) lo = mid; else hi = mid - 1;
+        }
+        const int list = S.probe_list[(size_t)q * max_nprobe + lo];
+        s_probe[tid] = (uint32_t)lo;
+        s_blk[tid] = (uint32_t)*table_entry(D, list, (u - gstart[lo]) / gpb);
       }
-      if (keep1) {
-        const uint32_t slot = (uint32_t)__popcll(m0) + (uint32_t)__popcll(m1 & below);
-        rk[slot] = key1;
-        rp[slot] = off + v1;
+    }
+    if (c0 == u_lo) {
+      float4 *dst = reinterpret_cast<float4 *>(pq_lut);
+#pragma unroll
+      for (int r = 0; r < kLutRegs; ++r) {
+        const int i = tid + r * kPqScanThreads;
+        if (i < M * 64) dst[i] = lut_reg[r];
+      }
+    }
+    __syncthreads();
+    const uint32_t n_here = min((uint32_t)kPqScanThreads, u_hi - c0);
+    // a wavefront takes kPqUnits consecutive groups at a time: all their loads are in flight together,
+    // and their survivors are appended with one reservation
+    for (uint32_t i0 = (uint32_t)(kPqUnits * wave); i0 < n_here; i0 += kPqUnits * kPqScanWaves) {
+      const uint32_t *__restrict__ x[kPqUnits];
+      uint32_t len[kPqUnits], off[kPqUnits], v[kPqUnits];
+      bool live[kPqUnits];
+#pragma unroll
+      for (int j = 0; j < kPqUnits; ++j) {
+        live[j] = i0 + j < n_here;  // uniform over the wavefront
+        const uint32_t i = live[j] ? i0 + j : i0;
+        // the same for every lane: kept in scalar registers, so is the address arithmetic below
+        const uint32_t p = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_probe[i]);
+        const uint32_t blk = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_blk[i]);
+        const uint32_t g = c0 + i - (uint32_t)__builtin_amdgcn_readfirstlane((int)gstart[p]);
+        const size_t o = (size_t)q * max_nprobe + p;
+        x[j] = block_codes(D, blk) + (size_t)(g % gpb) * words * kWave + lane;
+        len[j] = S.probe_len[o];
+        off[j] = S.probe_off[o];
+        v[j] = g * kWave + lane;
+      }
+      float acc[kPqUnits];
+#pragma unroll
+      for (int j = 0; j < kPqUnits; ++j) acc[j] = 0.f;
+      for (int cw = 0; cw < words; cw += 4) {  // 16 codes of every group at a time: their loads go out together
+        uint32_t w[4][kPqUnits];
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+          for (int j = 0; j < kPqUnits; ++j) w[cc][j] = cw + cc < words ? x[j][(size_t)(cw + cc) * kWave] : 0u;
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+          if (cw + cc < words) {  // uniform
+            const float *t = pq_lut + (size_t)(cw + cc) * 4 * 256;
+#pragma unroll
+            for (int j = 0; j < kPqUnits; ++j) acc[j] += t[w[cc][j] & 255u];
+#pragma unroll
+            for (int j = 0; j < kPqUnits; ++j) acc[j] += t[256 + ((w[cc][j] >> 8) & 255u)];
+#pragma unroll
+            for (int j = 0; j < kPqUnits; ++j) acc[j] += t[512 + ((w[cc][j] >> 16) & 255u)];
+#pragma unroll
+            for (int j = 0; j < kPqUnits; ++j) acc[j] += t[768 + (w[cc][j] >> 24)];
+          }
+        }
+      }
+      uint32_t key[kPqUnits];
+      unsigned long long mask[kPqUnits];
+      uint32_t n_keep = 0;
+#pragma unroll
+      for (int j = 0; j < kPqUnits; ++j) {
+        key[j] = key_of_float((metric == 0 ? acc[j] : -acc[j]) + 0.0f);
+        mask[j] = __ballot(live[j] && v[j] < len[j] && key[j] <= bound);
+        n_keep += (uint32_t)__popcll(mask[j]);
+      }
+      // Survivors wait in the wavefront's own slice of LDS and go out kPqStage at a time: every
+      // reservation of a query goes to the same word, so the fewer the better.
+      if (staged + n_keep > (uint32_t)kPqStage) {  // uniform over the wavefront
+        pq_flush(S, q, base, my_key, my_pos, staged, lane);
+        staged = 0;
+      }
+      if (n_keep > (uint32_t)kPqStage) {  // more than the slice holds: straight out
+        uint32_t at = 0;
+        if (lane == 0) at = atomicAdd(&S.rec_cnt[q], n_keep);
+        at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+        const unsigned long long below = (1ull << lane) - 1ull;
+        uint32_t *rk = S.rec_key + base + at, *rp = S.rec_pos + base + at;
+#pragma unroll
+        for (int j = 0; j < kPqUnits; ++j) {
+          if ((mask[j] >> lane) & 1ull) {
+            const uint32_t slot = (uint32_t)__popcll(mask[j] & below);
+            rk[slot] = key[j];
+            rp[slot] = off[j] + v[j];
+          }
+          rk += __popcll(mask[j]);
+          rp += __popcll(mask[j]);
+        }
+      } else if (n_keep) {
+        const unsigned long long below = (1ull << lane) - 1ull;
+#pragma unroll
+        for (int j = 0; j < kPqUnits; ++j) {
+          if ((mask[j] >> lane) & 1ull) {
+            const uint32_t slot = staged + (uint32_t)__popcll(mask[j] & below);
+            my_key[slot] = key[j];
+            my_pos[slot] = off[j] + v[j];
+          }
+          staged += (uint32_t)__popcll(mask[j]);
+        }
       }
     }
   }
+  if (staged) pq_flush(S, q, base, my_key, my_pos, staged, lane);
+}
+
+// The bound of every query of a request over quantised lists (the grouping by list that the scan
+// of flat lists needs is not made).
+__global__ __launch_bounds__(kGroupThreads) void k_pq_bound(Dev D, int nprobe, int max_nprobe, int k,
+                                                            SearchScratch S) {
+  sample_bound<true>(D, (int)blockIdx.x, nprobe, max_nprobe, k, nullptr, S);
 }
 
 // ------------------------------------------------------------ top-k selection
@@ -1286,7 +1407,6 @@ void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, con
 
 // Wavefronts per workgroup of the scan: as many (4, 2, 1) as fit their query tiles into 64 KiB of LDS
 static int scan_waves(const Dev &D) {
-  if (D.pq_m > 0) return 1;  // a workgroup of the scan over codes is one wavefront
   const size_t per_wave = (size_t)kScanTileQueries * D.d * sizeof(float);
   int waves = kScanWaves;
   while (waves > 1 && per_wave * waves > 65536) waves /= 2;
@@ -1304,20 +1424,32 @@ static int scan_grid(const Dev &D, int item_budget) {
 void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int k, const float *Q,
                   int item_budget, const SearchScratch &S, hipStream_t s) {
   if (nq <= 0) return;
+  if (D.pq_m > 0) {
+    hipLaunchKernelGGL(k_pq_bound, dim3((unsigned)nq), dim3(kGroupThreads), 0, s, D, nprobe, max_nprobe, k, S);
+    return;
+  }
   // workgroup 0 groups the pairs, workgroup 1 + q sets the bound of query q
   hipLaunchKernelGGL(k_group, dim3(1 + (unsigned)nq), dim3(kGroupThreads), 0, s, D, (int)nq, nprobe,
-                     max_nprobe, k, (uint32_t)(D.pq_m > 0 ? 1 : kScanTileQueries), Q, (uint32_t)item_budget,
+                     max_nprobe, k, Q, (uint32_t)item_budget,
                      (uint32_t)(scan_grid(D, item_budget) / (int)kXcds * scan_waves(D)), S);
 }
 
-void launch_scan(const Dev &D, int64_t nq, int max_nprobe, const float *Q, int item_budget,
+void launch_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const float *Q, int item_budget,
                  const SearchScratch &S, hipStream_t s) {
   if (nq <= 0) return;
-  dim3 grid((unsigned)scan_grid(D, item_budget));
   if (D.pq_m > 0) {
-    hipLaunchKernelGGL(k_pq_scan, grid, dim3(kWave), (size_t)D.pq_m * 256 * sizeof(float), s, D, max_nprobe, S);
+    // parts per query, from the request's budget of work items: 32 items' worth to a workgroup
+    int parts = (int)(item_budget / (nq * 32));
+    parts = parts < 1 ? 1 : (parts > 64 ? 64 : parts);
+    const size_t lds = (size_t)D.pq_m * 256 * sizeof(float);
+    if (lds > 48 * 1024)  // with the kernel's own 8 KiB this passes the default limit of a workgroup
+      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k_pq_scan),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL(k_pq_scan, dim3((unsigned)(nq * parts)), dim3(kPqScanThreads), lds, s, D, nprobe,
+                       max_nprobe, parts, S);
     return;
   }
+  dim3 grid((unsigned)scan_grid(D, item_budget));
   const int waves = scan_waves(D);
   const size_t lds = (size_t)waves * kScanTileQueries * D.d * sizeof(float);
   if (D.metric == 0)

@@ -8,7 +8,12 @@
 * `block_size_sweep`: the analogue of the paper's block-size figure ("Effects
   of memory block size"): latency, scan rate and pad memory as T_m grows.
 
-Both use configuration 2's synthetic data (byte-valued, d = 128, 1 M vectors,
+* `pq_study`: product-quantised lists (the IVF-PQ kind of list the paper names
+  beside IVF-Flat) in the same blocks: load rate, bytes per vector, latency
+  and scan time per query batch, insertion latency, and how many of the flat
+  index's top-k the coded index returns.
+
+All use configuration 2's synthetic data (byte-valued, d = 128, 1 M vectors,
 1024 lists) and go through the same C ABI as everything else.
 """
 from __future__ import annotations
@@ -179,3 +184,70 @@ def block_size_sweep(scale: float = 1.0, sizes=(64, 128, 256, 512, 1024, 2048), 
         rows.append(row)
         g.close()
     return {"study": "block_size", "workload": w.name, "rows": rows}
+
+
+def pq_study(scale: float = 1.0, ms=(16, 32), iters: int = 200) -> dict:
+    dev = torch.device("cuda:0")
+    w = synth.config(2, scale=scale)
+    base, cents, queries, inserts = (_to_dev(a, dev) for a in (w.base, w.centroids, w.queries, w.inserts))
+    n_all = len(w.base) + 2 * len(w.inserts)
+    blocks = n_all // w.block_vecs + 2 * w.nlist + 64
+    kw = dict(pool_blocks=blocks, n_resources=8, max_batch=256, max_k=128, max_nprobe=64, max_add_batch=65536,
+              candidates_per_query=65536)
+    ds, ss = torch.cuda.Stream(dev), torch.cuda.Stream(dev)
+    flat = rtams.Index(w.d, w.nlist, w.metric, w.block_vecs, **kw)
+    flat.set_centroids(cents, stream=ds)
+    flat.add(base, stream=ds)
+    ds.synchronize()
+    nq_recall = min(1024, len(w.queries))
+
+    def ids_of(index, o):
+        ids = index.search(queries[o:min(o + 256, nq_recall)], w.k, w.nprobe, stream=ss)[1]
+        ss.synchronize()
+        return ids.cpu().numpy()
+
+    exact = np.concatenate([ids_of(flat, o) for o in range(0, nq_recall, 256)])
+    flat_bytes = int(flat.pool_stats().pool_bytes)
+    flat.close()
+    rows = []
+    for M in ms:
+        cb = _to_dev(synth.codebooks_from_rows(w.seed, w.base, M), dev)
+        g = rtams.Index(w.d, w.nlist, w.metric, w.block_vecs, pq_m=M, **kw)
+        g.set_centroids(cents, stream=ds)
+        g.set_codebooks(cb, stream=ds)
+        t0 = time.perf_counter()
+        g.add(base, stream=ds)
+        ds.synchronize()
+        bulk_s = time.perf_counter() - t0
+        st = g.pool_stats()
+        row = {"pq_m": M, "bytes_per_vector_in_lists": M + 8, "pool_bytes": int(st.pool_bytes),
+               "flat_pool_bytes": flat_bytes, "bulk_load_vectors_per_s": len(w.base) / bulk_s, "search": {}}
+        hit = 0
+        for o in range(0, nq_recall, 256):
+            got = ids_of(g, o)
+            hit += sum(len(np.intersect1d(got[i], exact[o + i])) for i in range(len(got)))
+        row["share_of_flat_topk_returned"] = hit / (nq_recall * w.k)
+        for bs in (1, 10, 32, 256):
+            g.scan_time(reset=True)
+            g.set_param("profile_scan", 1)
+            lat = _search_latencies(g, queries, bs, w.k, w.nprobe, iters, ss, dev)
+            g.set_param("profile_scan", 0)
+            ms_, cnt = g.scan_time(reset=True)
+            row["search"][str(bs)] = {"p50_ms": _p(lat, 50), "p99_ms": _p(lat, 99), "qps": bs / (np.mean(lat) * 1e-3),
+                                      "scan_ms": ms_ / max(cnt, 1)}
+        ib = w.insert_batch
+        lat = []
+        for i in range(iters + 10):
+            t0 = time.perf_counter()
+            g.add(inserts[(i % (len(inserts) // ib)) * ib:(i % (len(inserts) // ib)) * ib + ib], stream=ds)
+            ds.synchronize()
+            if i >= 10:
+                lat.append((time.perf_counter() - t0) * 1e3)
+        row["insert_batch64_p50_ms"] = _p(lat, 50)
+        row["insert_batch64_p99_ms"] = _p(lat, 99)
+        g.validate()
+        assert g.poll_error() == 0
+        rows.append(row)
+        g.close()
+    return {"study": "product_quantised_lists", "workload": w.name, "k": w.k, "nprobe": w.nprobe,
+            "codebooks": "256 sampled sub-vectors per sub-space (untrained)", "rows": rows}

@@ -1,4 +1,4 @@
-"""The two side studies run end to end on a shrunken workload (their numbers
+"""The side studies run end to end on a shrunken workload (their numbers
 are not checked here, only that they complete, validate and report sane fields)."""
 import pytest
 
@@ -24,3 +24,13 @@ def test_block_size_sweep_small():
     assert pads[1] > pads[0] > 0
     for r in out["rows"]:
         assert r["search"]["256"]["scan_ms"] > 0
+
+
+def test_pq_study_small():
+    from paper_2408_02937_amd import studies
+    print("[case] product-quantiser study, scale 0.03, M 16", flush=True)
+    out = studies.pq_study(scale=0.03, ms=(16,), iters=5)
+    r = out["rows"][0]
+    assert r["pool_bytes"] < r["flat_pool_bytes"]  # (the fixed part of the pool dominates at this scale)
+    assert 0.0 < r["share_of_flat_topk_returned"] <= 1.0
+    assert r["search"]["256"]["scan_ms"] > 0
