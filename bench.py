@@ -46,6 +46,8 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true", help="only the timed steps (for profiler runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only the plain copy kernel on 1 GiB (yardstick for the traffic counters)")
+    ap.add_argument("--pq-m", type=int, default=0,
+                    help="with --study pq: only this number of sub-spaces, and only the --batch query batch")
     ap.add_argument("--study", choices=["rearrange", "blocksize", "pq"],
                     help="run one of the side studies instead of the benchmark (one JSON line each)")
     args = ap.parse_args()
@@ -73,6 +75,9 @@ def main() -> int:
         from paper_2408_02937_amd import studies
         fn = {"rearrange": studies.rearrangement_study, "blocksize": studies.block_size_sweep,
               "pq": studies.pq_study}[args.study]
+        if args.study == "pq" and args.pq_m:
+            print(json.dumps(fn(scale=args.scale, iters=args.latency_iters, ms=(args.pq_m,), batches=(args.batch,))))
+            return 0
         print(json.dumps(fn(scale=args.scale, iters=args.latency_iters)))
         return 0
     t_gen = time.perf_counter()

@@ -27,6 +27,9 @@ import torch
 from . import rtams, synth
 
 
+LDS_LOOKUPS_PEAK_G = 256 * 128 / 4 * 2.4  # 4-byte LDS reads per nanosecond of the whole chip, conflict-free
+
+
 def _p(xs, q):
     return float(np.percentile(np.asarray(xs, dtype=np.float64), q)) if len(xs) else float("nan")
 
@@ -186,7 +189,7 @@ def block_size_sweep(scale: float = 1.0, sizes=(64, 128, 256, 512, 1024, 2048), 
     return {"study": "block_size", "workload": w.name, "rows": rows}
 
 
-def pq_study(scale: float = 1.0, ms=(16, 32), iters: int = 200) -> dict:
+def pq_study(scale: float = 1.0, ms=(16, 32), iters: int = 200, batches=(1, 10, 32, 256)) -> dict:
     dev = torch.device("cuda:0")
     w = synth.config(2, scale=scale)
     base, cents, queries, inserts = (_to_dev(a, dev) for a in (w.base, w.centroids, w.queries, w.inserts))
@@ -222,19 +225,32 @@ def pq_study(scale: float = 1.0, ms=(16, 32), iters: int = 200) -> dict:
         st = g.pool_stats()
         row = {"pq_m": M, "bytes_per_vector_in_lists": M + 8, "pool_bytes": int(st.pool_bytes),
                "flat_pool_bytes": flat_bytes, "bulk_load_vectors_per_s": len(w.base) / bulk_s, "search": {}}
+        sizes_now = g.list_sizes()
         hit = 0
         for o in range(0, nq_recall, 256):
             got = ids_of(g, o)
             hit += sum(len(np.intersect1d(got[i], exact[o + i])) for i in range(len(got)))
         row["share_of_flat_topk_returned"] = hit / (nq_recall * w.k)
-        for bs in (1, 10, 32, 256):
+        for bs in batches:
             g.scan_time(reset=True)
             g.set_param("profile_scan", 1)
             lat = _search_latencies(g, queries, bs, w.k, w.nprobe, iters, ss, dev)
             g.set_param("profile_scan", 0)
             ms_, cnt = g.scan_time(reset=True)
+            # table look-ups of one scan launch: one per (query, candidate, sub-space); the yardstick is what
+            # the LDS of 256 CUs delivers without bank conflicts (128 bytes per clock each, 2.4 GHz, 4-byte entries)
+            nb = max(len(queries) // bs, 1)
+            looks = []
+            for i in range(min(16, nb)):
+                pl = g.probe(queries[i * bs:(i + 1) * bs], w.nprobe).cpu().numpy()
+                looks.append(float(sizes_now[pl].sum()) * M)
+            scan_ms = ms_ / max(cnt, 1)
+            rate = float(np.mean(looks)) / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else None
             row["search"][str(bs)] = {"p50_ms": _p(lat, 50), "p99_ms": _p(lat, 99), "qps": bs / (np.mean(lat) * 1e-3),
-                                      "scan_ms": ms_ / max(cnt, 1)}
+                                      "scan_ms": scan_ms,
+                                      "roofline": {"bound": "lds", "achieved": rate, "peak": LDS_LOOKUPS_PEAK_G,
+                                                   "unit": "G look-ups/s", "frac": rate / LDS_LOOKUPS_PEAK_G if rate else None,
+                                                   "lookups_per_launch": float(np.mean(looks))}}
         ib = w.insert_batch
         lat = []
         for i in range(iters + 10):
