@@ -27,6 +27,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+VALU_ISSUE_PEAK_T = 256 * 4 * 16 * 2.4e9 / 1e12  # fp32 vector instructions per lane and second, all CUs (no packed math)
 
 
 def percentile(xs, p):
@@ -156,6 +157,11 @@ def main() -> int:
         pair_bytes.append(int(per_list(ln).sum()))
         union_bytes.append(int(per_list(sizes[np.unique(pl)]).sum()))
     pair_b, union_b = float(np.mean(pair_bytes)), float(np.mean(union_bytes))
+    # Arithmetic of the same launch: every (query, candidate) pair costs d subtract + d fused
+    # multiply-add instructions per lane for L2 (d multiply-adds for IP); the yardstick is the rate at
+    # which 256 CUs x 4 SIMDs x 16 lanes issue one fp32 instruction per lane and clock at 2.4 GHz.
+    pair_vecs = pair_b / (w.d * 4 + 4.0 / w.block_vecs)
+    lane_ops = pair_vecs * w.d * (2 if w.metric == "l2" else 1)
     scan_avg_ms = scan_ms / max(scan_n, 1)
     # The scan reads a list once for all the queries of the batch that probe it, so
     # the bytes it must move are those of the UNION of the probed lists; bytes
@@ -174,7 +180,11 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": "k_scan", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_launch": union_b, "pair_bytes_per_launch": pair_b,
-                     "avg_launch_ms": scan_avg_ms, "launches_timed": scan_n},
+                     "avg_launch_ms": scan_avg_ms, "launches_timed": scan_n,
+                     "alu_issue": {"lane_instructions_per_launch": lane_ops,
+                                   "achieved_T_per_s": lane_ops / (scan_avg_ms * 1e-3) / 1e12 if scan_n else None,
+                                   "peak_T_per_s": VALU_ISSUE_PEAK_T,
+                                   "frac": lane_ops / (scan_avg_ms * 1e-3) / 1e12 / VALU_ISSUE_PEAK_T if scan_n else None}},
         "inserts_per_s_in_step": args.steps * ib / elapsed,
         "bulk_load_vectors_per_s": len(w.base) / bulk_s,
     }
