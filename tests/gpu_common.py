@@ -2,11 +2,14 @@
 same workload, compare list contents canonically."""
 from __future__ import annotations
 
+import threading
+
 import numpy as np
 import torch
 
 from oracle.oracle import OracleIndex
 from paper_2408_02937_amd import rtams
+from tests.helpers import assert_topk_matches
 
 
 def dev(a: np.ndarray) -> torch.Tensor:
@@ -53,3 +56,91 @@ def assert_lists_equal(g, o, batch_bounds=None):
             assert np.all(np.diff(b) >= 0), f"list {k}: batches interleave"
     st = g.pool_stats()
     assert st.ntotal == o.ntotal and st.blocks_in_use == o.blocks_in_use
+
+
+def _matches(metric, d, i, rd, ri):
+    try:
+        assert_topk_matches(metric, d[None], i[None], rd[None], ri[None], rtol=1e-4, atol=1e-5)
+        return True
+    except AssertionError:
+        return False
+
+
+def whole_batches_check(w, g, o, n_search_threads):
+    """Base set in, then the insert stream batch by batch on a data stream while searcher threads
+    query on streams of their own.  A search must see whole batches only: its answer equals the
+    oracle's on SOME prefix of the batches, between those finished before it was submitted and those
+    submitted before it finished; at rest the answers are exactly the oracle's on everything."""
+    g.add(dev(w.base)); o.add(w.base)
+    nb = len(w.inserts) // w.insert_batch
+    batches = [w.inserts[b * w.insert_batch:(b + 1) * w.insert_batch] for b in range(nb)]
+    # the queries are the inserted vectors themselves, so every batch changes some answers
+    qh = np.concatenate([b[:2] for b in batches])[:64]
+    expected = [o.search(qh, w.k, w.nprobe)]
+    for b in batches:
+        o.add(b)
+        expected.append(o.search(qh, w.k, w.nprobe))
+    dbatches = [dev(b) for b in batches]
+    q = dev(qh)
+    torch.cuda.synchronize()
+
+    data = torch.cuda.Stream()
+    events = [torch.cuda.Event() for _ in range(nb)]
+    started, recorded = [0], [0]        # batches whose add has begun / whose event is on the stream
+    bad, checked = [], [0]
+
+    def completed():
+        c = 0
+        while c < recorded[0] and events[c].query():
+            c += 1
+        return c
+
+    def inserter():
+        for b in range(nb):
+            started[0] = b + 1
+            g.add(dbatches[b], stream=data)
+            events[b].record(data)
+            recorded[0] = b + 1
+            if b % 4 == 3:
+                data.synchronize()
+
+    def searcher():
+        s = torch.cuda.Stream()
+        od = torch.empty((len(qh), w.k), dtype=torch.float32, device="cuda:0")
+        oi = torch.empty((len(qh), w.k), dtype=torch.int64, device="cuda:0")
+        while True:
+            lo = completed()
+            try:
+                g.search(q, w.k, w.nprobe, od, oi, stream=s)
+            except rtams.RtamsError as e:
+                if e.code == rtams.EBUSY:
+                    s.synchronize(); continue
+                bad.append(str(e)); return
+            s.synchronize()
+            hi = started[0]
+            d, i = od.cpu().numpy(), oi.cpu().numpy()
+            for r in range(len(qh)):
+                ok = [p for p in range(lo, hi + 1)
+                      if _matches(w.metric, d[r], i[r], expected[p][0][r], expected[p][1][r])]
+                if not ok:
+                    bad.append(f"query {r}: no batch prefix in [{lo}, {hi}] explains the result"); return
+            checked[0] += 1
+            if lo >= nb:
+                return
+
+    ts = [threading.Thread(target=searcher) for _ in range(n_search_threads)]
+    ti = threading.Thread(target=inserter)
+    for t in ts:
+        t.start()
+    ti.start()
+    ti.join()
+    for t in ts:
+        t.join()
+    assert not bad, bad[0]
+    assert checked[0] >= n_search_threads
+    torch.cuda.synchronize()
+    assert g.poll_error() == 0
+    g.validate()
+    d, i = g.search(q, w.k, w.nprobe)                   # at rest: exactly the last prefix
+    assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), expected[-1][0], expected[-1][1],
+                        rtol=1e-4, atol=1e-5)

@@ -8,7 +8,7 @@ import torch
 
 from oracle.oracle import OracleIndex
 from paper_2408_02937_amd import rtams, synth
-from tests.gpu_common import dev
+from tests.gpu_common import dev, whole_batches_check
 from tests.helpers import assert_topk_matches
 
 pytestmark = pytest.mark.gpu
@@ -16,12 +16,12 @@ pytestmark = pytest.mark.gpu
 RTOL = 1e-4
 
 
-def make_pq_pair(w, M, cb, pool_blocks=None, rearrange_threshold=0, **kw):
+def make_pq_pair(w, M, cb, pool_blocks=None, rearrange_threshold=0, n_resources=2, **kw):
     n_all = len(w.base) + len(w.inserts)
     if pool_blocks is None:
         pool_blocks = n_all // w.block_vecs + 2 * w.nlist + 8
     g = rtams.Index(w.d, w.nlist, w.metric, w.block_vecs, pool_blocks=pool_blocks,
-                    rearrange_threshold=rearrange_threshold, n_resources=2, max_batch=256, max_k=128,
+                    rearrange_threshold=rearrange_threshold, n_resources=n_resources, max_batch=256, max_k=128,
                     max_nprobe=min(64, w.nlist), max_add_batch=65536, candidates_per_query=n_all + 64,
                     pq_m=M, **kw)
     g.set_centroids(dev(w.centroids))
@@ -203,3 +203,15 @@ def test_pq_state_and_argument_errors():
     with pytest.raises((rtams.RtamsError, ValueError)):
         f.set_codebooks(dev(np.zeros((4, 256, 4), np.float32)))
     f.close()
+
+
+def test_pq_search_sees_whole_batches_only():
+    """Insertion into coded lists on the data stream while two threads search: every answer is the
+    oracle's for some prefix of the batches (codes and ids of a batch become visible together)."""
+    w = synth.gaussian_l2("pq-concurrent", 79, d=32, n_base=10_000, n_queries=64, n_inserts=2_000,
+                          insert_batch=50, nlist=64, block_vecs=64)
+    cb = synth.codebooks_from_rows(w.seed, w.base, 8)
+    g, o = make_pq_pair(w, 8, cb, n_resources=8)
+    whole_batches_check(w, g, o, 2)
+    assert_code_lists_equal(g, o)
+    g.close()
