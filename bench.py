@@ -49,7 +49,8 @@ def main() -> int:
                     help="run only the plain copy kernel on 1 GiB (yardstick for the traffic counters)")
     ap.add_argument("--pq-m", type=int, default=0,
                     help="with --study pq: only this number of sub-spaces, and only the --batch query batch")
-    ap.add_argument("--study", choices=["rearrange", "blocksize", "pq"],
+    ap.add_argument("--shape", type=int, default=0, help="with --study shapes: only this configuration (3, 4 or 5)")
+    ap.add_argument("--study", choices=["rearrange", "blocksize", "pq", "shapes"],
                     help="run one of the side studies instead of the benchmark (one JSON line each)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -75,9 +76,12 @@ def main() -> int:
     if args.study:
         from paper_2408_02937_amd import studies
         fn = {"rearrange": studies.rearrangement_study, "blocksize": studies.block_size_sweep,
-              "pq": studies.pq_study}[args.study]
+              "pq": studies.pq_study, "shapes": studies.shape_study}[args.study]
         if args.study == "pq" and args.pq_m:
             print(json.dumps(fn(scale=args.scale, iters=args.latency_iters, ms=(args.pq_m,), batches=(args.batch,))))
+            return 0
+        if args.study == "shapes" and args.shape:
+            print(json.dumps(fn(scale=args.scale, iters=args.latency_iters, which=(args.shape,))))
             return 0
         print(json.dumps(fn(scale=args.scale, iters=args.latency_iters)))
         return 0

@@ -310,7 +310,9 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
     plen[p] = len;
     pay[p] = len;  // reuse as lengths for the prefix sum below
     // rank of this pair among the pairs that probe the same list (grouping for the scan)
-    S.pair_slot[(size_t)q * max_nprobe + p] = atomicAdd(&S.list_cnt[list], 1u);
+    const uint32_t slot = atomicAdd(&S.list_cnt[list], 1u);
+    S.pair_slot[(size_t)q * max_nprobe + p] = slot;
+    if (slot == 0) S.touched[atomicAdd(&S.queues->n_touched, 1u)] = (uint32_t)list;  // first pair of the list
   }
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -356,6 +358,7 @@ constexpr int kSampleMax = 4096;  // candidates the bound of a query is taken fr
 #define RTAMS_SAMPLE_DIVISOR 4
 #endif
 constexpr int kSampleDivisor = RTAMS_SAMPLE_DIVISOR;
+constexpr int kNoBoundBelow = 4096;  // candidates of a query up to which the scan keeps them all
 
 // The scan writes nothing for a candidate that cannot be among the k best of
 // its query: before it starts, every query gets a BOUND, the k-th best score
@@ -452,12 +455,25 @@ __device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, in
   __shared__ __attribute__((aligned(8))) uint32_t hist[256];
   __shared__ uint32_t bc[4];
   const int tid = threadIdx.x;
+  // A query with no more candidates than the selection holds in LDS at once needs no bound: its
+  // records cost less than a sample would (short lists, wide vectors).
+  if (S.qtotal[q] <= (uint32_t)kNoBoundBelow) {  // uniform over the workgroup
+    if (tid == 0) {
+      S.bound[q] = 0xFFFFFFFFu;
+      S.rec_cnt[q] = 0u;
+    }
+    return;
+  }
   // sample size: 4 k, at least 512 and at least a fraction of the nearest list (the longer that
-  // list, the more candidates a given score admits), at most kSampleMax, in whole groups
+  // list, the more candidates a given score admits), at most kSampleMax and at most 1 MiB of
+  // vectors (one workgroup reads the sample: a hot list of wide vectors would hold up the scan),
+  // in whole groups
+  uint32_t cap = PQ ? (uint32_t)kSampleMax : ((1u << 20) / ((uint32_t)D.d * 4u)) & ~(uint32_t)(kWave - 1);
+  cap = cap < 512u ? 512u : (cap > (uint32_t)kSampleMax ? (uint32_t)kSampleMax : cap);
   uint32_t want = (uint32_t)k * 4u;
   const uint32_t part = S.probe_len[(size_t)q * max_nprobe] / (uint32_t)kSampleDivisor;
   want = want < part ? part : want;
-  want = want < 512u ? 512u : (want > (uint32_t)kSampleMax ? (uint32_t)kSampleMax : want);
+  want = want < 512u ? 512u : (want > cap ? cap : want);
   const uint32_t want_groups = (want + kWave - 1) / kWave;
   if (!PQ)
     for (int c = tid; c < D.d4; c += kGroupThreads) qv[c] = reinterpret_cast<const float4 *>(Q + (size_t)q * D.d)[c];
@@ -495,6 +511,7 @@ __device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, in
 // for which the request has at most `item_budget` items and no XCD more than
 // `max_per_xcd` (the launch of the scan is sized from those two).
 constexpr int kSegChoices = 8;  // segment lengths 2, 4, ..., 256 groups
+constexpr int kListChunk = 16;  // lists a thread of the grouping workgroup handles side by side
 
 __device__ inline void wg_scan3(uint32_t &a, uint32_t &b, unsigned long long &c, uint32_t *sa,
                                 uint32_t *sb, unsigned long long *sc) {
@@ -538,13 +555,27 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
   __shared__ unsigned long long s_c[kGroupThreads];
   __shared__ uint32_t s_items[kSegChoices];
   __shared__ uint32_t s_begin[9];
-  __shared__ uint32_t s_istart[kGroupThreads];
-  const int tid = threadIdx.x;
-  const int per = (D.nlist + kGroupThreads - 1) / kGroupThreads;
-  const int l0 = tid * per, l1 = min(D.nlist, l0 + per);
-  uint32_t *list_cnt = S.list_cnt, *list_len = S.list_len, *grouped = S.grouped;
-  uint4 *tile_desc = S.tile_desc;
+  constexpr uint32_t kHugeItems = 512, kHugeCap = 64;  // lists with this many items: at most so many are spread over the workgroup
+  __shared__ uint4 s_huge_pl[kHugeCap];
+  __shared__ uint32_t s_huge_ist[kHugeCap];
+  __shared__ uint32_t s_nhuge;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  if (tid == 0) s_nhuge = 0;
+  uint32_t *__restrict__ list_cnt = S.list_cnt;
+  uint32_t *grouped = S.grouped;
+  uint4 *__restrict__ tile_desc = S.tile_desc;
+  uint4 *__restrict__ plist = S.plist;
+  uint32_t *__restrict__ pistart = S.pistart;
   ScanQueues *Qs = S.queues;
+  // The probed lists of the request, in the order in which their first pair was registered by the
+  // plan (any order serves: the items of one list follow each other, that is all the scan needs).
+  // A thread owns `per` consecutive entries and walks them kListChunk at a time, so that the loads
+  // of a chunk go out together: this workgroup is alone on its CU, and a pass over the lists is a
+  // chain of memory latencies otherwise.  Lists nobody probes are never looked at (16,384 lists and
+  // 256 x 64 pairs: a third of the lists).
+  const uint32_t n_c = Qs->n_touched;
+  const uint32_t per = (n_c + kGroupThreads - 1) / kGroupThreads;
+  const uint32_t e0 = min(n_c, (uint32_t)tid * per), e1 = min(n_c, e0 + per);
   // Cost of a list for the split over the XCDs, per group of 64 vectors: reading it once from HBM
   // (each XCD has its own link to memory) plus the arithmetic of every query that probes it.  On
   // this chip one group's bytes cost about as much as the arithmetic of 12 queries (L2) or 24 (IP).
@@ -559,18 +590,26 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
     uint32_t cnt[kSegChoices];
 #pragma unroll
     for (int e = 0; e < kSegChoices; ++e) cnt[e] = 0;
-    for (int l = l0; l < l1; ++l) {
-      const uint32_t c = list_cnt[l];
-      const uint32_t len =
-          c ? __hip_atomic_load(&D.visible_len[l], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
-      list_len[l] = len;
-      if (!c) continue;
-      const uint32_t groups = (len + kWave - 1) / kWave;
-      const uint32_t tiles = (c + kScanTileQueries - 1) / kScanTileQueries;
+    for (uint32_t eb = e0; eb < e1; eb += kListChunk) {
+      uint32_t l[kListChunk], c[kListChunk], len[kListChunk];
 #pragma unroll
-      for (int e = 0; e < kSegChoices; ++e) {
-        const uint32_t sg = 2u << e;
-        cnt[e] += (groups ? (groups + sg - 1) / sg : 1u) * tiles;
+      for (int t = 0; t < kListChunk; ++t) l[t] = eb + t < e1 ? S.touched[eb + t] : 0u;
+#pragma unroll
+      for (int t = 0; t < kListChunk; ++t) c[t] = eb + t < e1 ? list_cnt[l[t]] : 0u;
+#pragma unroll
+      for (int t = 0; t < kListChunk; ++t)
+        len[t] = eb + t < e1 ? __hip_atomic_load(&D.visible_len[l[t]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+#pragma unroll
+      for (int t = 0; t < kListChunk; ++t) {
+        if (eb + t >= e1) continue;
+        plist[eb + t] = make_uint4(l[t], 0u, c[t], len[t]);
+        const uint32_t groups = (len[t] + kWave - 1) / kWave;
+        const uint32_t tiles = (c[t] + kScanTileQueries - 1) / kScanTileQueries;
+#pragma unroll
+        for (int e = 0; e < kSegChoices; ++e) {
+          const uint32_t sg = 2u << e;
+          cnt[e] += (groups ? (groups + sg - 1) / sg : 1u) * tiles;
+        }
       }
     }
     // totals per choice: shuffles inside the wavefront, one LDS atomic per wavefront
@@ -579,7 +618,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
     for (int e = 0; e < kSegChoices; ++e) {
       uint32_t v = cnt[e];
       for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
-      if ((tid & (kWave - 1)) == 0 && v) atomicAdd(&s_items[e], v);
+      if (lane == 0 && v) atomicAdd(&s_items[e], v);
     }
   }
   __syncthreads();
@@ -591,40 +630,52 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
     const uint32_t seg = 2u << choice;
     uint32_t np = 0, ni = 0;
     unsigned long long wk = 0;
-    for (int l = l0; l < l1; ++l) {
-      const uint32_t c = list_cnt[l];
-      if (!c) continue;
-      const uint32_t groups = (list_len[l] + kWave - 1) / kWave;
-      np += c;
-      ni += (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
-      wk += (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
+    for (uint32_t eb = e0; eb < e1; eb += kListChunk) {
+      uint4 pl[kListChunk];
+#pragma unroll
+      for (int t = 0; t < kListChunk; ++t) pl[t] = eb + t < e1 ? plist[eb + t] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+      for (int t = 0; t < kListChunk; ++t) {
+        const uint32_t c = pl[t].z;
+        if (!c) continue;
+        const uint32_t groups = (pl[t].w + kWave - 1) / kWave;
+        np += c;
+        ni += (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
+        wk += (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
+      }
     }
     uint32_t inp = np, ini = ni;
     unsigned long long iwk = wk;
     wg_scan3(inp, ini, iwk, s_a, s_b, s_c);
-    const uint32_t total_pairs = s_a[kGroupThreads - 1];
     const uint32_t total_items = s_b[kGroupThreads - 1];
     const unsigned long long total_work = s_c[kGroupThreads - 1];
-    uint32_t pstart = inp - np, istart = ini - ni;
-    unsigned long long wstart = iwk - wk;
+    const uint32_t pstart0 = inp - np, istart0 = ini - ni;
+    const unsigned long long wstart0 = iwk - wk;
     // XCD x starts at the item at which the work prefix passes x/8 of the total
     if (tid < 9) s_begin[tid] = tid == 8 ? total_items : 0u;
     __syncthreads();
     {
-      uint32_t is = istart;
-      unsigned long long ws = wstart;
-      for (int l = l0; l < l1; ++l) {
-        const uint32_t c = list_cnt[l];
-        if (!c) continue;
-        const uint32_t groups = (list_len[l] + kWave - 1) / kWave;
-        const unsigned long long w = (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
-        const uint32_t n = (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
-        for (uint32_t x = 1; x < 8; ++x) {  // the cut falls inside this list: at the item the same share of it ends at
-          const unsigned long long cut = total_work * x / 8;
-          if (ws <= cut && cut < ws + w) s_begin[x] = is + (uint32_t)((cut - ws) * n / w);
+      uint32_t is = istart0;
+      unsigned long long ws = wstart0;
+      for (uint32_t eb = e0; eb < e1; eb += kListChunk) {
+        uint4 pl[kListChunk];
+#pragma unroll
+        for (int t = 0; t < kListChunk; ++t) pl[t] = eb + t < e1 ? plist[eb + t] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+        for (int t = 0; t < kListChunk; ++t) {
+          const uint32_t c = pl[t].z;
+          if (!c) continue;
+          const uint32_t groups = (pl[t].w + kWave - 1) / kWave;
+          const unsigned long long w = (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
+          const uint32_t n =
+              (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
+          for (uint32_t x = 1; x < 8; ++x) {  // the cut falls inside this list: at the item the same share of it ends at
+            const unsigned long long cut = total_work * x / 8;
+            if (ws <= cut && cut < ws + w) s_begin[x] = is + (uint32_t)((cut - ws) * n / w);
+          }
+          is += n;
+          ws += w;
         }
-        is += n;
-        ws += w;
       }
     }
     __syncthreads();
@@ -650,57 +701,104 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
         D.mirror->error = -6;
       }
     }
-    s_istart[tid] = istart;  // where the items of this thread's lists start
-    for (int l = l0; l < l1; ++l) {
-      const uint32_t c = list_cnt[l];
-      list_cnt[l] = pstart;  // from here on: where the list's pairs start
-      pstart += c;
-    }
-    __syncthreads();  // list starts and item starts written above are read below by other threads
-    // Item descriptors: every thread writes an equal share of consecutive items, whatever
-    // lists they belong to (a hot list probed by many queries has hundreds of items, most
-    // lists a dozen).  Item j lies in the lists of the last thread whose items start at or
-    // before j; inside a list the tiles of one segment follow each other, and the tiles are
-    // of (almost) equal size.
-    if (fits) {
-      const uint32_t share = (total_items + kGroupThreads - 1) / kGroupThreads;
-      uint32_t j = (uint32_t)tid * share;
-      const uint32_t j_end = min(total_items, j + share);
-      while (j < j_end) {
-        const uint32_t j_before = j;
-        int lo = 0, hi = kGroupThreads - 1;
-        while (lo < hi) {
-          const int mid = (lo + hi + 1) >> 1;
-          if (s_istart[mid] <= j) lo = mid; else hi = mid - 1;
-        }
-        uint32_t base = s_istart[lo];
-        const int le = min(D.nlist, lo * per + per);
-        for (int l = lo * per; l < le && j < j_end; ++l) {
-          const uint32_t start = list_cnt[l];
-          const uint32_t c = (l + 1 < D.nlist ? list_cnt[l + 1] : total_pairs) - start;
+    // where the pairs and the items of every probed list start
+    {
+      uint32_t ps = pstart0, is = istart0;
+      for (uint32_t eb = e0; eb < e1; eb += kListChunk) {
+        uint4 pl[kListChunk];
+#pragma unroll
+        for (int t = 0; t < kListChunk; ++t) pl[t] = eb + t < e1 ? plist[eb + t] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+        for (int t = 0; t < kListChunk; ++t) {
+          const uint32_t c = pl[t].z;
           if (!c) continue;
-          const uint32_t groups = (list_len[l] + kWave - 1) / kWave;
-          const uint32_t segs = groups ? (groups + seg - 1) / seg : 1u;
-          const uint32_t tiles = (c + kScanTileQueries - 1) / kScanTileQueries;
-          const uint32_t n = segs * tiles;
-          if (j < base + n) {
-            const uint32_t r = j - base, stop = min(j_end, base + n);
-            uint32_t sg = r / tiles, t = r - sg * tiles;
-            const uint32_t small = c / tiles, extra = c - small * tiles;  // the first `extra` tiles hold one more
-            for (; j < stop; ++j) {
-              const uint32_t p_lo = t * small + min(t, extra);
-              tile_desc[j] = make_uint4((uint32_t)l, start + p_lo, small + (t < extra ? 1u : 0u), sg);
-              if (++t == tiles) { t = 0; ++sg; }
-            }
-          }
-          base += n;
+          const uint32_t groups = (pl[t].w + kWave - 1) / kWave;
+          plist[eb + t] = make_uint4(pl[t].x, ps, c, pl[t].w);
+          pistart[eb + t] = is;
+          list_cnt[pl[t].x] = ps;  // from here on: where the list's pairs start
+          ps += c;
+          is += (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
         }
-        // j is now past this thread's share, or at the first item of a list of a later thread
-        if (j == j_before) break;  // cannot happen: the item counts above are the ones the starts were made from
+      }
+    }
+    __syncthreads();  // entries written above are read below by other threads
+    // Item descriptors.  A wavefront takes a sixteenth of the entries, 64 at a time, lane = entry.
+    // Most lists have a handful of items: their lane writes them itself.  A list with more is taken
+    // by the whole wavefront, the lanes writing its items side by side, and one with very many (a
+    // hot list probed by dozens of queries has thousands) by the whole workgroup afterwards.  Inside a list the tiles of one segment follow each other,
+    // and the tiles are of (almost) equal size.
+    if (fits) {
+      constexpr uint32_t kWaves = kGroupThreads / kWave;
+      constexpr uint32_t kOwnItems = 16;
+      const uint32_t w0 = (uint32_t)((unsigned long long)n_c * wave / kWaves);
+      const uint32_t w1 = (uint32_t)((unsigned long long)n_c * (wave + 1) / kWaves);
+      for (uint32_t eb = w0; eb < w1; eb += kWave) {
+        const uint32_t mine = eb + (uint32_t)lane;
+        const uint4 pl = mine < w1 ? plist[mine] : make_uint4(0u, 0u, 0u, 0u);
+        const uint32_t ist = mine < w1 ? pistart[mine] : 0u;
+        uint32_t n = 0, tiles = 1, small = 0, extra = 0;
+        if (pl.z) {
+          const uint32_t groups = (pl.w + kWave - 1) / kWave;
+          tiles = (pl.z + kScanTileQueries - 1) / kScanTileQueries;
+          n = (groups ? (groups + seg - 1) / seg : 1u) * tiles;
+          small = pl.z / tiles;
+          extra = pl.z - small * tiles;  // the first `extra` tiles hold one more
+        }
+        if (n <= kOwnItems) {
+          uint32_t sg = 0, tt = 0;
+          for (uint32_t i = 0; i < n; ++i) {
+            const uint32_t p_lo = tt * small + min(tt, extra);
+            tile_desc[ist + i] = make_uint4(pl.x, pl.y + p_lo, small + (tt < extra ? 1u : 0u), sg);
+            if (++tt == tiles) { tt = 0; ++sg; }
+          }
+        }
+        // the few lists with very many items are left to the whole workgroup (below)
+        bool huge = n >= kHugeItems;
+        if (huge) {
+          const uint32_t slot = atomicAdd(&s_nhuge, 1u);
+          if (slot < kHugeCap) {
+            s_huge_pl[slot] = pl;
+            s_huge_ist[slot] = ist;
+          } else {
+            huge = false;  // no room: the wavefront takes it after all
+          }
+        }
+        unsigned long long big = __ballot(n > kOwnItems && !huge);
+        while (big) {  // uniform over the wavefront
+          const int t = __builtin_ctzll(big);
+          big &= big - 1;
+          const uint32_t l = (uint32_t)__shfl((int)pl.x, t), ps = (uint32_t)__shfl((int)pl.y, t);
+          const uint32_t first = (uint32_t)__shfl((int)ist, t), n_t = (uint32_t)__shfl((int)n, t);
+          const uint32_t tiles_t = (uint32_t)__shfl((int)tiles, t);
+          const uint32_t small_t = (uint32_t)__shfl((int)small, t), extra_t = (uint32_t)__shfl((int)extra, t);
+          for (uint32_t i = (uint32_t)lane; i < n_t; i += kWave) {
+            const uint32_t sg = i / tiles_t, tt = i - sg * tiles_t;
+            const uint32_t p_lo = tt * small_t + min(tt, extra_t);
+            tile_desc[first + i] = make_uint4(l, ps + p_lo, small_t + (tt < extra_t ? 1u : 0u), sg);
+          }
+        }
+      }
+    }
+    __syncthreads();
+    if (fits) {
+      const uint32_t nh = min(s_nhuge, kHugeCap);
+      for (uint32_t h = 0; h < nh; ++h) {  // uniform over the workgroup
+        const uint4 pl = s_huge_pl[h];
+        const uint32_t first = s_huge_ist[h];
+        const uint32_t groups = (pl.w + kWave - 1) / kWave;
+        const uint32_t tiles = (pl.z + kScanTileQueries - 1) / kScanTileQueries;
+        const uint32_t n = (groups ? (groups + seg - 1) / seg : 1u) * tiles;
+        const uint32_t small = pl.z / tiles, extra = pl.z - small * tiles;
+        for (uint32_t i = (uint32_t)tid; i < n; i += kGroupThreads) {
+          const uint32_t sg = i / tiles, tt = i - sg * tiles;
+          const uint32_t p_lo = tt * small + min(tt, extra);
+          tile_desc[first + i] = make_uint4(pl.x, pl.y + p_lo, small + (tt < extra ? 1u : 0u), sg);
+        }
       }
     }
     break;
   }
+  __syncthreads();  // the pair starts written above are read below by other threads
   // scatter of the pairs into their list's group, eight independent chains of loads per thread
   const int npairs = nq * nprobe;
   for (int base = tid; base < npairs; base += 8 * kGroupThreads) {

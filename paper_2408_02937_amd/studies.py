@@ -13,7 +13,11 @@
   and scan time per query batch, insertion latency, and how many of the flat
   index's top-k the coded index returns.
 
-All use configuration 2's synthetic data (byte-valued, d = 128, 1 M vectors,
+* `shape_study`: configurations 3, 4 and 5 (other dimensions, metrics, list
+  counts, block sizes and batch sizes) at a fraction of their base sets: load
+  rate, latency per request at the configuration's batch, scan time and bytes.
+
+The first three use configuration 2's synthetic data (byte-valued, d = 128, 1 M vectors,
 1024 lists) and go through the same C ABI as everything else.
 """
 from __future__ import annotations
@@ -267,3 +271,67 @@ def pq_study(scale: float = 1.0, ms=(16, 32), iters: int = 200, batches=(1, 10, 
         g.close()
     return {"study": "product_quantised_lists", "workload": w.name, "k": w.k, "nprobe": w.nprobe,
             "codebooks": "256 sampled sub-vectors per sub-space (untrained)", "rows": rows}
+
+
+def shape_study(scale: float = 1.0, iters: int = 100, which=(3, 4, 5)) -> dict:
+    """scale 1.0 stands for a fifth of configuration 3's and 4's base sets (2 M x 96, 1 M x 768) and a
+    tenth of configuration 5's (2 M x 256): the host has to draw them."""
+    dev = torch.device("cuda:0")
+    frac = {3: 0.2, 4: 0.2, 5: 0.1}
+    batches = {3: (128,), 4: (1, 64), 5: (256,)}
+    rows = []
+    for idx in which:
+        t0 = time.perf_counter()
+        w = synth.config(idx, scale=frac[idx] * scale)
+        t_gen = time.perf_counter() - t0
+        base, cents, queries, inserts = (_to_dev(a, dev) for a in (w.base, w.centroids, w.queries, w.inserts))
+        n_all = len(w.base) + 2 * len(w.inserts)
+        g = rtams.Index(w.d, w.nlist, w.metric, w.block_vecs, pool_blocks=n_all // w.block_vecs + 2 * w.nlist + 64,
+                        n_resources=8, max_batch=256, max_k=128, max_nprobe=64, max_add_batch=65536,
+                        candidates_per_query=max(65536, 4 * w.nprobe * (len(w.base) // w.nlist + w.block_vecs)))
+        ds, ss = torch.cuda.Stream(dev), torch.cuda.Stream(dev)
+        g.set_centroids(cents, stream=ds)
+        t0 = time.perf_counter()
+        g.add(base, stream=ds)
+        ds.synchronize()
+        bulk_s = time.perf_counter() - t0
+        sizes_now = g.list_sizes()
+        st = g.pool_stats()
+        row = {"workload": w.name, "n_base": len(w.base), "d": w.d, "nlist": w.nlist, "metric": w.metric,
+               "block_vecs": w.block_vecs, "nprobe": w.nprobe, "k": w.k, "host_generation_s": t_gen,
+               "bulk_load_vectors_per_s": len(w.base) / bulk_s, "blocks_in_use": st.blocks_in_use,
+               "longest_list": int(sizes_now.max()), "search": {}}
+        for bs in batches[idx]:
+            g.scan_time(reset=True)
+            g.set_param("profile_scan", 1)
+            lat = _search_latencies(g, queries, bs, w.k, w.nprobe, iters, ss, dev)
+            g.set_param("profile_scan", 0)
+            ms, cnt = g.scan_time(reset=True)
+            nb = max(len(queries) // bs, 1)
+            ub = []
+            for i in range(min(16, nb)):
+                pl = g.probe(queries[i * bs:(i + 1) * bs], w.nprobe).cpu().numpy()
+                ub.append(int((sizes_now[np.unique(pl)] * w.d * 4).sum()))
+            scan_ms = ms / max(cnt, 1)
+            gbps = float(np.mean(ub)) / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else None
+            row["search"][str(bs)] = {"p50_ms": _p(lat, 50), "p99_ms": _p(lat, 99), "qps": bs / (np.mean(lat) * 1e-3),
+                                      "scan_ms": scan_ms, "scan_bytes": float(np.mean(ub)), "scan_GBps": gbps,
+                                      "frac_of_hbm_peak": gbps / 8000.0 if gbps else None}
+        ib = w.insert_batch
+        n_ib = max(len(inserts) // ib, 1)
+        lat = []
+        for i in range(iters + 10):
+            t0 = time.perf_counter()
+            g.add(inserts[(i % n_ib) * ib:(i % n_ib) * ib + ib], stream=ds)
+            ds.synchronize()
+            if i >= 10:
+                lat.append((time.perf_counter() - t0) * 1e3)
+        row["insert_batch"] = ib
+        row["insert_p50_ms"] = _p(lat, 50)
+        row["inserts_per_s_one_batch_in_flight"] = ib / (np.mean(lat) * 1e-3)
+        assert g.poll_error() == 0
+        rows.append(row)
+        g.close()
+        del base, cents, queries, inserts, w
+        torch.cuda.empty_cache()
+    return {"study": "shapes", "rows": rows}

@@ -34,3 +34,13 @@ def test_pq_study_small():
     assert r["pool_bytes"] < r["flat_pool_bytes"]  # (the fixed part of the pool dominates at this scale)
     assert 0.0 < r["share_of_flat_topk_returned"] <= 1.0
     assert r["search"]["256"]["scan_ms"] > 0
+
+
+def test_shape_study_small():
+    from paper_2408_02937_amd import studies
+    print("[case] shape study, scale 0.02", flush=True)
+    out = studies.shape_study(scale=0.02, iters=5)
+    assert [r["d"] for r in out["rows"]] == [96, 768, 256]
+    for r in out["rows"]:
+        for v in r["search"].values():
+            assert v["scan_ms"] > 0 and v["p50_ms"] > 0
