@@ -10,8 +10,7 @@ namespace rtams {
 struct ScanQueues {
   uint32_t begin[9];    // XCD x owns items begin[x] .. begin[x+1]-1
   uint32_t seg_groups;  // 64-vector groups per work item
-  uint32_t n_touched;   // lists probed by the request (counted by the plan as their first pair arrives)
-  uint32_t pad[21];
+  uint32_t pad[22];
 };
 
 // The scan keeps, for every query, only the candidates that are not worse than
@@ -31,11 +30,11 @@ struct SearchScratch {
   uint32_t *rec_cnt;    // [max_batch] survivors recorded so far
   unsigned long long *cursor; // bump pointer into the survivor records
   uint32_t *list_cnt;   // [nlist] queries probing each list, then start of the list's pair group
-  uint32_t *touched;    // [min(nlist, max_batch * max_nprobe)] the probed lists, in order of arrival
   uint32_t *pair_slot;  // [max_batch][max_nprobe] rank of the pair among the pairs of its list
   uint32_t *grouped;    // [max_batch * max_nprobe] pairs (query << 10 | probe) grouped by list
-  uint4 *plist;         // [as touched] per probed list {list, first pair, pairs, length as seen by the grouping step}
-  uint32_t *pistart;    // [as touched] first work item of the list
+  uint4 *plist;         // [min(nlist, max_batch * max_nprobe)] per probed list, in list order: {list, first pair,
+                        // pairs, length as seen by the grouping step}
+  uint32_t *pistart;    // [as plist] first work item of the list
   uint4 *tile_desc;     // [item_cap] {list, first pair of the tile, pairs of the tile, segment} per item
   uint32_t item_cap;
   ScanQueues *queues;   // work items of this request, split into one queue per XCD

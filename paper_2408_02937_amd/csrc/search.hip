@@ -310,9 +310,7 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
     plen[p] = len;
     pay[p] = len;  // reuse as lengths for the prefix sum below
     // rank of this pair among the pairs that probe the same list (grouping for the scan)
-    const uint32_t slot = atomicAdd(&S.list_cnt[list], 1u);
-    S.pair_slot[(size_t)q * max_nprobe + p] = slot;
-    if (slot == 0) S.touched[atomicAdd(&S.queues->n_touched, 1u)] = (uint32_t)list;  // first pair of the list
+    S.pair_slot[(size_t)q * max_nprobe + p] = atomicAdd(&S.list_cnt[list], 1u);
   }
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -559,6 +557,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
   __shared__ uint4 s_huge_pl[kHugeCap];
   __shared__ uint32_t s_huge_ist[kHugeCap];
   __shared__ uint32_t s_nhuge;
+  __shared__ uint32_t s_rows[kListChunk * (kGroupThreads / kWave) + 1];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   if (tid == 0) s_nhuge = 0;
   uint32_t *__restrict__ list_cnt = S.list_cnt;
@@ -567,60 +566,95 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
   uint4 *__restrict__ plist = S.plist;
   uint32_t *__restrict__ pistart = S.pistart;
   ScanQueues *Qs = S.queues;
-  // The probed lists of the request, in the order in which their first pair was registered by the
-  // plan (any order serves: the items of one list follow each other, that is all the scan needs).
-  // A thread owns `per` consecutive entries and walks them kListChunk at a time, so that the loads
-  // of a chunk go out together: this workgroup is alone on its CU, and a pass over the lists is a
-  // chain of memory latencies otherwise.  Lists nobody probes are never looked at (16,384 lists and
-  // 256 x 64 pairs: a third of the lists).
-  const uint32_t n_c = Qs->n_touched;
-  const uint32_t per = (n_c + kGroupThreads - 1) / kGroupThreads;
-  const uint32_t e0 = min(n_c, (uint32_t)tid * per), e1 = min(n_c, e0 + per);
   // Cost of a list for the split over the XCDs, per group of 64 vectors: reading it once from HBM
   // (each XCD has its own link to memory) plus the arithmetic of every query that probes it.  On
   // this chip one group's bytes cost about as much as the arithmetic of 12 queries (L2) or 24 (IP).
   const uint32_t byte_weight = D.metric == 0 ? 12u : 24u;
 
-  // The visible length of every probed list is read ONCE: an insertion may publish
-  // while this kernel runs, and the passes below must agree on the segment counts.
-  // (Each pair's own snapshot was taken earlier, so it is not longer than this one.)
+  // The probed lists, compacted in list order (neighbouring lists sit in neighbouring blocks after a
+  // bulk load, and the scan reads faster in that order): entry = {list, first pair, pairs, length}.
+  // The pair counters are read 1024 consecutive lists at a time, 16 such rows per thread in flight;
+  // the place of a probed list among the entries comes from ballots and one small prefix sum.  Lists
+  // nobody probes are not looked at again (16,384 lists, 256 x 64 pairs: a quarter of the lists).
+  // The visible length of every probed list is read ONCE: an insertion may publish while this kernel
+  // runs, and the passes below must agree on the segment counts.  (Each pair's own snapshot was
+  // taken earlier, so it is not longer than this one.)
+  uint32_t n_c = 0;
+  uint32_t cnt[kSegChoices];  // work items of this thread's lists for every segment length
+#pragma unroll
+  for (int e = 0; e < kSegChoices; ++e) cnt[e] = 0;
   if (tid < kSegChoices) s_items[tid] = 0;
-  __syncthreads();
-  {
-    uint32_t cnt[kSegChoices];
+  constexpr int kWavesG = kGroupThreads / kWave;
+  for (int lb = 0; lb < D.nlist; lb += kListChunk * kGroupThreads) {  // uniform over the workgroup
+    const int rows = min(kListChunk, (D.nlist - lb + kGroupThreads - 1) / kGroupThreads);
+    uint32_t c[kListChunk];
+    unsigned long long flags[kListChunk];
 #pragma unroll
-    for (int e = 0; e < kSegChoices; ++e) cnt[e] = 0;
-    for (uint32_t eb = e0; eb < e1; eb += kListChunk) {
-      uint32_t l[kListChunk], c[kListChunk], len[kListChunk];
+    for (int t = 0; t < kListChunk; ++t) {
+      const int l = lb + t * kGroupThreads + tid;
+      c[t] = t < rows && l < D.nlist ? list_cnt[l] : 0u;
+    }
 #pragma unroll
-      for (int t = 0; t < kListChunk; ++t) l[t] = eb + t < e1 ? S.touched[eb + t] : 0u;
-#pragma unroll
-      for (int t = 0; t < kListChunk; ++t) c[t] = eb + t < e1 ? list_cnt[l[t]] : 0u;
-#pragma unroll
-      for (int t = 0; t < kListChunk; ++t)
-        len[t] = eb + t < e1 ? __hip_atomic_load(&D.visible_len[l[t]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
-#pragma unroll
-      for (int t = 0; t < kListChunk; ++t) {
-        if (eb + t >= e1) continue;
-        plist[eb + t] = make_uint4(l[t], 0u, c[t], len[t]);
-        const uint32_t groups = (len[t] + kWave - 1) / kWave;
-        const uint32_t tiles = (c[t] + kScanTileQueries - 1) / kScanTileQueries;
-#pragma unroll
-        for (int e = 0; e < kSegChoices; ++e) {
-          const uint32_t sg = 2u << e;
-          cnt[e] += (groups ? (groups + sg - 1) / sg : 1u) * tiles;
-        }
+    for (int t = 0; t < kListChunk; ++t) {
+      flags[t] = 0ull;
+      if (t < rows) {  // uniform
+        flags[t] = __ballot(c[t] != 0u);
+        if (lane == 0) s_rows[t * kWavesG + wave] = (uint32_t)__popcll(flags[t]);
       }
     }
-    // totals per choice: shuffles inside the wavefront, one LDS atomic per wavefront
-    // (every lane adding to the same LDS word would serialise)
-#pragma unroll
-    for (int e = 0; e < kSegChoices; ++e) {
-      uint32_t v = cnt[e];
-      for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
-      if (lane == 0 && v) atomicAdd(&s_items[e], v);
+    __syncthreads();
+    if (wave == 0) {  // running sum over the (row, wavefront) counts, in list order
+      uint32_t carry = 0;
+      const int counts = rows * kWavesG;
+      for (int i0 = 0; i0 < counts; i0 += kWave) {
+        const uint32_t v = i0 + lane < counts ? s_rows[i0 + lane] : 0u;
+        uint32_t incl = v;
+        for (int o = 1; o < kWave; o <<= 1) {
+          const uint32_t x = __shfl_up(incl, o);
+          if (lane >= o) incl += x;
+        }
+        if (i0 + lane < counts) s_rows[i0 + lane] = carry + incl - v;
+        carry += __shfl(incl, kWave - 1);
+      }
+      if (lane == 0) s_rows[kListChunk * kWavesG] = carry;
     }
+    __syncthreads();
+    uint32_t len[kListChunk];
+#pragma unroll
+    for (int t = 0; t < kListChunk; ++t)
+      len[t] = c[t] ? __hip_atomic_load(&D.visible_len[lb + t * kGroupThreads + tid], __ATOMIC_RELAXED,
+                                        __HIP_MEMORY_SCOPE_AGENT)
+                    : 0u;
+#pragma unroll
+    for (int t = 0; t < kListChunk; ++t) {
+      if (!c[t]) continue;
+      const uint32_t at =
+          n_c + s_rows[t * kWavesG + wave] + (uint32_t)__popcll(flags[t] & ((1ull << lane) - 1ull));
+      plist[at] = make_uint4((uint32_t)(lb + t * kGroupThreads + tid), 0u, c[t], len[t]);
+      const uint32_t groups = (len[t] + kWave - 1) / kWave;
+      const uint32_t tiles = (c[t] + kScanTileQueries - 1) / kScanTileQueries;
+#pragma unroll
+      for (int e = 0; e < kSegChoices; ++e) {
+        const uint32_t sg = 2u << e;
+        cnt[e] += (groups ? (groups + sg - 1) / sg : 1u) * tiles;
+      }
+    }
+    n_c += s_rows[kListChunk * kWavesG];
+    __syncthreads();  // the counts are reused by the next rows; the entries are read below by other threads
   }
+  // totals per segment length: shuffles inside the wavefront, one LDS atomic per wavefront
+  // (every lane adding to the same LDS word would serialise)
+#pragma unroll
+  for (int e = 0; e < kSegChoices; ++e) {
+    uint32_t v = cnt[e];
+    for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    if (lane == 0 && v) atomicAdd(&s_items[e], v);
+  }
+  // From here on a thread owns `per` consecutive entries and walks them kListChunk at a time, so
+  // that the loads of a chunk go out together: this workgroup is alone on its CU, and a pass over the
+  // entries is a chain of memory latencies otherwise.
+  const uint32_t per = (n_c + kGroupThreads - 1) / kGroupThreads;
+  const uint32_t e0 = min(n_c, (uint32_t)tid * per), e1 = min(n_c, e0 + per);
   __syncthreads();
   int choice = kSegChoices - 1;
   for (int e = 0; e < kSegChoices; ++e)
