@@ -136,7 +136,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
 
 struct ScratchLayout {
   size_t scores, approx, probe_list, probe_len, probe_off, qbase, qtotal, bound, rec_cnt, cursor, lut, records, fixed;
-  size_t list_cnt, pair_slot, grouped, plist, pistart, tile_desc, queues, item_cap;
+  size_t list_cnt, pair_start, pair_slot, grouped, plist, pistart, tile_desc, queues, item_cap;
 };
 
 void lay_out_scratch(const rtams_config *c, ScratchLayout *S) {
@@ -158,6 +158,7 @@ void lay_out_scratch(const rtams_config *c, ScratchLayout *S) {
   S->list_cnt = take((size_t)c->nlist * 4);
   S->queues = take(sizeof(ScanQueues));
   const size_t probed = mb * mp < (size_t)c->nlist ? mb * mp : (size_t)c->nlist;  // lists one request can probe
+  S->pair_start = take((size_t)c->nlist * 4);
   S->pair_slot = take(mb * mp * 4);
   S->grouped = take(mb * mp * 4);
   S->plist = take(probed * 16);
@@ -438,6 +439,7 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
     S.rec_cnt = reinterpret_cast<uint32_t *>(p + SL.rec_cnt);
     S.cursor = reinterpret_cast<unsigned long long *>(p + SL.cursor);
     S.list_cnt = reinterpret_cast<uint32_t *>(p + SL.list_cnt);
+    S.pair_start = reinterpret_cast<uint32_t *>(p + SL.pair_start);
     S.pair_slot = reinterpret_cast<uint32_t *>(p + SL.pair_slot);
     S.grouped = reinterpret_cast<uint32_t *>(p + SL.grouped);
     S.plist = reinterpret_cast<uint4 *>(p + SL.plist);

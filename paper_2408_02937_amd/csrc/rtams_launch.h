@@ -29,7 +29,8 @@ struct SearchScratch {
   uint32_t *bound;      // [max_batch] key of the score the scan compares with
   uint32_t *rec_cnt;    // [max_batch] survivors recorded so far
   unsigned long long *cursor; // bump pointer into the survivor records
-  uint32_t *list_cnt;   // [nlist] queries probing each list, then start of the list's pair group
+  uint32_t *list_cnt;   // [nlist] queries probing each list
+  uint32_t *pair_start; // [nlist] where the pairs of a probed list start in `grouped`
   uint32_t *pair_slot;  // [max_batch][max_nprobe] rank of the pair among the pairs of its list
   uint32_t *grouped;    // [max_batch * max_nprobe] pairs (query << 10 | probe) grouped by list
   uint4 *plist;         // [min(nlist, max_batch * max_nprobe)] per probed list, in list order: {list, first pair,
@@ -123,8 +124,8 @@ void launch_publish(const Dev &D, hipStream_t s);
 // search.hip -----------------------------------------------------------------
 void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const SearchScratch &S,
                        const float *Q, bool from_approx, int32_t *probe_out, hipStream_t s);
-// One launch does two things side by side: one workgroup groups the pairs by list
-// and cuts the scan into work items; one workgroup per query sets the query's bound.
+// One launch does three things side by side: one workgroup cuts the scan into work
+// items, one groups the pairs by list, one per query sets the query's bound.
 // (Quantised lists are scanned per query: only the bounds are set.)
 void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int k, const float *Q,
                   int item_budget, const SearchScratch &S, hipStream_t s);

@@ -540,12 +540,96 @@ __device__ inline void wg_scan3(uint32_t &a, uint32_t &b, unsigned long long &c,
   __syncthreads();
 }
 
+// The pairs of the request grouped by list: `grouped` holds, list after list in list order, the
+// (query, probe) pairs that probe the list, each at the rank the plan gave it.  One workgroup, beside
+// the one that cuts the work items (both derive the same pair starts from the same counters: a
+// running sum of the pair counts over the lists, 1024 consecutive lists at a time, 16 rows in flight).
+__device__ void scatter_pairs(const Dev &D, int nq, int nprobe, int max_nprobe, const SearchScratch &S) {
+  constexpr int kWavesG = kGroupThreads / kWave;
+  __shared__ uint32_t s_tot[kListChunk * kWavesG + 1];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const uint32_t *__restrict__ list_cnt = S.list_cnt;
+  uint32_t *__restrict__ pair_start = S.pair_start;
+  uint32_t before = 0;  // pairs of the lists in front of the current rows
+  for (int lb = 0; lb < D.nlist; lb += kListChunk * kGroupThreads) {  // uniform over the workgroup
+    const int rows = min(kListChunk, (D.nlist - lb + kGroupThreads - 1) / kGroupThreads);
+    uint32_t c[kListChunk], incl[kListChunk];
+#pragma unroll
+    for (int t = 0; t < kListChunk; ++t) {
+      const int l = lb + t * kGroupThreads + tid;
+      c[t] = t < rows && l < D.nlist ? list_cnt[l] : 0u;
+    }
+#pragma unroll
+    for (int t = 0; t < kListChunk; ++t) {
+      incl[t] = c[t];
+      if (t < rows) {  // uniform
+        for (int o = 1; o < kWave; o <<= 1) {
+          const uint32_t x = __shfl_up(incl[t], o);
+          if (lane >= o) incl[t] += x;
+        }
+        if (lane == kWave - 1) s_tot[t * kWavesG + wave] = incl[t];
+      }
+    }
+    __syncthreads();
+    if (wave == 0) {  // running sum over the (row, wavefront) totals, in list order
+      uint32_t carry = 0;
+      const int counts = rows * kWavesG;
+      for (int i0 = 0; i0 < counts; i0 += kWave) {
+        const uint32_t v = i0 + lane < counts ? s_tot[i0 + lane] : 0u;
+        uint32_t in2 = v;
+        for (int o = 1; o < kWave; o <<= 1) {
+          const uint32_t x = __shfl_up(in2, o);
+          if (lane >= o) in2 += x;
+        }
+        if (i0 + lane < counts) s_tot[i0 + lane] = carry + in2 - v;
+        carry += __shfl(in2, kWave - 1);
+      }
+      if (lane == 0) s_tot[kListChunk * kWavesG] = carry;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < kListChunk; ++t)
+      if (c[t]) pair_start[lb + t * kGroupThreads + tid] = before + s_tot[t * kWavesG + wave] + incl[t] - c[t];
+    before += s_tot[kListChunk * kWavesG];
+    __syncthreads();  // the totals are reused by the next rows; the starts are read below by other threads
+  }
+  // eight independent chains of loads per thread
+  const int npairs = nq * nprobe;
+  for (int base = tid; base < npairs; base += 8 * kGroupThreads) {
+    int l[8];
+    uint32_t slot[8], pk[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int idx = base + u * kGroupThreads;
+      if (idx < npairs) {
+        const int q = idx / nprobe, p = idx - q * nprobe;
+        const size_t o = (size_t)q * max_nprobe + p;
+        l[u] = S.probe_list[o];
+        slot[u] = S.pair_slot[o];
+        pk[u] = ((uint32_t)q << 10) | (uint32_t)p;
+      } else {
+        l[u] = -1;
+      }
+    }
+    uint32_t start[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) start[u] = l[u] >= 0 ? pair_start[l[u]] : 0u;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (l[u] >= 0) S.grouped[start[u] + slot[u]] = pk[u];
+  }
+}
+
 __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int nprobe, int max_nprobe, int k,
                                                          const float *__restrict__ Q,
                                                          uint32_t item_budget, uint32_t max_per_xcd,
                                                          SearchScratch S) {
-  if (blockIdx.x > 0) {  // uniform over the workgroup: this one sets the bound of query blockIdx.x - 1
-    sample_bound<false>(D, (int)blockIdx.x - 1, nprobe, max_nprobe, k, Q, S);
+  if (blockIdx.x == 1) {  // uniform over the workgroup: this one groups the pairs by list
+    scatter_pairs(D, nq, nprobe, max_nprobe, S);
+    return;
+  }
+  if (blockIdx.x > 1) {  // this one sets the bound of query blockIdx.x - 2
+    sample_bound<false>(D, (int)blockIdx.x - 2, nprobe, max_nprobe, k, Q, S);
     return;
   }
   __shared__ uint32_t s_a[kGroupThreads];
@@ -560,8 +644,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
   __shared__ uint32_t s_rows[kListChunk * (kGroupThreads / kWave) + 1];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   if (tid == 0) s_nhuge = 0;
-  uint32_t *__restrict__ list_cnt = S.list_cnt;
-  uint32_t *grouped = S.grouped;
+  const uint32_t *__restrict__ list_cnt = S.list_cnt;
   uint4 *__restrict__ tile_desc = S.tile_desc;
   uint4 *__restrict__ plist = S.plist;
   uint32_t *__restrict__ pistart = S.pistart;
@@ -749,7 +832,6 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
           const uint32_t groups = (pl[t].w + kWave - 1) / kWave;
           plist[eb + t] = make_uint4(pl[t].x, ps, c, pl[t].w);
           pistart[eb + t] = is;
-          list_cnt[pl[t].x] = ps;  // from here on: where the list's pairs start
           ps += c;
           is += (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
         }
@@ -831,32 +913,6 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
       }
     }
     break;
-  }
-  __syncthreads();  // the pair starts written above are read below by other threads
-  // scatter of the pairs into their list's group, eight independent chains of loads per thread
-  const int npairs = nq * nprobe;
-  for (int base = tid; base < npairs; base += 8 * kGroupThreads) {
-    int l[8];
-    uint32_t slot[8], pk[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int idx = base + u * kGroupThreads;
-      if (idx < npairs) {
-        const int q = idx / nprobe, p = idx - q * nprobe;
-        const size_t o = (size_t)q * max_nprobe + p;
-        l[u] = S.probe_list[o];
-        slot[u] = S.pair_slot[o];
-        pk[u] = ((uint32_t)q << 10) | (uint32_t)p;
-      } else {
-        l[u] = -1;
-      }
-    }
-    uint32_t start[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) start[u] = l[u] >= 0 ? list_cnt[l[u]] : 0u;
-#pragma unroll
-    for (int u = 0; u < 8; ++u)
-      if (l[u] >= 0) grouped[start[u] + slot[u]] = pk[u];
   }
 }
 
@@ -1560,8 +1616,8 @@ void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int k, c
     hipLaunchKernelGGL(k_pq_bound, dim3((unsigned)nq), dim3(kGroupThreads), 0, s, D, nprobe, max_nprobe, k, S);
     return;
   }
-  // workgroup 0 groups the pairs, workgroup 1 + q sets the bound of query q
-  hipLaunchKernelGGL(k_group, dim3(1 + (unsigned)nq), dim3(kGroupThreads), 0, s, D, (int)nq, nprobe,
+  // workgroup 0 cuts the work items, workgroup 1 groups the pairs, workgroup 2 + q sets the bound of query q
+  hipLaunchKernelGGL(k_group, dim3(2 + (unsigned)nq), dim3(kGroupThreads), 0, s, D, (int)nq, nprobe,
                      max_nprobe, k, Q, (uint32_t)item_budget,
                      (uint32_t)(scan_grid(D, item_budget) / (int)kXcds * scan_waves(D)), S);
 }
