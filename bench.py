@@ -5,11 +5,15 @@ A step is one pass of the whole path over one batch of synthetic input: one
 insertion batch on the data stream (assignment, slot reservation, block
 opening, fill, publication) and, concurrently, one search batch on a pooled
 search stream (coarse scores, probe selection, list scan, top-k).  The
-workload is configuration 2 of the benchmark spec (byte-valued L2, d=128, 1M base
+workload is the SIFT-shaped configuration (byte-valued L2, d=128, 1M base
 vectors, nlist=1024, nprobe=32, k=100, block of 128 vectors, inserts in batches
 of 64), with every input resident in HBM before the timed region starts.
 
-Prints ONE JSON line; see the design doc for the meaning of each field.
+Prints ONE JSON line.  `value` is queries per second over the timed steps;
+`roofline` is for the list scan (bytes of the union of the probed lists per
+launch over the launch's mean duration, measured with HIP events on the
+caller's stream, against 8 TB/s; `alu_issue` is the arithmetic side of the
+same launches); `cpu_baseline` is the CPU oracle on the host cores.
 """
 from __future__ import annotations
 
@@ -54,7 +58,7 @@ def main() -> int:
                     help="run one of the side studies instead of the benchmark (one JSON line each)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU only: this build has no multi-GPU path (see DESIGN.md, sharding)",
+        print("bench.py measures one GPU only: this build has no multi-GPU path (lists would be sharded by owner GPU)",
               file=sys.stderr)
         return 2
 
