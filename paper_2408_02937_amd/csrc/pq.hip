@@ -3,8 +3,8 @@
 // IVF-Flat as a kind of list its memory blocks hold and leaves the quantiser to
 // the textbook: Jegou et al., product quantization for nearest neighbour
 // search.)  This file holds what differs on the insertion side and the
-// per-request table of sub-scores; the scan over codes lives with the other
-// scan in search.hip.
+// export; the per-request table of sub-scores and the scan over codes live with
+// the other scan in search.hip.
 //
 // Layout: groups of 64 vectors as for floats; the chunk is one 32-bit word of 4
 // codes, so a wavefront reading word c of a group loads 256 consecutive bytes,
@@ -91,23 +91,6 @@ __global__ __launch_bounds__(256) void k_pq_fill(Dev D, int64_t n, const float *
   if (m == 0) block_ids(D, b)[moff] = ids ? ids[i] : id_base + i;
 }
 
-// ---- table of sub-scores of a request: lut[q][m][c] = squared distance (L2) or inner product
-// (IP) between sub-vector m of query q and entry c of codebook m, fp32, one FMA chain in the
-// order of the dimensions.  One workgroup per (query, sub-space), thread = entry.
-__global__ __launch_bounds__(256) void k_pq_lut(Dev D, const float *__restrict__ Q, float *__restrict__ lut) {
-  const int M = D.pq_m, ds = D.d / M;
-  const int q = blockIdx.x, m = blockIdx.y, c = threadIdx.x;
-  const float *y = Q + (size_t)q * D.d + (size_t)m * ds;
-  const float *e = D.codebooks + ((size_t)m * 256 + c) * ds;
-  float acc = 0.f;
-  if (D.metric == 0) {
-    for (int j = 0; j < ds; ++j) { const float u = e[j] - y[j]; acc = fmaf(u, u, acc); }
-  } else {
-    for (int j = 0; j < ds; ++j) acc = fmaf(e[j], y[j], acc);
-  }
-  lut[((size_t)q * M + m) * 256 + c] = acc;
-}
-
 // ---- export: thread (position, word): un-interleaves 4 codes of one vector
 __global__ __launch_bounds__(256) void k_pq_export(Dev D, int list, int64_t n, int64_t *__restrict__ ids,
                                                    uint8_t *__restrict__ codes) {
@@ -128,11 +111,6 @@ void launch_pq_fill(const Dev &D, int64_t n, const float *Y, const int64_t *ids,
   const int64_t waves = (n + kFillVecs - 1) / kFillVecs * D.pq_m;
   hipLaunchKernelGGL(k_pq_fill, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, D, n, Y, ids, id_base,
                      S.assign, S.did);
-}
-
-void launch_pq_lut(const Dev &D, int64_t nq, const float *Q, float *lut, hipStream_t s) {
-  if (nq <= 0) return;
-  hipLaunchKernelGGL(k_pq_lut, dim3((unsigned)nq, (unsigned)D.pq_m), dim3(256), 0, s, D, Q, lut);
 }
 
 void launch_pq_export(const Dev &D, int list, int64_t n, int64_t *ids, uint8_t *codes, hipStream_t s) {

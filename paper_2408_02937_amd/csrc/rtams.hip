@@ -573,7 +573,6 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   // a rearrangement is switching block tables: start behind its last switch
   if (ix->fence_cur) (void)hipStreamWaitEvent(s, ix->fence_cur, 0);
   coarse_and_plan(ix, nq, d_queries, nprobe, S, nullptr, s);
-  if (D.pq_m > 0) launch_pq_lut(D, nq, d_queries, S.lut, s);
   // The grouped scan is cut into work items of bounded size, one wavefront each;
   // the budget of items grows with the request so that a small batch still
   // spreads over the chip and a large one is not drowned in per-item overhead.

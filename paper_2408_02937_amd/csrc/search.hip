@@ -1326,9 +1326,60 @@ __global__ __launch_bounds__(kPqScanThreads) void k_pq_scan(Dev D, int nprobe, i
 
 // The bound of every query of a request over quantised lists (the grouping by list that the scan
 // of flat lists needs is not made).
+// The workgroup of a query first writes the query's table of sub-scores: lut[q][m][c] = squared
+// distance (L2) or inner product (IP) between sub-vector m of the query and entry c of codebook m,
+// fp32, one FMA chain in the order of the dimensions; its sample and the scan read it from there.
 __global__ __launch_bounds__(kGroupThreads) void k_pq_bound(Dev D, int nprobe, int max_nprobe, int k,
-                                                            SearchScratch S) {
-  sample_bound<true>(D, (int)blockIdx.x, nprobe, max_nprobe, k, nullptr, S);
+                                                            const float *__restrict__ Q, SearchScratch S) {
+  const int q = blockIdx.x;
+  {
+    const int M = D.pq_m, ds = D.d / M;
+    const float *__restrict__ yq = Q + (size_t)q * D.d;
+    float *__restrict__ lut = S.lut + (size_t)q * M * 256;
+    // M * 256 entries, 1024 threads: M / 4 rounds, four of them side by side (their loads overlap);
+    // 16-byte loads where the sub-space allows
+    for (int i0 = threadIdx.x; i0 < M * 256; i0 += 4 * kGroupThreads) {
+      float acc[4] = {0.f, 0.f, 0.f, 0.f};
+      if (ds % 4 == 0) {  // uniform
+        for (int j4 = 0; j4 < ds / 4; ++j4) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int i = i0 + r * kGroupThreads;
+            if (i < M * 256) {
+              const float4 ev = reinterpret_cast<const float4 *>(D.codebooks + (size_t)i * ds)[j4];
+              const float4 yv = reinterpret_cast<const float4 *>(yq + (size_t)(i >> 8) * ds)[j4];
+              if (D.metric == 0) {
+                const float u0 = ev.x - yv.x, u1 = ev.y - yv.y, u2 = ev.z - yv.z, u3 = ev.w - yv.w;
+                acc[r] = fmaf(u0, u0, acc[r]); acc[r] = fmaf(u1, u1, acc[r]);
+                acc[r] = fmaf(u2, u2, acc[r]); acc[r] = fmaf(u3, u3, acc[r]);
+              } else {
+                acc[r] = fmaf(ev.x, yv.x, acc[r]); acc[r] = fmaf(ev.y, yv.y, acc[r]);
+                acc[r] = fmaf(ev.z, yv.z, acc[r]); acc[r] = fmaf(ev.w, yv.w, acc[r]);
+              }
+            }
+          }
+        }
+      } else {
+        for (int j = 0; j < ds; ++j) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int i = i0 + r * kGroupThreads;
+            if (i < M * 256) {
+              const float ev = D.codebooks[(size_t)i * ds + j], yv = yq[(size_t)(i >> 8) * ds + j];
+              if (D.metric == 0) { const float u = ev - yv; acc[r] = fmaf(u, u, acc[r]); }
+              else acc[r] = fmaf(ev, yv, acc[r]);
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (i0 + r * kGroupThreads < M * 256) lut[i0 + r * kGroupThreads] = acc[r];
+    }
+  }
+  __threadfence_block();
+  __syncthreads();  // the sample below reads the table
+  sample_bound<true>(D, q, nprobe, max_nprobe, k, nullptr, S);
 }
 
 // ------------------------------------------------------------ top-k selection
@@ -1613,7 +1664,7 @@ void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int k, c
                   int item_budget, const SearchScratch &S, hipStream_t s) {
   if (nq <= 0) return;
   if (D.pq_m > 0) {
-    hipLaunchKernelGGL(k_pq_bound, dim3((unsigned)nq), dim3(kGroupThreads), 0, s, D, nprobe, max_nprobe, k, S);
+    hipLaunchKernelGGL(k_pq_bound, dim3((unsigned)nq), dim3(kGroupThreads), 0, s, D, nprobe, max_nprobe, k, Q, S);
     return;
   }
   // workgroup 0 cuts the work items, workgroup 1 groups the pairs, workgroup 2 + q sets the bound of query q
