@@ -46,7 +46,7 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=256, help="queries per search batch")
     ap.add_argument("--scale", type=float, default=1.0, help="shrinks base/query/insert counts")
     ap.add_argument("--search-streams", type=int, default=4)
-    ap.add_argument("--latency-iters", type=int, default=300)
+    ap.add_argument("--latency-iters", type=int, default=2000)
     ap.add_argument("--cpu-queries", type=int, default=1024, help="queries of the oracle sample; 0 skips it")
     ap.add_argument("--no-extras", action="store_true", help="only the timed steps (for profiler runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
