@@ -305,6 +305,40 @@ def extras(args, g, w, torch, rtams, q_batches, queries, ins_batches, data_strea
         }
     out["latency_by_query_batch"] = per_batch
 
+    # the configuration's own mix: closed-loop searches of the benchmark's batch on all search streams while
+    # the insertion thread keeps its 10,000 vectors/s (the timed steps insert 64 vectors per search batch,
+    # about 40 times that rate)
+    B = args.batch
+    nb = len(queries) // B
+    outs = [(torch.empty((B, k), dtype=torch.float32, device=dev), torch.empty((B, k), dtype=torch.int64, device=dev))
+            for _ in search_streams]
+    stop.clear()
+    sent[0] = 0
+    th = threading.Thread(target=inserter)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    th.start()
+    n_req = 4000
+    for i in range(n_req):
+        si = i % len(search_streams)
+        while True:
+            try:
+                g.search(queries[(i % nb) * B:(i % nb + 1) * B], k, nprobe, outs[si][0], outs[si][1],
+                         stream=search_streams[si])
+                break
+            except rtams.RtamsError as e:
+                if e.code != rtams.EBUSY:
+                    raise
+                search_streams[(si + 1) % len(search_streams)].synchronize()
+    for st_ in search_streams:
+        st_.synchronize()
+    dt = time.perf_counter() - t0
+    stop.set()
+    th.join()
+    data_stream.synchronize()
+    out["at_configured_insert_rate"] = {"qps": n_req * B / dt, "query_batch": B, "search_streams": len(search_streams),
+                                        "inserts_per_s": sent[0] / dt}
+
     # practical ceiling of a streaming read on this chip: the library's plain read kernel over 1 GiB
     src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).zero_()
     sink = torch.zeros(1, dtype=torch.float32, device=dev)
