@@ -17,6 +17,10 @@
   counts, block sizes and batch sizes) at a fraction of their base sets: load
   rate, latency per request at the configuration's batch, scan time and bytes.
 
+* `mixed_load_study`: configuration 4's protocol: an open-loop stream of
+  operations (70 % queries, 30 % inserted vectors) offered at fixed rates, 7
+  search streams and the data stream; latency from arrival to completion.
+
 The first three use configuration 2's synthetic data (byte-valued, d = 128, 1 M vectors,
 1024 lists) and go through the same C ABI as everything else.
 """
@@ -335,3 +339,111 @@ def shape_study(scale: float = 1.0, iters: int = 100, which=(3, 4, 5)) -> dict:
         del base, cents, queries, inserts, w
         torch.cuda.empty_cache()
     return {"study": "shapes", "rows": rows}
+
+
+def mixed_load_study(scale: float = 1.0, rates=(1_000, 5_000, 20_000, 50_000, 200_000), seconds: float = 2.0,
+                     iters: int = 0) -> dict:
+    """Open loop: operations arrive as a Poisson process at the offered rate whatever the index does; an
+    operation is one query (70 %) or one inserted vector (30 %).  Queries are sent in batches whose size is
+    drawn from {1, 2, 4, ..., 64} (a batch leaves when that many have arrived), inserted vectors in batches
+    of 64.  Latency of an operation = completion of its batch minus its own arrival (it includes the wait
+    for the batch to fill, which dominates at low rates); service time = completion minus submission of the
+    batch.  `iters` is unused."""
+    dev = torch.device("cuda:0")
+    w = synth.config(4, scale=0.2 * scale)
+    rng = np.random.Generator(np.random.PCG64([w.seed, 99]))
+    base, cents, queries, inserts = (_to_dev(a, dev) for a in (w.base, w.centroids, w.queries, w.inserts))
+    n_all = len(w.base) + 4 * len(w.inserts) + 200_000
+    g = rtams.Index(w.d, w.nlist, w.metric, w.block_vecs, pool_blocks=n_all // w.block_vecs + 2 * w.nlist + 64,
+                    n_resources=16, max_batch=64, max_k=16, max_nprobe=w.nprobe, max_add_batch=65536,
+                    candidates_per_query=65536)
+    data = torch.cuda.Stream(dev)
+    sstreams = [torch.cuda.Stream(dev) for _ in range(7)]
+    g.set_centroids(cents, stream=data)
+    g.add(base, stream=data)
+    data.synchronize()
+    od = [torch.empty((64, w.k), dtype=torch.float32, device=dev) for _ in range(64)]
+    oi = [torch.empty((64, w.k), dtype=torch.int64, device=dev) for _ in range(64)]
+    for s_ in sstreams:  # warm up every stream
+        g.search(queries[:64], w.k, w.nprobe, od[0], oi[0], stream=s_)
+        s_.synchronize()
+    rows = []
+    nq, ni = len(queries), len(inserts)
+    for rate in rates:
+        n_ops = int(rate * seconds)
+        gaps = rng.exponential(1.0 / rate, size=n_ops)
+        arrivals = np.cumsum(gaps)
+        is_query = rng.random(n_ops) < 0.7
+        pend_q, pend_i = [], []          # arrival times of operations waiting for their batch
+        want = int(2 ** rng.integers(0, 7))
+        in_flight = []                   # (event, arrival times, kind)
+        q_lat, i_lat, q_svc, i_svc = [], [], [], []
+        busy = 0
+        qpos = ipos = slot = 0
+        free_events = [torch.cuda.Event() for _ in range(256)]
+
+        def reap(block=False):
+            keep = []
+            for ev, arr, kind, t_sub in in_flight:
+                if block:
+                    ev.synchronize()
+                if block or ev.query():
+                    t = time.perf_counter() - t_start
+                    (q_lat if kind == "q" else i_lat).extend((t - a) * 1e3 for a in arr)
+                    (q_svc if kind == "q" else i_svc).append((t - t_sub) * 1e3)
+                    free_events.append(ev)
+                else:
+                    keep.append((ev, arr, kind, t_sub))
+            in_flight[:] = keep
+
+        t_start = time.perf_counter()
+        for op in range(n_ops):
+            while time.perf_counter() - t_start < arrivals[op]:
+                reap()
+            if is_query[op]:
+                pend_q.append(arrivals[op])
+                if len(pend_q) >= want:
+                    bs = len(pend_q)
+                    st = sstreams[slot % len(sstreams)]
+                    t_sub = time.perf_counter() - t_start
+                    while True:
+                        try:
+                            g.search(queries[qpos:qpos + bs], w.k, w.nprobe, od[slot % 64][:bs], oi[slot % 64][:bs], stream=st)
+                            break
+                        except rtams.RtamsError as e:
+                            if e.code != rtams.EBUSY:
+                                raise
+                            busy += 1
+                            reap()
+                    ev = free_events.pop() if free_events else torch.cuda.Event()
+                    ev.record(st)
+                    in_flight.append((ev, pend_q, "q", t_sub))
+                    pend_q = []
+                    qpos = (qpos + bs) % (nq - 64)
+                    slot += 1
+                    want = int(2 ** rng.integers(0, 7))
+            else:
+                pend_i.append(arrivals[op])
+                if len(pend_i) >= 64:
+                    t_sub = time.perf_counter() - t_start
+                    g.add(inserts[ipos:ipos + 64], stream=data)
+                    ev = free_events.pop() if free_events else torch.cuda.Event()
+                    ev.record(data)
+                    in_flight.append((ev, pend_i, "i", t_sub))
+                    pend_i = []
+                    ipos = (ipos + 64) % (ni - 64)
+        t_sent = time.perf_counter() - t_start
+        reap(block=True)
+        t_done = time.perf_counter() - t_start
+        assert g.poll_error() == 0
+        rows.append({"offered_ops_per_s": rate, "operations": n_ops, "achieved_ops_per_s": (len(q_lat) + len(i_lat)) / t_done,
+                     "generator_lag_ms": (t_sent - float(arrivals[-1])) * 1e3,
+                     "query_latency_ms": {"p50": _p(q_lat, 50), "p99": _p(q_lat, 99), "n": len(q_lat)},
+                     "insert_latency_ms": {"p50": _p(i_lat, 50), "p99": _p(i_lat, 99), "n": len(i_lat)},
+                     "search_service_ms": {"p50": _p(q_svc, 50), "p99": _p(q_svc, 99), "requests": len(q_svc)},
+                     "insert_service_ms": {"p50": _p(i_svc, 50), "p99": _p(i_svc, 99), "requests": len(i_svc)},
+                     "requests_refused_busy": busy})
+    g.validate()
+    g.close()
+    return {"study": "mixed_load", "workload": w.name, "n_base": len(w.base), "nprobe": w.nprobe, "k": w.k,
+            "search_streams": len(sstreams), "seconds_per_rate": seconds, "rows": rows}

@@ -44,3 +44,12 @@ def test_shape_study_small():
     for r in out["rows"]:
         for v in r["search"].values():
             assert v["scan_ms"] > 0 and v["p50_ms"] > 0
+
+
+def test_mixed_load_study_small():
+    from paper_2408_02937_amd import studies
+    print("[case] mixed load study, scale 0.02, 2000 operations/s for 0.5 s", flush=True)
+    out = studies.mixed_load_study(scale=0.02, rates=(2_000,), seconds=0.5)
+    r = out["rows"][0]
+    assert r["query_latency_ms"]["n"] + r["insert_latency_ms"]["n"] > 0
+    assert r["query_latency_ms"]["p50"] > 0
