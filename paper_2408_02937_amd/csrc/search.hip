@@ -453,9 +453,13 @@ __device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, in
   __shared__ __attribute__((aligned(8))) uint32_t hist[256];
   __shared__ uint32_t bc[4];
   const int tid = threadIdx.x;
-  // A query with no more candidates than the selection holds in LDS at once needs no bound: its
-  // records cost less than a sample would (short lists, wide vectors).
-  if (S.qtotal[q] <= (uint32_t)kNoBoundBelow) {  // uniform over the workgroup
+  // A query with no more candidates than the selection holds in LDS at once needs no bound.  For
+  // inner products neither does one whose records cost less than a sample would: the sample is 512
+  // vectors or more read by one workgroup (80 us at d = 768), a record is 8 bytes (short lists, wide
+  // vectors).  (For L2 the bound also lets the scan stop early, which is worth the sample.)
+  const uint32_t no_bound_below =
+      D.metric == 0 ? (uint32_t)kNoBoundBelow : max((uint32_t)kNoBoundBelow, 32u * (uint32_t)D.d);
+  if (S.qtotal[q] <= no_bound_below) {  // uniform over the workgroup
     if (tid == 0) {
       S.bound[q] = 0xFFFFFFFFu;
       S.rec_cnt[q] = 0u;
