@@ -147,7 +147,11 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
 
 /* Rearrangement algorithm of the paper: makes the blocks of `list` physically
  * contiguous behind its first block by exchanging blocks with their physical
- * neighbours; list == -1 handles every list for which Exceed() holds.
+ * neighbours.  list == -1 handles every list for which Exceed() holds: one
+ * round after another (a round moves one list, a long chain takes several),
+ * and this form WAITS for each round on the stream, because only the device
+ * knows whether another is owed; with a list given the call only enqueues.
+ * (rtams_add enqueues one such round by itself whenever a list exceeds.)
  * Ordered with add on the data stream; searches keep running and see either
  * placement, never a mixture. */
 int rtams_rearrange(rtams_index *ix, int32_t list, void *hip_stream);

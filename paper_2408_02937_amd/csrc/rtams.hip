@@ -627,7 +627,17 @@ int rtams_rearrange(rtams_index *ix, int32_t list, void *hip_stream) {
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   int rc = enter_data_stream(ix, s);
   if (rc) return rc;
-  if ((rc = rearrange_round(ix, list, s))) return rc;  // blocks in use are the same before and after
+  if (list >= 0) {
+    if ((rc = rearrange_round(ix, list, s))) return rc;  // blocks in use are the same before and after
+    return leave_data_stream(ix, s);
+  }
+  // Every list for which Exceed() holds: one round handles one list (a long chain takes several),
+  // and only the device knows whether another is owed, so this form waits for each round.
+  for (int64_t it = 0; it < 8 * (int64_t)ix->cfg.nlist + 64; ++it) {
+    if ((rc = rearrange_round(ix, -1, s))) return rc;
+    HIP_TRY(hipStreamSynchronize(s));
+    if (ix->mirror->exceed_lists == 0) break;
+  }
   return leave_data_stream(ix, s);
 }
 

@@ -21,6 +21,10 @@
   operations (70 % queries, 30 % inserted vectors) offered at fixed rates, 7
   search streams and the data stream; latency from arrival to completion.
 
+* `growth_study`: configuration 5's protocol: Zipf-distributed inserts at a
+  fixed rate with Exceed() armed, so rearrangement rounds run between the
+  insertion batches while searches run beside them; latency second by second.
+
 The first three use configuration 2's synthetic data (byte-valued, d = 128, 1 M vectors,
 1024 lists) and go through the same C ABI as everything else.
 """
@@ -447,3 +451,98 @@ def mixed_load_study(scale: float = 1.0, rates=(1_000, 5_000, 20_000, 50_000, 20
     g.close()
     return {"study": "mixed_load", "workload": w.name, "n_base": len(w.base), "nprobe": w.nprobe, "k": w.k,
             "search_streams": len(sstreams), "seconds_per_rate": seconds, "rows": rows}
+
+
+def growth_study(scale: float = 1.0, seconds: float = 6.0, rate: float = 100_000.0, threshold: int = 10_000,
+                 iters: int = 0) -> dict:
+    """Skewed growth under load: a tenth of configuration 5's base set, then `seconds` of inserts at `rate`
+    vectors/s (batches of 1024, list popularity Zipf(1.1)) on the data stream with the rearrangement
+    threshold armed, and closed-loop searches (batch 256, nprobe 64, k 50) on a search stream.  Reports the
+    search latency per second of the run and the state of the hottest lists.  `iters` is unused."""
+    dev = torch.device("cuda:0")
+    w = synth.config(5, scale=0.1 * scale)
+    base, cents, queries, inserts = (_to_dev(a, dev) for a in (w.base, w.centroids, w.queries, w.inserts))
+    ib = w.insert_batch
+    n_new = int(rate * seconds) + 4 * ib
+    n_all = len(w.base) + n_new
+    g = rtams.Index(w.d, w.nlist, w.metric, w.block_vecs, pool_blocks=n_all // w.block_vecs + 3 * w.nlist + 4096,
+                    rearrange_threshold=threshold, n_resources=8, max_batch=256, max_k=64, max_nprobe=64,
+                    max_add_batch=65536,
+                    candidates_per_query=max(65536, 4 * w.nprobe * (n_all // w.nlist + w.block_vecs)))
+    data, ss = torch.cuda.Stream(dev), torch.cuda.Stream(dev)
+    g.set_centroids(cents, stream=data)
+    g.add(base, stream=data)
+    data.synchronize()
+    sizes0 = g.list_sizes()
+    hot = [int(i) for i in np.argsort(-sizes0)[:4]]
+    runs0 = {h: g.list_info(h)[1] for h in hot}
+    st0 = g.pool_stats()
+    bs = 256
+    od = torch.empty((bs, w.k), dtype=torch.float32, device=dev)
+    oi = torch.empty((bs, w.k), dtype=torch.int64, device=dev)
+    nb = max(len(queries) // bs, 1)
+
+    def search_for(duration, sink):
+        i = 0
+        t_end = time.perf_counter() + duration
+        while time.perf_counter() < t_end:
+            t = time.perf_counter()
+            g.search(queries[(i % nb) * bs:(i % nb) * bs + bs], w.k, w.nprobe, od, oi, stream=ss)
+            ss.synchronize()
+            sink.append((t, (time.perf_counter() - t) * 1e3))
+            i += 1
+
+    quiet = []
+    search_for(0.5, quiet)
+    stop = threading.Event()
+    sent = [0]
+    n_ib = len(inserts) // ib
+
+    def inserter():
+        period = ib / rate
+        nxt = time.perf_counter()
+        i = 0
+        while not stop.is_set():
+            g.add(inserts[(i % n_ib) * ib:(i % n_ib) * ib + ib], stream=data)
+            sent[0] += ib
+            i += 1
+            nxt += period
+            dt = nxt - time.perf_counter()
+            if dt > 0:
+                time.sleep(dt)
+
+    lat = []
+    th = threading.Thread(target=inserter)
+    t0 = time.perf_counter()
+    th.start()
+    search_for(seconds, lat)
+    stop.set()
+    th.join()
+    data.synchronize()
+    t_run = time.perf_counter() - t0
+    g.rearrange(-1, stream=data)  # the rounds the last batches asked for
+    data.synchronize()
+    after = []
+    search_for(0.5, after)
+    assert g.poll_error() == 0
+    g.validate()
+    sizes1 = g.list_sizes()
+    st1 = g.pool_stats()
+    per_second = []
+    for sec in range(int(seconds)):
+        xs = [l for (t, l) in lat if sec <= t - t0 < sec + 1]
+        per_second.append({"second": sec, "requests": len(xs), "p50_ms": _p(xs, 50), "p99_ms": _p(xs, 99)})
+    out = {"study": "skewed_growth", "workload": w.name, "n_base": len(w.base), "rearrange_threshold": threshold,
+           "insert_rate_offered": rate, "insert_rate_achieved": sent[0] / t_run, "vectors_inserted": sent[0],
+           "search": {"before": {"p50_ms": _p([l for _, l in quiet], 50), "p99_ms": _p([l for _, l in quiet], 99)},
+                      "during": {"p50_ms": _p([l for _, l in lat], 50), "p99_ms": _p([l for _, l in lat], 99),
+                                 "requests": len(lat), "per_second": per_second},
+                      "after": {"p50_ms": _p([l for _, l in after], 50), "p99_ms": _p([l for _, l in after], 99)}},
+           "hot_lists": [{"list": h, "vectors_before": int(sizes0[h]), "vectors_after": int(sizes1[h]),
+                          "blocks_after": int(g.list_info(h)[0]), "runs_before": int(runs0[h]),
+                          "runs_after": int(g.list_info(h)[1])} for h in hot],
+           "pool": {"blocks_in_use_before": st0.blocks_in_use, "blocks_in_use_after": st1.blocks_in_use,
+                    "blocks_free_after": st1.blocks_free, "lists_exceeding_after": st1.lists_exceeding,
+                    "utilisation_after": st1.utilisation}}
+    g.close()
+    return out

@@ -53,3 +53,14 @@ def test_mixed_load_study_small():
     r = out["rows"][0]
     assert r["query_latency_ms"]["n"] + r["insert_latency_ms"]["n"] > 0
     assert r["query_latency_ms"]["p50"] > 0
+
+
+def test_growth_study_small():
+    from paper_2408_02937_amd import studies
+    print("[case] growth study, scale 0.05, 1 s at 50,000 vectors/s, threshold 500", flush=True)
+    out = studies.growth_study(scale=0.05, seconds=1.0, rate=50_000.0, threshold=500)
+    assert out["vectors_inserted"] > 0 and out["search"]["during"]["requests"] > 0
+    h = out["hot_lists"][0]
+    assert h["vectors_after"] > h["vectors_before"]
+    assert h["runs_after"] <= 3          # the hot list was compacted on the way
+    assert out["pool"]["lists_exceeding_after"] == 0
