@@ -211,8 +211,8 @@ int rtams_copy_plain(void *d_dst, const void *d_src, size_t bytes, void *hip_str
 int rtams_read_plain(const void *d_src, size_t bytes, float *d_sink, void *hip_stream);
 /* Launch-shape knobs ("restrict the number of blocks and threads per kernel",
  * Stream-Cached Multi-Stream Execution, consideration 2).  key: "scan_max_items"
- * (most work items, one workgroup each, one list-scan launch is cut
- * into; default 32768), "scan_items_per_pair" (items per (query, list) pair a small
+ * (most work items, one wavefront each, one list-scan launch is cut
+ * into; a (query, list) pair is always at least one; default 32768), "scan_items_per_pair" (items per (query, list) pair a small
  * request may be cut into; default 8), "profile_scan" (see rtams_scan_time), and
  * "use_mfma": whether approximate coarse scores from the matrix cores filter the
  * centroids before the exact arithmetic decides (0 never, 1 for batches large
