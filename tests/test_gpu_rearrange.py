@@ -148,3 +148,23 @@ def test_searches_stay_correct_while_blocks_move():
     g.validate()
     assert_lists_equal(g, o)
     g.close()
+
+
+def test_rearrange_all_handles_every_exceeding_list():
+    """Several lists pass T_m' in ONE batch; rearrange(-1) must bring all of them in order (one round
+    handles one list), not just the first."""
+    w, g, o, rng = interleaved(nlist=4, rounds=3, threshold=250)     # 192 per list, scattered: nobody exceeds
+    assert g.pool_stats().lists_exceeding == 0
+    y = np.concatenate([(w.centroids[k] + 0.5 * rng.standard_normal((70, w.d))).astype(np.float32)
+                        for k in (0, 2, 3)])                         # 262 > 250 for three lists at once
+    perm = rng.permutation(len(y))
+    g.add(dev(y[perm])); o.add(y[perm])
+    assert g.pool_stats().lists_exceeding == 3
+    g.rearrange(-1)
+    g.validate()
+    assert g.pool_stats().lists_exceeding == 0
+    for k in (0, 2, 3):
+        assert g.list_info(k)[2] == 0                                # every one of them had its round
+    assert runs_of(g, 3) == 1    # the last one handled is in one run (an earlier one may have given way to a later)
+    assert_lists_equal(g, o)
+    g.close()
