@@ -294,9 +294,14 @@ def shape_study(scale: float = 1.0, iters: int = 100, which=(3, 4, 5)) -> dict:
         t_gen = time.perf_counter() - t0
         base, cents, queries, inserts = (_to_dev(a, dev) for a in (w.base, w.centroids, w.queries, w.inserts))
         n_all = len(w.base) + 2 * len(w.inserts)
+        # room for the candidates: a few times the average, and for the skewed set a quarter of everything
+        # (most queries of a batch may probe the hottest list, which holds a seventh of the vectors)
+        cand = max(65536, 4 * w.nprobe * (len(w.base) // w.nlist + w.block_vecs))
+        if idx == 5:
+            cand = max(cand, len(w.base) // 4)
         g = rtams.Index(w.d, w.nlist, w.metric, w.block_vecs, pool_blocks=n_all // w.block_vecs + 2 * w.nlist + 64,
-                        n_resources=8, max_batch=256, max_k=128, max_nprobe=64, max_add_batch=65536,
-                        candidates_per_query=max(65536, 4 * w.nprobe * (len(w.base) // w.nlist + w.block_vecs)))
+                        n_resources=4, max_batch=256, max_k=128, max_nprobe=64, max_add_batch=65536,
+                        candidates_per_query=cand)
         ds, ss = torch.cuda.Stream(dev), torch.cuda.Stream(dev)
         g.set_centroids(cents, stream=ds)
         t0 = time.perf_counter()
