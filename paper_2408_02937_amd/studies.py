@@ -40,6 +40,7 @@ from . import rtams, synth
 
 
 LDS_LOOKUPS_PEAK_G = 256 * 128 / 4 * 2.4  # 4-byte LDS reads per nanosecond of the whole chip, conflict-free
+VALU_ISSUE_PEAK_T = 256 * 64 * 2.4e9 / 1e12  # unpacked fp32 lane instructions per second, all CUs
 
 
 def _p(xs, q):
@@ -321,15 +322,22 @@ def shape_study(scale: float = 1.0, iters: int = 100, which=(3, 4, 5)) -> dict:
             g.set_param("profile_scan", 0)
             ms, cnt = g.scan_time(reset=True)
             nb = max(len(queries) // bs, 1)
-            ub = []
+            ub, pairs = [], []
             for i in range(min(16, nb)):
                 pl = g.probe(queries[i * bs:(i + 1) * bs], w.nprobe).cpu().numpy()
                 ub.append(int((sizes_now[np.unique(pl)] * w.d * 4).sum()))
+                pairs.append(int(sizes_now[pl].sum()))
             scan_ms = ms / max(cnt, 1)
             gbps = float(np.mean(ub)) / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else None
+            # arithmetic of the same launch: d subtract + d multiply-add lane instructions per (query, candidate)
+            # pair for L2, d multiply-adds for IP, against 256 CUs x 64 lanes x 2.4 GHz unpacked fp32 issue
+            lane_ops = float(np.mean(pairs)) * w.d * (2 if w.metric == "l2" else 1)
+            t_ops = lane_ops / (scan_ms * 1e-3) / 1e12 if scan_ms > 0 else None
             row["search"][str(bs)] = {"p50_ms": _p(lat, 50), "p99_ms": _p(lat, 99), "qps": bs / (np.mean(lat) * 1e-3),
                                       "scan_ms": scan_ms, "scan_bytes": float(np.mean(ub)), "scan_GBps": gbps,
-                                      "frac_of_hbm_peak": gbps / 8000.0 if gbps else None}
+                                      "frac_of_hbm_peak": gbps / 8000.0 if gbps else None,
+                                      "pairs": float(np.mean(pairs)), "alu_T_lane_instructions_per_s": t_ops,
+                                      "frac_of_alu_issue_peak": t_ops / VALU_ISSUE_PEAK_T if t_ops else None}
         ib = w.insert_batch
         n_ib = max(len(inserts) // ib, 1)
         lat = []
