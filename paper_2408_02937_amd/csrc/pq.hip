@@ -19,7 +19,8 @@ namespace rtams {
 // entry.  Lane l holds entries l, l + 64, l + 128, l + 192: it reads each of their coordinates once
 // for the 8 vectors, keeps its best (distance, entry) per vector, and a butterfly over the
 // wavefront leaves the overall best in every lane; lane v then writes the byte of vector v to its
-// place (the wavefront of sub-space 0 also writes the ids).
+// place (the wavefront of sub-space 0 also writes the ids).  The codebooks are read from a copy
+// with the entries innermost, so that the 64 lanes of a load read consecutive floats.
 constexpr int kFillVecs = 8;
 
 __global__ __launch_bounds__(256) void k_pq_fill(Dev D, int64_t n, const float *__restrict__ Y,
@@ -28,13 +29,14 @@ __global__ __launch_bounds__(256) void k_pq_fill(Dev D, int64_t n, const float *
                                                  const uint32_t *__restrict__ did) {
   const int M = D.pq_m, ds = D.d / M;
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t w = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  // the same for every lane: said so, so that the vectors' coordinates below come through the scalar unit
+  const int64_t w = (int64_t)blockIdx.x * (blockDim.x / kWave) + __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
   const int64_t tiles = (n + kFillVecs - 1) / kFillVecs;
   if (w >= tiles * M) return;  // uniform over the wavefront
   const int m = (int)(w % M);
   const int64_t i0 = (w / M) * kFillVecs;
-  const float *cb = D.codebooks + (size_t)m * 256 * ds;
-  const float *yrow[kFillVecs];
+  const float *cbt = D.codebooks_t + (size_t)m * ds * 256;  // [dimension][entry]: a wavefront's loads are consecutive
+  const float *__restrict__ yrow[kFillVecs];
 #pragma unroll
   for (int v = 0; v < kFillVecs; ++v) {
     const int64_t i = i0 + v < n ? i0 + v : n - 1;  // the tail of the last tile repeats the last vector
@@ -48,7 +50,7 @@ __global__ __launch_bounds__(256) void k_pq_fill(Dev D, int64_t n, const float *
   for (int j = 0; j < ds; ++j) {
     double e[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) e[u] = (double)cb[(size_t)(lane + kWave * u) * ds + j];
+    for (int u = 0; u < 4; ++u) e[u] = (double)cbt[(size_t)j * 256 + lane + kWave * u];
 #pragma unroll
     for (int v = 0; v < kFillVecs; ++v) {
       const double y = (double)yrow[v][j];
@@ -103,6 +105,21 @@ __global__ __launch_bounds__(256) void k_pq_export(Dev D, int list, int64_t n, i
   const uint32_t b = (uint32_t)*table_entry(D, list, mid);
   if (codes) reinterpret_cast<uint32_t *>(codes)[pos * words + c] = block_codes(D, b)[code_word_index(D, moff, c)];
   if (ids && c == 0) ids[pos] = block_ids(D, b)[moff];
+}
+
+// entries innermost: codebooks_t[m][j][c] = codebooks[m][c][j]
+__global__ __launch_bounds__(256) void k_pq_transpose(Dev D) {
+  const int ds = D.d / D.pq_m;
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= (int64_t)256 * D.d) return;
+  const int c = (int)(t & 255);
+  const int64_t mj = t >> 8;  // m * ds + j
+  const int m = (int)(mj / ds), j = (int)(mj - (int64_t)m * ds);
+  D.codebooks_t[t] = D.codebooks[((size_t)m * 256 + c) * ds + j];
+}
+
+void launch_pq_transpose(const Dev &D, hipStream_t s) {
+  hipLaunchKernelGGL(k_pq_transpose, dim3((unsigned)D.d), dim3(256), 0, s, D);
 }
 
 void launch_pq_fill(const Dev &D, int64_t n, const float *Y, const int64_t *ids, int64_t id_base,

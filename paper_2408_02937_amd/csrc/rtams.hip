@@ -37,7 +37,7 @@ inline size_t up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Byte offsets of everything in front of the blocks.
 struct Layout {
-  size_t ctrl, hook, centroids, cnorm, codebooks, tc_min, tc_cnt, tc_col, tc_val, tile_rows, reserved_len, visible_len, online, nblk, exceed, seg_dir;
+  size_t ctrl, hook, centroids, cnorm, codebooks, codebooks_t, tc_min, tc_cnt, tc_col, tc_val, tile_rows, reserved_len, visible_len, online, nblk, exceed, seg_dir;
   size_t ins_assign, ins_did, ins_pscore, ins_pidx, part_cap;
   size_t rearr_head, rearr_arrays;
   size_t fixed_end;          // end of the part that does not depend on the block count
@@ -89,6 +89,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
   L->centroids = take(nl * c->d * sizeof(float));
   L->cnorm = take(nl * sizeof(float));
   L->codebooks = take(c->pq_m > 0 ? (size_t)256 * c->d * sizeof(float) : 0);
+  L->codebooks_t = take(c->pq_m > 0 ? (size_t)256 * c->d * sizeof(float) : 0);
   L->reserved_len = take(nl * 4);
   L->visible_len = take(nl * 4);
   L->online = take(nl * 4);
@@ -368,6 +369,7 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   D.centroids = reinterpret_cast<float *>(base + L.centroids);
   D.cnorm = reinterpret_cast<float *>(base + L.cnorm);
   D.codebooks = reinterpret_cast<float *>(base + L.codebooks);
+  D.codebooks_t = reinterpret_cast<float *>(base + L.codebooks_t);
   D.pq_m = cfg->pq_m;
   D.reserved_len = reinterpret_cast<uint32_t *>(base + L.reserved_len);
   D.visible_len = reinterpret_cast<uint32_t *>(base + L.visible_len);
@@ -503,6 +505,8 @@ int rtams_set_codebooks(rtams_index *ix, const float *d_codebooks, void *hip_str
   int rc = enter_data_stream(ix, s);
   if (rc) return rc;
   HIP_TRY(hipMemcpyAsync(ix->dev.codebooks, d_codebooks, (size_t)256 * ix->cfg.d * 4, hipMemcpyDeviceToDevice, s));
+  launch_pq_transpose(ix->dev, s);
+  HIP_TRY(hipGetLastError());
   ix->has_codebooks = true;
   return leave_data_stream(ix, s);
 }

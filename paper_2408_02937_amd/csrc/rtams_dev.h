@@ -68,6 +68,7 @@ struct Dev {
   float *centroids;         // [nlist][d]
   float *cnorm;             // [nlist] squared norms of the centroids (fp32)
   float *codebooks;         // [pq_m][256][d / pq_m] (product-quantised lists only)
+  float *codebooks_t;       // the same with the entries innermost: [pq_m][d / pq_m][256] (for coding inserted vectors)
   uint32_t *reserved_len;   // [nlist] next free position (atomicAdd target)
   uint32_t *visible_len;    // [nlist] length searches may read
   uint32_t *online;         // [nlist] vectors since the last rearrangement

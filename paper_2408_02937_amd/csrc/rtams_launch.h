@@ -137,6 +137,7 @@ void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
 // pq.hip -----------------------------------------------------------------------
 void launch_pq_fill(const Dev &D, int64_t n, const float *Y, const int64_t *ids, int64_t id_base,
                     const InsertScratch &S, hipStream_t s);
+void launch_pq_transpose(const Dev &D, hipStream_t s);  // after the codebooks changed
 void launch_pq_export(const Dev &D, int list, int64_t n, int64_t *ids, uint8_t *codes, hipStream_t s);
 
 // rearrange.hip --------------------------------------------------------------
