@@ -63,3 +63,28 @@ def test_create_needs_memory():
     h = C.c_void_p()
     assert L.rtams_create(C.byref(cfg()), C.byref(h)) == rtams.EINVAL
     assert b"pool and scratch" in L.rtams_last_error()
+
+
+@pytest.mark.parametrize("bad_m", [3, 6, 12, 68, -4])
+def test_bad_quantiser_shapes_are_refused_on_the_host(bad_m):
+    """pq_m must be 0, or a multiple of 4 up to 64 that divides d (here d = 32)."""
+    L = rtams.lib()
+    assert L.rtams_pool_bytes_for(C.byref(cfg(pq_m=bad_m)), 10) == 0
+    assert b"pq_m" in L.rtams_last_error()
+
+
+def test_quantised_blocks_are_smaller_and_carry_a_table_per_query():
+    L = rtams.lib()
+    flat, pq = cfg(), cfg(pq_m=8)
+    stride = lambda c: (L.rtams_pool_bytes_for(C.byref(c), 2010) - L.rtams_pool_bytes_for(C.byref(c), 1010)) // 1000
+    # header 128 + 64 ids + 64 x 8 code bytes = 1152 -> 1280 with the 256-byte padding, plus 16 bytes of tables
+    assert abs(stride(pq) - (1280 + 16)) <= 1 and stride(pq) < stride(flat)
+    # per query a table of pq_m x 256 floats in every stream resource
+    extra = L.rtams_scratch_bytes_for(C.byref(pq), 0) - L.rtams_scratch_bytes_for(C.byref(flat), 0)
+    assert extra == 16 * 8 * 256 * 4
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess, sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
