@@ -217,7 +217,12 @@ int rtams_read_plain(const void *d_src, size_t bytes, float *d_sink, void *hip_s
  * "use_mfma": whether approximate coarse scores from the matrix cores filter the
  * centroids before the exact arithmetic decides (0 never, 1 for batches large
  * enough to repay it (default), 2 for every batch of 32 rows or more; results
- * are identical in all three).  EINVAL for an unknown key. */
+ * are identical in all three); "ordered_add": 0 (default) reserves the positions
+ * of a batch inside a list with one atomic per vector, in arrival order, as
+ * Algorithm 2 does; 1 hands them out in the order of the batch, so that every
+ * list holds the sequence that inserting the vectors one at a time would give
+ * (the same on every run; one thread per list walks the batch: slower, meant
+ * for checking and debugging).  EINVAL for an unknown key. */
 int rtams_set_param(rtams_index *ix, const char *key, int64_t value);
 
 #ifdef __cplusplus

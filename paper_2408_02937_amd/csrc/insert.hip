@@ -40,6 +40,23 @@ __global__ __launch_bounds__(256) void k_reserve(Dev D, int64_t n, int splits,
   if (reserve) did[i] = atomicAdd(&D.reserved_len[bi], 1u);
 }
 
+// ---- reservation in input order.  The atomic reservation above hands out the positions of a
+// batch inside a list in arrival order, which is any order (Algorithm 2 takes `did` from an
+// atomicAdd as well).  This variant gives the vectors of a batch that fall into one list
+// consecutive positions in the order in which they stand in the batch, which is what inserting
+// them one at a time would do: the lists then hold the same SEQUENCE on every run.  One thread per
+// list walks the batch's assignments (every lane of a wavefront reads the same word).
+__global__ __launch_bounds__(256) void k_reserve_ordered(Dev D, int64_t n, const int32_t *__restrict__ assign,
+                                                         uint32_t *__restrict__ did) {
+  const int list = blockIdx.x * blockDim.x + threadIdx.x;
+  if (list >= D.nlist) return;
+  uint32_t at = D.reserved_len[list];
+  const uint32_t before = at;
+  for (int64_t i = 0; i < n; ++i)
+    if (assign[i] == list) did[i] = at++;
+  if (at != before) D.reserved_len[list] = at;
+}
+
 // ---- open: one wavefront per list.  Positions visible_len .. reserved_len-1
 // were reserved by this batch; every block index in [nblk, ceil(reserved/T_m))
 // is opened here: table segments first, then blocks from the free stack or the
@@ -185,6 +202,12 @@ void launch_reserve(const Dev &D, int64_t n, int splits, const InsertScratch &S,
   unsigned grid = (unsigned)((n + 255) / 256);
   hipLaunchKernelGGL(k_reserve, dim3(grid), dim3(256), 0, s, D, n, splits, S.pscore, S.pidx,
                      reserve ? 1 : 0, assign_out ? assign_out : S.assign, S.did);
+}
+
+void launch_reserve_ordered(const Dev &D, int64_t n, const InsertScratch &S, hipStream_t s) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(k_reserve_ordered, dim3((unsigned)((D.nlist + 255) / 256)), dim3(256), 0, s, D, n, S.assign,
+                     S.did);
 }
 
 void launch_open(const Dev &D, hipStream_t s) {

@@ -208,6 +208,7 @@ struct rtams_index {
   std::atomic<int64_t> scan_max_items{32768};    // ... and per request
   std::atomic<int64_t> profile_scan{0};
   bool has_codebooks = false;
+  std::atomic<int64_t> ordered_add{0};  // positions inside a list in the order of the batch instead of arrival order
   std::atomic<int64_t> use_mfma{1};  // matrix-core filter in front of the exact coarse arithmetic
   std::mutex prof_mutex;
   double scan_ms = 0.0;      // sum of measured scan-kernel durations
@@ -537,10 +538,16 @@ int rtams_add(rtams_index *ix, int64_t n, const float *d_vecs, const int64_t *d_
   int rc = enter_data_stream(ix, s);
   if (rc) return rc;
   const int64_t round = ix->cfg.max_add_batch;
+  const bool ordered = ix->ordered_add.load(std::memory_order_relaxed) != 0;
   for (int64_t o = 0; o < n; o += round) {
     int64_t m = n - o < round ? n - o : round;
     const float *Y = d_vecs + (size_t)o * D.d;
-    assign_round(ix, m, Y, true, ix->ins.assign, s);
+    if (ordered) {
+      assign_round(ix, m, Y, false, ix->ins.assign, s);
+      launch_reserve_ordered(D, m, ix->ins, s);
+    } else {
+      assign_round(ix, m, Y, true, ix->ins.assign, s);
+    }
     launch_open(D, s);
     if (D.pq_m > 0) launch_pq_fill(D, m, Y, d_ids ? d_ids + o : nullptr, ix->ntotal_host + o, ix->ins, s);
     else launch_fill(D, m, Y, d_ids ? d_ids + o : nullptr, ix->ntotal_host + o, ix->ins, s);
@@ -876,6 +883,7 @@ int rtams_read_plain(const void *d_src, size_t bytes, float *d_sink, void *hip_s
 int rtams_set_param(rtams_index *ix, const char *key, int64_t value) {
   if (!ix || !key) return fail(RTAMS_EINVAL, "NULL argument");
   if (!strcmp(key, "profile_scan")) { ix->profile_scan = value; return RTAMS_OK; }
+  if (!strcmp(key, "ordered_add")) { ix->ordered_add = value; return RTAMS_OK; }
   if (!strcmp(key, "use_mfma")) { ix->use_mfma = value; return RTAMS_OK; }
   if (!strcmp(key, "scan_max_items")) { ix->scan_max_items = value > 1024 ? value : 1024; return RTAMS_OK; }
   if (!strcmp(key, "scan_items_per_pair")) { ix->scan_items_per_pair = value > 0 ? value : 1; return RTAMS_OK; }

@@ -116,6 +116,8 @@ void launch_assign_refine(const Dev &D, int64_t n, const float *Y, const TileCan
 // insert.hip -----------------------------------------------------------------
 void launch_reserve(const Dev &D, int64_t n, int splits, const InsertScratch &S, bool reserve,
                     int32_t *assign_out, hipStream_t s);
+// Positions for a batch whose lists are already in S.assign, in the order of the batch (one thread per list).
+void launch_reserve_ordered(const Dev &D, int64_t n, const InsertScratch &S, hipStream_t s);
 void launch_open(const Dev &D, hipStream_t s);
 void launch_fill(const Dev &D, int64_t n, const float *Y, const int64_t *ids, int64_t id_base,
                  const InsertScratch &S, hipStream_t s);

@@ -60,6 +60,43 @@ def test_list_contents_and_block_structure(loaded):
     assert_lists_equal(g, o, bounds)
 
 
+@pytest.mark.parametrize("name,mfma,max_add_batch", [("tiny-l2", 0, 65536), ("zipf-l2", 2, 65536),
+                                                     ("zipf-l2", 0, 1000), ("unit-ip", 2, 4096)])
+def test_ordered_insertion_gives_the_oracle_s_sequences(name, mfma, max_add_batch):
+    """With positions handed out in the order of the batch ("ordered_add") every
+    list holds, entry by entry, what inserting the vectors one at a time gives:
+    the oracle's sequences, not merely its sets.  The bulk load is cut into
+    rounds of max_add_batch inside the library; the skewed set puts hundreds of
+    vectors of one batch, and several new blocks, into one list."""
+    w = workloads()[name]
+    print(f"[case] ordered insertion, workload={w.name} use_mfma={mfma} max_add_batch={max_add_batch}", flush=True)
+    g, o = make_pair(w, max_add_batch=max_add_batch)
+    g.set_param("use_mfma", mfma)
+    g.set_param("ordered_add", 1)
+    g.add(dev(w.base))
+    o.add(w.base)
+    for b in range(0, len(w.inserts), w.insert_batch):
+        chunk = w.inserts[b:b + w.insert_batch]
+        g.add(dev(chunk))
+        o.add(chunk)
+    torch.cuda.synchronize()
+    assert g.poll_error() == 0
+    g.validate()
+    assert np.array_equal(g.list_sizes(), o.list_sizes())
+    for k in range(g.nlist):
+        gi, gx = g.list_export(k)
+        oi, ox = o.list_export(k)
+        assert np.array_equal(gi.cpu().numpy(), oi), f"list {k}: id sequence differs"
+        assert np.array_equal(gx.cpu().numpy().view(np.uint32), ox.view(np.uint32)), f"list {k}: vectors differ"
+    # and a search over them is the oracle's
+    q = w.queries[:64]
+    d, i = g.search(dev(q), w.k, w.nprobe)
+    torch.cuda.synchronize()
+    rd, ri = o.search(q, w.k, w.nprobe)
+    assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), rd, ri, RTOL)
+    g.close()
+
+
 def test_probe_selection_is_bit_exact(loaded):
     w, g, o, _ = loaded
     for nprobe in (1, w.nprobe, min(w.nlist, 64)):
