@@ -43,7 +43,7 @@ enum rtams_status {
   RTAMS_EPOOL = -3,   /* the block pool cannot hold the blocks this call may need */
   RTAMS_EBUSY = -4,   /* every stream resource is in flight: request rejected */
   RTAMS_EHIP = -5,    /* a HIP runtime call failed */
-  RTAMS_ESCRATCH = -6 /* a search needed more candidate scratch than one resource holds */
+  RTAMS_ESCRATCH = -6 /* a search needed more candidate scratch than its resource and the shared reserve hold */
 };
 
 typedef struct rtams_config {
@@ -66,6 +66,11 @@ typedef struct rtams_config {
   int32_t pq_m;          /* 0: the lists hold the vectors (IVF-Flat).  M > 0: they hold
                             product-quantiser codes, M bytes per vector (IVF-PQ): M a
                             multiple of 4, at most 64, dividing d */
+  size_t overflow_bytes; /* the last overflow_bytes of d_scratch are a reserve shared by all
+                            stream resources (the paper's overflow chunks from a central pool,
+                            Deployment Detail): a query whose candidates do not fit into what is
+                            left of its request's own slice gets room there until its request
+                            is finished; 0: no reserve */
 } rtams_config;
 
 typedef struct rtams_stats {
@@ -80,6 +85,9 @@ typedef struct rtams_stats {
   double utilisation;       /* blocks_in_use / blocks_total; the paper alerts above 0.9 */
   int64_t lists_exceeding;  /* lists for which Exceed() currently holds */
   int64_t table_entries_used, table_entries_total;
+  int64_t overflow_total;   /* candidate entries the shared scratch reserve holds */
+  int64_t overflow_in_use;  /* ... of which handed out to queries of requests not yet finished */
+  int64_t overflow_users;   /* such queries */
 } rtams_stats;
 
 /* Bytes of pool needed for `blocks` blocks under this configuration (d_pool and
@@ -89,7 +97,10 @@ size_t rtams_pool_bytes_for(const rtams_config *cfg, int64_t blocks);
 /* Bytes of scratch one stream resource needs so that a search of max_batch
  * queries may score `candidates_per_query` list entries per query (8 bytes
  * per entry: key and position of those that survive the pruning bound, with
- * room for all). */
+ * room for all).  A request whose queries have more candidates than that in
+ * total takes the rest from the shared reserve (overflow_bytes: 256 bytes plus
+ * 8 per entry), and fails with ESCRATCH (rtams_poll_error) for the queries
+ * that fit neither. */
 size_t rtams_scratch_bytes_for(const rtams_config *cfg, int64_t candidates_per_query);
 
 /* Creates the index over caller-owned device memory (both regions 256-byte

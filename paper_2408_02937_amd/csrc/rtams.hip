@@ -208,6 +208,8 @@ struct rtams_index {
   std::atomic<int64_t> scan_max_items{32768};    // ... and per request
   std::atomic<int64_t> profile_scan{0};
   bool has_codebooks = false;
+  unsigned long long *ovf_word = nullptr;  // device: state of the shared scratch reserve
+  unsigned long long ovf_cap = 0;
   std::atomic<int64_t> ordered_add{0};  // positions inside a list in the order of the batch instead of arrival order
   std::atomic<int64_t> use_mfma{1};  // matrix-core filter in front of the exact coarse arithmetic
   std::mutex prof_mutex;
@@ -346,7 +348,8 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
                 cfg->pool_bytes, L.fixed_end, L.block_stride);
   ScratchLayout SL;
   lay_out_scratch(cfg, &SL);
-  size_t slice = cfg->scratch_bytes / (size_t)cfg->n_resources / kAlign * kAlign;
+  if (cfg->overflow_bytes > cfg->scratch_bytes) return fail(RTAMS_EINVAL, "overflow_bytes exceeds scratch_bytes");
+  size_t slice = (cfg->scratch_bytes - cfg->overflow_bytes) / (size_t)cfg->n_resources / kAlign * kAlign;
   if (slice < SL.fixed + kAlign)
     return fail(RTAMS_EINVAL, "scratch slice of %zu bytes is smaller than its fixed part %zu", slice,
                 SL.fixed + kAlign);
@@ -427,6 +430,14 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   if (!ix->res) return bail(fail(RTAMS_EINVAL, "out of host memory"));
   ix->n_res = cfg->n_resources;
   char *sb = static_cast<char *>(cfg->d_scratch);
+  // the shared reserve behind the slices: one word, then two arrays of equal length
+  char *ovf = sb + (size_t)cfg->n_resources * slice;
+  const size_t ovf_bytes = cfg->overflow_bytes >= 3 * kAlign ? cfg->scratch_bytes - (size_t)cfg->n_resources * slice : 0;
+  const unsigned long long ovf_cap = ovf_bytes ? (ovf_bytes - kAlign) / (2 * kAlign) * (kAlign / 4) : 0;
+  if (ovf_cap >> kOverflowShift) return bail(fail(RTAMS_EINVAL, "overflow_bytes too large"));
+  if (ovf_cap && hipMemset(ovf, 0, kAlign) != hipSuccess) return bail(fail(RTAMS_EHIP, "hipMemset of the scratch reserve failed"));
+  ix->ovf_word = ovf_cap ? reinterpret_cast<unsigned long long *>(ovf) : nullptr;
+  ix->ovf_cap = ovf_cap;
   for (int r = 0; r < ix->n_res; ++r) {
     char *p = sb + (size_t)r * slice;
     SearchScratch &S = ix->res[r].s;
@@ -454,6 +465,10 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
     S.cand_cap = (slice - SL.fixed) / (2 * kAlign) * (kAlign / 4);
     S.rec_key = reinterpret_cast<uint32_t *>(p + SL.records);
     S.rec_pos = S.rec_key + S.cand_cap;
+    S.ovf_word = ix->ovf_word;
+    S.ovf_cap = ovf_cap;
+    S.ovf_key = reinterpret_cast<uint32_t *>(ovf + kAlign);
+    S.ovf_pos = S.ovf_key + ovf_cap;
     if (hipEventCreateWithFlags(&ix->res[r].done, hipEventDisableTiming) != hipSuccess ||
         hipEventCreate(&ix->res[r].t0) != hipSuccess || hipEventCreate(&ix->res[r].t1) != hipSuccess)
       return bail(fail(RTAMS_EHIP, "hipEventCreate failed"));
@@ -815,6 +830,13 @@ int rtams_pool_stats(rtams_index *ix, rtams_stats *out) {
   out->lists_exceeding = c.exceed_lists;
   out->table_entries_used = c.slab_cur;
   out->table_entries_total = (int64_t)ix->lay.slab_cap;
+  out->overflow_total = (int64_t)ix->ovf_cap;
+  if (ix->ovf_word) {  // as of now: searches in flight on other streams may hold room
+    unsigned long long w = 0;
+    HIP_TRY(hipMemcpy(&w, ix->ovf_word, 8, hipMemcpyDeviceToHost));
+    out->overflow_in_use = (int64_t)(w & ((1ull << kOverflowShift) - 1ull));
+    out->overflow_users = (int64_t)(w >> kOverflowShift);
+  }
   ix->avail_lb = out->blocks_total - out->blocks_in_use;
   return RTAMS_OK;
 }

@@ -43,7 +43,15 @@ struct SearchScratch {
   uint32_t *rec_key;    // survivors: key of the score (smaller is better) ...
   uint32_t *rec_pos;    // ... and position among the query's candidates
   unsigned long long cand_cap;  // entries of each of the two arrays
+  // the reserve shared by all resources: a query whose candidates do not fit into the slice gets its
+  // room here (bit 63 of its qbase says so) until its selection has finished
+  unsigned long long *ovf_word; // queries holding room << 40 | entries handed out (back to 0 when nobody holds any)
+  uint32_t *ovf_key, *ovf_pos;
+  unsigned long long ovf_cap;   // entries of each of the two arrays, below 2^40
 };
+
+constexpr unsigned long long kInOverflow = 1ull << 63;  // flag in SearchScratch::qbase
+constexpr int kOverflowShift = 40;
 
 constexpr int kScanTileQueries = 8;  // queries that share one pass over a list
 

@@ -19,6 +19,40 @@ __device__ inline uint32_t key_of_float(float x) {
   return (b >> 31) ? ~b : (b | 0x80000000u);
 }
 
+// ------------------------------------------------------- survivor records
+// Where a query's records lie: in its request's slice or, flagged, in the reserve all resources share.
+__device__ inline uint32_t *rec_keys_of(const SearchScratch &S, unsigned long long qbase) {
+  return (qbase & kInOverflow) ? S.ovf_key + (qbase & ~kInOverflow) : S.rec_key + qbase;
+}
+__device__ inline uint32_t *rec_poss_of(const SearchScratch &S, unsigned long long qbase) {
+  return (qbase & kInOverflow) ? S.ovf_pos + (qbase & ~kInOverflow) : S.rec_pos + qbase;
+}
+// Room for `want` entries from the shared reserve (one thread): the start, flagged, or ~0 when it does
+// not have that much left.  The reserve is a bump pointer that falls back to zero when the last
+// holder lets go: users << 40 | entries handed out, moved by compare-and-swap.
+__device__ inline unsigned long long overflow_take(const SearchScratch &S, unsigned long long want) {
+  if (!S.ovf_word) return ~0ull;
+  const unsigned long long mask = (1ull << kOverflowShift) - 1ull;
+  unsigned long long w = __hip_atomic_load(S.ovf_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (;;) {  // ends: every failed exchange means another thread's succeeded
+    const unsigned long long used = w & mask;
+    if (used + want > S.ovf_cap) return ~0ull;
+    const unsigned long long seen = atomicCAS(S.ovf_word, w, (((w >> kOverflowShift) + 1ull) << kOverflowShift) | (used + want));
+    if (seen == w) return kInOverflow | used;
+    w = seen;
+  }
+}
+__device__ inline void overflow_give_back(const SearchScratch &S) {
+  const unsigned long long mask = (1ull << kOverflowShift) - 1ull;
+  unsigned long long w = __hip_atomic_load(S.ovf_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (;;) {
+    const unsigned long long users = (w >> kOverflowShift) - 1ull;
+    const unsigned long long seen = atomicCAS(S.ovf_word, w, users ? (users << kOverflowShift) | (w & mask) : 0ull);
+    if (seen == w) return;
+    w = seen;
+  }
+}
+
 // ------------------------------------------------- workgroup radix selection
 // Finds the threshold of the k smallest keys among the valid items 0..n-1.
 // fn(i, key) returns false for items that do not take part.  On return T is
@@ -321,9 +355,15 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
       tot += len;
     }
     unsigned long long base = 0;
+    if (probe_out) tot = 0;  // the probe hook: nothing is scanned afterwards, no room for records is taken
     if (tot > 0xFFFFFFFFull) tot = ~0ull;  // cannot be indexed: treated as overflow below
     if (tot != ~0ull) base = atomicAdd(S.cursor, tot);
-    if (tot == ~0ull || base + tot > S.cand_cap) {  // not enough candidate scratch for this query
+    if (tot != ~0ull && base + tot > S.cand_cap) {  // does not fit into the slice any more: the shared reserve
+      base = overflow_take(S, tot);
+      if (base == ~0ull) tot = ~0ull;
+    }
+    if (tot == ~0ull) {  // not enough candidate scratch for this query
+      base = 0;
       atomicCAS(&D.ctrl->error, 0, -6);
       D.mirror->error = -6;
       tot = 0;
@@ -950,14 +990,16 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
   // lane i < NQ looks after query i of the item: how far its list goes, its bound, where its
   // survivor records go
   uint32_t my_q = 0, my_len = 0, my_off = 0, my_bound = 0;
-  uint64_t my_base = 0;  // start of the query's slice of rec_key / rec_pos
+  uint64_t my_keys = 0, my_poss = 0;  // addresses of the query's survivor records (keys, positions)
   if (lane < NQ) {
     const uint32_t pk = S.grouped[first + lane];
     my_q = pk >> 10;
     const size_t o = (size_t)my_q * max_nprobe + (pk & 1023u);
     my_len = S.probe_len[o];
     my_off = S.probe_off[o];
-    my_base = S.qbase[my_q];
+    const unsigned long long qb = S.qbase[my_q];
+    my_keys = (uint64_t)(uintptr_t)rec_keys_of(S, qb);
+    my_poss = (uint64_t)(uintptr_t)rec_poss_of(S, qb);
     my_bound = S.bound[my_q];
   }
   // the bound as a score (L2: keys of non-negative floats order like the floats; "keep everything" is +inf)
@@ -1091,10 +1133,10 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
 #pragma unroll
         for (int i = 0; i < NQ; ++i) {
           if ((m0[i] | m1[i]) == 0) continue;  // uniform
-          const uint64_t at = lane_u64(my_base, i) + lane_u32(base_mine, i);
+          const uint64_t at = 4ull * lane_u32(base_mine, i);
           const uint32_t off = lane_u32(my_off, i);
-          GlobalU32 *rk = (GlobalU32 *)((uint64_t)(uintptr_t)S.rec_key + 4ull * at);
-          GlobalU32 *rp = (GlobalU32 *)((uint64_t)(uintptr_t)S.rec_pos + 4ull * at);
+          GlobalU32 *rk = (GlobalU32 *)(lane_u64(my_keys, i) + at);
+          GlobalU32 *rp = (GlobalU32 *)(lane_u64(my_poss, i) + at);
           if ((m0[i] >> lane) & 1ull) {
             const uint32_t slot = (uint32_t)__popcll(m0[i] & below);
             rk[slot] = key_of_float((METRIC == 0 ? acc0[i] : -acc0[i]) + 0.0f);
@@ -1174,7 +1216,7 @@ __device__ inline void pq_flush(const SearchScratch &S, int q, unsigned long lon
   uint32_t at = 0;
   if (lane == 0) at = atomicAdd(&S.rec_cnt[q], n);
   at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
-  uint32_t *rk = S.rec_key + base + at, *rp = S.rec_pos + base + at;
+  uint32_t *rk = rec_keys_of(S, base) + at, *rp = rec_poss_of(S, base) + at;
   for (uint32_t i = (uint32_t)lane; i < n; i += kWave) {
     rk[i] = my_key[i];
     rp[i] = my_pos[i];
@@ -1324,7 +1366,7 @@ __global__ __launch_bounds__(kPqScanThreads) void k_pq_scan(Dev D, int nprobe, i
         if (lane == 0) at = atomicAdd(&S.rec_cnt[q], n_keep);
         at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
         const unsigned long long below = (1ull << lane) - 1ull;
-        uint32_t *rk = S.rec_key + base + at, *rp = S.rec_pos + base + at;
+        uint32_t *rk = rec_keys_of(S, base) + at, *rp = rec_poss_of(S, base) + at;
 #pragma unroll
         for (int j = 0; j < kPqUnits; ++j) {
           if ((mask[j] >> lane) & 1ull) {
@@ -1524,7 +1566,7 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
   const int q = blockIdx.x;
   const int n = (int)S.rec_cnt[q];
   const unsigned long long base = S.qbase[q];
-  const uint32_t *rk = S.rec_key + base, *rp = S.rec_pos + base;
+  const uint32_t *rk = rec_keys_of(S, base), *rp = rec_poss_of(S, base);
   const int metric = D.metric;
   const int lane = threadIdx.x & (kWave - 1);
   for (int p = threadIdx.x; p < nprobe; p += kTopkThreads) {
@@ -1657,6 +1699,9 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
       out_ids[o] = -1;
     }
   }
+  // the records are not looked at any more (the selection ended with a barrier): room taken from
+  // the shared reserve goes back
+  if ((base & kInOverflow) && threadIdx.x == 0) overflow_give_back(S);
 }
 
 // ---------------------------------------------------------------- launchers

@@ -38,7 +38,8 @@ class Config(C.Structure):
                 ("d_pool", C.c_void_p), ("pool_bytes", C.c_size_t),
                 ("d_scratch", C.c_void_p), ("scratch_bytes", C.c_size_t),
                 ("n_resources", C.c_int32), ("max_batch", C.c_int32), ("max_k", C.c_int32),
-                ("max_nprobe", C.c_int32), ("max_add_batch", C.c_int32), ("pq_m", C.c_int32)]
+                ("max_nprobe", C.c_int32), ("max_add_batch", C.c_int32), ("pq_m", C.c_int32),
+                ("overflow_bytes", C.c_size_t)]
 
 
 class Stats(C.Structure):
@@ -47,7 +48,8 @@ class Stats(C.Structure):
                 ("blocks_in_use", C.c_int64), ("block_bytes", C.c_int64),
                 ("pool_bytes", C.c_int64), ("meta_bytes", C.c_int64), ("utilisation", C.c_double),
                 ("lists_exceeding", C.c_int64), ("table_entries_used", C.c_int64),
-                ("table_entries_total", C.c_int64)]
+                ("table_entries_total", C.c_int64), ("overflow_total", C.c_int64),
+                ("overflow_in_use", C.c_int64), ("overflow_users", C.c_int64)]
 
 
 class RtamsError(RuntimeError):
@@ -135,7 +137,8 @@ class Index:
                  pool_blocks: Optional[int] = None, pool_bytes: Optional[int] = None,
                  rearrange_threshold: int = 0, n_resources: int = 8, max_batch: int = 256,
                  max_k: int = 128, max_nprobe: int = 64, max_add_batch: int = 65536,
-                 candidates_per_query: int = 65536, device: str = "cuda:0", pq_m: int = 0):
+                 candidates_per_query: int = 65536, device: str = "cuda:0", pq_m: int = 0,
+                 overflow_candidates: int = 0):
         L = lib()
         self.d, self.nlist, self.block_vecs, self.pq_m = d, nlist, block_vecs, pq_m
         self.metric = {"l2": L2, "ip": IP}[metric]
@@ -155,9 +158,13 @@ class Index:
             raise RtamsError(EINVAL, "scratch_bytes_for", L.rtams_last_error().decode())
         # caller-owned device memory: one pool, one scratch area
         self.pool = torch.empty(pool_bytes, dtype=torch.uint8, device=self.device)
-        self.scratch = torch.empty(per_res * n_resources, dtype=torch.uint8, device=self.device)
+        # the reserve shared by all resources: a word (256 bytes) and 8 bytes per candidate entry
+        overflow_bytes = 256 + 2 * ((overflow_candidates * 4 + 255) // 256 * 256) if overflow_candidates > 0 else 0
+        scratch_bytes = per_res * n_resources + overflow_bytes
+        self.scratch = torch.empty(scratch_bytes, dtype=torch.uint8, device=self.device)
         cfg.d_pool, cfg.pool_bytes = self.pool.data_ptr(), pool_bytes
-        cfg.d_scratch, cfg.scratch_bytes = self.scratch.data_ptr(), per_res * n_resources
+        cfg.d_scratch, cfg.scratch_bytes = self.scratch.data_ptr(), scratch_bytes
+        cfg.overflow_bytes = overflow_bytes
         self.cfg = cfg
         h = C.c_void_p()
         torch.cuda.synchronize(self.device)
