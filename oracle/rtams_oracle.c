@@ -282,8 +282,8 @@ int orc_rearrange(orc_index *ix, int k) {
     if (tgt >= ix->npool) break;        /* the pool ends here: stay partly compacted */
     if (src == tgt) continue;
     int occupied = 0;
-    if (tgt >= ix->cur_P) {             /* never handed out: move the frontier past it */
-      for (int64_t b = ix->cur_P; b < tgt; ++b) give_block(ix, (int32_t)b);
+    if (tgt >= ix->cur_P) {             /* never handed out (targets advance one block at a
+                                           time, so tgt == cur_P): the frontier moves past it */
       ix->cur_P = tgt + 1;
     } else if (ix->owner[tgt] < 0) {    /* sits on the free stack */
       unfree_block(ix, (int32_t)tgt);

@@ -110,10 +110,10 @@ def test_pool_exhaustion_leaves_no_trace():
     assert ix.blocks_in_use == 3
 
 
-def two_list_index(T_m, T_mp, alloc):
+def two_list_index(T_m, T_mp, alloc, pool_blocks=64):
     """Two lists A=0, B=1 in 2-d; one block is opened per entry of alloc."""
     C = np.array([[1, 0], [0, 1]], dtype=np.float32)
-    ix = OracleIndex(2, 2, "ip", T_m, rearrange_threshold=T_mp, pool_blocks=64)
+    ix = OracleIndex(2, 2, "ip", T_m, rearrange_threshold=T_mp, pool_blocks=pool_blocks)
     ix.set_centroids(C)
     for who in alloc:                                           # fill one whole block each time
         ix.add(np.repeat(C[who:who + 1], T_m, axis=0) * np.float32(1 + ix.ntotal))
@@ -152,6 +152,68 @@ def test_rearrangement_into_free_and_fresh_blocks():
     assert ix.blocks_in_use == 5
     ix.add(np.array([[1, 0]] * 2, dtype=np.float32))            # next block comes off the free stack
     assert ix.list_chain(0).tolist() == [0, 1, 2, 3] and ix.nfree == 0
+
+
+def test_a_rearranged_list_can_be_the_next_victim():
+    """Worked by hand from the Rearrangement algorithm (exchange of the two blocks'
+    contents and owners): B = 0 2 4, A = 1 3.  Compacting A exchanges 3 with 2
+    (A = 1 2, B = 0 3 4).  Compacting B then takes both of A's blocks, the one A
+    was opened with and the one it was just given: 1 against 3, then 2 against
+    4 (B = 0 1 2, A = 3 4).  Every block stays in exactly one chain."""
+    ix = two_list_index(2, 0, [1, 0, 1, 0, 1])
+    assert ix.list_chain(1).tolist() == [0, 2, 4] and ix.list_chain(0).tolist() == [1, 3]
+    before = [ix.list_export(k) for k in range(2)]
+    ix.rearrange(0)
+    assert ix.list_chain(0).tolist() == [1, 2] and ix.list_chain(1).tolist() == [0, 3, 4]
+    ix.rearrange(1)
+    assert ix.list_chain(1).tolist() == [0, 1, 2] and ix.list_chain(0).tolist() == [3, 4]
+    assert ix.list_jumps(0) == 0 and ix.list_jumps(1) == 0 and ix.blocks_in_use == 5 and ix.nfree == 0
+    for k in range(2):
+        ids, x = ix.list_export(k)
+        assert np.array_equal(ids, before[k][0]) and np.array_equal(x, before[k][1])
+    assert [ix.slot(0, did) for did in range(4)] == [(3, 0), (3, 1), (4, 0), (4, 1)]
+
+
+def test_rearrangement_onto_a_block_of_the_free_stack_in_a_full_pool():
+    """Worked by hand, pool of exactly 8 blocks.  A = 0 2 5, B = 1 3 4.  Compacting
+    A exchanges 1 and 2 with B's first block in turn (A = 0 1 2, B = 5 3 4).  B now
+    starts at the frontier: its targets 6 and 7 were never handed out, its blocks 3
+    and 4 go to the free stack (4 on top) and the pool's bump pointer is at its
+    end.  A's next block comes off the stack (4: the pool is full otherwise, the
+    add must not be refused); compacting A then finds its target 3 ON the stack:
+    3 leaves the stack, 4 returns to it.  Later blocks: 4 again, then nothing."""
+    from oracle.oracle import OracleError
+    ix = two_list_index(2, 0, [0, 1, 0, 1, 1, 0], pool_blocks=8)
+    C = np.array([[1, 0], [0, 1]], dtype=np.float32)
+    block_for = lambda who: np.repeat(C[who:who + 1], 2, axis=0)
+    assert ix.list_chain(0).tolist() == [0, 2, 5] and ix.list_chain(1).tolist() == [1, 3, 4]
+    ix.rearrange(0)
+    assert ix.list_chain(0).tolist() == [0, 1, 2] and ix.list_chain(1).tolist() == [5, 3, 4]
+    ix.rearrange(1)
+    assert ix.list_chain(1).tolist() == [5, 6, 7] and ix.cur_P == 8 and ix.nfree == 2 and ix.blocks_in_use == 6
+    ix.add(block_for(0))                                        # bump pointer exhausted, two blocks on the stack
+    assert ix.list_chain(0).tolist() == [0, 1, 2, 4] and ix.nfree == 1
+    ix.rearrange(0)
+    assert ix.list_chain(0).tolist() == [0, 1, 2, 3] and ix.nfree == 1 and ix.blocks_in_use == 7
+    ix.add(block_for(1))
+    assert ix.list_chain(1).tolist() == [5, 6, 7, 4] and ix.nfree == 0 and ix.blocks_in_use == 8
+    with pytest.raises(OracleError):
+        ix.add(block_for(0))                                    # now the pool is full
+    owned = np.concatenate([ix.list_chain(0), ix.list_chain(1)])
+    assert sorted(owned.tolist()) == list(range(8))
+
+
+def test_rearrangement_stops_at_the_end_of_the_pool():
+    """The same start in a pool of 7 blocks: B's second target (7) does not
+    exist, the list stays compacted as far as the pool reaches."""
+    ix = two_list_index(2, 0, [0, 1, 0, 1, 1, 0], pool_blocks=7)
+    ix.rearrange(0)
+    before = ix.list_export(1)
+    ix.rearrange(1)
+    assert ix.list_chain(1).tolist() == [5, 6, 4] and ix.cur_P == 7 and ix.nfree == 1 and ix.blocks_in_use == 6
+    assert ix.list_jumps(1) == 1
+    ids, x = ix.list_export(1)
+    assert np.array_equal(ids, before[0]) and np.array_equal(x, before[1])
 
 
 def test_exceed_is_a_strict_inequality():

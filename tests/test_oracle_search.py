@@ -155,6 +155,20 @@ def test_coarse_arithmetic_is_one_fma_per_dimension_in_order(metric):
     assert differs_from_reversed > 0 and (metric == "ip" or differs_from_unfused > 0)
 
 
+def test_ranking_uses_the_double_scores_not_their_float_roundings():
+    """x1 = (1 + 2^-23, 0) and x2 = (1, 2^-11) against q = 0: the squared distances
+    1 + 2^-22 + 2^-46 and 1 + 2^-22 differ in double and are one number in float.
+    x2 is nearer although its id is the larger one."""
+    ix = OracleIndex(2, 1, "l2", 4)
+    ix.set_centroids(np.zeros((1, 2), np.float32))
+    x = np.array([[1 + 2.0 ** -23, 0], [1, 2.0 ** -11]], dtype=np.float32)
+    ix.add(x)
+    d, i = ix.search(np.zeros((1, 2), np.float32), 2, 1)
+    assert i[0].tolist() == [1, 0]
+    assert d[0].tolist() == [1 + 2.0 ** -22, 1 + 2.0 ** -22 + 2.0 ** -46]
+    assert np.float32(d[0, 0]) == np.float32(d[0, 1])
+
+
 def test_short_lists_pad_and_argument_errors():
     from oracle.oracle import OracleError
     ix = OracleIndex(4, 4, "ip", 2)
