@@ -80,6 +80,30 @@ def test_rearrange_into_free_fresh_and_own_blocks():
     g.close()
 
 
+def test_rearrangement_without_enough_spare_blocks_leaves_everything_as_it_is():
+    """Moving the occupants of the target range out needs one spare block each for
+    a while; a pool that is nearly full has too few, and the round gives up: no
+    block moves, nothing is lost, no error is raised, and later adds still work."""
+    print("[case] rearrangement in a nearly full pool", flush=True)
+    w, g, o, rng = interleaved(nlist=2, rounds=6, pool_blocks=15)     # 12 blocks in use, 3 spare
+    chains = [g.list_chain(k).copy() for k in range(2)]
+    assert chains[0].tolist() == [0, 2, 4, 6, 8, 10] and chains[1].tolist() == [1, 3, 5, 7, 9, 11]
+    for k in (1, 0):                                                   # 5 occupants in the way, 3 spare blocks
+        g.rearrange(k)
+        torch.cuda.synchronize()
+        g.validate()
+        assert g.poll_error() == 0
+        assert [g.list_chain(j).tolist() for j in range(2)] == [c.tolist() for c in chains]
+    st = g.pool_stats()
+    assert st.blocks_in_use == 12 and st.blocks_free == 0
+    assert_lists_equal(g, o)
+    y = (w.centroids[0] + 0.5 * rng.standard_normal((64, w.d))).astype(np.float32)
+    g.add(dev(y)); o.add(y)
+    g.validate()
+    assert_lists_equal(g, o)
+    g.close()
+
+
 def test_exceed_triggers_rearrangement_behind_the_batch():
     """Exceed() is evaluated when a batch is published; the round is enqueued by
     the next add (or by rearrange(-1)).  The oracle rearranges at once; the logical
