@@ -17,6 +17,7 @@ _SRC = os.path.join(_HERE, "rtams_oracle.c")
 _LIB = os.path.join(_HERE, "librtams_oracle.so")
 
 L2, IP = 0, 1
+STORAGE = {"f32": 0, "f16": 1, "u8": 2}
 OK, EINVAL, ESTATE, EPOOL = 0, -1, -2, -3
 
 
@@ -44,6 +45,9 @@ def lib():
         L.orc_destroy.argtypes = [vp]
         L.orc_set_centroids.argtypes = [vp, vp]
         L.orc_set_codebooks.argtypes = [vp, i32, vp]
+        L.orc_set_storage.argtypes = [vp, i32]
+        L.orc_stored.restype = None
+        L.orc_stored.argtypes = [i32, i64, vp, vp]
         L.orc_pq_encode.argtypes = [vp, i64, vp, vp]
         L.orc_list_export_codes.argtypes = [vp, i32, vp, vp]
         L.orc_assign.argtypes = [vp, i64, vp, vp]
@@ -106,6 +110,10 @@ class OracleIndex:
         c = _f32(centroids)
         assert c.shape == (self.nlist, self.d)
         self._chk(lib().orc_set_centroids(self._h, _ptr(c)), "set_centroids")
+
+    def set_storage(self, storage: str) -> None:
+        """What flat lists keep of a vector: "f32", "f16" or "u8" (before the first add)."""
+        self._chk(lib().orc_set_storage(self._h, STORAGE[storage]), "set_storage")
 
     def set_codebooks(self, codebooks) -> None:
         """codebooks [M][256][d / M]: the lists hold product-quantiser codes from here on."""
@@ -217,6 +225,14 @@ class OracleIndex:
 
     def pool_bytes_in_use(self, header_bytes: int = 0) -> int:
         return lib().orc_pool_bytes_in_use(self._h, header_bytes)
+
+
+def stored(storage: str, values) -> np.ndarray:
+    """What a list with this storage keeps of each value (float32 in, float32 out)."""
+    v = _f32(values)
+    out = np.empty_like(v)
+    lib().orc_stored(STORAGE[storage], v.size, _ptr(v), _ptr(out))
+    return out
 
 
 def threads() -> int:

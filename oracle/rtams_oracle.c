@@ -59,6 +59,18 @@
  *     the query's sub-vector and the codebook entry, plain double arithmetic.
  *   orc_set_codebooks / orc_pq_encode / orc_add / orc_search follow that.
  *
+ * Narrow storage of flat lists (a step towards the quantised lists that keeps
+ * the vectors themselves; the paper stores 32-bit floats): a list may hold its
+ * vectors as IEEE half-precision numbers or as bytes.  Readings:
+ *   - a vector joins the list of its nearest centroid as it is given; what the
+ *     list keeps, returns and scans is the vector after the conversion;
+ *   - half: round to nearest, ties to even, values past the largest half
+ *     become infinity (the IEEE conversion);
+ *   - byte: rounded to the nearest integer, ties to even, then clamped to
+ *     0..255; not-a-number becomes 0.  (Byte-valued data is kept exactly.)
+ *   - scores are computed as for 32-bit storage, on the converted vectors.
+ *   orc_set_storage / orc_stored follow that.
+ *
  * Pins (tests/test_oracle_*.py): brute-force exact k-NN when every list is
  * probed; restriction to the probed lists otherwise; membership invariants;
  * closed forms for block counts and slot addresses; the pad-memory figure of
@@ -77,6 +89,7 @@
 
 enum { ORC_L2 = 0, ORC_IP = 1 };
 enum { ORC_OK = 0, ORC_EINVAL = -1, ORC_ESTATE = -2, ORC_EPOOL = -3 };
+enum { ORC_F32 = 0, ORC_F16 = 1, ORC_U8 = 2 };
 
 typedef struct {
   int64_t n, cap;      /* logical length and capacity of the arrays below   */
@@ -96,6 +109,7 @@ typedef struct {
   int has_C;
   int pq_m;            /* sub-spaces of a product quantiser, 0: flat lists    */
   float *CB;           /* [M][256][d / M] codebooks                          */
+  int storage;         /* ORC_F32 / ORC_F16 / ORC_U8: what flat lists keep     */
   orc_list *L;
   int64_t npool;       /* |P|: number of blocks in the central pool          */
   int64_t cur_P;       /* blocks 0..cur_P-1 have been handed out at least once */
@@ -185,11 +199,48 @@ int orc_set_centroids(orc_index *ix, const float *C) {
   return ORC_OK;
 }
 
+/* What a flat list keeps of a coordinate.  Half precision: the number is
+ * rounded to a multiple of the spacing of halves at its magnitude, 2^(e-10)
+ * for a number in [2^e, 2^(e+1)) and 2^-24 below 2^-14 (subnormal halves);
+ * rintf rounds to nearest, ties to even, and the scalings by powers of two are
+ * exact.  The largest half is 65504. */
+static float stored_value(int storage, float f) {
+  if (storage == ORC_F16) {
+    if (isnan(f) || isinf(f) || f == 0.0f) return f;
+    int e;
+    (void)frexpf(fabsf(f), &e);           /* |f| = m 2^e with m in [0.5, 1) */
+    int q = e - 11;                       /* exponent of the spacing */
+    if (q < -24) q = -24;
+    float r = ldexpf(rintf(ldexpf(f, -q)), q);
+    if (fabsf(r) > 65504.0f) r = copysignf(INFINITY, f);
+    return r;
+  }
+  if (storage == ORC_U8) {
+    if (isnan(f)) return 0.0f;
+    float r = rintf(f);
+    return r > 0.0f ? (r > 255.0f ? 255.0f : r) : 0.0f;
+  }
+  return f;
+}
+
+/* Storage of flat lists; only before the first vector is added. */
+int orc_set_storage(orc_index *ix, int storage) {
+  if (!ix || storage < ORC_F32 || storage > ORC_U8) return ORC_EINVAL;
+  if (ix->ntotal > 0 || ix->pq_m) return ORC_ESTATE;
+  ix->storage = storage;
+  return ORC_OK;
+}
+
+/* The conversion by itself: out[i] = what a list with this storage keeps of in[i]. */
+void orc_stored(int storage, int64_t n, const float *in, float *out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = stored_value(storage, in[i]);
+}
+
 /* Codebooks of a product quantiser: CB [M][256][d / M].  Only before the
  * first vector is added. */
 int orc_set_codebooks(orc_index *ix, int M, const float *CB) {
   if (!ix || !CB || M < 1 || ix->d % M != 0) return ORC_EINVAL;
-  if (ix->ntotal > 0) return ORC_ESTATE;
+  if (ix->ntotal > 0 || ix->storage != ORC_F32) return ORC_ESTATE;
   free(ix->CB);
   ix->CB = (float *)malloc((size_t)256 * ix->d * sizeof(float));
   memcpy(ix->CB, CB, (size_t)256 * ix->d * sizeof(float));
@@ -367,7 +418,9 @@ int orc_add(orc_index *ix, int64_t n, const float *Y, const int64_t *ids, const 
     list_reserve(l, ix->d, ix->pq_m, did + 1);
     l->ids[did] = ids ? ids[i] : gid + i;
     if (ix->pq_m) memcpy(l->codes + (size_t)did * ix->pq_m, codes + (size_t)i * ix->pq_m, (size_t)ix->pq_m);
-    else memcpy(l->x + (size_t)did * ix->d, Y + (size_t)i * ix->d, (size_t)ix->d * sizeof(float));
+    else
+      for (int j = 0; j < ix->d; ++j)
+        l->x[(size_t)did * ix->d + j] = stored_value(ix->storage, Y[(size_t)i * ix->d + j]);
     l->n = did + 1;
     l->online++;
   }
