@@ -46,6 +46,14 @@ enum rtams_status {
   RTAMS_ESCRATCH = -6 /* a search needed more candidate scratch than its resource and the shared reserve hold */
 };
 
+/* What a flat list keeps of each coordinate (a cheaper step towards the quantised lists: the
+ * paper stores 32-bit floats).  A vector joins the list of its nearest centroid as it is given;
+ * the list keeps, returns (rtams_list_export) and scans the converted vector.  F16: IEEE half
+ * precision, round to nearest even, overflow to infinity; d a multiple of 8.  U8: rounded to the
+ * nearest integer (ties to even) and clamped to 0..255, NaN becomes 0 — byte-valued data is kept
+ * exactly; d a multiple of 16.  Scores are fp32 arithmetic on the converted values, as for F32. */
+enum rtams_storage { RTAMS_F32 = 0, RTAMS_F16 = 1, RTAMS_U8 = 2 };
+
 typedef struct rtams_config {
   int32_t d;          /* vector dimension, multiple of 4 */
   int32_t nlist;      /* number of inverted lists / centroids */
@@ -66,6 +74,7 @@ typedef struct rtams_config {
   int32_t pq_m;          /* 0: the lists hold the vectors (IVF-Flat).  M > 0: they hold
                             product-quantiser codes, M bytes per vector (IVF-PQ): M a
                             multiple of 4, at most 64, dividing d */
+  int32_t storage;       /* rtams_storage: what flat lists keep of a vector (pq_m must be 0 for the narrow kinds) */
   size_t overflow_bytes; /* the last overflow_bytes of d_scratch are a reserve shared by all
                             stream resources (the paper's overflow chunks from a central pool,
                             Deployment Detail): a query whose candidates do not fit into what is

@@ -267,6 +267,7 @@ __global__ __launch_bounds__(256) void k_assign_refine(Dev D, int64_t n, const f
     best_s = take ? s : best_s;
     best_c = take ? c : best_c;
   }
+  if (best_c == 0x7fffffff) best_c = 0;  // no score compared (a vector with a NaN): nothing was better than the first centroid
   if (lane == 0) {
     assign[i] = best_c;
     if (reserve) did[i] = atomicAdd(&D.reserved_len[best_c], 1u);

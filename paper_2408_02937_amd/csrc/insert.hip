@@ -36,6 +36,7 @@ __global__ __launch_bounds__(256) void k_reserve(Dev D, int64_t n, int splits,
     bool better = bi < 0 || (cs != bs ? (D.metric == 0 ? cs < bs : cs > bs) : ci < bi);
     if (better) { bs = cs; bi = ci; }
   }
+  if (bi < 0) bi = 0;  // no score compared (a vector with a NaN): nothing was better than the first centroid
   assign[i] = bi;
   if (reserve) did[i] = atomicAdd(&D.reserved_len[bi], 1u);
 }
@@ -141,22 +142,33 @@ __global__ __launch_bounds__(256) void k_open(Dev D) {
   if (lane == 0) D.nblk[list] = nb_new;
 }
 
-// ---- fill: thread (vector i, chunk c) writes dimensions 4c..4c+3 of vector i
-// to its slot; the thread of chunk 0 also writes the id.
+// ---- fill: thread (vector i, chunk c) writes chunk c (16 bytes: 4 floats, 8 halves or 16 bytes)
+// of vector i to its slot; the thread of chunk 0 also writes the id.
 __global__ __launch_bounds__(256) void k_fill(Dev D, int64_t n, const float *__restrict__ Y,
                                               const int64_t *__restrict__ ids, int64_t id_base,
                                               const int32_t *__restrict__ assign,
                                               const uint32_t *__restrict__ did) {
   int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= n * D.d4) return;
-  int64_t i = t / D.d4;
-  int c = (int)(t - i * D.d4);
+  if (t >= n * D.vchunks) return;
+  int64_t i = t / D.vchunks;
+  int c = (int)(t - i * D.vchunks);
   int list = assign[i];
   uint32_t pos = did[i];
   uint32_t mid = pos / (uint32_t)D.T_m, moff = pos % (uint32_t)D.T_m;
   if (mid >= D.nblk[list]) return;  // the block could not be opened (pool exhausted)
   uint32_t b = (uint32_t)*table_entry(D, list, mid);
-  float4 v = reinterpret_cast<const float4 *>(Y)[i * D.d4 + c];
+  const float4 *y = reinterpret_cast<const float4 *>(Y) + i * D.d4;
+  float4 v;
+  if (D.storage == 1) {
+    const float4 a = y[2 * c], e = y[2 * c + 1];
+    v = make_float4(__uint_as_float(pack_halves(a.x, a.y)), __uint_as_float(pack_halves(a.z, a.w)),
+                    __uint_as_float(pack_halves(e.x, e.y)), __uint_as_float(pack_halves(e.z, e.w)));
+  } else if (D.storage == 2) {
+    v = make_float4(__uint_as_float(pack_bytes(y[4 * c])), __uint_as_float(pack_bytes(y[4 * c + 1])),
+                    __uint_as_float(pack_bytes(y[4 * c + 2])), __uint_as_float(pack_bytes(y[4 * c + 3])));
+  } else {
+    v = y[c];
+  }
   block_vecs(D, b)[vec_chunk_index(D, moff, c)] = v;
   if (c == 0) block_ids(D, b)[moff] = ids ? ids[i] : id_base + i;
 }
@@ -218,7 +230,7 @@ void launch_open(const Dev &D, hipStream_t s) {
 void launch_fill(const Dev &D, int64_t n, const float *Y, const int64_t *ids, int64_t id_base,
                  const InsertScratch &S, hipStream_t s) {
   if (n <= 0) return;
-  int64_t threads = n * D.d4;
+  int64_t threads = n * D.vchunks;
   unsigned grid = (unsigned)((threads + 255) / 256);
   hipLaunchKernelGGL(k_fill, dim3(grid), dim3(256), 0, s, D, n, Y, ids, id_base, S.assign, S.did);
 }

@@ -4,16 +4,27 @@
 
 namespace rtams {
 
-// thread (position, chunk): un-interleaves one float4 of one vector
+// thread (position, chunk): un-interleaves one 16-byte chunk of one vector and writes its 4, 8 or 16 floats
 __global__ __launch_bounds__(256) void k_export(Dev D, int list, int64_t n, int64_t *__restrict__ ids,
                                                 float *__restrict__ vecs) {
   int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= n * D.d4) return;
-  int64_t pos = t / D.d4;
-  int c = (int)(t - pos * D.d4);
+  if (t >= n * D.vchunks) return;
+  int64_t pos = t / D.vchunks;
+  int c = (int)(t - pos * D.vchunks);
   uint32_t mid = (uint32_t)(pos / D.T_m), moff = (uint32_t)(pos % D.T_m);
   uint32_t b = (uint32_t)*table_entry(D, list, mid);
-  if (vecs) reinterpret_cast<float4 *>(vecs)[pos * D.d4 + c] = block_vecs(D, b)[vec_chunk_index(D, moff, c)];
+  if (vecs) {
+    const float4 raw = block_vecs(D, b)[vec_chunk_index(D, moff, c)];
+    float4 *out = reinterpret_cast<float4 *>(vecs) + pos * D.d4;
+    if (D.storage == 1) {
+      out[2 * c] = chunk_piece<1>(raw, 0); out[2 * c + 1] = chunk_piece<1>(raw, 1);
+    } else if (D.storage == 2) {
+      out[4 * c] = chunk_piece<2>(raw, 0); out[4 * c + 1] = chunk_piece<2>(raw, 1);
+      out[4 * c + 2] = chunk_piece<2>(raw, 2); out[4 * c + 3] = chunk_piece<2>(raw, 3);
+    } else {
+      out[c] = raw;
+    }
+  }
   if (ids && c == 0) ids[pos] = block_ids(D, b)[moff];
 }
 
@@ -142,7 +153,7 @@ void launch_copy_plain(void *dst, const void *src, size_t bytes, hipStream_t s) 
 
 void launch_export(const Dev &D, int list, int64_t n, int64_t *ids, float *vecs, hipStream_t s) {
   if (n <= 0) return;
-  int64_t threads = n * D.d4;
+  int64_t threads = n * D.vchunks;
   hipLaunchKernelGGL(k_export, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, D, list, n,
                      ids, vecs);
 }

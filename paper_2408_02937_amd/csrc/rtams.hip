@@ -61,6 +61,10 @@ bool config_ok(const rtams_config *c, bool need_memory) {
   if (c->pq_m < 0 || (c->pq_m > 0 && (c->pq_m % 4 != 0 || c->pq_m > 64 || c->d % c->pq_m != 0)))
     return fail(RTAMS_EINVAL, "pq_m must be 0, or a multiple of 4 up to 64 that divides d; got %d", c->pq_m), false;
   if (c->metric != RTAMS_L2 && c->metric != RTAMS_IP) return fail(RTAMS_EINVAL, "unknown metric"), false;
+  if (c->storage < RTAMS_F32 || c->storage > RTAMS_U8 || (c->storage != RTAMS_F32 && c->pq_m > 0) ||
+      (c->storage == RTAMS_F16 && c->d % 8 != 0) || (c->storage == RTAMS_U8 && c->d % 16 != 0))
+    return fail(RTAMS_EINVAL, "storage must be F32, or F16 with d a multiple of 8, or U8 with d a multiple of 16, "
+                              "the narrow kinds with pq_m 0; got storage %d, d %d, pq_m %d", c->storage, c->d, c->pq_m), false;
   if (c->block_vecs <= 0 || c->block_vecs % kWave != 0)
     return fail(RTAMS_EINVAL, "block_vecs must be a positive multiple of 64, got %d", c->block_vecs), false;
   if (c->n_resources < 1 || c->n_resources > 256)
@@ -118,7 +122,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
   L->ids_off = kHeaderBytes;
   L->vec_off = kHeaderBytes + (uint32_t)c->block_vecs * 8u;
   // a vector takes d floats, or pq_m code bytes
-  L->block_stride = up((size_t)L->vec_off + (size_t)c->block_vecs * (c->pq_m > 0 ? (size_t)c->pq_m : (size_t)c->d * 4), kAlign);
+  L->block_stride = up((size_t)L->vec_off + (size_t)c->block_vecs * (c->pq_m > 0 ? (size_t)c->pq_m : (size_t)c->d * (c->storage == RTAMS_F16 ? 2 : c->storage == RTAMS_U8 ? 1 : 4)), kAlign);
   if (blocks < 0) {
     // per block: the block itself, 2 table entries, a free-stack entry and a mark
     size_t slack = 4 * kAlign + nl * kTableBase * 4;
@@ -362,6 +366,8 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   Dev &D = ix->dev;
   D.d = cfg->d; D.nlist = cfg->nlist; D.metric = cfg->metric; D.T_m = cfg->block_vecs;
   D.d4 = cfg->d / 4;
+  D.storage = cfg->storage;
+  D.vchunks = cfg->storage == RTAMS_F16 ? cfg->d / 8 : cfg->storage == RTAMS_U8 ? cfg->d / 16 : cfg->d / 4;
   D.groups_per_block = cfg->block_vecs / kWave;
   D.nblocks = (uint32_t)L.nblocks;
   D.slab_cap = (uint32_t)(L.slab_cap > 0xffffffffull ? 0xffffffffull : L.slab_cap);

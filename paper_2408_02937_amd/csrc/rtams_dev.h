@@ -55,6 +55,8 @@ struct Dev {
   int32_t d, nlist, metric, T_m;
   int32_t pq_m;             // 0: flat lists; M > 0: product-quantiser codes, M bytes per vector
   int32_t d4;               // d / 4
+  int32_t storage;          // what flat lists keep of a coordinate: 0 float, 1 half, 2 byte
+  int32_t vchunks;          // 16-byte chunks of a stored vector: d / 4, d / 8 or d / 16
   int32_t groups_per_block; // T_m / 64
   uint32_t nblocks;         // |P|
   uint32_t slab_cap;        // entries in the table slab
@@ -123,12 +125,42 @@ __device__ inline size_t code_word_index(const Dev &D, uint32_t moff, int c) {
 
 // Interleaved vector layout inside a block (the paper's equation for "mv",
 // re-derived for 64-wide wavefronts): vectors are taken in groups of 64; inside
-// a group, chunk c (dimensions 4c..4c+3) of the 64 vectors is contiguous, one
-// float4 per vector.  A wavefront reading chunk c of a group loads 1 KiB of
-// consecutive memory, lane = vector.
+// a group, chunk c (16 bytes: dimensions 4c..4c+3 of floats, 8c..8c+7 of halves,
+// 16c..16c+15 of bytes) of the 64 vectors is contiguous, one float4 per vector.
+// A wavefront reading chunk c of a group loads 1 KiB of consecutive memory,
+// lane = vector.
 __device__ inline size_t vec_chunk_index(const Dev &D, uint32_t moff, int c) {
   uint32_t group = moff / kWave, lane = moff % kWave;
-  return ((size_t)group * D.d4 + c) * kWave + lane;
+  return ((size_t)group * D.vchunks + c) * kWave + lane;
+}
+
+// ---- narrow storage: a 16-byte chunk holds 8 halves or 16 bytes.  piece s of a chunk is the
+// float4 of its dimensions 4s..4s+3 (2 pieces of halves, 4 of bytes).
+typedef _Float16 Half2 __attribute__((ext_vector_type(2)));
+template <int ST>
+__device__ __forceinline__ float4 chunk_piece(const float4 &raw, int s) {
+  if (ST == 1) {
+    const Half2 a = __builtin_bit_cast(Half2, s == 0 ? raw.x : raw.z);
+    const Half2 b = __builtin_bit_cast(Half2, s == 0 ? raw.y : raw.w);
+    return make_float4((float)a.x, (float)a.y, (float)b.x, (float)b.y);
+  } else if (ST == 2) {
+    const uint32_t w = __float_as_uint(s == 0 ? raw.x : s == 1 ? raw.y : s == 2 ? raw.z : raw.w);
+    return make_float4((float)(w & 255u), (float)((w >> 8) & 255u), (float)((w >> 16) & 255u), (float)(w >> 24));
+  }
+  return raw;
+}
+constexpr int pieces_of(int storage) { return storage == 1 ? 2 : storage == 2 ? 4 : 1; }
+// the conversions on the way in: IEEE round to nearest even (overflow to infinity) for halves;
+// nearest integer, ties to even, clamped to 0..255 for bytes (fmaxf drops a NaN)
+__device__ __forceinline__ uint32_t pack_halves(float lo, float hi) {
+  Half2 h;
+  h.x = (_Float16)lo;
+  h.y = (_Float16)hi;
+  return __builtin_bit_cast(uint32_t, h);
+}
+__device__ __forceinline__ uint32_t byte_of(float f) { return (uint32_t)fminf(fmaxf(__builtin_rintf(f), 0.f), 255.f); }
+__device__ __forceinline__ uint32_t pack_bytes(const float4 &v) {
+  return byte_of(v.x) | (byte_of(v.y) << 8) | (byte_of(v.z) << 16) | (byte_of(v.w) << 24);
 }
 
 }  // namespace rtams

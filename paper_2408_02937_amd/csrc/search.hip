@@ -407,12 +407,13 @@ constexpr int kNoBoundBelow = 4096;  // candidates of a query up to which the sc
 // group of 64 vectors, lane = vector, scores to LDS, radix selection there.
 // These workgroups run beside the one that groups the pairs (same launch): both
 // need only the plan, and the scan needs both.
-template <int METRIC>
+template <int METRIC, int ST>
 __device__ void sample_scores(const Dev &D, int nprobe, int max_nprobe, int q, uint32_t want_groups,
                               const float *__restrict__ Q, const SearchScratch &S, const float4 *qv,
                               uint32_t *skey) {
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-  const int d4 = D.d4;
+  const int d4 = D.vchunks;  // 16-byte chunks of a stored vector
+  constexpr int kPieces = pieces_of(ST);  // float4s of the query that go with a chunk
   const uint32_t gpb = (uint32_t)D.groups_per_block;
   const size_t group_stride = (size_t)d4 * kWave;
   // the sample is the first want_groups groups of the probed lists taken in order, nearest first
@@ -435,9 +436,15 @@ __device__ void sample_scores(const Dev &D, int nprobe, int max_nprobe, int q, u
 #pragma unroll
         for (int u = 0; u < 8; ++u) v[u] = x[(size_t)(c + u) * kWave];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) accumulate<METRIC>(acc, v[u], qv[c + u]);
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+          for (int s = 0; s < kPieces; ++s) accumulate<METRIC>(acc, chunk_piece<ST>(v[u], s), qv[(c + u) * kPieces + s]);
       }
-      for (; c < d4; ++c) accumulate<METRIC>(acc, x[(size_t)c * kWave], qv[c]);
+      for (; c < d4; ++c) {
+        const float4 v = x[(size_t)c * kWave];
+#pragma unroll
+        for (int s = 0; s < kPieces; ++s) accumulate<METRIC>(acc, chunk_piece<ST>(v, s), qv[c * kPieces + s]);
+      }
       const uint32_t v = g * kWave + lane;
       skey[(size_t)(g_first + g) * kWave + lane] =
           v < len ? key_of_float((METRIC == 0 ? acc : -acc) + 0.0f) : 0xFFFFFFFFu;
@@ -510,7 +517,7 @@ __device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, in
   // list, the more candidates a given score admits), at most kSampleMax and at most 1 MiB of
   // vectors (one workgroup reads the sample: a hot list of wide vectors would hold up the scan),
   // in whole groups
-  uint32_t cap = PQ ? (uint32_t)kSampleMax : ((1u << 20) / ((uint32_t)D.d * 4u)) & ~(uint32_t)(kWave - 1);
+  uint32_t cap = PQ ? (uint32_t)kSampleMax : ((1u << 20) / ((uint32_t)D.vchunks * 16u)) & ~(uint32_t)(kWave - 1);
   cap = cap < 512u ? 512u : (cap > (uint32_t)kSampleMax ? (uint32_t)kSampleMax : cap);
   uint32_t want = (uint32_t)k * 4u;
   const uint32_t part = S.probe_len[(size_t)q * max_nprobe] / (uint32_t)kSampleDivisor;
@@ -522,8 +529,15 @@ __device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, in
   for (int i = tid; i < (int)(want_groups * kWave); i += kGroupThreads) skey[i] = 0xFFFFFFFFu;
   __syncthreads();
   if (PQ) pq_sample_scores(D, nprobe, max_nprobe, q, want_groups, S, skey);
-  else if (D.metric == 0) sample_scores<0>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
-  else sample_scores<1>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
+  else if (D.metric == 0) {
+    if (D.storage == 1) sample_scores<0, 1>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
+    else if (D.storage == 2) sample_scores<0, 2>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
+    else sample_scores<0, 0>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
+  } else {
+    if (D.storage == 1) sample_scores<1, 1>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
+    else if (D.storage == 2) sample_scores<1, 2>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
+    else sample_scores<1, 0>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
+  }
   __syncthreads();
   // k-th smallest key of the sample; with fewer than k candidates in it, it is the worst key
   // and everything is kept
@@ -975,7 +989,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
 // items with few queries were measured: they cost a wavefront of occupancy and gain nothing.
 constexpr int prefetch_chunks(int) { return 2; }
 
-template <int METRIC, int NQ>
+template <int METRIC, int NQ, int ST>
 __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
                                           const float *__restrict__ Q, int max_nprobe, int list,
                                           uint32_t first, uint32_t g_begin, uint32_t g_count,
@@ -985,7 +999,11 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
   // where whole pairs of groups drop out; with more queries somebody is nearly always still in
   // and the branches cost more than the skipped arithmetic saves (measured: 8 queries 3 % slower).
   constexpr bool kPrune = METRIC == 0 && NQ <= 4;
-  const int d4 = D.d4;
+  // Narrow storage: a 16-byte chunk of a stored vector holds 8 halves or 16 bytes, i.e. kPieces
+  // float4s' worth of dimensions; they are widened in registers, piece by piece, and meet the
+  // matching float4 of each query.  vc chunks per stored vector, d4 float4s per query.
+  constexpr int kPieces = pieces_of(ST);
+  const int d4 = D.d4, vc = D.vchunks;
   const int lane = threadIdx.x & (kWave - 1);
   // lane i < NQ looks after query i of the item: how far its list goes, its bound, where its
   // survivor records go
@@ -1023,7 +1041,7 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
     const uint32_t have = D.nblk[list] * gpb;
     if (ngroups > have) ngroups = have;
   }
-  const size_t group_stride = (size_t)d4 * kWave;
+  const size_t group_stride = (size_t)vc * kWave;
   for (uint32_t g0 = g_begin; g0 < ngroups; g0 += 2) {
     const bool two = g0 + 1 < ngroups;  // uniform over the wavefront
     const uint32_t g1 = two ? g0 + 1 : g0;
@@ -1039,7 +1057,7 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
     // Software pipeline over the chunks, two register sets of kPrefetch chunks
     // each: while one set is being accumulated the loads of the other are in
     // flight.
-    const int d4_main = d4 & ~(2 * kPrefetch - 1);
+    const int d4_main = vc & ~(2 * kPrefetch - 1);
     if (d4_main) {
       float4 a0[kPrefetch], a1[kPrefetch], b0v[kPrefetch], b1v[kPrefetch];
       auto load_set = [&](float4 *s0, float4 *s1, int cb) {
@@ -1051,16 +1069,34 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
         __builtin_amdgcn_sched_barrier(0);  // loads are issued here, not sunk towards their use
       };
       auto use_set = [&](const float4 *s0, const float4 *s1, int cb) {
+        if (ST == 0) {
 #pragma unroll
-        for (int i = 0; i < NQ; ++i) {
-          if (kPrune && !((alive >> i) & 1u)) continue;  // uniform: this query is out for this pair of groups
+          for (int i = 0; i < NQ; ++i) {
+            if (kPrune && !((alive >> i) & 1u)) continue;  // uniform: this query is out for this pair of groups
+#pragma unroll
+            for (int u = 0; u < kPrefetch; ++u) {
+              const float4 y = qs[i * d4 + cb + u];
+              accumulate<METRIC>(acc0[i], s0[u], y);
+              accumulate<METRIC>(acc1[i], s1[u], y);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keep one query's temporaries from piling up on the next
+          }
+        } else {
 #pragma unroll
           for (int u = 0; u < kPrefetch; ++u) {
-            const float4 y = qs[i * d4 + cb + u];
-            accumulate<METRIC>(acc0[i], s0[u], y);
-            accumulate<METRIC>(acc1[i], s1[u], y);
+#pragma unroll
+            for (int s = 0; s < kPieces; ++s) {
+              const float4 x0 = chunk_piece<ST>(s0[u], s), x1 = chunk_piece<ST>(s1[u], s);
+#pragma unroll
+              for (int i = 0; i < NQ; ++i) {
+                if (kPrune && !((alive >> i) & 1u)) continue;  // uniform
+                const float4 y = qs[i * d4 + (cb + u) * kPieces + s];
+                accumulate<METRIC>(acc0[i], x0, y);
+                accumulate<METRIC>(acc1[i], x1, y);
+              }
+              __builtin_amdgcn_sched_barrier(0);  // one piece's widened values at a time
+            }
           }
-          __builtin_amdgcn_sched_barrier(0);  // keep one query's temporaries from piling up on the next
         }
       };
       load_set(a0, a1, 0);
@@ -1092,13 +1128,17 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
         use_set(b0v, b1v, c + kPrefetch);
       }
     }
-    for (int c = d4_main; c < d4 && alive != 0u; ++c) {  // dimensions beyond the last full double set
-      const float4 x0 = xa[(size_t)c * kWave], x1 = xb[(size_t)c * kWave];
+    for (int c = d4_main; c < vc && alive != 0u; ++c) {  // chunks beyond the last full double set
+      const float4 r0 = xa[(size_t)c * kWave], r1 = xb[(size_t)c * kWave];
 #pragma unroll
-      for (int i = 0; i < NQ; ++i) {
-        const float4 y = qs[i * d4 + c];
-        accumulate<METRIC>(acc0[i], x0, y);
-        accumulate<METRIC>(acc1[i], x1, y);
+      for (int s = 0; s < kPieces; ++s) {
+        const float4 x0 = chunk_piece<ST>(r0, s), x1 = chunk_piece<ST>(r1, s);
+#pragma unroll
+        for (int i = 0; i < NQ; ++i) {
+          const float4 y = qs[i * d4 + c * kPieces + s];
+          accumulate<METRIC>(acc0[i], x0, y);
+          accumulate<METRIC>(acc1[i], x1, y);
+        }
       }
     }
     // Only what is not worse than the query's bound is kept: appended to the query's survivor
@@ -1165,7 +1205,7 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
 constexpr uint32_t kXcds = 8;
 constexpr int kScanWaves = 4;
 
-template <int METRIC>
+template <int METRIC, int ST>
 __global__ __launch_bounds__(kScanWaves * kWave) void k_scan(Dev D, int max_nprobe,
                                                              const float *__restrict__ Q, SearchScratch S) {
   extern __shared__ float4 qs_all[];  // [wavefronts][kScanTileQueries][d / 4]
@@ -1184,14 +1224,14 @@ __global__ __launch_bounds__(kScanWaves * kWave) void k_scan(Dev D, int max_npro
   const uint32_t g_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)desc.w) * seg;
   switch (pairs) {
     case 0: break;
-    case 1: scan_item<METRIC, 1>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-    case 2: scan_item<METRIC, 2>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-    case 3: scan_item<METRIC, 3>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-    case 4: scan_item<METRIC, 4>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-    case 5: scan_item<METRIC, 5>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-    case 6: scan_item<METRIC, 6>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-    case 7: scan_item<METRIC, 7>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
-    default: scan_item<METRIC, 8>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 1: scan_item<METRIC, 1, ST>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 2: scan_item<METRIC, 2, ST>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 3: scan_item<METRIC, 3, ST>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 4: scan_item<METRIC, 4, ST>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 5: scan_item<METRIC, 5, ST>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 6: scan_item<METRIC, 6, ST>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    case 7: scan_item<METRIC, 7, ST>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
+    default: scan_item<METRIC, 8, ST>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
   }
 }
 
@@ -1764,10 +1804,15 @@ void launch_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const flo
   dim3 grid((unsigned)scan_grid(D, item_budget));
   const int waves = scan_waves(D);
   const size_t lds = (size_t)waves * kScanTileQueries * D.d * sizeof(float);
-  if (D.metric == 0)
-    hipLaunchKernelGGL(k_scan<0>, grid, dim3(waves * kWave), lds, s, D, max_nprobe, Q, S);
-  else
-    hipLaunchKernelGGL(k_scan<1>, grid, dim3(waves * kWave), lds, s, D, max_nprobe, Q, S);
+  const dim3 block(waves * kWave);
+  switch (D.metric * 3 + D.storage) {
+    case 0: hipLaunchKernelGGL((k_scan<0, 0>), grid, block, lds, s, D, max_nprobe, Q, S); break;
+    case 1: hipLaunchKernelGGL((k_scan<0, 1>), grid, block, lds, s, D, max_nprobe, Q, S); break;
+    case 2: hipLaunchKernelGGL((k_scan<0, 2>), grid, block, lds, s, D, max_nprobe, Q, S); break;
+    case 3: hipLaunchKernelGGL((k_scan<1, 0>), grid, block, lds, s, D, max_nprobe, Q, S); break;
+    case 4: hipLaunchKernelGGL((k_scan<1, 1>), grid, block, lds, s, D, max_nprobe, Q, S); break;
+    default: hipLaunchKernelGGL((k_scan<1, 2>), grid, block, lds, s, D, max_nprobe, Q, S); break;
+  }
 }
 
 void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,

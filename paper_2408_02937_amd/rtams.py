@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "librtams.so")
 
 L2, IP = 0, 1
 OK, EINVAL, ESTATE, EPOOL, EBUSY, EHIP, ESCRATCH = 0, -1, -2, -3, -4, -5, -6
+STORAGE = {"f32": 0, "f16": 1, "u8": 2}  # what flat lists keep of a coordinate
 _NAMES = {EINVAL: "EINVAL", ESTATE: "ESTATE", EPOOL: "EPOOL", EBUSY: "EBUSY", EHIP: "EHIP",
           ESCRATCH: "ESCRATCH"}
 
@@ -39,7 +40,7 @@ class Config(C.Structure):
                 ("d_scratch", C.c_void_p), ("scratch_bytes", C.c_size_t),
                 ("n_resources", C.c_int32), ("max_batch", C.c_int32), ("max_k", C.c_int32),
                 ("max_nprobe", C.c_int32), ("max_add_batch", C.c_int32), ("pq_m", C.c_int32),
-                ("overflow_bytes", C.c_size_t)]
+                ("storage", C.c_int32), ("overflow_bytes", C.c_size_t)]
 
 
 class Stats(C.Structure):
@@ -138,7 +139,7 @@ class Index:
                  rearrange_threshold: int = 0, n_resources: int = 8, max_batch: int = 256,
                  max_k: int = 128, max_nprobe: int = 64, max_add_batch: int = 65536,
                  candidates_per_query: int = 65536, device: str = "cuda:0", pq_m: int = 0,
-                 overflow_candidates: int = 0):
+                 overflow_candidates: int = 0, storage: str = "f32"):
         L = lib()
         self.d, self.nlist, self.block_vecs, self.pq_m = d, nlist, block_vecs, pq_m
         self.metric = {"l2": L2, "ip": IP}[metric]
@@ -146,7 +147,8 @@ class Index:
         cfg = Config(d=d, nlist=nlist, metric=self.metric, block_vecs=block_vecs,
                      rearrange_threshold=rearrange_threshold, n_resources=n_resources,
                      max_batch=max_batch, max_k=max_k, max_nprobe=min(max_nprobe, nlist),
-                     max_add_batch=max_add_batch, pq_m=pq_m)
+                     max_add_batch=max_add_batch, pq_m=pq_m, storage=STORAGE[storage])
+        self.storage = storage
         if pool_bytes is None:
             if pool_blocks is None:
                 raise ValueError("give pool_blocks or pool_bytes")

@@ -17,7 +17,7 @@ def dev(a: np.ndarray) -> torch.Tensor:
 
 
 def make_pair(w, pool_blocks=None, rearrange_threshold=0, max_batch=256, max_k=128, max_nprobe=64,
-              candidates_per_query=None, n_resources=4, max_add_batch=65536):
+              candidates_per_query=None, n_resources=4, max_add_batch=65536, storage="f32"):
     """(gpu index, oracle index) over workload w, centroids set, nothing added."""
     n_all = len(w.base) + len(w.inserts)
     if pool_blocks is None:
@@ -27,11 +27,13 @@ def make_pair(w, pool_blocks=None, rearrange_threshold=0, max_batch=256, max_k=1
     g = rtams.Index(w.d, w.nlist, w.metric, w.block_vecs, pool_blocks=pool_blocks,
                     rearrange_threshold=rearrange_threshold, n_resources=n_resources,
                     max_batch=max_batch, max_k=max_k, max_nprobe=min(max_nprobe, w.nlist),
-                    max_add_batch=max_add_batch, candidates_per_query=candidates_per_query)
+                    max_add_batch=max_add_batch, candidates_per_query=candidates_per_query, storage=storage)
     g.set_centroids(dev(w.centroids))
     o = OracleIndex(w.d, w.nlist, w.metric, w.block_vecs, rearrange_threshold=rearrange_threshold,
                     pool_blocks=pool_blocks)
     o.set_centroids(w.centroids)
+    if storage != "f32":
+        o.set_storage(storage)
     return g, o
 
 

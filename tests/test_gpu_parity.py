@@ -370,6 +370,33 @@ def test_empty_index_short_lists_and_errors():
     g.close()
 
 
+@pytest.mark.parametrize("mfma", [0, 2])
+def test_vectors_whose_scores_do_not_compare_go_to_the_first_list(mfma):
+    """A vector with a NaN coordinate has no nearest centroid: no score is better
+    than another.  Both sides then leave it with the first centroid (the running
+    best starts there and is never beaten), and every other vector of the batch is
+    placed as usual."""
+    w = workloads()["tiny-l2"]
+    print(f"[case] NaN vectors in a batch, use_mfma={mfma}", flush=True)
+    g, o = make_pair(w)
+    g.set_param("use_mfma", mfma)
+    y = w.inserts[:48].copy()
+    y[3, 5] = np.nan
+    y[17, :] = np.nan
+    y[40, 0] = np.nan
+    assert o.assign(y)[[3, 17, 40]].tolist() == [0, 0, 0]
+    assert np.array_equal(g.assign(dev(y)).cpu().numpy(), o.assign(y))
+    g.add(dev(w.base[:2000])); o.add(w.base[:2000])
+    g.add(dev(y)); o.add(y)
+    torch.cuda.synchronize()
+    assert g.poll_error() == 0
+    g.validate()
+    assert np.array_equal(g.list_sizes(), o.list_sizes())
+    ids = g.list_export(0)[0].cpu().numpy()
+    assert {2003, 2017, 2040} <= set(ids.tolist())
+    g.close()
+
+
 def test_pool_exhaustion_is_refused_before_anything_is_enqueued():
     d, nlist, T = 4, 2, 64
     C = np.eye(2, 4, dtype=np.float32)

@@ -88,3 +88,20 @@ def test_bench_refuses_more_than_one_gpu():
     import subprocess, sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+@pytest.mark.parametrize("bad", [dict(storage=3), dict(storage=-1), dict(storage=1, d=36), dict(storage=2, d=40),
+                                 dict(storage=1, pq_m=8), dict(storage=2, pq_m=8)])
+def test_bad_storage_is_refused_on_the_host(bad):
+    """Halves need d % 8 == 0, bytes d % 16 == 0, and quantised lists keep codes, not vectors."""
+    L = rtams.lib()
+    assert L.rtams_pool_bytes_for(C.byref(cfg(**bad)), 10) == 0
+    assert b"storage" in L.rtams_last_error()
+
+
+def test_narrow_storage_shrinks_the_blocks():
+    L = rtams.lib()
+    stride = lambda c: (L.rtams_pool_bytes_for(C.byref(c), 2010) - L.rtams_pool_bytes_for(C.byref(c), 1010)) // 1000
+    f32, f16, u8 = (stride(cfg(storage=s)) for s in (0, 1, 2))
+    # header 128 + 64 ids x 8 + 64 vectors x 32 dimensions x {4, 2, 1} bytes, padded to 256, plus 16 bytes of tables
+    assert (f32, f16, u8) == (8960 + 16, 4864 + 16, 2816 + 16)    # 8832, 4736, 2688 padded
