@@ -54,7 +54,7 @@ def main() -> int:
     ap.add_argument("--pq-m", type=int, default=0,
                     help="with --study pq: only this number of sub-spaces, and only the --batch query batch")
     ap.add_argument("--shape", type=int, default=0, help="with --study shapes: only this configuration (3, 4 or 5)")
-    ap.add_argument("--study", choices=["rearrange", "blocksize", "pq", "shapes", "mixed", "growth"],
+    ap.add_argument("--study", choices=["rearrange", "blocksize", "pq", "storage", "shapes", "mixed", "growth"],
                     help="run one of the side studies instead of the benchmark (one JSON line each)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -80,7 +80,7 @@ def main() -> int:
     if args.study:
         from paper_2408_02937_amd import studies
         fn = {"rearrange": studies.rearrangement_study, "blocksize": studies.block_size_sweep,
-              "pq": studies.pq_study, "shapes": studies.shape_study,
+              "pq": studies.pq_study, "storage": studies.storage_study, "shapes": studies.shape_study,
               "mixed": studies.mixed_load_study, "growth": studies.growth_study}[args.study]
         if args.study == "pq" and args.pq_m:
             print(json.dumps(fn(scale=args.scale, iters=args.latency_iters, ms=(args.pq_m,), batches=(args.batch,))))

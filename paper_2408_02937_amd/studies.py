@@ -282,6 +282,82 @@ def pq_study(scale: float = 1.0, ms=(16, 32), iters: int = 200, batches=(1, 10, 
             "codebooks": "256 sampled sub-vectors per sub-space (untrained)", "rows": rows}
 
 
+def storage_study(scale: float = 1.0, iters: int = 200, batches=(1, 10, 32, 256)) -> dict:
+    """Flat lists that keep floats, halves or bytes: memory, insertion rate, search latency and the scan's
+    rate in bytes of what the lists hold.  Two data sets: configuration 2 (byte-valued, so all three kinds
+    return the same answers) and a fifth of configuration 3 (unit vectors, inner products; floats and halves)."""
+    dev = torch.device("cuda:0")
+    elem = {"f32": 4, "f16": 2, "u8": 1}
+    out = []
+    for idx, frac, kinds in ((2, 1.0, ("f32", "f16", "u8")), (3, 0.2, ("f32", "f16"))):
+        w = synth.config(idx, scale=frac * scale)
+        base, cents, queries, inserts = (_to_dev(a, dev) for a in (w.base, w.centroids, w.queries, w.inserts))
+        n_all = len(w.base) + 2 * len(w.inserts)
+        blocks = n_all // w.block_vecs + 2 * w.nlist + 64
+        cand = max(65536, 4 * w.nprobe * (len(w.base) // w.nlist + w.block_vecs))
+        ds, ss = torch.cuda.Stream(dev), torch.cuda.Stream(dev)
+        nq_recall = min(1024, len(w.queries))
+        exact = None
+        rows = []
+        for kind in kinds:
+            g = rtams.Index(w.d, w.nlist, w.metric, w.block_vecs, pool_blocks=blocks, n_resources=8, max_batch=256,
+                            max_k=128, max_nprobe=64, max_add_batch=65536, candidates_per_query=cand, storage=kind)
+            g.set_centroids(cents, stream=ds)
+            t0 = time.perf_counter()
+            g.add(base, stream=ds)
+            ds.synchronize()
+            bulk_s = time.perf_counter() - t0
+            st = g.pool_stats()
+            got = []
+            for o in range(0, nq_recall, 256):
+                ids = g.search(queries[o:min(o + 256, nq_recall)], w.k, w.nprobe, stream=ss)[1]
+                ss.synchronize()
+                got.append(ids.cpu().numpy())
+            got = np.concatenate(got)
+            if exact is None:
+                exact = got
+            share = sum(len(np.intersect1d(got[i], exact[i])) for i in range(len(got))) / (len(got) * w.k)
+            row = {"storage": kind, "bytes_per_vector_in_lists": w.d * elem[kind] + 8,
+                   "block_bytes": int(st.block_bytes), "blocks_in_use": int(st.blocks_in_use),
+                   "list_bytes": int(st.block_bytes) * int(st.blocks_in_use),
+                   "bulk_load_vectors_per_s": len(w.base) / bulk_s, "share_of_f32_topk_returned": share,
+                   "search": {}}
+            sizes_now = g.list_sizes()
+            for bs in batches:
+                g.scan_time(reset=True)
+                g.set_param("profile_scan", 1)
+                lat = _search_latencies(g, queries, bs, w.k, w.nprobe, iters, ss, dev)
+                g.set_param("profile_scan", 0)
+                ms_, cnt = g.scan_time(reset=True)
+                nb = max(len(queries) // bs, 1)
+                union = []  # bytes of the union of the probed lists, as stored
+                for i in range(min(16, nb)):
+                    pl = np.unique(g.probe(queries[i * bs:(i + 1) * bs], w.nprobe).cpu().numpy())
+                    union.append(float(sizes_now[pl].sum()) * w.d * elem[kind])
+                scan_ms = ms_ / max(cnt, 1)
+                gbps = float(np.mean(union)) / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else None
+                row["search"][str(bs)] = {"p50_ms": _p(lat, 50), "p99_ms": _p(lat, 99),
+                                          "qps": bs / (np.mean(lat) * 1e-3), "scan_ms": scan_ms,
+                                          "scan_bytes_per_launch": float(np.mean(union)), "scan_GBps": gbps,
+                                          "frac_of_hbm_peak": gbps / 8000.0 if gbps else None}
+            ib = w.insert_batch
+            lat = []
+            for i in range(iters + 10):
+                t0 = time.perf_counter()
+                g.add(inserts[(i % (len(inserts) // ib)) * ib:(i % (len(inserts) // ib)) * ib + ib], stream=ds)
+                ds.synchronize()
+                if i >= 10:
+                    lat.append((time.perf_counter() - t0) * 1e3)
+            row["insert_batch_p50_ms"] = _p(lat, 50)
+            g.validate()
+            assert g.poll_error() == 0
+            rows.append(row)
+            g.close()
+        out.append({"workload": w.name, "metric": w.metric, "d": w.d, "n_base": len(w.base), "k": w.k,
+                    "nprobe": w.nprobe, "insert_batch": w.insert_batch, "rows": rows})
+    return {"study": "storage_of_flat_lists", "sets": out}
+
+
 def shape_study(scale: float = 1.0, iters: int = 100, which=(3, 4, 5)) -> dict:
     """scale 1.0 stands for a fifth of configuration 3's and 4's base sets (2 M x 96, 1 M x 768) and a
     tenth of configuration 5's (2 M x 256): the host has to draw them."""

@@ -36,6 +36,20 @@ def test_pq_study_small():
     assert r["search"]["256"]["scan_ms"] > 0
 
 
+def test_storage_study_small():
+    from paper_2408_02937_amd import studies
+    print("[case] storage study, scale 0.03", flush=True)
+    out = studies.storage_study(scale=0.03, iters=5, batches=(1, 32))
+    byte_set, unit_set = out["sets"]
+    assert [r["storage"] for r in byte_set["rows"]] == ["f32", "f16", "u8"]
+    assert all(r["share_of_f32_topk_returned"] == 1.0 for r in byte_set["rows"])   # byte values survive both
+    sizes = [r["block_bytes"] for r in byte_set["rows"]]
+    assert sizes[0] > sizes[1] > sizes[2]
+    assert unit_set["rows"][1]["share_of_f32_topk_returned"] > 0.9
+    for r in byte_set["rows"] + unit_set["rows"]:
+        assert r["search"]["32"]["scan_ms"] > 0
+
+
 def test_shape_study_small():
     from paper_2408_02937_amd import studies
     print("[case] shape study, scale 0.02", flush=True)
