@@ -185,7 +185,8 @@ int rtams_list_size(rtams_index *ix, int32_t list, int64_t *out);
 int rtams_list_info(rtams_index *ix, int32_t list, int64_t *blocks, int64_t *runs,
                     int64_t *online);
 /* Logical content of one list in list order: d_ids [cap] and d_vecs [cap][d]
- * row-major (either may be NULL); *n_out = list length; EINVAL if cap is too small. */
+ * row-major fp32 (either may be NULL; with F16 or U8 storage the vectors as the
+ * list keeps them, widened); *n_out = list length; EINVAL if cap is too small. */
 int rtams_list_export(rtams_index *ix, int32_t list, int64_t cap, int64_t *d_ids, float *d_vecs,
                       int64_t *n_out, void *hip_stream);
 /* Physical block numbers of the list's chain, in logical order (host array). */
