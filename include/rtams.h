@@ -76,10 +76,13 @@ typedef struct rtams_config {
                             multiple of 4, at most 64, dividing d */
   int32_t storage;       /* rtams_storage: what flat lists keep of a vector (pq_m must be 0 for the narrow kinds) */
   size_t overflow_bytes; /* the last overflow_bytes of d_scratch are a reserve shared by all
-                            stream resources (the paper's overflow chunks from a central pool,
-                            Deployment Detail): a query whose candidates do not fit into what is
-                            left of its request's own slice gets room there until its request
-                            is finished; 0: no reserve */
+                            stream resources, cut into chunks of equal size (the paper's overflow
+                            chunks from a central pool, Deployment Detail).  A request whose
+                            queries' candidates do not all fit into its own slice leases one
+                            free chunk for the rest and returns it when it is finished; queries
+                            that fit neither the slice nor the chunk (or find every chunk
+                            leased) come back empty and raise ESCRATCH.  0: no reserve */
+  int32_t overflow_chunks; /* how many chunks, 1..32; 0 means 4 */
 } rtams_config;
 
 typedef struct rtams_stats {
@@ -94,9 +97,9 @@ typedef struct rtams_stats {
   double utilisation;       /* blocks_in_use / blocks_total; the paper alerts above 0.9 */
   int64_t lists_exceeding;  /* lists for which Exceed() currently holds */
   int64_t table_entries_used, table_entries_total;
-  int64_t overflow_total;   /* candidate entries the shared scratch reserve holds */
-  int64_t overflow_in_use;  /* ... of which handed out to queries of requests not yet finished */
-  int64_t overflow_users;   /* such queries */
+  int64_t overflow_chunks;         /* chunks of the shared scratch reserve */
+  int64_t overflow_chunk_entries;  /* candidate entries one chunk holds */
+  int64_t overflow_chunks_leased;  /* chunks held by requests not yet finished */
 } rtams_stats;
 
 /* Bytes of pool needed for `blocks` blocks under this configuration (d_pool and
@@ -107,9 +110,9 @@ size_t rtams_pool_bytes_for(const rtams_config *cfg, int64_t blocks);
  * queries may score `candidates_per_query` list entries per query (8 bytes
  * per entry: key and position of those that survive the pruning bound, with
  * room for all).  A request whose queries have more candidates than that in
- * total takes the rest from the shared reserve (overflow_bytes: 256 bytes plus
- * 8 per entry), and fails with ESCRATCH (rtams_poll_error) for the queries
- * that fit neither. */
+ * total leases a chunk of the shared reserve for the rest (overflow_bytes: 256
+ * bytes plus 8 per entry, over overflow_chunks chunks), and fails with ESCRATCH
+ * (rtams_poll_error) for the queries that fit neither. */
 size_t rtams_scratch_bytes_for(const rtams_config *cfg, int64_t candidates_per_query);
 
 /* Creates the index over caller-owned device memory (both regions 256-byte
@@ -205,9 +208,17 @@ int rtams_probe(rtams_index *ix, int64_t nq, const float *d_queries, int32_t npr
 int rtams_assign(rtams_index *ix, int64_t n, const float *d_vecs, int32_t *d_out,
                  void *hip_stream);
 
-/* Sticky asynchronous error raised by a kernel (pool overflow, scratch
- * overflow); RTAMS_OK if none.  Does not synchronise. */
+/* Sticky asynchronous error raised by a kernel; RTAMS_OK if none.  Does not
+ * synchronise.  EPOOL (a batch found the pool exhausted on the device: the batch
+ * was dropped as a whole and the index takes no further vectors) comes first
+ * and stays.  ESCRATCH (some query of some search had more candidates than its
+ * slice and the reserve could take: that query came back empty) concerns
+ * searches only, inserts and later searches go on as usual; it stays until
+ * rtams_clear_error. */
 int rtams_poll_error(rtams_index *ix);
+/* Forgets an ESCRATCH (not an EPOOL).  Synchronous; call it when no search is
+ * in flight, or a failure being raised at that moment may be lost. */
+int rtams_clear_error(rtams_index *ix);
 const char *rtams_last_error(void);
 /* Codes of a product-quantised list in list order: d_ids [cap] int64 (or NULL),
  * d_codes [cap][pq_m] bytes (or NULL), *n_out = entries of the list (at most

@@ -140,7 +140,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
 }
 
 struct ScratchLayout {
-  size_t scores, approx, probe_list, probe_len, probe_off, qbase, qtotal, bound, rec_cnt, cursor, lut, records, fixed;
+  size_t scores, approx, probe_list, probe_len, probe_off, qbase, qtotal, bound, rec_cnt, cursor, req_words, lut, records, fixed;
   size_t list_cnt, pair_start, pair_slot, grouped, plist, pistart, tile_desc, queues, item_cap;
 };
 
@@ -159,6 +159,7 @@ void lay_out_scratch(const rtams_config *c, ScratchLayout *S) {
   S->bound = take(mb * 4);
   S->rec_cnt = take(mb * 4);
   S->cursor = take(8);
+  S->req_words = take(16);  // the request's chunk of the shared reserve: chunk, finished workgroups, cursor
   // list_cnt and the queue heads are cleared together at the start of every request
   S->list_cnt = take((size_t)c->nlist * 4);
   S->queues = take(sizeof(ScanQueues));
@@ -212,8 +213,9 @@ struct rtams_index {
   std::atomic<int64_t> scan_max_items{32768};    // ... and per request
   std::atomic<int64_t> profile_scan{0};
   bool has_codebooks = false;
-  unsigned long long *ovf_word = nullptr;  // device: state of the shared scratch reserve
-  unsigned long long ovf_cap = 0;
+  uint32_t *ovf_leased = nullptr;  // device: which chunks of the shared scratch reserve are leased
+  uint32_t ovf_chunks = 0;
+  unsigned long long ovf_chunk_cap = 0;
   std::atomic<int64_t> ordered_add{0};  // positions inside a list in the order of the batch instead of arrival order
   std::atomic<int64_t> use_mfma{1};  // matrix-core filter in front of the exact coarse arithmetic
   std::mutex prof_mutex;
@@ -353,6 +355,8 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   ScratchLayout SL;
   lay_out_scratch(cfg, &SL);
   if (cfg->overflow_bytes > cfg->scratch_bytes) return fail(RTAMS_EINVAL, "overflow_bytes exceeds scratch_bytes");
+  if (cfg->overflow_chunks < 0 || cfg->overflow_chunks > kMaxOverflowChunks)
+    return fail(RTAMS_EINVAL, "overflow_chunks must be in 0..%d", kMaxOverflowChunks);
   size_t slice = (cfg->scratch_bytes - cfg->overflow_bytes) / (size_t)cfg->n_resources / kAlign * kAlign;
   if (slice < SL.fixed + kAlign)
     return fail(RTAMS_EINVAL, "scratch slice of %zu bytes is smaller than its fixed part %zu", slice,
@@ -436,14 +440,20 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   if (!ix->res) return bail(fail(RTAMS_EINVAL, "out of host memory"));
   ix->n_res = cfg->n_resources;
   char *sb = static_cast<char *>(cfg->d_scratch);
-  // the shared reserve behind the slices: one word, then two arrays of equal length
+  // the shared reserve behind the slices: the lease words (256 bytes), then two arrays of equal length,
+  // each cut into overflow_chunks chunks
   char *ovf = sb + (size_t)cfg->n_resources * slice;
-  const size_t ovf_bytes = cfg->overflow_bytes >= 3 * kAlign ? cfg->scratch_bytes - (size_t)cfg->n_resources * slice : 0;
-  const unsigned long long ovf_cap = ovf_bytes ? (ovf_bytes - kAlign) / (2 * kAlign) * (kAlign / 4) : 0;
-  if (ovf_cap >> kOverflowShift) return bail(fail(RTAMS_EINVAL, "overflow_bytes too large"));
-  if (ovf_cap && hipMemset(ovf, 0, kAlign) != hipSuccess) return bail(fail(RTAMS_EHIP, "hipMemset of the scratch reserve failed"));
-  ix->ovf_word = ovf_cap ? reinterpret_cast<unsigned long long *>(ovf) : nullptr;
-  ix->ovf_cap = ovf_cap;
+  const uint32_t ovf_chunks = cfg->overflow_bytes > 0 ? (uint32_t)(cfg->overflow_chunks > 0 ? cfg->overflow_chunks : 4) : 0u;
+  const size_t ovf_bytes = ovf_chunks ? cfg->scratch_bytes - (size_t)cfg->n_resources * slice : 0;
+  // entries per chunk: what is left after the lease words, over two arrays and the chunks, in whole 256-byte units
+  const unsigned long long ovf_chunk_cap =
+      ovf_bytes > kAlign ? (ovf_bytes - kAlign) / (2 * kAlign * ovf_chunks) * (kAlign / 4) : 0;
+  if (ovf_chunks && ovf_chunk_cap == 0)
+    return bail(fail(RTAMS_EINVAL, "overflow_bytes %zu holds no chunk (%u chunks asked for)", cfg->overflow_bytes, ovf_chunks));
+  if (ovf_chunks && hipMemset(ovf, 0, kAlign) != hipSuccess) return bail(fail(RTAMS_EHIP, "hipMemset of the scratch reserve failed"));
+  ix->ovf_leased = ovf_chunks ? reinterpret_cast<uint32_t *>(ovf) : nullptr;
+  ix->ovf_chunks = ovf_chunks;
+  ix->ovf_chunk_cap = ovf_chunk_cap;
   for (int r = 0; r < ix->n_res; ++r) {
     char *p = sb + (size_t)r * slice;
     SearchScratch &S = ix->res[r].s;
@@ -471,10 +481,15 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
     S.cand_cap = (slice - SL.fixed) / (2 * kAlign) * (kAlign / 4);
     S.rec_key = reinterpret_cast<uint32_t *>(p + SL.records);
     S.rec_pos = S.rec_key + S.cand_cap;
-    S.ovf_word = ix->ovf_word;
-    S.ovf_cap = ovf_cap;
+    S.ovf_leased = ix->ovf_leased;
+    S.ovf_chunks = ovf_chunks;
+    S.ovf_chunk_cap = ovf_chunk_cap;
     S.ovf_key = reinterpret_cast<uint32_t *>(ovf + kAlign);
-    S.ovf_pos = S.ovf_key + ovf_cap;
+    S.ovf_pos = S.ovf_key + ovf_chunk_cap * ovf_chunks;
+    S.req_chunk = reinterpret_cast<uint32_t *>(p + SL.req_words);
+    S.req_done = S.req_chunk + 1;
+    S.req_cursor = reinterpret_cast<unsigned long long *>(p + SL.req_words + 8);
+    if (hipMemset(p + SL.req_words, 0, 16) != hipSuccess) return bail(fail(RTAMS_EHIP, "hipMemset of the scratch failed"));
     if (hipEventCreateWithFlags(&ix->res[r].done, hipEventDisableTiming) != hipSuccess ||
         hipEventCreate(&ix->res[r].t0) != hipSuccess || hipEventCreate(&ix->res[r].t1) != hipSuccess)
       return bail(fail(RTAMS_EHIP, "hipEventCreate failed"));
@@ -836,12 +851,12 @@ int rtams_pool_stats(rtams_index *ix, rtams_stats *out) {
   out->lists_exceeding = c.exceed_lists;
   out->table_entries_used = c.slab_cur;
   out->table_entries_total = (int64_t)ix->lay.slab_cap;
-  out->overflow_total = (int64_t)ix->ovf_cap;
-  if (ix->ovf_word) {  // as of now: searches in flight on other streams may hold room
-    unsigned long long w = 0;
-    HIP_TRY(hipMemcpy(&w, ix->ovf_word, 8, hipMemcpyDeviceToHost));
-    out->overflow_in_use = (int64_t)(w & ((1ull << kOverflowShift) - 1ull));
-    out->overflow_users = (int64_t)(w >> kOverflowShift);
+  out->overflow_chunks = ix->ovf_chunks;
+  out->overflow_chunk_entries = (int64_t)ix->ovf_chunk_cap;
+  if (ix->ovf_leased) {  // as of now: searches in flight on other streams may hold chunks
+    uint32_t leased[kMaxOverflowChunks];
+    HIP_TRY(hipMemcpy(leased, ix->ovf_leased, sizeof(uint32_t) * ix->ovf_chunks, hipMemcpyDeviceToHost));
+    for (uint32_t e = 0; e < ix->ovf_chunks; ++e) out->overflow_chunks_leased += leased[e] != 0;
   }
   ix->avail_lb = out->blocks_total - out->blocks_in_use;
   return RTAMS_OK;
@@ -872,7 +887,16 @@ int rtams_validate(rtams_index *ix, void *hip_stream) {
 
 int rtams_poll_error(rtams_index *ix) {
   if (!ix) return RTAMS_EINVAL;
-  return ix->mirror->error;
+  const int32_t e = ix->mirror->error;  // the pool's state first: it is the one that stays
+  return e ? e : ix->mirror->search_error;
+}
+
+int rtams_clear_error(rtams_index *ix) {
+  if (!ix) return fail(RTAMS_EINVAL, "NULL argument");
+  const int32_t zero = 0;
+  HIP_TRY(hipMemcpy(&ix->dev.ctrl->search_error, &zero, sizeof(zero), hipMemcpyHostToDevice));
+  ix->mirror->search_error = 0;
+  return RTAMS_OK;
 }
 
 int rtams_scan_time(rtams_index *ix, double *ms_sum, int64_t *launches, int reset) {

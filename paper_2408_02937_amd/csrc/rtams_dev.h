@@ -39,7 +39,8 @@ struct Ctrl {
   unsigned long long ntotal; // vectors visible
   uint32_t max_len;          // longest visible list
   uint32_t cnorm_max_bits;   // largest squared centroid norm, as float bits
-  uint32_t pad3[26];
+  int32_t search_error;      // rtams_status raised by a kernel of a search (scratch too small): inserts do not look at it
+  uint32_t pad3[25];
 };
 
 // Words the device writes straight into pinned host memory, so the host can
@@ -48,7 +49,7 @@ struct HostMirror {
   volatile int32_t error;
   volatile uint32_t exceed_lists;
   volatile uint32_t max_len;
-  volatile uint32_t pad;
+  volatile int32_t search_error;
 };
 
 struct Dev {

@@ -43,15 +43,20 @@ struct SearchScratch {
   uint32_t *rec_key;    // survivors: key of the score (smaller is better) ...
   uint32_t *rec_pos;    // ... and position among the query's candidates
   unsigned long long cand_cap;  // entries of each of the two arrays
-  // the reserve shared by all resources: a query whose candidates do not fit into the slice gets its
-  // room here (bit 63 of its qbase says so) until its selection has finished
-  unsigned long long *ovf_word; // queries holding room << 40 | entries handed out (back to 0 when nobody holds any)
-  uint32_t *ovf_key, *ovf_pos;
-  unsigned long long ovf_cap;   // entries of each of the two arrays, below 2^40
+  // The reserve shared by all resources, cut into chunks of equal size.  A request whose queries do not
+  // all fit into the slice leases ONE chunk (the first query in need takes it, the others share it);
+  // queries placed there carry bit 63 in their qbase; the request's last selection workgroup returns it.
+  uint32_t *ovf_leased;         // [ovf_chunks] central: 0 free, 1 leased
+  uint32_t ovf_chunks;
+  unsigned long long ovf_chunk_cap;  // entries of a chunk (in each of the two arrays)
+  uint32_t *ovf_key, *ovf_pos;  // central: [ovf_chunks * ovf_chunk_cap] each
+  uint32_t *req_chunk;          // this resource's request: 0 none, 1 + the chunk it holds
+  uint32_t *req_done;           // selection workgroups of the request that have finished
+  unsigned long long *req_cursor;  // entries of the chunk handed out to the request's queries
 };
 
 constexpr unsigned long long kInOverflow = 1ull << 63;  // flag in SearchScratch::qbase
-constexpr int kOverflowShift = 40;
+constexpr int kMaxOverflowChunks = 32;
 
 constexpr int kScanTileQueries = 8;  // queries that share one pass over a list
 

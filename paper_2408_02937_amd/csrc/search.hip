@@ -27,29 +27,38 @@ __device__ inline uint32_t *rec_keys_of(const SearchScratch &S, unsigned long lo
 __device__ inline uint32_t *rec_poss_of(const SearchScratch &S, unsigned long long qbase) {
   return (qbase & kInOverflow) ? S.ovf_pos + (qbase & ~kInOverflow) : S.rec_pos + qbase;
 }
-// Room for `want` entries from the shared reserve (one thread): the start, flagged, or ~0 when it does
-// not have that much left.  The reserve is a bump pointer that falls back to zero when the last
-// holder lets go: users << 40 | entries handed out, moved by compare-and-swap.
+// Room for `want` entries in the request's chunk of the shared reserve (called by one thread per
+// query): the start, flagged, or ~0.  The first query of a request that needs it leases a free chunk
+// and installs it for the request; one that loses that race to a sibling hands its chunk straight
+// back and shares the sibling's.  Nothing here waits for anybody.
 __device__ inline unsigned long long overflow_take(const SearchScratch &S, unsigned long long want) {
-  if (!S.ovf_word) return ~0ull;
-  const unsigned long long mask = (1ull << kOverflowShift) - 1ull;
-  unsigned long long w = __hip_atomic_load(S.ovf_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  for (;;) {  // ends: every failed exchange means another thread's succeeded
-    const unsigned long long used = w & mask;
-    if (used + want > S.ovf_cap) return ~0ull;
-    const unsigned long long seen = atomicCAS(S.ovf_word, w, (((w >> kOverflowShift) + 1ull) << kOverflowShift) | (used + want));
-    if (seen == w) return kInOverflow | used;
-    w = seen;
-  }
+  if (S.ovf_chunks == 0 || want > S.ovf_chunk_cap) return ~0ull;
+  uint32_t c = __hip_atomic_load(S.req_chunk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (uint32_t e = 0; e < S.ovf_chunks && c == 0; ++e)
+    if (atomicCAS(&S.ovf_leased[e], 0u, 1u) == 0u) {
+      const uint32_t seen = atomicCAS(S.req_chunk, 0u, e + 1u);
+      if (seen == 0u) c = e + 1u;
+      else { atomicExch(&S.ovf_leased[e], 0u); c = seen; }
+    }
+  if (c == 0) c = __hip_atomic_load(S.req_chunk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // a sibling may have got the last one
+  if (c == 0) return ~0ull;  // every chunk is out
+  const unsigned long long off = atomicAdd(S.req_cursor, want);
+  if (off + want > S.ovf_chunk_cap) return ~0ull;
+  return kInOverflow | ((unsigned long long)(c - 1u) * S.ovf_chunk_cap + off);
 }
-__device__ inline void overflow_give_back(const SearchScratch &S) {
-  const unsigned long long mask = (1ull << kOverflowShift) - 1ull;
-  unsigned long long w = __hip_atomic_load(S.ovf_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  for (;;) {
-    const unsigned long long users = (w >> kOverflowShift) - 1ull;
-    const unsigned long long seen = atomicCAS(S.ovf_word, w, users ? (users << kOverflowShift) | (w & mask) : 0ull);
-    if (seen == w) return;
-    w = seen;
+// Every selection workgroup of a request reports here when it has read its last record; the last
+// one returns the request's chunk, if it holds one, and resets the request's words.
+__device__ inline void overflow_request_done(const SearchScratch &S, uint32_t workgroups) {
+  if (S.ovf_chunks == 0) return;
+  __threadfence();
+  if (atomicAdd(S.req_done, 1u) + 1u != workgroups) return;
+  const uint32_t c = __hip_atomic_load(S.req_chunk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(S.req_done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(S.req_cursor, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (c) {
+    __hip_atomic_store(S.req_chunk, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __threadfence();
+    atomicExch(&S.ovf_leased[c - 1u], 0u);
   }
 }
 
@@ -364,8 +373,8 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
     }
     if (tot == ~0ull) {  // not enough candidate scratch for this query
       base = 0;
-      atomicCAS(&D.ctrl->error, 0, -6);
-      D.mirror->error = -6;
+      atomicCAS(&D.ctrl->search_error, 0, -6);
+      D.mirror->search_error = -6;
       tot = 0;
       for (int p = 0; p < nprobe; ++p) { plen[p] = 0; poff[p] = 0; }
     }
@@ -872,8 +881,8 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
     if (tid == 0) {
       Qs->seg_groups = fits ? seg : 0u;
       if (!fits) {  // more tiles than the request's item descriptors hold: nothing is scanned, and the caller is told
-        atomicCAS(&D.ctrl->error, 0, -6);
-        D.mirror->error = -6;
+        atomicCAS(&D.ctrl->search_error, 0, -6);
+        D.mirror->search_error = -6;
       }
     }
     // where the pairs and the items of every probed list start
@@ -1739,9 +1748,8 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
       out_ids[o] = -1;
     }
   }
-  // the records are not looked at any more (the selection ended with a barrier): room taken from
-  // the shared reserve goes back
-  if ((base & kInOverflow) && threadIdx.x == 0) overflow_give_back(S);
+  // the records are not looked at any more (the selection ended with a barrier)
+  if (threadIdx.x == 0) overflow_request_done(S, gridDim.x);
 }
 
 // ---------------------------------------------------------------- launchers

@@ -28,7 +28,7 @@ SYMBOLS = [
     "rtams_set_centroids", "rtams_add", "rtams_search", "rtams_rearrange", "rtams_ntotal",
     "rtams_list_size", "rtams_list_info", "rtams_list_export", "rtams_list_chain",
     "rtams_list_sizes", "rtams_pool_stats", "rtams_validate", "rtams_probe", "rtams_assign",
-    "rtams_poll_error", "rtams_last_error", "rtams_set_param", "rtams_scan_time",
+    "rtams_poll_error", "rtams_clear_error", "rtams_last_error", "rtams_set_param", "rtams_scan_time",
     "rtams_copy_plain", "rtams_read_plain", "rtams_set_codebooks", "rtams_list_export_codes",
 ]
 
@@ -40,7 +40,7 @@ class Config(C.Structure):
                 ("d_scratch", C.c_void_p), ("scratch_bytes", C.c_size_t),
                 ("n_resources", C.c_int32), ("max_batch", C.c_int32), ("max_k", C.c_int32),
                 ("max_nprobe", C.c_int32), ("max_add_batch", C.c_int32), ("pq_m", C.c_int32),
-                ("storage", C.c_int32), ("overflow_bytes", C.c_size_t)]
+                ("storage", C.c_int32), ("overflow_bytes", C.c_size_t), ("overflow_chunks", C.c_int32)]
 
 
 class Stats(C.Structure):
@@ -49,8 +49,8 @@ class Stats(C.Structure):
                 ("blocks_in_use", C.c_int64), ("block_bytes", C.c_int64),
                 ("pool_bytes", C.c_int64), ("meta_bytes", C.c_int64), ("utilisation", C.c_double),
                 ("lists_exceeding", C.c_int64), ("table_entries_used", C.c_int64),
-                ("table_entries_total", C.c_int64), ("overflow_total", C.c_int64),
-                ("overflow_in_use", C.c_int64), ("overflow_users", C.c_int64)]
+                ("table_entries_total", C.c_int64), ("overflow_chunks", C.c_int64),
+                ("overflow_chunk_entries", C.c_int64), ("overflow_chunks_leased", C.c_int64)]
 
 
 class RtamsError(RuntimeError):
@@ -94,6 +94,7 @@ def lib():
         L.rtams_probe.argtypes = [vp, i64, vp, i32, vp, vp]
         L.rtams_assign.argtypes = [vp, i64, vp, vp, vp]
         L.rtams_poll_error.argtypes = [vp]
+        L.rtams_clear_error.argtypes = [vp]
         L.rtams_last_error.restype = C.c_char_p
         L.rtams_set_param.argtypes = [vp, C.c_char_p, i64]
         L.rtams_scan_time.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), C.c_int]
@@ -139,7 +140,7 @@ class Index:
                  rearrange_threshold: int = 0, n_resources: int = 8, max_batch: int = 256,
                  max_k: int = 128, max_nprobe: int = 64, max_add_batch: int = 65536,
                  candidates_per_query: int = 65536, device: str = "cuda:0", pq_m: int = 0,
-                 overflow_candidates: int = 0, storage: str = "f32"):
+                 overflow_candidates: int = 0, overflow_chunks: int = 4, storage: str = "f32"):
         L = lib()
         self.d, self.nlist, self.block_vecs, self.pq_m = d, nlist, block_vecs, pq_m
         self.metric = {"l2": L2, "ip": IP}[metric]
@@ -160,13 +161,16 @@ class Index:
             raise RtamsError(EINVAL, "scratch_bytes_for", L.rtams_last_error().decode())
         # caller-owned device memory: one pool, one scratch area
         self.pool = torch.empty(pool_bytes, dtype=torch.uint8, device=self.device)
-        # the reserve shared by all resources: a word (256 bytes) and 8 bytes per candidate entry
-        overflow_bytes = 256 + 2 * ((overflow_candidates * 4 + 255) // 256 * 256) if overflow_candidates > 0 else 0
+        # the reserve shared by all resources: lease words (256 bytes), then overflow_chunks chunks of
+        # overflow_candidates entries (8 bytes each, in two arrays)
+        overflow_bytes = (256 + 2 * overflow_chunks * ((overflow_candidates * 4 + 255) // 256 * 256)
+                          if overflow_candidates > 0 else 0)
         scratch_bytes = per_res * n_resources + overflow_bytes
         self.scratch = torch.empty(scratch_bytes, dtype=torch.uint8, device=self.device)
         cfg.d_pool, cfg.pool_bytes = self.pool.data_ptr(), pool_bytes
         cfg.d_scratch, cfg.scratch_bytes = self.scratch.data_ptr(), scratch_bytes
         cfg.overflow_bytes = overflow_bytes
+        cfg.overflow_chunks = overflow_chunks
         self.cfg = cfg
         h = C.c_void_p()
         torch.cuda.synchronize(self.device)
@@ -299,6 +303,9 @@ class Index:
 
     def poll_error(self) -> int:
         return lib().rtams_poll_error(self._h)
+
+    def clear_error(self) -> None:
+        _chk(lib().rtams_clear_error(self._h), "rtams_clear_error")
 
     def scan_time(self, reset: bool = False) -> Tuple[float, int]:
         ms, n = C.c_double(), C.c_int64()
