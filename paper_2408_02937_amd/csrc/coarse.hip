@@ -10,11 +10,21 @@ namespace rtams {
 constexpr int kCoarseThreads = 256;
 
 int coarse_vt(int d) { return d <= 1024 ? 8 : 4; }
+// ... and fewer for a small batch: every slot of a tile costs a full chain of fp64 operations per
+// centroid whether a vector sits in it or not, and a batch of a few tiles leaves most of the chip
+// idle (one workgroup per tile and centroid split).  The largest tile that still yields a
+// workgroup per compute unit, else single vectors.
+static int coarse_vt_for(const Dev &D, int64_t n) {
+  const int64_t max_s = (D.nlist + kCoarseThreads - 1) / kCoarseThreads;
+  for (int vt = coarse_vt(D.d); vt > 1; vt /= 2)
+    if ((n + vt - 1) / vt * max_s >= 256) return vt;
+  return 1;
+}
 
 // How many workgroups share the centroids of one vector tile, so that a small
 // batch still spreads over the chip.
 int coarse_splits(const Dev &D, int64_t n, size_t part_cap) {
-  int vt = coarse_vt(D.d);
+  int vt = coarse_vt_for(D, n);
   int64_t tiles = (n + vt - 1) / vt;
   int max_s = (D.nlist + kCoarseThreads - 1) / kCoarseThreads;
   int64_t want = (1024 + tiles - 1) / tiles;
@@ -141,14 +151,17 @@ static void launch_coarse(const Dev &D, int64_t n, const float *Y, int splits, d
                           double *pscore, int32_t *pidx, unsigned long long *cursor, uint32_t *zero,
                           int zero_n, hipStream_t s) {
   if (n <= 0) return;
-  int vt = coarse_vt(D.d);
+  int vt = coarse_vt_for(D, n);
   dim3 grid((unsigned)((n + vt - 1) / vt), (unsigned)splits);
   size_t lds = (size_t)vt * D.d * sizeof(double);
 #define RTAMS_GO(M, V) \
   hipLaunchKernelGGL((k_coarse<M, V, ARGMIN>), grid, dim3(kCoarseThreads), lds, s, D, n, Y, splits, \
                      scores, pscore, pidx, cursor, zero, zero_n)
-  if (D.metric == 0) { if (vt == 8) RTAMS_GO(0, 8); else RTAMS_GO(0, 4); }
-  else               { if (vt == 8) RTAMS_GO(1, 8); else RTAMS_GO(1, 4); }
+  if (D.metric == 0) {
+    if (vt == 8) RTAMS_GO(0, 8); else if (vt == 4) RTAMS_GO(0, 4); else if (vt == 2) RTAMS_GO(0, 2); else RTAMS_GO(0, 1);
+  } else {
+    if (vt == 8) RTAMS_GO(1, 8); else if (vt == 4) RTAMS_GO(1, 4); else if (vt == 2) RTAMS_GO(1, 2); else RTAMS_GO(1, 1);
+  }
 #undef RTAMS_GO
 }
 
