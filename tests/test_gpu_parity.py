@@ -397,6 +397,27 @@ def test_vectors_whose_scores_do_not_compare_go_to_the_first_list(mfma):
     g.close()
 
 
+@pytest.mark.parametrize("mfma", [0, 2])
+def test_queries_whose_scores_do_not_compare_disturb_nobody(loaded, mfma):
+    """Queries with a NaN coordinate have no nearest anything; they get some rows of
+    valid ids (or padding) back, and the other queries of the batch their exact answers."""
+    w, g, o, _ = loaded
+    g.set_param("use_mfma", mfma)
+    q = w.queries[:40].copy()
+    q[5, 1] = np.nan
+    q[33, :] = np.nan
+    d, i = g.search(dev(q), w.k, w.nprobe)
+    torch.cuda.synchronize()
+    g.set_param("use_mfma", 2)
+    assert g.poll_error() == 0
+    d, i = d.cpu().numpy(), i.cpu().numpy()
+    good = np.ones(40, bool); good[[5, 33]] = False
+    rd, ri = o.search(q[good], w.k, w.nprobe)
+    assert_topk_matches(w.metric, d[good], i[good], rd, ri, rtol=RTOL, atol=1e-6)
+    known = set(np.concatenate([g.list_export(k)[0].cpu().numpy() for k in range(g.nlist)]).tolist()) | {-1}
+    assert set(i[~good].ravel().tolist()) <= known
+
+
 def test_pool_exhaustion_is_refused_before_anything_is_enqueued():
     d, nlist, T = 4, 2, 64
     C = np.eye(2, 4, dtype=np.float32)
