@@ -79,6 +79,7 @@ __global__ __launch_bounds__(256) void k_pq_fill(Dev D, int64_t n, const float *
       best = take ? ob : best;
       code = take ? oc : code;
     }
+    code = best == best ? code : 0;  // no distance compared (a NaN in the sub-vector): nothing beat the first entry
     if (lane == v) mine = code;
   }
   if (lane >= kFillVecs || i0 + lane >= n) return;

@@ -215,3 +215,21 @@ def test_pq_search_sees_whole_batches_only():
     whole_batches_check(w, g, o, 2)
     assert_code_lists_equal(g, o)
     g.close()
+
+
+def test_vectors_with_a_nan_are_coded_like_the_oracle_does():
+    """A sub-vector with a NaN has no nearest codebook entry; both sides leave it with entry 0."""
+    w, M = cases()["byte-l2-m8"]
+    print(f"[case] pq NaN vectors, workload={w.name} M={M}", flush=True)
+    cb = synth.codebooks_from_rows(w.seed, w.base, M)
+    g, o = make_pq_pair(w, M, cb)
+    y = w.inserts[:40].copy()
+    y[2, 0] = np.nan          # first sub-space only
+    y[11, :] = np.nan
+    g.add(dev(w.base[:1000])); o.add(w.base[:1000])
+    g.add(dev(y)); o.add(y)
+    torch.cuda.synchronize()
+    assert g.poll_error() == 0
+    g.validate()
+    assert_code_lists_equal(g, o)
+    g.close()
