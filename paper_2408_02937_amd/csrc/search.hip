@@ -218,6 +218,44 @@ __device__ inline int next_pow2(int v) {
   return m;
 }
 
+// Sort of the first n entries in LDS by (k1, k2) ascending, pay carried along; entries from n up to
+// the next power of two may be overwritten.  A few hundred entries at most are ranked: a group
+// of S neighbouring lanes counts, each over its share of the entries, how many come before entry
+// e (equal pairs in the order they stand in), and the entry is written to that place — two
+// barriers instead of the dozens of dependent LDS round trips of a sorting network, which costs a
+// single wavefront 5 to 7 us for 32 to 128 entries.  More entries go through the network.
+constexpr int kRankSortMax = 256;
+__device__ inline void wg_sort(int n, uint64_t *k1, uint64_t *k2, uint32_t *pay) {
+  const int T = (int)blockDim.x;
+  if (n > kRankSortMax || n > T) {  // uniform over the workgroup
+    const int m = next_pow2(n > 0 ? n : 1);
+    __syncthreads();
+    for (int p = n + (int)threadIdx.x; p < m; p += T) { k1[p] = ~0ull; k2[p] = ~0ull; pay[p] = 0; }
+    wg_bitonic_sort(m, k1, k2, pay);
+    return;
+  }
+  __syncthreads();
+  int S = 1;  // lanes per entry: a power of two, at most a wavefront, S * n <= T
+  while (S < kWave && 2 * S * n <= T) S *= 2;
+  const int e = (int)threadIdx.x / S, s = (int)threadIdx.x % S;
+  const bool on = e < n;
+  uint64_t a1 = 0, a2 = 0;
+  uint32_t ap = 0, before = 0;
+  if (on) {
+    a1 = k1[e]; a2 = k2[e]; ap = pay[e];
+    const int per = (n + S - 1) / S;
+    const int lo = s * per, hi = lo + per < n ? lo + per : n;
+    for (int j = lo; j < hi; ++j) {
+      const uint64_t b1 = k1[j], b2 = k2[j];
+      before += (b1 < a1 || (b1 == a1 && (b2 < a2 || (b2 == a2 && j < e)))) ? 1u : 0u;
+    }
+  }
+  for (int o = 1; o < S; o <<= 1) before += __shfl_xor(before, o);  // the S lanes of an entry are neighbours in one wavefront
+  __syncthreads();  // everybody has read
+  if (on && s == 0) { k1[before] = a1; k2[before] = a2; pay[before] = ap; }
+  __syncthreads();
+}
+
 // ------------------------------------------------------------ probe and plan
 // One workgroup per query: the nprobe best centroids by (score, index), best
 // first; then the plan of the scan: the visible length of each probed list is
@@ -294,9 +332,7 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
         k1[p] = key_of_score(exact(c));
         k2[p] = (uint64_t)c;
       }
-      const int m = next_pow2(nc);
-      for (int p = nc + threadIdx.x; p < m; p += kSelThreads) { k1[p] = ~0ull; k2[p] = ~0ull; pay[p] = 0; }
-      wg_bitonic_sort(m, k1, k2, pay);  // by (exact score, index): the first nprobe are the answer
+      wg_sort(nc, k1, k2, pay);  // by (exact score, index): the first nprobe are the answer
       done = true;
     } else {
       for (int i = threadIdx.x; i < n; i += kSelThreads) sc[i] = exact(i);  // the filter did not narrow it: whole row
@@ -331,9 +367,7 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
     }
   }
   __syncthreads();
-  const int m = next_pow2(nprobe);
-  for (int p = nprobe + threadIdx.x; p < m; p += kSelThreads) { k1[p] = ~0ull; k2[p] = ~0ull; pay[p] = 0; }
-  wg_bitonic_sort(m, k1, k2, pay);
+  wg_sort(nprobe, k1, k2, pay);
   }  // !done
   if (done) {  // the sort carried no payload: the list index is the second key
     __syncthreads();
@@ -1590,9 +1624,7 @@ __device__ int select_topk(int count, int k, KeyFn key, ItemFn item, IdFn id_of,
     }
     __syncthreads();
   }
-  const int m = next_pow2(kk > 0 ? kk : 1);
-  for (int p = kk + threadIdx.x; p < m; p += blockDim.x) { sh.k1[p] = ~0ull; sh.k2[p] = ~0ull; sh.pay[p] = 0; }
-  wg_bitonic_sort(m, sh.k1, sh.k2, sh.pay);
+  wg_sort(kk, sh.k1, sh.k2, sh.pay);
   return kk;
 }
 
