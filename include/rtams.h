@@ -39,7 +39,7 @@ enum rtams_metric {
 enum rtams_status {
   RTAMS_OK = 0,
   RTAMS_EINVAL = -1,  /* bad argument */
-  RTAMS_ESTATE = -2,  /* centroids not set yet */
+  RTAMS_ESTATE = -2,  /* not in this state: centroids or codebooks not set yet, or set too late */
   RTAMS_EPOOL = -3,   /* the block pool cannot hold the blocks this call may need */
   RTAMS_EBUSY = -4,   /* every stream resource is in flight: request rejected */
   RTAMS_EHIP = -5,    /* a HIP runtime call failed */
@@ -63,7 +63,8 @@ typedef struct rtams_config {
                                   last rearrangement; <= 0 never triggers */
   void *d_pool;       /* device memory carved into control data, tables and blocks */
   size_t pool_bytes;
-  void *d_scratch;    /* device memory split evenly over the stream resources */
+  void *d_scratch;    /* device memory: one slice per stream resource, all of one size, then the
+                         shared reserve (overflow_bytes) if any */
   size_t scratch_bytes;
   int32_t n_resources;   /* search requests that may be in flight at once (paper: 32) */
   int32_t max_batch;     /* largest nq of one rtams_search call */
