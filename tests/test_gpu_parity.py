@@ -126,6 +126,28 @@ def test_search_all_lists_and_large_k(loaded):
     assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6)
 
 
+@pytest.mark.parametrize("mfma", [0, 2])
+def test_many_results_and_many_probes(mfma):
+    """k and nprobe beyond what is put in order by ranking (256 entries): the
+    sorting network with its padding, for the probe lists and for the results."""
+    w = synth.gaussian_l2("wide", 24, d=16, n_base=20_000, n_centres=50, nlist=400, block_vecs=64, n_queries=64,
+                          n_inserts=10, nprobe=300, k=700)
+    print(f"[case] k={w.k} nprobe={w.nprobe} nlist={w.nlist} use_mfma={mfma}", flush=True)
+    g, o = make_pair(w, max_k=1024, max_nprobe=400, max_batch=64)
+    g.set_param("use_mfma", mfma)
+    g.add(dev(w.base)); o.add(w.base)
+    for nprobe, k in ((300, 700), (257, 1024), (400, 300)):
+        q = w.queries[:40]
+        assert np.array_equal(g.probe(dev(q), nprobe).cpu().numpy(), o.probe(q, nprobe))
+        d, i = g.search(dev(q), k, nprobe)
+        torch.cuda.synchronize()
+        assert g.poll_error() == 0
+        rd, ri = o.search(q, k, nprobe)
+        assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6,
+                            what=f"nprobe {nprobe} k {k}")
+    g.close()
+
+
 def test_integer_valued_distances_are_exact():
     """Byte-valued data: every partial sum is an integer below 2^24, so fp32 is
     exact and ids (ties by id included) and distances must equal the oracle's."""
