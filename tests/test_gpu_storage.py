@@ -35,6 +35,13 @@ def cases():
                                                           nlist=64, block_vecs=64, n_queries=200, n_inserts=1_000,
                                                           insert_batch=100, nprobe=8, k=20), metric="ip")),
         "u8-fractional-l2": ("u8", frac),
+        # 15,000 candidates per query: the pruning bound and its sample over byte chunks are at work
+        "u8-dense-l2": ("u8", synth.byte_valued_l2("st-dense", 56, d=64, n_base=60_000, n_centres=30, nlist=64,
+                                                   block_vecs=128, n_queries=300, n_inserts=640, insert_batch=64,
+                                                   nprobe=16, k=100)),
+        "f16-dense-ip": ("f16", synth.unit_ip("st-dense-ip", 57, d=64, n_base=60_000, n_centres=100, nlist=64,
+                                              block_vecs=128, n_queries=300, n_inserts=512, insert_batch=512,
+                                              nprobe=16, k=20)),
     }
     return out
 
