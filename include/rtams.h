@@ -242,8 +242,8 @@ int rtams_copy_plain(void *d_dst, const void *d_src, size_t bytes, void *hip_str
  * memory it may write.  Its rate is the practical ceiling a streaming read
  * reaches on the chip, reported beside the list scan's. */
 int rtams_read_plain(const void *d_src, size_t bytes, float *d_sink, void *hip_stream);
-/* Launch-shape knobs ("restrict the number of blocks and threads per kernel",
- * Stream-Cached Multi-Stream Execution, consideration 2).  key: "scan_max_items"
+/* Launch-shape knobs (Stream-Cached Multi-Stream Execution, consideration 2: a
+ * kernel's blocks and threads are capped so that several kernels run side by side).  key: "scan_max_items"
  * (most work items, one wavefront each, one list-scan launch is cut
  * into; a (query, list) pair is always at least one; default 32768), "scan_items_per_pair" (items per (query, list) pair a small
  * request may be cut into; default 8), "profile_scan" (see rtams_scan_time), and

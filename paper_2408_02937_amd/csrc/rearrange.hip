@@ -4,7 +4,7 @@
 // physical position first + t; whatever sits there is moved out of the way.
 //
 // The paper exchanges two blocks through a temporary segment and waits twice
-// "until the blocks are spare".  Here the exchange is a relocation in two
+// for the blocks involved to be out of use.  Here the exchange is a relocation in two
 // steps, each followed by such a wait (a grace period for the searches in
 // flight, arranged by the host with events):
 //   step 1  every block that occupies a target position is copied to a block

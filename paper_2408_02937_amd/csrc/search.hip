@@ -1,7 +1,6 @@
 // Search path: probe selection and plan, list scan, top-k selection.
-// (Paper, introduction: "the vector lists belonging to the most relevant
-// clusters to the query are computed, and the final top-k vectors are
-// retrieved"; distances are exact, so the result is the textbook IVF-Flat one.)
+// (Paper, introduction: a query is compared with the lists of the clusters nearest to it only, and
+// the k best of those come back; distances are exact, so the result is the textbook IVF-Flat one.)
 #include "rtams_launch.h"
 
 namespace rtams {
@@ -1537,8 +1536,8 @@ __global__ __launch_bounds__(kGroupThreads) void k_pq_bound(Dev D, int nprobe, i
 
 // ------------------------------------------------------------ top-k selection
 // One workgroup per query takes the k best of the query's survivor records
-// (first-list candidates and what the grouped scan appended) by (score, id):
-// exact selection with the id tie-break, then a bitonic sort.  The records
+// (what the scan appended for it) by (score, id): exact selection with the id
+// tie-break, then a sort of the winners.  The records
 // number a few hundred as a rule and are worked on in LDS; a list longer than
 // LDS holds (massive ties) is selected from in place.
 constexpr int kSurvivorCap = 4096;
