@@ -6,7 +6,7 @@
 // The approximate scores only FILTER.  Which list a vector joins and which
 // lists a query probes are decided by the fixed double-precision arithmetic of
 // coarse.hip on the few centroids the filter cannot tell apart (refinement
-// kernels below and in search.hip), so the decisions stay bit-exact:
+// kernels below and in probe.hip), so the decisions stay bit-exact:
 //   approx(i, c) = |c|^2 - 2 <y_i, c>   (L2; |y_i|^2 is the same for every c)
 //   approx(i, c) = - <y_i, c>           (IP)            smaller is better
 // and |approx - exact| <= E_i = 4 (d + 4) 2^-24 (|y_i|^2 + max_c |c|^2), a bound

@@ -3,8 +3,8 @@
 // IVF-Flat as a kind of list its memory blocks hold and leaves the quantiser to
 // the textbook: Jegou et al., product quantization for nearest neighbour
 // search.)  This file holds what differs on the insertion side and the
-// export; the per-request table of sub-scores and the scan over codes live with
-// the other scan in search.hip.
+// export; the per-request table of sub-scores lives in group.hip, the scan over
+// codes in pq_scan.hip.
 //
 // Layout: groups of 64 vectors as for floats; the chunk is one 32-bit word of 4
 // codes, so a wavefront reading word c of a group loads 256 consecutive bytes,

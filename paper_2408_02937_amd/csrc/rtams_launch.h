@@ -136,7 +136,7 @@ void launch_fill(const Dev &D, int64_t n, const float *Y, const int64_t *ids, in
                  const InsertScratch &S, hipStream_t s);
 void launch_publish(const Dev &D, hipStream_t s);
 
-// search.hip -----------------------------------------------------------------
+// probe.hip, group.hip, scan.hip, pq_scan.hip, select.hip ---------------------
 void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const SearchScratch &S,
                        const float *Q, bool from_approx, int32_t *probe_out, hipStream_t s);
 // One launch does three things side by side: one workgroup cuts the scan into work
@@ -146,6 +146,9 @@ void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int k, c
                   int item_budget, const SearchScratch &S, hipStream_t s);
 void launch_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const float *Q, int item_budget,
                  const SearchScratch &S, hipStream_t s);
+// the scan over product-quantiser codes (launch_scan hands quantised lists on to it)
+void launch_pq_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int item_budget,
+                    const SearchScratch &S, hipStream_t s);
 void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
                    const SearchScratch &S, float *out_dist, int64_t *out_ids, hipStream_t s);
 

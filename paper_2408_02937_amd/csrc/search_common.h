@@ -1,0 +1,299 @@
+// What the kernels of the search path share: monotone key maps, where a query's survivor records
+// lie, workgroup-wide selection and sorting in LDS, the fp32 score of a vector against a query,
+// and the launch shape of the list scan (the planning kernel needs it as well).
+#pragma once
+#include "rtams_launch.h"
+
+namespace rtams {
+
+// ------------------------------------------------------------------ key maps
+// Monotone maps from scores to unsigned keys: a smaller key is a better score.
+__device__ inline uint64_t key_of_double(double x) {
+  uint64_t b = (uint64_t)__double_as_longlong(x);
+  return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+}
+__device__ inline uint32_t key_of_float(float x) {
+  uint32_t b = __float_as_uint(x);
+  return (b >> 31) ? ~b : (b | 0x80000000u);
+}
+
+// ------------------------------------------------------- survivor records
+// Where a query's records lie: in its request's slice or, flagged, in the reserve all resources share.
+__device__ inline uint32_t *rec_keys_of(const SearchScratch &S, unsigned long long qbase) {
+  return (qbase & kInOverflow) ? S.ovf_key + (qbase & ~kInOverflow) : S.rec_key + qbase;
+}
+__device__ inline uint32_t *rec_poss_of(const SearchScratch &S, unsigned long long qbase) {
+  return (qbase & kInOverflow) ? S.ovf_pos + (qbase & ~kInOverflow) : S.rec_pos + qbase;
+}
+// Room for `want` entries in the request's chunk of the shared reserve (called by one thread per
+// query): the start, flagged, or ~0.  The first query of a request that needs it leases a free chunk
+// and installs it for the request; one that loses that race to a sibling hands its chunk straight
+// back and shares the sibling's.  Nothing here waits for anybody.
+__device__ inline unsigned long long overflow_take(const SearchScratch &S, unsigned long long want) {
+  if (S.ovf_chunks == 0 || want > S.ovf_chunk_cap) return ~0ull;
+  uint32_t c = __hip_atomic_load(S.req_chunk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (uint32_t e = 0; e < S.ovf_chunks && c == 0; ++e)
+    if (atomicCAS(&S.ovf_leased[e], 0u, 1u) == 0u) {
+      const uint32_t seen = atomicCAS(S.req_chunk, 0u, e + 1u);
+      if (seen == 0u) c = e + 1u;
+      else { atomicExch(&S.ovf_leased[e], 0u); c = seen; }
+    }
+  if (c == 0) c = __hip_atomic_load(S.req_chunk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // a sibling may have got the last one
+  if (c == 0) return ~0ull;  // every chunk is out
+  const unsigned long long off = atomicAdd(S.req_cursor, want);
+  if (off + want > S.ovf_chunk_cap) return ~0ull;
+  return kInOverflow | ((unsigned long long)(c - 1u) * S.ovf_chunk_cap + off);
+}
+// Every selection workgroup of a request reports here when it has read its last record; the last
+// one returns the request's chunk, if it holds one, and resets the request's words.
+__device__ inline void overflow_request_done(const SearchScratch &S, uint32_t workgroups) {
+  if (S.ovf_chunks == 0) return;
+  __threadfence();
+  if (atomicAdd(S.req_done, 1u) + 1u != workgroups) return;
+  const uint32_t c = __hip_atomic_load(S.req_chunk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(S.req_done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(S.req_cursor, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (c) {
+    __hip_atomic_store(S.req_chunk, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __threadfence();
+    atomicExch(&S.ovf_leased[c - 1u], 0u);
+  }
+}
+
+// ------------------------------------------------- workgroup radix selection
+// Finds the threshold of the k smallest keys among the valid items 0..n-1.
+// fn(i, key) returns false for items that do not take part.  On return T is
+// a threshold such that every key < T belongs to the k smallest and, of the
+// c_eq keys not yet told apart from T, `need` belong to them (when c_eq == need
+// the selection stops early and T is the largest key that group can hold; else
+// T is the k-th smallest key itself and the c_eq keys equal it).  Callers take
+// key < T, and key == T under the tie rule.  Requires 1 <= k <= #valid.
+struct SelectResult {
+  uint64_t T;
+  uint32_t need, c_eq;
+};
+
+// After a histogram pass: the first wavefront finds the bin that holds the
+// need-th smallest item; bc = {bin, items in lower bins, items in the bin}.
+__device__ inline void wg_pick_bin(const uint32_t *hist, uint32_t need, uint32_t *bc) {
+  if (threadIdx.x < kWave) {  // first wavefront: which bin holds the need-th item
+      int l = threadIdx.x;
+      uint32_t h0 = hist[4 * l], h1 = hist[4 * l + 1], h2 = hist[4 * l + 2], h3 = hist[4 * l + 3];
+      uint32_t sum = h0 + h1 + h2 + h3, incl = sum;
+      for (int o = 1; o < kWave; o <<= 1) {
+        uint32_t t = __shfl_up(incl, o);
+        if (l >= o) incl += t;
+      }
+      uint32_t excl = incl - sum;
+      if (excl < need && need <= incl) {  // exactly one lane
+        uint32_t cum = excl;
+        int dg;
+        uint32_t hh;
+        if (cum + h0 >= need) { dg = 0; hh = h0; }
+        else { cum += h0;
+          if (cum + h1 >= need) { dg = 1; hh = h1; }
+          else { cum += h1;
+            if (cum + h2 >= need) { dg = 2; hh = h2; }
+            else { cum += h2; dg = 3; hh = h3; } } }
+        bc[0] = (uint32_t)(4 * l + dg);
+        bc[1] = cum;
+        bc[2] = hh;
+      }
+    }
+    __syncthreads();
+}
+
+// `each(body)` calls body(key) for every key of the calling thread that takes part.
+template <int BITS, typename Each>
+__device__ SelectResult wg_radix_select_each(uint32_t k, Each each, uint32_t *hist, uint32_t *bc) {
+  // Leading digits on which every key agrees are skipped: scores of one query's
+  // candidates share sign, exponent and often the first mantissa bits, and a
+  // histogram pass in which all lanes hit one LDS word serialises completely.
+  unsigned long long *mm = reinterpret_cast<unsigned long long *>(hist);  // {min, max} for a moment
+  if (threadIdx.x == 0) { mm[0] = ~0ull; mm[1] = 0ull; }
+  __syncthreads();
+  {
+    unsigned long long lo = ~0ull, hi = 0ull;
+    each([&](uint64_t key) { lo = key < lo ? key : lo; hi = key > hi ? key : hi; });
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+      const unsigned long long a = __shfl_xor(lo, o), b = __shfl_xor(hi, o);
+      lo = a < lo ? a : lo;
+      hi = b > hi ? b : hi;
+    }
+    if ((threadIdx.x & (kWave - 1)) == 0) { atomicMin(&mm[0], lo); atomicMax(&mm[1], hi); }
+  }
+  __syncthreads();
+  const uint64_t kmin = mm[0], kmax = mm[1];
+  __syncthreads();  // hist is reused below
+  int first_shift = BITS - 8;
+  uint64_t prefix = 0, mask = 0;
+  {
+    const uint64_t diff = kmin ^ kmax;
+    const int top = diff ? 63 - __clzll((long long)diff) : -1;  // highest bit in which keys differ
+    first_shift = top < 0 ? 0 : (top / 8) * 8;
+    if (first_shift > BITS - 8) first_shift = BITS - 8;
+    if (first_shift + 8 < 64) {
+      mask = ~0ull << (first_shift + 8);
+      if (BITS < 64) mask &= (1ull << BITS) - 1ull;
+    }
+    prefix = kmax & mask;
+  }
+  uint32_t need = k, c_eq = 0;
+  for (int shift = first_shift; shift >= 0; shift -= 8) {
+    for (int b = threadIdx.x; b < 256; b += blockDim.x) hist[b] = 0;
+    __syncthreads();
+    each([&](uint64_t key) {
+      if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & 255u], 1u);
+    });
+    __syncthreads();
+    wg_pick_bin(hist, need, bc);
+    uint32_t dg = bc[0];
+    need -= bc[1];
+    c_eq = bc[2];
+    prefix |= (uint64_t)dg << shift;
+    mask |= (uint64_t)255u << shift;
+    __syncthreads();
+    if (c_eq == need) {  // the whole bin belongs to the k smallest: the lower digits cannot matter
+      if (shift > 0) prefix |= (1ull << shift) - 1ull;  // threshold = largest key of the bin
+      break;
+    }
+  }
+  return {prefix, need, c_eq};
+}
+
+// Items 0..n-1 given by fn(i, key) (false: the item does not take part); keys are
+// read from memory, four independent loads in flight per thread.
+template <int BITS, typename Fn>
+__device__ SelectResult wg_radix_select(int n, uint32_t k, Fn fn, uint32_t *hist, uint32_t *bc) {
+  auto each = [&](auto body) {
+    for (int i0 = threadIdx.x; i0 < n; i0 += 4 * blockDim.x) {
+      uint64_t key[4];
+      bool ok[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {  // clamped index: the loads are unconditional and issue back to back
+        const int i = i0 + u * (int)blockDim.x;
+        ok[u] = fn(i < n ? i : n - 1, key[u]) && i < n;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (ok[u]) body(key[u]);
+    }
+  };
+  return wg_radix_select_each<BITS>(k, each, hist, bc);
+}
+
+// Bitonic sort of m (power of two) entries in LDS by (k1, k2) ascending; pay is
+// carried along.  The first wavefront does all of it (LDS operations of one
+// wavefront execute in order, so the steps need no workgroup barrier); the
+// others wait at the end.
+__device__ inline void wg_bitonic_sort(int m, uint64_t *k1, uint64_t *k2, uint32_t *pay) {
+  __syncthreads();
+  if (threadIdx.x < kWave) {
+    for (int size = 2; size <= m; size <<= 1) {
+      for (int stride = size >> 1; stride > 0; stride >>= 1) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        for (int t = threadIdx.x; t < m / 2; t += kWave) {
+          int i = 2 * t - (t & (stride - 1));
+          int j = i + stride;
+          bool up = (i & size) == 0;
+          uint64_t a1 = k1[i], a2 = k2[i], b1 = k1[j], b2 = k2[j];
+          bool a_gt_b = a1 != b1 ? a1 > b1 : a2 > b2;
+          if (a_gt_b == up) {
+            k1[i] = b1; k2[i] = b2; k1[j] = a1; k2[j] = a2;
+            uint32_t p = pay[i]; pay[i] = pay[j]; pay[j] = p;
+          }
+        }
+      }
+    }
+  }
+  __syncthreads();
+}
+
+__device__ inline int next_pow2(int v) {
+  int m = 1;
+  while (m < v) m <<= 1;
+  return m;
+}
+
+// Sort of the first n entries in LDS by (k1, k2) ascending, pay carried along; entries from n up to
+// the next power of two may be overwritten.  A few hundred entries at most are ranked: a group
+// of S neighbouring lanes counts, each over its share of the entries, how many come before entry
+// e (equal pairs in the order they stand in), and the entry is written to that place — two
+// barriers instead of the dozens of dependent LDS round trips of a sorting network, which costs a
+// single wavefront 5 to 7 us for 32 to 128 entries.  More entries go through the network.
+constexpr int kRankSortMax = 256;
+__device__ inline void wg_sort(int n, uint64_t *k1, uint64_t *k2, uint32_t *pay) {
+  const int T = (int)blockDim.x;
+  if (n > kRankSortMax || n > T) {  // uniform over the workgroup
+    const int m = next_pow2(n > 0 ? n : 1);
+    __syncthreads();
+    for (int p = n + (int)threadIdx.x; p < m; p += T) { k1[p] = ~0ull; k2[p] = ~0ull; pay[p] = 0; }
+    wg_bitonic_sort(m, k1, k2, pay);
+    return;
+  }
+  __syncthreads();
+  int S = 1;  // lanes per entry: a power of two, at most a wavefront, S * n <= T
+  while (S < kWave && 2 * S * n <= T) S *= 2;
+  const int e = (int)threadIdx.x / S, s = (int)threadIdx.x % S;
+  const bool on = e < n;
+  uint64_t a1 = 0, a2 = 0;
+  uint32_t ap = 0, before = 0;
+  if (on) {
+    a1 = k1[e]; a2 = k2[e]; ap = pay[e];
+    const int per = (n + S - 1) / S;
+    const int lo = s * per, hi = lo + per < n ? lo + per : n;
+    for (int j = lo; j < hi; ++j) {
+      const uint64_t b1 = k1[j], b2 = k2[j];
+      before += (b1 < a1 || (b1 == a1 && (b2 < a2 || (b2 == a2 && j < e)))) ? 1u : 0u;
+    }
+  }
+  for (int o = 1; o < S; o <<= 1) before += __shfl_xor(before, o);  // the S lanes of an entry are neighbours in one wavefront
+  __syncthreads();  // everybody has read
+  if (on && s == 0) { k1[before] = a1; k2[before] = a2; pay[before] = ap; }
+  __syncthreads();
+}
+
+
+// ------------------------------------------------------------------ fp32 score
+// Score of one vector against one query, 4 dimensions at a time, one FMA chain
+// in the order of the dimensions.
+typedef __attribute__((address_space(1))) float GlobalFloat;
+typedef __attribute__((address_space(1))) uint32_t GlobalU32;
+
+template <int METRIC>
+__device__ __forceinline__ void accumulate(float &acc, const float4 &x, const float4 &y) {
+  if (METRIC == 0) {
+    const float t0 = x.x - y.x, t1 = x.y - y.y, t2 = x.z - y.z, t3 = x.w - y.w;
+    acc = fmaf(t0, t0, acc); acc = fmaf(t1, t1, acc); acc = fmaf(t2, t2, acc); acc = fmaf(t3, t3, acc);
+  } else {
+    acc = fmaf(x.x, y.x, acc); acc = fmaf(x.y, y.y, acc); acc = fmaf(x.z, y.z, acc); acc = fmaf(x.w, y.w, acc);
+  }
+}
+
+
+// ---------------------------------------------------- launch shape of the scan
+// Hardware hands consecutive workgroup ids to the 8 XCDs in turn; a workgroup of the scan is up to
+// four wavefronts, one work item each.
+constexpr uint32_t kXcds = 8;
+constexpr int kScanWaves = 4;
+
+// Wavefronts per workgroup of the scan: as many (4, 2, 1) as fit their query tiles into 64 KiB of LDS
+inline int scan_waves(const Dev &D) {
+  const size_t per_wave = (size_t)kScanTileQueries * D.d * sizeof(float);
+  int waves = kScanWaves;
+  while (waves > 1 && per_wave * waves > 65536) waves /= 2;
+  return waves;
+}
+
+// workgroups of the scan launch for a budget of work items (one wavefront each):
+// room for an uneven split of the items over the XCDs
+inline int scan_grid(const Dev &D, int item_budget) {
+  const int waves = scan_waves(D);
+  const int wgs = (item_budget + item_budget / 2 + waves - 1) / waves;
+  return (wgs + (int)kXcds - 1) / (int)kXcds * (int)kXcds;
+}
+
+constexpr int kGroupThreads = 1024;  // workgroup of the planning kernels (k_group, k_pq_bound)
+
+}  // namespace rtams

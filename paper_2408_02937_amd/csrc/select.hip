@@ -1,0 +1,263 @@
+// Top-k selection: the k best of every query's survivor records, by (score, id).
+#include "search_common.h"
+
+namespace rtams {
+
+// ------------------------------------------------------------ top-k selection
+// One workgroup per query takes the k best of the query's survivor records
+// (what the scan appended for it) by (score, id): exact selection with the id
+// tie-break, then a sort of the winners.  The records
+// number a few hundred as a rule and are worked on in LDS; a list longer than
+// LDS holds (massive ties) is selected from in place.
+constexpr int kSurvivorCap = 4096;
+
+constexpr int kTieCap = 1024;  // candidates tied at the k-th score that are told apart in LDS
+
+struct SelectShared {
+  __attribute__((aligned(8))) uint32_t hist[256];  // also holds two 64-bit words for a moment
+  uint32_t bc[4];
+  uint32_t cnt[2];
+  uint64_t k1[kMaxK];
+  uint64_t k2[kMaxK];
+  uint32_t pay[kMaxK];
+  uint64_t tie_id[kTieCap];
+  uint32_t tie_item[kTieCap];
+};
+
+// Exact top-k among `count` items given by key(j) (32-bit score key) and
+// item(j) (candidate position, for the id lookup).  Leaves the winners sorted in
+// sh.k1 (score key), sh.k2 (id key), sh.pay (candidate position); returns how
+// many.  Candidates tied at the k-th score are told apart by id: their ids are
+// fetched once and ranked in LDS (with byte-valued data such ties are the rule,
+// a handful per query); only more ties than kTieCap go through a radix
+// selection over the ids.
+template <typename KeyFn, typename ItemFn, typename IdFn>
+__device__ int select_topk(int count, int k, KeyFn key, ItemFn item, IdFn id_of, SelectShared &sh) {
+  auto key_of_id = [](int64_t id) -> uint64_t { return (uint64_t)id ^ 0x8000000000000000ull; };
+  const int kk = k < count ? k : count;
+  SelectResult r1{~0ull, 0, 0}, r2{~0ull, 0, 0};
+  const bool all = count <= k;
+  if (!all)
+    r1 = wg_radix_select<32>(count, (uint32_t)k, [&](int j, uint64_t &kv) { kv = key(j); return true; },
+                             sh.hist, sh.bc);
+  const bool tie_break = !all && r1.c_eq > r1.need;  // not all of the candidates tied at the k-th score fit
+  const bool in_lds = tie_break && r1.c_eq <= (uint32_t)kTieCap;
+  if (tie_break && !in_lds)
+    r2 = wg_radix_select<64>(count, r1.need,
+                             [&](int j, uint64_t &kv) {
+                               if (key(j) != (uint32_t)r1.T) return false;
+                               kv = key_of_id(id_of(item(j)));
+                               return true;
+                             },
+                             sh.hist, sh.bc);
+  if (threadIdx.x == 0) sh.cnt[0] = sh.cnt[1] = 0;
+  __syncthreads();
+  for (int j = threadIdx.x; j < count; j += blockDim.x) {
+    const uint32_t kv = key(j);
+    bool take = all || kv < (uint32_t)r1.T || (kv == (uint32_t)r1.T && !tie_break);
+    int64_t id = 0;
+    bool have_id = false;
+    if (!take && kv == (uint32_t)r1.T) {
+      if (in_lds) {
+        sh.tie_item[atomicAdd(&sh.cnt[1], 1u)] = (uint32_t)item(j);
+      } else {
+        id = id_of(item(j)); have_id = true;
+        const uint64_t ik = key_of_id(id);
+        if (ik < r2.T) take = true;
+        else if (ik == r2.T) take = atomicAdd(&sh.cnt[1], 1u) < r2.need;  // identical (score, id) pairs
+      }
+    }
+    if (take) {
+      if (!have_id) id = id_of(item(j));
+      const uint32_t p = atomicAdd(&sh.cnt[0], 1u);
+      sh.k1[p] = kv; sh.k2[p] = key_of_id(id); sh.pay[p] = (uint32_t)item(j);
+    }
+  }
+  __syncthreads();
+  if (in_lds) {  // uniform over the workgroup
+    const int nt = (int)sh.cnt[1];  // == r1.c_eq
+    for (int t = threadIdx.x; t < nt; t += blockDim.x) sh.tie_id[t] = key_of_id(id_of((int)sh.tie_item[t]));
+    __syncthreads();
+    for (int t = threadIdx.x; t < nt; t += blockDim.x) {
+      const uint64_t mine = sh.tie_id[t];
+      uint32_t rank = 0;
+      for (int u = 0; u < nt; ++u) {
+        const uint64_t other = sh.tie_id[u];
+        rank += (other < mine || (other == mine && u < t)) ? 1u : 0u;
+      }
+      if (rank < r1.need) {
+        const uint32_t p = atomicAdd(&sh.cnt[0], 1u);
+        sh.k1[p] = (uint32_t)r1.T; sh.k2[p] = mine; sh.pay[p] = sh.tie_item[t];
+      }
+    }
+    __syncthreads();
+  }
+  wg_sort(kk, sh.k1, sh.k2, sh.pay);
+  return kk;
+}
+
+constexpr int kTopkThreads = 512;
+
+__device__ inline float score_of_key(uint32_t key, int metric) {
+  const float x = __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+  return metric == 0 ? x : -x;
+}
+
+__global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprobe, int max_nprobe,
+                                                        SearchScratch S, float *__restrict__ out_dist,
+                                                        int64_t *__restrict__ out_ids) {
+  __shared__ SelectShared sh;
+  __shared__ uint32_t offs[kMaxNprobe];
+  __shared__ int32_t lists[kMaxNprobe];
+  __shared__ uint32_t skey[kSurvivorCap];
+  __shared__ uint32_t sidx[kSurvivorCap];
+  __shared__ uint32_t scount;
+  const int q = blockIdx.x;
+  const int n = (int)S.rec_cnt[q];
+  const unsigned long long base = S.qbase[q];
+  const uint32_t *rk = rec_keys_of(S, base), *rp = rec_poss_of(S, base);
+  const int metric = D.metric;
+  const int lane = threadIdx.x & (kWave - 1);
+  for (int p = threadIdx.x; p < nprobe; p += kTopkThreads) {
+    offs[p] = S.probe_off[(size_t)q * max_nprobe + p];
+    lists[p] = S.probe_list[(size_t)q * max_nprobe + p];
+  }
+  if (threadIdx.x == 0) scount = 0;
+  __syncthreads();
+
+  // The records are taken into LDS in portions.  Once LDS is more than half full the k-th best
+  // of what it holds becomes the limit (it cannot be better than the final k-th best): what is
+  // worse is dropped, and later portions are filtered on the way in.  Under a limit only a few
+  // per cent of a portion pass as a rule, so a portion is four times what LDS could take if all
+  // of it passed; should it not fit after all, what it added is dropped, the limit is renewed
+  // and the portion is read again, cut to what fits for certain.  Ties that no limit can
+  // separate (LDS stays more than half full) are left to the selection in place below.
+  uint32_t limit = S.bound[q];
+  bool in_lds = true;
+  __shared__ uint32_t s_over;
+  int stretch = 1;  // portions as a multiple of the room in LDS
+  for (int next = 0; next < n;) {  // every branch here is uniform over the workgroup
+    const int count = (int)scount;
+    const int m = min(n - next, stretch * (kSurvivorCap - count));
+    if (threadIdx.x == 0) s_over = 0;
+    __syncthreads();
+    constexpr int kInFlight = 8;  // independent loads per thread
+    for (int j0 = 0; j0 < m; j0 += kInFlight * kTopkThreads) {
+      uint32_t kv[kInFlight];
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u) {  // clamped index: the loads are unconditional and issue back to back
+        const int j = j0 + u * kTopkThreads + (int)threadIdx.x;
+        kv[u] = rk[next + (j < m ? j : m - 1)];
+      }
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u) {
+        const int j = j0 + u * kTopkThreads + (int)threadIdx.x;
+        const bool keep = j < m && kv[u] <= limit;
+        const unsigned long long mask = __ballot(keep);
+        if (mask) {  // uniform over the wavefront
+          uint32_t at = 0;
+          if (lane == 0) at = atomicAdd(&scount, (uint32_t)__popcll(mask));
+          at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+          if (keep) {
+            const uint32_t slot = at + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+            if (slot < (uint32_t)kSurvivorCap) { skey[slot] = kv[u]; sidx[slot] = rp[next + j]; }
+            else s_over = 1u;
+          }
+        }
+      }
+    }
+    __syncthreads();
+    const bool over = s_over != 0;
+    __syncthreads();
+    if (over) {  // did not fit: forget what this portion added; below, the limit is renewed from the rest
+      if (threadIdx.x == 0) scount = (uint32_t)count;
+      __syncthreads();
+    } else {
+      next += m;
+      if (next >= n) break;
+    }
+    const int have = (int)scount;
+    if (!over && have <= kSurvivorCap / 2) continue;
+    if (have >= k) {
+      // tighten
+      const SelectResult r = wg_radix_select<32>(
+          have, (uint32_t)k, [&](int j, uint64_t &kv) { kv = skey[j]; return true; }, sh.hist, sh.bc);
+      limit = (uint32_t)r.T;
+      // drop what is worse: everybody reads its entries, then everybody writes the kept ones back
+      constexpr int kMine = kSurvivorCap / kTopkThreads;
+      uint32_t mk[kMine], mi[kMine];
+#pragma unroll
+      for (int u = 0; u < kMine; ++u) {
+        const int j = (int)threadIdx.x + u * kTopkThreads;
+        mk[u] = j < have ? skey[j] : 0xFFFFFFFFu;
+        mi[u] = j < have ? sidx[j] : 0u;
+      }
+      __syncthreads();
+      if (threadIdx.x == 0) scount = 0;
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < kMine; ++u) {
+        const int j = (int)threadIdx.x + u * kTopkThreads;
+        const bool keep = j < have && mk[u] <= limit;
+        const unsigned long long mask = __ballot(keep);
+        if (mask) {
+          uint32_t at = 0;
+          if (lane == 0) at = atomicAdd(&scount, (uint32_t)__popcll(mask));
+          at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+          if (keep) {
+            const uint32_t slot = at + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+            skey[slot] = mk[u];
+            sidx[slot] = mi[u];
+          }
+        }
+      }
+      __syncthreads();
+      if ((int)scount > kSurvivorCap / 2) { in_lds = false; break; }
+    }
+    // from the first limit on, portions may be stretched; a portion that did not fit is read
+    // again unstretched (it fits then, whatever it holds)
+    stretch = over ? 1 : 4;
+  }
+
+  // candidate position -> id: which probed list (last offset <= position), which place, which block
+  auto id_of = [&](int i) -> int64_t {
+    int lo = 0, hi = nprobe - 1;
+    while (lo < hi) {
+      int mid = (lo + hi + 1) >> 1;
+      if (offs[mid] <= (uint32_t)i) lo = mid; else hi = mid - 1;
+    }
+    uint32_t pos = (uint32_t)i - offs[lo];
+    uint32_t b = (uint32_t)*table_entry(D, lists[lo], pos / (uint32_t)D.T_m);
+    return block_ids(D, b)[pos % (uint32_t)D.T_m];
+  };
+
+  int kk;
+  if (in_lds)
+    kk = select_topk((int)scount, k, [&](int j) { return skey[j]; }, [&](int j) { return (int)sidx[j]; },
+                     id_of, sh);
+  else
+    kk = select_topk(n, k, [&](int j) { return rk[j]; }, [&](int j) { return (int)rp[j]; }, id_of, sh);
+
+  for (int r = threadIdx.x; r < k; r += kTopkThreads) {
+    size_t o = (size_t)q * k + r;
+    if (r < kk) {
+      out_dist[o] = score_of_key((uint32_t)sh.k1[r], metric);
+      out_ids[o] = (int64_t)(sh.k2[r] ^ 0x8000000000000000ull);
+    } else {
+      out_dist[o] = metric == 0 ? __builtin_inff() : -__builtin_inff();
+      out_ids[o] = -1;
+    }
+  }
+  // the records are not looked at any more (the selection ended with a barrier)
+  if (threadIdx.x == 0) overflow_request_done(S, gridDim.x);
+}
+
+
+void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
+                   const SearchScratch &S, float *out_dist, int64_t *out_ids, hipStream_t s) {
+  if (nq <= 0) return;
+  hipLaunchKernelGGL(k_select, dim3((unsigned)nq), dim3(kTopkThreads), 0, s, D, k, nprobe, max_nprobe,
+                     S, out_dist, out_ids);
+}
+
+}  // namespace rtams
