@@ -73,28 +73,38 @@ __global__ __launch_bounds__(kMfmaThreads) void k_coarse_mfma(Dev D, int64_t n, 
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
 
-  // staging: thread t loads a float4 (4 consecutive k) of one row
+  // staging: thread t loads a float4 (4 consecutive k) of one row of the vectors and of two rows of the
+  // centroids into registers, one k-tile ahead: the loads of tile t + 1 are in flight while the
+  // matrix cores work on tile t out of LDS
   const int ld_row = tid / 4, ld_k = (tid % 4) * 4;  // 64 rows x 16 k per pass
   float nsq = 0.f;  // this thread's share of |y_row|^2
+  float4 va, vb[2];
+  auto fetch = [&](int k0) {
+    const int64_t r = row0 + ld_row;
+    va = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (r < n && k0 + ld_k < d) va = *reinterpret_cast<const float4 *>(Y + r * d + k0 + ld_k);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int c = col0 + ld_row + 64 * h;
+      vb[h] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (c < D.nlist && k0 + ld_k < d)
+        vb[h] = *reinterpret_cast<const float4 *>(D.centroids + (size_t)c * d + k0 + ld_k);
+    }
+  };
+  fetch(0);
   for (int k0 = 0; k0 < d; k0 += kTileK) {
     {
-      const int64_t r = row0 + ld_row;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (r < n && k0 + ld_k < d) v = *reinterpret_cast<const float4 *>(Y + r * d + k0 + ld_k);
-      if (!MATRIX) nsq = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, nsq))));
+      if (!MATRIX) nsq = fmaf(va.x, va.x, fmaf(va.y, va.y, fmaf(va.z, va.z, fmaf(va.w, va.w, nsq))));
       float *dst = sA + ld_row * kLdsStride + ld_k;
-      dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+      dst[0] = va.x; dst[1] = va.y; dst[2] = va.z; dst[3] = va.w;
     }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int cr = ld_row + 64 * h, c = col0 + cr;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (c < D.nlist && k0 + ld_k < d)
-        v = *reinterpret_cast<const float4 *>(D.centroids + (size_t)c * d + k0 + ld_k);
-      float *dst = sB + cr * kLdsStride + ld_k;
-      dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+      float *dst = sB + (ld_row + 64 * h) * kLdsStride + ld_k;
+      dst[0] = vb[h].x; dst[1] = vb[h].y; dst[2] = vb[h].z; dst[3] = vb[h].w;
     }
     __syncthreads();
+    if (k0 + kTileK < d) fetch(k0 + kTileK);  // uniform
     // operand layout of v_mfma_f32_32x32x2_f32: lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32]
     const float *pa = sA + (wm * 32 + (lane & 31)) * kLdsStride + (lane >> 5);
     const float *pb = sB + (wn * 64 + (lane & 31)) * kLdsStride + (lane >> 5);
