@@ -18,6 +18,7 @@ same launches); `cpu_baseline` is the CPU oracle on the host cores.
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -185,7 +186,11 @@ def main() -> int:
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "n_base": len(w.base), "d": w.d, "nlist": w.nlist,
                    "block_vecs": w.block_vecs, "metric": w.metric, "query_batch": B, "nprobe": nprobe,
-                   "k": k, "insert_batch": ib, "search_streams": args.search_streams, "seed": w.seed},
+                   "k": k, "insert_batch": ib, "search_streams": args.search_streams, "seed": w.seed,
+                   # what was measured on: the first MiB of the base set, and the hardware queues asked for
+                   "base_sha256_first_mib": hashlib.sha256(w.base.tobytes()[:1 << 20]).hexdigest()[:16],
+                   "numpy": np.__version__,
+                   "gpu_max_hw_queues": os.environ.get("GPU_MAX_HW_QUEUES", "runtime default (4)")},
         "roofline": {"bound": "hbm", "kernel": "k_scan", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_launch": union_b, "pair_bytes_per_launch": pair_b,
