@@ -72,9 +72,16 @@
  *   orc_set_storage / orc_stored follow that.
  *
  * Pins (tests/test_oracle_*.py): brute-force exact k-NN when every list is
- * probed; restriction to the probed lists otherwise; membership invariants;
- * closed forms for block counts and slot addresses; the pad-memory figure of
- * the block-size experiment; the figure-1 style rearrangement scenario.
+ * probed; restriction to the probed lists otherwise; ranking by the double
+ * scores where their float roundings coincide; membership invariants; closed
+ * forms for block counts and slot addresses; the pad-memory figure of the
+ * block-size experiment; rearrangement scenarios worked by hand (the figure-1
+ * style exchange, a rearranged list as the next victim, a target on the free
+ * stack of a full pool, the end of the pool); the strictness of Exceed();
+ * numpy's IEEE conversions and brute force over independently converted
+ * vectors for the narrow storage; exact-rational emulation of the coarse
+ * arithmetic.  (Each was seen to fail when the matching mistake was planted in
+ * a copy of this file.)
  * Parity unpinned: the order of vectors of one batch inside a list and the
  * physical block numbers (several results are correct; compared canonically).
  */
