@@ -115,9 +115,9 @@ void launch_coarse_argmin(const Dev &D, int64_t n, const float *Y, int splits, d
 // When the matrix-core filter runs in front of the exact coarse arithmetic: the
 // batch has to be a dense contraction large enough to repay the extra kernel and
 // the refinement (measured crossovers on MI355X, d = 128 and 768: about 1 M (query,
-// centroid) pairs for a search, 4 M pairs and 1024 rows for an assignment).
+// centroid) pairs for a search and for an assignment alike).
 inline bool mfma_pays_for_search(int64_t nq, int64_t nlist) { return nq >= 32 && nq * nlist >= (int64_t)1 << 20; }
-inline bool mfma_pays_for_assign(int64_t m, int64_t nlist) { return m >= 1024 && m * nlist >= (int64_t)4 << 20; }
+inline bool mfma_pays_for_assign(int64_t m, int64_t nlist) { return m >= 32 && m * nlist >= (int64_t)1 << 20; }
 void launch_centroid_norms(const Dev &D, hipStream_t s);
 void launch_coarse_mfma(const Dev &D, int64_t n, const float *Y, float *approx,
                         unsigned long long *cursor_to_clear, uint32_t *zero, int zero_n, hipStream_t s);
