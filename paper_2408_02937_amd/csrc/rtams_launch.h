@@ -117,7 +117,10 @@ void launch_coarse_argmin(const Dev &D, int64_t n, const float *Y, int splits, d
 // the refinement (measured crossovers on MI355X, d = 128 and 768: about 1 M (query,
 // centroid) pairs for a search and for an assignment alike).
 inline bool mfma_pays_for_search(int64_t nq, int64_t nlist) { return nq >= 32 && nq * nlist >= (int64_t)1 << 20; }
-inline bool mfma_pays_for_assign(int64_t m, int64_t nlist) { return m >= 32 && m * nlist >= (int64_t)1 << 20; }
+// (with 8192 centroids or more, whose tiles alone fill the chip, an assignment pays from half as many pairs)
+inline bool mfma_pays_for_assign(int64_t m, int64_t nlist) {
+  return m >= 32 && m * nlist >= (nlist >= 8192 ? (int64_t)1 << 19 : (int64_t)1 << 20);
+}
 void launch_centroid_norms(const Dev &D, hipStream_t s);
 void launch_coarse_mfma(const Dev &D, int64_t n, const float *Y, float *approx,
                         unsigned long long *cursor_to_clear, uint32_t *zero, int zero_n, hipStream_t s);
