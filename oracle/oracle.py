@@ -148,10 +148,15 @@ class OracleIndex:
         self._chk(lib().orc_coarse_scores(self._h, _ptr(y), _ptr(out)), "coarse_scores")
         return out
 
-    def add(self, vecs, ids=None) -> None:
+    def add(self, vecs, ids=None, assign=None) -> None:
+        """Inserts the vectors one after the other.  `assign` may carry the list of each vector as
+        assign() would compute it (a parallel pass done beforehand, or an assignment known and
+        checked by other means); None computes it here."""
         y = _f32(vecs).reshape(-1, self.d)
         i = None if ids is None else np.ascontiguousarray(ids, dtype=np.int64)
-        self._chk(lib().orc_add(self._h, y.shape[0], _ptr(y), _ptr(i), None), "add")
+        a = None if assign is None else np.ascontiguousarray(assign, dtype=np.int32)
+        assert a is None or a.shape == (y.shape[0],)
+        self._chk(lib().orc_add(self._h, y.shape[0], _ptr(y), _ptr(i), _ptr(a)), "add")
 
     def rearrange(self, lst: int) -> None:
         self._chk(lib().orc_rearrange(self._h, lst), "rearrange")

@@ -12,6 +12,8 @@ dimension, order of magnitude and value type stand in for them.
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 from typing import Optional
 
@@ -44,25 +46,56 @@ def _rng(seed: int, stream: int) -> np.random.Generator:
     return np.random.Generator(np.random.PCG64([seed, stream]))
 
 
+# Sets above this many coordinates are drawn in chunks of rows, every chunk from a generator of its
+# own (seeded from the parent stream), on several threads: the result is a pure function of the seed
+# whatever the thread count, and a 20 GB set takes seconds instead of a minute.  Smaller sets keep
+# the single-stream draw.
+_BIG_SET = 1 << 27
+_CHUNK_ROWS = 1 << 17
+
+
 def mixture(
     rng: np.random.Generator,
     centres: np.ndarray,
     n: int,
     sigma: float,
     component: Optional[np.ndarray] = None,
+    post=None,
 ) -> np.ndarray:
-    """n points: a uniformly drawn (or given) centre plus isotropic noise."""
+    """n points: a uniformly drawn (or given) centre plus isotropic noise.  `post`, if given,
+    rewrites rows in place (rounding, normalisation)."""
     if component is None:
         component = rng.integers(0, centres.shape[0], size=n)
-    out = rng.standard_normal((n, centres.shape[1]), dtype=np.float32)
-    out *= np.float32(sigma)
-    out += centres[component]
+    d = centres.shape[1]
+    if n * d <= _BIG_SET:
+        out = rng.standard_normal((n, d), dtype=np.float32)
+        out *= np.float32(sigma)
+        out += centres[component]
+        if post is not None:
+            post(out)
+        return out
+    out = np.empty((n, d), dtype=np.float32)
+    nchunks = (n + _CHUNK_ROWS - 1) // _CHUNK_ROWS
+    seeds = rng.integers(0, 1 << 62, size=nchunks)
+
+    def draw(c: int) -> None:
+        r = np.random.Generator(np.random.PCG64(int(seeds[c])))
+        blk = out[c * _CHUNK_ROWS:(c + 1) * _CHUNK_ROWS]
+        r.standard_normal(out=blk, dtype=np.float32)
+        blk *= np.float32(sigma)
+        blk += centres[component[c * _CHUNK_ROWS:(c + 1) * _CHUNK_ROWS]]
+        if post is not None:
+            post(blk)
+
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+        list(pool.map(draw, range(nchunks)))
     return out
 
 
-def _unit(x: np.ndarray) -> np.ndarray:
+def _unit_rows(x: np.ndarray) -> None:
+    """Rows scaled to unit length in place (norm in double, one rounding to float)."""
     nrm = np.sqrt((x.astype(np.float64) ** 2).sum(axis=1, keepdims=True))
-    return (x / np.maximum(nrm, 1e-30)).astype(np.float32)
+    x[:] = (x / np.maximum(nrm, 1e-30)).astype(np.float32)
 
 
 def _pick_rows(rng: np.random.Generator, base: np.ndarray, n: int) -> np.ndarray:
@@ -115,11 +148,12 @@ def byte_valued_l2(
     Gaussian noise, rounded and clipped."""
     centres = _rng(seed, 0).uniform(0.0, 128.0, size=(n_centres, d)).astype(np.float32)
 
-    def draw(stream: int, n: int) -> np.ndarray:
-        x = mixture(_rng(seed, stream), centres, n, sigma)
+    def to_bytes(x: np.ndarray) -> None:
         np.rint(x, out=x)
         np.clip(x, 0.0, 255.0, out=x)
-        return x
+
+    def draw(stream: int, n: int) -> np.ndarray:
+        return mixture(_rng(seed, stream), centres, n, sigma, post=to_bytes)
 
     base = draw(1, n_base)
     centroids = _pick_rows(_rng(seed, 2), base, nlist)
@@ -146,10 +180,10 @@ def unit_ip(
 ) -> Workload:
     """Unit-normalised embeddings searched by inner product."""
     centres = _rng(seed, 0).standard_normal((n_centres, d), dtype=np.float32)
-    base = _unit(mixture(_rng(seed, 1), centres, n_base, sigma))
+    base = mixture(_rng(seed, 1), centres, n_base, sigma, post=_unit_rows)
     centroids = _pick_rows(_rng(seed, 2), base, nlist)
-    queries = _unit(mixture(_rng(seed, 3), centres, n_queries, sigma))
-    inserts = _unit(mixture(_rng(seed, 4), centres, n_inserts, sigma))
+    queries = mixture(_rng(seed, 3), centres, n_queries, sigma, post=_unit_rows)
+    inserts = mixture(_rng(seed, 4), centres, n_inserts, sigma, post=_unit_rows)
     return Workload(name, "ip", d, nlist, block_vecs, nprobe, k, base, centroids,
                     queries, inserts, insert_batch, seed)
 
