@@ -46,6 +46,23 @@ __device__ void sample_scores(const Dev &D, int nprobe, int max_nprobe, int q, u
       const float4 *__restrict__ x = block_vecs(D, b) + (size_t)(g % gpb) * group_stride + lane;
       float acc = 0.f;
       int c = 0;
+      if (METRIC == 1 && ST == 0 && D.scan_mfma) {
+        // inner products of float lists on the matrix cores, exactly as the scan computes them (same
+        // instruction, same order of the coordinates), so that a candidate's score here and there is
+        // the same bits: every lane offers the one query, component l % 4 of the result is the score
+        // of the lane's own vector
+        MfmaAcc m = {0.f, 0.f, 0.f, 0.f};
+        for (; c + 8 <= d4; c += 8) {
+          float4 v[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) v[u] = x[(size_t)(c + u) * kWave];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) mfma_chunk(m, v[u], qv[c + u]);
+        }
+        for (; c < d4; ++c) mfma_chunk(m, x[(size_t)c * kWave], qv[c]);
+        const int r = lane & 3;
+        acc = r == 0 ? m[0] : r == 1 ? m[1] : r == 2 ? m[2] : m[3];
+      }
       for (; c + 8 <= d4; c += 8) {  // eight loads of 1 KiB in flight per wavefront
         float4 v[8];
 #pragma unroll
@@ -115,6 +132,18 @@ __device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, in
   __shared__ __attribute__((aligned(8))) uint32_t hist[256];
   __shared__ uint32_t bc[4];
   const int tid = threadIdx.x;
+  // |q|^2 for the norm form of the squared distance (the first wavefront computes it, in double)
+  const bool norm_form = !PQ && uses_norm_form(D);
+  __shared__ float s_qn;
+  if (norm_form && tid < kWave) {
+    double a = 0.0;
+    for (int c = tid; c < D.d; c += kWave) {
+      const double v = (double)Q[(size_t)q * D.d + c];
+      a = __builtin_fma(v, v, a);
+    }
+    for (int o = kWave / 2; o > 0; o >>= 1) a += __shfl_xor(a, o);
+    if (tid == 0) { s_qn = (float)a; S.qnorm[q] = (float)a; }
+  }
   // A query with no more candidates than the selection holds in LDS at once needs no bound.  For
   // inner products neither does one whose records cost less than a sample would: the sample is 512
   // vectors or more read by one workgroup (80 us at d = 768), a record is 8 bytes (short lists, wide
@@ -163,6 +192,8 @@ __device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, in
     bound = (uint32_t)r.T;  // the k-th smallest key, or an upper bound of it that admits the same candidates
   }
   if (tid == 0) {
+    // the sample's scores are direct-form ones; the scan may compare norm-form scores with the bound
+    if (norm_form) bound = loosened_key(bound, norm_form_slack(D.d), s_qn);
     S.bound[q] = bound;
     S.rec_cnt[q] = 0u;
   }

@@ -140,7 +140,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
 }
 
 struct ScratchLayout {
-  size_t scores, approx, probe_list, probe_len, probe_off, qbase, qtotal, bound, rec_cnt, cursor, req_words, lut, records, fixed;
+  size_t scores, approx, probe_list, probe_len, probe_off, qbase, qtotal, bound, qnorm, rec_cnt, cursor, req_words, lut, records, fixed;
   size_t list_cnt, pair_start, pair_slot, grouped, plist, pistart, tile_desc, queues, item_cap;
 };
 
@@ -157,6 +157,7 @@ void lay_out_scratch(const rtams_config *c, ScratchLayout *S) {
   S->qbase = take(mb * 8);
   S->qtotal = take(mb * 4);
   S->bound = take(mb * 4);
+  S->qnorm = take(mb * 4);
   S->rec_cnt = take(mb * 4);
   S->cursor = take(8);
   S->req_words = take(16);  // the request's chunk of the shared reserve: chunk, finished workgroups, cursor
@@ -218,6 +219,7 @@ struct rtams_index {
   unsigned long long ovf_chunk_cap = 0;
   std::atomic<int64_t> ordered_add{0};  // positions inside a list in the order of the batch instead of arrival order
   std::atomic<int64_t> use_mfma{1};  // matrix-core filter in front of the exact coarse arithmetic
+  std::atomic<int64_t> scan_mfma{1}; // flat float lists: the scan's dot products on the matrix cores
   std::mutex prof_mutex;
   double scan_ms = 0.0;      // sum of measured scan-kernel durations
   int64_t scan_launches = 0;
@@ -466,6 +468,7 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
     S.qbase = reinterpret_cast<unsigned long long *>(p + SL.qbase);
     S.qtotal = reinterpret_cast<uint32_t *>(p + SL.qtotal);
     S.bound = reinterpret_cast<uint32_t *>(p + SL.bound);
+    S.qnorm = reinterpret_cast<float *>(p + SL.qnorm);
     S.rec_cnt = reinterpret_cast<uint32_t *>(p + SL.rec_cnt);
     S.cursor = reinterpret_cast<unsigned long long *>(p + SL.cursor);
     S.list_cnt = reinterpret_cast<uint32_t *>(p + SL.list_cnt);
@@ -615,7 +618,8 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   int r = acquire(ix);
   if (r < 0) return fail(RTAMS_EBUSY, "all %d stream resources are in flight", ix->n_res);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const Dev &D = ix->dev;
+  Dev D = ix->dev;
+  D.scan_mfma = D.pq_m == 0 && D.storage == RTAMS_F32 && ix->scan_mfma.load(std::memory_order_relaxed) != 0;
   const SearchScratch &S = ix->res[r].s;
   // a rearrangement is switching block tables: start behind its last switch
   if (ix->fence_cur) (void)hipStreamWaitEvent(s, ix->fence_cur, 0);
@@ -633,7 +637,7 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   if (timed) (void)hipEventRecord(ix->res[r].t0, s);
   launch_scan(D, nq, nprobe, ix->cfg.max_nprobe, d_queries, (int)budget, S, s);
   if (timed) { (void)hipEventRecord(ix->res[r].t1, s); ix->res[r].timed = true; }
-  launch_select(D, nq, k, nprobe, ix->cfg.max_nprobe, S, d_out_dist, d_out_ids, s);
+  launch_select(D, nq, k, nprobe, ix->cfg.max_nprobe, d_queries, S, d_out_dist, d_out_ids, s);
   hipError_t e = hipGetLastError();
   hipError_t e2 = hipEventRecord(ix->res[r].done, s);
   ix->res[r].state.store(RES_PENDING, std::memory_order_release);
@@ -937,6 +941,7 @@ int rtams_set_param(rtams_index *ix, const char *key, int64_t value) {
   if (!strcmp(key, "profile_scan")) { ix->profile_scan = value; return RTAMS_OK; }
   if (!strcmp(key, "ordered_add")) { ix->ordered_add = value; return RTAMS_OK; }
   if (!strcmp(key, "use_mfma")) { ix->use_mfma = value; return RTAMS_OK; }
+  if (!strcmp(key, "scan_mfma")) { ix->scan_mfma = value; return RTAMS_OK; }
   if (!strcmp(key, "scan_max_items")) { ix->scan_max_items = value > 1024 ? value : 1024; return RTAMS_OK; }
   if (!strcmp(key, "scan_items_per_pair")) { ix->scan_items_per_pair = value > 0 ? value : 1; return RTAMS_OK; }
   return fail(RTAMS_EINVAL, "unknown parameter %s", key);

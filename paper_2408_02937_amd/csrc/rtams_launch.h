@@ -27,6 +27,7 @@ struct SearchScratch {
   unsigned long long *qbase;  // [max_batch] start of the query's slice of rec_key / rec_pos
   uint32_t *qtotal;     // [max_batch] candidates of the query
   uint32_t *bound;      // [max_batch] key of the score the scan compares with
+  float *qnorm;         // [max_batch] squared norms of the queries (norm form of the squared distance)
   uint32_t *rec_cnt;    // [max_batch] survivors recorded so far
   unsigned long long *cursor; // bump pointer into the survivor records
   uint32_t *list_cnt;   // [nlist] queries probing each list
@@ -152,7 +153,7 @@ void launch_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const flo
 // the scan over product-quantiser codes (launch_scan hands quantised lists on to it)
 void launch_pq_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int item_budget,
                     const SearchScratch &S, hipStream_t s);
-void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
+void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe, const float *Q,
                    const SearchScratch &S, float *out_dist, int64_t *out_ids, hipStream_t s);
 
 // pq.hip -----------------------------------------------------------------------

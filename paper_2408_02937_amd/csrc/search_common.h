@@ -271,6 +271,59 @@ __device__ __forceinline__ void accumulate(float &acc, const float4 &x, const fl
   }
 }
 
+// ------------------------------------------- dot products on the matrix cores
+// v_mfma_f32_4x4x1 (16 blocks): a wavefront multiplies, block by block, a column of 4 values of A by a
+// row of 4 values of B.  Lane l supplies one value of each; component r of the result in lane l is
+//   a[lane 4 (l / 4) + r] * b[lane l]
+// added to what the component held.  With a = one coordinate of the 64 vectors of a group (lane =
+// vector, exactly what the interleaved layout hands to a wavefront) and b = the same coordinate of
+// query l % 4, d such instructions leave, in lane l, the inner products of vectors 4 (l / 4) .. + 3 with
+// query l % 4: 64 vectors x 4 queries per instruction and coordinate, no data movement in between.
+typedef float MfmaAcc __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void mfma_step(MfmaAcc &acc, float x, float y) {
+  acc = __builtin_amdgcn_mfma_f32_4x4x1f32(x, y, acc, 0, 0, 0);
+}
+// a chunk of 4 coordinates into one accumulator, in the order of the coordinates
+__device__ __forceinline__ void mfma_chunk(MfmaAcc &acc, const float4 &x, const float4 &y) {
+  mfma_step(acc, x.x, y.x);
+  mfma_step(acc, x.y, y.y);
+  mfma_step(acc, x.z, y.z);
+  mfma_step(acc, x.w, y.w);
+}
+// value of lane 4 (l / 4) + r for every lane l (a move inside each group of four lanes)
+template <int R>
+__device__ __forceinline__ float quad_broadcast(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), R * 0x55, 0xf, 0xf, true));
+}
+
+// ---- norm form of the squared distance.  On the matrix cores a squared distance is scored as
+// |x|^2 + |q|^2 - 2 <x, q> (the inner products are the contraction; |x|^2 is accumulated once per
+// vector beside it).  That value differs from the direct form sum (x - q)^2 (which is what the bound's
+// sample computes and what is returned) by rounding errors that grow with the norms, not with the
+// distance:
+//   |norm form - direct form| <= slack * (2 v + 3 |q|^2),  slack = 1.01 (4 d + 8) 2^-24,
+// for v either of the two values (d roundings for |x|^2, up to 2 d for <x, q> whatever the order of
+// its terms, three more for the combination, d + 2 roundings of the direct form; |x|^2 + |q|^2 <=
+// 2 |x - q|^2 + 3 |q|^2).  So whoever compares a norm-form score with a limit taken from direct-form
+// scores, or the other way round, first raises the limit by that much ("loosened"), and the selection
+// scores its finalists again in the direct form: the result is the one the direct form gives.
+__device__ inline float norm_form_slack(int d) { return 1.01f * (float)(4 * d + 8) * 5.9604645e-8f; }
+__device__ inline float loosened(float v, float slack, float qn) {
+  const float r = v + slack * (2.f * fmaxf(v, 0.f) + 3.f * qn) + 1e-30f;
+  return r + fabsf(r) * 2.4e-7f;  // the rounding of this very computation
+}
+__device__ inline float l2_score_of_key(uint32_t key) {
+  return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
+__device__ inline uint32_t loosened_key(uint32_t key, float slack, float qn) {
+  if (key == 0xFFFFFFFFu) return key;  // "keep everything"
+  return key_of_float(loosened(l2_score_of_key(key), slack, qn) + 0.0f);
+}
+// which lists a request scores through the norm form: flat float lists under the L2 metric
+__device__ __host__ inline bool uses_norm_form(const Dev &D) {
+  return D.scan_mfma != 0 && D.metric == 0 && D.pq_m == 0 && D.storage == 0;
+}
+
 
 // ---------------------------------------------------- launch shape of the scan
 // Hardware hands consecutive workgroup ids to the 8 XCDs in turn; a workgroup of the scan is up to
@@ -280,7 +333,7 @@ constexpr int kScanWaves = 4;
 
 // Wavefronts per workgroup of the scan: as many (4, 2, 1) as fit their query tiles into 64 KiB of LDS
 inline int scan_waves(const Dev &D) {
-  const size_t per_wave = (size_t)kScanTileQueries * D.d * sizeof(float);
+  const size_t per_wave = (size_t)kScanTileQueries * (D.d + 4) * sizeof(float);  // a tile's queries, rows one float4 apart
   int waves = kScanWaves;
   while (waves > 1 && per_wave * waves > 65536) waves /= 2;
   return waves;

@@ -104,7 +104,8 @@ __device__ inline float score_of_key(uint32_t key, int metric) {
 }
 
 __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprobe, int max_nprobe,
-                                                        SearchScratch S, float *__restrict__ out_dist,
+                                                        const float *__restrict__ Q, SearchScratch S,
+                                                        float *__restrict__ out_dist,
                                                         int64_t *__restrict__ out_ids) {
   __shared__ SelectShared sh;
   __shared__ uint32_t offs[kMaxNprobe];
@@ -132,6 +133,46 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
   // of it passed; should it not fit after all, what it added is dropped, the limit is renewed
   // and the portion is read again, cut to what fits for certain.  Ties that no limit can
   // separate (LDS stays more than half full) are left to the selection in place below.
+  // With norm-form scores among the records (flat float lists under L2 scored on the matrix cores) a
+  // limit taken from the k-th best record is loosened twice: once to bound the k-th best direct-form
+  // score from above, once more to admit every record whose direct-form score may reach that.
+  const bool approx = uses_norm_form(D);
+  const float slack = norm_form_slack(D.d), qn = approx ? S.qnorm[q] : 0.f;
+  auto limit_from = [&](uint32_t kth) {
+    return approx ? loosened_key(loosened_key(kth, slack, qn), slack, qn) : kth;
+  };
+  // what LDS holds is cut down to the records not worse than the limit: everybody reads its
+  // entries, then everybody writes the kept ones back
+  auto keep_not_worse = [&](int have, uint32_t lim) {
+    constexpr int kMine = kSurvivorCap / kTopkThreads;
+    uint32_t mk[kMine], mi[kMine];
+#pragma unroll
+    for (int u = 0; u < kMine; ++u) {
+      const int j = (int)threadIdx.x + u * kTopkThreads;
+      mk[u] = j < have ? skey[j] : 0xFFFFFFFFu;
+      mi[u] = j < have ? sidx[j] : 0u;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) scount = 0;
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kMine; ++u) {
+      const int j = (int)threadIdx.x + u * kTopkThreads;
+      const bool keep = j < have && mk[u] <= lim;
+      const unsigned long long mask = __ballot(keep);
+      if (mask) {
+        uint32_t at = 0;
+        if (lane == 0) at = atomicAdd(&scount, (uint32_t)__popcll(mask));
+        at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+        if (keep) {
+          const uint32_t slot = at + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+          skey[slot] = mk[u];
+          sidx[slot] = mi[u];
+        }
+      }
+    }
+    __syncthreads();
+  };
   uint32_t limit = S.bound[q];
   bool in_lds = true;
   __shared__ uint32_t s_over;
@@ -182,36 +223,9 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
       // tighten
       const SelectResult r = wg_radix_select<32>(
           have, (uint32_t)k, [&](int j, uint64_t &kv) { kv = skey[j]; return true; }, sh.hist, sh.bc);
-      limit = (uint32_t)r.T;
-      // drop what is worse: everybody reads its entries, then everybody writes the kept ones back
-      constexpr int kMine = kSurvivorCap / kTopkThreads;
-      uint32_t mk[kMine], mi[kMine];
-#pragma unroll
-      for (int u = 0; u < kMine; ++u) {
-        const int j = (int)threadIdx.x + u * kTopkThreads;
-        mk[u] = j < have ? skey[j] : 0xFFFFFFFFu;
-        mi[u] = j < have ? sidx[j] : 0u;
-      }
-      __syncthreads();
-      if (threadIdx.x == 0) scount = 0;
-      __syncthreads();
-#pragma unroll
-      for (int u = 0; u < kMine; ++u) {
-        const int j = (int)threadIdx.x + u * kTopkThreads;
-        const bool keep = j < have && mk[u] <= limit;
-        const unsigned long long mask = __ballot(keep);
-        if (mask) {
-          uint32_t at = 0;
-          if (lane == 0) at = atomicAdd(&scount, (uint32_t)__popcll(mask));
-          at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
-          if (keep) {
-            const uint32_t slot = at + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-            skey[slot] = mk[u];
-            sidx[slot] = mi[u];
-          }
-        }
-      }
-      __syncthreads();
+      const uint32_t lim = limit_from((uint32_t)r.T);
+      limit = lim < limit ? lim : limit;
+      keep_not_worse(have, limit);  // drop what is worse
       if ((int)scount > kSurvivorCap / 2) { in_lds = false; break; }
     }
     // from the first limit on, portions may be stretched; a portion that did not fit is read
@@ -219,24 +233,120 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
     stretch = over ? 1 : 4;
   }
 
-  // candidate position -> id: which probed list (last offset <= position), which place, which block
-  auto id_of = [&](int i) -> int64_t {
+  // candidate position -> which probed list (last offset <= position), which place, which block
+  auto locate = [&](int i, uint32_t &b, uint32_t &moff) {
     int lo = 0, hi = nprobe - 1;
     while (lo < hi) {
       int mid = (lo + hi + 1) >> 1;
       if (offs[mid] <= (uint32_t)i) lo = mid; else hi = mid - 1;
     }
-    uint32_t pos = (uint32_t)i - offs[lo];
-    uint32_t b = (uint32_t)*table_entry(D, lists[lo], pos / (uint32_t)D.T_m);
-    return block_ids(D, b)[pos % (uint32_t)D.T_m];
+    const uint32_t pos = (uint32_t)i - offs[lo];
+    b = (uint32_t)*table_entry(D, lists[lo], pos / (uint32_t)D.T_m);
+    moff = pos % (uint32_t)D.T_m;
   };
-
-  int kk;
-  if (in_lds)
-    kk = select_topk((int)scount, k, [&](int j) { return skey[j]; }, [&](int j) { return (int)sidx[j]; },
-                     id_of, sh);
-  else
-    kk = select_topk(n, k, [&](int j) { return rk[j]; }, [&](int j) { return (int)rp[j]; }, id_of, sh);
+  auto id_of = [&](int i) -> int64_t {
+    uint32_t b, moff;
+    locate(i, b, moff);
+    return block_ids(D, b)[moff];
+  };
+  // candidate position -> key of its direct-form squared distance.  Four neighbouring lanes share
+  // a candidate (a vector's chunks of 4 dimensions lie 1 KiB apart: every chunk is a memory
+  // transaction of its own, and this way all of them are in flight at once): lane s of the four
+  // takes chunks s, s + 4, ..., and the four partial sums are added pairwise.  All four lanes call
+  // this with the same position and get the key.
+  auto direct_key = [&](int i, int64_t *id) -> uint32_t {
+    uint32_t b, moff;
+    locate(i, b, moff);
+    const int sub = (int)(threadIdx.x & 3u);
+    if (id && sub == 0) *id = block_ids(D, b)[moff];
+    const float4 *__restrict__ x =
+        block_vecs(D, b) + (size_t)(moff / kWave) * D.d4 * kWave + (moff & (kWave - 1));
+    const float4 *__restrict__ y = reinterpret_cast<const float4 *>(Q + (size_t)q * D.d);
+    float acc = 0.f;
+    int c = sub;
+    for (; c + 28 < D.d4; c += 32) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = x[(size_t)(c + 4 * u) * kWave];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) accumulate<0>(acc, v[u], y[c + 4 * u]);
+    }
+    for (; c < D.d4; c += 4) accumulate<0>(acc, x[(size_t)c * kWave], y[c]);
+    acc += __shfl_xor(acc, 1);
+    acc += __shfl_xor(acc, 2);
+    return key_of_float(acc + 0.0f);
+  };
+  int kk = -1;
+  if (approx && in_lds) {  // uniform over the workgroup
+    // The usual case: the finalists (every record that may be among the k best by direct-form
+    // scores, i.e. not worse than the twice loosened k-th best of what LDS holds) number little
+    // more than k.  They get their direct-form scores and ids in one go and are sorted by those.
+    const int have = (int)scount;
+    uint32_t lim = 0xFFFFFFFFu;
+    if (have > k) {
+      const SelectResult r = wg_radix_select<32>(
+          have, (uint32_t)k, [&](int j, uint64_t &kv) { kv = skey[j]; return true; }, sh.hist, sh.bc);
+      lim = limit_from((uint32_t)r.T);
+      limit = lim < limit ? lim : limit;
+    }
+    if (threadIdx.x == 0) sh.cnt[0] = 0;
+    __syncthreads();
+    for (int j = threadIdx.x; j < have; j += kTopkThreads)
+      if (skey[j] <= lim) {
+        const uint32_t p = atomicAdd(&sh.cnt[0], 1u);
+        if (p < (uint32_t)kMaxK) sh.pay[p] = sidx[j];
+      }
+    __syncthreads();
+    const int m = (int)sh.cnt[0];
+    if (m <= kMaxK) {
+      for (int p0 = 0; p0 < m; p0 += kTopkThreads / 4) {  // uniform trip count: the lanes of a four stay together
+        const int p = p0 + (int)(threadIdx.x >> 2);
+        int64_t id = 0;
+        const uint32_t key = direct_key((int)sh.pay[p < m ? p : m - 1], &id);
+        if (p < m && (threadIdx.x & 3u) == 0) {
+          sh.k1[p] = key;
+          sh.k2[p] = (uint64_t)id ^ 0x8000000000000000ull;
+        }
+      }
+      wg_sort(m, sh.k1, sh.k2, sh.pay);
+      kk = k < m ? k : m;
+    }
+  }
+  if (approx && kk < 0) {  // uniform over the workgroup
+    // Many finalists (near-ties by the thousand): whatever is not worse than the limit is scored
+    // again where it lies, and the selection then runs on direct-form scores as for the other kinds of list.
+    if (in_lds) {
+      keep_not_worse((int)scount, limit);
+      const int have = (int)scount;
+      for (int j0 = 0; j0 < have; j0 += kTopkThreads / 4) {
+        const int j = j0 + (int)(threadIdx.x >> 2);
+        const uint32_t key = direct_key((int)sidx[j < have ? j : have - 1], nullptr);
+        if (j < have && (threadIdx.x & 3u) == 0) skey[j] = key;
+      }
+    } else {
+      // the records are this query's own
+      uint32_t *wk = const_cast<uint32_t *>(rk);
+      for (int j0 = 0; j0 < n; j0 += kTopkThreads / 4) {
+        const int j = j0 + (int)(threadIdx.x >> 2);
+        const int jj = j < n ? j : n - 1;
+        const bool want = rk[jj] <= limit;
+        uint32_t key = 0xFFFFFFFFu;
+        if (__any(want)) {  // uniform over the wavefront, so the fours stay together
+          const uint32_t dk = direct_key((int)rp[jj], nullptr);
+          key = want ? dk : key;
+        }
+        if (j < n && (threadIdx.x & 3u) == 0) wk[j] = key;
+      }
+    }
+    __syncthreads();
+  }
+  if (kk < 0) {
+    if (in_lds)
+      kk = select_topk((int)scount, k, [&](int j) { return skey[j]; }, [&](int j) { return (int)sidx[j]; },
+                       id_of, sh);
+    else
+      kk = select_topk(n, k, [&](int j) { return rk[j]; }, [&](int j) { return (int)rp[j]; }, id_of, sh);
+  }
 
   for (int r = threadIdx.x; r < k; r += kTopkThreads) {
     size_t o = (size_t)q * k + r;
@@ -253,11 +363,11 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
 }
 
 
-void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe,
+void launch_select(const Dev &D, int64_t nq, int k, int nprobe, int max_nprobe, const float *Q,
                    const SearchScratch &S, float *out_dist, int64_t *out_ids, hipStream_t s) {
   if (nq <= 0) return;
   hipLaunchKernelGGL(k_select, dim3((unsigned)nq), dim3(kTopkThreads), 0, s, D, k, nprobe, max_nprobe,
-                     S, out_dist, out_ids);
+                     Q, S, out_dist, out_ids);
 }
 
 }  // namespace rtams

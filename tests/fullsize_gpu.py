@@ -6,7 +6,7 @@ import torch
 from paper_2408_02937_amd import rtams, synth
 from oracle.oracle import OracleIndex
 from tests.fullsize_common import compare_lists, say
-from tests.gpu_common import dev
+from tests.gpu_common import dev, scan_modes
 from tests.helpers import assert_topk_matches
 
 
@@ -52,16 +52,20 @@ def check_lengths_and_lists(request, w, g, o, n_lists=14):
 
 def check_queries(request, w, g, o, q, batch, what):
     s = torch.cuda.Stream()
-    got_d, got_i = [], []
-    for lo in range(0, len(q), batch):
-        d, i = g.search(dev(q[lo:lo + batch]), w.k, w.nprobe, stream=s)
-        s.synchronize()
-        got_d.append(d.cpu().numpy()); got_i.append(i.cpu().numpy())
-    assert g.poll_error() == 0
+    got = {}
+    for mode in scan_modes(g):  # dot products on the matrix cores, then on the vector unit
+        got_d, got_i = [], []
+        for lo in range(0, len(q), batch):
+            d, i = g.search(dev(q[lo:lo + batch]), w.k, w.nprobe, stream=s)
+            s.synchronize()
+            got_d.append(d.cpu().numpy()); got_i.append(i.cpu().numpy())
+        assert g.poll_error() == 0
+        got[mode] = (np.concatenate(got_d), np.concatenate(got_i))
     probes = g.probe(dev(q[:batch]), w.nprobe).cpu().numpy()
     assert np.array_equal(probes, o.probe(q[:batch], w.nprobe)), f"{what}: probed lists differ"
     say(request, f"{what}: {len(q)} queries answered on the GPU; the oracle's turn")
     rd, ri = o.search(q, w.k, w.nprobe)
-    assert_topk_matches(w.metric, np.concatenate(got_d), np.concatenate(got_i), rd, ri, rtol=RTOL, atol=ATOL, what=what)
+    for mode, (gd, gi) in got.items():
+        assert_topk_matches(w.metric, gd, gi, rd, ri, rtol=RTOL, atol=ATOL, what=f"{what}, scan_mfma {mode}")
 
 

@@ -16,6 +16,18 @@ def dev(a: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
 
 
+def scan_modes(g, modes=(1, 0)):
+    """Runs the body of a for loop once per arithmetic of the list scan: dot products on the matrix
+    cores (the default for flat float lists), then on the vector unit.  Answers must agree with the
+    oracle either way.  The default is restored afterwards."""
+    try:
+        for m in modes:
+            g.set_param("scan_mfma", m)
+            yield m
+    finally:
+        g.set_param("scan_mfma", 1)
+
+
 def make_pair(w, pool_blocks=None, rearrange_threshold=0, max_batch=256, max_k=128, max_nprobe=64,
               candidates_per_query=None, n_resources=4, max_add_batch=65536, storage="f32"):
     """(gpu index, oracle index) over workload w, centroids set, nothing added."""

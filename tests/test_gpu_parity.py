@@ -4,7 +4,7 @@ import pytest
 import torch
 
 from paper_2408_02937_amd import rtams, synth
-from tests.gpu_common import assert_lists_equal, dev, make_pair
+from tests.gpu_common import assert_lists_equal, dev, make_pair, scan_modes
 from tests.helpers import assert_topk_matches
 
 pytestmark = pytest.mark.gpu
@@ -108,22 +108,25 @@ def test_probe_selection_is_bit_exact(loaded):
 def test_search_matches_oracle(loaded, batch):
     w, g, o, _ = loaded
     q = w.queries[:batch]
-    d, i = g.search(dev(q), w.k, w.nprobe)
-    torch.cuda.synchronize()
-    assert g.poll_error() == 0
     rd, ri = o.search(q, w.k, w.nprobe)
-    assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6,
-                        what=f"{w.name} batch {batch}")
+    for mode in scan_modes(g):
+        d, i = g.search(dev(q), w.k, w.nprobe)
+        torch.cuda.synchronize()
+        assert g.poll_error() == 0
+        assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6,
+                            what=f"{w.name} batch {batch} scan_mfma {mode}")
 
 
 def test_search_all_lists_and_large_k(loaded):
     w, g, o, _ = loaded
     nprobe = min(w.nlist, 64)
     q = w.queries[:32]
-    d, i = g.search(dev(q), 128, nprobe)
-    torch.cuda.synchronize()
     rd, ri = o.search(q, 128, nprobe)
-    assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6)
+    for mode in scan_modes(g):
+        d, i = g.search(dev(q), 128, nprobe)
+        torch.cuda.synchronize()
+        assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6,
+                            what=f"scan_mfma {mode}")
 
 
 @pytest.mark.parametrize("mfma", [0, 2])
@@ -139,12 +142,13 @@ def test_many_results_and_many_probes(mfma):
     for nprobe, k in ((300, 700), (257, 1024), (400, 300)):
         q = w.queries[:40]
         assert np.array_equal(g.probe(dev(q), nprobe).cpu().numpy(), o.probe(q, nprobe))
-        d, i = g.search(dev(q), k, nprobe)
-        torch.cuda.synchronize()
-        assert g.poll_error() == 0
         rd, ri = o.search(q, k, nprobe)
-        assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6,
-                            what=f"nprobe {nprobe} k {k}")
+        for mode in scan_modes(g):
+            d, i = g.search(dev(q), k, nprobe)
+            torch.cuda.synchronize()
+            assert g.poll_error() == 0
+            assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6,
+                                what=f"nprobe {nprobe} k {k} scan_mfma {mode}")
     g.close()
 
 
@@ -156,13 +160,14 @@ def test_integer_valued_distances_are_exact():
     base = np.concatenate([w.base, w.base[:500]])      # duplicates: exact ties
     g.add(dev(base)); o.add(base)
     q = w.queries[:256]
-    d, i = g.search(dev(q), w.k, w.nprobe)
-    torch.cuda.synchronize()
     rd, ri = o.search(q, w.k, w.nprobe)
-    assert np.array_equal(i.cpu().numpy(), ri)
-    assert np.array_equal(d.cpu().numpy().astype(np.float64), rd)
-    d, i = g.search(dev(base[7:8]), 2, w.nprobe)      # both copies of a duplicated row, lower id first
-    assert i.cpu().numpy()[0].tolist() == [7, len(w.base) + 7] and d.cpu().numpy()[0].tolist() == [0.0, 0.0]
+    for mode in scan_modes(g):  # the norm form of the matrix cores is exact on such data as well
+        d, i = g.search(dev(q), w.k, w.nprobe)
+        torch.cuda.synchronize()
+        assert np.array_equal(i.cpu().numpy(), ri), f"scan_mfma {mode}"
+        assert np.array_equal(d.cpu().numpy().astype(np.float64), rd), f"scan_mfma {mode}"
+        d, i = g.search(dev(base[7:8]), 2, w.nprobe)      # both copies of a duplicated row, lower id first
+        assert i.cpu().numpy()[0].tolist() == [7, len(w.base) + 7] and d.cpu().numpy()[0].tolist() == [0.0, 0.0]
     g.close()
 
 
@@ -260,9 +265,11 @@ def test_odd_shapes(shape):
     g.validate()
     assert_lists_equal(g, o)
     q = (C[rng.integers(0, nlist, shape["batch"])] + 0.3 * rng.standard_normal((shape["batch"], d))).astype(np.float32)
-    dd, ii = g.search(dev(q), shape["k"], shape["nprobe"])
     rd, ri = o.search(q, shape["k"], shape["nprobe"])
-    assert_topk_matches(metric, dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-5)
+    for mode in scan_modes(g):
+        dd, ii = g.search(dev(q), shape["k"], shape["nprobe"])
+        assert_topk_matches(metric, dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6,
+                            what=f"scan_mfma {mode}")
     g.close()
 
 
@@ -290,9 +297,11 @@ def test_loose_bound_and_worst_first_records():
     q = np.zeros((3, d), np.float32)
     q[:, 0] = (0.95, 0.9, 0.8)
     for k in (1, 100):
-        dd, ii = g.search(dev(q), k, nlist)
         rd, ri = o.search(q, k, nlist)
-        assert_topk_matches("l2", dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6)
+        for mode in scan_modes(g):
+            dd, ii = g.search(dev(q), k, nlist)
+            assert_topk_matches("l2", dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6,
+                                what=f"k {k} scan_mfma {mode}")
     g.close()
 
 
@@ -308,10 +317,12 @@ def test_k_larger_than_a_query_has_candidates():
     y = rng.standard_normal((700, d)).astype(np.float32)
     g.add(dev(y)); o.add(y)
     q = rng.standard_normal((40, d)).astype(np.float32)
-    dd, ii = g.search(dev(q), 128, 2)
     rd, ri = o.search(q, 128, 2)
     assert (ri == -1).any()  # some query does run short
-    assert_topk_matches("ip", dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6)
+    for mode in scan_modes(g):
+        dd, ii = g.search(dev(q), 128, 2)
+        assert_topk_matches("ip", dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6,
+                            what=f"scan_mfma {mode}")
     g.close()
 
 
@@ -330,10 +341,39 @@ def test_massive_ties_fall_back_to_in_place_selection():
     y = np.concatenate([same, other])
     g.add(dev(y), dev(ids)); o.add(y, ids)
     q = np.concatenate([C[1:2] + np.float32(0.25), other[:7]])
-    dd, ii = g.search(dev(q), 100, 4)
     rd, ri = o.search(q, 100, 4)
-    assert np.array_equal(ii.cpu().numpy()[0], ri[0]) and np.all(dd.cpu().numpy()[0] == 0.0)
-    assert_topk_matches("l2", dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6)
+    for mode in scan_modes(g):
+        dd, ii = g.search(dev(q), 100, 4)
+        assert np.array_equal(ii.cpu().numpy()[0], ri[0]) and np.all(dd.cpu().numpy()[0] == 0.0), f"scan_mfma {mode}"
+        assert_topk_matches("l2", dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6,
+                            what=f"scan_mfma {mode}")
+    g.close()
+
+
+@pytest.mark.parametrize("offset", [30.0, 1000.0])
+def test_scan_under_cancellation(offset):
+    """Squared distances of vectors far from the origin and close to each other.  On the matrix cores
+    the scan scores |x|^2 + |q|^2 - 2 <x, q>, which loses the significant digits of such distances
+    (at offset 1000 every digit: norms of 6.4e7 against distances of 0.6); the margin it keeps and the
+    direct-form scores the selection gives its finalists must return the oracle's answer within the
+    tolerance all the same.  Tiles of one query and of many (a batch of 1 and of 200 that share lists)."""
+    rng = np.random.default_rng(1234)
+    d, nlist = 64, 32
+    C = (offset + rng.standard_normal((nlist, d))).astype(np.float32)
+    w = synth.Workload("scan-cancellation", "l2", d, nlist, 64, 8, 20, np.zeros((0, d), np.float32), C,
+                       np.zeros((0, d), np.float32), np.zeros((0, d), np.float32), 1, 0)
+    g, o = make_pair(w, pool_blocks=1200, candidates_per_query=60000)
+    y = (C[rng.integers(0, nlist, 50000)] + 0.1 * rng.standard_normal((50000, d))).astype(np.float32)
+    g.add(dev(y)); o.add(y)
+    assert np.array_equal(g.list_sizes(), o.list_sizes())
+    q = (C[rng.integers(0, nlist, 200)] + 0.1 * rng.standard_normal((200, d))).astype(np.float32)
+    for nq in (1, 200):
+        rd, ri = o.search(q[:nq], 20, 8)
+        for mode in scan_modes(g):
+            dd, ii = g.search(dev(q[:nq]), 20, 8)
+            assert g.poll_error() == 0
+            assert_topk_matches("l2", dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6,
+                                what=f"offset {offset} batch {nq} scan_mfma {mode}")
     g.close()
 
 

@@ -57,6 +57,7 @@ def test_random_operations_against_the_oracle(seed):
         g.set_codebooks(dev(cb)); o.set_codebooks(cb)
     g.set_param("use_mfma", c["mfma"])
     g.set_param("ordered_add", c["ordered"])
+    arith = np.random.default_rng(seed + 1)  # which arithmetic each search scans with (a stream of its own)
     if c["n_base"]:
         g.add(dev(base[:c["n_base"]])); o.add(base[:c["n_base"]])
     added = c["n_base"]
@@ -80,12 +81,14 @@ def test_random_operations_against_the_oracle(seed):
             k = int(rng.choice([1, 3, 10, 50, 100, 128]))
             nprobe = int(rng.integers(1, min(64, nlist) + 1))
             q = draw(nq)
+            scan_mfma = int(arith.random() < 0.7)
+            g.set_param("scan_mfma", scan_mfma)  # dot products on the matrix cores, or on the vector unit
             dd, ii = g.search(dev(q), k, nprobe)
             torch.cuda.synchronize()
             assert g.poll_error() == 0, f"step {step}"
             rd, ri = o.search(q, k, nprobe)
             assert_topk_matches(metric, dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=1e-4,
-                                atol=1e-5 if pq else 1e-6, what=f"step {step}: nq {nq} k {k} nprobe {nprobe}")
+                                atol=1e-5 if pq else 1e-6, what=f"step {step}: nq {nq} k {k} nprobe {nprobe} scan_mfma {scan_mfma}")
     torch.cuda.synchronize()
     g.validate()
     assert g.poll_error() == 0
