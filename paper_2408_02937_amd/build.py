@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librtams.so")
-SOURCES = ["rtams.hip", "coarse.hip", "coarse_mfma.hip", "insert.hip", "pq.hip", "probe.hip", "group.hip", "scan.hip",
+SOURCES = ["rtams.hip", "coarse.hip", "coarse_mfma.hip", "insert.hip", "pq.hip", "probe.hip", "group.hip", "scan.hip", "scan_mm.hip",
            "pq_scan.hip", "select.hip", "rearrange.hip", "maint.hip"]
 HEADERS = ["rtams_dev.h", "rtams_launch.h", "search_common.h", os.path.join("..", "..", "include", "rtams.h")]
 

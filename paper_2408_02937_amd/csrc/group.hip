@@ -201,11 +201,11 @@ __device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, in
 
 // ------------------------------------------------------------ pair grouping
 // The (query, probed list) pairs of a request are grouped by list, so that the
-// scan reads a list once for up to kScanTileQueries queries.  One workgroup:
+// scan reads a list once for up to tile_q queries (the scan kernel's choice).  One workgroup:
 // prefix sums over the lists of the pair counts, the work-item counts and the
 // work, then the item descriptors, the split of the items over the 8 XCDs and
 // the grouped pair array.  A work item is (list, segment of seg_groups
-// 64-vector groups, tile of up to kScanTileQueries of the queries probing the
+// 64-vector groups, tile of up to tile_q of the queries probing the
 // list); one wavefront walks it.  The items of one segment follow each other, so
 // they run at the same time on the same CU or on its neighbours and the segment
 // comes from HBM once.  Segments bound the work of one item, so that long lists
@@ -327,7 +327,8 @@ __device__ void scatter_pairs(const Dev &D, int nq, int nprobe, int max_nprobe, 
 __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int nprobe, int max_nprobe, int k,
                                                          const float *__restrict__ Q,
                                                          uint32_t item_budget, uint32_t max_per_xcd,
-                                                         SearchScratch S) {
+                                                         uint32_t tile_q, int min_choice, SearchScratch S) {
+  const int tile_shift = 31 - __clz((int)tile_q);  // tiles hold a power of two of queries
   if (blockIdx.x == 1) {  // uniform over the workgroup: this one groups the pairs by list
     scatter_pairs(D, nq, nprobe, max_nprobe, S);
     return;
@@ -356,7 +357,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
   // Cost of a list for the split over the XCDs, per group of 64 vectors: reading it once from HBM
   // (each XCD has its own link to memory) plus the arithmetic of every query that probes it.  On
   // this chip one group's bytes cost about as much as the arithmetic of 12 queries (L2) or 24 (IP).
-  const uint32_t byte_weight = D.metric == 0 ? 12u : 24u;
+  const uint32_t byte_weight = D.scan_byte_weight > 0 ? (uint32_t)D.scan_byte_weight : D.metric == 0 ? 12u : 24u;
 
   // The probed lists, compacted in list order (neighbouring lists sit in neighbouring blocks after a
   // bulk load, and the scan reads faster in that order): entry = {list, first pair, pairs, length}.
@@ -419,7 +420,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
           n_c + s_rows[t * kWavesG + wave] + (uint32_t)__popcll(flags[t] & ((1ull << lane) - 1ull));
       plist[at] = make_uint4((uint32_t)(lb + t * kGroupThreads + tid), 0u, c[t], len[t]);
       const uint32_t groups = (len[t] + kWave - 1) / kWave;
-      const uint32_t tiles = (c[t] + kScanTileQueries - 1) / kScanTileQueries;
+      const uint32_t tiles = (c[t] + tile_q - 1) >> tile_shift;
 #pragma unroll
       for (int e = 0; e < kSegChoices; ++e) {
         const uint32_t sg = 2u << e;
@@ -444,7 +445,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
   const uint32_t e0 = min(n_c, (uint32_t)tid * per), e1 = min(n_c, e0 + per);
   __syncthreads();
   int choice = kSegChoices - 1;
-  for (int e = 0; e < kSegChoices; ++e)
+  for (int e = min_choice; e < kSegChoices; ++e)
     if (s_items[e] <= item_budget && s_items[e] <= S.item_cap) { choice = e; break; }
 
   for (;; ++choice) {  // uniform: every thread sees the same totals
@@ -461,7 +462,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
         if (!c) continue;
         const uint32_t groups = (pl[t].w + kWave - 1) / kWave;
         np += c;
-        ni += (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
+        ni += (groups ? (groups + seg - 1) / seg : 1u) * ((c + tile_q - 1) >> tile_shift);
         wk += (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
       }
     }
@@ -489,7 +490,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
           const uint32_t groups = (pl[t].w + kWave - 1) / kWave;
           const unsigned long long w = (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
           const uint32_t n =
-              (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
+              (groups ? (groups + seg - 1) / seg : 1u) * ((c + tile_q - 1) >> tile_shift);
           for (uint32_t x = 1; x < 8; ++x) {  // the cut falls inside this list: at the item the same share of it ends at
             const unsigned long long cut = total_work * x / 8;
             if (ws <= cut && cut < ws + w) s_begin[x] = is + (uint32_t)((cut - ws) * n / w);
@@ -537,7 +538,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
           plist[eb + t] = make_uint4(pl[t].x, ps, c, pl[t].w);
           pistart[eb + t] = is;
           ps += c;
-          is += (groups ? (groups + seg - 1) / seg : 1u) * ((c + kScanTileQueries - 1) / kScanTileQueries);
+          is += (groups ? (groups + seg - 1) / seg : 1u) * ((c + tile_q - 1) >> tile_shift);
         }
       }
     }
@@ -559,7 +560,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
         uint32_t n = 0, tiles = 1, small = 0, extra = 0;
         if (pl.z) {
           const uint32_t groups = (pl.w + kWave - 1) / kWave;
-          tiles = (pl.z + kScanTileQueries - 1) / kScanTileQueries;
+          tiles = (pl.z + tile_q - 1) >> tile_shift;
           n = (groups ? (groups + seg - 1) / seg : 1u) * tiles;
           small = pl.z / tiles;
           extra = pl.z - small * tiles;  // the first `extra` tiles hold one more
@@ -606,7 +607,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
         const uint4 pl = s_huge_pl[h];
         const uint32_t first = s_huge_ist[h];
         const uint32_t groups = (pl.w + kWave - 1) / kWave;
-        const uint32_t tiles = (pl.z + kScanTileQueries - 1) / kScanTileQueries;
+        const uint32_t tiles = (pl.z + tile_q - 1) >> tile_shift;
         const uint32_t n = (groups ? (groups + seg - 1) / seg : 1u) * tiles;
         const uint32_t small = pl.z / tiles, extra = pl.z - small * tiles;
         for (uint32_t i = (uint32_t)tid; i < n; i += kGroupThreads) {
@@ -688,9 +689,10 @@ void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int k, c
     return;
   }
   // workgroup 0 cuts the work items, workgroup 1 groups the pairs, workgroup 2 + q sets the bound of query q
+  const ScanShape sh = scan_shape(D, nq, item_budget);
   hipLaunchKernelGGL(k_group, dim3(2 + (unsigned)nq), dim3(kGroupThreads), 0, s, D, (int)nq, nprobe,
                      max_nprobe, k, Q, (uint32_t)item_budget,
-                     (uint32_t)(scan_grid(D, item_budget) / (int)kXcds * scan_waves(D)), S);
+                     (uint32_t)(sh.grid / (int)kXcds * sh.items_per_wg), (uint32_t)sh.tile_q, sh.min_choice, S);
 }
 
 }  // namespace rtams

@@ -150,6 +150,10 @@ void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int k, c
                   int item_budget, const SearchScratch &S, hipStream_t s);
 void launch_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const float *Q, int item_budget,
                  const SearchScratch &S, hipStream_t s);
+// the scan of flat float lists on the matrix cores (launch_scan hands such requests on to it)
+struct ScanShape;
+void launch_scan_mm(const Dev &D, const ScanShape &sh, int max_nprobe, const float *Q, const SearchScratch &S,
+                    hipStream_t s);
 // the scan over product-quantiser codes (launch_scan hands quantised lists on to it)
 void launch_pq_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int item_budget,
                     const SearchScratch &S, hipStream_t s);

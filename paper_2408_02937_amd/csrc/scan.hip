@@ -223,204 +223,6 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
   __builtin_amdgcn_wave_barrier();  // the LDS slice is rewritten by the next item
 }
 
-// ------------------------------------------------ the same item on the matrix cores
-// Flat float lists: the scores of a tile are a small dense contraction (vectors x queries over the
-// dimensions), and the interleaved layout hands a wavefront exactly the operand the 4x4x1 matrix
-// instruction wants: lane = vector, one coordinate per instruction (search_common.h).  The tile's
-// queries sit in LDS as before, in QG groups of four (rows past the tile's last query are zero); lane
-// l reads the float4 of query 4 g + l % 4 once per chunk and group of queries, and four matrix
-// instructions per group of vectors use it up.  Per 1 KiB of list data that is 4 QG matrix
-// instructions of 8 cycles instead of 16 to 64 vector instructions of 4, and the vector unit is left
-// with |x|^2 (squared distances only), so the kernel sits on the memory side.
-// Inner products are returned as the contraction leaves them.  Squared distances take the norm form
-// |x|^2 + |q|^2 - 2 <x, q>, whose rounding errors scale with the norms: the bound they are compared
-// with was loosened by the proven margin, and the selection scores its finalists again in the direct
-// form, so what is returned is exactly what the direct form gives.
-// Afterwards lane l holds, for each group of queries g, the scores of vectors 4 (l / 4) .. + 3 of both
-// groups of vectors against ONE query, 4 g + l % 4: it knows that query's length, bound and record
-// arrays, counts its own survivors, a prefix sum over the lanes of the same query hands out the places,
-// and one lane per query reserves them with one atomic.
-template <int METRIC, int QG>
-__device__ __forceinline__ void scan_item_mfma(const Dev &D, const SearchScratch &S,
-                                               const float *__restrict__ Q, int max_nprobe, int list,
-                                               uint32_t first, uint32_t nq_item, uint32_t g_begin,
-                                               uint32_t g_count, float4 *qs) {
-  constexpr int kPrefetch = 2;
-  constexpr int NQP = 4 * QG;  // rows of queries in LDS, the tile's own first
-  const int d4 = D.d4;
-  const int qstride = d4 + 1;  // float4s between two queries in LDS: an odd stride keeps the four rows a read touches on different banks
-  const int lane = threadIdx.x & (kWave - 1);
-  const int sub = lane & 3;
-  uint32_t my_q = 0, my_len = 0, my_off = 0, my_bound = 0, my_qn = 0;
-  uint64_t my_keys = 0, my_poss = 0;
-  if (lane < (int)nq_item) {
-    const uint32_t pk = S.grouped[first + lane];
-    my_q = pk >> 10;
-    const size_t o = (size_t)my_q * max_nprobe + (pk & 1023u);
-    my_len = S.probe_len[o];
-    my_off = S.probe_off[o];
-    const unsigned long long qb = S.qbase[my_q];
-    my_keys = (uint64_t)(uintptr_t)rec_keys_of(S, qb);
-    my_poss = (uint64_t)(uintptr_t)rec_poss_of(S, qb);
-    my_bound = S.bound[my_q];
-    if (METRIC == 0) my_qn = __float_as_uint(S.qnorm[my_q]);
-  }
-  uint32_t maxlen = 0;
-#pragma unroll
-  for (int i = 0; i < NQP; ++i) {
-    const uint32_t q = (uint32_t)__builtin_amdgcn_readlane((int)my_q, i);
-    const uint32_t len = (uint32_t)__builtin_amdgcn_readlane((int)my_len, i);
-    maxlen = len > maxlen ? len : maxlen;
-    const float4 *src = reinterpret_cast<const float4 *>(Q + (size_t)q * D.d);
-    const bool real = i < (int)nq_item;  // uniform
-    for (int c = lane; c < d4; c += kWave) qs[i * qstride + c] = real ? src[c] : make_float4(0.f, 0.f, 0.f, 0.f);
-  }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  // what this lane needs to know of its query in each group of queries
-  uint32_t len_g[QG], off_g[QG], bound_g[QG], qidx_g[QG];
-  float qn_g[QG];
-  uint64_t keys_g[QG], poss_g[QG];
-#pragma unroll
-  for (int g = 0; g < QG; ++g) {
-    const int src = 4 * g + sub;
-    len_g[g] = (uint32_t)__shfl((int)my_len, src);  // 0 for rows past the tile: nothing of theirs is kept
-    off_g[g] = (uint32_t)__shfl((int)my_off, src);
-    bound_g[g] = (uint32_t)__shfl((int)my_bound, src);
-    qidx_g[g] = (uint32_t)__shfl((int)my_q, src);
-    qn_g[g] = __uint_as_float((uint32_t)__shfl((int)my_qn, src));
-    keys_g[g] = (uint64_t)(uint32_t)__shfl((int)(uint32_t)my_keys, src) |
-                ((uint64_t)(uint32_t)__shfl((int)(uint32_t)(my_keys >> 32), src) << 32);
-    poss_g[g] = (uint64_t)(uint32_t)__shfl((int)(uint32_t)my_poss, src) |
-                ((uint64_t)(uint32_t)__shfl((int)(uint32_t)(my_poss >> 32), src) << 32);
-  }
-  const float4 *__restrict__ qrow = qs + sub * qstride;  // query sub of group 0; group g is 4 g rows on
-
-  uint32_t ngroups = (maxlen + kWave - 1) / kWave;
-  if (ngroups > g_begin + g_count) ngroups = g_begin + g_count;
-  const uint32_t gpb = (uint32_t)D.groups_per_block;
-  {  // never index the block table past the list's chain, whatever the descriptors say
-    const uint32_t have = D.nblk[list] * gpb;
-    if (ngroups > have) ngroups = have;
-  }
-  const size_t group_stride = (size_t)d4 * kWave;
-  for (uint32_t g0 = g_begin; g0 < ngroups; g0 += 2) {
-    const bool two = g0 + 1 < ngroups;  // uniform over the wavefront
-    const uint32_t g1 = two ? g0 + 1 : g0;
-    const uint32_t b0 = (uint32_t)*table_entry(D, list, g0 / gpb);
-    const uint32_t b1 = (uint32_t)*table_entry(D, list, g1 / gpb);
-    const float4 *__restrict__ xa = block_vecs(D, b0) + (size_t)(g0 % gpb) * group_stride + lane;
-    const float4 *__restrict__ xb = block_vecs(D, b1) + (size_t)(g1 % gpb) * group_stride + lane;
-    MfmaAcc acc0[QG], acc1[QG];
-#pragma unroll
-    for (int g = 0; g < QG; ++g) { acc0[g] = (MfmaAcc){0.f, 0.f, 0.f, 0.f}; acc1[g] = (MfmaAcc){0.f, 0.f, 0.f, 0.f}; }
-    float n0 = 0.f, n1 = 0.f;  // |x|^2 of the lane's own two vectors
-    auto use = [&](const float4 &x0, const float4 &x1, int c) {
-      if (METRIC == 0) { accumulate<1>(n0, x0, x0); accumulate<1>(n1, x1, x1); }
-      // every accumulator takes the coordinates in their order; the 2 QG chains are interleaved so that
-      // no instruction waits for the one in front of it
-      float4 y[QG];
-#pragma unroll
-      for (int g = 0; g < QG; ++g) y[g] = qrow[4 * g * qstride + c];
-#pragma unroll
-      for (int g = 0; g < QG; ++g) { mfma_step(acc0[g], x0.x, y[g].x); mfma_step(acc1[g], x1.x, y[g].x); }
-#pragma unroll
-      for (int g = 0; g < QG; ++g) { mfma_step(acc0[g], x0.y, y[g].y); mfma_step(acc1[g], x1.y, y[g].y); }
-#pragma unroll
-      for (int g = 0; g < QG; ++g) { mfma_step(acc0[g], x0.z, y[g].z); mfma_step(acc1[g], x1.z, y[g].z); }
-#pragma unroll
-      for (int g = 0; g < QG; ++g) { mfma_step(acc0[g], x0.w, y[g].w); mfma_step(acc1[g], x1.w, y[g].w); }
-    };
-    const int d4_main = d4 & ~(2 * kPrefetch - 1);
-    if (d4_main) {
-      float4 a0[kPrefetch], a1[kPrefetch], b0v[kPrefetch], b1v[kPrefetch];
-      auto load_set = [&](float4 *s0, float4 *s1, int cb) {
-#pragma unroll
-        for (int u = 0; u < kPrefetch; ++u) {
-          s0[u] = xa[(size_t)(cb + u) * kWave];
-          s1[u] = xb[(size_t)(cb + u) * kWave];
-        }
-        __builtin_amdgcn_sched_barrier(0);  // loads are issued here, not sunk towards their use
-      };
-      auto use_set = [&](const float4 *s0, const float4 *s1, int cb) {
-#pragma unroll
-        for (int u = 0; u < kPrefetch; ++u) use(s0[u], s1[u], cb + u);
-        __builtin_amdgcn_sched_barrier(0);
-      };
-      load_set(a0, a1, 0);
-      int c = 0;
-#pragma unroll 1
-      for (; c + 2 * kPrefetch < d4_main; c += 2 * kPrefetch) {
-        load_set(b0v, b1v, c + kPrefetch);
-        use_set(a0, a1, c);
-        load_set(a0, a1, c + 2 * kPrefetch);
-        use_set(b0v, b1v, c + kPrefetch);
-      }
-      load_set(b0v, b1v, c + kPrefetch);
-      use_set(a0, a1, c);
-      use_set(b0v, b1v, c + kPrefetch);
-    }
-    for (int c = d4_main; c < d4; ++c) use(xa[(size_t)c * kWave], xb[(size_t)c * kWave], c);
-
-    // scores -> keys; which of the lane's 8 candidates per group of queries survive
-    const uint32_t vbase0 = g0 * kWave + 4u * (uint32_t)(lane >> 2), vbase1 = vbase0 + kWave;
-    uint32_t key0[QG][4], key1[QG][4], pass[QG], cnt[QG];
-    bool any = false;
-    {
-      const float nr0[4] = {quad_broadcast<0>(n0), quad_broadcast<1>(n0), quad_broadcast<2>(n0), quad_broadcast<3>(n0)};
-      const float nr1[4] = {quad_broadcast<0>(n1), quad_broadcast<1>(n1), quad_broadcast<2>(n1), quad_broadcast<3>(n1)};
-#pragma unroll
-      for (int g = 0; g < QG; ++g) {
-        pass[g] = 0u;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          float s0 = acc0[g][r], s1 = acc1[g][r];
-          if (METRIC == 0) {
-            s0 = fmaf(-2.f, s0, nr0[r] + qn_g[g]);
-            s1 = fmaf(-2.f, s1, nr1[r] + qn_g[g]);
-          } else {
-            s0 = -s0; s1 = -s1;
-          }
-          key0[g][r] = key_of_float(s0 + 0.0f);
-          key1[g][r] = key_of_float(s1 + 0.0f);
-          if (vbase0 + r < len_g[g] && key0[g][r] <= bound_g[g]) pass[g] |= 1u << r;
-          if (two && vbase1 + r < len_g[g] && key1[g][r] <= bound_g[g]) pass[g] |= 16u << r;
-        }
-        cnt[g] = (uint32_t)__popc(pass[g]);
-        any = any || cnt[g] != 0u;
-      }
-    }
-    if (__ballot(any) != 0ull) {  // uniform
-#pragma unroll
-      for (int g = 0; g < QG; ++g) {
-        // places: running count over the lanes of the same query (every fourth lane), then one atomic per query
-        uint32_t incl = cnt[g];
-#pragma unroll
-        for (int o = 4; o < kWave; o <<= 1) {
-          const uint32_t t = (uint32_t)__shfl_up((int)incl, o);
-          if (lane >= o) incl += t;
-        }
-        uint32_t base = 0;
-        if (lane >= kWave - 4 && incl != 0u) base = atomicAdd(&S.rec_cnt[qidx_g[g]], incl);  // lanes 60..63 hold the totals
-        base = (uint32_t)__shfl((int)base, kWave - 4 + sub);
-        if (pass[g]) {
-          uint32_t slot = base + incl - cnt[g];
-          GlobalU32 *rk = (GlobalU32 *)(keys_g[g] + 4ull * slot);
-          GlobalU32 *rp = (GlobalU32 *)(poss_g[g] + 4ull * slot);
-          uint32_t at = 0;
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            if (pass[g] & (1u << r)) { rk[at] = key0[g][r]; rp[at] = off_g[g] + vbase0 + r; ++at; }
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            if (pass[g] & (16u << r)) { rk[at] = key1[g][r]; rp[at] = off_g[g] + vbase1 + r; ++at; }
-        }
-      }
-    }
-  }
-  __builtin_amdgcn_wave_barrier();  // the LDS slice is rewritten by the next item
-}
-
 // The hardware's workgroup dispatcher is the work queue (a new workgroup starts
 // wherever room frees up).  A workgroup is four wavefronts that take four
 // consecutive work items, one each, and work on their own: own slice of LDS, no
@@ -430,10 +232,10 @@ __device__ __forceinline__ void scan_item_mfma(const Dev &D, const SearchScratch
 // 4 (i / 8) + 3 of that XCD's range of items (a contiguous range of lists).
 // Wavefronts past the end of their range leave at once.
 
-template <int METRIC, int ST, bool MM>
+template <int METRIC, int ST>
 __global__ __launch_bounds__(kScanWaves * kWave) void k_scan(Dev D, int max_nprobe,
                                                              const float *__restrict__ Q, SearchScratch S) {
-  extern __shared__ float4 qs_all[];  // [wavefronts][kScanTileQueries][d / 4 + 1]
+  extern __shared__ float4 qs_all[];  // [wavefronts][kScanTileQueries][d / 4]
   const ScanQueues *Qs = S.queues;
   const uint32_t x = blockIdx.x % kXcds;
   const uint32_t wave = threadIdx.x / kWave, waves = blockDim.x / kWave;
@@ -441,19 +243,12 @@ __global__ __launch_bounds__(kScanWaves * kWave) void k_scan(Dev D, int max_npro
   if (item >= Qs->begin[x + 1]) return;
   const uint32_t seg = Qs->seg_groups;
   if (seg == 0) return;
-  float4 *qs = qs_all + (size_t)wave * kScanTileQueries * (D.d4 + 1);
+  float4 *qs = qs_all + (size_t)wave * kScanTileQueries * D.d4;
   const uint4 desc = S.tile_desc[item];
   const int list = __builtin_amdgcn_readfirstlane((int)desc.x);
   const uint32_t first = (uint32_t)__builtin_amdgcn_readfirstlane((int)desc.y);
   const uint32_t pairs = (uint32_t)__builtin_amdgcn_readfirstlane((int)desc.z);
   const uint32_t g_begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)desc.w) * seg;
-  // MM: flat float lists scored on the matrix cores, every tile of the request (so that a (query,
-  // vector) pair gets the same bits whatever tile it falls into, the bound's sample included).
-  if (MM) {
-    if (pairs > 4) scan_item_mfma<METRIC, 2>(D, S, Q, max_nprobe, list, first, pairs, g_begin, seg, qs);
-    else if (pairs > 0) scan_item_mfma<METRIC, 1>(D, S, Q, max_nprobe, list, first, pairs, g_begin, seg, qs);
-    return;
-  }
   switch (pairs) {
     case 0: break;
     case 1: scan_item<METRIC, 1, ST>(D, S, Q, max_nprobe, list, first, g_begin, seg, qs); break;
@@ -475,22 +270,19 @@ void launch_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const flo
     launch_pq_scan(D, nq, nprobe, max_nprobe, item_budget, S, s);
     return;
   }
-  dim3 grid((unsigned)scan_grid(D, item_budget));
-  const int waves = scan_waves(D);
-  const size_t lds = (size_t)waves * kScanTileQueries * (D.d + 4) * sizeof(float);
-  const dim3 block(waves * kWave);
-  if (D.scan_mfma && D.storage == 0) {
-    if (D.metric == 0) hipLaunchKernelGGL((k_scan<0, 0, true>), grid, block, lds, s, D, max_nprobe, Q, S);
-    else hipLaunchKernelGGL((k_scan<1, 0, true>), grid, block, lds, s, D, max_nprobe, Q, S);
+  const ScanShape sh = scan_shape(D, nq, item_budget);
+  if (sh.mm) {
+    launch_scan_mm(D, sh, max_nprobe, Q, S, s);
     return;
   }
+  const dim3 grid((unsigned)sh.grid), block((unsigned)sh.threads);
   switch (D.metric * 3 + D.storage) {
-    case 0: hipLaunchKernelGGL((k_scan<0, 0, false>), grid, block, lds, s, D, max_nprobe, Q, S); break;
-    case 1: hipLaunchKernelGGL((k_scan<0, 1, false>), grid, block, lds, s, D, max_nprobe, Q, S); break;
-    case 2: hipLaunchKernelGGL((k_scan<0, 2, false>), grid, block, lds, s, D, max_nprobe, Q, S); break;
-    case 3: hipLaunchKernelGGL((k_scan<1, 0, false>), grid, block, lds, s, D, max_nprobe, Q, S); break;
-    case 4: hipLaunchKernelGGL((k_scan<1, 1, false>), grid, block, lds, s, D, max_nprobe, Q, S); break;
-    default: hipLaunchKernelGGL((k_scan<1, 2, false>), grid, block, lds, s, D, max_nprobe, Q, S); break;
+    case 0: hipLaunchKernelGGL((k_scan<0, 0>), grid, block, sh.lds, s, D, max_nprobe, Q, S); break;
+    case 1: hipLaunchKernelGGL((k_scan<0, 1>), grid, block, sh.lds, s, D, max_nprobe, Q, S); break;
+    case 2: hipLaunchKernelGGL((k_scan<0, 2>), grid, block, sh.lds, s, D, max_nprobe, Q, S); break;
+    case 3: hipLaunchKernelGGL((k_scan<1, 0>), grid, block, sh.lds, s, D, max_nprobe, Q, S); break;
+    case 4: hipLaunchKernelGGL((k_scan<1, 1>), grid, block, sh.lds, s, D, max_nprobe, Q, S); break;
+    default: hipLaunchKernelGGL((k_scan<1, 2>), grid, block, sh.lds, s, D, max_nprobe, Q, S); break;
   }
 }
 

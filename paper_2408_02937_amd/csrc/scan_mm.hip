@@ -1,0 +1,357 @@
+// The list scan of flat float lists on the matrix cores.
+#include "search_common.h"
+
+namespace rtams {
+
+// The scores of a tile are a small dense contraction (vectors x queries over the dimensions), and the
+// interleaved layout hands a wavefront exactly the operand the 4x4x1 matrix instruction wants: lane =
+// vector, one coordinate per instruction (search_common.h).  A workgroup takes one work item (list,
+// segment, tile of up to 4 QGMAX of the queries probing the list).  The tile's queries go to LDS once,
+// in groups of four (rows past the tile's last query are zero), each with the words the scan needs of
+// it: how far its list goes, its bound, where its survivor records go.  Then the four wavefronts share
+// out the segment's groups of 64 vectors, NG at a time, and work on their own: per chunk of 4
+// dimensions a wavefront loads 1 KiB per group of vectors ONCE, lane l reads the float4 of query
+// 4 g + l % 4 of every group of queries g, and four matrix instructions per group of vectors and of
+// queries use them up.  Per 1 KiB of list data that is 4 matrix instructions of 8 cycles for every 4
+// queries, against 16 to 32 vector instructions of 4 cycles, and the vector unit is left with |x|^2
+// (squared distances only): the kernel sits on the memory side, and a list is read once per 32 of
+// the queries that probe it.
+// Inner products are returned as the contraction leaves them (the bound's sample uses the same
+// instruction sequence, so a pair scores the same bits there and here).  Squared distances take the
+// norm form |x|^2 + |q|^2 - 2 <x, q>, whose rounding errors scale with the norms: the bound they are
+// compared with was loosened by the proven margin, and the selection scores its finalists again in
+// the direct form, so what is returned is exactly what the direct form gives.
+// Afterwards lane l holds, for each group of queries g, the scores of vectors 4 (l / 4) .. + 3 of each
+// group of vectors against ONE query, 4 g + l % 4.  What is not worse than that query's bound goes to a
+// staging area of the wavefront in LDS (places from ballots, no waiting); when the area is full, and
+// when the wavefront is through with its groups, the staged survivors are counted per query with LDS
+// atomics, ONE global atomic instruction reserves the places of all the tile's queries, and the
+// records go out.  (A returning global atomic per group of queries and of vectors, waited for each
+// time, cost more than the scan itself: dozens of wavefronts reserve from the same few counters.)
+
+struct TileQuery {  // kMmQueryWords 32-bit words
+  uint32_t q, len, off, bound;
+  float qn;
+  uint32_t pad[3];
+  uint64_t keys, poss;  // addresses of the query's survivor records (keys, positions)
+};
+static_assert(sizeof(TileQuery) == kMmQueryWords * 4, "words per query of a tile");
+
+template <int CAP>
+struct WaveStage {  // survivors of one wavefront on their way out
+  uint32_t key[CAP], pos[CAP];
+  uint8_t row[CAP];  // which query of the tile
+  uint32_t qcnt[32], qbase[32];
+};
+static_assert(sizeof(WaveStage<256>) == mm_stage_bytes(256) && sizeof(WaveStage<512>) == mm_stage_bytes(512),
+              "staging bytes per wavefront");
+
+template <int METRIC, int QG, int NG>
+__device__ __forceinline__ void scan_groups_mm(const Dev &D, const SearchScratch &S, int list, uint32_t g_lo,
+                                               uint32_t g_hi, const float4 *qs, const TileQuery *tq,
+                                               WaveStage<mm_stage_cap(NG)> &st) {
+  constexpr int kCap = mm_stage_cap(NG);  // a group of queries yields at most 4 NG 64 survivors at once: they always fit an empty area
+  constexpr int kPrefetch = NG == 1 ? 4 : 2;  // chunks per register set: 8 KiB of loads in flight per wavefront
+  const int d4 = D.d4;
+  const int qstride = d4 + 1;  // float4s between two queries in LDS: an odd stride keeps the four rows a read touches on different banks
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int sub = lane & 3;
+  const float4 *__restrict__ qrow = qs + sub * qstride;  // query `sub` of group 0; group g is 4 g rows on
+  const uint32_t gpb = (uint32_t)D.groups_per_block;
+  const size_t group_stride = (size_t)d4 * kWave;
+  uint32_t staged = 0;  // survivors in the staging area (uniform over the wavefront)
+  auto wave_sync = [] {  // LDS operations of one wavefront execute in order; keep the compiler from moving them
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  };
+  auto flush = [&]() __attribute__((always_inline)) {
+    if (lane < 32) st.qcnt[lane] = 0u;
+    wave_sync();
+    constexpr int kMine = kCap / kWave;
+    uint32_t rank[kMine], row[kMine];
+#pragma unroll
+    for (int u = 0; u < kMine; ++u) {
+      const uint32_t e = (uint32_t)lane + u * kWave;
+      row[u] = e < staged ? st.row[e] : 0u;
+      rank[u] = e < staged ? atomicAdd(&st.qcnt[row[u]], 1u) : 0u;  // place among the query's survivors of this flush
+    }
+    wave_sync();
+    if (lane < 32) {
+      const uint32_t c = st.qcnt[lane];
+      st.qbase[lane] = c ? atomicAdd(&S.rec_cnt[tq[lane].q], c) : 0u;  // rows past the tile's last query have none
+    }
+    wave_sync();
+#pragma unroll
+    for (int u = 0; u < kMine; ++u) {
+      const uint32_t e = (uint32_t)lane + u * kWave;
+      if (e < staged) {
+        // (a pointer rebuilt from integers has no address space: say "global", or the stores become FLAT
+        // operations, and while one of those is pending every wait of the load pipeline has to be for
+        // ALL outstanding memory operations)
+        const uint64_t at = 4ull * (st.qbase[row[u]] + rank[u]);
+        *(GlobalU32 *)(tq[row[u]].keys + at) = st.key[e];
+        *(GlobalU32 *)(tq[row[u]].poss + at) = st.pos[e];
+      }
+    }
+    wave_sync();
+    staged = 0;
+  };
+  for (uint32_t g0 = g_lo + (uint32_t)wave * NG; g0 < g_hi; g0 += kMmWaves * NG) {
+    const bool two = NG == 2 && g0 + 1 < g_hi;  // uniform over the wavefront
+    const uint32_t g1 = two ? g0 + 1 : g0;
+    const uint32_t b0 = (uint32_t)*table_entry(D, list, g0 / gpb);
+    const uint32_t b1 = NG == 2 ? (uint32_t)*table_entry(D, list, g1 / gpb) : b0;
+    const float4 *__restrict__ xa = block_vecs(D, b0) + (size_t)(g0 % gpb) * group_stride + lane;
+    const float4 *__restrict__ xb = block_vecs(D, b1) + (size_t)(g1 % gpb) * group_stride + lane;
+    MfmaAcc acc[NG][QG];
+#pragma unroll
+    for (int v = 0; v < NG; ++v)
+#pragma unroll
+      for (int g = 0; g < QG; ++g) acc[v][g] = (MfmaAcc){0.f, 0.f, 0.f, 0.f};
+    float nrm[NG];  // |x|^2 of the lane's own vectors
+#pragma unroll
+    for (int v = 0; v < NG; ++v) nrm[v] = 0.f;
+    // every accumulator takes the coordinates in their order; the NG QG chains are interleaved so that
+    // no instruction waits for the one in front of it
+    auto use = [&](const float4 *x, int c) {
+      if (METRIC == 0) {
+#pragma unroll
+        for (int v = 0; v < NG; ++v) accumulate<1>(nrm[v], x[v], x[v]);
+      }
+      constexpr int kHalf = QG == 6 ? 3 : QG > 4 ? 4 : QG;  // groups of queries whose coordinates are held at once (a divisor of QG)
+#pragma unroll
+      for (int h = 0; h < QG; h += kHalf) {
+        float4 y[kHalf];
+#pragma unroll
+        for (int g = 0; g < kHalf; ++g) y[g] = qrow[4 * (h + g) * qstride + c];
+#pragma unroll
+        for (int g = 0; g < kHalf; ++g)
+#pragma unroll
+          for (int v = 0; v < NG; ++v) mfma_step(acc[v][h + g], x[v].x, y[g].x);
+#pragma unroll
+        for (int g = 0; g < kHalf; ++g)
+#pragma unroll
+          for (int v = 0; v < NG; ++v) mfma_step(acc[v][h + g], x[v].y, y[g].y);
+#pragma unroll
+        for (int g = 0; g < kHalf; ++g)
+#pragma unroll
+          for (int v = 0; v < NG; ++v) mfma_step(acc[v][h + g], x[v].z, y[g].z);
+#pragma unroll
+        for (int g = 0; g < kHalf; ++g)
+#pragma unroll
+          for (int v = 0; v < NG; ++v) mfma_step(acc[v][h + g], x[v].w, y[g].w);
+      }
+    };
+    const int d4_main = d4 & ~(2 * kPrefetch - 1);
+    if (d4_main) {
+      float4 sa[kPrefetch][NG], sb[kPrefetch][NG];
+      auto load_set = [&](float4 (*s)[NG], int cb) {
+#pragma unroll
+        for (int u = 0; u < kPrefetch; ++u) {
+          s[u][0] = xa[(size_t)(cb + u) * kWave];
+          if (NG == 2) s[u][NG - 1] = xb[(size_t)(cb + u) * kWave];
+        }
+        __builtin_amdgcn_sched_barrier(0);  // loads are issued here, not sunk towards their use
+      };
+      auto use_set = [&](float4 (*s)[NG], int cb) {
+#pragma unroll
+        for (int u = 0; u < kPrefetch; ++u) use(s[u], cb + u);
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      load_set(sa, 0);
+      int c = 0;
+#pragma unroll 1
+      for (; c + 2 * kPrefetch < d4_main; c += 2 * kPrefetch) {
+        load_set(sb, c + kPrefetch);
+        use_set(sa, c);
+        load_set(sa, c + 2 * kPrefetch);
+        use_set(sb, c + kPrefetch);
+      }
+      load_set(sb, c + kPrefetch);
+      use_set(sa, c);
+      use_set(sb, c + kPrefetch);
+    }
+    for (int c = d4_main; c < d4; ++c) {
+      float4 x[NG];
+      x[0] = xa[(size_t)c * kWave];
+      if (NG == 2) x[NG - 1] = xb[(size_t)c * kWave];
+      use(x, c);
+    }
+
+    // scores -> keys; which of the lane's 4 NG candidates per group of queries survive
+    float nr[NG][4];
+#pragma unroll
+    for (int v = 0; v < NG; ++v) {
+      nr[v][0] = quad_broadcast<0>(nrm[v]); nr[v][1] = quad_broadcast<1>(nrm[v]);
+      nr[v][2] = quad_broadcast<2>(nrm[v]); nr[v][3] = quad_broadcast<3>(nrm[v]);
+    }
+    const uint32_t vbase = g0 * kWave + 4u * (uint32_t)(lane >> 2);  // the next group of vectors is 64 on
+#pragma unroll
+    for (int g = 0; g < QG; ++g) {
+      const TileQuery me = tq[4 * g + sub];  // len 0 for rows past the tile: nothing of theirs is kept
+      uint32_t key[NG][4], pass = 0u;
+#pragma unroll
+      for (int v = 0; v < NG; ++v)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float sc = acc[v][g][r];
+          sc = METRIC == 0 ? fmaf(-2.f, sc, nr[v][r] + me.qn) : -sc;
+          key[v][r] = key_of_float(sc + 0.0f);
+          if ((v == 0 || two) && vbase + v * kWave + r < me.len && key[v][r] <= me.bound) pass |= 1u << (4 * v + r);
+        }
+      if (__ballot(pass != 0u) == 0ull) continue;  // uniform
+      // places in the staging area: candidate i of every lane, lane after lane, then candidate i + 1
+      uint32_t at[4 * NG], total = 0;
+#pragma unroll
+      for (int i = 0; i < 4 * NG; ++i) {
+        const unsigned long long m = __ballot((pass >> i) & 1u);
+        at[i] = total + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+        total += (uint32_t)__popcll(m);
+      }
+      if (staged + total > (uint32_t)kCap) flush();  // uniform
+#pragma unroll
+      for (int v = 0; v < NG; ++v)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (pass & (1u << (4 * v + r))) {
+            const uint32_t e = staged + at[4 * v + r];
+            st.key[e] = key[v][r];
+            st.pos[e] = me.off + vbase + v * kWave + r;
+            st.row[e] = (uint8_t)(4 * g + sub);
+          }
+      staged += total;
+    }
+  }
+  if (staged) flush();
+}
+
+// Hardware hands consecutive workgroup ids to the 8 XCDs in turn, so workgroup i runs on XCD i % 8 and
+// takes item i / 8 of that XCD's range of items (a contiguous range of lists); workgroups past the end
+// of their range leave at once.
+template <int METRIC, int QGMAX>
+__global__ __launch_bounds__(kMmWaves *kWave) void k_scan_mm(Dev D, int max_nprobe, const float *__restrict__ Q,
+                                                             SearchScratch S, int tile_rows) {
+  extern __shared__ float4 lds_mm[];  // [tile_rows][d / 4 + 1] coordinates of the tile's queries, [tile_rows] TileQuery, [wavefronts] WaveStage
+  const ScanQueues *Qs = S.queues;
+  const uint32_t x = blockIdx.x % kXcds;
+  const uint32_t item = Qs->begin[x] + blockIdx.x / kXcds;
+  if (item >= Qs->begin[x + 1]) return;
+  const uint32_t seg = Qs->seg_groups;
+  if (seg == 0) return;
+  const uint4 desc = S.tile_desc[item];
+  const int list = (int)desc.x;
+  const uint32_t first = desc.y, pairs = desc.z;
+  if (pairs == 0) return;
+  const int d4 = D.d4, qstride = d4 + 1;
+  float4 *qs = lds_mm;
+  TileQuery *tq = reinterpret_cast<TileQuery *>(lds_mm + (size_t)tile_rows * qstride);
+  constexpr int kNG = QGMAX == 2 ? 2 : 1;  // groups of vectors a wavefront takes at a time
+  WaveStage<mm_stage_cap(kNG)> &st = reinterpret_cast<WaveStage<mm_stage_cap(kNG)> *>(tq + tile_rows)[threadIdx.x / kWave];
+  // groups of four queries of this tile: 1, 2, 3, 4, 6 or 8, whichever holds the item's queries; exactly
+  // that many rows of LDS are set up, and the instantiation below reads exactly that many (the plan never
+  // puts more queries into a tile than tile_rows)
+  int qg = (int)((pairs + 3u) / 4u);
+  qg = qg == 5 ? 6 : qg == 7 ? 8 : qg;
+  const int rows = 4 * qg;
+  if (rows > tile_rows || qg > QGMAX) return;  // a descriptor the launch was not sized for: nothing is scanned
+  // the tile's queries: words first (one thread per row), then coordinates (the workgroup together)
+  uint32_t my_len = 0;
+  if ((int)threadIdx.x < rows) {
+    TileQuery t{};
+    if (threadIdx.x < pairs) {
+      const uint32_t pk = S.grouped[first + threadIdx.x];
+      t.q = pk >> 10;
+      const size_t o = (size_t)t.q * max_nprobe + (pk & 1023u);
+      t.len = S.probe_len[o];
+      t.off = S.probe_off[o];
+      const unsigned long long qb = S.qbase[t.q];
+      t.keys = (uint64_t)(uintptr_t)rec_keys_of(S, qb);
+      t.poss = (uint64_t)(uintptr_t)rec_poss_of(S, qb);
+      t.bound = S.bound[t.q];
+      if (METRIC == 0) t.qn = S.qnorm[t.q];
+    }
+    tq[threadIdx.x] = t;
+    my_len = t.len;
+  }
+  // coordinates: the rows x d / 4 float4s of the tile are dealt out over the workgroup, eight independent
+  // loads per thread in flight (a row at a time would be a chain of memory latencies per row); which
+  // query a row holds is read from the grouped pairs again rather than waited for in LDS
+  {
+    const int total = rows * d4;
+    constexpr int kInFlight = 8, kThreads = kMmWaves * kWave;
+    for (int base = (int)threadIdx.x; base < total; base += kInFlight * kThreads) {
+      uint32_t pk[kInFlight];
+      int row[kInFlight], col[kInFlight];
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u) {
+        const int idx = base + u * kThreads;
+        row[u] = idx < total ? idx / d4 : rows;
+        col[u] = idx - row[u] * d4;
+        pk[u] = row[u] < (int)pairs ? S.grouped[first + row[u]] : 0u;
+      }
+      float4 v[kInFlight];
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u)
+        v[u] = row[u] < (int)pairs ? reinterpret_cast<const float4 *>(Q + (size_t)(pk[u] >> 10) * D.d)[col[u]]
+                                   : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u)
+        if (row[u] < rows) qs[row[u] * qstride + col[u]] = v[u];
+    }
+  }
+  // how far the longest of the tile's snapshots goes (the first wavefront holds the lengths)
+  __shared__ uint32_t s_maxlen;
+  if (threadIdx.x < kWave) {
+    uint32_t m = my_len;
+    for (int o = kWave / 2; o > 0; o >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, o));
+    if (threadIdx.x == 0) s_maxlen = m;
+  }
+  __syncthreads();
+  const uint32_t g_begin = desc.w * seg;
+  uint32_t g_end = (s_maxlen + kWave - 1) / kWave;  // groups any query of the tile wants
+  if (g_end > g_begin + seg) g_end = g_begin + seg;  // ... inside this item's segment
+  {  // never index the block table past the list's chain, whatever the descriptors say
+    const uint32_t have = D.nblk[list] * (uint32_t)D.groups_per_block;
+    if (g_end > have) g_end = have;
+  }
+  // no barrier from here on: the wavefronts only read the tile
+  if constexpr (QGMAX == 2) {
+    if (qg == 1) scan_groups_mm<METRIC, 1, 2>(D, S, list, g_begin, g_end, qs, tq, st);
+    else scan_groups_mm<METRIC, 2, 2>(D, S, list, g_begin, g_end, qs, tq, st);
+  } else {
+    switch (qg) {
+      case 1: scan_groups_mm<METRIC, 1, 1>(D, S, list, g_begin, g_end, qs, tq, st); break;
+      case 2: scan_groups_mm<METRIC, 2, 1>(D, S, list, g_begin, g_end, qs, tq, st); break;
+      case 3: scan_groups_mm<METRIC, 3, 1>(D, S, list, g_begin, g_end, qs, tq, st); break;
+      case 4: scan_groups_mm<METRIC, 4, 1>(D, S, list, g_begin, g_end, qs, tq, st); break;
+      case 6: scan_groups_mm<METRIC, 6, 1>(D, S, list, g_begin, g_end, qs, tq, st); break;
+      default: scan_groups_mm<METRIC, 8, 1>(D, S, list, g_begin, g_end, qs, tq, st); break;
+    }
+  }
+}
+
+template <typename K>
+static void allow_large_lds(K kernel) {
+  // above 64 KiB of dynamic LDS a kernel has to be told (wide vectors only); once per kernel and process
+  (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMmLdsMax);
+}
+
+void launch_scan_mm(const Dev &D, const ScanShape &sh, int max_nprobe, const float *Q, const SearchScratch &S,
+                    hipStream_t s) {
+  static const bool once = [] {
+    allow_large_lds(k_scan_mm<0, 2>); allow_large_lds(k_scan_mm<0, 8>);
+    allow_large_lds(k_scan_mm<1, 2>); allow_large_lds(k_scan_mm<1, 8>);
+    return true;
+  }();
+  (void)once;
+  const dim3 grid((unsigned)sh.grid), block((unsigned)sh.threads);
+  if (D.metric == 0) {
+    if (sh.qgmax == 8) hipLaunchKernelGGL((k_scan_mm<0, 8>), grid, block, sh.lds, s, D, max_nprobe, Q, S, sh.tile_q);
+    else hipLaunchKernelGGL((k_scan_mm<0, 2>), grid, block, sh.lds, s, D, max_nprobe, Q, S, sh.tile_q);
+  } else {
+    if (sh.qgmax == 8) hipLaunchKernelGGL((k_scan_mm<1, 8>), grid, block, sh.lds, s, D, max_nprobe, Q, S, sh.tile_q);
+    else hipLaunchKernelGGL((k_scan_mm<1, 2>), grid, block, sh.lds, s, D, max_nprobe, Q, S, sh.tile_q);
+  }
+}
+
+}  // namespace rtams

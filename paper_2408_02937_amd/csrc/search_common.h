@@ -331,20 +331,65 @@ __device__ __host__ inline bool uses_norm_form(const Dev &D) {
 constexpr uint32_t kXcds = 8;
 constexpr int kScanWaves = 4;
 
-// Wavefronts per workgroup of the scan: as many (4, 2, 1) as fit their query tiles into 64 KiB of LDS
-inline int scan_waves(const Dev &D) {
-  const size_t per_wave = (size_t)kScanTileQueries * (D.d + 4) * sizeof(float);  // a tile's queries, rows one float4 apart
-  int waves = kScanWaves;
-  while (waves > 1 && per_wave * waves > 65536) waves /= 2;
-  return waves;
-}
+// Launch shape of a list scan.  Two kernels share the plan of work items (list, segment, tile of the
+// queries probing the list):
+//  - vector unit (narrow storage, or the matrix cores switched off): a workgroup is up to four
+//    wavefronts that take four consecutive items, one each, every one with its own tile of up to 8
+//    queries in LDS;
+//  - matrix cores (flat float lists): a workgroup takes ONE item, its tile of up to 32 queries sits in
+//    LDS once, and its four wavefronts share out the item's groups of vectors.  Large tiles are what
+//    keeps a hot list from being read once per 8 of the dozens of queries that probe it; the price is
+//    registers (fewer wavefronts per SIMD), so small requests, whose tiles are small anyway, run an
+//    instantiation with tiles of up to 8.
+struct ScanShape {
+  bool mm;           // the matrix-core kernel
+  int tile_q;        // queries of a tile at most
+  int qgmax;         // matrix cores: groups of four queries the instantiation holds (2 or 8)
+  int min_choice;    // shortest segment the plan may choose: 2 << min_choice groups of 64 vectors
+  int items_per_wg;  // items a workgroup takes
+  int threads;       // of a workgroup
+  int grid;          // workgroups
+  size_t lds;        // dynamic LDS bytes of a workgroup
+};
+constexpr int kMmWaves = 4;            // wavefronts of a workgroup of the matrix-core scan
+constexpr int kMmQueryWords = 12;      // 32-bit words of LDS per query of a tile beside its coordinates
+// survivors a wavefront stages in LDS before it reserves their places (it takes ng groups of 64 vectors at a
+// time), and the bytes that takes: keys, positions, rows, and two words for each of 32 queries
+constexpr int mm_stage_cap(int ng) { return 256 * ng; }
+constexpr size_t mm_stage_bytes(int cap) { return (size_t)cap * 9 + 256; }
+constexpr size_t kMmLdsMax = 160 * 1024 - 1024;  // what a workgroup may take of the CU's 160 KiB
 
-// workgroups of the scan launch for a budget of work items (one wavefront each):
-// room for an uneven split of the items over the XCDs
-inline int scan_grid(const Dev &D, int item_budget) {
-  const int waves = scan_waves(D);
-  const int wgs = (item_budget + item_budget / 2 + waves - 1) / waves;
-  return (wgs + (int)kXcds - 1) / (int)kXcds * (int)kXcds;
+inline ScanShape scan_shape(const Dev &D, int64_t nq, int item_budget) {
+  ScanShape sh{};
+  sh.mm = D.scan_mfma != 0 && D.storage == 0 && D.pq_m == 0;
+  // room for an uneven split of the items over the XCDs
+  const int items = item_budget + item_budget / 2;
+  if (!sh.mm) {
+    const size_t per_wave = (size_t)kScanTileQueries * D.d * sizeof(float);
+    int waves = kScanWaves;  // as many (4, 2, 1) as fit their query tiles into 64 KiB of LDS
+    while (waves > 1 && per_wave * waves > 65536) waves /= 2;
+    sh.tile_q = kScanTileQueries;
+    sh.min_choice = 0;
+    sh.items_per_wg = waves;
+    sh.threads = waves * kWave;
+    sh.lds = per_wave * waves;
+    sh.grid = ((items + waves - 1) / waves + (int)kXcds - 1) / (int)kXcds * (int)kXcds;
+    return sh;
+  }
+  const size_t row = (size_t)(D.d + 4) * sizeof(float) + kMmQueryWords * 4;  // a query of the tile: coordinates, one float4 of padding, its words
+  sh.qgmax = nq >= 64 ? 8 : 2;
+  int rows = 4 * sh.qgmax;
+  // two workgroups of the large-tile kernel should fit a CU side by side; a tile is never below 8 queries
+  const size_t stage = kMmWaves * mm_stage_bytes(mm_stage_cap(sh.qgmax == 2 ? 2 : 1));
+  while (rows > 8 && row * rows + stage > 64 * 1024) rows /= 2;
+  while (rows > 4 && row * rows + stage > kMmLdsMax) rows /= 2;
+  sh.tile_q = rows;
+  sh.min_choice = sh.qgmax == 8 ? 3 : 0;  // large tiles: at least 16 groups to an item (setting up a tile of 32 queries has to pay)
+  sh.items_per_wg = 1;
+  sh.threads = kMmWaves * kWave;
+  sh.lds = row * rows + stage;
+  sh.grid = (items + (int)kXcds - 1) / (int)kXcds * (int)kXcds;
+  return sh;
 }
 
 constexpr int kGroupThreads = 1024;  // workgroup of the planning kernels (k_group, k_pq_bound)
