@@ -221,6 +221,7 @@ struct rtams_index {
   std::atomic<int64_t> use_mfma{1};  // matrix-core filter in front of the exact coarse arithmetic
   std::atomic<int64_t> scan_mfma{1}; // flat float lists: the scan's dot products on the matrix cores
   std::atomic<int64_t> scan_byte_weight{0};
+  std::atomic<int64_t> scan_min_choice{-1};
   std::mutex prof_mutex;
   double scan_ms = 0.0;      // sum of measured scan-kernel durations
   int64_t scan_launches = 0;
@@ -622,6 +623,7 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   Dev D = ix->dev;
   D.scan_mfma = D.pq_m == 0 && D.storage == RTAMS_F32 && ix->scan_mfma.load(std::memory_order_relaxed) != 0;
   D.scan_byte_weight = (int32_t)ix->scan_byte_weight.load(std::memory_order_relaxed);
+  D.scan_min_choice = (int32_t)ix->scan_min_choice.load(std::memory_order_relaxed);
   const SearchScratch &S = ix->res[r].s;
   // a rearrangement is switching block tables: start behind its last switch
   if (ix->fence_cur) (void)hipStreamWaitEvent(s, ix->fence_cur, 0);
@@ -944,6 +946,7 @@ int rtams_set_param(rtams_index *ix, const char *key, int64_t value) {
   if (!strcmp(key, "ordered_add")) { ix->ordered_add = value; return RTAMS_OK; }
   if (!strcmp(key, "use_mfma")) { ix->use_mfma = value; return RTAMS_OK; }
   if (!strcmp(key, "scan_mfma")) { ix->scan_mfma = value; return RTAMS_OK; }
+  if (!strcmp(key, "scan_min_choice")) { ix->scan_min_choice = value < 0 ? -1 : value > 7 ? 7 : value; return RTAMS_OK; }
   if (!strcmp(key, "scan_byte_weight")) { ix->scan_byte_weight = value > 0 ? value : 0; return RTAMS_OK; }
   if (!strcmp(key, "scan_max_items")) { ix->scan_max_items = value > 1024 ? value : 1024; return RTAMS_OK; }
   if (!strcmp(key, "scan_items_per_pair")) { ix->scan_items_per_pair = value > 0 ? value : 1; return RTAMS_OK; }

@@ -48,8 +48,8 @@ static_assert(sizeof(WaveStage<256>) == mm_stage_bytes(256) && sizeof(WaveStage<
 
 template <int METRIC, int QG, int NG>
 __device__ __forceinline__ void scan_groups_mm(const Dev &D, const SearchScratch &S, int list, uint32_t g_lo,
-                                               uint32_t g_hi, const float4 *qs, const TileQuery *tq,
-                                               WaveStage<mm_stage_cap(NG)> &st) {
+                                               uint32_t g_hi, uint32_t first_b0, uint32_t first_b1, const float4 *qs,
+                                               const TileQuery *tq, WaveStage<mm_stage_cap(NG)> &st) {
   constexpr int kCap = mm_stage_cap(NG);  // a group of queries yields at most 4 NG 64 survivors at once: they always fit an empty area
   constexpr int kPrefetch = NG == 1 ? 4 : 2;  // chunks per register set: 8 KiB of loads in flight per wavefront
   const int d4 = D.d4;
@@ -96,13 +96,46 @@ __device__ __forceinline__ void scan_groups_mm(const Dev &D, const SearchScratch
     wave_sync();
     staged = 0;
   };
-  for (uint32_t g0 = g_lo + (uint32_t)wave * NG; g0 < g_hi; g0 += kMmWaves * NG) {
+  // The wavefront's groups of vectors, NG at a time, as a software pipeline ACROSS the groups: while one
+  // is being streamed the block numbers of the next are looked up, and the first loads of the next go out
+  // before the survivors of this one are dealt with, so that neither the two dependent table reads nor
+  // the first trip to memory of a group stand between two groups (a quarter of a group's time at d = 128).
+  // (the early loads hold a register set across the survivors' code: the instantiation for small tiles,
+  // which takes two groups at a time, would drop from 4 to 3 wavefronts per SIMD and goes without)
+  constexpr bool kEarlyLoad = NG == 1;
+  const int d4_main = d4 & ~(2 * kPrefetch - 1);  // chunks that go through the two register sets
+  float4 sa[kPrefetch][NG], sb[kPrefetch][NG];
+  auto load_set = [&](float4 (*s)[NG], const float4 *__restrict__ pa, const float4 *__restrict__ pb, int cb) {
+#pragma unroll
+    for (int u = 0; u < kPrefetch; ++u) {
+      s[u][0] = pa[(size_t)(cb + u) * kWave];
+      if (NG == 2) s[u][NG - 1] = pb[(size_t)(cb + u) * kWave];
+    }
+    __builtin_amdgcn_sched_barrier(0);  // loads are issued here, not sunk towards their use
+  };
+  auto blocks_of = [&](uint32_t g0, uint32_t &b0, uint32_t &b1) {
+    const uint32_t g1 = NG == 2 && g0 + 1 < g_hi ? g0 + 1 : g0;
+    b0 = (uint32_t)*table_entry(D, list, g0 / gpb);
+    b1 = NG == 2 ? (uint32_t)*table_entry(D, list, g1 / gpb) : b0;
+  };
+  auto place = [&](uint32_t g0, uint32_t b0, uint32_t b1, const float4 *&pa, const float4 *&pb) {
+    const uint32_t g1 = NG == 2 && g0 + 1 < g_hi ? g0 + 1 : g0;
+    pa = block_vecs(D, b0) + (size_t)(g0 % gpb) * group_stride + lane;
+    pb = block_vecs(D, b1) + (size_t)(g1 % gpb) * group_stride + lane;
+  };
+  uint32_t g0 = g_lo + (uint32_t)wave * NG;
+  if (g0 >= g_hi) return;  // nothing staged yet
+  const float4 *xa, *xb;
+  {
+    place(g0, first_b0, first_b1, xa, xb);  // looked up by the caller while the tile was set up
+    if (kEarlyLoad && d4_main) load_set(sa, xa, xb, 0);
+  }
+  for (;;) {
     const bool two = NG == 2 && g0 + 1 < g_hi;  // uniform over the wavefront
-    const uint32_t g1 = two ? g0 + 1 : g0;
-    const uint32_t b0 = (uint32_t)*table_entry(D, list, g0 / gpb);
-    const uint32_t b1 = NG == 2 ? (uint32_t)*table_entry(D, list, g1 / gpb) : b0;
-    const float4 *__restrict__ xa = block_vecs(D, b0) + (size_t)(g0 % gpb) * group_stride + lane;
-    const float4 *__restrict__ xb = block_vecs(D, b1) + (size_t)(g1 % gpb) * group_stride + lane;
+    const uint32_t g_next = g0 + kMmWaves * NG;
+    const bool more = g_next < g_hi;  // uniform
+    uint32_t nb0 = 0, nb1 = 0;
+    if (more) blocks_of(g_next, nb0, nb1);  // on their way while this group is streamed
     MfmaAcc acc[NG][QG];
 #pragma unroll
     for (int v = 0; v < NG; ++v)
@@ -142,32 +175,22 @@ __device__ __forceinline__ void scan_groups_mm(const Dev &D, const SearchScratch
           for (int v = 0; v < NG; ++v) mfma_step(acc[v][h + g], x[v].w, y[g].w);
       }
     };
-    const int d4_main = d4 & ~(2 * kPrefetch - 1);
-    if (d4_main) {
-      float4 sa[kPrefetch][NG], sb[kPrefetch][NG];
-      auto load_set = [&](float4 (*s)[NG], int cb) {
+    auto use_set = [&](float4 (*s)[NG], int cb) {
 #pragma unroll
-        for (int u = 0; u < kPrefetch; ++u) {
-          s[u][0] = xa[(size_t)(cb + u) * kWave];
-          if (NG == 2) s[u][NG - 1] = xb[(size_t)(cb + u) * kWave];
-        }
-        __builtin_amdgcn_sched_barrier(0);  // loads are issued here, not sunk towards their use
-      };
-      auto use_set = [&](float4 (*s)[NG], int cb) {
-#pragma unroll
-        for (int u = 0; u < kPrefetch; ++u) use(s[u], cb + u);
-        __builtin_amdgcn_sched_barrier(0);
-      };
-      load_set(sa, 0);
+      for (int u = 0; u < kPrefetch; ++u) use(s[u], cb + u);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    if (d4_main) {  // (with early loads set a holds chunks 0 .. kPrefetch - 1 of this group already)
+      if (!kEarlyLoad) load_set(sa, xa, xb, 0);
       int c = 0;
 #pragma unroll 1
       for (; c + 2 * kPrefetch < d4_main; c += 2 * kPrefetch) {
-        load_set(sb, c + kPrefetch);
+        load_set(sb, xa, xb, c + kPrefetch);
         use_set(sa, c);
-        load_set(sa, c + 2 * kPrefetch);
+        load_set(sa, xa, xb, c + 2 * kPrefetch);
         use_set(sb, c + kPrefetch);
       }
-      load_set(sb, c + kPrefetch);
+      load_set(sb, xa, xb, c + kPrefetch);
       use_set(sa, c);
       use_set(sb, c + kPrefetch);
     }
@@ -176,6 +199,11 @@ __device__ __forceinline__ void scan_groups_mm(const Dev &D, const SearchScratch
       x[0] = xa[(size_t)c * kWave];
       if (NG == 2) x[NG - 1] = xb[(size_t)c * kWave];
       use(x, c);
+    }
+    const float4 *na = xa, *nb = xb;
+    if (more) {  // the next group's first loads go out before this group's survivors are dealt with
+      place(g_next, nb0, nb1, na, nb);
+      if (kEarlyLoad && d4_main) load_set(sa, na, nb, 0);
     }
 
     // scores -> keys; which of the lane's 4 NG candidates per group of queries survive
@@ -221,6 +249,10 @@ __device__ __forceinline__ void scan_groups_mm(const Dev &D, const SearchScratch
           }
       staged += total;
     }
+    if (!more) break;
+    g0 = g_next;
+    xa = na;
+    xb = nb;
   }
   if (staged) flush();
 }
@@ -254,6 +286,18 @@ __global__ __launch_bounds__(kMmWaves *kWave) void k_scan_mm(Dev D, int max_npro
   qg = qg == 5 ? 6 : qg == 7 ? 8 : qg;
   const int rows = 4 * qg;
   if (rows > tile_rows || qg > QGMAX) return;  // a descriptor the launch was not sized for: nothing is scanned
+  // The block numbers of the wavefront's first groups of vectors are asked for now (two dependent reads)
+  // and used after the tile is set up.  Never past the list's chain, whatever the descriptors say.
+  const uint32_t g_begin = desc.w * seg;
+  const uint32_t g_have = D.nblk[list] * (uint32_t)D.groups_per_block;
+  uint32_t first_b0 = 0, first_b1 = 0;
+  {
+    const uint32_t g0 = g_begin + (threadIdx.x / kWave) * kNG;
+    if (g0 < g_have) first_b0 = (uint32_t)*table_entry(D, list, g0 / (uint32_t)D.groups_per_block);
+    first_b1 = first_b0;
+    // (should the second group turn out to lie past what the tile wants, its loads are not used)
+    if (kNG == 2 && g0 + 1 < g_have) first_b1 = (uint32_t)*table_entry(D, list, (g0 + 1) / (uint32_t)D.groups_per_block);
+  }
   // the tile's queries: words first (one thread per row), then coordinates (the workgroup together)
   uint32_t my_len = 0;
   if ((int)threadIdx.x < rows) {
@@ -307,25 +351,21 @@ __global__ __launch_bounds__(kMmWaves *kWave) void k_scan_mm(Dev D, int max_npro
     if (threadIdx.x == 0) s_maxlen = m;
   }
   __syncthreads();
-  const uint32_t g_begin = desc.w * seg;
   uint32_t g_end = (s_maxlen + kWave - 1) / kWave;  // groups any query of the tile wants
   if (g_end > g_begin + seg) g_end = g_begin + seg;  // ... inside this item's segment
-  {  // never index the block table past the list's chain, whatever the descriptors say
-    const uint32_t have = D.nblk[list] * (uint32_t)D.groups_per_block;
-    if (g_end > have) g_end = have;
-  }
+  if (g_end > g_have) g_end = g_have;
   // no barrier from here on: the wavefronts only read the tile
   if constexpr (QGMAX == 2) {
-    if (qg == 1) scan_groups_mm<METRIC, 1, 2>(D, S, list, g_begin, g_end, qs, tq, st);
-    else scan_groups_mm<METRIC, 2, 2>(D, S, list, g_begin, g_end, qs, tq, st);
+    if (qg == 1) scan_groups_mm<METRIC, 1, 2>(D, S, list, g_begin, g_end, first_b0, first_b1, qs, tq, st);
+    else scan_groups_mm<METRIC, 2, 2>(D, S, list, g_begin, g_end, first_b0, first_b1, qs, tq, st);
   } else {
     switch (qg) {
-      case 1: scan_groups_mm<METRIC, 1, 1>(D, S, list, g_begin, g_end, qs, tq, st); break;
-      case 2: scan_groups_mm<METRIC, 2, 1>(D, S, list, g_begin, g_end, qs, tq, st); break;
-      case 3: scan_groups_mm<METRIC, 3, 1>(D, S, list, g_begin, g_end, qs, tq, st); break;
-      case 4: scan_groups_mm<METRIC, 4, 1>(D, S, list, g_begin, g_end, qs, tq, st); break;
-      case 6: scan_groups_mm<METRIC, 6, 1>(D, S, list, g_begin, g_end, qs, tq, st); break;
-      default: scan_groups_mm<METRIC, 8, 1>(D, S, list, g_begin, g_end, qs, tq, st); break;
+      case 1: scan_groups_mm<METRIC, 1, 1>(D, S, list, g_begin, g_end, first_b0, first_b1, qs, tq, st); break;
+      case 2: scan_groups_mm<METRIC, 2, 1>(D, S, list, g_begin, g_end, first_b0, first_b1, qs, tq, st); break;
+      case 3: scan_groups_mm<METRIC, 3, 1>(D, S, list, g_begin, g_end, first_b0, first_b1, qs, tq, st); break;
+      case 4: scan_groups_mm<METRIC, 4, 1>(D, S, list, g_begin, g_end, first_b0, first_b1, qs, tq, st); break;
+      case 6: scan_groups_mm<METRIC, 6, 1>(D, S, list, g_begin, g_end, first_b0, first_b1, qs, tq, st); break;
+      default: scan_groups_mm<METRIC, 8, 1>(D, S, list, g_begin, g_end, first_b0, first_b1, qs, tq, st); break;
     }
   }
 }

@@ -384,7 +384,8 @@ inline ScanShape scan_shape(const Dev &D, int64_t nq, int item_budget) {
   while (rows > 8 && row * rows + stage > 64 * 1024) rows /= 2;
   while (rows > 4 && row * rows + stage > kMmLdsMax) rows /= 2;
   sh.tile_q = rows;
-  sh.min_choice = sh.qgmax == 8 ? 3 : 0;  // large tiles: at least 16 groups to an item (setting up a tile of 32 queries has to pay)
+  sh.min_choice = sh.qgmax == 8 ? 2 : 0;  // large tiles: at least 8 groups to an item, two for every wavefront (measured: 4 and 16 are slower)
+  if (D.scan_min_choice >= 0) sh.min_choice = D.scan_min_choice;
   sh.items_per_wg = 1;
   sh.threads = kMmWaves * kWave;
   sh.lds = row * rows + stage;
