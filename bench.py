@@ -385,6 +385,8 @@ def main() -> int:
     ap.add_argument("--latency-iters", type=int, default=0, help="requests per latency figure (default 300, 2000 for configuration 2)")
     ap.add_argument("--cpu-queries", type=int, default=0, help="queries of the oracle sample (default 128, 1024 for configuration 2); -1 skips it")
     ap.add_argument("--no-extras", action="store_true", help="only the timed steps (for profiler runs)")
+    ap.add_argument("--set", action="append", default=[], metavar="KEY=VALUE",
+                    help="a launch-shape parameter of the library (rtams_set_param), e.g. scan_mfma=0; may be repeated")
     ap.add_argument("--no-config2", action="store_true", help="leave out the short block for configuration 2")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only the plain copy kernel on 1 GiB (yardstick for the traffic counters)")
@@ -432,6 +434,9 @@ def main() -> int:
 
     b = Bench(torch, rtams, synth, args.config, args.scale, args.batch, args.search_streams)
     w = b.w
+    params = {k: int(v) for k, v in (kv.split("=") for kv in args.set)}
+    for key, value in params.items():
+        b.g.set_param(key, value)
     note(f"configuration {args.config}: {args.warmup} warm-up and {args.steps} timed steps")
     elapsed, scan_ms, scan_n = b.timed_steps(args.steps, args.warmup)
     qps = args.steps * b.B / elapsed
@@ -448,6 +453,8 @@ def main() -> int:
         "host_generation_s": b.host_generation_s,
         "rearrange_after_bulk_load_s": b.rearrange_after_load_s,
     }
+    if params:
+        result["config"]["library_parameters"] = params
     if not args.no_extras:
         big = args.config != 2
         iters = args.latency_iters or (300 if big else 2000)

@@ -689,7 +689,7 @@ void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int k, c
     return;
   }
   // workgroup 0 cuts the work items, workgroup 1 groups the pairs, workgroup 2 + q sets the bound of query q
-  const ScanShape sh = scan_shape(D, nq, item_budget);
+  const ScanShape sh = scan_shape(D, item_budget);
   hipLaunchKernelGGL(k_group, dim3(2 + (unsigned)nq), dim3(kGroupThreads), 0, s, D, (int)nq, nprobe,
                      max_nprobe, k, Q, (uint32_t)item_budget,
                      (uint32_t)(sh.grid / (int)kXcds * sh.items_per_wg), (uint32_t)sh.tile_q, sh.min_choice, S);

@@ -10,7 +10,7 @@
 #include <new>
 #include <shared_mutex>
 
-#include "rtams_launch.h"
+#include "search_common.h"
 
 using namespace rtams;
 
@@ -182,6 +182,7 @@ struct Resource {
   std::atomic<int> state{RES_FREE};
   hipEvent_t done = nullptr;
   hipEvent_t t0 = nullptr, t1 = nullptr;  // around the grouped scan when profiling is on
+  hipEvent_t scan_done = nullptr;         // behind the scan of the slot's request (large requests queue up their scans)
   bool timed = false;
   SearchScratch s{};
 };
@@ -222,6 +223,14 @@ struct rtams_index {
   std::atomic<int64_t> scan_mfma{1}; // flat float lists: the scan's dot products on the matrix cores
   std::atomic<int64_t> scan_byte_weight{0};
   std::atomic<int64_t> scan_min_choice{-1};
+  // Scans of large requests run one after the other, whatever streams they are on: such a scan fills the
+  // chip by itself, and two of them side by side only slow each other down (both finish when the sum of
+  // their work is done, instead of one after half of it); everything else of a request still overlaps
+  // with other requests' scans.  (Consideration 2 of the multi-stream section: what a kernel may take
+  // of the chip is limited so that kernels of other streams are not held up.)
+  std::mutex scan_mutex;
+  hipEvent_t scan_tail = nullptr;                 // behind the last large scan enqueued, or nullptr
+  std::atomic<int64_t> scan_exclusive_pairs{4096};  // (query, list) pairs from which a request's scan queues up; 0 never
   std::mutex prof_mutex;
   double scan_ms = 0.0;      // sum of measured scan-kernel durations
   int64_t scan_launches = 0;
@@ -496,6 +505,7 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
     S.req_cursor = reinterpret_cast<unsigned long long *>(p + SL.req_words + 8);
     if (hipMemset(p + SL.req_words, 0, 16) != hipSuccess) return bail(fail(RTAMS_EHIP, "hipMemset of the scratch failed"));
     if (hipEventCreateWithFlags(&ix->res[r].done, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&ix->res[r].scan_done, hipEventDisableTiming) != hipSuccess ||
         hipEventCreate(&ix->res[r].t0) != hipSuccess || hipEventCreate(&ix->res[r].t1) != hipSuccess)
       return bail(fail(RTAMS_EHIP, "hipEventCreate failed"));
   }
@@ -513,6 +523,7 @@ int rtams_destroy(rtams_index *ix) {
       (void)hipEventDestroy(ix->res[r].done);
       if (ix->res[r].t0) (void)hipEventDestroy(ix->res[r].t0);
       if (ix->res[r].t1) (void)hipEventDestroy(ix->res[r].t1);
+      if (ix->res[r].scan_done) (void)hipEventDestroy(ix->res[r].scan_done);
     }
   delete[] ix->res;
   if (ix->data_done) (void)hipEventDestroy(ix->data_done);
@@ -621,7 +632,10 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   if (r < 0) return fail(RTAMS_EBUSY, "all %d stream resources are in flight", ix->n_res);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   Dev D = ix->dev;
-  D.scan_mfma = D.pq_m == 0 && D.storage == RTAMS_F32 && ix->scan_mfma.load(std::memory_order_relaxed) != 0;
+  {  // flat float lists: large requests scan on the matrix cores (0 never, 1 from kMmMinBatch queries, 2 always)
+    const int64_t mode = ix->scan_mfma.load(std::memory_order_relaxed);
+    D.scan_mfma = D.pq_m == 0 && D.storage == RTAMS_F32 && (mode == 2 || (mode == 1 && nq >= kMmMinBatch));
+  }
   D.scan_byte_weight = (int32_t)ix->scan_byte_weight.load(std::memory_order_relaxed);
   D.scan_min_choice = (int32_t)ix->scan_min_choice.load(std::memory_order_relaxed);
   const SearchScratch &S = ix->res[r].s;
@@ -638,9 +652,20 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   if (budget < 1024) budget = 1024;
   launch_group(D, nq, nprobe, ix->cfg.max_nprobe, k, d_queries, (int)budget, S, s);
   const bool timed = ix->profile_scan.load(std::memory_order_relaxed) != 0;
-  if (timed) (void)hipEventRecord(ix->res[r].t0, s);
-  launch_scan(D, nq, nprobe, ix->cfg.max_nprobe, d_queries, (int)budget, S, s);
-  if (timed) { (void)hipEventRecord(ix->res[r].t1, s); ix->res[r].timed = true; }
+  const int64_t excl = ix->scan_exclusive_pairs.load(std::memory_order_relaxed);
+  if (excl > 0 && nq * nprobe >= excl) {  // a large scan: behind the large scan enqueued before it
+    std::lock_guard<std::mutex> chain(ix->scan_mutex);
+    if (ix->scan_tail && ix->scan_tail != ix->res[r].scan_done) (void)hipStreamWaitEvent(s, ix->scan_tail, 0);
+    if (timed) (void)hipEventRecord(ix->res[r].t0, s);
+    launch_scan(D, nq, nprobe, ix->cfg.max_nprobe, d_queries, (int)budget, S, s);
+    if (timed) { (void)hipEventRecord(ix->res[r].t1, s); ix->res[r].timed = true; }
+    (void)hipEventRecord(ix->res[r].scan_done, s);
+    ix->scan_tail = ix->res[r].scan_done;
+  } else {
+    if (timed) (void)hipEventRecord(ix->res[r].t0, s);
+    launch_scan(D, nq, nprobe, ix->cfg.max_nprobe, d_queries, (int)budget, S, s);
+    if (timed) { (void)hipEventRecord(ix->res[r].t1, s); ix->res[r].timed = true; }
+  }
   launch_select(D, nq, k, nprobe, ix->cfg.max_nprobe, d_queries, S, d_out_dist, d_out_ids, s);
   hipError_t e = hipGetLastError();
   hipError_t e2 = hipEventRecord(ix->res[r].done, s);
@@ -946,6 +971,7 @@ int rtams_set_param(rtams_index *ix, const char *key, int64_t value) {
   if (!strcmp(key, "ordered_add")) { ix->ordered_add = value; return RTAMS_OK; }
   if (!strcmp(key, "use_mfma")) { ix->use_mfma = value; return RTAMS_OK; }
   if (!strcmp(key, "scan_mfma")) { ix->scan_mfma = value; return RTAMS_OK; }
+  if (!strcmp(key, "scan_exclusive_pairs")) { ix->scan_exclusive_pairs = value > 0 ? value : 0; return RTAMS_OK; }
   if (!strcmp(key, "scan_min_choice")) { ix->scan_min_choice = value < 0 ? -1 : value > 7 ? 7 : value; return RTAMS_OK; }
   if (!strcmp(key, "scan_byte_weight")) { ix->scan_byte_weight = value > 0 ? value : 0; return RTAMS_OK; }
   if (!strcmp(key, "scan_max_items")) { ix->scan_max_items = value > 1024 ? value : 1024; return RTAMS_OK; }

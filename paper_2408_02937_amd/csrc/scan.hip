@@ -270,7 +270,7 @@ void launch_scan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const flo
     launch_pq_scan(D, nq, nprobe, max_nprobe, item_budget, S, s);
     return;
   }
-  const ScanShape sh = scan_shape(D, nq, item_budget);
+  const ScanShape sh = scan_shape(D, item_budget);
   if (sh.mm) {
     launch_scan_mm(D, sh, max_nprobe, Q, S, s);
     return;

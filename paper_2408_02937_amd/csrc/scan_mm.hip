@@ -6,28 +6,27 @@ namespace rtams {
 // The scores of a tile are a small dense contraction (vectors x queries over the dimensions), and the
 // interleaved layout hands a wavefront exactly the operand the 4x4x1 matrix instruction wants: lane =
 // vector, one coordinate per instruction (search_common.h).  A workgroup takes one work item (list,
-// segment, tile of up to 4 QGMAX of the queries probing the list).  The tile's queries go to LDS once,
-// in groups of four (rows past the tile's last query are zero), each with the words the scan needs of
+// segment, tile of up to 32 of the queries probing the list).  The tile's queries go to LDS once, in
+// groups of four (rows past the tile's last query are zero), each with the words the scan needs of
 // it: how far its list goes, its bound, where its survivor records go.  Then the four wavefronts share
-// out the segment's groups of 64 vectors, NG at a time, and work on their own: per chunk of 4
-// dimensions a wavefront loads 1 KiB per group of vectors ONCE, lane l reads the float4 of query
-// 4 g + l % 4 of every group of queries g, and four matrix instructions per group of vectors and of
-// queries use them up.  Per 1 KiB of list data that is 4 matrix instructions of 8 cycles for every 4
-// queries, against 16 to 32 vector instructions of 4 cycles, and the vector unit is left with |x|^2
-// (squared distances only): the kernel sits on the memory side, and a list is read once per 32 of
-// the queries that probe it.
+// out the segment's groups of 64 vectors and work on their own: per chunk of 4 dimensions a wavefront
+// loads 1 KiB ONCE, lane l reads the float4 of query 4 g + l % 4 of every group of queries g, and four
+// matrix instructions per group of queries use them up.  Per 1 KiB of list data that is 4 matrix
+// instructions of 8 cycles for every 4 queries, against 16 to 32 vector instructions of 4 cycles, and
+// the vector unit is left with |x|^2 (squared distances only): the kernel sits on the memory side,
+// and a list is read once per 32 of the queries that probe it.
 // Inner products are returned as the contraction leaves them (the bound's sample uses the same
 // instruction sequence, so a pair scores the same bits there and here).  Squared distances take the
 // norm form |x|^2 + |q|^2 - 2 <x, q>, whose rounding errors scale with the norms: the bound they are
 // compared with was loosened by the proven margin, and the selection scores its finalists again in
 // the direct form, so what is returned is exactly what the direct form gives.
-// Afterwards lane l holds, for each group of queries g, the scores of vectors 4 (l / 4) .. + 3 of each
-// group of vectors against ONE query, 4 g + l % 4.  What is not worse than that query's bound goes to a
-// staging area of the wavefront in LDS (places from ballots, no waiting); when the area is full, and
-// when the wavefront is through with its groups, the staged survivors are counted per query with LDS
-// atomics, ONE global atomic instruction reserves the places of all the tile's queries, and the
-// records go out.  (A returning global atomic per group of queries and of vectors, waited for each
-// time, cost more than the scan itself: dozens of wavefronts reserve from the same few counters.)
+// Afterwards lane l holds, for each group of queries g, the scores of vectors 4 (l / 4) .. + 3 against
+// ONE query, 4 g + l % 4.  What is not worse than that query's bound goes to a staging area of the
+// wavefront in LDS (places from ballots, no waiting); when the area is full, and when the wavefront
+// is through with its groups, the staged survivors are counted per query with LDS atomics, ONE
+// global atomic instruction reserves the places of all the tile's queries, and the records go out.
+// (A returning global atomic per group of queries and of vectors, waited for each time, cost more
+// than the scan itself: dozens of wavefronts reserve from the same few counters.)
 
 struct TileQuery {  // kMmQueryWords 32-bit words
   uint32_t q, len, off, bound;
@@ -37,21 +36,20 @@ struct TileQuery {  // kMmQueryWords 32-bit words
 };
 static_assert(sizeof(TileQuery) == kMmQueryWords * 4, "words per query of a tile");
 
-template <int CAP>
 struct WaveStage {  // survivors of one wavefront on their way out
-  uint32_t key[CAP], pos[CAP];
-  uint8_t row[CAP];  // which query of the tile
-  uint32_t qcnt[32], qbase[32];
+  uint32_t key[kMmStageCap], pos[kMmStageCap];
+  uint8_t row[kMmStageCap];  // which query of the tile
+  uint32_t qcnt[kMmTileMax], qbase[kMmTileMax];
 };
-static_assert(sizeof(WaveStage<256>) == mm_stage_bytes(256) && sizeof(WaveStage<512>) == mm_stage_bytes(512),
-              "staging bytes per wavefront");
+static_assert(sizeof(WaveStage) == kMmStageBytes, "staging bytes per wavefront");
 
-template <int METRIC, int QG, int NG>
+// The groups g_lo + wave, g_lo + wave + 4, ... below g_hi of the list against QG groups of four queries.
+// first_b: the block that holds the wavefront's first group (looked up by the caller).
+template <int METRIC, int QG>
 __device__ __forceinline__ void scan_groups_mm(const Dev &D, const SearchScratch &S, int list, uint32_t g_lo,
-                                               uint32_t g_hi, uint32_t first_b0, uint32_t first_b1, const float4 *qs,
-                                               const TileQuery *tq, WaveStage<mm_stage_cap(NG)> &st) {
-  constexpr int kCap = mm_stage_cap(NG);  // a group of queries yields at most 4 NG 64 survivors at once: they always fit an empty area
-  constexpr int kPrefetch = NG == 1 ? 4 : 2;  // chunks per register set: 8 KiB of loads in flight per wavefront
+                                               uint32_t g_hi, uint32_t first_b, const float4 *qs,
+                                               const TileQuery *tq, WaveStage &st) {
+  constexpr int kPrefetch = 4;  // chunks per register set: 8 KiB of loads in flight per wavefront
   const int d4 = D.d4;
   const int qstride = d4 + 1;  // float4s between two queries in LDS: an odd stride keeps the four rows a read touches on different banks
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -65,9 +63,9 @@ __device__ __forceinline__ void scan_groups_mm(const Dev &D, const SearchScratch
     __builtin_amdgcn_wave_barrier();
   };
   auto flush = [&]() __attribute__((always_inline)) {
-    if (lane < 32) st.qcnt[lane] = 0u;
+    if (lane < kMmTileMax) st.qcnt[lane] = 0u;
     wave_sync();
-    constexpr int kMine = kCap / kWave;
+    constexpr int kMine = kMmStageCap / kWave;
     uint32_t rank[kMine], row[kMine];
 #pragma unroll
     for (int u = 0; u < kMine; ++u) {
@@ -76,7 +74,7 @@ __device__ __forceinline__ void scan_groups_mm(const Dev &D, const SearchScratch
       rank[u] = e < staged ? atomicAdd(&st.qcnt[row[u]], 1u) : 0u;  // place among the query's survivors of this flush
     }
     wave_sync();
-    if (lane < 32) {
+    if (lane < kMmTileMax) {
       const uint32_t c = st.qcnt[lane];
       st.qbase[lane] = c ? atomicAdd(&S.rec_cnt[tq[lane].q], c) : 0u;  // rows past the tile's last query have none
     }
@@ -96,61 +94,37 @@ __device__ __forceinline__ void scan_groups_mm(const Dev &D, const SearchScratch
     wave_sync();
     staged = 0;
   };
-  // The wavefront's groups of vectors, NG at a time, as a software pipeline ACROSS the groups: while one
-  // is being streamed the block numbers of the next are looked up, and the first loads of the next go out
-  // before the survivors of this one are dealt with, so that neither the two dependent table reads nor
-  // the first trip to memory of a group stand between two groups (a quarter of a group's time at d = 128).
-  // (the early loads hold a register set across the survivors' code: the instantiation for small tiles,
-  // which takes two groups at a time, would drop from 4 to 3 wavefronts per SIMD and goes without)
-  constexpr bool kEarlyLoad = NG == 1;
+  // The wavefront's groups of vectors as a software pipeline ACROSS the groups: while one is being
+  // streamed the block number of the next is looked up, and the first loads of the next go out before
+  // the survivors of this one are dealt with, so that neither the two dependent table reads nor the
+  // first trip to memory of a group stand between two groups (a quarter of a group's time at d = 128).
   const int d4_main = d4 & ~(2 * kPrefetch - 1);  // chunks that go through the two register sets
-  float4 sa[kPrefetch][NG], sb[kPrefetch][NG];
-  auto load_set = [&](float4 (*s)[NG], const float4 *__restrict__ pa, const float4 *__restrict__ pb, int cb) {
+  float4 sa[kPrefetch], sb[kPrefetch];
+  auto load_set = [&](float4 *s, const float4 *__restrict__ p, int cb) {
 #pragma unroll
-    for (int u = 0; u < kPrefetch; ++u) {
-      s[u][0] = pa[(size_t)(cb + u) * kWave];
-      if (NG == 2) s[u][NG - 1] = pb[(size_t)(cb + u) * kWave];
-    }
+    for (int u = 0; u < kPrefetch; ++u) s[u] = p[(size_t)(cb + u) * kWave];
     __builtin_amdgcn_sched_barrier(0);  // loads are issued here, not sunk towards their use
   };
-  auto blocks_of = [&](uint32_t g0, uint32_t &b0, uint32_t &b1) {
-    const uint32_t g1 = NG == 2 && g0 + 1 < g_hi ? g0 + 1 : g0;
-    b0 = (uint32_t)*table_entry(D, list, g0 / gpb);
-    b1 = NG == 2 ? (uint32_t)*table_entry(D, list, g1 / gpb) : b0;
+  auto place = [&](uint32_t g, uint32_t b) -> const float4 * {
+    return block_vecs(D, b) + (size_t)(g % gpb) * group_stride + lane;
   };
-  auto place = [&](uint32_t g0, uint32_t b0, uint32_t b1, const float4 *&pa, const float4 *&pb) {
-    const uint32_t g1 = NG == 2 && g0 + 1 < g_hi ? g0 + 1 : g0;
-    pa = block_vecs(D, b0) + (size_t)(g0 % gpb) * group_stride + lane;
-    pb = block_vecs(D, b1) + (size_t)(g1 % gpb) * group_stride + lane;
-  };
-  uint32_t g0 = g_lo + (uint32_t)wave * NG;
+  uint32_t g0 = g_lo + (uint32_t)wave;
   if (g0 >= g_hi) return;  // nothing staged yet
-  const float4 *xa, *xb;
-  {
-    place(g0, first_b0, first_b1, xa, xb);  // looked up by the caller while the tile was set up
-    if (kEarlyLoad && d4_main) load_set(sa, xa, xb, 0);
-  }
+  const float4 *x = place(g0, first_b);
+  if (d4_main) load_set(sa, x, 0);
   for (;;) {
-    const bool two = NG == 2 && g0 + 1 < g_hi;  // uniform over the wavefront
-    const uint32_t g_next = g0 + kMmWaves * NG;
-    const bool more = g_next < g_hi;  // uniform
-    uint32_t nb0 = 0, nb1 = 0;
-    if (more) blocks_of(g_next, nb0, nb1);  // on their way while this group is streamed
-    MfmaAcc acc[NG][QG];
+    const uint32_t g_next = g0 + kMmWaves;
+    const bool more = g_next < g_hi;  // uniform over the wavefront
+    uint32_t next_b = 0;
+    if (more) next_b = (uint32_t)*table_entry(D, list, g_next / gpb);  // on its way while this group is streamed
+    MfmaAcc acc[QG];
 #pragma unroll
-    for (int v = 0; v < NG; ++v)
-#pragma unroll
-      for (int g = 0; g < QG; ++g) acc[v][g] = (MfmaAcc){0.f, 0.f, 0.f, 0.f};
-    float nrm[NG];  // |x|^2 of the lane's own vectors
-#pragma unroll
-    for (int v = 0; v < NG; ++v) nrm[v] = 0.f;
-    // every accumulator takes the coordinates in their order; the NG QG chains are interleaved so that
-    // no instruction waits for the one in front of it
-    auto use = [&](const float4 *x, int c) {
-      if (METRIC == 0) {
-#pragma unroll
-        for (int v = 0; v < NG; ++v) accumulate<1>(nrm[v], x[v], x[v]);
-      }
+    for (int g = 0; g < QG; ++g) acc[g] = (MfmaAcc){0.f, 0.f, 0.f, 0.f};
+    float nrm = 0.f;  // |x|^2 of the lane's own vector
+    // every accumulator takes the coordinates in their order; the chains of the groups of queries are
+    // interleaved so that no instruction waits for the one in front of it
+    auto use = [&](const float4 &v, int c) {
+      if (METRIC == 0) accumulate<1>(nrm, v, v);
       constexpr int kHalf = QG == 6 ? 3 : QG > 4 ? 4 : QG;  // groups of queries whose coordinates are held at once (a divisor of QG)
 #pragma unroll
       for (int h = 0; h < QG; h += kHalf) {
@@ -158,101 +132,77 @@ __device__ __forceinline__ void scan_groups_mm(const Dev &D, const SearchScratch
 #pragma unroll
         for (int g = 0; g < kHalf; ++g) y[g] = qrow[4 * (h + g) * qstride + c];
 #pragma unroll
-        for (int g = 0; g < kHalf; ++g)
+        for (int g = 0; g < kHalf; ++g) mfma_step(acc[h + g], v.x, y[g].x);
 #pragma unroll
-          for (int v = 0; v < NG; ++v) mfma_step(acc[v][h + g], x[v].x, y[g].x);
+        for (int g = 0; g < kHalf; ++g) mfma_step(acc[h + g], v.y, y[g].y);
 #pragma unroll
-        for (int g = 0; g < kHalf; ++g)
+        for (int g = 0; g < kHalf; ++g) mfma_step(acc[h + g], v.z, y[g].z);
 #pragma unroll
-          for (int v = 0; v < NG; ++v) mfma_step(acc[v][h + g], x[v].y, y[g].y);
-#pragma unroll
-        for (int g = 0; g < kHalf; ++g)
-#pragma unroll
-          for (int v = 0; v < NG; ++v) mfma_step(acc[v][h + g], x[v].z, y[g].z);
-#pragma unroll
-        for (int g = 0; g < kHalf; ++g)
-#pragma unroll
-          for (int v = 0; v < NG; ++v) mfma_step(acc[v][h + g], x[v].w, y[g].w);
+        for (int g = 0; g < kHalf; ++g) mfma_step(acc[h + g], v.w, y[g].w);
       }
     };
-    auto use_set = [&](float4 (*s)[NG], int cb) {
+    auto use_set = [&](const float4 *s, int cb) {
 #pragma unroll
       for (int u = 0; u < kPrefetch; ++u) use(s[u], cb + u);
       __builtin_amdgcn_sched_barrier(0);
     };
-    if (d4_main) {  // (with early loads set a holds chunks 0 .. kPrefetch - 1 of this group already)
-      if (!kEarlyLoad) load_set(sa, xa, xb, 0);
+    if (d4_main) {  // set a holds chunks 0 .. kPrefetch - 1 of this group already
       int c = 0;
 #pragma unroll 1
       for (; c + 2 * kPrefetch < d4_main; c += 2 * kPrefetch) {
-        load_set(sb, xa, xb, c + kPrefetch);
+        load_set(sb, x, c + kPrefetch);
         use_set(sa, c);
-        load_set(sa, xa, xb, c + 2 * kPrefetch);
+        load_set(sa, x, c + 2 * kPrefetch);
         use_set(sb, c + kPrefetch);
       }
-      load_set(sb, xa, xb, c + kPrefetch);
+      load_set(sb, x, c + kPrefetch);
       use_set(sa, c);
       use_set(sb, c + kPrefetch);
     }
-    for (int c = d4_main; c < d4; ++c) {
-      float4 x[NG];
-      x[0] = xa[(size_t)c * kWave];
-      if (NG == 2) x[NG - 1] = xb[(size_t)c * kWave];
-      use(x, c);
-    }
-    const float4 *na = xa, *nb = xb;
+    for (int c = d4_main; c < d4; ++c) use(x[(size_t)c * kWave], c);
+    const float4 *x_next = x;
     if (more) {  // the next group's first loads go out before this group's survivors are dealt with
-      place(g_next, nb0, nb1, na, nb);
-      if (kEarlyLoad && d4_main) load_set(sa, na, nb, 0);
+      x_next = place(g_next, next_b);
+      if (d4_main) load_set(sa, x_next, 0);
     }
 
-    // scores -> keys; which of the lane's 4 NG candidates per group of queries survive
-    float nr[NG][4];
-#pragma unroll
-    for (int v = 0; v < NG; ++v) {
-      nr[v][0] = quad_broadcast<0>(nrm[v]); nr[v][1] = quad_broadcast<1>(nrm[v]);
-      nr[v][2] = quad_broadcast<2>(nrm[v]); nr[v][3] = quad_broadcast<3>(nrm[v]);
-    }
-    const uint32_t vbase = g0 * kWave + 4u * (uint32_t)(lane >> 2);  // the next group of vectors is 64 on
+    // scores -> keys; which of the lane's 4 candidates per group of queries survive
+    const float nr[4] = {quad_broadcast<0>(nrm), quad_broadcast<1>(nrm), quad_broadcast<2>(nrm), quad_broadcast<3>(nrm)};
+    const uint32_t vbase = g0 * kWave + 4u * (uint32_t)(lane >> 2);
 #pragma unroll
     for (int g = 0; g < QG; ++g) {
       const TileQuery me = tq[4 * g + sub];  // len 0 for rows past the tile: nothing of theirs is kept
-      uint32_t key[NG][4], pass = 0u;
+      uint32_t key[4], pass = 0u;
 #pragma unroll
-      for (int v = 0; v < NG; ++v)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          float sc = acc[v][g][r];
-          sc = METRIC == 0 ? fmaf(-2.f, sc, nr[v][r] + me.qn) : -sc;
-          key[v][r] = key_of_float(sc + 0.0f);
-          if ((v == 0 || two) && vbase + v * kWave + r < me.len && key[v][r] <= me.bound) pass |= 1u << (4 * v + r);
-        }
+      for (int r = 0; r < 4; ++r) {
+        float sc = acc[g][r];
+        sc = METRIC == 0 ? fmaf(-2.f, sc, nr[r] + me.qn) : -sc;
+        key[r] = key_of_float(sc + 0.0f);
+        if (vbase + r < me.len && key[r] <= me.bound) pass |= 1u << r;
+      }
       if (__ballot(pass != 0u) == 0ull) continue;  // uniform
-      // places in the staging area: candidate i of every lane, lane after lane, then candidate i + 1
-      uint32_t at[4 * NG], total = 0;
+      // places in the staging area: candidate r of every lane, lane after lane, then candidate r + 1
+      uint32_t at[4], total = 0;
 #pragma unroll
-      for (int i = 0; i < 4 * NG; ++i) {
-        const unsigned long long m = __ballot((pass >> i) & 1u);
-        at[i] = total + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+      for (int r = 0; r < 4; ++r) {
+        const unsigned long long m = __ballot((pass >> r) & 1u);
+        at[r] = total + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
         total += (uint32_t)__popcll(m);
       }
-      if (staged + total > (uint32_t)kCap) flush();  // uniform
+      if (staged + total > (uint32_t)kMmStageCap) flush();  // uniform; at most 4 x 64 at once: they always fit an empty area
 #pragma unroll
-      for (int v = 0; v < NG; ++v)
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (pass & (1u << (4 * v + r))) {
-            const uint32_t e = staged + at[4 * v + r];
-            st.key[e] = key[v][r];
-            st.pos[e] = me.off + vbase + v * kWave + r;
-            st.row[e] = (uint8_t)(4 * g + sub);
-          }
+      for (int r = 0; r < 4; ++r)
+        if (pass & (1u << r)) {
+          const uint32_t e = staged + at[r];
+          st.key[e] = key[r];
+          st.pos[e] = me.off + vbase + r;
+          st.row[e] = (uint8_t)(4 * g + sub);
+        }
       staged += total;
     }
     if (!more) break;
     g0 = g_next;
-    xa = na;
-    xb = nb;
+    x = x_next;
   }
   if (staged) flush();
 }
@@ -260,14 +210,14 @@ __device__ __forceinline__ void scan_groups_mm(const Dev &D, const SearchScratch
 // Hardware hands consecutive workgroup ids to the 8 XCDs in turn, so workgroup i runs on XCD i % 8 and
 // takes item i / 8 of that XCD's range of items (a contiguous range of lists); workgroups past the end
 // of their range leave at once.
-template <int METRIC, int QGMAX>
+template <int METRIC>
 __global__ __launch_bounds__(kMmWaves *kWave) void k_scan_mm(Dev D, int max_nprobe, const float *__restrict__ Q,
                                                              SearchScratch S, int tile_rows) {
   extern __shared__ float4 lds_mm[];  // [tile_rows][d / 4 + 1] coordinates of the tile's queries, [tile_rows] TileQuery, [wavefronts] WaveStage
   const ScanQueues *Qs = S.queues;
-  const uint32_t x = blockIdx.x % kXcds;
-  const uint32_t item = Qs->begin[x] + blockIdx.x / kXcds;
-  if (item >= Qs->begin[x + 1]) return;
+  const uint32_t xcd = blockIdx.x % kXcds;
+  const uint32_t item = Qs->begin[xcd] + blockIdx.x / kXcds;
+  if (item >= Qs->begin[xcd + 1]) return;
   const uint32_t seg = Qs->seg_groups;
   if (seg == 0) return;
   const uint4 desc = S.tile_desc[item];
@@ -277,26 +227,22 @@ __global__ __launch_bounds__(kMmWaves *kWave) void k_scan_mm(Dev D, int max_npro
   const int d4 = D.d4, qstride = d4 + 1;
   float4 *qs = lds_mm;
   TileQuery *tq = reinterpret_cast<TileQuery *>(lds_mm + (size_t)tile_rows * qstride);
-  constexpr int kNG = QGMAX == 2 ? 2 : 1;  // groups of vectors a wavefront takes at a time
-  WaveStage<mm_stage_cap(kNG)> &st = reinterpret_cast<WaveStage<mm_stage_cap(kNG)> *>(tq + tile_rows)[threadIdx.x / kWave];
+  WaveStage &st = reinterpret_cast<WaveStage *>(tq + tile_rows)[threadIdx.x / kWave];
   // groups of four queries of this tile: 1, 2, 3, 4, 6 or 8, whichever holds the item's queries; exactly
   // that many rows of LDS are set up, and the instantiation below reads exactly that many (the plan never
   // puts more queries into a tile than tile_rows)
   int qg = (int)((pairs + 3u) / 4u);
   qg = qg == 5 ? 6 : qg == 7 ? 8 : qg;
   const int rows = 4 * qg;
-  if (rows > tile_rows || qg > QGMAX) return;  // a descriptor the launch was not sized for: nothing is scanned
-  // The block numbers of the wavefront's first groups of vectors are asked for now (two dependent reads)
+  if (rows > tile_rows || rows > kMmTileMax) return;  // a descriptor the launch was not sized for: nothing is scanned
+  // The block number of the wavefront's first group of vectors is asked for now (two dependent reads)
   // and used after the tile is set up.  Never past the list's chain, whatever the descriptors say.
   const uint32_t g_begin = desc.w * seg;
   const uint32_t g_have = D.nblk[list] * (uint32_t)D.groups_per_block;
-  uint32_t first_b0 = 0, first_b1 = 0;
+  uint32_t first_b = 0;
   {
-    const uint32_t g0 = g_begin + (threadIdx.x / kWave) * kNG;
-    if (g0 < g_have) first_b0 = (uint32_t)*table_entry(D, list, g0 / (uint32_t)D.groups_per_block);
-    first_b1 = first_b0;
-    // (should the second group turn out to lie past what the tile wants, its loads are not used)
-    if (kNG == 2 && g0 + 1 < g_have) first_b1 = (uint32_t)*table_entry(D, list, (g0 + 1) / (uint32_t)D.groups_per_block);
+    const uint32_t g0 = g_begin + threadIdx.x / kWave;
+    if (g0 < g_have) first_b = (uint32_t)*table_entry(D, list, g0 / (uint32_t)D.groups_per_block);
   }
   // the tile's queries: words first (one thread per row), then coordinates (the workgroup together)
   uint32_t my_len = 0;
@@ -355,43 +301,28 @@ __global__ __launch_bounds__(kMmWaves *kWave) void k_scan_mm(Dev D, int max_npro
   if (g_end > g_begin + seg) g_end = g_begin + seg;  // ... inside this item's segment
   if (g_end > g_have) g_end = g_have;
   // no barrier from here on: the wavefronts only read the tile
-  if constexpr (QGMAX == 2) {
-    if (qg == 1) scan_groups_mm<METRIC, 1, 2>(D, S, list, g_begin, g_end, first_b0, first_b1, qs, tq, st);
-    else scan_groups_mm<METRIC, 2, 2>(D, S, list, g_begin, g_end, first_b0, first_b1, qs, tq, st);
-  } else {
-    switch (qg) {
-      case 1: scan_groups_mm<METRIC, 1, 1>(D, S, list, g_begin, g_end, first_b0, first_b1, qs, tq, st); break;
-      case 2: scan_groups_mm<METRIC, 2, 1>(D, S, list, g_begin, g_end, first_b0, first_b1, qs, tq, st); break;
-      case 3: scan_groups_mm<METRIC, 3, 1>(D, S, list, g_begin, g_end, first_b0, first_b1, qs, tq, st); break;
-      case 4: scan_groups_mm<METRIC, 4, 1>(D, S, list, g_begin, g_end, first_b0, first_b1, qs, tq, st); break;
-      case 6: scan_groups_mm<METRIC, 6, 1>(D, S, list, g_begin, g_end, first_b0, first_b1, qs, tq, st); break;
-      default: scan_groups_mm<METRIC, 8, 1>(D, S, list, g_begin, g_end, first_b0, first_b1, qs, tq, st); break;
-    }
+  switch (qg) {
+    case 1: scan_groups_mm<METRIC, 1>(D, S, list, g_begin, g_end, first_b, qs, tq, st); break;
+    case 2: scan_groups_mm<METRIC, 2>(D, S, list, g_begin, g_end, first_b, qs, tq, st); break;
+    case 3: scan_groups_mm<METRIC, 3>(D, S, list, g_begin, g_end, first_b, qs, tq, st); break;
+    case 4: scan_groups_mm<METRIC, 4>(D, S, list, g_begin, g_end, first_b, qs, tq, st); break;
+    case 6: scan_groups_mm<METRIC, 6>(D, S, list, g_begin, g_end, first_b, qs, tq, st); break;
+    default: scan_groups_mm<METRIC, 8>(D, S, list, g_begin, g_end, first_b, qs, tq, st); break;
   }
-}
-
-template <typename K>
-static void allow_large_lds(K kernel) {
-  // above 64 KiB of dynamic LDS a kernel has to be told (wide vectors only); once per kernel and process
-  (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMmLdsMax);
 }
 
 void launch_scan_mm(const Dev &D, const ScanShape &sh, int max_nprobe, const float *Q, const SearchScratch &S,
                     hipStream_t s) {
+  // above 64 KiB of dynamic LDS a kernel has to be told (wide vectors only); once per kernel and process
   static const bool once = [] {
-    allow_large_lds(k_scan_mm<0, 2>); allow_large_lds(k_scan_mm<0, 8>);
-    allow_large_lds(k_scan_mm<1, 2>); allow_large_lds(k_scan_mm<1, 8>);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k_scan_mm<0>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMmLdsMax);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k_scan_mm<1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMmLdsMax);
     return true;
   }();
   (void)once;
   const dim3 grid((unsigned)sh.grid), block((unsigned)sh.threads);
-  if (D.metric == 0) {
-    if (sh.qgmax == 8) hipLaunchKernelGGL((k_scan_mm<0, 8>), grid, block, sh.lds, s, D, max_nprobe, Q, S, sh.tile_q);
-    else hipLaunchKernelGGL((k_scan_mm<0, 2>), grid, block, sh.lds, s, D, max_nprobe, Q, S, sh.tile_q);
-  } else {
-    if (sh.qgmax == 8) hipLaunchKernelGGL((k_scan_mm<1, 8>), grid, block, sh.lds, s, D, max_nprobe, Q, S, sh.tile_q);
-    else hipLaunchKernelGGL((k_scan_mm<1, 2>), grid, block, sh.lds, s, D, max_nprobe, Q, S, sh.tile_q);
-  }
+  if (D.metric == 0) hipLaunchKernelGGL((k_scan_mm<0>), grid, block, sh.lds, s, D, max_nprobe, Q, S, sh.tile_q);
+  else hipLaunchKernelGGL((k_scan_mm<1>), grid, block, sh.lds, s, D, max_nprobe, Q, S, sh.tile_q);
 }
 
 }  // namespace rtams

@@ -333,18 +333,19 @@ constexpr int kScanWaves = 4;
 
 // Launch shape of a list scan.  Two kernels share the plan of work items (list, segment, tile of the
 // queries probing the list):
-//  - vector unit (narrow storage, or the matrix cores switched off): a workgroup is up to four
-//    wavefronts that take four consecutive items, one each, every one with its own tile of up to 8
-//    queries in LDS;
-//  - matrix cores (flat float lists): a workgroup takes ONE item, its tile of up to 32 queries sits in
-//    LDS once, and its four wavefronts share out the item's groups of vectors.  Large tiles are what
-//    keeps a hot list from being read once per 8 of the dozens of queries that probe it; the price is
-//    registers (fewer wavefronts per SIMD), so small requests, whose tiles are small anyway, run an
-//    instantiation with tiles of up to 8.
+//  - vector unit (narrow storage, small requests, or the matrix cores switched off): a workgroup is up
+//    to four wavefronts that take four consecutive items, one each, every one with its own tile of up
+//    to 8 queries in LDS;
+//  - matrix cores (flat float lists, requests of 64 queries or more): a workgroup takes ONE item, its
+//    tile of up to 32 queries sits in LDS once, and its four wavefronts share out the item's groups of
+//    vectors.  Large tiles are what keeps a hot list from being read once per 8 of the dozens of
+//    queries that probe it; the price is registers (3 wavefronts per SIMD instead of 4) and a tile to
+//    set up per item, which small requests, whose tiles hold a query or two, do not get back
+//    (measured at 1 and 32 queries: 15 to 20 % slower than the vector unit with its partial-distance
+//    pruning).
 struct ScanShape {
   bool mm;           // the matrix-core kernel
   int tile_q;        // queries of a tile at most
-  int qgmax;         // matrix cores: groups of four queries the instantiation holds (2 or 8)
   int min_choice;    // shortest segment the plan may choose: 2 << min_choice groups of 64 vectors
   int items_per_wg;  // items a workgroup takes
   int threads;       // of a workgroup
@@ -352,14 +353,14 @@ struct ScanShape {
   size_t lds;        // dynamic LDS bytes of a workgroup
 };
 constexpr int kMmWaves = 4;            // wavefronts of a workgroup of the matrix-core scan
+constexpr int kMmTileMax = 32;         // queries of its tile at most
 constexpr int kMmQueryWords = 12;      // 32-bit words of LDS per query of a tile beside its coordinates
-// survivors a wavefront stages in LDS before it reserves their places (it takes ng groups of 64 vectors at a
-// time), and the bytes that takes: keys, positions, rows, and two words for each of 32 queries
-constexpr int mm_stage_cap(int ng) { return 256 * ng; }
-constexpr size_t mm_stage_bytes(int cap) { return (size_t)cap * 9 + 256; }
+constexpr int kMmStageCap = 256;       // survivors a wavefront stages in LDS before it reserves their places
+constexpr size_t kMmStageBytes = (size_t)kMmStageCap * 9 + 8 * kMmTileMax;  // keys, positions, rows, and two words per query of the tile
 constexpr size_t kMmLdsMax = 160 * 1024 - 1024;  // what a workgroup may take of the CU's 160 KiB
+constexpr int kMmMinBatch = 64;        // queries of a request from which the matrix-core scan pays
 
-inline ScanShape scan_shape(const Dev &D, int64_t nq, int item_budget) {
+inline ScanShape scan_shape(const Dev &D, int item_budget) {
   ScanShape sh{};
   sh.mm = D.scan_mfma != 0 && D.storage == 0 && D.pq_m == 0;
   // room for an uneven split of the items over the XCDs
@@ -377,14 +378,13 @@ inline ScanShape scan_shape(const Dev &D, int64_t nq, int item_budget) {
     return sh;
   }
   const size_t row = (size_t)(D.d + 4) * sizeof(float) + kMmQueryWords * 4;  // a query of the tile: coordinates, one float4 of padding, its words
-  sh.qgmax = nq >= 64 ? 8 : 2;
-  int rows = 4 * sh.qgmax;
-  // two workgroups of the large-tile kernel should fit a CU side by side; a tile is never below 8 queries
-  const size_t stage = kMmWaves * mm_stage_bytes(mm_stage_cap(sh.qgmax == 2 ? 2 : 1));
+  const size_t stage = kMmWaves * kMmStageBytes;
+  int rows = kMmTileMax;
+  // two workgroups should fit a CU side by side; a tile is never below 8 queries unless LDS cannot hold that
   while (rows > 8 && row * rows + stage > 64 * 1024) rows /= 2;
   while (rows > 4 && row * rows + stage > kMmLdsMax) rows /= 2;
   sh.tile_q = rows;
-  sh.min_choice = sh.qgmax == 8 ? 2 : 0;  // large tiles: at least 8 groups to an item, two for every wavefront (measured: 4 and 16 are slower)
+  sh.min_choice = 2;  // at least 8 groups to an item, two for every wavefront (measured: 4 and 16 are slower)
   if (D.scan_min_choice >= 0) sh.min_choice = D.scan_min_choice;
   sh.items_per_wg = 1;
   sh.threads = kMmWaves * kWave;
