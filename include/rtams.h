@@ -43,7 +43,9 @@ enum rtams_status {
   RTAMS_EPOOL = -3,   /* the block pool cannot hold the blocks this call may need */
   RTAMS_EBUSY = -4,   /* every stream resource is in flight: request rejected */
   RTAMS_EHIP = -5,    /* a HIP runtime call failed */
-  RTAMS_ESCRATCH = -6 /* a search needed more candidate scratch than its resource and the shared reserve hold */
+  RTAMS_ESCRATCH = -6, /* a search needed more candidate scratch than its resource and the shared reserve hold */
+  RTAMS_ENOSPARE = -7  /* a rearrangement found no spare block in the pool to move a block through: the chains
+                          it could not compact are as they were, Exceed() keeps holding for their lists */
 };
 
 /* What a flat list keeps of each coordinate (a cheaper step towards the quantised lists: the
@@ -101,6 +103,9 @@ typedef struct rtams_stats {
   int64_t overflow_chunks;         /* chunks of the shared scratch reserve */
   int64_t overflow_chunk_entries;  /* candidate entries one chunk holds */
   int64_t overflow_chunks_leased;  /* chunks held by requests not yet finished */
+  int64_t rearrangement_state;     /* of the last rearrangement round: 0 its list is contiguous (or nothing was to
+                                      do), 1 another round is owed (a round moves as many blocks as the pool has
+                                      spare blocks for, at most 4096), 2 stalled: no spare block at all */
 } rtams_stats;
 
 /* Bytes of pool needed for `blocks` blocks under this configuration (d_pool and
@@ -171,11 +176,20 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
 
 /* Rearrangement algorithm of the paper: makes the blocks of `list` physically
  * contiguous behind its first block by exchanging blocks with their physical
- * neighbours.  list == -1 handles every list for which Exceed() holds: one
- * round after another (a round moves one list, a long chain takes several),
- * and this form WAITS for each round on the stream, because only the device
- * knows whether another is owed; with a list given the call only enqueues.
- * (rtams_add enqueues one such round by itself whenever a list exceeds.)
+ * neighbours.  list == -1 handles every list for which Exceed() holds.  The work
+ * goes in rounds (a round moves one list's blocks: at most 4096, and no more
+ * than the pool has spare blocks to move the displaced occupants through, one
+ * at least while a single block is free), and this call WAITS for each round
+ * on the stream, because only the device knows whether another is owed; it
+ * returns when the chain is contiguous (list >= 0) or no list exceeds (-1).
+ * ENOSPARE when the pool has no spare block at all: nothing is lost, the
+ * chains concerned are as they were and Exceed() keeps holding for them.
+ * rtams_add enqueues ONE round by itself, without waiting, when it finds that
+ * Exceed() held after an EARLIER batch was published (the device reports that
+ * through a word of pinned host memory).  After the last batch of a burst
+ * nothing follows that could carry the round: a caller who wants every
+ * exceeding list compacted then calls rtams_rearrange(ix, -1, ...) itself
+ * (rtams_pool_stats().lists_exceeding tells whether any is left).
  * Ordered with add on the data stream; searches keep running and see either
  * placement, never a mixture. */
 int rtams_rearrange(rtams_index *ix, int32_t list, void *hip_stream);

@@ -15,7 +15,12 @@
 //   step 3  the positions the list gave up go to the free stack.
 // A search sees, for every block, either the old or the new place, and both
 // hold the same bytes while it may look.  The number of blocks in use does not
-// change; only one spare block per displaced occupant is needed meanwhile.
+// change; one spare block per displaced occupant is needed meanwhile, and a round
+// moves as many blocks as the spare blocks of the moment allow (at least one as
+// long as a single block is free: the paper's one temporary segment), so a long
+// chain in a nearly full pool is compacted over several rounds instead of not
+// at all.  Exceed() keeps holding for the list until its chain is contiguous;
+// only a pool without any spare block stalls it, and that is reported.
 #include "rtams_launch.h"
 
 namespace rtams {
@@ -51,20 +56,30 @@ __device__ inline void finish_list(const Dev &D, int list) {  // Exceed() no lon
 // execution" in the paper; a workgroup here, the work is a few prefix sums).
 __global__ __launch_bounds__(kRearrThreads) void k_rearr_plan(Dev D, RearrangeScratch R, int list_arg) {
   __shared__ uint32_t lds[kRearrThreads];
-  __shared__ uint32_t s_list, s_free_in_range;
+  __shared__ uint32_t s_list, s_free_in_range, s_vict;
   const int tid = threadIdx.x;
   RearrangeHead *H = R.head;
 
   // the list: the caller's, or the first one for which Exceed() holds
-  if (tid == 0) s_list = list_arg >= 0 ? (uint32_t)list_arg : 0xffffffffu;
+  // (taken in turn: the first exceeding list behind the one handled last, so that a list that is
+  // stalled for lack of a spare block does not keep the others waiting)
+  __shared__ uint32_t s_wrap;
+  const uint32_t after = H->cursor;  // lists below this one come last
+  if (tid == 0) { s_list = list_arg >= 0 ? (uint32_t)list_arg : 0xffffffffu; s_wrap = 0xffffffffu; }
   __syncthreads();
   if (list_arg < 0) {
     for (int l = tid; l < D.nlist; l += kRearrThreads)
-      if (D.exceed[l]) atomicMin(&s_list, (uint32_t)l);
+      if (D.exceed[l]) atomicMin((uint32_t)l >= after ? &s_list : &s_wrap, (uint32_t)l);
+    __syncthreads();
+    if (tid == 0 && s_list == 0xffffffffu) s_list = s_wrap;
     __syncthreads();
   }
   const int list = (int)s_list;
-  if (tid == 0) { H->list = list; H->count = 0; H->nvict = 0; }
+  if (tid == 0) {
+    H->list = list; H->count = 0; H->nvict = 0; H->done = 0;
+    H->state = 0;  // nothing owed, unless the code below says otherwise
+    D.mirror->rearr_state = 0;
+  }
   if (list < 0 || s_list == 0xffffffffu) return;
   const uint32_t nb = D.nblk[list];
   if (nb <= 1) {
@@ -92,10 +107,9 @@ __global__ __launch_bounds__(kRearrThreads) void k_rearr_plan(Dev D, RearrangeSc
     if (tid == 0) finish_list(D, list);
     return;
   }
-  // the round covers targets up to and including that of its last move
   __syncthreads();
-  const uint32_t t_last = R.mv_t[M - 1];
-  const uint32_t lo = b0 + 1, hi = b0 + t_last;  // target range, inclusive
+  const uint32_t M_all = M;  // moves this round would make with spare blocks enough
+  const uint32_t lo = b0 + 1;  // first target
 
   // classify what sits at each target
   uint32_t nvict = 0;
@@ -118,22 +132,43 @@ __global__ __launch_bounds__(kRearrThreads) void k_rearr_plan(Dev D, RearrangeSc
     __syncthreads();
   }
 
-  // how many free-stack entries lie in the target range (they leave the stack)
-  if (tid == 0) s_free_in_range = 0;
-  __syncthreads();
+  // The round covers targets up to and including that of its last move.  Every occupant in use needs a
+  // spare block; with fewer spare blocks than occupants the round is cut to as many of its first moves
+  // as the spare blocks allow (halved until it fits: a shorter round has fewer occupants, a smaller
+  // target range and therefore no fewer spare blocks).
   const int ft = D.ctrl->free_top > 0 ? D.ctrl->free_top : 0;
-  for (int i = tid; i < ft; i += kRearrThreads) {
-    uint32_t b = (uint32_t)D.free_stack[i];
-    if (b >= lo && b <= hi) atomicAdd(&s_free_in_range, 1u);
+  uint32_t hi, new_cur, t_last;
+  for (;;) {  // uniform over the workgroup
+    t_last = R.mv_t[M - 1];
+    hi = b0 + t_last;  // last target, inclusive
+    // how many free-stack entries lie in the target range (they leave the stack), how many occupants in use
+    __syncthreads();
+    if (tid == 0) { s_free_in_range = 0; s_vict = 0; }
+    __syncthreads();
+    for (int i = tid; i < ft; i += kRearrThreads) {
+      uint32_t b = (uint32_t)D.free_stack[i];
+      if (b >= lo && b <= hi) atomicAdd(&s_free_in_range, 1u);
+    }
+    for (uint32_t j = tid; j < M; j += kRearrThreads)
+      if (R.kind[j] == 2) atomicAdd(&s_vict, 1u);
+    __syncthreads();
+    nvict = s_vict;
+    new_cur = hi + 1 > old_cur ? hi + 1 : old_cur;
+    const uint32_t spare = (uint32_t)ft - s_free_in_range + (D.nblocks - new_cur);
+    if (nvict <= spare) break;
+    if (M == 1) {
+      // not a single spare block for the first occupant: nothing can move.  Exceed() keeps holding for
+      // the list (its chain is as broken as before); the host is told, and the next round looks at
+      // another list first.
+      if (tid == 0) {
+        H->state = 2;
+        H->cursor = (uint32_t)list + 1u < (uint32_t)D.nlist ? (uint32_t)list + 1u : 0u;
+        D.mirror->rearr_state = 2;
+      }
+      return;
+    }
+    M = (M + 1) / 2;
   }
-  __syncthreads();
-  const uint32_t new_cur = hi + 1 > old_cur ? hi + 1 : old_cur;
-  const uint32_t spare = (uint32_t)ft - s_free_in_range + (D.nblocks - new_cur);
-  if (nvict > spare) {  // not enough spare blocks to move the occupants out: give up for now
-    if (tid == 0) finish_list(D, list);
-    return;
-  }
-
   // from here on the allocator state changes
   // 1. free-stack entries inside the range are dropped, the rest keeps its order
   uint32_t kept = 0;
@@ -161,7 +196,11 @@ __global__ __launch_bounds__(kRearrThreads) void k_rearr_plan(Dev D, RearrangeSc
     D.ctrl->cur_P = new_cur + (nvict - from_stack);
     H->count = M;
     H->nvict = nvict;
-    H->done = t_last + 1 >= tmax ? 1u : 0u;  // did this round reach the end of what can be placed
+    // did this round reach the end of what can be placed?  If not, another is owed.
+    H->done = M == M_all && t_last + 1 >= tmax ? 1u : 0u;
+    H->state = H->done ? 0u : 1u;
+    H->cursor = H->done ? ((uint32_t)list + 1u < (uint32_t)D.nlist ? (uint32_t)list + 1u : 0u) : (uint32_t)list;
+    D.mirror->rearr_state = H->state;
   }
 }
 

@@ -269,10 +269,12 @@ int enter_data_stream(rtams_index *ix, hipStream_t s) {
   return RTAMS_OK;
 }
 
-int leave_data_stream(rtams_index *ix, hipStream_t s) {
-  HIP_TRY(hipEventRecord(ix->data_done, s));
-  return RTAMS_OK;
-}
+// Whatever way a call on the data stream ends, the next one has to find where it ended.
+struct DataStreamScope {
+  rtams_index *ix;
+  hipStream_t s;
+  ~DataStreamScope() { (void)hipEventRecord(ix->data_done, s); }
+};
 
 // The owner of a resource (state BUSY) collects the scan timing of its last request.
 void harvest(rtams_index *ix, Resource &R) {
@@ -541,12 +543,13 @@ int rtams_set_centroids(rtams_index *ix, const float *d_centroids, void *hip_str
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   int rc = enter_data_stream(ix, s);
   if (rc) return rc;
+  DataStreamScope scope{ix, s};
   HIP_TRY(hipMemcpyAsync(ix->dev.centroids, d_centroids, (size_t)ix->cfg.nlist * ix->cfg.d * 4,
                          hipMemcpyDeviceToDevice, s));
   launch_centroid_norms(ix->dev, s);
   HIP_TRY(hipGetLastError());
   ix->has_centroids = true;
-  return leave_data_stream(ix, s);
+  return RTAMS_OK;
 }
 
 int rtams_set_codebooks(rtams_index *ix, const float *d_codebooks, void *hip_stream) {
@@ -557,11 +560,12 @@ int rtams_set_codebooks(rtams_index *ix, const float *d_codebooks, void *hip_str
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   int rc = enter_data_stream(ix, s);
   if (rc) return rc;
+  DataStreamScope scope{ix, s};
   HIP_TRY(hipMemcpyAsync(ix->dev.codebooks, d_codebooks, (size_t)256 * ix->cfg.d * 4, hipMemcpyDeviceToDevice, s));
   launch_pq_transpose(ix->dev, s);
   HIP_TRY(hipGetLastError());
   ix->has_codebooks = true;
-  return leave_data_stream(ix, s);
+  return RTAMS_OK;
 }
 
 int rtams_add(rtams_index *ix, int64_t n, const float *d_vecs, const int64_t *d_ids, void *hip_stream) {
@@ -589,6 +593,7 @@ int rtams_add(rtams_index *ix, int64_t n, const float *d_vecs, const int64_t *d_
   }
   int rc = enter_data_stream(ix, s);
   if (rc) return rc;
+  DataStreamScope scope{ix, s};
   const int64_t round = ix->cfg.max_add_batch;
   const bool ordered = ix->ordered_add.load(std::memory_order_relaxed) != 0;
   for (int64_t o = 0; o < n; o += round) {
@@ -613,7 +618,7 @@ int rtams_add(rtams_index *ix, int64_t n, const float *d_vecs, const int64_t *d_
   if (ix->cfg.rearrange_threshold > 0 && ix->mirror->exceed_lists > 0) {
     if ((rc = rearrange_round(ix, -1, s))) return rc;
   }
-  return leave_data_stream(ix, s);
+  return RTAMS_OK;
 }
 
 int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k, int32_t nprobe,
@@ -707,18 +712,37 @@ int rtams_rearrange(rtams_index *ix, int32_t list, void *hip_stream) {
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   int rc = enter_data_stream(ix, s);
   if (rc) return rc;
+  DataStreamScope scope{ix, s};
+  // A round moves at most kRearrangeCap blocks, and no more than the pool has spare blocks for; only the
+  // device knows whether another is owed, so every round is waited for.
+  const int64_t max_rounds = (int64_t)ix->dev.nblocks + 8 * (int64_t)ix->cfg.nlist + 64;
   if (list >= 0) {
-    if ((rc = rearrange_round(ix, list, s))) return rc;  // blocks in use are the same before and after
-    return leave_data_stream(ix, s);
+    for (int64_t it = 0; it < max_rounds; ++it) {
+      if ((rc = rearrange_round(ix, list, s))) return rc;  // blocks in use are the same before and after
+      HIP_TRY(hipStreamSynchronize(s));
+      const uint32_t state = ix->mirror->rearr_state;
+      if (state == 2)
+        return fail(RTAMS_ENOSPARE, "list %d: no spare block in the pool to move a block through; its chain is as it was", list);
+      if (state == 0) break;
+    }
+    return RTAMS_OK;
   }
-  // Every list for which Exceed() holds: one round handles one list (a long chain takes several),
-  // and only the device knows whether another is owed, so this form waits for each round.
-  for (int64_t it = 0; it < 8 * (int64_t)ix->cfg.nlist + 64; ++it) {
+  // Every list for which Exceed() holds, one after the other.  A list that stalls for lack of a spare
+  // block keeps its flag; when a whole turn through the exceeding lists moved nothing, the call gives up.
+  int64_t stalled_in_a_row = 0;
+  for (int64_t it = 0; it < max_rounds; ++it) {
+    if (ix->mirror->exceed_lists == 0) break;
     if ((rc = rearrange_round(ix, -1, s))) return rc;
     HIP_TRY(hipStreamSynchronize(s));
-    if (ix->mirror->exceed_lists == 0) break;
+    if (ix->mirror->rearr_state == 2) {
+      if (++stalled_in_a_row >= (int64_t)ix->mirror->exceed_lists)
+        return fail(RTAMS_ENOSPARE, "%u lists exceed, and the pool has no spare block to move a block through",
+                    ix->mirror->exceed_lists);
+    } else {
+      stalled_in_a_row = 0;
+    }
   }
-  return leave_data_stream(ix, s);
+  return RTAMS_OK;
 }
 
 int rtams_probe(rtams_index *ix, int64_t nq, const float *d_queries, int32_t nprobe, int32_t *d_out,
@@ -750,13 +774,14 @@ int rtams_assign(rtams_index *ix, int64_t n, const float *d_vecs, int32_t *d_out
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   int rc = enter_data_stream(ix, s);
   if (rc) return rc;
+  DataStreamScope scope{ix, s};
   const int64_t round = ix->cfg.max_add_batch;
   for (int64_t o = 0; o < n; o += round) {
     int64_t m = n - o < round ? n - o : round;
     assign_round(ix, m, d_vecs + (size_t)o * ix->dev.d, false, d_out + o, s);
   }
   HIP_TRY(hipGetLastError());
-  return leave_data_stream(ix, s);
+  return RTAMS_OK;
 }
 
 // ------------------------------------------------------------ introspection
@@ -886,6 +911,7 @@ int rtams_pool_stats(rtams_index *ix, rtams_stats *out) {
   out->table_entries_total = (int64_t)ix->lay.slab_cap;
   out->overflow_chunks = ix->ovf_chunks;
   out->overflow_chunk_entries = (int64_t)ix->ovf_chunk_cap;
+  out->rearrangement_state = ix->mirror->rearr_state;
   if (ix->ovf_leased) {  // as of now: searches in flight on other streams may hold chunks
     uint32_t leased[kMaxOverflowChunks];
     HIP_TRY(hipMemcpy(leased, ix->ovf_leased, sizeof(uint32_t) * ix->ovf_chunks, hipMemcpyDeviceToHost));

@@ -50,6 +50,7 @@ struct HostMirror {
   volatile uint32_t exceed_lists;
   volatile uint32_t max_len;
   volatile int32_t search_error;
+  volatile uint32_t rearr_state;  // of the last rearrangement round: 0 done, 1 another round owed, 2 stalled for lack of a spare block
 };
 
 struct Dev {

@@ -89,6 +89,9 @@ struct RearrangeHead {
   uint32_t count;  // moves of this round
   uint32_t nvict;  // occupants that had to be moved out of the way
   uint32_t done;   // the round reaches the end of the chain
+  uint32_t state;  // after the round: 0 the list is contiguous (or nothing was to do), 1 another round is owed,
+                   // 2 stalled: no spare block in the pool
+  uint32_t cursor; // where the search for the next exceeding list starts (kept from round to round)
 };
 struct RearrangeScratch {
   RearrangeHead *head;

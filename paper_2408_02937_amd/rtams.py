@@ -17,10 +17,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "librtams.so")
 
 L2, IP = 0, 1
-OK, EINVAL, ESTATE, EPOOL, EBUSY, EHIP, ESCRATCH = 0, -1, -2, -3, -4, -5, -6
+OK, EINVAL, ESTATE, EPOOL, EBUSY, EHIP, ESCRATCH, ENOSPARE = 0, -1, -2, -3, -4, -5, -6, -7
 STORAGE = {"f32": 0, "f16": 1, "u8": 2}  # what flat lists keep of a coordinate
 _NAMES = {EINVAL: "EINVAL", ESTATE: "ESTATE", EPOOL: "EPOOL", EBUSY: "EBUSY", EHIP: "EHIP",
-          ESCRATCH: "ESCRATCH"}
+          ESCRATCH: "ESCRATCH", ENOSPARE: "ENOSPARE"}
 
 # every symbol include/rtams.h declares
 SYMBOLS = [
@@ -50,7 +50,8 @@ class Stats(C.Structure):
                 ("pool_bytes", C.c_int64), ("meta_bytes", C.c_int64), ("utilisation", C.c_double),
                 ("lists_exceeding", C.c_int64), ("table_entries_used", C.c_int64),
                 ("table_entries_total", C.c_int64), ("overflow_chunks", C.c_int64),
-                ("overflow_chunk_entries", C.c_int64), ("overflow_chunks_leased", C.c_int64)]
+                ("overflow_chunk_entries", C.c_int64), ("overflow_chunks_leased", C.c_int64),
+                ("rearrangement_state", C.c_int64)]
 
 
 class RtamsError(RuntimeError):

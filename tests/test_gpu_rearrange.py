@@ -14,8 +14,9 @@ from tests.helpers import assert_topk_matches
 pytestmark = pytest.mark.gpu
 
 
-def interleaved(nlist=3, d=8, T=64, rounds=6, seed=3, threshold=0, pool_blocks=200):
-    """Lists grown in turn, one block at a time, so every chain is scattered."""
+def interleaved(nlist=3, d=8, T=64, rounds=6, seed=3, threshold=0, pool_blocks=200, settle=False):
+    """Lists grown in turn, one block at a time, so every chain is scattered.  settle: wait for every
+    batch, so that what it made exceed is known to the next add (which then carries the round)."""
     rng = np.random.default_rng(seed)
     C = (np.eye(nlist, d) * 10).astype(np.float32)
     w = synth.Workload("interleaved", "l2", d, nlist, T, nlist, 10, np.zeros((0, d), np.float32), C,
@@ -25,7 +26,18 @@ def interleaved(nlist=3, d=8, T=64, rounds=6, seed=3, threshold=0, pool_blocks=2
         for k in range(nlist):
             y = (C[k] + 0.5 * rng.standard_normal((T, d))).astype(np.float32)
             g.add(dev(y)); o.add(y)
+            if settle:
+                torch.cuda.synchronize()
     return w, g, o, rng
+
+
+def open_one_more_block_each(w, g, o, rng):
+    """One vector into every list, each opening a new block.  (Near a full pool add() refuses what MAY
+    need more blocks than are left: a batch of one vector can need only one.)"""
+    for k in range(w.nlist):
+        y = (w.centroids[k:k + 1] + 0.5 * rng.standard_normal((1, w.d))).astype(np.float32)
+        g.add(dev(y)); o.add(y)
+        torch.cuda.synchronize()
 
 
 def runs_of(g, k):
@@ -80,26 +92,89 @@ def test_rearrange_into_free_fresh_and_own_blocks():
     g.close()
 
 
-def test_rearrangement_without_enough_spare_blocks_leaves_everything_as_it_is():
-    """Moving the occupants of the target range out needs one spare block each for
-    a while; a pool that is nearly full has too few, and the round gives up: no
-    block moves, nothing is lost, no error is raised, and later adds still work."""
-    print("[case] rearrangement in a nearly full pool", flush=True)
-    w, g, o, rng = interleaved(nlist=2, rounds=6, pool_blocks=15)     # 12 blocks in use, 3 spare
+def test_rearrangement_with_a_single_spare_block_compacts_the_chain_round_by_round():
+    """Moving the occupants of the target range out needs one spare block each for a while.  A pool
+    with ONE free block (the paper's one temporary segment) still gets there: every round moves what
+    the spare blocks allow, and the call goes on until the chain is contiguous.  Lists equal the
+    oracle's throughout, blocks in use never change."""
+    print("[case] rearrangement with one spare block", flush=True)
+    w, g, o, rng = interleaved(nlist=2, rounds=5, pool_blocks=13)
+    open_one_more_block_each(w, g, o, rng)                             # 12 blocks in use, 1 spare
+    assert g.list_chain(0).tolist() == [0, 2, 4, 6, 8, 10] and g.list_chain(1).tolist() == [1, 3, 5, 7, 9, 11]
+    for k in (1, 0):
+        g.rearrange(k)                                                 # 5 occupants in the way, 1 spare block
+        g.validate()
+        assert g.poll_error() == 0
+        c = g.list_chain(k)
+        assert runs_of(g, k) == 1 and np.array_equal(c, c[0] + np.arange(6))
+        st = g.pool_stats()
+        assert st.blocks_in_use == 12 and st.rearrangement_state == 0
+        assert_lists_equal(g, o)
+    y = (w.centroids[:1] + 0.5 * rng.standard_normal((1, w.d))).astype(np.float32)
+    g.add(dev(y)); o.add(y)                                            # the index keeps working
+    g.validate()
+    assert_lists_equal(g, o)
+    g.close()
+
+
+def test_rearrangement_in_a_full_pool_reports_that_it_is_stalled():
+    """No spare block at all: nothing can move.  The call says so (ENOSPARE), every chain is as it was,
+    Exceed() keeps holding for the list, and searches and the index go on as usual."""
+    print("[case] rearrangement in a full pool", flush=True)
+    w, g, o, rng = interleaved(nlist=2, rounds=5, pool_blocks=12, threshold=10_000)
+    open_one_more_block_each(w, g, o, rng)                             # 12 blocks in use, none spare
+    assert g.pool_stats().blocks_in_use == 12
     chains = [g.list_chain(k).copy() for k in range(2)]
-    assert chains[0].tolist() == [0, 2, 4, 6, 8, 10] and chains[1].tolist() == [1, 3, 5, 7, 9, 11]
-    for k in (1, 0):                                                   # 5 occupants in the way, 3 spare blocks
-        g.rearrange(k)
-        torch.cuda.synchronize()
+    for k in (1, 0):
+        with pytest.raises(rtams.RtamsError) as e:
+            g.rearrange(k)
+        assert e.value.code == rtams.ENOSPARE
         g.validate()
         assert g.poll_error() == 0
         assert [g.list_chain(j).tolist() for j in range(2)] == [c.tolist() for c in chains]
-    st = g.pool_stats()
-    assert st.blocks_in_use == 12 and st.blocks_free == 0
+        assert g.pool_stats().rearrangement_state == 2
     assert_lists_equal(g, o)
-    y = (w.centroids[0] + 0.5 * rng.standard_normal((64, w.d))).astype(np.float32)
-    g.add(dev(y)); o.add(y)
+    q = (w.centroids + 0.1).astype(np.float32)
+    dd, ii = g.search(dev(q), 10, 2)
+    rd, ri = o.search(q, 10, 2)
+    assert_topk_matches("l2", dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=1e-4, atol=1e-6)
+    g.close()
+
+
+def test_exceeding_lists_in_a_nearly_full_pool_are_compacted_a_few_blocks_at_a_time():
+    """Exceed() armed while the pool fills up to its last block: the rounds the adds carry move what the
+    spare blocks of the moment allow and keep the flag until the chain is contiguous; in the end either
+    nothing exceeds, or the pool is full and rearrange(-1) says that it is stalled without clearing
+    anything."""
+    w, g, o, rng = interleaved(nlist=2, rounds=5, pool_blocks=12, threshold=150, settle=True)
+    open_one_more_block_each(w, g, o, rng)
     g.validate()
+    assert_lists_equal(g, o)
+    st = g.pool_stats()
+    assert st.blocks_in_use == 12
+    if st.lists_exceeding:
+        with pytest.raises(rtams.RtamsError) as e:
+            g.rearrange(-1)
+        assert e.value.code == rtams.ENOSPARE
+        assert g.pool_stats().lists_exceeding == st.lists_exceeding
+        g.validate()
+        assert_lists_equal(g, o)
+    g.close()
+
+
+def test_the_last_batch_exceeds_and_nothing_follows():
+    """An add only carries the round that an EARLIER batch made necessary.  After the last batch of a
+    burst the list stays flagged (and scattered) until the caller asks: rearrange(-1) then compacts it."""
+    w, g, o, rng = interleaved(nlist=3, rounds=3, threshold=250)       # 192 per list: no trigger
+    y = (w.centroids[2] + 0.5 * rng.standard_normal((64, w.d))).astype(np.float32)  # 256 > 250
+    g.add(dev(y)); o.add(y)
+    st = g.pool_stats()
+    assert st.lists_exceeding == 1 and runs_of(g, 2) == 3              # blocks 2 | 5 | 8 9: nothing has moved yet
+    g.rearrange(-1)
+    g.validate()
+    st = g.pool_stats()
+    assert st.lists_exceeding == 0 and st.rearrangement_state == 0 and runs_of(g, 2) == 1
+    assert g.list_info(2)[2] == 0
     assert_lists_equal(g, o)
     g.close()
 
