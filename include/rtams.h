@@ -174,6 +174,22 @@ int rtams_add(rtams_index *ix, int64_t n, const float *d_vecs, const int64_t *d_
 int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k, int32_t nprobe,
                  float *d_out_dist, int64_t *d_out_ids, void *hip_stream);
 
+/* rtams_search for callers that cannot allocate and have no scratch of their own to hand over: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same answers,
+ * same kernels; the request's scratch is not a slice of the caller's d_scratch but an array in the device
+ * image of this library (32 MiB on every GPU the library runs on, held until the process ends; its
+ * address on the index's device is looked up once, in rtams_create).  Neither this call nor anything it
+ * launches allocates or frees memory.  Limits: nq at most 64 (EINVAL beyond; also EINVAL when the fixed
+ * part of a request of this index, which grows with nlist and max_nprobe, does not fit the array); a
+ * query's candidates beyond what the array holds behind that fixed part (about two million entries at
+ * nlist 16384, more with fewer lists) make that query come back empty with ESCRATCH, as for rtams_search
+ * without a reserve.  Every call on a GPU shares that GPU's array, which keeps the last call's contents
+ * (each request clears what it needs cleared): one request at a time.  A second call on the same index
+ * before the first has finished is refused with EBUSY; calls through DIFFERENT indexes on one GPU that
+ * overlap are not detected and race. */
+int rtams_search_noalloc(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k, int32_t nprobe,
+                         float *d_out_dist, int64_t *d_out_ids, void *hip_stream);
+
 /* Rearrangement algorithm of the paper: makes the blocks of `list` physically
  * contiguous behind its first block by exchanging blocks with their physical
  * neighbours.  list == -1 handles every list for which Exceed() holds.  The work

@@ -176,6 +176,33 @@ void lay_out_scratch(const rtams_config *c, ScratchLayout *S) {
   S->fixed = o;
 }
 
+// Search scratch for callers that cannot hand any over and must not allocate (rtams_search_noalloc):
+// one array in the device image of this library.  Every GPU the library runs on holds its own copy at
+// its own address until the process ends; the name below is only a host-side stand-in for the symbol,
+// never a device address: host code uses the pointer hipGetSymbolAddress returns for the current device.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+constexpr int kStaticMaxBatch = 64;  // queries of one rtams_search_noalloc call at most
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::mutex g_static_mutex;
+void *g_static_ptr[kMaxDevices] = {};  // per device: where its copy of `scratch` lies
+
+// Address of the current device's copy of the array, resolved once per device with that device current.
+int static_scratch_of_current_device(void **out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(RTAMS_EINVAL, "device %d outside 0..%d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> g(g_static_mutex);
+  if (!g_static_ptr[dev]) {
+    void *p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(RTAMS_EHIP, "hipGetSymbolAddress returned no address");
+    g_static_ptr[dev] = p;
+  }
+  *out = g_static_ptr[dev];
+  return RTAMS_OK;
+}
+
 enum { RES_FREE = 0, RES_BUSY = 1, RES_PENDING = 2 };
 
 struct Resource {
@@ -197,8 +224,10 @@ struct rtams_index {
   RearrangeScratch rearr{};
   HostMirror *mirror = nullptr;
   char *hook = nullptr;  // device scratch of the introspection calls
-  Resource *res = nullptr;
+  Resource *res = nullptr;  // n_res pooled ones over the caller's scratch, then one over the library's static array
   int n_res = 0;
+  bool static_ok = false;    // the static array holds a request of this index
+  int static_max_batch = 0;
   bool has_centroids = false;
   std::mutex data_mutex;  // add / rearrange / hooks: the single data stream of the paper
   hipStream_t data_stream = nullptr;
@@ -451,7 +480,7 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
       hipEventCreateWithFlags(&ix->fence_ev[1], hipEventDisableTiming) != hipSuccess)
     return bail(fail(RTAMS_EHIP, "hipEventCreate failed"));
 
-  ix->res = new (std::nothrow) Resource[cfg->n_resources];
+  ix->res = new (std::nothrow) Resource[cfg->n_resources + 1];
   if (!ix->res) return bail(fail(RTAMS_EINVAL, "out of host memory"));
   ix->n_res = cfg->n_resources;
   char *sb = static_cast<char *>(cfg->d_scratch);
@@ -469,9 +498,8 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   ix->ovf_leased = ovf_chunks ? reinterpret_cast<uint32_t *>(ovf) : nullptr;
   ix->ovf_chunks = ovf_chunks;
   ix->ovf_chunk_cap = ovf_chunk_cap;
-  for (int r = 0; r < ix->n_res; ++r) {
-    char *p = sb + (size_t)r * slice;
-    SearchScratch &S = ix->res[r].s;
+  auto lay_slice = [&](Resource &R, char *p, const ScratchLayout &SL, size_t slice_bytes, bool with_reserve) -> int {
+    SearchScratch &S = R.s;
     S.scores = reinterpret_cast<double *>(p + SL.scores);
     S.approx = reinterpret_cast<float *>(p + SL.approx);
     S.lut = reinterpret_cast<float *>(p + SL.lut);
@@ -494,22 +522,44 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
     S.item_cap = (uint32_t)SL.item_cap;
     S.queues = reinterpret_cast<ScanQueues *>(p + SL.queues);
     // the rest of the slice: two arrays of equal length
-    S.cand_cap = (slice - SL.fixed) / (2 * kAlign) * (kAlign / 4);
+    S.cand_cap = (slice_bytes - SL.fixed) / (2 * kAlign) * (kAlign / 4);
     S.rec_key = reinterpret_cast<uint32_t *>(p + SL.records);
     S.rec_pos = S.rec_key + S.cand_cap;
-    S.ovf_leased = ix->ovf_leased;
-    S.ovf_chunks = ovf_chunks;
-    S.ovf_chunk_cap = ovf_chunk_cap;
+    S.ovf_leased = with_reserve ? ix->ovf_leased : nullptr;
+    S.ovf_chunks = with_reserve ? ovf_chunks : 0u;
+    S.ovf_chunk_cap = with_reserve ? ovf_chunk_cap : 0ull;
     S.ovf_key = reinterpret_cast<uint32_t *>(ovf + kAlign);
     S.ovf_pos = S.ovf_key + ovf_chunk_cap * ovf_chunks;
     S.req_chunk = reinterpret_cast<uint32_t *>(p + SL.req_words);
     S.req_done = S.req_chunk + 1;
     S.req_cursor = reinterpret_cast<unsigned long long *>(p + SL.req_words + 8);
-    if (hipMemset(p + SL.req_words, 0, 16) != hipSuccess) return bail(fail(RTAMS_EHIP, "hipMemset of the scratch failed"));
-    if (hipEventCreateWithFlags(&ix->res[r].done, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&ix->res[r].scan_done, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreate(&ix->res[r].t0) != hipSuccess || hipEventCreate(&ix->res[r].t1) != hipSuccess)
-      return bail(fail(RTAMS_EHIP, "hipEventCreate failed"));
+    if (hipMemset(p + SL.req_words, 0, 16) != hipSuccess) return fail(RTAMS_EHIP, "hipMemset of the scratch failed");
+    if (hipEventCreateWithFlags(&R.done, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&R.scan_done, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreate(&R.t0) != hipSuccess || hipEventCreate(&R.t1) != hipSuccess)
+      return fail(RTAMS_EHIP, "hipEventCreate failed");
+    return RTAMS_OK;
+  };
+  for (int r = 0; r < ix->n_res; ++r) {
+    const int rc = lay_slice(ix->res[r], sb + (size_t)r * slice, SL, slice, true);
+    if (rc) return bail(rc);
+  }
+  // the extra resource over the library's static array, for requests of up to kStaticMaxBatch queries
+  // (its fixed part is laid out for that many; an index whose fixed part alone does not fit goes without)
+  {
+    rtams_config small = *cfg;
+    small.max_batch = cfg->max_batch < kStaticMaxBatch ? cfg->max_batch : kStaticMaxBatch;
+    ScratchLayout SS;
+    lay_out_scratch(&small, &SS);
+    void *sp = nullptr;
+    const int rc = static_scratch_of_current_device(&sp);
+    if (rc) return bail(rc);
+    ix->static_max_batch = small.max_batch;
+    ix->static_ok = SS.fixed + 64 * kAlign <= kStaticScratchBytes;
+    if (ix->static_ok) {
+      const int rc2 = lay_slice(ix->res[ix->n_res], static_cast<char *>(sp), SS, kStaticScratchBytes, false);
+      if (rc2) return bail(rc2);
+    }
   }
   if (hipDeviceSynchronize() != hipSuccess) return bail(fail(RTAMS_EHIP, "hipDeviceSynchronize failed"));
   *out = ix;
@@ -519,7 +569,7 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
 int rtams_destroy(rtams_index *ix) {
   if (!ix) return RTAMS_OK;
   if (ix->have_data_stream) (void)hipStreamSynchronize(ix->data_stream);
-  for (int r = 0; r < ix->n_res; ++r)
+  for (int r = 0; ix->res && r <= ix->n_res; ++r)
     if (ix->res[r].done) {
       (void)hipEventSynchronize(ix->res[r].done);
       (void)hipEventDestroy(ix->res[r].done);
@@ -621,8 +671,10 @@ int rtams_add(rtams_index *ix, int64_t n, const float *d_vecs, const int64_t *d_
   return RTAMS_OK;
 }
 
-int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k, int32_t nprobe,
-                 float *d_out_dist, int64_t *d_out_ids, void *hip_stream) {
+// What rtams_search and rtams_search_noalloc share: the argument checks, and the request itself on the
+// resource the caller took (pooled: a slice of the caller's scratch; n_res: the library's static array).
+static int check_search_args(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k, int32_t nprobe,
+                             float *d_out_dist, int64_t *d_out_ids) {
   if (!ix || nq < 0) return fail(RTAMS_EINVAL, "bad argument to search");
   if (nq > ix->cfg.max_batch) return fail(RTAMS_EINVAL, "nq %lld exceeds max_batch %d", (long long)nq, ix->cfg.max_batch);
   if (k < 1 || k > ix->cfg.max_k) return fail(RTAMS_EINVAL, "k %d outside 1..max_k %d", k, ix->cfg.max_k);
@@ -630,11 +682,12 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
     return fail(RTAMS_EINVAL, "nprobe %d outside 1..max_nprobe %d", nprobe, ix->cfg.max_nprobe);
   if (!ix->has_centroids) return fail(RTAMS_ESTATE, "search before set_centroids");
   if (ix->cfg.pq_m > 0 && !ix->has_codebooks) return fail(RTAMS_ESTATE, "search before set_codebooks");
-  if (nq == 0) return RTAMS_OK;
-  if (!d_queries || !d_out_dist || !d_out_ids) return fail(RTAMS_EINVAL, "NULL buffer");
-  std::shared_lock<std::shared_mutex> in_flight(ix->fence_mutex);
-  int r = acquire(ix);
-  if (r < 0) return fail(RTAMS_EBUSY, "all %d stream resources are in flight", ix->n_res);
+  if (nq > 0 && (!d_queries || !d_out_dist || !d_out_ids)) return fail(RTAMS_EINVAL, "NULL buffer");
+  return RTAMS_OK;
+}
+
+static int search_on(rtams_index *ix, int r, int64_t nq, const float *d_queries, int32_t k, int32_t nprobe,
+                     float *d_out_dist, int64_t *d_out_ids, void *hip_stream) {
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   Dev D = ix->dev;
   {  // flat float lists: large requests scan on the matrix cores (0 never, 1 from kMmMinBatch queries, 2 always)
@@ -680,6 +733,40 @@ int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k,
   return RTAMS_OK;
 }
 
+int rtams_search(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k, int32_t nprobe,
+                 float *d_out_dist, int64_t *d_out_ids, void *hip_stream) {
+  const int rc = check_search_args(ix, nq, d_queries, k, nprobe, d_out_dist, d_out_ids);
+  if (rc || nq == 0) return rc;
+  std::shared_lock<std::shared_mutex> in_flight(ix->fence_mutex);
+  const int r = acquire(ix);
+  if (r < 0) return fail(RTAMS_EBUSY, "all %d stream resources are in flight", ix->n_res);
+  return search_on(ix, r, nq, d_queries, k, nprobe, d_out_dist, d_out_ids, hip_stream);
+}
+
+int rtams_search_noalloc(rtams_index *ix, int64_t nq, const float *d_queries, int32_t k, int32_t nprobe,
+                         float *d_out_dist, int64_t *d_out_ids, void *hip_stream) {
+  const int rc = check_search_args(ix, nq, d_queries, k, nprobe, d_out_dist, d_out_ids);
+  if (rc || nq == 0) return rc;
+  if (nq > kStaticMaxBatch)
+    return fail(RTAMS_EINVAL, "nq %lld exceeds the %d queries a request on the library's static scratch may hold",
+                (long long)nq, kStaticMaxBatch);
+  if (!ix->static_ok)
+    return fail(RTAMS_EINVAL, "the fixed part of a request of this index (nlist %d, max_nprobe %d) does not fit the "
+                              "library's static scratch of %zu bytes", ix->cfg.nlist, ix->cfg.max_nprobe, kStaticScratchBytes);
+  std::shared_lock<std::shared_mutex> in_flight(ix->fence_mutex);
+  // the one resource over the static array: free, or its last request has finished
+  Resource &R = ix->res[ix->n_res];
+  int st = R.state.load(std::memory_order_acquire);
+  bool mine = false;
+  if (st == RES_FREE) mine = R.state.compare_exchange_strong(st, RES_BUSY, std::memory_order_acq_rel);
+  else if (st == RES_PENDING && hipEventQuery(R.done) == hipSuccess)
+    mine = R.state.compare_exchange_strong(st, RES_BUSY, std::memory_order_acq_rel);
+  (void)hipGetLastError();  // hipEventQuery leaves hipErrorNotReady behind
+  if (!mine) return fail(RTAMS_EBUSY, "the request before this one on the static scratch has not finished");
+  harvest(ix, R);
+  return search_on(ix, ix->n_res, nq, d_queries, k, nprobe, d_out_dist, d_out_ids, hip_stream);
+}
+
 // Grace period: the work enqueued next on the data stream starts only after
 // every search request that is in flight now has finished, and every search
 // enqueued from now on starts behind `ev` (the table switch just enqueued).
@@ -687,7 +774,7 @@ static int fence_searches(rtams_index *ix, hipEvent_t ev, hipStream_t s) {
   HIP_TRY(hipEventRecord(ev, s));
   std::unique_lock<std::shared_mutex> g(ix->fence_mutex);
   ix->fence_cur = ev;
-  for (int r = 0; r < ix->n_res; ++r)
+  for (int r = 0; r <= ix->n_res; ++r)  // the pooled resources and the one over the static array
     if (ix->res[r].state.load(std::memory_order_acquire) == RES_PENDING)
       HIP_TRY(hipStreamWaitEvent(s, ix->res[r].done, 0));
   return RTAMS_OK;

@@ -30,6 +30,7 @@ SYMBOLS = [
     "rtams_list_sizes", "rtams_pool_stats", "rtams_validate", "rtams_probe", "rtams_assign",
     "rtams_poll_error", "rtams_clear_error", "rtams_last_error", "rtams_set_param", "rtams_scan_time",
     "rtams_copy_plain", "rtams_read_plain", "rtams_set_codebooks", "rtams_list_export_codes",
+    "rtams_search_noalloc",
 ]
 
 
@@ -83,6 +84,7 @@ def lib():
         L.rtams_list_export_codes.argtypes = [vp, i32, i64, vp, vp, C.POINTER(i64), vp]
         L.rtams_add.argtypes = [vp, i64, vp, vp, vp]
         L.rtams_search.argtypes = [vp, i64, vp, i32, i32, vp, vp, vp]
+        L.rtams_search_noalloc.argtypes = [vp, i64, vp, i32, i32, vp, vp, vp]
         L.rtams_rearrange.argtypes = [vp, i32, vp]
         L.rtams_ntotal.argtypes = [vp, C.POINTER(i64)]
         L.rtams_list_size.argtypes = [vp, i32, C.POINTER(i64)]
@@ -223,6 +225,19 @@ class Index:
         _chk(lib().rtams_search(self._h, nq, q.data_ptr(), k, nprobe, out_dist.data_ptr(),
                                 out_ids.data_ptr(), _stream_ptr(stream)), "rtams_search")
         return out_dist, out_ids
+
+    def search_noalloc(self, queries: torch.Tensor, k: int, nprobe: int, out_dist: torch.Tensor,
+                       out_ids: torch.Tensor, stream=None) -> None:
+        """rtams_search_noalloc: the request's scratch is the library's static array; the caller brings
+        the output tensors ([nq][k] float32 and int64)."""
+        q = _dev_f32(queries, self.d, "queries")
+        nq = q.shape[0]
+        if not (out_dist.is_cuda and out_dist.dtype == torch.float32 and out_dist.is_contiguous()
+                and tuple(out_dist.shape) == (nq, k) and out_ids.is_cuda and out_ids.dtype == torch.int64
+                and out_ids.is_contiguous() and tuple(out_ids.shape) == (nq, k)):
+            raise ValueError("out_dist / out_ids must be contiguous CUDA tensors [nq][k] of float32 / int64")
+        _chk(lib().rtams_search_noalloc(self._h, nq, q.data_ptr(), k, nprobe, out_dist.data_ptr(),
+                                        out_ids.data_ptr(), _stream_ptr(stream)), "rtams_search_noalloc")
 
     def rearrange(self, lst: int = -1, stream=None) -> None:
         _chk(lib().rtams_rearrange(self._h, lst, _stream_ptr(stream)), "rtams_rearrange")
