@@ -121,6 +121,12 @@ size_t rtams_pool_bytes_for(const rtams_config *cfg, int64_t blocks);
  * (rtams_poll_error) for the queries that fit neither. */
 size_t rtams_scratch_bytes_for(const rtams_config *cfg, int64_t candidates_per_query);
 
+/* Bytes of the shared reserve (the overflow_bytes of the configuration, to be added to d_scratch behind
+ * the resources' slices) for `chunks` chunks of `candidates_per_chunk` candidate entries each: the
+ * lease words and, per chunk, room for the key and the position of every entry.  0 on bad arguments
+ * (chunks outside 1..32, a negative count). */
+size_t rtams_overflow_bytes_for(int32_t chunks, int64_t candidates_per_chunk);
+
 /* Creates the index over caller-owned device memory (both regions 256-byte
  * aligned).  Lays out the pool, clears its control data, creates the stream
  * resources.  Synchronous. EINVAL when a size does not fit (rtams_last_error()
@@ -257,21 +263,6 @@ const char *rtams_last_error(void);
 int rtams_list_export_codes(rtams_index *ix, int32_t list, int64_t cap, int64_t *d_ids, uint8_t *d_codes,
                             int64_t *n_out, void *hip_stream);
 
-/* Measured duration of the list-scan kernel: with the parameter "profile_scan"
- * set to 1, every search brackets its scan launch with two HIP events on the
- * caller's stream; this call adds up the pairs of the requests that have
- * finished (ms_sum in milliseconds, launches = how many) and optionally resets
- * the sums.  Does not synchronise. */
-int rtams_scan_time(rtams_index *ix, double *ms_sum, int64_t *launches, int reset);
-/* Measurement aid, not part of the method: a plain device-to-device copy kernel
- * (bytes a multiple of 16).  Profiler counters of HBM traffic are scaled by
- * what they read for this kernel, whose traffic is known. */
-int rtams_copy_plain(void *d_dst, const void *d_src, size_t bytes, void *hip_stream);
-/* Measurement aid, not part of the method: a kernel that only reads `bytes`
- * (a multiple of 16) of device memory; d_sink points to 4 bytes of device
- * memory it may write.  Its rate is the practical ceiling a streaming read
- * reaches on the chip, reported beside the list scan's. */
-int rtams_read_plain(const void *d_src, size_t bytes, float *d_sink, void *hip_stream);
 /* Launch-shape knobs (Stream-Cached Multi-Stream Execution, consideration 2: a
  * kernel's blocks and threads are capped so that several kernels run side by side).  key: "scan_max_items"
  * (most work items, one wavefront each, one list-scan launch is cut

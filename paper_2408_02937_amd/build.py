@@ -9,7 +9,8 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librtams.so")
 SOURCES = ["rtams.hip", "coarse.hip", "coarse_mfma.hip", "insert.hip", "pq.hip", "probe.hip", "group.hip", "scan.hip", "scan_mm.hip",
            "pq_scan.hip", "select.hip", "rearrange.hip", "maint.hip"]
-HEADERS = ["rtams_dev.h", "rtams_launch.h", "search_common.h", os.path.join("..", "..", "include", "rtams.h")]
+HEADERS = ["rtams_dev.h", "rtams_launch.h", "search_common.h", os.path.join("..", "..", "include", "rtams.h"),
+           os.path.join("..", "..", "include", "rtams_measure.h")]
 
 # packed-fp32 instructions are switched off for every device compilation
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

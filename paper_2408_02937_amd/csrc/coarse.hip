@@ -9,7 +9,8 @@ namespace rtams {
 
 constexpr int kCoarseThreads = 256;
 
-int coarse_vt(int d) { return d <= 1024 ? 8 : 4; }
+// vectors per workgroup: their coordinates sit in LDS as doubles, 48 KiB at most (the workgroup has 3 KiB of its own)
+int coarse_vt(int d) { return d <= 768 ? 8 : d <= 1536 ? 4 : 2; }
 // ... and fewer for a small batch: every slot of a tile costs a full chain of fp64 operations per
 // centroid whether a vector sits in it or not, and a batch of a few tiles leaves most of the chip
 // idle (one workgroup per tile and centroid split).  The largest tile that still yields a

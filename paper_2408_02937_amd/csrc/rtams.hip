@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/rtams.h: pool layout, stream
 // resources, and the enqueue-only entry points.
 #include "../../include/rtams.h"
+#include "../../include/rtams_measure.h"
 
 #include <atomic>
 #include <cstdarg>
@@ -385,6 +386,12 @@ size_t rtams_scratch_bytes_for(const rtams_config *cfg, int64_t candidates_per_q
   lay_out_scratch(cfg, &S);
   // key and position of a surviving candidate: 8 bytes each, room for all of them
   return up(S.fixed + 2 * up((size_t)cfg->max_batch * (size_t)candidates_per_query * 4, kAlign), kAlign);
+}
+
+size_t rtams_overflow_bytes_for(int32_t chunks, int64_t candidates_per_chunk) {
+  if (chunks < 1 || chunks > kMaxOverflowChunks || candidates_per_chunk < 0) return 0;
+  // the lease words, then two arrays (keys, positions) cut into chunks of whole 256-byte units
+  return kAlign + 2 * (size_t)chunks * up((size_t)candidates_per_chunk * 4, kAlign);
 }
 
 int rtams_create(const rtams_config *cfg, rtams_index **out) {

@@ -22,7 +22,7 @@ STORAGE = {"f32": 0, "f16": 1, "u8": 2}  # what flat lists keep of a coordinate
 _NAMES = {EINVAL: "EINVAL", ESTATE: "ESTATE", EPOOL: "EPOOL", EBUSY: "EBUSY", EHIP: "EHIP",
           ESCRATCH: "ESCRATCH", ENOSPARE: "ENOSPARE"}
 
-# every symbol include/rtams.h declares
+# every symbol include/rtams.h and include/rtams_measure.h declare
 SYMBOLS = [
     "rtams_pool_bytes_for", "rtams_scratch_bytes_for", "rtams_create", "rtams_destroy",
     "rtams_set_centroids", "rtams_add", "rtams_search", "rtams_rearrange", "rtams_ntotal",
@@ -30,7 +30,7 @@ SYMBOLS = [
     "rtams_list_sizes", "rtams_pool_stats", "rtams_validate", "rtams_probe", "rtams_assign",
     "rtams_poll_error", "rtams_clear_error", "rtams_last_error", "rtams_set_param", "rtams_scan_time",
     "rtams_copy_plain", "rtams_read_plain", "rtams_set_codebooks", "rtams_list_export_codes",
-    "rtams_search_noalloc",
+    "rtams_search_noalloc", "rtams_overflow_bytes_for",
 ]
 
 
@@ -77,6 +77,8 @@ def lib():
         L.rtams_pool_bytes_for.argtypes = [cp, i64]
         L.rtams_scratch_bytes_for.restype = C.c_size_t
         L.rtams_scratch_bytes_for.argtypes = [cp, i64]
+        L.rtams_overflow_bytes_for.restype = C.c_size_t
+        L.rtams_overflow_bytes_for.argtypes = [i32, i64]
         L.rtams_create.argtypes = [cp, C.POINTER(vp)]
         L.rtams_destroy.argtypes = [vp]
         L.rtams_set_centroids.argtypes = [vp, vp, vp]
@@ -164,10 +166,12 @@ class Index:
             raise RtamsError(EINVAL, "scratch_bytes_for", L.rtams_last_error().decode())
         # caller-owned device memory: one pool, one scratch area
         self.pool = torch.empty(pool_bytes, dtype=torch.uint8, device=self.device)
-        # the reserve shared by all resources: lease words (256 bytes), then overflow_chunks chunks of
-        # overflow_candidates entries (8 bytes each, in two arrays)
-        overflow_bytes = (256 + 2 * overflow_chunks * ((overflow_candidates * 4 + 255) // 256 * 256)
-                          if overflow_candidates > 0 else 0)
+        # the reserve shared by all resources: overflow_chunks chunks of overflow_candidates entries
+        overflow_bytes = 0
+        if overflow_candidates > 0:
+            overflow_bytes = L.rtams_overflow_bytes_for(overflow_chunks, overflow_candidates)
+            if overflow_bytes == 0:
+                raise RtamsError(EINVAL, "overflow_bytes_for", "overflow_chunks must be in 1..32")
         scratch_bytes = per_res * n_resources + overflow_bytes
         self.scratch = torch.empty(scratch_bytes, dtype=torch.uint8, device=self.device)
         cfg.d_pool, cfg.pool_bytes = self.pool.data_ptr(), pool_bytes

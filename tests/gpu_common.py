@@ -9,7 +9,7 @@ import torch
 
 from oracle.oracle import OracleIndex
 from paper_2408_02937_amd import rtams
-from tests.helpers import assert_topk_matches
+from tests.helpers import ATOL, RTOL, assert_topk_matches
 
 
 def dev(a: np.ndarray) -> torch.Tensor:
@@ -73,15 +73,15 @@ def assert_lists_equal(g, o, batch_bounds=None):
     assert st.ntotal == o.ntotal and st.blocks_in_use == o.blocks_in_use
 
 
-def _matches(metric, d, i, rd, ri):
+def _matches(metric, d, i, rd, ri, atol=ATOL):
     try:
-        assert_topk_matches(metric, d[None], i[None], rd[None], ri[None], rtol=1e-4, atol=1e-5)
+        assert_topk_matches(metric, d[None], i[None], rd[None], ri[None], rtol=RTOL, atol=atol)
         return True
     except AssertionError:
         return False
 
 
-def whole_batches_check(w, g, o, n_search_threads):
+def whole_batches_check(w, g, o, n_search_threads, atol=ATOL):
     """Base set in, then the insert stream batch by batch on a data stream while searcher threads
     query on streams of their own.  A search must see whole batches only: its answer equals the
     oracle's on SOME prefix of the batches, between those finished before it was submitted and those
@@ -136,7 +136,7 @@ def whole_batches_check(w, g, o, n_search_threads):
             d, i = od.cpu().numpy(), oi.cpu().numpy()
             for r in range(len(qh)):
                 ok = [p for p in range(lo, hi + 1)
-                      if _matches(w.metric, d[r], i[r], expected[p][0][r], expected[p][1][r])]
+                      if _matches(w.metric, d[r], i[r], expected[p][0][r], expected[p][1][r], atol)]
                 if not ok:
                     bad.append(f"query {r}: no batch prefix in [{lo}, {hi}] explains the result"); return
             checked[0] += 1
@@ -158,4 +158,4 @@ def whole_batches_check(w, g, o, n_search_threads):
     g.validate()
     d, i = g.search(q, w.k, w.nprobe)                   # at rest: exactly the last prefix
     assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), expected[-1][0], expected[-1][1],
-                        rtol=1e-4, atol=1e-5)
+                        rtol=RTOL, atol=atol)

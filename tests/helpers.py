@@ -7,6 +7,13 @@ from fractions import Fraction
 import numpy as np
 
 
+# The tolerance of every comparison of fp32 scores with the oracle's doubles: 1e-4 relative (the figure the
+# build states) plus 1e-6 absolute for scores near zero.  Scores of product-quantised lists are sums of M
+# table entries, each rounded to fp32 on its own, of either sign for inner products: their absolute part
+# is 1e-5.
+RTOL, ATOL, ATOL_PQ = 1e-4, 1e-6, 1e-5
+
+
 def brute_force_scores(metric: str, X: np.ndarray, q: np.ndarray) -> np.ndarray:
     """Exact-definition scores of one query against every row of X, in float64."""
     X64, q64 = X.astype(np.float64), q.astype(np.float64)
@@ -33,9 +40,12 @@ def brute_force_topk(metric: str, X: np.ndarray, ids: np.ndarray, q: np.ndarray,
 
 def assert_topk_matches(metric, got_d, got_i, ref_d, ref_i, rtol, atol=0.0, what=""):
     """got == ref up to ties: distances agree position by position within the
-    tolerance; an id may differ only where its reference distance is within the
-    tolerance of the distance of the position it is compared with or of the
-    k-th (boundary) distance."""
+    tolerance; an id may differ only where its reference distance is within TWICE
+    the tolerance of the distance of the position it is compared with or of the
+    k-th (boundary) distance.  (Twice: the implementation ranks by its own scores,
+    each within the tolerance t of the reference; two candidates it puts the other
+    way round therefore lie within 2 t of each other in the reference, and no closer
+    bound holds.)"""
     got_d, ref_d = np.asarray(got_d, dtype=np.float64), np.asarray(ref_d, dtype=np.float64)
     assert got_d.shape == ref_d.shape and got_i.shape == ref_i.shape, what
     fin = np.isfinite(ref_d)

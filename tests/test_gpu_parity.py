@@ -273,6 +273,35 @@ def test_odd_shapes(shape):
     g.close()
 
 
+@pytest.mark.parametrize("d,metric", [(1024, "l2"), (2048, "ip"), (2048, "l2")])
+def test_widest_vectors(d, metric):
+    """The widest vectors the configuration accepts (d up to 2048): the coarse kernel's tile of vectors
+    and the scans' tiles of queries have to fit LDS; assignment, lists, probes and searches as ever."""
+    rng = np.random.default_rng(d)
+    nlist = 48
+    C = rng.standard_normal((nlist, d)).astype(np.float32)
+    w = synth.Workload("wide-vectors", metric, d, nlist, 64, 8, 10, np.zeros((0, d), np.float32), C,
+                       np.zeros((0, d), np.float32), np.zeros((0, d), np.float32), 1, 0)
+    g, o = make_pair(w, pool_blocks=200, candidates_per_query=6000)
+    y = (C[rng.integers(0, nlist, 3000)] + 0.3 * rng.standard_normal((3000, d))).astype(np.float32)
+    for use_mfma in (0, 2):
+        g.set_param("use_mfma", use_mfma)
+        assert np.array_equal(g.assign(dev(y[:300])).cpu().numpy(), o.assign(y[:300])), f"use_mfma {use_mfma}"
+    g.add(dev(y)); o.add(y)
+    g.validate()
+    assert_lists_equal(g, o)
+    q = (C[rng.integers(0, nlist, 70)] + 0.3 * rng.standard_normal((70, d))).astype(np.float32)
+    for nq in (1, 70):
+        assert np.array_equal(g.probe(dev(q[:nq]), 8).cpu().numpy(), o.probe(q[:nq], 8))
+        rd, ri = o.search(q[:nq], 10, 8)
+        for mode in scan_modes(g):
+            dd, ii = g.search(dev(q[:nq]), 10, 8)
+            assert g.poll_error() == 0
+            assert_topk_matches(metric, dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-6,
+                                what=f"d {d} batch {nq} scan_mfma {mode}")
+    g.close()
+
+
 def test_loose_bound_and_worst_first_records():
     """The pruning bound of a query comes from the head of its nearest list.  Here that head is 600
     decoys far from the query, so every candidate passes the bound, and the true neighbours sit

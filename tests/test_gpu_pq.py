@@ -9,7 +9,7 @@ import torch
 from oracle.oracle import OracleIndex
 from paper_2408_02937_amd import rtams, synth
 from tests.gpu_common import dev, whole_batches_check
-from tests.helpers import assert_topk_matches
+from tests.helpers import ATOL_PQ, assert_topk_matches
 
 pytestmark = pytest.mark.gpu
 
@@ -94,7 +94,7 @@ def test_pq_search_matches_oracle(loaded, batch):
     torch.cuda.synchronize()
     assert g.poll_error() == 0
     rd, ri = o.search(q, w.k, w.nprobe)
-    assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-5,
+    assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), rd, ri, rtol=RTOL, atol=ATOL_PQ,
                         what=f"{w.name} batch {batch}")
 
 
@@ -105,7 +105,7 @@ def test_pq_search_all_lists_and_large_k(loaded):
     d, i = g.search(dev(q), 128, nprobe)
     torch.cuda.synchronize()
     rd, ri = o.search(q, 128, nprobe)
-    assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-5)
+    assert_topk_matches(w.metric, d.cpu().numpy(), i.cpu().numpy(), rd, ri, rtol=RTOL, atol=ATOL_PQ)
 
 
 def test_integer_valued_tables_make_the_scores_exact():
@@ -175,7 +175,7 @@ def test_rearrangement_moves_coded_blocks_intact():
         assert g.list_info(k)[1] == 1
         assert_code_lists_equal(g, o)
         dd, ii = g.search(dev(x[:64]), 10, 3)
-        assert_topk_matches("l2", dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=1e-5)
+        assert_topk_matches("l2", dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=RTOL, atol=ATOL_PQ)
     g.close()
 
 
@@ -212,7 +212,7 @@ def test_pq_search_sees_whole_batches_only():
                           insert_batch=50, nlist=64, block_vecs=64)
     cb = synth.codebooks_from_rows(w.seed, w.base, 8)
     g, o = make_pq_pair(w, 8, cb, n_resources=8)
-    whole_batches_check(w, g, o, 2)
+    whole_batches_check(w, g, o, 2, atol=ATOL_PQ)
     assert_code_lists_equal(g, o)
     g.close()
 

@@ -9,7 +9,7 @@ import torch
 from oracle.oracle import OracleIndex
 from paper_2408_02937_amd import rtams, synth
 from tests.gpu_common import assert_lists_equal, dev
-from tests.helpers import assert_topk_matches
+from tests.helpers import ATOL, ATOL_PQ, assert_topk_matches
 
 pytestmark = pytest.mark.gpu
 
@@ -88,7 +88,7 @@ def test_random_operations_against_the_oracle(seed):
             assert g.poll_error() == 0, f"step {step}"
             rd, ri = o.search(q, k, nprobe)
             assert_topk_matches(metric, dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=1e-4,
-                                atol=1e-5 if pq else 1e-6, what=f"step {step}: nq {nq} k {k} nprobe {nprobe} scan_mfma {scan_mfma}")
+                                atol=ATOL_PQ if pq else ATOL, what=f"step {step}: nq {nq} k {k} nprobe {nprobe} scan_mfma {scan_mfma}")
     torch.cuda.synchronize()
     g.validate()
     assert g.poll_error() == 0

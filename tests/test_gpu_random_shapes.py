@@ -8,7 +8,7 @@ import torch
 from oracle.oracle import OracleIndex
 from paper_2408_02937_amd import rtams, synth
 from tests.gpu_common import assert_lists_equal, dev
-from tests.helpers import assert_topk_matches
+from tests.helpers import ATOL, ATOL_PQ, assert_topk_matches
 
 pytestmark = pytest.mark.gpu
 
@@ -89,6 +89,6 @@ def test_random_shape(c):
         torch.cuda.synchronize()
         assert g.poll_error() == 0
         rd, ri = o.search(q, c["k"], c["nprobe"])
-        assert_topk_matches(c["metric"], dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=1e-4, atol=1e-5,
+        assert_topk_matches(c["metric"], dd.cpu().numpy(), ii.cpu().numpy(), rd, ri, rtol=1e-4, atol=ATOL_PQ if c.get("pq") else ATOL,
                             what=f"batch {bs}")
     g.close()

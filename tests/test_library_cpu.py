@@ -12,9 +12,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def header_symbols():
-    text = open(os.path.join(ROOT, "include", "rtams.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(rtams_[a-z_]+)\s*\(", text)))
+    found = set()
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):  # rtams.h and rtams_measure.h
+        text = open(os.path.join(ROOT, "include", name)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        found |= set(re.findall(r"\b(rtams_[a-z_]+)\s*\(", text))
+    return sorted(found)
 
 
 def test_library_exports_every_declared_symbol():
@@ -30,6 +33,14 @@ def cfg(**kw):
                 max_batch=16, max_k=10, max_nprobe=8, max_add_batch=1024)
     base.update(kw)
     return rtams.Config(**base)
+
+
+def test_reserve_size_arithmetic():
+    L = rtams.lib()
+    f = L.rtams_overflow_bytes_for
+    assert f(4, 1000) == 256 + 2 * 4 * 4096          # 4000 bytes round up to whole 256-byte units
+    assert f(1, 64) == 256 + 2 * 256 and f(32, 0) == 256
+    assert f(0, 10) == 0 and f(33, 10) == 0 and f(4, -1) == 0
 
 
 def test_pool_size_arithmetic():
