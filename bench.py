@@ -421,7 +421,7 @@ def main() -> int:
         fn = {"rearrange": studies.rearrangement_study, "blocksize": studies.block_size_sweep,
               "pq": studies.pq_study, "storage": studies.storage_study, "shapes": studies.shape_study,
               "mixed": studies.mixed_load_study, "growth": studies.growth_study,
-              "rearrange5": getattr(studies, "hot_list_rearrangement_study", None)}[args.study]
+              "rearrange5": studies.hot_list_rearrangement_study}[args.study]
         iters = args.latency_iters or 2000
         if args.study == "pq" and args.pq_m:
             print(json.dumps(fn(scale=args.scale, iters=iters, ms=(args.pq_m,), batches=(args.batch or 256,))))

@@ -5,6 +5,9 @@
   vector goes to one list until it holds T_m' of them; search latency before,
   the cost of rearranging that list, search latency after, and what searches
   see while the rearrangement runs.
+* `hot_list_rearrangement_study`: the same table on the skewed configuration's
+  hottest list (millions of vectors), grown by 10,000 / 50,000 / 100,000 online
+  vectors.
 * `block_size_sweep`: the analogue of the paper's block-size figure ("Effects
   of memory block size"): latency, scan rate and pad memory as T_m grows.
 
@@ -149,6 +152,101 @@ def rearrangement_study(scale: float = 1.0, thresholds=(10_000, 50_000, 100_000)
         })
         g.close()
     return {"study": "rearrangement", "workload": w.name, "block_vecs": w.block_vecs, "rows": rows}
+
+
+def hot_list_rearrangement_study(scale: float = 1.0, thresholds=(10_000, 50_000, 100_000), iters: int = 100) -> dict:
+    """The paper's rearrangement table on the skewed configuration (20 M x 256 under a Zipf(1.1) law): T_m' + 1
+    online vectors all go to the HOTTEST list (millions of vectors, thousands of blocks, made contiguous
+    after the bulk load), in batches of 1024 that alternate with batches of ordinary traffic so that the
+    list's new blocks interleave with other lists'.  Search latency (queries that probe the hot list;
+    batches of 1, 10 and 256) before, the wall time of rearranging the list while a searcher runs beside
+    it, latency after.  One index for all thresholds: the hot list keeps growing."""
+    dev = torch.device("cuda:0")
+    w = synth.config(5, scale=scale)
+    rng = np.random.Generator(np.random.PCG64([w.seed, 78]))
+    cents, inserts = (_to_dev(a, dev) for a in (w.centroids, w.inserts))
+    n_online = sum(t + 1 for t in thresholds)
+    n_all = len(w.base) + 2 * n_online + 64 * w.insert_batch
+    g = rtams.Index(w.d, w.nlist, w.metric, w.block_vecs, pool_blocks=n_all // w.block_vecs + 3 * w.nlist + 8192,
+                    n_resources=8, max_batch=256, max_k=64, max_nprobe=64, max_add_batch=65536,
+                    candidates_per_query=max(65536, (len(w.base) + 2 * n_online) // 4))
+    ds, ss, s2 = torch.cuda.Stream(dev), torch.cuda.Stream(dev), torch.cuda.Stream(dev)
+    g.set_centroids(cents, stream=ds)
+    for lo in range(0, len(w.base), 1 << 22):
+        part = _to_dev(w.base[lo:lo + (1 << 22)], dev)
+        g.add(part, stream=ds)
+        ds.synchronize()
+        del part
+    sizes = g.list_sizes()
+    hot = int(sizes.argmax())
+    t0 = time.perf_counter()
+    g.rearrange(hot, stream=ds)  # the offline segment is contiguous
+    ds.synchronize()
+    first_ms = (time.perf_counter() - t0) * 1e3
+    blocks0, runs0, _ = g.list_info(hot)
+    rows = []
+    ib = w.insert_batch
+    j = 0
+    for thr in thresholds:
+        n_hot = thr + 1
+        hv = _to_dev((w.centroids[hot][None, :] + 0.1 * rng.standard_normal((n_hot, w.d))).astype(np.float32), dev)
+        on_hot = float((g.assign(hv[:4096]).cpu().numpy() == hot).mean())
+        for o in range(0, n_hot, ib):  # a batch into the hot list, a batch of ordinary traffic, in turn
+            g.add(hv[o:o + ib], stream=ds)
+            g.add(inserts[(j % (len(inserts) // ib)) * ib:(j % (len(inserts) // ib)) * ib + ib], stream=ds)
+            j += 1
+        ds.synchronize()
+        blocks, runs_before, _ = g.list_info(hot)
+        qh = hv[:2560]
+        batches = (1, 10, 256)
+        before = {bs: _search_latencies(g, qh, bs, w.k, w.nprobe, iters, ss, dev) for bs in batches}
+        during, stop = [], threading.Event()
+
+        def searcher():
+            od = torch.empty((10, w.k), dtype=torch.float32, device=dev)
+            oi = torch.empty((10, w.k), dtype=torch.int64, device=dev)
+            i = 0
+            while not stop.is_set():
+                t = time.perf_counter()
+                g.search(qh[(i % 100) * 10:(i % 100) * 10 + 10], w.k, w.nprobe, od, oi, stream=s2)
+                s2.synchronize()
+                during.append((t, (time.perf_counter() - t) * 1e3))
+                i += 1
+
+        th = threading.Thread(target=searcher)
+        th.start()
+        time.sleep(0.05)
+        t0 = time.perf_counter()
+        g.rearrange(hot, stream=ds)
+        ds.synchronize()
+        t1 = time.perf_counter()
+        time.sleep(0.02)
+        stop.set()
+        th.join()
+        overl = [l for (t, l) in during if t + l * 1e-3 >= t0 and t <= t1]
+        quiet = [l for (t, l) in during if t + l * 1e-3 < t0]
+        _, runs_after, _ = g.list_info(hot)
+        after = {bs: _search_latencies(g, qh, bs, w.k, w.nprobe, iters, ss, dev) for bs in batches}
+        assert g.poll_error() == 0
+        rows.append({
+            "threshold": thr, "hot_list_len": int(g.list_sizes()[hot]), "blocks": int(blocks),
+            "share_of_online_vectors_on_hot_list": on_hot,
+            "runs_before": int(runs_before), "runs_after": int(runs_after),
+            "rearrange_cost_ms": (t1 - t0) * 1e3,
+            "latency_ms": {str(bs): {"before_p50": _p(before[bs], 50), "before_p99": _p(before[bs], 99),
+                                     "after_p50": _p(after[bs], 50), "after_p99": _p(after[bs], 99)}
+                           for bs in batches},
+            "searches_during_rearrangement": {"count": len(overl), "max_ms": max(overl) if overl else None,
+                                              "quiet_p50_ms": _p(quiet, 50), "quiet_max_ms": max(quiet) if quiet else None},
+        })
+    g.validate()
+    st = g.pool_stats()
+    out = {"study": "hot_list_rearrangement", "workload": w.name, "n_base": len(w.base), "block_vecs": w.block_vecs,
+           "hot_list": hot, "hot_list_len_after_bulk_load": int(sizes[hot]), "hot_list_blocks_after_bulk_load": int(blocks0),
+           "first_rearrangement_ms": first_ms, "runs_after_first_rearrangement": int(runs0),
+           "blocks_in_use": st.blocks_in_use, "rows": rows}
+    g.close()
+    return out
 
 
 def block_size_sweep(scale: float = 1.0, sizes=(64, 128, 256, 512, 1024, 2048), iters: int = 200) -> dict:
