@@ -61,7 +61,7 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
     yn = 0.f;
     for (int w = 0; w < kSelThreads / kWave; ++w) yn += s_red[w];
     const float cmax = __uint_as_float(D.ctrl->cnorm_max_bits);
-    const float band = 8.f * (float)(D.d + 4) * 5.9604645e-8f * (yn + cmax) * 1.01f;  // 2 E, see coarse_mfma.hip
+    const float band = coarse_band(D.d, yn + cmax) * 1.01f;  // 2 E, see coarse_mfma.hip
     const SelectResult ra = wg_radix_select<32>(
         n, (uint32_t)nprobe, [&](int i, uint64_t &k) { k = key_of_float(ap[i] + 0.0f); return true; }, hist, bc);
     const uint32_t tk = (uint32_t)ra.T;  // key of (an upper bound of) the nprobe-th smallest approximation

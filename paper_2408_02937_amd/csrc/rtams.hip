@@ -38,7 +38,7 @@ inline size_t up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Byte offsets of everything in front of the blocks.
 struct Layout {
-  size_t ctrl, hook, centroids, cnorm, codebooks, codebooks_t, tc_min, tc_cnt, tc_col, tc_val, tile_rows, reserved_len, visible_len, online, nblk, exceed, seg_dir;
+  size_t ctrl, hook, centroids, cnorm, csplit, codebooks, codebooks_t, tc_min, tc_cnt, tc_col, tc_val, tile_rows, reserved_len, visible_len, online, nblk, exceed, seg_dir;
   size_t ins_assign, ins_did, ins_pscore, ins_pidx, part_cap;
   size_t rearr_head, rearr_arrays;
   size_t fixed_end;          // end of the part that does not depend on the block count
@@ -93,6 +93,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
   L->hook = take(kHookBytes);
   L->centroids = take(nl * c->d * sizeof(float));
   L->cnorm = take(nl * sizeof(float));
+  L->csplit = take(nl * (size_t)((c->d + 7) / 8) * 32);
   L->codebooks = take(c->pq_m > 0 ? (size_t)256 * c->d * sizeof(float) : 0);
   L->codebooks_t = take(c->pq_m > 0 ? (size_t)256 * c->d * sizeof(float) : 0);
   L->reserved_len = take(nl * 4);
@@ -433,6 +434,8 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   D.ctrl = reinterpret_cast<Ctrl *>(base + L.ctrl);
   D.centroids = reinterpret_cast<float *>(base + L.centroids);
   D.cnorm = reinterpret_cast<float *>(base + L.cnorm);
+  D.csplit = reinterpret_cast<u32x4 *>(base + L.csplit);
+  D.dgroups = (cfg->d + 7) / 8;
   D.codebooks = reinterpret_cast<float *>(base + L.codebooks);
   D.codebooks_t = reinterpret_cast<float *>(base + L.codebooks_t);
   D.pq_m = cfg->pq_m;

@@ -53,6 +53,8 @@ struct HostMirror {
   volatile uint32_t rearr_state;  // of the last rearrangement round: 0 done, 1 another round owed, 2 stalled for lack of a spare block
 };
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 struct Dev {
   int32_t d, nlist, metric, T_m;
   int32_t pq_m;             // 0: flat lists; M > 0: product-quantiser codes, M bytes per vector
@@ -74,6 +76,8 @@ struct Dev {
   HostMirror *mirror;       // pinned host memory, device-visible
   float *centroids;         // [nlist][d]
   float *cnorm;             // [nlist] squared norms of the centroids (fp32)
+  u32x4 *csplit;            // [nlist][dgroups][2] the centroids as bf16 halves: per group of 8 coordinates the 8 hi, then the 8 lo
+  int32_t dgroups;          // groups of 8 coordinates of a centroid: ceil(d / 8)
   float *codebooks;         // [pq_m][256][d / pq_m] (product-quantised lists only)
   float *codebooks_t;       // the same with the entries innermost: [pq_m][d / pq_m][256] (for coding inserted vectors)
   uint32_t *reserved_len;   // [nlist] next free position (atomicAdd target)

@@ -125,7 +125,12 @@ inline bool mfma_pays_for_search(int64_t nq, int64_t nlist) { return nq >= 32 &&
 inline bool mfma_pays_for_assign(int64_t m, int64_t nlist) {
   return m >= 32 && m * nlist >= (nlist >= 8192 ? (int64_t)1 << 19 : (int64_t)1 << 20);
 }
-void launch_centroid_norms(const Dev &D, hipStream_t s);
+// Twice the error bound of an approximate score, for a vector of squared norm |y|^2 (norms = |y|^2 + max |c|^2):
+// the exact best lies among the centroids whose approximation is within this of the smallest one.
+__host__ __device__ inline float coarse_band(int d, float norms) {
+  return (8.f * (float)(d + 4) * 5.9604645e-8f + 8.f * 1.52587890625e-5f) * norms;
+}
+void launch_centroid_norms(const Dev &D, hipStream_t s);  // and the centroids' split form
 void launch_coarse_mfma(const Dev &D, int64_t n, const float *Y, float *approx,
                         unsigned long long *cursor_to_clear, uint32_t *zero, int zero_n, hipStream_t s);
 int coarse_tiles(const Dev &D);
