@@ -8,8 +8,9 @@
 // hi = bf16(x), lo = bf16(x - hi), |r| <= 2^-16 |x|.  Three products,
 // hi hi + hi lo + lo hi (each exact in fp32, accumulated in fp32), leave out
 // lo lo and the two r terms: at most 3.02 * 2^-16 |x c| per coordinate.  The
-// centroids are split once, when they are set; the vectors on their way into
-// LDS.
+// centroids are split once, when they are set; the vectors of a batch by a
+// small kernel in front of the contraction, which then only copies 16-byte
+// operands from memory to LDS to the matrix cores.
 //
 // The approximate scores only FILTER.  Which list a vector joins and which
 // lists a query probes are decided by the fixed double-precision arithmetic of
@@ -40,9 +41,11 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kMfmaThreads = 256;  // 4 wavefronts: 2 (rows) x 2 (columns), 64 x 64 results each
 constexpr int kTileM = 128, kTileN = 128, kTileK = 32;
-// an operand row in LDS: the tile's 4 groups of 8 bf16 (16 bytes each) and 16 bytes of padding, so that
-// the rows 8 neighbouring lanes read start 20 banks apart and cover all 32
-constexpr int kRowBytes = (kTileK / 8) * 16 + 16;
+// an operand row in LDS: the tile's 4 groups of 8 bf16 (16 bytes each), group g of row r at place
+// g ^ ((r >> 1) & 3) of the row's 4: the 8 rows that neighbouring lanes read or write then cover all
+// 32 banks once, with no padding
+constexpr int kRowBytes = (kTileK / 8) * 16;
+__device__ inline int lds_place(int row, int g) { return row * kRowBytes + ((g ^ ((row >> 1) & 3)) * 16); }
 constexpr int kXcds = 8;  // workgroups go to the chip's 8 dies (each with its own L2) in turn
 
 // the two bf16 halves of a pair of floats, packed as the matrix instruction wants them
@@ -80,34 +83,56 @@ __global__ __launch_bounds__(256) void k_centroid_norms(Dev D) {
   atomicMax(&D.ctrl->cnorm_max_bits, __float_as_uint(n));  // non-negative floats order like their bits
 }
 
-__global__ __launch_bounds__(256) void k_centroid_split(Dev D) {
-  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= (int64_t)D.nlist * D.dgroups) return;
-  const int c = (int)(t / D.dgroups), g = (int)(t % D.dgroups);
-  const float *row = D.centroids + (size_t)c * D.d;
+// bf16 halves of rows of d floats: per row and group of 8 coordinates 16 bytes of hi halves then 16 bytes
+// of lo halves; coordinates past d are zero, up to whole steps of 32 (D.dgroups groups)
+__device__ inline void split_group(const Dev &D, const float *row, int g, u32x4 *out) {
   float4 u = make_float4(0.f, 0.f, 0.f, 0.f), v = u;
   if (g * 8 < D.d) u = *reinterpret_cast<const float4 *>(row + g * 8);
   if (g * 8 + 4 < D.d) v = *reinterpret_cast<const float4 *>(row + g * 8 + 4);
   u32x4 hi, lo;
   split_eight(u, v, hi, lo);
-  D.csplit[2 * t] = hi;
-  D.csplit[2 * t + 1] = lo;
+  out[2 * g] = hi;
+  out[2 * g + 1] = lo;
+}
+
+__global__ __launch_bounds__(256) void k_centroid_split(Dev D) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= (int64_t)D.nlist * D.dgroups) return;
+  const int c = (int)(t / D.dgroups), g = (int)(t % D.dgroups);
+  split_group(D, D.centroids + (size_t)c * D.d, g, D.csplit + (size_t)c * D.dgroups * 2);
+}
+
+// one wavefront per vector of a batch: its split form and, if asked for, its squared norm
+__global__ __launch_bounds__(256) void k_split_rows(Dev D, int64_t n, const float *__restrict__ Y,
+                                                    u32x4 *__restrict__ split, float *__restrict__ norms) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t i = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  if (i >= n) return;  // uniform over the wavefront
+  const float *row = Y + i * D.d;
+  for (int g = lane; g < D.dgroups; g += kWave) split_group(D, row, g, split + (size_t)i * D.dgroups * 2);
+  if (!norms) return;
+  float nsq = 0.f;
+  for (int j = lane; j < D.d; j += kWave) nsq = fmaf(row[j], row[j], nsq);
+  for (int o = kWave / 2; o > 0; o >>= 1) nsq += __shfl_xor(nsq, o);
+  if (lane == 0) norms[i] = nsq;
 }
 
 // ---- approx[i][c] for i < n, c < nlist
 template <int METRIC, bool MATRIX>
-__global__ __launch_bounds__(kMfmaThreads) void k_coarse_mfma(Dev D, int64_t n, const float *__restrict__ Y,
+__global__ __launch_bounds__(kMfmaThreads, 3) void k_coarse_mfma(Dev D, int64_t n, const u32x4 *__restrict__ ysplit,
+                                                              const float *__restrict__ ynorm,
                                                               float *__restrict__ approx, TileCands tc,
                                                               unsigned long long *cursor_to_clear,
                                                               uint32_t *__restrict__ zero, int zero_n) {
   __shared__ __align__(16) unsigned char s_op[4][kTileM * kRowBytes];  // vectors hi, lo; centroids hi, lo
   __shared__ float s_min[kTileM][2];
+  __shared__ float s_cn[kTileN];  // |c|^2 of the tile's centroids (0 past the last one), read after the last barrier of the k loop
   __shared__ float s_norm[kTileM];
   __shared__ uint32_t s_cnt[kTileM];
   __shared__ int32_t s_col[kTileM][kTileCands];
   __shared__ float s_val[kTileM][kTileCands];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-  const int wm = wave & 1, wn = wave >> 1;  // wavefront's place in the 2 x 2 arrangement
+  const int wv = wave & 1, wc = wave >> 1;  // wavefront's place in the 2 (vectors) x 2 (centroids) arrangement
   const int d = D.d;
 
   // per-request counters of the search plan start from zero (no memset node on the stream)
@@ -127,6 +152,8 @@ __global__ __launch_bounds__(kMfmaThreads) void k_coarse_mfma(Dev D, int64_t n, 
   const int64_t row0 = (int64_t)(turn / per_die) * kTileM;
   const int col0 = col_tile * kTileN;
 
+  if (tid < kTileN) s_cn[tid] = (METRIC == 0 && col0 + tid < D.nlist) ? D.cnorm[col0 + tid] : 0.f;
+
   floatx16 acc[2][2];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
@@ -135,151 +162,149 @@ __global__ __launch_bounds__(kMfmaThreads) void k_coarse_mfma(Dev D, int64_t n, 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-  // staging: thread t brings group t % 4 (8 consecutive k) of rows t / 4 and t / 4 + 64 of the vectors and
-  // of the centroids into registers, one k-tile ahead: the loads of tile t + 1 are in flight while the
-  // matrix cores work on tile t out of LDS
+  // staging: thread t brings group t % 4 (8 consecutive k, 32 bytes of halves) of rows t / 4 and t / 4 + 64
+  // of the vectors and of the centroids into registers, one k-tile ahead: the loads of tile t + 1 are in
+  // flight while the matrix cores work on tile t out of LDS.  Rows past the last vector or centroid read
+  // the last one (their scores are dropped below); the k past d are zero in both split forms.
   const int ld_row = tid / 4, ld_g = tid % 4;
-  float nsq[2] = {0.f, 0.f};  // this thread's share of |y_row|^2
-  float4 va[2][2];
-  u32x4 vb[2][2];
-  auto fetch = [&](int k0) {
-    const int k = k0 + ld_g * 8;
+  const u32x4 *src[2][2];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int64_t r = row0 + ld_row + 64 * h;
-      va[h][0] = va[h][1] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (r < n && k < d) va[h][0] = *reinterpret_cast<const float4 *>(Y + r * d + k);
-      if (r < n && k + 4 < d) va[h][1] = *reinterpret_cast<const float4 *>(Y + r * d + k + 4);
-      const int c = col0 + ld_row + 64 * h;
-      vb[h][0] = vb[h][1] = u32x4{0u, 0u, 0u, 0u};
-      if (c < D.nlist && k < d) {
-        const u32x4 *p = D.csplit + ((size_t)c * D.dgroups + k / 8) * 2;
-        vb[h][0] = p[0];
-        vb[h][1] = p[1];
+  for (int h = 0; h < 2; ++h) {
+    const int64_t r = row0 + ld_row + 64 * h;
+    const int c = col0 + ld_row + 64 * h;
+    src[h][0] = ysplit + ((size_t)(r < n ? r : n - 1) * D.dgroups + ld_g) * 2;
+    src[h][1] = D.csplit + ((size_t)(c < D.nlist ? c : D.nlist - 1) * D.dgroups + ld_g) * 2;
+  }
+  u32x4 stage[2][2][2];  // [row half][vectors, centroids][hi, lo]
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int w = 0; w < 2; ++w) {
+        stage[h][w][0] = src[h][w][k0 / 4];
+        stage[h][w][1] = src[h][w][k0 / 4 + 1];
       }
-    }
   };
   fetch(0);
   for (int k0 = 0; k0 < d; k0 += kTileK) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const float4 u = va[h][0], v = va[h][1];
-      if (!MATRIX)
-        nsq[h] = fmaf(u.x, u.x, fmaf(u.y, u.y, fmaf(u.z, u.z, fmaf(u.w, u.w,
-                 fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, nsq[h]))))))));
-      u32x4 hi, lo;
-      split_eight(u, v, hi, lo);
-      const int at = (ld_row + 64 * h) * kRowBytes + ld_g * 16;
-      *reinterpret_cast<u32x4 *>(&s_op[0][at]) = hi;
-      *reinterpret_cast<u32x4 *>(&s_op[1][at]) = lo;
-      *reinterpret_cast<u32x4 *>(&s_op[2][at]) = vb[h][0];
-      *reinterpret_cast<u32x4 *>(&s_op[3][at]) = vb[h][1];
+      const int at = lds_place(ld_row + 64 * h, ld_g);
+      *reinterpret_cast<u32x4 *>(&s_op[0][at]) = stage[h][0][0];
+      *reinterpret_cast<u32x4 *>(&s_op[1][at]) = stage[h][0][1];
+      *reinterpret_cast<u32x4 *>(&s_op[2][at]) = stage[h][1][0];
+      *reinterpret_cast<u32x4 *>(&s_op[3][at]) = stage[h][1][1];
     }
     __syncthreads();
     if (k0 + kTileK < d) fetch(k0 + kTileK);  // uniform
     // operands of v_mfma_f32_32x32x16_bf16: lane l supplies 8 consecutive k, the group l / 32 of the
-    // 16, of row (or column) l % 32; vectors and centroids use the same split of k over the lanes
+    // 16, of row (or column) l % 32; vectors and centroids use the same split of k over the lanes.
+    // The centroids are the rows of the product and the vectors its columns, so that a lane ends up
+    // with 32 scores of ONE vector per block column and the smallest of them is found in registers.
 #pragma unroll
     for (int kk = 0; kk < kTileK / 16; ++kk) {
-      const int off = (lane & 31) * kRowBytes + (kk * 2 + (lane >> 5)) * 16;
-      bf16x8 ah[2], al[2], bh[2], bl[2];
+      const int off = lds_place(lane & 31, kk * 2 + (lane >> 5));  // (block rows start at multiples of 32: same place)
+      bf16x8 ch[2], cl[2], yh[2], yl[2];
 #pragma unroll
       for (int a = 0; a < 2; ++a) {
-        const int at = (wm * 64 + a * 32) * kRowBytes + off;
-        ah[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&s_op[0][at]));
-        al[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&s_op[1][at]));
+        const int at = (wc * 64 + a * 32) * kRowBytes + off;
+        ch[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&s_op[2][at]));
+        cl[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&s_op[3][at]));
       }
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
-        const int at = (wn * 64 + b * 32) * kRowBytes + off;
-        bh[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&s_op[2][at]));
-        bl[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&s_op[3][at]));
+        const int at = (wv * 64 + b * 32) * kRowBytes + off;
+        yh[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&s_op[0][at]));
+        yl[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&s_op[1][at]));
       }
       // the small products first; every accumulator is touched once in four instructions
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[a], bh[b], acc[a][b], 0, 0, 0);
+        for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cl[a], yh[b], acc[a][b], 0, 0, 0);
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bl[b], acc[a][b], 0, 0, 0);
+        for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[a], yl[b], acc[a][b], 0, 0, 0);
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[a], bh[b], acc[a][b], 0, 0, 0);
+        for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[a], yh[b], acc[a][b], 0, 0, 0);
     }
     __syncthreads();
   }
 
-  // result layout: register r of lane l holds row (r / 4) * 8 + (l / 32) * 4 + r % 4, column l % 32 of a
-  // 32 x 32 block
-  auto row_of = [&](int a, int r) { return wm * 64 + a * 32 + (r / 4) * 8 + (lane >> 5) * 4 + (r % 4); };
-  if (MATRIX) {
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      const int c = col0 + wn * 64 + b * 32 + (lane & 31);
-      if (c >= D.nlist) continue;
-      const float cn = METRIC == 0 ? D.cnorm[c] : 0.f;
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int64_t i = row0 + row_of(a, r);
-          if (i < n) approx[(size_t)i * D.nlist + c] = METRIC == 0 ? cn - 2.f * acc[a][b][r] : -acc[a][b][r];
-        }
-    }
-    return;
-  }
-  // The tile is reduced here: per row its smallest score and the columns within the band of it.
-#pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    const int c = col0 + wn * 64 + b * 32 + (lane & 31);
-    const bool real = c < D.nlist;
-    const float cn = (METRIC == 0 && real) ? D.cnorm[c] : 0.f;
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        acc[a][b][r] = real ? (METRIC == 0 ? cn - 2.f * acc[a][b][r] : -acc[a][b][r]) : __builtin_inff();
-  }
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {  // |y_row|^2: the four threads that staged a row add up their shares
-    float t = nsq[h];
-    t += __shfl_xor(t, 1);
-    t += __shfl_xor(t, 2);
-    if ((tid & 3) == 0) s_norm[ld_row + 64 * h] = t;
-  }
-  if (tid < kTileM) s_cnt[tid] = 0u;
-#pragma unroll
-  for (int a = 0; a < 2; ++a)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {  // smallest score of each row over this wavefront's 64 columns
-      float v = fminf(acc[a][0][r], acc[a][1][r]);
-      for (int o = 16; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o));  // stays inside a half of 32 lanes
-      if ((lane & 31) == 0) s_min[row_of(a, r)][wn] = v;
-    }
-  __syncthreads();
-  const float cmax = __uint_as_float(D.ctrl->cnorm_max_bits);
+  // result layout of a 32 x 32 block: register r of lane l holds row (r / 4) * 8 + (l / 32) * 4 + r % 4 (a
+  // centroid), column l % 32 (a vector); acc[a][b] is the block of centroid block a and vector block b
+  auto centroid_of = [&](int a, int r) { return col0 + wc * 64 + a * 32 + (r / 4) * 8 + (lane >> 5) * 4 + (r % 4); };
+  // scores in place: |c|^2 - 2 <y, c> or - <y, c>; centroids past the last one score +inf
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int row = row_of(a, r);
-      const float tmin = fminf(s_min[row][0], s_min[row][1]);
-      // 2 E of the row, a little wider than the refinement's (1.02 against 1.01), so that what the
-      // refinement asks for is certainly among what is kept here
-      const float band = coarse_band(D.d, s_norm[row] + cmax) * 1.02f;
+      const int c = centroid_of(a, r);
+      const bool real = c < D.nlist;
+      const float cn = s_cn[c - col0];
 #pragma unroll
       for (int b = 0; b < 2; ++b)
-        if (acc[a][b][r] <= tmin + band) {
-          const uint32_t slot = atomicAdd(&s_cnt[row], 1u);
-          if (slot < (uint32_t)kTileCands) {
-            s_col[row][slot] = col0 + wn * 64 + b * 32 + (lane & 31);
-            s_val[row][slot] = acc[a][b][r];
+        acc[a][b][r] = real ? (METRIC == 0 ? cn - 2.f * acc[a][b][r] : -acc[a][b][r]) : __builtin_inff();
+    }
+  if (MATRIX) {
+    const bool quads = D.nlist % 4 == 0;  // a lane's 4 consecutive centroids of one vector go out as one 16-byte store
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const int64_t i = row0 + wv * 64 + b * 32 + (lane & 31);
+      if (i >= n) continue;
+      float *out = approx + (size_t)i * D.nlist;
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int r = 0; r < 16; r += 4) {
+          const int c = centroid_of(a, r);
+          if (quads && c + 3 < D.nlist) {
+            *reinterpret_cast<float4 *>(out + c) = make_float4(acc[a][b][r], acc[a][b][r + 1], acc[a][b][r + 2], acc[a][b][r + 3]);
+          } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              if (c + j < D.nlist) out[c + j] = acc[a][b][r + j];
           }
         }
     }
+    return;
+  }
+  // The tile is reduced here: per vector its smallest score and the centroids within the band of it.
+  if (tid < kTileM) s_norm[tid] = ynorm[row0 + tid < n ? row0 + tid : n - 1];
+  if (tid < kTileM) s_cnt[tid] = 0u;
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {  // smallest score of this lane's vector over the wavefront's 64 centroids
+    float v = __builtin_inff();
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) v = fminf(v, acc[a][b][r]);
+    v = fminf(v, __shfl_xor(v, 32));  // the other half of the lanes holds the other centroids of the same vector
+    if (lane < 32) s_min[wv * 64 + b * 32 + lane][wc] = v;
+  }
+  __syncthreads();
+  const float cmax = __uint_as_float(D.ctrl->cnorm_max_bits);
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    const int row = wv * 64 + b * 32 + (lane & 31);
+    // the smallest of the tile plus 2 E of the vector, a little wider than the refinement's (1.02 against
+    // 1.01), so that what the refinement asks for is certainly among what is kept here
+    const float limit = fminf(s_min[row][0], s_min[row][1]) + coarse_band(D.d, s_norm[row] + cmax) * 1.02f;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (acc[a][b][r] <= limit && centroid_of(a, r) < D.nlist) {
+          const uint32_t slot = atomicAdd(&s_cnt[row], 1u);
+          if (slot < (uint32_t)kTileCands) {
+            s_col[row][slot] = centroid_of(a, r);
+            s_val[row][slot] = acc[a][b][r];
+          }
+        }
+  }
   __syncthreads();
   if (tid < kTileM && row0 + tid < n) {
     const size_t at = (size_t)(row0 + tid) * tc.tiles + col_tile;
@@ -400,24 +425,31 @@ static unsigned tile_grid(const Dev &D, int64_t n) {
   return (unsigned)(((n + kTileM - 1) / kTileM) * per_die * kXcds);
 }
 
-void launch_coarse_mfma(const Dev &D, int64_t n, const float *Y, float *approx,
+static void launch_split_rows(const Dev &D, int64_t n, const float *Y, u32x4 *split, float *norms, hipStream_t s) {
+  hipLaunchKernelGGL(k_split_rows, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, s, D, n, Y, split, norms);
+}
+
+void launch_coarse_mfma(const Dev &D, int64_t n, const float *Y, u32x4 *split, float *approx,
                         unsigned long long *cursor_to_clear, uint32_t *zero, int zero_n, hipStream_t s) {
   if (n <= 0) return;
+  launch_split_rows(D, n, Y, split, nullptr, s);
   const dim3 grid(tile_grid(D, n));
   const TileCands none{};
   if (D.metric == 0)
-    hipLaunchKernelGGL((k_coarse_mfma<0, true>), grid, dim3(kMfmaThreads), 0, s, D, n, Y, approx, none, cursor_to_clear, zero, zero_n);
+    hipLaunchKernelGGL((k_coarse_mfma<0, true>), grid, dim3(kMfmaThreads), 0, s, D, n, split, nullptr, approx, none, cursor_to_clear, zero, zero_n);
   else
-    hipLaunchKernelGGL((k_coarse_mfma<1, true>), grid, dim3(kMfmaThreads), 0, s, D, n, Y, approx, none, cursor_to_clear, zero, zero_n);
+    hipLaunchKernelGGL((k_coarse_mfma<1, true>), grid, dim3(kMfmaThreads), 0, s, D, n, split, nullptr, approx, none, cursor_to_clear, zero, zero_n);
 }
 
-void launch_coarse_tiles(const Dev &D, int64_t n, const float *Y, const TileCands &tc, hipStream_t s) {
+void launch_coarse_tiles(const Dev &D, int64_t n, const float *Y, u32x4 *split, float *norms, const TileCands &tc,
+                         hipStream_t s) {
   if (n <= 0) return;
+  launch_split_rows(D, n, Y, split, norms, s);
   const dim3 grid(tile_grid(D, n));
   if (D.metric == 0)
-    hipLaunchKernelGGL((k_coarse_mfma<0, false>), grid, dim3(kMfmaThreads), 0, s, D, n, Y, nullptr, tc, nullptr, nullptr, 0);
+    hipLaunchKernelGGL((k_coarse_mfma<0, false>), grid, dim3(kMfmaThreads), 0, s, D, n, split, norms, nullptr, tc, nullptr, nullptr, 0);
   else
-    hipLaunchKernelGGL((k_coarse_mfma<1, false>), grid, dim3(kMfmaThreads), 0, s, D, n, Y, nullptr, tc, nullptr, nullptr, 0);
+    hipLaunchKernelGGL((k_coarse_mfma<1, false>), grid, dim3(kMfmaThreads), 0, s, D, n, split, norms, nullptr, tc, nullptr, nullptr, 0);
 }
 
 void launch_assign_refine(const Dev &D, int64_t n, const float *Y, const TileCands &tc, bool reserve,

@@ -38,7 +38,7 @@ inline size_t up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Byte offsets of everything in front of the blocks.
 struct Layout {
-  size_t ctrl, hook, centroids, cnorm, csplit, codebooks, codebooks_t, tc_min, tc_cnt, tc_col, tc_val, tile_rows, reserved_len, visible_len, online, nblk, exceed, seg_dir;
+  size_t ctrl, hook, centroids, cnorm, csplit, codebooks, codebooks_t, tc_min, tc_cnt, tc_col, tc_val, ins_ysplit, ins_ynorm, tile_rows, reserved_len, visible_len, online, nblk, exceed, seg_dir;
   size_t ins_assign, ins_did, ins_pscore, ins_pidx, part_cap;
   size_t rearr_head, rearr_arrays;
   size_t fixed_end;          // end of the part that does not depend on the block count
@@ -93,7 +93,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
   L->hook = take(kHookBytes);
   L->centroids = take(nl * c->d * sizeof(float));
   L->cnorm = take(nl * sizeof(float));
-  L->csplit = take(nl * (size_t)((c->d + 7) / 8) * 32);
+  L->csplit = take(nl * (size_t)((c->d + 31) / 32) * 4 * 32);
   L->codebooks = take(c->pq_m > 0 ? (size_t)256 * c->d * sizeof(float) : 0);
   L->codebooks_t = take(c->pq_m > 0 ? (size_t)256 * c->d * sizeof(float) : 0);
   L->reserved_len = take(nl * 4);
@@ -110,9 +110,13 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
   {  // tile digests of one insertion sub-round (40 bytes per row and tile): at most 64 MiB, at least 64 rows
     const size_t tiles = (nl + 127) / 128;
     size_t rows = ((size_t)64 << 20) / (tiles * 40);
+    const size_t split_row = (size_t)((c->d + 31) / 32) * 4 * 32;  // a vector as bf16 halves: at most 64 MiB of those, too
+    if (rows > ((size_t)64 << 20) / split_row) rows = ((size_t)64 << 20) / split_row;
     if (rows > (size_t)c->max_add_batch) rows = (size_t)c->max_add_batch;
     if (rows < 64) rows = 64;
     L->tile_rows = rows;
+    L->ins_ysplit = take(rows * split_row);
+    L->ins_ynorm = take(rows * 4);
     L->tc_min = take(rows * tiles * 4);
     L->tc_cnt = take(rows * tiles * 4);
     L->tc_col = take(rows * tiles * kTileCands * 4);
@@ -142,7 +146,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
 }
 
 struct ScratchLayout {
-  size_t scores, approx, probe_list, probe_len, probe_off, qbase, qtotal, bound, qnorm, rec_cnt, cursor, req_words, lut, records, fixed;
+  size_t scores, approx, probe_list, probe_len, probe_off, qbase, qtotal, bound, qnorm, qsplit, rec_cnt, cursor, req_words, lut, records, fixed;
   size_t list_cnt, pair_start, pair_slot, grouped, plist, pistart, tile_desc, queues, item_cap;
 };
 
@@ -160,6 +164,7 @@ void lay_out_scratch(const rtams_config *c, ScratchLayout *S) {
   S->qtotal = take(mb * 4);
   S->bound = take(mb * 4);
   S->qnorm = take(mb * 4);
+  S->qsplit = take(mb * (size_t)((c->d + 31) / 32) * 4 * 32);
   S->rec_cnt = take(mb * 4);
   S->cursor = take(8);
   S->req_words = take(16);  // the request's chunk of the shared reserve: chunk, finished workgroups, cursor
@@ -282,7 +287,7 @@ void coarse_and_plan(rtams_index *ix, int64_t nq, const float *Q, int nprobe, co
   const Dev &D = ix->dev;
   const int64_t mode = ix->use_mfma.load(std::memory_order_relaxed);  // 0 never, 1 when it pays, 2 from 32 rows
   const bool mfma = mode == 2 ? nq >= 32 : mode == 1 && mfma_pays_for_search(nq, D.nlist);
-  if (mfma) launch_coarse_mfma(D, nq, Q, S.approx, S.cursor, S.list_cnt, plan_words(ix), s);
+  if (mfma) launch_coarse_mfma(D, nq, Q, S.qsplit, S.approx, S.cursor, S.list_cnt, plan_words(ix), s);
   else launch_coarse_scores(D, nq, Q, S.scores, S.cursor, S.list_cnt, plan_words(ix), s);
   launch_probe_plan(D, nq, nprobe, ix->cfg.max_nprobe, S, Q, mfma, probe_out, s);
 }
@@ -351,7 +356,7 @@ void assign_round(rtams_index *ix, int64_t m, const float *Y, bool reserve, int3
   if (mode == 2 ? m >= 32 : mode == 1 && mfma_pays_for_assign(m, D.nlist)) {
     for (int64_t o = 0; o < m; o += ix->ins.tile_rows) {
       const int64_t mm = m - o < ix->ins.tile_rows ? m - o : ix->ins.tile_rows;
-      launch_coarse_tiles(D, mm, Y + (size_t)o * D.d, ix->ins.tiles, s);
+      launch_coarse_tiles(D, mm, Y + (size_t)o * D.d, ix->ins.ysplit, ix->ins.ynorm, ix->ins.tiles, s);
       launch_assign_refine(D, mm, Y + (size_t)o * D.d, ix->ins.tiles, reserve, assign_out + o, ix->ins.did + o, s);
     }
   } else {
@@ -435,7 +440,7 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   D.centroids = reinterpret_cast<float *>(base + L.centroids);
   D.cnorm = reinterpret_cast<float *>(base + L.cnorm);
   D.csplit = reinterpret_cast<u32x4 *>(base + L.csplit);
-  D.dgroups = (cfg->d + 7) / 8;
+  D.dgroups = (cfg->d + 31) / 32 * 4;
   D.codebooks = reinterpret_cast<float *>(base + L.codebooks);
   D.codebooks_t = reinterpret_cast<float *>(base + L.codebooks_t);
   D.pq_m = cfg->pq_m;
@@ -460,6 +465,8 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   ix->ins.tiles.col = reinterpret_cast<int32_t *>(base + L.tc_col);
   ix->ins.tiles.val = reinterpret_cast<float *>(base + L.tc_val);
   ix->ins.tile_rows = (int64_t)L.tile_rows;
+  ix->ins.ysplit = reinterpret_cast<u32x4 *>(base + L.ins_ysplit);
+  ix->ins.ynorm = reinterpret_cast<float *>(base + L.ins_ynorm);
   {
     uint32_t *a = reinterpret_cast<uint32_t *>(base + L.rearr_arrays);
     RearrangeScratch &R = ix->rearr;
@@ -520,6 +527,7 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
     S.qtotal = reinterpret_cast<uint32_t *>(p + SL.qtotal);
     S.bound = reinterpret_cast<uint32_t *>(p + SL.bound);
     S.qnorm = reinterpret_cast<float *>(p + SL.qnorm);
+    S.qsplit = reinterpret_cast<u32x4 *>(p + SL.qsplit);
     S.rec_cnt = reinterpret_cast<uint32_t *>(p + SL.rec_cnt);
     S.cursor = reinterpret_cast<unsigned long long *>(p + SL.cursor);
     S.list_cnt = reinterpret_cast<uint32_t *>(p + SL.list_cnt);

@@ -77,7 +77,7 @@ struct Dev {
   float *centroids;         // [nlist][d]
   float *cnorm;             // [nlist] squared norms of the centroids (fp32)
   u32x4 *csplit;            // [nlist][dgroups][2] the centroids as bf16 halves: per group of 8 coordinates the 8 hi, then the 8 lo
-  int32_t dgroups;          // groups of 8 coordinates of a centroid: ceil(d / 8)
+  int32_t dgroups;          // groups of 8 coordinates of a split row, padded with zeros to whole steps of 32 coordinates: 4 ceil(d / 32)
   float *codebooks;         // [pq_m][256][d / pq_m] (product-quantised lists only)
   float *codebooks_t;       // the same with the entries innermost: [pq_m][d / pq_m][256] (for coding inserted vectors)
   uint32_t *reserved_len;   // [nlist] next free position (atomicAdd target)

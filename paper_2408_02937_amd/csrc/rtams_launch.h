@@ -28,6 +28,7 @@ struct SearchScratch {
   uint32_t *qtotal;     // [max_batch] candidates of the query
   uint32_t *bound;      // [max_batch] key of the score the scan compares with
   float *qnorm;         // [max_batch] squared norms of the queries (norm form of the squared distance)
+  u32x4 *qsplit;        // [max_batch][dgroups][2] the queries as bf16 halves, for the matrix-core coarse scores
   uint32_t *rec_cnt;    // [max_batch] survivors recorded so far
   unsigned long long *cursor; // bump pointer into the survivor records
   uint32_t *list_cnt;   // [nlist] queries probing each list
@@ -80,6 +81,8 @@ struct InsertScratch {
   int32_t *pidx;     // [part_cap]
   size_t part_cap;
   TileCands tiles;   // per (row, tile of 128 centroids) digest of the approximate scores of one sub-round
+  u32x4 *ysplit;     // [tile_rows][dgroups][2] the vectors of one sub-round as bf16 halves
+  float *ynorm;      // [tile_rows] their squared norms
   int64_t tile_rows; // rows one sub-round may hold
 };
 
@@ -131,10 +134,12 @@ __host__ __device__ inline float coarse_band(int d, float norms) {
   return (8.f * (float)(d + 4) * 5.9604645e-8f + 8.f * 1.52587890625e-5f) * norms;
 }
 void launch_centroid_norms(const Dev &D, hipStream_t s);  // and the centroids' split form
-void launch_coarse_mfma(const Dev &D, int64_t n, const float *Y, float *approx,
+// (`split` takes the n rows as bf16 halves, [n][dgroups][2] 16-byte words; `norms` their n squared norms)
+void launch_coarse_mfma(const Dev &D, int64_t n, const float *Y, u32x4 *split, float *approx,
                         unsigned long long *cursor_to_clear, uint32_t *zero, int zero_n, hipStream_t s);
 int coarse_tiles(const Dev &D);
-void launch_coarse_tiles(const Dev &D, int64_t n, const float *Y, const TileCands &tc, hipStream_t s);
+void launch_coarse_tiles(const Dev &D, int64_t n, const float *Y, u32x4 *split, float *norms, const TileCands &tc,
+                         hipStream_t s);
 void launch_assign_refine(const Dev &D, int64_t n, const float *Y, const TileCands &tc, bool reserve,
                           int32_t *assign, uint32_t *did, hipStream_t s);
 
