@@ -423,8 +423,12 @@ def main() -> int:
               "mixed": studies.mixed_load_study, "growth": studies.growth_study,
               "rearrange5": studies.hot_list_rearrangement_study}[args.study]
         iters = args.latency_iters or 2000
-        if args.study == "pq" and args.pq_m:
-            print(json.dumps(fn(scale=args.scale, iters=iters, ms=(args.pq_m,), batches=(args.batch or 256,))))
+        if args.study == "pq":
+            params = {k: int(v) for k, v in (kv.split("=") for kv in args.set)}
+            if args.pq_m:
+                print(json.dumps(fn(scale=args.scale, iters=iters, ms=(args.pq_m,), batches=(args.batch or 256,), params=params)))
+            else:
+                print(json.dumps(fn(scale=args.scale, iters=iters, params=params)))
             return 0
         if args.study == "shapes" and args.shape:
             print(json.dumps(fn(scale=args.scale, iters=iters, which=(args.shape,))))

@@ -245,7 +245,7 @@ struct rtams_index {
   std::shared_mutex fence_mutex;
   hipEvent_t fence_ev[2] = {nullptr, nullptr};  // table switches of the running rearrangement
   hipEvent_t fence_cur = nullptr;               // what a new search must wait for, or nullptr
-  int64_t ntotal_host = 0;   // vectors handed to add so far
+  std::atomic<int64_t> ntotal_host{0};   // vectors handed to add so far (written under data_mutex; searches read it for estimates)
   int64_t avail_lb = 0;      // lower bound of the blocks still available in the pool
   std::atomic<int64_t> scan_items_per_pair{8};   // work items the plan may cut per (query, list) pair
   std::atomic<int64_t> scan_max_items{32768};    // ... and per request
@@ -259,14 +259,20 @@ struct rtams_index {
   std::atomic<int64_t> scan_mfma{1}; // flat float lists: the scan's dot products on the matrix cores
   std::atomic<int64_t> scan_byte_weight{0};
   std::atomic<int64_t> scan_min_choice{-1};
-  // Scans of large requests run one after the other, whatever streams they are on: such a scan fills the
-  // chip by itself, and two of them side by side only slow each other down (both finish when the sum of
-  // their work is done, instead of one after half of it); everything else of a request still overlaps
-  // with other requests' scans.  (Consideration 2 of the multi-stream section: what a kernel may take
-  // of the chip is limited so that kernels of other streams are not held up.)
+  // Scans of LONG requests run one after the other, whatever streams they are on: such a scan fills the
+  // chip by itself for milliseconds, and two of them side by side only slow each other down (both finish
+  // when the sum of their work is done, instead of one after half of it); everything else of a request
+  // still overlaps with other requests' scans.  (Consideration 2 of the multi-stream section: what a
+  // kernel may take of the chip is limited so that kernels of other streams are not held up.)  Handing
+  // the chip from one stream to the next costs some tens of microseconds, which a scan of a
+  // millisecond or more does not feel (measured: 2 % of the throughput at 2.7 ms a scan) and shorter
+  // ones do (12 % at 0.6 ms, 23 % at 0.12 ms): those overlap freely and fill each other's tails.  A
+  // request is long when the list bytes its (query, list) pairs are expected to meet (lists of
+  // average length) reach scan_exclusive_bytes.
   std::mutex scan_mutex;
   hipEvent_t scan_tail = nullptr;                 // behind the last large scan enqueued, or nullptr
-  std::atomic<int64_t> scan_exclusive_pairs{4096};  // (query, list) pairs from which a request's scan queues up; 0 never
+  std::atomic<int64_t> scan_exclusive_pairs{4096};  // (query, list) pairs from which a request's scan may queue up; 0 never
+  std::atomic<int64_t> scan_exclusive_bytes{(int64_t)16 << 30};  // ... and expected list bytes of those pairs from which it does
   std::mutex prof_mutex;
   double scan_ms = 0.0;      // sum of measured scan-kernel durations
   int64_t scan_launches = 0;
@@ -729,7 +735,11 @@ static int search_on(rtams_index *ix, int r, int64_t nq, const float *d_queries,
   launch_group(D, nq, nprobe, ix->cfg.max_nprobe, k, d_queries, (int)budget, S, s);
   const bool timed = ix->profile_scan.load(std::memory_order_relaxed) != 0;
   const int64_t excl = ix->scan_exclusive_pairs.load(std::memory_order_relaxed);
-  if (excl > 0 && nq * nprobe >= excl) {  // a large scan: behind the large scan enqueued before it
+  // expected list bytes of the request's pairs: lists of average length
+  const int64_t vec_bytes = D.pq_m > 0 ? D.pq_m : (int64_t)D.vchunks * 16;
+  const int64_t pair_bytes = nq * nprobe * (ix->ntotal_host / ix->cfg.nlist + 1) * vec_bytes;
+  if (excl > 0 && nq * nprobe >= excl &&
+      pair_bytes >= ix->scan_exclusive_bytes.load(std::memory_order_relaxed)) {  // a long scan: behind the long scan enqueued before it
     std::lock_guard<std::mutex> chain(ix->scan_mutex);
     if (ix->scan_tail && ix->scan_tail != ix->res[r].scan_done) (void)hipStreamWaitEvent(s, ix->scan_tail, 0);
     if (timed) (void)hipEventRecord(ix->res[r].t0, s);
@@ -1103,6 +1113,7 @@ int rtams_set_param(rtams_index *ix, const char *key, int64_t value) {
   if (!strcmp(key, "use_mfma")) { ix->use_mfma = value; return RTAMS_OK; }
   if (!strcmp(key, "scan_mfma")) { ix->scan_mfma = value; return RTAMS_OK; }
   if (!strcmp(key, "scan_exclusive_pairs")) { ix->scan_exclusive_pairs = value > 0 ? value : 0; return RTAMS_OK; }
+  if (!strcmp(key, "scan_exclusive_bytes")) { ix->scan_exclusive_bytes = value > 0 ? value : 0; return RTAMS_OK; }
   if (!strcmp(key, "scan_min_choice")) { ix->scan_min_choice = value < 0 ? -1 : value > 7 ? 7 : value; return RTAMS_OK; }
   if (!strcmp(key, "scan_byte_weight")) { ix->scan_byte_weight = value > 0 ? value : 0; return RTAMS_OK; }
   if (!strcmp(key, "scan_max_items")) { ix->scan_max_items = value > 1024 ? value : 1024; return RTAMS_OK; }

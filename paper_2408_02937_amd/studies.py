@@ -300,7 +300,7 @@ def block_size_sweep(scale: float = 1.0, sizes=(64, 128, 256, 512, 1024, 2048), 
     return {"study": "block_size", "workload": w.name, "rows": rows}
 
 
-def pq_study(scale: float = 1.0, ms=(16, 32), iters: int = 200, batches=(1, 10, 32, 256)) -> dict:
+def pq_study(scale: float = 1.0, ms=(16, 32), iters: int = 200, batches=(1, 10, 32, 256), params=None) -> dict:
     dev = torch.device("cuda:0")
     w = synth.config(2, scale=scale)
     base, cents, queries, inserts = (_to_dev(a, dev) for a in (w.base, w.centroids, w.queries, w.inserts))
@@ -329,6 +329,8 @@ def pq_study(scale: float = 1.0, ms=(16, 32), iters: int = 200, batches=(1, 10, 
         g = rtams.Index(w.d, w.nlist, w.metric, w.block_vecs, pq_m=M, **kw)
         g.set_centroids(cents, stream=ds)
         g.set_codebooks(cb, stream=ds)
+        for key, value in (params or {}).items():  # launch-shape parameters of the library, e.g. pq_by_list
+            g.set_param(key, value)
         t0 = time.perf_counter()
         g.add(base, stream=ds)
         ds.synchronize()
