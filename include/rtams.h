@@ -263,20 +263,39 @@ const char *rtams_last_error(void);
 int rtams_list_export_codes(rtams_index *ix, int32_t list, int64_t cap, int64_t *d_ids, uint8_t *d_codes,
                             int64_t *n_out, void *hip_stream);
 
-/* Launch-shape knobs (Stream-Cached Multi-Stream Execution, consideration 2: a
- * kernel's blocks and threads are capped so that several kernels run side by side).  key: "scan_max_items"
- * (most work items, one wavefront each, one list-scan launch is cut
- * into; a (query, list) pair is always at least one; default 32768), "scan_items_per_pair" (items per (query, list) pair a small
- * request may be cut into; default 8), "profile_scan" (see rtams_scan_time), and
- * "use_mfma": whether approximate coarse scores from the matrix cores filter the
- * centroids before the exact arithmetic decides (0 never, 1 for batches large
- * enough to repay it (default), 2 for every batch of 32 rows or more; results
- * are identical in all three); "ordered_add": 0 (default) reserves the positions
- * of a batch inside a list with one atomic per vector, in arrival order, as
- * Algorithm 2 does; 1 hands them out in the order of the batch, so that every
- * list holds the sequence that inserting the vectors one at a time would give
- * (the same on every run; one thread per list walks the batch: slower, meant
- * for checking and debugging).  EINVAL for an unknown key. */
+/* Launch-shape knobs (Stream-Cached Multi-Stream Execution, consideration 2: what a kernel may take
+ * of the chip is capped so that several kernels run side by side).  None of them changes a result.
+ * EINVAL for an unknown key; values out of a key's range are clamped.  May be called while requests
+ * are in flight: a request takes the values it finds when it is enqueued.
+ *   "scan_max_items"       most work items one list-scan launch is cut into (a (query, list) pair is
+ *                          always at least one); default 32768, at least 1024.
+ *   "scan_items_per_pair"  work items per (query, list) pair a small request may be cut into;
+ *                          default 8.
+ *   "scan_mfma"            flat float lists: whether the scan's dot products run on the matrix cores,
+ *                          one workgroup per work item with a tile of up to 32 queries in LDS.  0
+ *                          never, 1 for requests of 64 queries or more (default), 2 always.
+ *   "scan_min_choice"      shortest segment of a list the plan may make a work item of, as the power
+ *                          e of 2 << e groups of 64 vectors (0..7); -1 (default) leaves it to the
+ *                          scan kernel (2 groups on the vector unit, 8 on the matrix cores).
+ *   "scan_byte_weight"     what reading a group of 64 vectors costs, in queries' worth of arithmetic,
+ *                          when the work is split over the chip's 8 dies; 0 (default) takes 12 for
+ *                          L2 and 24 for inner products.
+ *   "scan_exclusive_pairs" / "scan_exclusive_bytes"
+ *                          a request's scan queues up behind the previous such scan, whatever streams
+ *                          they are on, when the request has at least so many (query, list) pairs
+ *                          (default 4096; 0: never) AND those pairs are expected to meet at least so
+ *                          many list bytes, lists taken at their average length (default 16 GiB):
+ *                          scans of a millisecond or more gain nothing from running side by side.
+ *   "use_mfma"             whether approximate coarse scores from the matrix cores filter the
+ *                          centroids before the exact arithmetic decides: 0 never, 1 for batches large
+ *                          enough to repay it (default), 2 for every batch of 32 rows or more.
+ *   "ordered_add"          0 (default) reserves the positions of a batch inside a list with one atomic
+ *                          per vector, in arrival order, as the Insertion algorithm does; 1 hands them
+ *                          out in the order of the batch, so that every list holds the sequence that
+ *                          inserting the vectors one at a time would give (one thread per list walks
+ *                          the batch: slower, meant for checking).  This one changes the ORDER inside
+ *                          a list, which the paper leaves to the atomics.
+ *   "profile_scan"         see rtams_scan_time (rtams_measure.h). */
 int rtams_set_param(rtams_index *ix, const char *key, int64_t value);
 
 #ifdef __cplusplus
