@@ -170,6 +170,23 @@ class Bench:
         assert g.poll_error() == 0, "a kernel raised an error during the timed steps"
         return elapsed, scan_ms, scan_n
 
+    def scan_scheduling(self, steps, warmup, union_b):
+        """The same timed steps with the scans of different requests made to run one after the other,
+        and left to overlap: the library queues them up only when they are long, and a scan that
+        shares the chip with another one takes longer without being any less efficient, so the
+        per-launch duration (and with it `roofline.frac`) reads differently in the two modes."""
+        g, out = self.g, {}
+        for name, (pairs, nbytes) in (("one_at_a_time", (1, 1)), ("overlapping", (0, 1))):
+            g.set_param("scan_exclusive_pairs", pairs)
+            g.set_param("scan_exclusive_bytes", nbytes)
+            e, ms, n = self.timed_steps(steps, warmup)
+            avg = ms / max(n, 1)
+            out[name] = {"qps": steps * self.B / e, "ms_per_step": e / steps * 1e3, "scan_avg_launch_ms": avg,
+                         "scan_frac_of_hbm_peak": union_b / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS if n else None}
+        g.set_param("scan_exclusive_pairs", 4096)  # the library's defaults
+        g.set_param("scan_exclusive_bytes", 16 << 30)
+        return out
+
     def scan_bytes(self, batches, bs=None, first=0):
         """Algorithmic bytes of the scan per launch: what the method must read.  The scan reads a list
         once for all the queries of the batch that probe it, so these are the bytes of the UNION of
@@ -467,6 +484,8 @@ def main() -> int:
     if not args.no_extras:
         big = args.config != 2
         iters = args.latency_iters or (300 if big else 2000)
+        if not params:
+            result["scan_scheduling"] = b.scan_scheduling(args.steps, args.warmup, union_b)
         result["latency_by_query_batch"] = b.latency_table(iters, PROTOCOL[args.config]["latency_batches"])
         note(f"configuration {args.config}: closed-loop searches on every stream beside the insert stream")
         result["at_configured_insert_rate"] = b.at_configured_rate(400 if big else 4000)
@@ -494,6 +513,7 @@ def main() -> int:
         block = {"config": b2.config_block(), "value": 200 * b2.B / e2, "unit": "queries/s",
                  "ms_per_step": e2 / 200 * 1e3,
                  "roofline": b2.roofline(ms2, n2, p2, u2, measured_traffic(b2.w.name, b2.B)),
+                 "scan_scheduling": b2.scan_scheduling(200, 20, u2),
                  "latency_by_query_batch": b2.latency_table(args.latency_iters or 1000, PROTOCOL[2]["latency_batches"]),
                  "at_configured_insert_rate": b2.at_configured_rate(2000),
                  "inserts_per_s_saturated": b2.saturated_inserts(300),

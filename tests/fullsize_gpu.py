@@ -7,10 +7,7 @@ from paper_2408_02937_amd import rtams, synth
 from oracle.oracle import OracleIndex
 from tests.fullsize_common import compare_lists, say
 from tests.gpu_common import dev, scan_modes
-from tests.helpers import assert_topk_matches
-
-
-RTOL, ATOL = 1e-4, 1e-6
+from tests.helpers import ATOL, RTOL, assert_topk_matches
 
 
 def build_pair(request, w, assign, cand, rearrange_threshold=0, spare_blocks=64):

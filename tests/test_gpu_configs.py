@@ -10,11 +10,10 @@ import torch
 
 from paper_2408_02937_amd import rtams, synth
 from tests.gpu_common import assert_lists_equal, dev, make_pair
-from tests.helpers import assert_topk_matches
+from tests.helpers import assert_topk_matches, RTOL
 
 pytestmark = pytest.mark.gpu
 
-RTOL = 1e-4
 
 
 def load(w, g, o):

@@ -10,11 +10,10 @@ import torch
 from oracle.oracle import OracleIndex
 from paper_2408_02937_amd import rtams, synth
 from tests.gpu_common import dev
-from tests.helpers import assert_topk_matches
+from tests.helpers import assert_topk_matches, RTOL
 
 pytestmark = pytest.mark.gpu
 
-RTOL = 1e-4
 
 
 def small_set():

@@ -9,11 +9,10 @@ import torch
 from oracle.oracle import OracleIndex
 from paper_2408_02937_amd import rtams, synth
 from tests.gpu_common import dev, whole_batches_check
-from tests.helpers import ATOL_PQ, assert_topk_matches
+from tests.helpers import assert_topk_matches, ATOL_PQ, RTOL
 
 pytestmark = pytest.mark.gpu
 
-RTOL = 1e-4
 
 
 def make_pq_pair(w, M, cb, pool_blocks=None, rearrange_threshold=0, n_resources=2, **kw):
