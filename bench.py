@@ -218,6 +218,7 @@ class Bench:
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                 "bytes_per_launch": union_b, "pair_bytes_per_launch": pair_b,
                 "avg_launch_ms": scan_avg_ms, "launches_timed": scan_n,
+                # what the direct form of the same launch costs on the vector unit (the matrix-core scan does not pay it)
                 "alu_issue": {"lane_instructions_per_launch": lane_ops,
                               "achieved_T_per_s": lane_ops / (scan_avg_ms * 1e-3) / 1e12 if scan_n else None,
                               "peak_T_per_s": VALU_ISSUE_PEAK_T,
