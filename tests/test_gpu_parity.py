@@ -248,9 +248,12 @@ def test_coarse_filter_under_cancellation():
     dict(d=20, nlist=37, block_vecs=192, metric="ip", nprobe=9, k=1000, batch=5),
     dict(d=260, nlist=50, block_vecs=128, metric="l2", nprobe=50, k=33, batch=130),
 ])
-def test_odd_shapes(shape):
-    """Dimensions that are not a multiple of the scan's pipeline depth, blocks of three groups,
-    list counts that are no power of two, every list probed, k = 1 and k near its maximum."""
+@pytest.mark.parametrize("mfma", [1, 2])
+def test_odd_shapes(shape, mfma):
+    """Dimensions that are not a multiple of the scan's pipeline depth (nor of the 32 coordinates the
+    matrix-core filter takes per step), blocks of three groups, list counts that are no power of two
+    (nor a multiple of the filter's 128-centroid tiles), every list probed, k = 1 and k near its
+    maximum; with the coarse filter left to the library's rule and forced on."""
     d, nlist, metric = shape["d"], shape["nlist"], shape["metric"]
     rng = np.random.default_rng(100 + d)
     C = rng.standard_normal((nlist, d)).astype(np.float32)
@@ -258,6 +261,7 @@ def test_odd_shapes(shape):
                        np.zeros((0, d), np.float32), C, np.zeros((0, d), np.float32),
                        np.zeros((0, d), np.float32), 1, 0)
     g, o = make_pair(w, pool_blocks=600, max_k=1024, max_nprobe=128, candidates_per_query=30000)
+    g.set_param("use_mfma", mfma)
     y = (C[rng.integers(0, nlist, 25000)] + 0.3 * rng.standard_normal((25000, d))).astype(np.float32)
     for b in range(0, len(y), 7000):  # ragged batches
         g.add(dev(y[b:b + 7000])); o.add(y[b:b + 7000])
