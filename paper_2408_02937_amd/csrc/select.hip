@@ -182,7 +182,7 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
     const int m = min(n - next, stretch * (kSurvivorCap - count));
     if (threadIdx.x == 0) s_over = 0;
     __syncthreads();
-    constexpr int kInFlight = 8;  // independent loads per thread
+    constexpr int kInFlight = 32;  // independent loads per thread: 16,384 keys per round trip to memory
     for (int j0 = 0; j0 < m; j0 += kInFlight * kTopkThreads) {
       uint32_t kv[kInFlight];
 #pragma unroll
