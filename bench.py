@@ -406,7 +406,7 @@ def main() -> int:
     ap.add_argument("--scale", type=float, default=1.0, help="shrinks base/query/insert counts")
     ap.add_argument("--search-streams", type=int, default=0, help="default: the configuration's")
     ap.add_argument("--latency-iters", type=int, default=0, help="requests per latency figure (default 300, 2000 for configuration 2)")
-    ap.add_argument("--cpu-queries", type=int, default=0, help="queries of the oracle sample (default 128, 1024 for configuration 2); -1 skips it")
+    ap.add_argument("--cpu-queries", type=int, default=0, help="queries of the oracle sample (default: 768 for configuration 5, 512 for 3, 8192 for 2); -1 skips it")
     ap.add_argument("--no-extras", action="store_true", help="only the timed steps (for profiler runs)")
     ap.add_argument("--set", action="append", default=[], metavar="KEY=VALUE",
                     help="a launch-shape parameter of the library (rtams_set_param), e.g. scan_mfma=0; may be repeated")
