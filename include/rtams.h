@@ -273,7 +273,9 @@ int rtams_list_export_codes(rtams_index *ix, int32_t list, int64_t cap, int64_t 
  *                          default 8.
  *   "scan_mfma"            flat float lists: whether the scan's dot products run on the matrix cores,
  *                          one workgroup per work item with a tile of up to 32 queries in LDS.  0
- *                          never, 1 for requests of 64 queries or more (default), 2 always.
+ *                          never, 2 always, 1 (default) for requests of 64 queries or more whose tiles
+ *                          hold several queries: at least as many (query, list) pairs as lists, or a
+ *                          list 16 times as long as the average.
  *   "scan_min_choice"      shortest segment of a list the plan may make a work item of, as the power
  *                          e of 2 << e groups of 64 vectors (0..7); -1 (default) leaves it to the
  *                          scan kernel (2 groups on the vector unit, 8 on the matrix cores).

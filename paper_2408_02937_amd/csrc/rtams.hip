@@ -714,9 +714,18 @@ static int search_on(rtams_index *ix, int r, int64_t nq, const float *d_queries,
                      float *d_out_dist, int64_t *d_out_ids, void *hip_stream) {
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   Dev D = ix->dev;
-  {  // flat float lists: large requests scan on the matrix cores (0 never, 1 from kMmMinBatch queries, 2 always)
+  {  // flat float lists: requests whose tiles hold several queries scan on the matrix cores (0 never, 1 by the rule below, 2 always)
     const int64_t mode = ix->scan_mfma.load(std::memory_order_relaxed);
-    D.scan_mfma = D.pq_m == 0 && D.storage == RTAMS_F32 && (mode == 2 || (mode == 1 && nq >= kMmMinBatch));
+    // A tile is the queries of the request that probe one list.  With at least as many (query, list)
+    // pairs as lists, or with a list far longer than the average (a hot list is probed by a good
+    // share of any batch and holds most of the bytes), tiles of several queries do most of the work:
+    // that is what the matrix-core kernel is for.  A request whose pairs spread thinly over many lists
+    // of similar length has tiles of one query each and is better off on the vector unit (measured:
+    // 64 queries x 32 probes over 8,192 lists of 768 dimensions, 643 against 667 us).
+    const int64_t avg_len = ix->ntotal_host / ix->cfg.nlist + 1;
+    const bool shared = nq * nprobe >= ix->cfg.nlist || (int64_t)ix->mirror->max_len >= 16 * avg_len;
+    D.scan_mfma = D.pq_m == 0 && D.storage == RTAMS_F32 &&
+                  (mode == 2 || (mode == 1 && nq >= kMmMinBatch && shared));
   }
   D.scan_byte_weight = (int32_t)ix->scan_byte_weight.load(std::memory_order_relaxed);
   D.scan_min_choice = (int32_t)ix->scan_min_choice.load(std::memory_order_relaxed);
