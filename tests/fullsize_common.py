@@ -14,7 +14,6 @@ import numpy as np
 from concurrent.futures import ThreadPoolExecutor
 from threadpoolctl import threadpool_limits
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 _T0 = time.time()
 
 
@@ -26,12 +25,6 @@ def say(request, msg: str) -> None:
             print(line, flush=True)
     else:
         print(line, flush=True)
-    try:
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "fullsize_progress.log"), "a") as f:
-            f.write(line + "\n")
-    except OSError:
-        pass
 
 
 def filtered_assignment(o, metric: str, X: np.ndarray, C: np.ndarray, rows_per_step: int = 4096,
