@@ -40,7 +40,15 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kMfmaThreads = 256;  // 4 wavefronts: 2 (rows) x 2 (columns), 64 x 64 results each
-constexpr int kTileM = 128, kTileN = 128, kTileK = 32;
+#ifndef RTAMS_COARSE_VB
+#define RTAMS_COARSE_VB 2
+#endif
+// 32-vector blocks per wavefront: 2 (64 x 64 scores, 3 wavefronts per SIMD) or 4 (64 x 128 scores, a quarter
+// less LDS traffic per matrix instruction, 2 wavefronts per SIMD; measured: no faster, 28.0 against 28.8 M
+// vectors/s in a bulk load of 20 M x 256 over 16,384 centroids)
+constexpr int kVB = RTAMS_COARSE_VB;
+constexpr int kTileM = 2 * kVB * 32, kTileN = 128, kTileK = 32;  // vectors, centroids, coordinates per step
+constexpr int kVH = kTileM / 64;    // 64-row portions of the vectors a thread stages
 // an operand row in LDS: the tile's 4 groups of 8 bf16 (16 bytes each), group g of row r at place
 // g ^ ((r >> 1) & 3) of the row's 4: the 8 rows that neighbouring lanes read or write then cover all
 // 32 banks once, with no padding
@@ -119,12 +127,13 @@ __global__ __launch_bounds__(256) void k_split_rows(Dev D, int64_t n, const floa
 
 // ---- approx[i][c] for i < n, c < nlist
 template <int METRIC, bool MATRIX>
-__global__ __launch_bounds__(kMfmaThreads, 3) void k_coarse_mfma(Dev D, int64_t n, const u32x4 *__restrict__ ysplit,
+__global__ __launch_bounds__(kMfmaThreads, kVB == 2 ? 3 : 2) void k_coarse_mfma(Dev D, int64_t n, const u32x4 *__restrict__ ysplit,
                                                               const float *__restrict__ ynorm,
                                                               float *__restrict__ approx, TileCands tc,
                                                               unsigned long long *cursor_to_clear,
                                                               uint32_t *__restrict__ zero, int zero_n) {
-  __shared__ __align__(16) unsigned char s_op[4][kTileM * kRowBytes];  // vectors hi, lo; centroids hi, lo
+  __shared__ __align__(16) unsigned char s_y[2][kTileM * kRowBytes];  // vectors: hi, lo
+  __shared__ __align__(16) unsigned char s_c[2][kTileN * kRowBytes];  // centroids: hi, lo
   __shared__ float s_min[kTileM][2];
   __shared__ float s_cn[kTileN];  // |c|^2 of the tile's centroids (0 past the last one), read after the last barrier of the k loop
   __shared__ float s_norm[kTileM];
@@ -154,11 +163,11 @@ __global__ __launch_bounds__(kMfmaThreads, 3) void k_coarse_mfma(Dev D, int64_t 
 
   if (tid < kTileN) s_cn[tid] = (METRIC == 0 && col0 + tid < D.nlist) ? D.cnorm[col0 + tid] : 0.f;
 
-  floatx16 acc[2][2];
+  floatx16 acc[2][kVB];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < kVB; ++b)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
@@ -167,33 +176,43 @@ __global__ __launch_bounds__(kMfmaThreads, 3) void k_coarse_mfma(Dev D, int64_t 
   // flight while the matrix cores work on tile t out of LDS.  Rows past the last vector or centroid read
   // the last one (their scores are dropped below); the k past d are zero in both split forms.
   const int ld_row = tid / 4, ld_g = tid % 4;
-  const u32x4 *src[2][2];
+  const u32x4 *srcy[kVH], *srcc[2];
+#pragma unroll
+  for (int h = 0; h < kVH; ++h) {
+    const int64_t r = row0 + ld_row + 64 * h;
+    srcy[h] = ysplit + ((size_t)(r < n ? r : n - 1) * D.dgroups + ld_g) * 2;
+  }
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
-    const int64_t r = row0 + ld_row + 64 * h;
     const int c = col0 + ld_row + 64 * h;
-    src[h][0] = ysplit + ((size_t)(r < n ? r : n - 1) * D.dgroups + ld_g) * 2;
-    src[h][1] = D.csplit + ((size_t)(c < D.nlist ? c : D.nlist - 1) * D.dgroups + ld_g) * 2;
+    srcc[h] = D.csplit + ((size_t)(c < D.nlist ? c : D.nlist - 1) * D.dgroups + ld_g) * 2;
   }
-  u32x4 stage[2][2][2];  // [row half][vectors, centroids][hi, lo]
+  u32x4 stagey[kVH][2], stagec[2][2];  // [64-row portion][hi, lo]
   auto fetch = [&](int k0) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int h = 0; h < kVH; ++h) {
+      stagey[h][0] = srcy[h][k0 / 4];
+      stagey[h][1] = srcy[h][k0 / 4 + 1];
+    }
 #pragma unroll
-      for (int w = 0; w < 2; ++w) {
-        stage[h][w][0] = src[h][w][k0 / 4];
-        stage[h][w][1] = src[h][w][k0 / 4 + 1];
-      }
+    for (int h = 0; h < 2; ++h) {
+      stagec[h][0] = srcc[h][k0 / 4];
+      stagec[h][1] = srcc[h][k0 / 4 + 1];
+    }
   };
   fetch(0);
   for (int k0 = 0; k0 < d; k0 += kTileK) {
 #pragma unroll
+    for (int h = 0; h < kVH; ++h) {
+      const int at = lds_place(ld_row + 64 * h, ld_g);
+      *reinterpret_cast<u32x4 *>(&s_y[0][at]) = stagey[h][0];
+      *reinterpret_cast<u32x4 *>(&s_y[1][at]) = stagey[h][1];
+    }
+#pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int at = lds_place(ld_row + 64 * h, ld_g);
-      *reinterpret_cast<u32x4 *>(&s_op[0][at]) = stage[h][0][0];
-      *reinterpret_cast<u32x4 *>(&s_op[1][at]) = stage[h][0][1];
-      *reinterpret_cast<u32x4 *>(&s_op[2][at]) = stage[h][1][0];
-      *reinterpret_cast<u32x4 *>(&s_op[3][at]) = stage[h][1][1];
+      *reinterpret_cast<u32x4 *>(&s_c[0][at]) = stagec[h][0];
+      *reinterpret_cast<u32x4 *>(&s_c[1][at]) = stagec[h][1];
     }
     __syncthreads();
     if (k0 + kTileK < d) fetch(k0 + kTileK);  // uniform
@@ -204,32 +223,32 @@ __global__ __launch_bounds__(kMfmaThreads, 3) void k_coarse_mfma(Dev D, int64_t 
 #pragma unroll
     for (int kk = 0; kk < kTileK / 16; ++kk) {
       const int off = lds_place(lane & 31, kk * 2 + (lane >> 5));  // (block rows start at multiples of 32: same place)
-      bf16x8 ch[2], cl[2], yh[2], yl[2];
+      bf16x8 ch[2], cl[2], yh[kVB], yl[kVB];
 #pragma unroll
       for (int a = 0; a < 2; ++a) {
         const int at = (wc * 64 + a * 32) * kRowBytes + off;
-        ch[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&s_op[2][at]));
-        cl[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&s_op[3][at]));
+        ch[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&s_c[0][at]));
+        cl[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&s_c[1][at]));
       }
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        const int at = (wv * 64 + b * 32) * kRowBytes + off;
-        yh[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&s_op[0][at]));
-        yl[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&s_op[1][at]));
+      for (int b = 0; b < kVB; ++b) {
+        const int at = (wv * kVB * 32 + b * 32) * kRowBytes + off;
+        yh[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&s_y[0][at]));
+        yl[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&s_y[1][at]));
       }
-      // the small products first; every accumulator is touched once in four instructions
+      // the small products first; every accumulator is touched once in 2 kVB instructions
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cl[a], yh[b], acc[a][b], 0, 0, 0);
+        for (int b = 0; b < kVB; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cl[a], yh[b], acc[a][b], 0, 0, 0);
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[a], yl[b], acc[a][b], 0, 0, 0);
+        for (int b = 0; b < kVB; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[a], yl[b], acc[a][b], 0, 0, 0);
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[a], yh[b], acc[a][b], 0, 0, 0);
+        for (int b = 0; b < kVB; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[a], yh[b], acc[a][b], 0, 0, 0);
     }
     __syncthreads();
   }
@@ -246,14 +265,14 @@ __global__ __launch_bounds__(kMfmaThreads, 3) void k_coarse_mfma(Dev D, int64_t 
       const bool real = c < D.nlist;
       const float cn = s_cn[c - col0];
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
+      for (int b = 0; b < kVB; ++b)
         acc[a][b][r] = real ? (METRIC == 0 ? cn - 2.f * acc[a][b][r] : -acc[a][b][r]) : __builtin_inff();
     }
   if (MATRIX) {
     const bool quads = D.nlist % 4 == 0;  // a lane's 4 consecutive centroids of one vector go out as one 16-byte store
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      const int64_t i = row0 + wv * 64 + b * 32 + (lane & 31);
+    for (int b = 0; b < kVB; ++b) {
+      const int64_t i = row0 + wv * kVB * 32 + b * 32 + (lane & 31);
       if (i >= n) continue;
       float *out = approx + (size_t)i * D.nlist;
 #pragma unroll
@@ -276,20 +295,20 @@ __global__ __launch_bounds__(kMfmaThreads, 3) void k_coarse_mfma(Dev D, int64_t 
   if (tid < kTileM) s_norm[tid] = ynorm[row0 + tid < n ? row0 + tid : n - 1];
   if (tid < kTileM) s_cnt[tid] = 0u;
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {  // smallest score of this lane's vector over the wavefront's 64 centroids
+  for (int b = 0; b < kVB; ++b) {  // smallest score of this lane's vector over the wavefront's 64 centroids
     float v = __builtin_inff();
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
       for (int r = 0; r < 16; ++r) v = fminf(v, acc[a][b][r]);
     v = fminf(v, __shfl_xor(v, 32));  // the other half of the lanes holds the other centroids of the same vector
-    if (lane < 32) s_min[wv * 64 + b * 32 + lane][wc] = v;
+    if (lane < 32) s_min[wv * kVB * 32 + b * 32 + lane][wc] = v;
   }
   __syncthreads();
   const float cmax = __uint_as_float(D.ctrl->cnorm_max_bits);
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    const int row = wv * 64 + b * 32 + (lane & 31);
+  for (int b = 0; b < kVB; ++b) {
+    const int row = wv * kVB * 32 + b * 32 + (lane & 31);
     // the smallest of the tile plus 2 E of the vector, a little wider than the refinement's (1.02 against
     // 1.01), so that what the refinement asks for is certainly among what is kept here
     const float limit = fminf(s_min[row][0], s_min[row][1]) + coarse_band(D.d, s_norm[row] + cmax) * 1.02f;
