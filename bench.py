@@ -416,7 +416,7 @@ def main() -> int:
     ap.add_argument("--pq-m", type=int, default=0,
                     help="with --study pq: only this number of sub-spaces, and only the --batch query batch")
     ap.add_argument("--shape", type=int, default=0, help="with --study shapes: only this configuration (3, 4 or 5)")
-    ap.add_argument("--study", choices=["rearrange", "rearrange5", "blocksize", "pq", "storage", "shapes", "mixed", "growth"],
+    ap.add_argument("--study", choices=["rearrange", "rearrange5", "blocksize", "pq", "storage", "shapes", "mixed", "growth", "online"],
                     help="run one of the side studies instead of the benchmark (one JSON line each)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -444,7 +444,7 @@ def main() -> int:
         fn = {"rearrange": studies.rearrangement_study, "blocksize": studies.block_size_sweep,
               "pq": studies.pq_study, "storage": studies.storage_study, "shapes": studies.shape_study,
               "mixed": studies.mixed_load_study, "growth": studies.growth_study,
-              "rearrange5": studies.hot_list_rearrangement_study}[args.study]
+              "rearrange5": studies.hot_list_rearrangement_study, "online": studies.online_latency_study}[args.study]
         iters = args.latency_iters or 2000
         if args.study == "pq":
             params = {k: int(v) for k, v in (kv.split("=") for kv in args.set)}

@@ -642,6 +642,130 @@ def mixed_load_study(scale: float = 1.0, rates=(1_000, 5_000, 20_000, 50_000, 20
             "search_streams": len(sstreams), "seconds_per_rate": seconds, "rows": rows}
 
 
+def online_latency_study(scale: float = 1.0, search_rates=(1_000, 5_000, 10_000),
+                         insert_rates=(0, 100, 1_000, 2_000, 5_000, 10_000, 50_000), seconds: float = 3.0,
+                         iters: int = 0) -> dict:
+    """The shape of the paper's online experiment (its figure of average latency against the insert rate
+    at fixed search rates; section "Comparing to state-of-the-art methods") on configuration 2's data:
+    single queries arrive as a Poisson process at QPS_search and are sent one request each (nprobe 32, k
+    100); single vectors arrive at QPS_insert and leave in batches of up to 64 (a batch leaves when it is
+    full, or 10 ms after its first vector arrived); 7 search streams and the data stream.  Reported per
+    point, as the paper does: the average latency of a search request plus the average latency of an
+    insertion request (submission to completion), their p99s, and the time an operation waited for its
+    batch.  `iters` is unused."""
+    dev = torch.device("cuda:0")
+    w = synth.config(2, scale=scale)
+    rng = np.random.Generator(np.random.PCG64([w.seed, 77]))
+    base, cents, queries, inserts = (_to_dev(a, dev) for a in (w.base, w.centroids, w.queries, w.inserts))
+    n_all = len(w.base) + 3_000_000
+    g = rtams.Index(w.d, w.nlist, w.metric, w.block_vecs, pool_blocks=n_all // w.block_vecs + 2 * w.nlist + 64,
+                    n_resources=16, max_batch=64, max_k=128, max_nprobe=w.nprobe, max_add_batch=65536,
+                    candidates_per_query=65536)
+    data = torch.cuda.Stream(dev)
+    sstreams = [torch.cuda.Stream(dev) for _ in range(7)]
+    g.set_centroids(cents, stream=data)
+    g.add(base, stream=data)
+    data.synchronize()
+    od = [torch.empty((1, w.k), dtype=torch.float32, device=dev) for _ in range(64)]
+    oi = [torch.empty((1, w.k), dtype=torch.int64, device=dev) for _ in range(64)]
+    for s_ in sstreams:
+        g.search(queries[:1], w.k, w.nprobe, od[0], oi[0], stream=s_)
+        s_.synchronize()
+    nq, ni = len(queries), len(inserts)
+    flush_s = 0.010
+    rows = []
+    for qs in search_rates:
+        for qi in insert_rates:
+            n_q = int(qs * seconds)
+            tq = np.cumsum(rng.exponential(1.0 / qs, size=n_q))
+            ti = np.cumsum(rng.exponential(1.0 / qi, size=int(qi * seconds))) if qi > 0 else np.zeros(0)
+            times = np.concatenate([tq, ti])
+            kinds = np.concatenate([np.ones(len(tq), bool), np.zeros(len(ti), bool)])
+            order = np.argsort(times, kind="stable")
+            times, kinds = times[order], kinds[order]
+            in_flight, q_lat, i_lat, i_wait = [], [], [], []
+            pend_i = []
+            busy = 0
+            qpos = ipos = slot = 0
+            free_events = [torch.cuda.Event() for _ in range(256)]
+
+            def reap(block=False):
+                keep = []
+                for ev, arr, kind, t_sub in in_flight:
+                    if block:
+                        ev.synchronize()
+                    if block or ev.query():
+                        t = time.perf_counter() - t_start
+                        if kind == "q":
+                            q_lat.append((t - t_sub) * 1e3)
+                        else:
+                            i_lat.append((t - t_sub) * 1e3)
+                            i_wait.extend((t_sub - a) * 1e3 for a in arr)
+                        free_events.append(ev)
+                    else:
+                        keep.append((ev, arr, kind, t_sub))
+                in_flight[:] = keep
+
+            def flush_inserts():
+                nonlocal pend_i, ipos
+                t_sub = time.perf_counter() - t_start
+                n = len(pend_i)
+                g.add(inserts[ipos:ipos + n], stream=data)
+                ev = free_events.pop() if free_events else torch.cuda.Event()
+                ev.record(data)
+                in_flight.append((ev, pend_i, "i", t_sub))
+                pend_i = []
+                ipos = (ipos + n) % (ni - 64)
+
+            t_start = time.perf_counter()
+            for op in range(len(times)):
+                while True:
+                    now = time.perf_counter() - t_start
+                    if pend_i and now - pend_i[0] >= flush_s:
+                        flush_inserts()
+                    if now >= times[op]:
+                        break
+                    reap()
+                if kinds[op]:
+                    st = sstreams[slot % len(sstreams)]
+                    t_sub = time.perf_counter() - t_start
+                    while True:
+                        try:
+                            g.search(queries[qpos:qpos + 1], w.k, w.nprobe, od[slot % 64], oi[slot % 64], stream=st)
+                            break
+                        except rtams.RtamsError as e:
+                            if e.code != rtams.EBUSY:
+                                raise
+                            busy += 1
+                            reap()
+                    ev = free_events.pop() if free_events else torch.cuda.Event()
+                    ev.record(st)
+                    in_flight.append((ev, None, "q", t_sub))
+                    qpos = (qpos + 1) % (nq - 1)
+                    slot += 1
+                else:
+                    pend_i.append(times[op])
+                    if len(pend_i) >= 64:
+                        flush_inserts()
+            if pend_i:
+                flush_inserts()
+            t_sent = time.perf_counter() - t_start
+            reap(block=True)
+            assert g.poll_error() == 0
+            sa = float(np.mean(q_lat)) if q_lat else 0.0
+            ia = float(np.mean(i_lat)) if i_lat else 0.0
+            rows.append({"qps_search": qs, "qps_insert": qi, "search_requests": len(q_lat), "insert_requests": len(i_lat),
+                         "latency_avg_ms": sa + ia, "search_avg_ms": sa, "search_p99_ms": _p(q_lat, 99) if q_lat else None,
+                         "insert_avg_ms": ia if i_lat else None, "insert_p99_ms": _p(i_lat, 99) if i_lat else None,
+                         "insert_wait_for_batch_avg_ms": float(np.mean(i_wait)) if i_wait else None,
+                         "generator_lag_ms": (t_sent - float(times[-1])) * 1e3, "requests_refused_busy": busy})
+    g.validate()
+    g.close()
+    return {"study": "online_latency", "workload": w.name, "n_base": len(w.base), "nprobe": w.nprobe, "k": w.k,
+            "search_streams": len(sstreams), "seconds_per_point": seconds, "insert_batch": 64, "insert_flush_ms": flush_s * 1e3,
+            "rows": rows}
+
+
 def growth_study(scale: float = 1.0, seconds: float = 6.0, rate: float = 100_000.0, threshold: int = 10_000,
                  iters: int = 0) -> dict:
     """Skewed growth under load: a tenth of configuration 5's base set, then `seconds` of inserts at `rate`

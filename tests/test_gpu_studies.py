@@ -91,3 +91,13 @@ def test_growth_study_small():
     # device's report of the last exceeding batch reached the host)
     assert h["runs_after"] <= max(3, h["blocks_after"] // 4)
     assert out["pool"]["lists_exceeding_after"] == 0
+
+
+def test_online_latency_study_small():
+    from paper_2408_02937_amd import studies
+    print("[case] online latency study, scale 0.03, 1000 queries/s, 0 and 5000 vectors/s, 0.3 s each", flush=True)
+    out = studies.online_latency_study(scale=0.03, search_rates=(1000,), insert_rates=(0, 5000), seconds=0.3)
+    quiet, busy = out["rows"]
+    assert quiet["insert_requests"] == 0 and quiet["search_requests"] == 300
+    assert busy["insert_requests"] > 0 and busy["insert_avg_ms"] > 0
+    assert busy["latency_avg_ms"] == pytest.approx(busy["search_avg_ms"] + busy["insert_avg_ms"])
