@@ -64,7 +64,8 @@ typedef struct rtams_config {
   int64_t rearrange_threshold; /* T_m' of Exceed(): vectors appended to a list since its
                                   last rearrangement; <= 0 never triggers */
   void *d_pool;       /* device memory carved into control data, tables and blocks */
-  size_t pool_bytes;
+  size_t pool_bytes;  /* at most what holds 2^32 / block_vecs blocks (a search names a candidate by its
+                         place in the pool, a 32-bit number): rtams_create says EINVAL beyond that */
   void *d_scratch;    /* device memory: one slice per stream resource, all of one size, then the
                          shared reserve (overflow_bytes) if any */
   size_t scratch_bytes;

@@ -41,7 +41,7 @@ __device__ void sample_scores(const Dev &D, int nprobe, int max_nprobe, int q, u
     const uint32_t have = D.nblk[list] * gpb;  // never index the block table past the chain
     if (groups > have) groups = have;
     if (groups > want_groups - g_first) groups = want_groups - g_first;
-    for (uint32_t g = (uint32_t)wave; g < groups; g += kGroupThreads / kWave) {
+    for (uint32_t g = (uint32_t)wave; g < groups; g += blockDim.x / kWave) {
       const uint32_t b = (uint32_t)*table_entry(D, list, g / gpb);
       const float4 *__restrict__ x = block_vecs(D, b) + (size_t)(g % gpb) * group_stride + lane;
       float acc = 0.f;
@@ -63,7 +63,18 @@ __device__ void sample_scores(const Dev &D, int nprobe, int max_nprobe, int q, u
         const int r = lane & 3;
         acc = r == 0 ? m[0] : r == 1 ? m[1] : r == 2 ? m[2] : m[3];
       }
-      for (; c + 8 <= d4; c += 8) {  // eight loads of 1 KiB in flight per wavefront
+      // loads of 1 KiB in flight per wavefront: sixteen, then eight, then one at a time (the workgroup
+      // is alone on its CU and a group is a chain of such round trips)
+      if (ST == 0) {
+        for (; c + 16 <= d4; c += 16) {
+          float4 v[16];
+#pragma unroll
+          for (int u = 0; u < 16; ++u) v[u] = x[(size_t)(c + u) * kWave];
+#pragma unroll
+          for (int u = 0; u < 16; ++u) accumulate<METRIC>(acc, v[u], qv[c + u]);
+        }
+      }
+      for (; c + 8 <= d4; c += 8) {
         float4 v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) v[u] = x[(size_t)(c + u) * kWave];
@@ -104,7 +115,7 @@ __device__ void pq_sample_scores(const Dev &D, int nprobe, int max_nprobe, int q
     const uint32_t have = D.nblk[list] * gpb;  // never index the block table past the chain
     if (groups > have) groups = have;
     if (groups > want_groups - g_first) groups = want_groups - g_first;
-    for (uint32_t g = (uint32_t)wave; g < groups; g += kGroupThreads / kWave) {
+    for (uint32_t g = (uint32_t)wave; g < groups; g += blockDim.x / kWave) {
       const uint32_t b = (uint32_t)*table_entry(D, list, g / gpb);
       const uint32_t *__restrict__ x = block_codes(D, b) + (size_t)(g % gpb) * words * kWave + lane;
       float acc = 0.f;
@@ -124,11 +135,15 @@ __device__ void pq_sample_scores(const Dev &D, int nprobe, int max_nprobe, int q
   }
 }
 
+// LDS of a bound: the query (d <= 2048) and the keys of the sample.  The caller owns it, so that a
+// kernel whose workgroups do different jobs can use the same bytes for each.
+constexpr size_t kBoundLdsBytes = 512 * sizeof(float4) + kSampleMax * sizeof(uint32_t);
+
 template <bool PQ>
 __device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, int k, const float *__restrict__ Q,
-                             const SearchScratch &S) {
-  __shared__ float4 qv[512];  // the query (d <= 2048)
-  __shared__ uint32_t skey[kSampleMax];
+                             const SearchScratch &S, unsigned char *lds) {
+  float4 *qv = reinterpret_cast<float4 *>(lds);
+  uint32_t *skey = reinterpret_cast<uint32_t *>(lds + 512 * sizeof(float4));
   __shared__ __attribute__((aligned(8))) uint32_t hist[256];
   __shared__ uint32_t bc[4];
   const int tid = threadIdx.x;
@@ -169,8 +184,8 @@ __device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, in
   want = want < 512u ? 512u : (want > cap ? cap : want);
   const uint32_t want_groups = (want + kWave - 1) / kWave;
   if (!PQ)
-    for (int c = tid; c < D.d4; c += kGroupThreads) qv[c] = reinterpret_cast<const float4 *>(Q + (size_t)q * D.d)[c];
-  for (int i = tid; i < (int)(want_groups * kWave); i += kGroupThreads) skey[i] = 0xFFFFFFFFu;
+    for (int c = tid; c < D.d4; c += (int)blockDim.x) qv[c] = reinterpret_cast<const float4 *>(Q + (size_t)q * D.d)[c];
+  for (int i = tid; i < (int)(want_groups * kWave); i += (int)blockDim.x) skey[i] = 0xFFFFFFFFu;
   __syncthreads();
   if (PQ) pq_sample_scores(D, nprobe, max_nprobe, q, want_groups, S, skey);
   else if (D.metric == 0) {
@@ -213,6 +228,7 @@ __device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, in
 // for which the request has at most `item_budget` items and no XCD more than
 // `max_per_xcd` (the launch of the scan is sized from those two).
 constexpr int kSegChoices = 8;  // segment lengths 2, 4, ..., 256 groups
+constexpr int kLdsEntries = 1024;  // probed lists of a request up to which their entries stay in LDS
 constexpr int kListChunk = 16;  // lists a thread of the grouping workgroup handles side by side
 
 __device__ inline void wg_scan3(uint32_t &a, uint32_t &b, unsigned long long &c, uint32_t *sa,
@@ -247,7 +263,7 @@ __device__ inline void wg_scan3(uint32_t &a, uint32_t &b, unsigned long long &c,
 // The pairs of the request grouped by list: `grouped` holds, list after list in list order, the
 // (query, probe) pairs that probe the list, each at the rank the plan gave it.  One workgroup, beside
 // the one that cuts the work items (both derive the same pair starts from the same counters: a
-// running sum of the pair counts over the lists, 1024 consecutive lists at a time, 16 rows in flight).
+// running sum of the pair counts over the lists, a row of consecutive lists per thread at a time, 16 rows in flight).
 __device__ void scatter_pairs(const Dev &D, int nq, int nprobe, int max_nprobe, const SearchScratch &S) {
   constexpr int kWavesG = kGroupThreads / kWave;
   __shared__ uint32_t s_tot[kListChunk * kWavesG + 1];
@@ -333,8 +349,11 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
     scatter_pairs(D, nq, nprobe, max_nprobe, S);
     return;
   }
+  // the bound's query and sample keys, or the entries of the probed lists of a small request
+  __shared__ __attribute__((aligned(16))) unsigned char s_raw[kBoundLdsBytes];
+  static_assert(kBoundLdsBytes >= kLdsEntries * (sizeof(uint4) + sizeof(uint32_t)), "the entries share the bound's LDS");
   if (blockIdx.x > 1) {  // this one sets the bound of query blockIdx.x - 2
-    sample_bound<false>(D, (int)blockIdx.x - 2, nprobe, max_nprobe, k, Q, S);
+    sample_bound<false>(D, (int)blockIdx.x - 2, nprobe, max_nprobe, k, Q, S, s_raw);
     return;
   }
   __shared__ uint32_t s_a[kGroupThreads];
@@ -351,8 +370,13 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
   if (tid == 0) s_nhuge = 0;
   const uint32_t *__restrict__ list_cnt = S.list_cnt;
   uint4 *__restrict__ tile_desc = S.tile_desc;
-  uint4 *__restrict__ plist = S.plist;
-  uint32_t *__restrict__ pistart = S.pistart;
+  // The entries of the probed lists are written by one thread and read by another several times
+  // over: every such hand-over through global memory is a round trip of a microsecond that nothing
+  // hides (this workgroup is alone on its CU).  A request that can probe at most kLdsEntries
+  // different lists keeps them in LDS.
+  const bool lean = (long long)min((long long)D.nlist, (long long)nq * nprobe) <= kLdsEntries;
+  uint4 *plist = lean ? reinterpret_cast<uint4 *>(s_raw) : S.plist;
+  uint32_t *pistart = lean ? reinterpret_cast<uint32_t *>(s_raw + kLdsEntries * sizeof(uint4)) : S.pistart;
   ScanQueues *Qs = S.queues;
   // Cost of a list for the split over the XCDs, per group of 64 vectors: reading it once from HBM
   // (each XCD has its own link to memory) plus the arithmetic of every query that probes it.  On
@@ -361,7 +385,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
 
   // The probed lists, compacted in list order (neighbouring lists sit in neighbouring blocks after a
   // bulk load, and the scan reads faster in that order): entry = {list, first pair, pairs, length}.
-  // The pair counters are read 1024 consecutive lists at a time, 16 such rows per thread in flight;
+  // The pair counters are read a row of consecutive lists (one per thread) at a time, 16 such rows in flight;
   // the place of a probed list among the entries comes from ballots and one small prefix sum.  Lists
   // nobody probes are not looked at again (16,384 lists, 256 x 64 pairs: a quarter of the lists).
   // The visible length of every probed list is read ONCE: an insertion may publish while this kernel
@@ -622,12 +646,14 @@ __global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int npro
 }
 
 
+constexpr int kPqBoundThreads = 1024;
+
 // The bound of every query of a request over quantised lists (the grouping by list that the scan
 // of flat lists needs is not made).
 // The workgroup of a query first writes the query's table of sub-scores: lut[q][m][c] = squared
 // distance (L2) or inner product (IP) between sub-vector m of the query and entry c of codebook m,
 // fp32, one FMA chain in the order of the dimensions; its sample and the scan read it from there.
-__global__ __launch_bounds__(kGroupThreads) void k_pq_bound(Dev D, int nprobe, int max_nprobe, int k,
+__global__ __launch_bounds__(kPqBoundThreads) void k_pq_bound(Dev D, int nprobe, int max_nprobe, int k,
                                                             const float *__restrict__ Q, SearchScratch S) {
   const int q = blockIdx.x;
   {
@@ -636,13 +662,13 @@ __global__ __launch_bounds__(kGroupThreads) void k_pq_bound(Dev D, int nprobe, i
     float *__restrict__ lut = S.lut + (size_t)q * M * 256;
     // M * 256 entries, 1024 threads: M / 4 rounds, four of them side by side (their loads overlap);
     // 16-byte loads where the sub-space allows
-    for (int i0 = threadIdx.x; i0 < M * 256; i0 += 4 * kGroupThreads) {
+    for (int i0 = threadIdx.x; i0 < M * 256; i0 += 4 * kPqBoundThreads) {
       float acc[4] = {0.f, 0.f, 0.f, 0.f};
       if (ds % 4 == 0) {  // uniform
         for (int j4 = 0; j4 < ds / 4; ++j4) {
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
-            const int i = i0 + r * kGroupThreads;
+            const int i = i0 + r * kPqBoundThreads;
             if (i < M * 256) {
               const float4 ev = reinterpret_cast<const float4 *>(D.codebooks + (size_t)i * ds)[j4];
               const float4 yv = reinterpret_cast<const float4 *>(yq + (size_t)(i >> 8) * ds)[j4];
@@ -661,7 +687,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_pq_bound(Dev D, int nprobe, i
         for (int j = 0; j < ds; ++j) {
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
-            const int i = i0 + r * kGroupThreads;
+            const int i = i0 + r * kPqBoundThreads;
             if (i < M * 256) {
               const float ev = D.codebooks[(size_t)i * ds + j], yv = yq[(size_t)(i >> 8) * ds + j];
               if (D.metric == 0) { const float u = ev - yv; acc[r] = fmaf(u, u, acc[r]); }
@@ -672,12 +698,13 @@ __global__ __launch_bounds__(kGroupThreads) void k_pq_bound(Dev D, int nprobe, i
       }
 #pragma unroll
       for (int r = 0; r < 4; ++r)
-        if (i0 + r * kGroupThreads < M * 256) lut[i0 + r * kGroupThreads] = acc[r];
+        if (i0 + r * kPqBoundThreads < M * 256) lut[i0 + r * kPqBoundThreads] = acc[r];
     }
   }
   __threadfence_block();
   __syncthreads();  // the sample below reads the table
-  sample_bound<true>(D, q, nprobe, max_nprobe, k, nullptr, S);
+  __shared__ __attribute__((aligned(16))) unsigned char s_raw[kBoundLdsBytes];
+  sample_bound<true>(D, q, nprobe, max_nprobe, k, nullptr, S, s_raw);
 }
 
 
@@ -685,7 +712,7 @@ void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int k, c
                   int item_budget, const SearchScratch &S, hipStream_t s) {
   if (nq <= 0) return;
   if (D.pq_m > 0) {
-    hipLaunchKernelGGL(k_pq_bound, dim3((unsigned)nq), dim3(kGroupThreads), 0, s, D, nprobe, max_nprobe, k, Q, S);
+    hipLaunchKernelGGL(k_pq_bound, dim3((unsigned)nq), dim3(kPqBoundThreads), 0, s, D, nprobe, max_nprobe, k, Q, S);
     return;
   }
   // workgroup 0 cuts the work items, workgroup 1 groups the pairs, workgroup 2 + q sets the bound of query q

@@ -115,7 +115,7 @@ __global__ __launch_bounds__(kPqScanThreads) void k_pq_scan(Dev D, int nprobe, i
     // and their survivors are appended with one reservation
     for (uint32_t i0 = (uint32_t)(kPqUnits * wave); i0 < n_here; i0 += kPqUnits * kPqScanWaves) {
       const uint32_t *__restrict__ x[kPqUnits];
-      uint32_t len[kPqUnits], off[kPqUnits], v[kPqUnits];
+      uint32_t len[kPqUnits], slot0[kPqUnits], v[kPqUnits];
       bool live[kPqUnits];
 #pragma unroll
       for (int j = 0; j < kPqUnits; ++j) {
@@ -128,7 +128,7 @@ __global__ __launch_bounds__(kPqScanThreads) void k_pq_scan(Dev D, int nprobe, i
         const size_t o = (size_t)q * max_nprobe + p;
         x[j] = block_codes(D, blk) + (size_t)(g % gpb) * words * kWave + lane;
         len[j] = S.probe_len[o];
-        off[j] = S.probe_off[o];
+        slot0[j] = slot_of(D, blk, (g % gpb) * kWave + (uint32_t)lane);
         v[j] = g * kWave + lane;
       }
       float acc[kPqUnits];
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kPqScanThreads) void k_pq_scan(Dev D, int nprobe, i
           if ((mask[j] >> lane) & 1ull) {
             const uint32_t slot = (uint32_t)__popcll(mask[j] & below);
             rk[slot] = key[j];
-            rp[slot] = off[j] + v[j];
+            rp[slot] = slot0[j];
           }
           rk += __popcll(mask[j]);
           rp += __popcll(mask[j]);
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(kPqScanThreads) void k_pq_scan(Dev D, int nprobe, i
           if ((mask[j] >> lane) & 1ull) {
             const uint32_t slot = staged + (uint32_t)__popcll(mask[j] & below);
             my_key[slot] = key[j];
-            my_pos[slot] = off[j] + v[j];
+            my_pos[slot] = slot0[j];
           }
           staged += (uint32_t)__popcll(mask[j]);
         }

@@ -128,7 +128,6 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
   // plan
   int32_t *pl = S.probe_list + (size_t)q * max_nprobe;
   uint32_t *plen = S.probe_len + (size_t)q * max_nprobe;
-  uint32_t *poff = S.probe_off + (size_t)q * max_nprobe;
   for (int p = threadIdx.x; p < nprobe; p += kSelThreads) {
     int list = (int)pay[p];
     pl[p] = list;
@@ -143,9 +142,7 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
   if (threadIdx.x == 0) {
     unsigned long long tot = 0;
     for (int p = 0; p < nprobe; ++p) {
-      uint32_t len = pay[p];
-      poff[p] = (uint32_t)tot;
-      tot += len;
+      tot += pay[p];
     }
     unsigned long long base = 0;
     if (probe_out) tot = 0;  // the probe hook: nothing is scanned afterwards, no room for records is taken
@@ -160,7 +157,7 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
       atomicCAS(&D.ctrl->search_error, 0, -6);
       D.mirror->search_error = -6;
       tot = 0;
-      for (int p = 0; p < nprobe; ++p) { plen[p] = 0; poff[p] = 0; }
+      for (int p = 0; p < nprobe; ++p) plen[p] = 0;
     }
     S.qbase[q] = base;
     S.qtotal[q] = (uint32_t)tot;

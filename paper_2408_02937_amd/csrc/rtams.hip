@@ -146,7 +146,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
 }
 
 struct ScratchLayout {
-  size_t scores, approx, probe_list, probe_len, probe_off, qbase, qtotal, bound, qnorm, qsplit, rec_cnt, cursor, req_words, lut, records, fixed;
+  size_t scores, approx, probe_list, probe_len, qbase, qtotal, bound, qnorm, qsplit, rec_cnt, cursor, req_words, lut, records, fixed;
   size_t list_cnt, pair_start, pair_slot, grouped, plist, pistart, tile_desc, queues, item_cap;
 };
 
@@ -159,7 +159,6 @@ void lay_out_scratch(const rtams_config *c, ScratchLayout *S) {
   S->lut = take(c->pq_m > 0 ? mb * c->pq_m * 256 * 4 : 0);
   S->probe_list = take(mb * mp * 4);
   S->probe_len = take(mb * mp * 4);
-  S->probe_off = take(mb * mp * 4);
   S->qbase = take(mb * 8);
   S->qtotal = take(mb * 4);
   S->bound = take(mb * 4);
@@ -415,6 +414,11 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   if (L.nblocks < 1 || L.total > cfg->pool_bytes)
     return fail(RTAMS_EINVAL, "pool of %zu bytes holds no block (control data needs %zu, a block %zu)",
                 cfg->pool_bytes, L.fixed_end, L.block_stride);
+  // a search names a surviving candidate by its place in the pool, a 32-bit number
+  if ((uint64_t)L.nblocks * (uint64_t)cfg->block_vecs > (1ull << 32))
+    return fail(RTAMS_EINVAL, "pool of %zu bytes holds %lld blocks of %d vectors: more than 2^32 places; pass at most %zu bytes",
+                cfg->pool_bytes, (long long)L.nblocks, cfg->block_vecs,
+                rtams_pool_bytes_for(cfg, (int64_t)((1ull << 32) / (uint64_t)cfg->block_vecs)));
   ScratchLayout SL;
   lay_out_scratch(cfg, &SL);
   if (cfg->overflow_bytes > cfg->scratch_bytes) return fail(RTAMS_EINVAL, "overflow_bytes exceeds scratch_bytes");
@@ -528,7 +532,6 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
     S.lut = reinterpret_cast<float *>(p + SL.lut);
     S.probe_list = reinterpret_cast<int32_t *>(p + SL.probe_list);
     S.probe_len = reinterpret_cast<uint32_t *>(p + SL.probe_len);
-    S.probe_off = reinterpret_cast<uint32_t *>(p + SL.probe_off);
     S.qbase = reinterpret_cast<unsigned long long *>(p + SL.qbase);
     S.qtotal = reinterpret_cast<uint32_t *>(p + SL.qtotal);
     S.bound = reinterpret_cast<uint32_t *>(p + SL.bound);

@@ -112,6 +112,13 @@ __device__ inline int32_t *table_entry(const Dev &D, int list, uint32_t i) {
   return D.slab + off + (i - table_seg_first(s));
 }
 
+// A vector's place in the pool as one 32-bit number (block * T_m + place in the block; the pool holds
+// at most 2^32 places, which rtams_create checks): what a search keeps of a surviving candidate, so
+// that whoever needs its id or its coordinates later goes straight to the block.  The block stays
+// what it was until the request has finished: a rearrangement waits for the requests in flight
+// before it reuses a block.
+__device__ inline uint32_t slot_of(const Dev &D, uint32_t b, uint32_t place) { return b * (uint32_t)D.T_m + place; }
+
 __device__ inline BlockHeader *block_header(const Dev &D, uint32_t b) {
   return reinterpret_cast<BlockHeader *>(D.blocks + (size_t)b * D.block_stride);
 }

@@ -23,7 +23,6 @@ struct SearchScratch {
   float *approx;        // [max_batch][nlist] approximate coarse scores from the matrix cores
   int32_t *probe_list;  // [max_batch][max_nprobe]
   uint32_t *probe_len;  // [max_batch][max_nprobe] list lengths as seen by this request
-  uint32_t *probe_off;  // [max_batch][max_nprobe] start of the list inside the query's candidates
   unsigned long long *qbase;  // [max_batch] start of the query's slice of rec_key / rec_pos
   uint32_t *qtotal;     // [max_batch] candidates of the query
   uint32_t *bound;      // [max_batch] key of the score the scan compares with
@@ -43,7 +42,7 @@ struct SearchScratch {
   ScanQueues *queues;   // work items of this request, split into one queue per XCD
   float *lut;           // [max_batch][pq_m][256] sub-scores of the queries against the codebooks (PQ lists)
   uint32_t *rec_key;    // survivors: key of the score (smaller is better) ...
-  uint32_t *rec_pos;    // ... and position among the query's candidates
+  uint32_t *rec_pos;    // ... and its place in the pool (slot_of)
   unsigned long long cand_cap;  // entries of each of the two arrays
   // The reserve shared by all resources, cut into chunks of equal size.  A request whose queries do not
   // all fit into the slice leases ONE chunk (the first query in need takes it, the others share it);

@@ -36,14 +36,13 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
   const int lane = threadIdx.x & (kWave - 1);
   // lane i < NQ looks after query i of the item: how far its list goes, its bound, where its
   // survivor records go
-  uint32_t my_q = 0, my_len = 0, my_off = 0, my_bound = 0;
+  uint32_t my_q = 0, my_len = 0, my_bound = 0;
   uint64_t my_keys = 0, my_poss = 0;  // addresses of the query's survivor records (keys, positions)
   if (lane < NQ) {
     const uint32_t pk = S.grouped[first + lane];
     my_q = pk >> 10;
     const size_t o = (size_t)my_q * max_nprobe + (pk & 1023u);
     my_len = S.probe_len[o];
-    my_off = S.probe_off[o];
     const unsigned long long qb = S.qbase[my_q];
     my_keys = (uint64_t)(uintptr_t)rec_keys_of(S, qb);
     my_poss = (uint64_t)(uintptr_t)rec_poss_of(S, qb);
@@ -203,18 +202,17 @@ __device__ __forceinline__ void scan_item(const Dev &D, const SearchScratch &S,
         for (int i = 0; i < NQ; ++i) {
           if ((m0[i] | m1[i]) == 0) continue;  // uniform
           const uint64_t at = 4ull * lane_u32(base_mine, i);
-          const uint32_t off = lane_u32(my_off, i);
           GlobalU32 *rk = (GlobalU32 *)(lane_u64(my_keys, i) + at);
           GlobalU32 *rp = (GlobalU32 *)(lane_u64(my_poss, i) + at);
           if ((m0[i] >> lane) & 1ull) {
             const uint32_t slot = (uint32_t)__popcll(m0[i] & below);
             rk[slot] = key_of_float((METRIC == 0 ? acc0[i] : -acc0[i]) + 0.0f);
-            rp[slot] = off + v0;
+            rp[slot] = slot_of(D, b0, (g0 % gpb) * kWave + (uint32_t)lane);
           }
           if ((m1[i] >> lane) & 1ull) {
             const uint32_t slot = (uint32_t)__popcll(m0[i]) + (uint32_t)__popcll(m1[i] & below);
             rk[slot] = key_of_float((METRIC == 0 ? acc1[i] : -acc1[i]) + 0.0f);
-            rp[slot] = off + v1;
+            rp[slot] = slot_of(D, b1, (g1 % gpb) * kWave + (uint32_t)lane);
           }
         }
       }

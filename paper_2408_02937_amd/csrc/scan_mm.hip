@@ -29,9 +29,9 @@ namespace rtams {
 // than the scan itself: dozens of wavefronts reserve from the same few counters.)
 
 struct TileQuery {  // kMmQueryWords 32-bit words
-  uint32_t q, len, off, bound;
+  uint32_t q, len, bound;
   float qn;
-  uint32_t pad[3];
+  uint32_t pad[4];
   uint64_t keys, poss;  // addresses of the query's survivor records (keys, positions)
 };
 static_assert(sizeof(TileQuery) == kMmQueryWords * 4, "words per query of a tile");
@@ -111,6 +111,7 @@ __device__ __forceinline__ void scan_groups_mm(const Dev &D, const SearchScratch
   uint32_t g0 = g_lo + (uint32_t)wave;
   if (g0 >= g_hi) return;  // nothing staged yet
   const float4 *x = place(g0, first_b);
+  uint32_t cur_b = first_b;  // the block of group g0
   if (d4_main) load_set(sa, x, 0);
   for (;;) {
     const uint32_t g_next = g0 + kMmWaves;
@@ -169,6 +170,7 @@ __device__ __forceinline__ void scan_groups_mm(const Dev &D, const SearchScratch
     // scores -> keys; which of the lane's 4 candidates per group of queries survive
     const float nr[4] = {quad_broadcast<0>(nrm), quad_broadcast<1>(nrm), quad_broadcast<2>(nrm), quad_broadcast<3>(nrm)};
     const uint32_t vbase = g0 * kWave + 4u * (uint32_t)(lane >> 2);
+    const uint32_t slot_base = slot_of(D, cur_b, (g0 % gpb) * kWave + 4u * (uint32_t)(lane >> 2));
 #pragma unroll
     for (int g = 0; g < QG; ++g) {
       const TileQuery me = tq[4 * g + sub];  // len 0 for rows past the tile: nothing of theirs is kept
@@ -195,7 +197,7 @@ __device__ __forceinline__ void scan_groups_mm(const Dev &D, const SearchScratch
         if (pass & (1u << r)) {
           const uint32_t e = staged + at[r];
           st.key[e] = key[r];
-          st.pos[e] = me.off + vbase + r;
+          st.pos[e] = slot_base + r;
           st.row[e] = (uint8_t)(4 * g + sub);
         }
       staged += total;
@@ -203,6 +205,7 @@ __device__ __forceinline__ void scan_groups_mm(const Dev &D, const SearchScratch
     if (!more) break;
     g0 = g_next;
     x = x_next;
+    cur_b = next_b;
   }
   if (staged) flush();
 }
@@ -253,7 +256,6 @@ __global__ __launch_bounds__(kMmWaves *kWave) void k_scan_mm(Dev D, int max_npro
       t.q = pk >> 10;
       const size_t o = (size_t)t.q * max_nprobe + (pk & 1023u);
       t.len = S.probe_len[o];
-      t.off = S.probe_off[o];
       const unsigned long long qb = S.qbase[t.q];
       t.keys = (uint64_t)(uintptr_t)rec_keys_of(S, qb);
       t.poss = (uint64_t)(uintptr_t)rec_poss_of(S, qb);

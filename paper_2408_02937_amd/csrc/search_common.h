@@ -182,6 +182,52 @@ __device__ SelectResult wg_radix_select(int n, uint32_t k, Fn fn, uint32_t *hist
   return wg_radix_select_each<BITS>(k, each, hist, bc);
 }
 
+// The same for a few hundred 32-bit keys that lie in LDS (16-byte aligned), one per thread: a thread
+// counts the keys below its own (four keys per LDS read, which the whole wavefront shares; a compare
+// and an add per key); the k-th smallest key T is the largest key with fewer than k keys below it.
+// Three barriers where the radix passes take a dozen, but the work grows with the square of n: it
+// pays up to kRankSelectMax keys.  T is the k-th smallest key itself.  Requires 1 <= k <= n <=
+// min(blockDim.x, kRankSelectMax); bc holds 4 words.
+constexpr int kRankSelectMax = 384;
+__device__ inline SelectResult wg_rank_select(int n, uint32_t k, const uint32_t *keys, uint32_t *bc) {
+  const int t = (int)threadIdx.x;
+  if (t < 4) bc[t] = 0u;
+  __syncthreads();  // the keys are in place
+  uint32_t mine = 0u, lt = 0xFFFFFFFFu;
+  if (t < n) {
+    mine = keys[t];
+    lt = 0u;
+    int j = 0;
+    for (; j + 4 <= n; j += 4) {
+      const uint4 o = *reinterpret_cast<const uint4 *>(keys + j);
+      lt += o.x < mine ? 1u : 0u;
+      lt += o.y < mine ? 1u : 0u;
+      lt += o.z < mine ? 1u : 0u;
+      lt += o.w < mine ? 1u : 0u;
+    }
+    for (; j < n; ++j) lt += keys[j] < mine ? 1u : 0u;
+  }
+  {  // the largest key with fewer than k keys below it
+    uint32_t c = lt < k ? mine : 0u;
+    for (int o = kWave / 2; o > 0; o >>= 1) c = max(c, (uint32_t)__shfl_xor((int)c, o));
+    if ((t & (kWave - 1)) == 0 && t < n) atomicMax(&bc[0], c);
+  }
+  __syncthreads();
+  const uint32_t T = bc[0];
+  {  // how many keys equal it, and how many of them belong to the k smallest
+    const bool is = t < n && mine == T;
+    const unsigned long long m = __ballot(is);
+    if (m && (t & (kWave - 1)) == __builtin_ctzll(m)) {
+      atomicAdd(&bc[2], (uint32_t)__popcll(m));
+      bc[1] = k - lt;  // the same value from every wavefront that holds such a key
+    }
+  }
+  __syncthreads();
+  const SelectResult r{(uint64_t)T, bc[1], bc[2]};
+  __syncthreads();  // bc may be reused
+  return r;
+}
+
 // Bitonic sort of m (power of two) entries in LDS by (k1, k2) ascending; pay is
 // carried along.  The first wavefront does all of it (LDS operations of one
 // wavefront execute in order, so the steps need no workgroup barrier); the
@@ -243,10 +289,21 @@ __device__ inline void wg_sort(int n, uint64_t *k1, uint64_t *k2, uint32_t *pay)
     a1 = k1[e]; a2 = k2[e]; ap = pay[e];
     const int per = (n + S - 1) / S;
     const int lo = s * per, hi = lo + per < n ? lo + per : n;
-    for (int j = lo; j < hi; ++j) {
-      const uint64_t b1 = k1[j], b2 = k2[j];
-      before += (b1 < a1 || (b1 == a1 && (b2 < a2 || (b2 == a2 && j < e)))) ? 1u : 0u;
+    // the second key is only looked at where the first ties; four first keys per round of LDS reads
+    auto count = [&](int j, uint64_t b1) {
+      if (b1 < a1) {
+        ++before;
+      } else if (b1 == a1) {
+        const uint64_t b2 = k2[j];
+        before += (b2 < a2 || (b2 == a2 && j < e)) ? 1u : 0u;
+      }
+    };
+    int j = lo;
+    for (; j + 4 <= hi; j += 4) {
+      const uint64_t b0 = k1[j], b1 = k1[j + 1], b2 = k1[j + 2], b3 = k1[j + 3];
+      count(j, b0); count(j + 1, b1); count(j + 2, b2); count(j + 3, b3);
     }
+    for (; j < hi; ++j) count(j, k1[j]);
   }
   for (int o = 1; o < S; o <<= 1) before += __shfl_xor(before, o);  // the S lanes of an entry are neighbours in one wavefront
   __syncthreads();  // everybody has read
@@ -393,6 +450,9 @@ inline ScanShape scan_shape(const Dev &D, int item_budget) {
   return sh;
 }
 
-constexpr int kGroupThreads = 1024;  // workgroup of the planning kernels (k_group, k_pq_bound)
+// Workgroup of the planning kernel (k_group).  Two of them fit a CU side by side, so that a request
+// of as many queries as the chip has CUs, with its two extra workgroups, still starts all at once
+// (with 1024 threads the last two waited for the first to finish: 17 us at 256 queries).
+constexpr int kGroupThreads = 512;
 
 }  // namespace rtams

@@ -25,21 +25,27 @@ struct SelectShared {
 };
 
 // Exact top-k among `count` items given by key(j) (32-bit score key) and
-// item(j) (candidate position, for the id lookup).  Leaves the winners sorted in
-// sh.k1 (score key), sh.k2 (id key), sh.pay (candidate position); returns how
+// item(j) (the candidate's place in the pool, for the id lookup).  Leaves the winners sorted in
+// sh.k1 (score key), sh.k2 (id key), sh.pay (place in the pool); returns how
 // many.  Candidates tied at the k-th score are told apart by id: their ids are
 // fetched once and ranked in LDS (with byte-valued data such ties are the rule,
 // a handful per query); only more ties than kTieCap go through a radix
 // selection over the ids.
+// `lds_keys`: where the keys lie if they lie in LDS (16-byte aligned), else NULL.
 template <typename KeyFn, typename ItemFn, typename IdFn>
-__device__ int select_topk(int count, int k, KeyFn key, ItemFn item, IdFn id_of, SelectShared &sh) {
+__device__ int select_topk(int count, int k, KeyFn key, ItemFn item, IdFn id_of, SelectShared &sh,
+                           const uint32_t *lds_keys) {
   auto key_of_id = [](int64_t id) -> uint64_t { return (uint64_t)id ^ 0x8000000000000000ull; };
   const int kk = k < count ? k : count;
   SelectResult r1{~0ull, 0, 0}, r2{~0ull, 0, 0};
   const bool all = count <= k;
-  if (!all)
-    r1 = wg_radix_select<32>(count, (uint32_t)k, [&](int j, uint64_t &kv) { kv = key(j); return true; },
-                             sh.hist, sh.bc);
+  if (!all) {
+    if (lds_keys && count <= kRankSelectMax)  // uniform over the workgroup
+      r1 = wg_rank_select(count, (uint32_t)k, lds_keys, sh.bc);
+    else
+      r1 = wg_radix_select<32>(count, (uint32_t)k, [&](int j, uint64_t &kv) { kv = key(j); return true; },
+                               sh.hist, sh.bc);
+  }
   const bool tie_break = !all && r1.c_eq > r1.need;  // not all of the candidates tied at the k-th score fit
   const bool in_lds = tie_break && r1.c_eq <= (uint32_t)kTieCap;
   if (tie_break && !in_lds)
@@ -97,6 +103,7 @@ __device__ int select_topk(int count, int k, KeyFn key, ItemFn item, IdFn id_of,
 }
 
 constexpr int kTopkThreads = 512;
+static_assert(kRankSelectMax <= kTopkThreads, "rank selection takes one key per thread");
 
 __device__ inline float score_of_key(uint32_t key, int metric) {
   const float x = __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
@@ -108,9 +115,7 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
                                                         float *__restrict__ out_dist,
                                                         int64_t *__restrict__ out_ids) {
   __shared__ SelectShared sh;
-  __shared__ uint32_t offs[kMaxNprobe];
-  __shared__ int32_t lists[kMaxNprobe];
-  __shared__ uint32_t skey[kSurvivorCap];
+  __shared__ __attribute__((aligned(16))) uint32_t skey[kSurvivorCap];
   __shared__ uint32_t sidx[kSurvivorCap];
   __shared__ uint32_t scount;
   const int q = blockIdx.x;
@@ -119,10 +124,6 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
   const uint32_t *rk = rec_keys_of(S, base), *rp = rec_poss_of(S, base);
   const int metric = D.metric;
   const int lane = threadIdx.x & (kWave - 1);
-  for (int p = threadIdx.x; p < nprobe; p += kTopkThreads) {
-    offs[p] = S.probe_off[(size_t)q * max_nprobe + p];
-    lists[p] = S.probe_list[(size_t)q * max_nprobe + p];
-  }
   if (threadIdx.x == 0) scount = 0;
   __syncthreads();
 
@@ -177,18 +178,41 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
   bool in_lds = true;
   __shared__ uint32_t s_over;
   int stretch = 1;  // portions as a multiple of the room in LDS
+  // More records than LDS holds (the query's bound was loose: its sample did not look like its
+  // candidates): a first limit comes from a pilot, every (n / kPilot)-th record, so that the
+  // records are filtered from the first portion on instead of filling LDS once unfiltered.
+  constexpr int kPilot = 1024;
+  if (n > kSurvivorCap && k <= kPilot) {  // uniform over the workgroup
+    const int stride = n / kPilot;
+    for (int j = threadIdx.x; j < kPilot; j += kTopkThreads) skey[j] = rk[(size_t)j * stride];
+    __syncthreads();
+    const SelectResult r = wg_radix_select<32>(
+        kPilot, (uint32_t)k, [&](int j, uint64_t &kv) { kv = skey[j]; return true; }, sh.hist, sh.bc);
+    const uint32_t lim = limit_from((uint32_t)r.T);
+    limit = lim < limit ? lim : limit;
+    stretch = 4;
+    __syncthreads();  // the pilot's keys are done with
+  }
   for (int next = 0; next < n;) {  // every branch here is uniform over the workgroup
     const int count = (int)scount;
     const int m = min(n - next, stretch * (kSurvivorCap - count));
     if (threadIdx.x == 0) s_over = 0;
     __syncthreads();
-    constexpr int kInFlight = 32;  // independent loads per thread: 16,384 keys per round trip to memory
+    // Independent loads per thread (keys and positions, 16 each): 8,192 records per round trip to memory.  The positions come with
+    // the keys whether their record passes or not: a load inside the loop below, for the records
+    // that pass, would make every turn of it a round trip of its own.
+    constexpr int kInFlight = 16;
     for (int j0 = 0; j0 < m; j0 += kInFlight * kTopkThreads) {
-      uint32_t kv[kInFlight];
+      uint32_t kv[kInFlight], pv[kInFlight];
 #pragma unroll
       for (int u = 0; u < kInFlight; ++u) {  // clamped index: the loads are unconditional and issue back to back
         const int j = j0 + u * kTopkThreads + (int)threadIdx.x;
         kv[u] = rk[next + (j < m ? j : m - 1)];
+      }
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u) {
+        const int j = j0 + u * kTopkThreads + (int)threadIdx.x;
+        pv[u] = rp[next + (j < m ? j : m - 1)];
       }
 #pragma unroll
       for (int u = 0; u < kInFlight; ++u) {
@@ -201,7 +225,7 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
           at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
           if (keep) {
             const uint32_t slot = at + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-            if (slot < (uint32_t)kSurvivorCap) { skey[slot] = kv[u]; sidx[slot] = rp[next + j]; }
+            if (slot < (uint32_t)kSurvivorCap) { skey[slot] = kv[u]; sidx[slot] = pv[u]; }
             else s_over = 1u;
           }
         }
@@ -233,27 +257,21 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
     stretch = over ? 1 : 4;
   }
 
-  // candidate position -> which probed list (last offset <= position), which place, which block
+  // a record's place in the pool (slot_of) -> which block, which place in it
   auto locate = [&](int i, uint32_t &b, uint32_t &moff) {
-    int lo = 0, hi = nprobe - 1;
-    while (lo < hi) {
-      int mid = (lo + hi + 1) >> 1;
-      if (offs[mid] <= (uint32_t)i) lo = mid; else hi = mid - 1;
-    }
-    const uint32_t pos = (uint32_t)i - offs[lo];
-    b = (uint32_t)*table_entry(D, lists[lo], pos / (uint32_t)D.T_m);
-    moff = pos % (uint32_t)D.T_m;
+    b = (uint32_t)i / (uint32_t)D.T_m;
+    moff = (uint32_t)i - b * (uint32_t)D.T_m;
   };
   auto id_of = [&](int i) -> int64_t {
     uint32_t b, moff;
     locate(i, b, moff);
     return block_ids(D, b)[moff];
   };
-  // candidate position -> key of its direct-form squared distance.  Four neighbouring lanes share
+  // place in the pool -> key of the candidate's direct-form squared distance.  Four neighbouring lanes share
   // a candidate (a vector's chunks of 4 dimensions lie 1 KiB apart: every chunk is a memory
   // transaction of its own, and this way all of them are in flight at once): lane s of the four
   // takes chunks s, s + 4, ..., and the four partial sums are added pairwise.  All four lanes call
-  // this with the same position and get the key.
+  // this with the same place and get the key.
   auto direct_key = [&](int i, int64_t *id) -> uint32_t {
     uint32_t b, moff;
     locate(i, b, moff);
@@ -276,6 +294,45 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
     acc += __shfl_xor(acc, 2);
     return key_of_float(acc + 0.0f);
   };
+  // The same for two candidates at once: both block look-ups go out together, then all the chunks of
+  // both (a candidate is a chain of two round trips to memory; two of them side by side cost one).
+  auto direct_key_pair = [&](int ia, int ib, int64_t *ida, int64_t *idb, uint32_t &ka, uint32_t &kb) {
+    uint32_t ba, ma, bb, mb;
+    locate(ia, ba, ma);
+    locate(ib, bb, mb);
+    const int sub = (int)(threadIdx.x & 3u);
+    if (sub == 0) {
+      *ida = block_ids(D, ba)[ma];
+      *idb = block_ids(D, bb)[mb];
+    }
+    const float4 *__restrict__ xa = block_vecs(D, ba) + (size_t)(ma / kWave) * D.d4 * kWave + (ma & (kWave - 1));
+    const float4 *__restrict__ xb = block_vecs(D, bb) + (size_t)(mb / kWave) * D.d4 * kWave + (mb & (kWave - 1));
+    const float4 *__restrict__ y = reinterpret_cast<const float4 *>(Q + (size_t)q * D.d);
+    float acca = 0.f, accb = 0.f;
+    int c = sub;
+    for (; c + 28 < D.d4; c += 32) {
+      float4 va[8], vb[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) va[u] = xa[(size_t)(c + 4 * u) * kWave];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) vb[u] = xb[(size_t)(c + 4 * u) * kWave];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) accumulate<0>(acca, va[u], y[c + 4 * u]);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) accumulate<0>(accb, vb[u], y[c + 4 * u]);
+    }
+    for (; c < D.d4; c += 4) {
+      const float4 va = xa[(size_t)c * kWave], vb = xb[(size_t)c * kWave];
+      accumulate<0>(acca, va, y[c]);
+      accumulate<0>(accb, vb, y[c]);
+    }
+    acca += __shfl_xor(acca, 1);
+    acca += __shfl_xor(acca, 2);
+    accb += __shfl_xor(accb, 1);
+    accb += __shfl_xor(accb, 2);
+    ka = key_of_float(acca + 0.0f);
+    kb = key_of_float(accb + 0.0f);
+  };
   int kk = -1;
   if (approx && in_lds) {  // uniform over the workgroup
     // The usual case: the finalists (every record that may be among the k best by direct-form
@@ -284,8 +341,11 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
     const int have = (int)scount;
     uint32_t lim = 0xFFFFFFFFu;
     if (have > k) {
-      const SelectResult r = wg_radix_select<32>(
-          have, (uint32_t)k, [&](int j, uint64_t &kv) { kv = skey[j]; return true; }, sh.hist, sh.bc);
+      const SelectResult r =
+          have <= kRankSelectMax
+              ? wg_rank_select(have, (uint32_t)k, skey, sh.bc)
+              : wg_radix_select<32>(
+                    have, (uint32_t)k, [&](int j, uint64_t &kv) { kv = skey[j]; return true; }, sh.hist, sh.bc);
       lim = limit_from((uint32_t)r.T);
       limit = lim < limit ? lim : limit;
     }
@@ -299,13 +359,27 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
     __syncthreads();
     const int m = (int)sh.cnt[0];
     if (m <= kMaxK) {
-      for (int p0 = 0; p0 < m; p0 += kTopkThreads / 4) {  // uniform trip count: the lanes of a four stay together
+      constexpr int kFours = kTopkThreads / 4;
+      for (int p0 = 0; p0 < m;) {  // uniform trip count: the lanes of a four stay together
         const int p = p0 + (int)(threadIdx.x >> 2);
-        int64_t id = 0;
-        const uint32_t key = direct_key((int)sh.pay[p < m ? p : m - 1], &id);
-        if (p < m && (threadIdx.x & 3u) == 0) {
-          sh.k1[p] = key;
-          sh.k2[p] = (uint64_t)id ^ 0x8000000000000000ull;
+        if (m - p0 > kFours) {  // uniform: every four takes two finalists, p and p + kFours
+          const int p2 = p + kFours;
+          int64_t id = 0, id2 = 0;
+          uint32_t key, key2;
+          direct_key_pair((int)sh.pay[p < m ? p : m - 1], (int)sh.pay[p2 < m ? p2 : m - 1], &id, &id2, key, key2);
+          if ((threadIdx.x & 3u) == 0) {
+            if (p < m) { sh.k1[p] = key; sh.k2[p] = (uint64_t)id ^ 0x8000000000000000ull; }
+            if (p2 < m) { sh.k1[p2] = key2; sh.k2[p2] = (uint64_t)id2 ^ 0x8000000000000000ull; }
+          }
+          p0 += 2 * kFours;
+        } else {
+          int64_t id = 0;
+          const uint32_t key = direct_key((int)sh.pay[p < m ? p : m - 1], &id);
+          if (p < m && (threadIdx.x & 3u) == 0) {
+            sh.k1[p] = key;
+            sh.k2[p] = (uint64_t)id ^ 0x8000000000000000ull;
+          }
+          p0 += kFours;
         }
       }
       wg_sort(m, sh.k1, sh.k2, sh.pay);
@@ -343,9 +417,9 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
   if (kk < 0) {
     if (in_lds)
       kk = select_topk((int)scount, k, [&](int j) { return skey[j]; }, [&](int j) { return (int)sidx[j]; },
-                       id_of, sh);
+                       id_of, sh, skey);
     else
-      kk = select_topk(n, k, [&](int j) { return rk[j]; }, [&](int j) { return (int)rp[j]; }, id_of, sh);
+      kk = select_topk(n, k, [&](int j) { return rk[j]; }, [&](int j) { return (int)rp[j]; }, id_of, sh, nullptr);
   }
 
   for (int r = threadIdx.x; r < k; r += kTopkThreads) {
