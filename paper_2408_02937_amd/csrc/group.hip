@@ -264,7 +264,10 @@ __device__ inline void wg_scan3(uint32_t &a, uint32_t &b, unsigned long long &c,
 // (query, probe) pairs that probe the list, each at the rank the plan gave it.  One workgroup, beside
 // the one that cuts the work items (both derive the same pair starts from the same counters: a
 // running sum of the pair counts over the lists, a row of consecutive lists per thread at a time, 16 rows in flight).
-__device__ void scatter_pairs(const Dev &D, int nq, int nprobe, int max_nprobe, const SearchScratch &S) {
+// Several workgroups may share the pairs (part `part` of `parts`): each derives all the starts (every
+// one of them writes the same numbers to pair_start) and places its own share of the pairs.
+__device__ void scatter_pairs(const Dev &D, int nq, int nprobe, int max_nprobe, const SearchScratch &S, int part,
+                              int parts) {
   constexpr int kWavesG = kGroupThreads / kWave;
   __shared__ uint32_t s_tot[kListChunk * kWavesG + 1];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
@@ -314,8 +317,10 @@ __device__ void scatter_pairs(const Dev &D, int nq, int nprobe, int max_nprobe, 
     __syncthreads();  // the totals are reused by the next rows; the starts are read below by other threads
   }
   // eight independent chains of loads per thread
-  const int npairs = nq * nprobe;
-  for (int base = tid; base < npairs; base += 8 * kGroupThreads) {
+  const int npairs_all = nq * nprobe;
+  const int share = (npairs_all + parts - 1) / parts;
+  const int npairs = min(npairs_all, (part + 1) * share);
+  for (int base = part * share + tid; base < npairs; base += 8 * kGroupThreads) {
     int l[8];
     uint32_t slot[8], pk[8];
 #pragma unroll
@@ -340,20 +345,21 @@ __device__ void scatter_pairs(const Dev &D, int nq, int nprobe, int max_nprobe, 
   }
 }
 
-__global__ __launch_bounds__(kGroupThreads) void k_group(Dev D, int nq, int nprobe, int max_nprobe, int k,
+__global__ __launch_bounds__(kGroupThreads, 4) void k_group(Dev D, int nq, int nprobe, int max_nprobe, int k,
                                                          const float *__restrict__ Q,
                                                          uint32_t item_budget, uint32_t max_per_xcd,
-                                                         uint32_t tile_q, int min_choice, SearchScratch S) {
+                                                         uint32_t tile_q, int min_choice, int scatterers,
+                                                         SearchScratch S) {
   const int tile_shift = 31 - __clz((int)tile_q);  // tiles hold a power of two of queries
-  if (blockIdx.x == 1) {  // uniform over the workgroup: this one groups the pairs by list
-    scatter_pairs(D, nq, nprobe, max_nprobe, S);
+  if (blockIdx.x >= 1 && (int)blockIdx.x <= scatterers) {  // uniform over the workgroup: these group the pairs by list
+    scatter_pairs(D, nq, nprobe, max_nprobe, S, (int)blockIdx.x - 1, scatterers);
     return;
   }
   // the bound's query and sample keys, or the entries of the probed lists of a small request
   __shared__ __attribute__((aligned(16))) unsigned char s_raw[kBoundLdsBytes];
   static_assert(kBoundLdsBytes >= kLdsEntries * (sizeof(uint4) + sizeof(uint32_t)), "the entries share the bound's LDS");
-  if (blockIdx.x > 1) {  // this one sets the bound of query blockIdx.x - 2
-    sample_bound<false>(D, (int)blockIdx.x - 2, nprobe, max_nprobe, k, Q, S, s_raw);
+  if (blockIdx.x > 0) {  // this one sets the bound of a query
+    sample_bound<false>(D, (int)blockIdx.x - 1 - scatterers, nprobe, max_nprobe, k, Q, S, s_raw);
     return;
   }
   __shared__ uint32_t s_a[kGroupThreads];
@@ -715,11 +721,15 @@ void launch_group(const Dev &D, int64_t nq, int nprobe, int max_nprobe, int k, c
     hipLaunchKernelGGL(k_pq_bound, dim3((unsigned)nq), dim3(kPqBoundThreads), 0, s, D, nprobe, max_nprobe, k, Q, S);
     return;
   }
-  // workgroup 0 cuts the work items, workgroup 1 groups the pairs, workgroup 2 + q sets the bound of query q
+  // workgroup 0 cuts the work items, the next few group the pairs (one for every 2048 pairs, at most 8:
+  // placing a pair is a chain of three round trips to memory), the others set the bound of a query each
   const ScanShape sh = scan_shape(D, item_budget);
-  hipLaunchKernelGGL(k_group, dim3(2 + (unsigned)nq), dim3(kGroupThreads), 0, s, D, (int)nq, nprobe,
-                     max_nprobe, k, Q, (uint32_t)item_budget,
-                     (uint32_t)(sh.grid / (int)kXcds * sh.items_per_wg), (uint32_t)sh.tile_q, sh.min_choice, S);
+  const int64_t pairs = nq * nprobe;
+  const int scatterers = (int)(pairs <= 2048 ? 1 : pairs >= 8 * 2048 ? 8 : (pairs + 2047) / 2048);
+  hipLaunchKernelGGL(k_group, dim3(1 + (unsigned)scatterers + (unsigned)nq), dim3(kGroupThreads), 0, s, D, (int)nq,
+                     nprobe, max_nprobe, k, Q, (uint32_t)item_budget,
+                     (uint32_t)(sh.grid / (int)kXcds * sh.items_per_wg), (uint32_t)sh.tile_q, sh.min_choice,
+                     scatterers, S);
 }
 
 }  // namespace rtams

@@ -182,52 +182,6 @@ __device__ SelectResult wg_radix_select(int n, uint32_t k, Fn fn, uint32_t *hist
   return wg_radix_select_each<BITS>(k, each, hist, bc);
 }
 
-// The same for a few hundred 32-bit keys that lie in LDS (16-byte aligned), one per thread: a thread
-// counts the keys below its own (four keys per LDS read, which the whole wavefront shares; a compare
-// and an add per key); the k-th smallest key T is the largest key with fewer than k keys below it.
-// Three barriers where the radix passes take a dozen, but the work grows with the square of n: it
-// pays up to kRankSelectMax keys.  T is the k-th smallest key itself.  Requires 1 <= k <= n <=
-// min(blockDim.x, kRankSelectMax); bc holds 4 words.
-constexpr int kRankSelectMax = 384;
-__device__ inline SelectResult wg_rank_select(int n, uint32_t k, const uint32_t *keys, uint32_t *bc) {
-  const int t = (int)threadIdx.x;
-  if (t < 4) bc[t] = 0u;
-  __syncthreads();  // the keys are in place
-  uint32_t mine = 0u, lt = 0xFFFFFFFFu;
-  if (t < n) {
-    mine = keys[t];
-    lt = 0u;
-    int j = 0;
-    for (; j + 4 <= n; j += 4) {
-      const uint4 o = *reinterpret_cast<const uint4 *>(keys + j);
-      lt += o.x < mine ? 1u : 0u;
-      lt += o.y < mine ? 1u : 0u;
-      lt += o.z < mine ? 1u : 0u;
-      lt += o.w < mine ? 1u : 0u;
-    }
-    for (; j < n; ++j) lt += keys[j] < mine ? 1u : 0u;
-  }
-  {  // the largest key with fewer than k keys below it
-    uint32_t c = lt < k ? mine : 0u;
-    for (int o = kWave / 2; o > 0; o >>= 1) c = max(c, (uint32_t)__shfl_xor((int)c, o));
-    if ((t & (kWave - 1)) == 0 && t < n) atomicMax(&bc[0], c);
-  }
-  __syncthreads();
-  const uint32_t T = bc[0];
-  {  // how many keys equal it, and how many of them belong to the k smallest
-    const bool is = t < n && mine == T;
-    const unsigned long long m = __ballot(is);
-    if (m && (t & (kWave - 1)) == __builtin_ctzll(m)) {
-      atomicAdd(&bc[2], (uint32_t)__popcll(m));
-      bc[1] = k - lt;  // the same value from every wavefront that holds such a key
-    }
-  }
-  __syncthreads();
-  const SelectResult r{(uint64_t)T, bc[1], bc[2]};
-  __syncthreads();  // bc may be reused
-  return r;
-}
-
 // Bitonic sort of m (power of two) entries in LDS by (k1, k2) ascending; pay is
 // carried along.  The first wavefront does all of it (LDS operations of one
 // wavefront execute in order, so the steps need no workgroup barrier); the

@@ -31,21 +31,15 @@ struct SelectShared {
 // fetched once and ranked in LDS (with byte-valued data such ties are the rule,
 // a handful per query); only more ties than kTieCap go through a radix
 // selection over the ids.
-// `lds_keys`: where the keys lie if they lie in LDS (16-byte aligned), else NULL.
 template <typename KeyFn, typename ItemFn, typename IdFn>
-__device__ int select_topk(int count, int k, KeyFn key, ItemFn item, IdFn id_of, SelectShared &sh,
-                           const uint32_t *lds_keys) {
+__device__ int select_topk(int count, int k, KeyFn key, ItemFn item, IdFn id_of, SelectShared &sh) {
   auto key_of_id = [](int64_t id) -> uint64_t { return (uint64_t)id ^ 0x8000000000000000ull; };
   const int kk = k < count ? k : count;
   SelectResult r1{~0ull, 0, 0}, r2{~0ull, 0, 0};
   const bool all = count <= k;
-  if (!all) {
-    if (lds_keys && count <= kRankSelectMax)  // uniform over the workgroup
-      r1 = wg_rank_select(count, (uint32_t)k, lds_keys, sh.bc);
-    else
-      r1 = wg_radix_select<32>(count, (uint32_t)k, [&](int j, uint64_t &kv) { kv = key(j); return true; },
-                               sh.hist, sh.bc);
-  }
+  if (!all)
+    r1 = wg_radix_select<32>(count, (uint32_t)k, [&](int j, uint64_t &kv) { kv = key(j); return true; },
+                             sh.hist, sh.bc);
   const bool tie_break = !all && r1.c_eq > r1.need;  // not all of the candidates tied at the k-th score fit
   const bool in_lds = tie_break && r1.c_eq <= (uint32_t)kTieCap;
   if (tie_break && !in_lds)
@@ -103,7 +97,6 @@ __device__ int select_topk(int count, int k, KeyFn key, ItemFn item, IdFn id_of,
 }
 
 constexpr int kTopkThreads = 512;
-static_assert(kRankSelectMax <= kTopkThreads, "rank selection takes one key per thread");
 
 __device__ inline float score_of_key(uint32_t key, int metric) {
   const float x = __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
@@ -115,7 +108,7 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
                                                         float *__restrict__ out_dist,
                                                         int64_t *__restrict__ out_ids) {
   __shared__ SelectShared sh;
-  __shared__ __attribute__((aligned(16))) uint32_t skey[kSurvivorCap];
+  __shared__ uint32_t skey[kSurvivorCap];
   __shared__ uint32_t sidx[kSurvivorCap];
   __shared__ uint32_t scount;
   const int q = blockIdx.x;
@@ -341,11 +334,8 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
     const int have = (int)scount;
     uint32_t lim = 0xFFFFFFFFu;
     if (have > k) {
-      const SelectResult r =
-          have <= kRankSelectMax
-              ? wg_rank_select(have, (uint32_t)k, skey, sh.bc)
-              : wg_radix_select<32>(
-                    have, (uint32_t)k, [&](int j, uint64_t &kv) { kv = skey[j]; return true; }, sh.hist, sh.bc);
+      const SelectResult r = wg_radix_select<32>(
+          have, (uint32_t)k, [&](int j, uint64_t &kv) { kv = skey[j]; return true; }, sh.hist, sh.bc);
       lim = limit_from((uint32_t)r.T);
       limit = lim < limit ? lim : limit;
     }
@@ -417,9 +407,9 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
   if (kk < 0) {
     if (in_lds)
       kk = select_topk((int)scount, k, [&](int j) { return skey[j]; }, [&](int j) { return (int)sidx[j]; },
-                       id_of, sh, skey);
+                       id_of, sh);
     else
-      kk = select_topk(n, k, [&](int j) { return rk[j]; }, [&](int j) { return (int)rp[j]; }, id_of, sh, nullptr);
+      kk = select_topk(n, k, [&](int j) { return rk[j]; }, [&](int j) { return (int)rp[j]; }, id_of, sh);
   }
 
   for (int r = threadIdx.x; r < k; r += kTopkThreads) {
