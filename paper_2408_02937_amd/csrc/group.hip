@@ -144,7 +144,7 @@ __device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, in
                              const SearchScratch &S, unsigned char *lds) {
   float4 *qv = reinterpret_cast<float4 *>(lds);
   uint32_t *skey = reinterpret_cast<uint32_t *>(lds + 512 * sizeof(float4));
-  __shared__ __attribute__((aligned(8))) uint32_t hist[256];
+  __shared__ __attribute__((aligned(8))) uint32_t hist[kSelectLdsWords];
   __shared__ uint32_t bc[4];
   const int tid = threadIdx.x;
   // |q|^2 for the norm form of the squared distance (the first wavefront computes it, in double)

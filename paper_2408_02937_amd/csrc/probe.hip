@@ -21,7 +21,7 @@ template <bool FROM_APPROX>
 __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, int max_nprobe,
                                                             SearchScratch S, const float *__restrict__ Q,
                                                             int32_t *probe_out) {
-  __shared__ __attribute__((aligned(8))) uint32_t hist[256];  // also holds two 64-bit words for a moment
+  __shared__ __attribute__((aligned(8))) uint32_t hist[kSelectLdsWords];
   __shared__ uint32_t bc[4];
   __shared__ uint32_t cnt[2];
   __shared__ uint64_t k1[kMaxNprobe];

@@ -2,6 +2,7 @@
 // lie, workgroup-wide selection and sorting in LDS, the fp32 score of a vector against a query,
 // and the launch shape of the list scan (the planning kernel needs it as well).
 #pragma once
+#include <type_traits>
 #include "rtams_launch.h"
 
 namespace rtams {
@@ -103,60 +104,78 @@ __device__ inline void wg_pick_bin(const uint32_t *hist, uint32_t need, uint32_t
     __syncthreads();
 }
 
-// `each(body)` calls body(key) for every key of the calling thread that takes part.
+// LDS of a selection: two histograms of 256 bins (while one is filled the other is cleared for the
+// next pass) and a slot of two 64-bit words per wavefront for the range of the keys.
+constexpr int kSelectLdsWords = 2 * 256 + 4 * 16;
+
+// `each(body)` calls body(key) for every key of the calling thread that takes part.  `hist` holds
+// kSelectLdsWords words, 8-byte aligned; the workgroup has at most 16 wavefronts.
 template <int BITS, typename Each>
 __device__ SelectResult wg_radix_select_each(uint32_t k, Each each, uint32_t *hist, uint32_t *bc) {
-  // Leading digits on which every key agrees are skipped: scores of one query's
-  // candidates share sign, exponent and often the first mantissa bits, and a
-  // histogram pass in which all lanes hit one LDS word serialises completely.
-  unsigned long long *mm = reinterpret_cast<unsigned long long *>(hist);  // {min, max} for a moment
-  if (threadIdx.x == 0) { mm[0] = ~0ull; mm[1] = 0ull; }
-  __syncthreads();
+  typedef typename std::conditional<BITS == 32, unsigned int, unsigned long long>::type Key;  // what the range is reduced in
+  // The first digit is the 8 bits that end at the highest bit in which any two keys differ: scores
+  // of one query's candidates share sign, exponent and often the first mantissa bits; digits on
+  // which every key agrees would make all lanes hit one LDS word (which serialises completely) and
+  // decide nothing, and a first digit cut out at a byte boundary often tells only a handful of
+  // bins apart.  This way the first pass uses all 256 bins, and a few hundred keys are usually
+  // done after one or two.
+  uint64_t *range = reinterpret_cast<uint64_t *>(hist + 512);  // per wavefront: {min, max}
+  const int lane = (int)(threadIdx.x & (kWave - 1)), wave = (int)(threadIdx.x / kWave);
+  __syncthreads();  // whatever used this LDS before is done
+  for (int b = threadIdx.x; b < 256; b += blockDim.x) hist[b] = 0;
   {
-    unsigned long long lo = ~0ull, hi = 0ull;
-    each([&](uint64_t key) { lo = key < lo ? key : lo; hi = key > hi ? key : hi; });
+    Key lo = ~(Key)0, hi = 0;
+    each([&](uint64_t key) { lo = (Key)key < lo ? (Key)key : lo; hi = (Key)key > hi ? (Key)key : hi; });
     for (int o = kWave / 2; o > 0; o >>= 1) {
-      const unsigned long long a = __shfl_xor(lo, o), b = __shfl_xor(hi, o);
+      const Key a = __shfl_xor(lo, o), b = __shfl_xor(hi, o);
       lo = a < lo ? a : lo;
       hi = b > hi ? b : hi;
     }
-    if ((threadIdx.x & (kWave - 1)) == 0) { atomicMin(&mm[0], lo); atomicMax(&mm[1], hi); }
+    if (lane == 0) { range[2 * wave] = (uint64_t)lo; range[2 * wave + 1] = (uint64_t)hi; }
   }
   __syncthreads();
-  const uint64_t kmin = mm[0], kmax = mm[1];
-  __syncthreads();  // hist is reused below
-  int first_shift = BITS - 8;
+  uint64_t kmin = ~0ull, kmax = 0ull;
+  for (int w = 0; w < (int)(blockDim.x / kWave); ++w) {
+    const uint64_t a = range[2 * w], b = range[2 * w + 1];
+    kmin = a < kmin ? a : kmin;
+    kmax = b > kmax ? b : kmax;
+  }
+  int shift = 0;
   uint64_t prefix = 0, mask = 0;
   {
     const uint64_t diff = kmin ^ kmax;
     const int top = diff ? 63 - __clzll((long long)diff) : -1;  // highest bit in which keys differ
-    first_shift = top < 0 ? 0 : (top / 8) * 8;
-    if (first_shift > BITS - 8) first_shift = BITS - 8;
-    if (first_shift + 8 < 64) {
-      mask = ~0ull << (first_shift + 8);
+    shift = top < 7 ? 0 : top - 7;
+    if (shift > BITS - 8) shift = BITS - 8;
+    if (shift + 8 < 64) {
+      mask = ~0ull << (shift + 8);
       if (BITS < 64) mask &= (1ull << BITS) - 1ull;
     }
     prefix = kmax & mask;
   }
   uint32_t need = k, c_eq = 0;
-  for (int shift = first_shift; shift >= 0; shift -= 8) {
-    for (int b = threadIdx.x; b < 256; b += blockDim.x) hist[b] = 0;
-    __syncthreads();
+  uint32_t *cur = hist, *other = hist + 256;
+  for (;;) {
     each([&](uint64_t key) {
-      if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & 255u], 1u);
+      if ((key & mask) == prefix) atomicAdd(&cur[(uint32_t)(key >> shift) & 255u], 1u);
     });
+    for (int b = threadIdx.x; b < 256; b += blockDim.x) other[b] = 0;  // for the next pass; last read before the previous barrier
     __syncthreads();
-    wg_pick_bin(hist, need, bc);
-    uint32_t dg = bc[0];
+    wg_pick_bin(cur, need, bc);  // ends with a barrier
+    const uint32_t dg = bc[0];  // (bc is written again only behind the next barrier)
     need -= bc[1];
     c_eq = bc[2];
+    // A digit that overlaps the one before it (the last one, when fewer than 8 bits were left) repeats
+    // bits the prefix already holds: only keys that match the prefix were counted, so they agree.
     prefix |= (uint64_t)dg << shift;
     mask |= (uint64_t)255u << shift;
-    __syncthreads();
     if (c_eq == need) {  // the whole bin belongs to the k smallest: the lower digits cannot matter
       if (shift > 0) prefix |= (1ull << shift) - 1ull;  // threshold = largest key of the bin
       break;
     }
+    if (shift == 0) break;
+    shift = shift >= 8 ? shift - 8 : 0;
+    uint32_t *t = cur; cur = other; other = t;
   }
   return {prefix, need, c_eq};
 }

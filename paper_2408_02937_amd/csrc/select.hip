@@ -14,7 +14,7 @@ constexpr int kSurvivorCap = 4096;
 constexpr int kTieCap = 1024;  // candidates tied at the k-th score that are told apart in LDS
 
 struct SelectShared {
-  __attribute__((aligned(8))) uint32_t hist[256];  // also holds two 64-bit words for a moment
+  __attribute__((aligned(8))) uint32_t hist[kSelectLdsWords];
   uint32_t bc[4];
   uint32_t cnt[2];
   uint64_t k1[kMaxK];
