@@ -22,10 +22,19 @@ constexpr int kNoBoundBelow = 4096;  // candidates of a query up to which the sc
 // group of 64 vectors, lane = vector, scores to LDS, radix selection there.
 // These workgroups run beside the one that groups the pairs (same launch): both
 // need only the plan, and the scan needs both.
+// What the sample needs of the nearest list, read ahead by the caller (every one of these is a round
+// trip to memory, and read where they are used they would follow one another): the list, its
+// length, its number of blocks, and where the table segment of this wavefront's first group starts.
+struct NearestList {
+  int list;
+  uint32_t len, nblk;
+  int32_t dir;
+};
+
 template <int METRIC, int ST>
 __device__ void sample_scores(const Dev &D, int nprobe, int max_nprobe, int q, uint32_t want_groups,
                               const float *__restrict__ Q, const SearchScratch &S, const float4 *qv,
-                              uint32_t *skey) {
+                              uint32_t *skey, const NearestList &first) {
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int d4 = D.vchunks;  // 16-byte chunks of a stored vector
   constexpr int kPieces = pieces_of(ST);  // float4s of the query that go with a chunk
@@ -35,14 +44,15 @@ __device__ void sample_scores(const Dev &D, int nprobe, int max_nprobe, int q, u
   uint32_t g_first = 0;  // groups of the lists before list p
   for (int p = 0; p < nprobe && g_first < want_groups; ++p) {  // uniform over the workgroup
     const size_t o = (size_t)q * max_nprobe + p;
-    const int list = S.probe_list[o];
-    const uint32_t len = S.probe_len[o];
+    const int list = p == 0 ? first.list : S.probe_list[o];
+    const uint32_t len = p == 0 ? first.len : S.probe_len[o];
     uint32_t groups = (len + kWave - 1) / kWave;
-    const uint32_t have = D.nblk[list] * gpb;  // never index the block table past the chain
+    const uint32_t have = (p == 0 ? first.nblk : D.nblk[list]) * gpb;  // never index the block table past the chain
     if (groups > have) groups = have;
     if (groups > want_groups - g_first) groups = want_groups - g_first;
     for (uint32_t g = (uint32_t)wave; g < groups; g += blockDim.x / kWave) {
-      const uint32_t b = (uint32_t)*table_entry(D, list, g / gpb);
+      const uint32_t b = p == 0 && g == (uint32_t)wave ? (uint32_t)*table_entry_at(D, first.dir, g / gpb)
+                                                       : (uint32_t)*table_entry(D, list, g / gpb);
       const float4 *__restrict__ x = block_vecs(D, b) + (size_t)(g % gpb) * group_stride + lane;
       float acc = 0.f;
       int c = 0;
@@ -147,6 +157,10 @@ __device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, in
   __shared__ __attribute__((aligned(8))) uint32_t hist[kSelectLdsWords];
   __shared__ uint32_t bc[4];
   const int tid = threadIdx.x;
+  // what decides how the workgroup goes on, all on its way at once
+  const size_t o0 = (size_t)q * max_nprobe;
+  const uint32_t qtotal = S.qtotal[q];
+  NearestList first{PQ ? 0 : S.probe_list[o0], S.probe_len[o0], 0u, 0};
   // |q|^2 for the norm form of the squared distance (the first wavefront computes it, in double)
   const bool norm_form = !PQ && uses_norm_form(D);
   __shared__ float s_qn;
@@ -165,7 +179,7 @@ __device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, in
   // vectors).  (For L2 the bound also lets the scan stop early, which is worth the sample.)
   const uint32_t no_bound_below =
       D.metric == 0 ? (uint32_t)kNoBoundBelow : max((uint32_t)kNoBoundBelow, 32u * (uint32_t)D.d);
-  if (S.qtotal[q] <= no_bound_below) {  // uniform over the workgroup
+  if (qtotal <= no_bound_below) {  // uniform over the workgroup
     if (tid == 0) {
       S.bound[q] = 0xFFFFFFFFu;
       S.rec_cnt[q] = 0u;
@@ -179,7 +193,11 @@ __device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, in
   uint32_t cap = PQ ? (uint32_t)kSampleMax : ((1u << 20) / ((uint32_t)D.vchunks * 16u)) & ~(uint32_t)(kWave - 1);
   cap = cap < 512u ? 512u : (cap > (uint32_t)kSampleMax ? (uint32_t)kSampleMax : cap);
   uint32_t want = (uint32_t)k * 4u;
-  const uint32_t part = S.probe_len[(size_t)q * max_nprobe] / (uint32_t)kSampleDivisor;
+  const uint32_t part = first.len / (uint32_t)kSampleDivisor;
+  if (!PQ) {  // on their way while the query and the keys are set up
+    first.nblk = D.nblk[first.list];
+    first.dir = table_dir(D, first.list, (uint32_t)(tid / kWave) / (uint32_t)D.groups_per_block);
+  }
   want = want < part ? part : want;
   want = want < 512u ? 512u : (want > cap ? cap : want);
   const uint32_t want_groups = (want + kWave - 1) / kWave;
@@ -189,13 +207,13 @@ __device__ void sample_bound(const Dev &D, int q, int nprobe, int max_nprobe, in
   __syncthreads();
   if (PQ) pq_sample_scores(D, nprobe, max_nprobe, q, want_groups, S, skey);
   else if (D.metric == 0) {
-    if (D.storage == 1) sample_scores<0, 1>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
-    else if (D.storage == 2) sample_scores<0, 2>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
-    else sample_scores<0, 0>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
+    if (D.storage == 1) sample_scores<0, 1>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey, first);
+    else if (D.storage == 2) sample_scores<0, 2>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey, first);
+    else sample_scores<0, 0>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey, first);
   } else {
-    if (D.storage == 1) sample_scores<1, 1>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
-    else if (D.storage == 2) sample_scores<1, 2>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
-    else sample_scores<1, 0>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey);
+    if (D.storage == 1) sample_scores<1, 1>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey, first);
+    else if (D.storage == 2) sample_scores<1, 2>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey, first);
+    else sample_scores<1, 0>(D, nprobe, max_nprobe, q, want_groups, Q, S, qv, skey, first);
   }
   __syncthreads();
   // k-th smallest key of the sample; with fewer than k candidates in it, it is the worst key

@@ -111,6 +111,15 @@ __device__ inline int32_t *table_entry(const Dev &D, int list, uint32_t i) {
   int32_t off = D.seg_dir[(size_t)list * kTableSegs + s];
   return D.slab + off + (i - table_seg_first(s));
 }
+// The same in its two dependent steps, for callers that want the first on its way early: where the
+// table segment of entry i starts (the word exists for every list and segment), then the entry
+// (which exists only below the list's number of blocks).
+__device__ inline int32_t table_dir(const Dev &D, int list, uint32_t i) {
+  return D.seg_dir[(size_t)list * kTableSegs + table_seg(i)];
+}
+__device__ inline int32_t *table_entry_at(const Dev &D, int32_t dir, uint32_t i) {
+  return D.slab + dir + (i - table_seg_first(table_seg(i)));
+}
 
 // A vector's place in the pool as one 32-bit number (block * T_m + place in the block; the pool holds
 // at most 2^32 places, which rtams_create checks): what a search keeps of a surviving candidate, so
