@@ -363,6 +363,20 @@ __device__ void scatter_pairs(const Dev &D, int nq, int nprobe, int max_nprobe, 
   }
 }
 
+// A thread's entries e0 .. e1 - 1, CH at a time: the loads of a chunk go out together, then body(e,
+// entry) for every entry of the chunk that is probed.
+template <int CH, typename Body>
+__device__ __forceinline__ void walk_entries(const uint4 *plist, uint32_t e0, uint32_t e1, Body body) {
+  for (uint32_t eb = e0; eb < e1; eb += CH) {
+    uint4 pl[CH];
+#pragma unroll
+    for (int t = 0; t < CH; ++t) pl[t] = eb + t < e1 ? plist[eb + t] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+    for (int t = 0; t < CH; ++t)
+      if (pl[t].z) body(eb + (uint32_t)t, pl[t]);
+  }
+}
+
 __global__ __launch_bounds__(kGroupThreads, 4) void k_group(Dev D, int nq, int nprobe, int max_nprobe, int k,
                                                          const float *__restrict__ Q,
                                                          uint32_t item_budget, uint32_t max_per_xcd,
@@ -487,10 +501,15 @@ __global__ __launch_bounds__(kGroupThreads, 4) void k_group(Dev D, int nq, int n
     if (lane == 0 && v) atomicAdd(&s_items[e], v);
   }
   // From here on a thread owns `per` consecutive entries and walks them kListChunk at a time, so
-  // that the loads of a chunk go out together: this workgroup is alone on its CU, and a pass over the
-  // entries is a chain of memory latencies otherwise.
+  // that the loads of a chunk go out together: a pass over the entries is a chain of memory
+  // latencies otherwise.  (With one or two entries to a thread the chunk is two wide: sixteen
+  // guarded loads, each waited for by itself, cost a small request three microseconds a pass.)
   const uint32_t per = (n_c + kGroupThreads - 1) / kGroupThreads;
   const uint32_t e0 = min(n_c, (uint32_t)tid * per), e1 = min(n_c, e0 + per);
+  auto for_my_entries = [&](auto body) {
+    if (per <= 2) walk_entries<2>(plist, e0, e1, body);  // uniform over the workgroup
+    else walk_entries<kListChunk>(plist, e0, e1, body);
+  };
   __syncthreads();
   int choice = kSegChoices - 1;
   for (int e = min_choice; e < kSegChoices; ++e)
@@ -500,20 +519,13 @@ __global__ __launch_bounds__(kGroupThreads, 4) void k_group(Dev D, int nq, int n
     const uint32_t seg = 2u << choice;
     uint32_t np = 0, ni = 0;
     unsigned long long wk = 0;
-    for (uint32_t eb = e0; eb < e1; eb += kListChunk) {
-      uint4 pl[kListChunk];
-#pragma unroll
-      for (int t = 0; t < kListChunk; ++t) pl[t] = eb + t < e1 ? plist[eb + t] : make_uint4(0u, 0u, 0u, 0u);
-#pragma unroll
-      for (int t = 0; t < kListChunk; ++t) {
-        const uint32_t c = pl[t].z;
-        if (!c) continue;
-        const uint32_t groups = (pl[t].w + kWave - 1) / kWave;
-        np += c;
-        ni += (groups ? (groups + seg - 1) / seg : 1u) * ((c + tile_q - 1) >> tile_shift);
-        wk += (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
-      }
-    }
+    for_my_entries([&](uint32_t, const uint4 &pl) {
+      const uint32_t c = pl.z;
+      const uint32_t groups = (pl.w + kWave - 1) / kWave;
+      np += c;
+      ni += (groups ? (groups + seg - 1) / seg : 1u) * ((c + tile_q - 1) >> tile_shift);
+      wk += (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
+    });
     uint32_t inp = np, ini = ni;
     unsigned long long iwk = wk;
     wg_scan3(inp, ini, iwk, s_a, s_b, s_c);
@@ -527,26 +539,18 @@ __global__ __launch_bounds__(kGroupThreads, 4) void k_group(Dev D, int nq, int n
     {
       uint32_t is = istart0;
       unsigned long long ws = wstart0;
-      for (uint32_t eb = e0; eb < e1; eb += kListChunk) {
-        uint4 pl[kListChunk];
-#pragma unroll
-        for (int t = 0; t < kListChunk; ++t) pl[t] = eb + t < e1 ? plist[eb + t] : make_uint4(0u, 0u, 0u, 0u);
-#pragma unroll
-        for (int t = 0; t < kListChunk; ++t) {
-          const uint32_t c = pl[t].z;
-          if (!c) continue;
-          const uint32_t groups = (pl[t].w + kWave - 1) / kWave;
-          const unsigned long long w = (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
-          const uint32_t n =
-              (groups ? (groups + seg - 1) / seg : 1u) * ((c + tile_q - 1) >> tile_shift);
-          for (uint32_t x = 1; x < 8; ++x) {  // the cut falls inside this list: at the item the same share of it ends at
-            const unsigned long long cut = total_work * x / 8;
-            if (ws <= cut && cut < ws + w) s_begin[x] = is + (uint32_t)((cut - ws) * n / w);
-          }
-          is += n;
-          ws += w;
+      for_my_entries([&](uint32_t, const uint4 &pl) {
+        const uint32_t c = pl.z;
+        const uint32_t groups = (pl.w + kWave - 1) / kWave;
+        const unsigned long long w = (unsigned long long)(c + byte_weight) * (groups ? groups : 1u);
+        const uint32_t n = (groups ? (groups + seg - 1) / seg : 1u) * ((c + tile_q - 1) >> tile_shift);
+        for (uint32_t x = 1; x < 8; ++x) {  // the cut falls inside this list: at the item the same share of it ends at
+          const unsigned long long cut = total_work * x / 8;
+          if (ws <= cut && cut < ws + w) s_begin[x] = is + (uint32_t)((cut - ws) * n / w);
         }
-      }
+        is += n;
+        ws += w;
+      });
     }
     __syncthreads();
     if (tid == 0)  // several cuts may fall into one list: keep the sequence monotone
@@ -574,21 +578,14 @@ __global__ __launch_bounds__(kGroupThreads, 4) void k_group(Dev D, int nq, int n
     // where the pairs and the items of every probed list start
     {
       uint32_t ps = pstart0, is = istart0;
-      for (uint32_t eb = e0; eb < e1; eb += kListChunk) {
-        uint4 pl[kListChunk];
-#pragma unroll
-        for (int t = 0; t < kListChunk; ++t) pl[t] = eb + t < e1 ? plist[eb + t] : make_uint4(0u, 0u, 0u, 0u);
-#pragma unroll
-        for (int t = 0; t < kListChunk; ++t) {
-          const uint32_t c = pl[t].z;
-          if (!c) continue;
-          const uint32_t groups = (pl[t].w + kWave - 1) / kWave;
-          plist[eb + t] = make_uint4(pl[t].x, ps, c, pl[t].w);
-          pistart[eb + t] = is;
-          ps += c;
-          is += (groups ? (groups + seg - 1) / seg : 1u) * ((c + tile_q - 1) >> tile_shift);
-        }
-      }
+      for_my_entries([&](uint32_t e, const uint4 &pl) {
+        const uint32_t c = pl.z;
+        const uint32_t groups = (pl.w + kWave - 1) / kWave;
+        plist[e] = make_uint4(pl.x, ps, c, pl.w);
+        pistart[e] = is;
+        ps += c;
+        is += (groups ? (groups + seg - 1) / seg : 1u) * ((c + tile_q - 1) >> tile_shift);
+      });
     }
     __syncthreads();  // entries written above are read below by other threads
     // Item descriptors.  A wavefront takes a sixteenth of the entries, 64 at a time, lane = entry.
