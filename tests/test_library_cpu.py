@@ -76,6 +76,24 @@ def test_create_needs_memory():
     assert b"pool and scratch" in L.rtams_last_error()
 
 
+def test_a_pool_of_more_than_2_to_32_places_is_refused_on_the_host():
+    """A search names a surviving candidate by its place in the pool, a 32-bit number: create says
+    EINVAL for a pool that would hold more places, and how many bytes it may have.  (The sizes are
+    checked before any memory is touched: the addresses given here are never used.)"""
+    L = rtams.lib()
+    c = cfg(d=4, block_vecs=64)
+    limit_blocks = (1 << 32) // 64
+    fits = L.rtams_pool_bytes_for(C.byref(c), limit_blocks)
+    c.d_pool, c.d_scratch = 0x10000, 0x20000
+    c.scratch_bytes = 1 << 30
+    c.pool_bytes = L.rtams_pool_bytes_for(C.byref(c), limit_blocks + 4096)
+    assert c.pool_bytes > fits > 0
+    h = C.c_void_p()
+    assert L.rtams_create(C.byref(c), C.byref(h)) == rtams.EINVAL and not h.value
+    msg = L.rtams_last_error().decode()
+    assert "2^32 places" in msg and str(fits) in msg
+
+
 @pytest.mark.parametrize("bad_m", [3, 6, 12, 68, -4])
 def test_bad_quantiser_shapes_are_refused_on_the_host(bad_m):
     """pq_m must be 0, or a multiple of 4 up to 64 that divides d (here d = 32)."""
