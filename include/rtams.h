@@ -289,6 +289,9 @@ int rtams_list_export_codes(rtams_index *ix, int32_t list, int64_t cap, int64_t 
  *                          (default 4096; 0: never) AND those pairs are expected to meet at least so
  *                          many list bytes, lists taken at their average length (default 16 GiB):
  *                          scans of a millisecond or more gain nothing from running side by side.
+ *   "scan_steal"           1 (default): in such a long scan on the matrix cores, a die that has run out
+ *                          of its share of the work items takes items from the back of another die's
+ *                          share; 0: every die scans its own share only.  The result is the same.
  *   "use_mfma"             whether approximate coarse scores from the matrix cores filter the
  *                          centroids before the exact arithmetic decides: 0 never, 1 for batches large
  *                          enough to repay it (default), 2 for every batch of 32 rows or more.

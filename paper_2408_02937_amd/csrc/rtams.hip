@@ -272,6 +272,7 @@ struct rtams_index {
   hipEvent_t scan_tail = nullptr;                 // behind the last large scan enqueued, or nullptr
   std::atomic<int64_t> scan_exclusive_pairs{4096};  // (query, list) pairs from which a request's scan may queue up; 0 never
   std::atomic<int64_t> scan_exclusive_bytes{(int64_t)16 << 30};  // ... and expected list bytes of those pairs from which it does
+  std::atomic<int64_t> scan_steal{1};  // such a long scan, on the matrix cores: XCDs that are done take items of the others
   std::mutex prof_mutex;
   double scan_ms = 0.0;      // sum of measured scan-kernel durations
   int64_t scan_launches = 0;
@@ -732,6 +733,13 @@ static int search_on(rtams_index *ix, int r, int64_t nq, const float *d_queries,
   }
   D.scan_byte_weight = (int32_t)ix->scan_byte_weight.load(std::memory_order_relaxed);
   D.scan_min_choice = (int32_t)ix->scan_min_choice.load(std::memory_order_relaxed);
+  // a long scan: its (query, list) pairs are expected to meet this many list bytes (lists of average length)
+  const int64_t excl = ix->scan_exclusive_pairs.load(std::memory_order_relaxed);
+  const int64_t vec_bytes = D.pq_m > 0 ? D.pq_m : (int64_t)D.vchunks * 16;
+  const int64_t pair_bytes = nq * nprobe * (ix->ntotal_host / ix->cfg.nlist + 1) * vec_bytes;
+  const bool long_scan = excl > 0 && nq * nprobe >= excl &&
+                         pair_bytes >= ix->scan_exclusive_bytes.load(std::memory_order_relaxed);
+  D.scan_steal = long_scan && ix->scan_steal.load(std::memory_order_relaxed) != 0;
   const SearchScratch &S = ix->res[r].s;
   // a rearrangement is switching block tables: start behind its last switch
   if (ix->fence_cur) (void)hipStreamWaitEvent(s, ix->fence_cur, 0);
@@ -746,12 +754,7 @@ static int search_on(rtams_index *ix, int r, int64_t nq, const float *d_queries,
   if (budget < 1024) budget = 1024;
   launch_group(D, nq, nprobe, ix->cfg.max_nprobe, k, d_queries, (int)budget, S, s);
   const bool timed = ix->profile_scan.load(std::memory_order_relaxed) != 0;
-  const int64_t excl = ix->scan_exclusive_pairs.load(std::memory_order_relaxed);
-  // expected list bytes of the request's pairs: lists of average length
-  const int64_t vec_bytes = D.pq_m > 0 ? D.pq_m : (int64_t)D.vchunks * 16;
-  const int64_t pair_bytes = nq * nprobe * (ix->ntotal_host / ix->cfg.nlist + 1) * vec_bytes;
-  if (excl > 0 && nq * nprobe >= excl &&
-      pair_bytes >= ix->scan_exclusive_bytes.load(std::memory_order_relaxed)) {  // a long scan: behind the long scan enqueued before it
+  if (long_scan) {  // behind the long scan enqueued before it
     std::lock_guard<std::mutex> chain(ix->scan_mutex);
     if (ix->scan_tail && ix->scan_tail != ix->res[r].scan_done) (void)hipStreamWaitEvent(s, ix->scan_tail, 0);
     if (timed) (void)hipEventRecord(ix->res[r].t0, s);
@@ -1125,6 +1128,7 @@ int rtams_set_param(rtams_index *ix, const char *key, int64_t value) {
   if (!strcmp(key, "use_mfma")) { ix->use_mfma = value; return RTAMS_OK; }
   if (!strcmp(key, "scan_mfma")) { ix->scan_mfma = value; return RTAMS_OK; }
   if (!strcmp(key, "scan_exclusive_pairs")) { ix->scan_exclusive_pairs = value > 0 ? value : 0; return RTAMS_OK; }
+  if (!strcmp(key, "scan_steal")) { ix->scan_steal = value != 0; return RTAMS_OK; }
   if (!strcmp(key, "scan_exclusive_bytes")) { ix->scan_exclusive_bytes = value > 0 ? value : 0; return RTAMS_OK; }
   if (!strcmp(key, "scan_min_choice")) { ix->scan_min_choice = value < 0 ? -1 : value > 7 ? 7 : value; return RTAMS_OK; }
   if (!strcmp(key, "scan_byte_weight")) { ix->scan_byte_weight = value > 0 ? value : 0; return RTAMS_OK; }

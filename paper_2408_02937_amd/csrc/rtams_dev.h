@@ -59,6 +59,7 @@ struct Dev {
   int32_t d, nlist, metric, T_m;
   int32_t pq_m;             // 0: flat lists; M > 0: product-quantiser codes, M bytes per vector
   int32_t scan_mfma;        // flat float lists: the scan's dot products run on the matrix cores (set per request)
+  int32_t scan_steal;       // a long scan on the matrix cores: XCDs that are done take items of the others (set per request)
   int32_t scan_min_choice;  // shortest segment the plan may choose, as a power of two of pairs of groups (-1: the kernel's default; set per request)
   int32_t scan_byte_weight; // cost of reading a group of a list, in queries' worth of arithmetic (0: the default; set per request)
   int32_t d4;               // d / 4

@@ -10,8 +10,13 @@ namespace rtams {
 struct ScanQueues {
   uint32_t begin[9];    // XCD x owns items begin[x] .. begin[x+1]-1
   uint32_t seg_groups;  // 64-vector groups per work item
-  uint32_t pad[22];
+  // Long scans on the matrix cores: an XCD that has run out of its own items takes items of the others
+  // from the back of their ranges (all of these words are zero when the request starts).
+  uint32_t back[8];     // items taken from the back of XCD y's range so far
+  uint32_t done_mask;   // bit y: nothing is left to take from XCD y
+  uint32_t pad[13];
 };
+static_assert(sizeof(ScanQueues) == 32 * 4, "the request's clearing pass covers the queue words");
 
 // The scan keeps, for every query, only the candidates that are not worse than
 // the query's BOUND (the k-th best score of a sample of its candidates, set

@@ -29,17 +29,24 @@ __device__ inline uint32_t *rec_poss_of(const SearchScratch &S, unsigned long lo
 // Room for `want` entries in the request's chunk of the shared reserve (called by one thread per
 // query): the start, flagged, or ~0.  The first query of a request that needs it leases a free chunk
 // and installs it for the request; one that loses that race to a sibling hands its chunk straight
-// back and shares the sibling's.  Nothing here waits for anybody.
+// back and shares the sibling's.  Nobody waits for anybody beyond a few bounded second looks.
 __device__ inline unsigned long long overflow_take(const SearchScratch &S, unsigned long long want) {
   if (S.ovf_chunks == 0 || want > S.ovf_chunk_cap) return ~0ull;
+  // Siblings that race for the request's chunk may hold several free chunks between them for a moment
+  // (all but one are handed back at once), and a query of ANOTHER request that looks just then finds
+  // every chunk out although one is about to come back: it looks again a bounded number of times
+  // before it gives up (a chunk that stays out is held by a request for as long as that request runs).
   uint32_t c = __hip_atomic_load(S.req_chunk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  for (uint32_t e = 0; e < S.ovf_chunks && c == 0; ++e)
-    if (atomicCAS(&S.ovf_leased[e], 0u, 1u) == 0u) {
-      const uint32_t seen = atomicCAS(S.req_chunk, 0u, e + 1u);
-      if (seen == 0u) c = e + 1u;
-      else { atomicExch(&S.ovf_leased[e], 0u); c = seen; }
-    }
-  if (c == 0) c = __hip_atomic_load(S.req_chunk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // a sibling may have got the last one
+  for (int round = 0; round < 32 && c == 0; ++round) {
+    for (uint32_t e = 0; e < S.ovf_chunks && c == 0; ++e)
+      if (atomicCAS(&S.ovf_leased[e], 0u, 1u) == 0u) {
+        const uint32_t seen = atomicCAS(S.req_chunk, 0u, e + 1u);
+        if (seen == 0u) c = e + 1u;
+        else { atomicExch(&S.ovf_leased[e], 0u); c = seen; }
+      }
+    if (c == 0) c = __hip_atomic_load(S.req_chunk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // a sibling may have got the last one
+    if (c == 0) __builtin_amdgcn_s_sleep(32);
+  }
   if (c == 0) return ~0ull;  // every chunk is out
   const unsigned long long off = atomicAdd(S.req_cursor, want);
   if (off + want > S.ovf_chunk_cap) return ~0ull;
