@@ -116,6 +116,37 @@ def test_search_matches_oracle(loaded, batch):
                             what=f"{w.name} batch {batch} scan_mfma {mode}")
 
 
+def test_long_scans_that_take_work_from_other_dies_match_the_oracle(loaded):
+    """A scan that the library takes for a long one lets a die that has run out of work items take
+    items from the back of another die's share (matrix-core scan).  Every request is made to count as
+    long here; with and without the taking the answers are the oracle's, and the same bits."""
+    w, g, o, _ = loaded
+    q = w.queries[:256]
+    rd, ri = o.search(q, w.k, w.nprobe)
+    got = {}
+    try:
+        g.set_param("scan_exclusive_pairs", 1)
+        g.set_param("scan_exclusive_bytes", 1)
+        g.set_param("scan_mfma", 2)
+        for steal in (1, 0):
+            g.set_param("scan_steal", steal)
+            for rep in range(3):  # which die finishes first differs from run to run
+                d, i = g.search(dev(q), w.k, w.nprobe)
+                torch.cuda.synchronize()
+                assert g.poll_error() == 0
+                d, i = d.cpu().numpy(), i.cpu().numpy()
+                assert_topk_matches(w.metric, d, i, rd, ri, rtol=RTOL, atol=1e-6, what=f"{w.name} steal {steal} run {rep}")
+                if got:
+                    assert np.array_equal(i, got["i"]) and np.array_equal(d.view(np.uint32), got["d"].view(np.uint32))
+                else:
+                    got = {"d": d, "i": i}
+    finally:
+        g.set_param("scan_steal", 1)
+        g.set_param("scan_mfma", 1)
+        g.set_param("scan_exclusive_pairs", 4096)
+        g.set_param("scan_exclusive_bytes", 16 << 30)
+
+
 def test_search_all_lists_and_large_k(loaded):
     w, g, o, _ = loaded
     nprobe = min(w.nlist, 64)
