@@ -4,7 +4,9 @@
 
 namespace rtams {
 
-constexpr int kSelThreads = 256;
+// Workgroup of the probe selection: 256 threads, or 1024 where a query has thousands of centroids to
+// go through (every pass of the selection reads them all).
+constexpr int kSelThreads = 256, kSelThreadsMany = 1024, kSelManyFrom = 4096;
 
 // ------------------------------------------------------------ probe and plan
 // One workgroup per query: the nprobe best centroids by (score, index), best
@@ -18,7 +20,7 @@ constexpr int kSelThreads = 256;
 // exactly.  If the band holds more candidates than LDS, the whole row is scored
 // exactly instead (what small requests, which skip the matrix cores, always do).
 template <bool FROM_APPROX>
-__global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, int max_nprobe,
+__global__ __launch_bounds__(kSelThreadsMany) void k_probe_plan(Dev D, int nprobe, int max_nprobe,
                                                             SearchScratch S, const float *__restrict__ Q,
                                                             int32_t *probe_out) {
   __shared__ __attribute__((aligned(8))) uint32_t hist[kSelectLdsWords];
@@ -27,7 +29,8 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
   __shared__ uint64_t k1[kMaxNprobe];
   __shared__ uint64_t k2[kMaxNprobe];
   __shared__ uint32_t pay[kMaxNprobe];
-  __shared__ float s_red[kSelThreads / kWave];
+  __shared__ float s_red[kSelThreadsMany / kWave];
+  const int T = (int)blockDim.x;
   const int q = blockIdx.x;
   const int n = D.nlist;
   double *sc = S.scores + (size_t)q * n;
@@ -54,12 +57,12 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
     const float *ap = S.approx + (size_t)q * n;
     // |y|^2 for the error band
     float yn = 0.f;
-    for (int j = threadIdx.x; j < D.d; j += kSelThreads) { const float v = Q[(size_t)q * D.d + j]; yn = fmaf(v, v, yn); }
+    for (int j = threadIdx.x; j < D.d; j += T) { const float v = Q[(size_t)q * D.d + j]; yn = fmaf(v, v, yn); }
     for (int o = kWave / 2; o > 0; o >>= 1) yn += __shfl_xor(yn, o);
     if ((threadIdx.x & (kWave - 1)) == 0) s_red[threadIdx.x / kWave] = yn;
     __syncthreads();
     yn = 0.f;
-    for (int w = 0; w < kSelThreads / kWave; ++w) yn += s_red[w];
+    for (int w = 0; w < T / kWave; ++w) yn += s_red[w];
     const float cmax = __uint_as_float(D.ctrl->cnorm_max_bits);
     const float band = coarse_band(D.d, yn + cmax) * 1.01f;  // 2 E, see coarse_mfma.hip
     const SelectResult ra = wg_radix_select<32>(
@@ -69,7 +72,7 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
     const float limit = t + band;
     if (threadIdx.x == 0) cnt[0] = 0;
     __syncthreads();
-    for (int i = threadIdx.x; i < n; i += kSelThreads)
+    for (int i = threadIdx.x; i < n; i += T)
       if (ap[i] <= limit) {
         uint32_t p = atomicAdd(&cnt[0], 1u);
         if (p < (uint32_t)kMaxNprobe) pay[p] = (uint32_t)i;
@@ -77,7 +80,7 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
     __syncthreads();
     const int nc = (int)cnt[0];
     if (nc >= nprobe && nc <= kMaxNprobe) {  // (fewer than nprobe: scores that do not compare, e.g. NaN)
-      for (int p = threadIdx.x; p < nc; p += kSelThreads) {
+      for (int p = threadIdx.x; p < nc; p += T) {
         const int c = (int)pay[p];
         k1[p] = key_of_score(exact(c));
         k2[p] = (uint64_t)c;
@@ -85,7 +88,7 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
       wg_sort(nc, k1, k2, pay);  // by (exact score, index): the first nprobe are the answer
       done = true;
     } else {
-      for (int i = threadIdx.x; i < n; i += kSelThreads) sc[i] = exact(i);  // the filter did not narrow it: whole row
+      for (int i = threadIdx.x; i < n; i += T) sc[i] = exact(i);  // the filter did not narrow it: whole row
       __syncthreads();
     }
   }
@@ -94,7 +97,7 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
   SelectResult r1{~0ull, 0, 0}, r2{~0ull, 0, 0};
   const bool all = nprobe >= n;
   if (!done && FROM_APPROX && all) {  // every list is probed: exact order of the whole row
-    for (int i = threadIdx.x; i < n; i += kSelThreads) sc[i] = exact(i);
+    for (int i = threadIdx.x; i < n; i += T) sc[i] = exact(i);
     __syncthreads();
   }
   if (!done) {
@@ -108,7 +111,7 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
   }
   if (threadIdx.x == 0) cnt[0] = 0;
   __syncthreads();
-  for (int i = threadIdx.x; i < n; i += kSelThreads) {
+  for (int i = threadIdx.x; i < n; i += T) {
     uint64_t k = key1(i);
     bool take = all || k < r1.T || (k == r1.T && (r1.c_eq <= r1.need || (uint64_t)i <= r2.T));
     if (take) {
@@ -121,14 +124,14 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
   }  // !done
   if (done) {  // the sort carried no payload: the list index is the second key
     __syncthreads();
-    for (int p = threadIdx.x; p < nprobe; p += kSelThreads) pay[p] = (uint32_t)k2[p];
+    for (int p = threadIdx.x; p < nprobe; p += T) pay[p] = (uint32_t)k2[p];
     __syncthreads();
   }
 
   // plan
   int32_t *pl = S.probe_list + (size_t)q * max_nprobe;
   uint32_t *plen = S.probe_len + (size_t)q * max_nprobe;
-  for (int p = threadIdx.x; p < nprobe; p += kSelThreads) {
+  for (int p = threadIdx.x; p < nprobe; p += T) {
     int list = (int)pay[p];
     pl[p] = list;
     if (probe_out) probe_out[(size_t)q * nprobe + p] = list;
@@ -168,11 +171,12 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_plan(Dev D, int nprobe, i
 void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const SearchScratch &S,
                        const float *Q, bool from_approx, int32_t *probe_out, hipStream_t s) {
   if (nq <= 0) return;
+  const unsigned threads = D.nlist >= kSelManyFrom ? kSelThreadsMany : kSelThreads;
   if (from_approx)
-    hipLaunchKernelGGL(k_probe_plan<true>, dim3((unsigned)nq), dim3(kSelThreads), 0, s, D, nprobe, max_nprobe,
+    hipLaunchKernelGGL(k_probe_plan<true>, dim3((unsigned)nq), dim3(threads), 0, s, D, nprobe, max_nprobe,
                        S, Q, probe_out);
   else
-    hipLaunchKernelGGL(k_probe_plan<false>, dim3((unsigned)nq), dim3(kSelThreads), 0, s, D, nprobe, max_nprobe,
+    hipLaunchKernelGGL(k_probe_plan<false>, dim3((unsigned)nq), dim3(threads), 0, s, D, nprobe, max_nprobe,
                        S, Q, probe_out);
 }
 
