@@ -172,40 +172,44 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
   __shared__ uint32_t s_over;
   int stretch = 1;  // portions as a multiple of the room in LDS
   // More records than LDS holds (the query's bound was loose: its sample did not look like its
-  // candidates): a first limit comes from a pilot, every (n / kPilot)-th record, so that the
-  // records are filtered from the first portion on instead of filling LDS once unfiltered.
+  // candidates): a first limit comes from a pilot, every (n / pilot)-th record, so that the
+  // records are filtered from the first portion on instead of filling LDS once unfiltered.  A query
+  // with tens of thousands of records (a hot list) takes a pilot as large as LDS: the k-th best of
+  // 4096 lets about k / 4096 of the records pass, which fit in one go.
   constexpr int kPilot = 1024;
   if (n > kSurvivorCap && k <= kPilot) {  // uniform over the workgroup
-    const int stride = n / kPilot;
-    for (int j = threadIdx.x; j < kPilot; j += kTopkThreads) skey[j] = rk[(size_t)j * stride];
+    const int pilot = n >= 8 * kSurvivorCap ? kSurvivorCap : kPilot;
+    const int stride = n / pilot;
+    for (int j = threadIdx.x; j < pilot; j += kTopkThreads) skey[j] = rk[(size_t)j * stride];
     __syncthreads();
     const SelectResult r = wg_radix_select<32>(
-        kPilot, (uint32_t)k, [&](int j, uint64_t &kv) { kv = skey[j]; return true; }, sh.hist, sh.bc);
+        pilot, (uint32_t)k, [&](int j, uint64_t &kv) { kv = skey[j]; return true; }, sh.hist, sh.bc);
     const uint32_t lim = limit_from((uint32_t)r.T);
     limit = lim < limit ? lim : limit;
-    stretch = 4;
+    stretch = pilot == kSurvivorCap ? 16 : 4;
     __syncthreads();  // the pilot's keys are done with
   }
-  for (int next = 0; next < n;) {  // every branch here is uniform over the workgroup
-    const int count = (int)scount;
-    const int m = min(n - next, stretch * (kSurvivorCap - count));
-    if (threadIdx.x == 0) s_over = 0;
-    __syncthreads();
-    // Independent loads per thread (keys and positions, 16 each): 8,192 records per round trip to memory.  The positions come with
-    // the keys whether their record passes or not: a load inside the loop below, for the records
-    // that pass, would make every turn of it a round trip of its own.
-    constexpr int kInFlight = 16;
+  // A query whose records take several round trips to stream keeps, of a record that passes, its
+  // index first and fetches the positions of what LDS holds in the end (the positions of the many
+  // that do not pass are never read); a query that is through in one round trip loads both together.
+  // 16 keys in flight per thread either way (24 or 32 take the kernel past 128 registers).
+  const bool deferred = n > 16 * kTopkThreads;  // uniform over the workgroup
+  auto stream = [&](auto tag, int next, int m) {
+    constexpr bool kDeferred = decltype(tag)::value;
+    constexpr int kInFlight = kDeferred ? 16 : 16;
     for (int j0 = 0; j0 < m; j0 += kInFlight * kTopkThreads) {
-      uint32_t kv[kInFlight], pv[kInFlight];
+      uint32_t kv[kInFlight], pv[kDeferred ? 1 : kInFlight];
 #pragma unroll
       for (int u = 0; u < kInFlight; ++u) {  // clamped index: the loads are unconditional and issue back to back
         const int j = j0 + u * kTopkThreads + (int)threadIdx.x;
         kv[u] = rk[next + (j < m ? j : m - 1)];
       }
+      if (!kDeferred) {
 #pragma unroll
-      for (int u = 0; u < kInFlight; ++u) {
-        const int j = j0 + u * kTopkThreads + (int)threadIdx.x;
-        pv[u] = rp[next + (j < m ? j : m - 1)];
+        for (int u = 0; u < kInFlight; ++u) {
+          const int j = j0 + u * kTopkThreads + (int)threadIdx.x;
+          pv[u] = rp[next + (j < m ? j : m - 1)];
+        }
       }
 #pragma unroll
       for (int u = 0; u < kInFlight; ++u) {
@@ -218,12 +222,22 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
           at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
           if (keep) {
             const uint32_t slot = at + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-            if (slot < (uint32_t)kSurvivorCap) { skey[slot] = kv[u]; sidx[slot] = pv[u]; }
+            if (slot < (uint32_t)kSurvivorCap) { skey[slot] = kv[u]; sidx[slot] = kDeferred ? (uint32_t)(next + j) : pv[kDeferred ? 0 : u]; }
             else s_over = 1u;
           }
         }
       }
     }
+  };
+  for (int next = 0; next < n;) {  // every branch here is uniform over the workgroup
+    const int count = (int)scount;
+    const int m = min(n - next, stretch * (kSurvivorCap - count));
+    if (threadIdx.x == 0) s_over = 0;
+    __syncthreads();
+    // (the positions come with the keys, or afterwards, but never from inside the filter loop: a load
+    // there, for the records that pass, would make every turn of it a round trip of its own)
+    if (deferred) stream(std::true_type{}, next, m);
+    else stream(std::false_type{}, next, m);
     __syncthreads();
     const bool over = s_over != 0;
     __syncthreads();
@@ -250,6 +264,12 @@ __global__ __launch_bounds__(kTopkThreads) void k_select(Dev D, int k, int nprob
     stretch = over ? 1 : 4;
   }
 
+  if (deferred && in_lds) {  // uniform: LDS holds indices of records; now their places in the pool
+    __syncthreads();
+    const int have = (int)scount;
+    for (int j = threadIdx.x; j < have; j += kTopkThreads) sidx[j] = rp[sidx[j]];
+    __syncthreads();
+  }
   // a record's place in the pool (slot_of) -> which block, which place in it
   auto locate = [&](int i, uint32_t &b, uint32_t &moff) {
     b = (uint32_t)i / (uint32_t)D.T_m;
