@@ -266,7 +266,9 @@ __global__ __launch_bounds__(kMmWaves *kWave) void k_scan_mm(Dev D, int max_npro
     __syncthreads();
     pairs = s_pairs;
     if (pairs == 0) return;  // uniform over the workgroup
-    if (s_item != own) desc = S.tile_desc[s_item];
+    // (a workgroup without an item of its own computed an `own` beyond its range, which may be the very
+    // number of the item it took from the next XCD: what it loaded above was nothing)
+    if (!has_own || s_item != own) desc = S.tile_desc[s_item];
   }
   const int list = (int)desc.x;
   const uint32_t first = desc.y;
