@@ -158,6 +158,7 @@ class Bench:
             self.step(i)
         torch.cuda.synchronize()
         g.scan_time(reset=True)
+        g.scan_kernels(reset=True)
         g.set_param("profile_scan", 1)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -167,6 +168,8 @@ class Bench:
         elapsed = time.perf_counter() - t0
         g.set_param("profile_scan", 0)
         scan_ms, scan_n = g.scan_time(reset=True)
+        by_kernel = g.scan_kernels(reset=True)  # which scan kernel the library chose for these requests
+        self.scan_kernel = max(by_kernel, key=by_kernel.get)
         assert g.poll_error() == 0, "a kernel raised an error during the timed steps"
         return elapsed, scan_ms, scan_n
 
@@ -214,7 +217,7 @@ class Bench:
         lane_ops = pair_vecs * w.d * (2 if w.metric == "l2" else 1)
         scan_avg_ms = scan_ms / max(scan_n, 1)
         achieved = union_b / (scan_avg_ms * 1e-3) / 1e9 if scan_n else float("nan")
-        return {"bound": "hbm", "kernel": "k_scan", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        return {"bound": "hbm", "kernel": self.scan_kernel, "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                 "bytes_per_launch": union_b, "pair_bytes_per_launch": pair_b,
                 "avg_launch_ms": scan_avg_ms, "launches_timed": scan_n,

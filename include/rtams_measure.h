@@ -20,6 +20,11 @@ extern "C" {
  * finished (ms_sum in milliseconds, launches = how many) and optionally resets
  * the sums.  Does not synchronise. */
 int rtams_scan_time(rtams_index *ix, double *ms_sum, int64_t *launches, int reset);
+/* Which kernel those timed launches were: launches3[0] counts the scans of the
+ * vector unit (k_scan), [1] those on the matrix cores (k_scan_mm), [2] those
+ * over product-quantiser codes (k_pq_scan), each since the last reset, counted
+ * at launch while "profile_scan" is 1.  The library chooses per request. */
+int rtams_scan_kernels(rtams_index *ix, int64_t *launches3, int reset);
 /* A plain device-to-device copy kernel
  * (bytes a multiple of 16).  Profiler counters of HBM traffic are scaled by
  * what they read for this kernel, whose traffic is known. */

@@ -249,6 +249,7 @@ struct rtams_index {
   std::atomic<int64_t> scan_items_per_pair{8};   // work items the plan may cut per (query, list) pair
   std::atomic<int64_t> scan_max_items{32768};    // ... and per request
   std::atomic<int64_t> profile_scan{0};
+  std::atomic<int64_t> timed_scans[3] = {{0}, {0}, {0}};  // timed launches of k_scan, k_scan_mm, k_pq_scan
   bool has_codebooks = false;
   uint32_t *ovf_leased = nullptr;  // device: which chunks of the shared scratch reserve are leased
   uint32_t ovf_chunks = 0;
@@ -754,6 +755,7 @@ static int search_on(rtams_index *ix, int r, int64_t nq, const float *d_queries,
   if (budget < 1024) budget = 1024;
   launch_group(D, nq, nprobe, ix->cfg.max_nprobe, k, d_queries, (int)budget, S, s);
   const bool timed = ix->profile_scan.load(std::memory_order_relaxed) != 0;
+  if (timed) ix->timed_scans[D.pq_m > 0 ? 2 : D.scan_mfma ? 1 : 0].fetch_add(1, std::memory_order_relaxed);
   if (long_scan) {  // behind the long scan enqueued before it
     std::lock_guard<std::mutex> chain(ix->scan_mutex);
     if (ix->scan_tail && ix->scan_tail != ix->res[r].scan_done) (void)hipStreamWaitEvent(s, ix->scan_tail, 0);
@@ -1104,6 +1106,14 @@ int rtams_scan_time(rtams_index *ix, double *ms_sum, int64_t *launches, int rese
   if (ms_sum) *ms_sum = ix->scan_ms;
   if (launches) *launches = ix->scan_launches;
   if (reset) { ix->scan_ms = 0.0; ix->scan_launches = 0; }
+  return RTAMS_OK;
+}
+
+int rtams_scan_kernels(rtams_index *ix, int64_t *launches3, int reset) {
+  if (!ix || !launches3) return fail(RTAMS_EINVAL, "NULL argument");
+  for (int i = 0; i < 3; ++i)
+    launches3[i] = reset ? ix->timed_scans[i].exchange(0, std::memory_order_relaxed)
+                         : ix->timed_scans[i].load(std::memory_order_relaxed);
   return RTAMS_OK;
 }
 

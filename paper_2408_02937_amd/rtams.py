@@ -30,7 +30,7 @@ SYMBOLS = [
     "rtams_list_sizes", "rtams_pool_stats", "rtams_validate", "rtams_probe", "rtams_assign",
     "rtams_poll_error", "rtams_clear_error", "rtams_last_error", "rtams_set_param", "rtams_scan_time",
     "rtams_copy_plain", "rtams_read_plain", "rtams_set_codebooks", "rtams_list_export_codes",
-    "rtams_search_noalloc", "rtams_overflow_bytes_for",
+    "rtams_search_noalloc", "rtams_overflow_bytes_for", "rtams_scan_kernels",
 ]
 
 
@@ -103,6 +103,7 @@ def lib():
         L.rtams_last_error.restype = C.c_char_p
         L.rtams_set_param.argtypes = [vp, C.c_char_p, i64]
         L.rtams_scan_time.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), C.c_int]
+        L.rtams_scan_kernels.argtypes = [vp, C.POINTER(i64), C.c_int]
         L.rtams_copy_plain.argtypes = [vp, vp, C.c_size_t, vp]
         L.rtams_read_plain.argtypes = [vp, C.c_size_t, vp, vp]
         _lib = L
@@ -331,6 +332,11 @@ class Index:
         ms, n = C.c_double(), C.c_int64()
         _chk(lib().rtams_scan_time(self._h, C.byref(ms), C.byref(n), int(reset)), "rtams_scan_time")
         return ms.value, n.value
+
+    def scan_kernels(self, reset: bool = False) -> dict:
+        n = (C.c_int64 * 3)()
+        _chk(lib().rtams_scan_kernels(self._h, n, int(reset)), "rtams_scan_kernels")
+        return {"k_scan": n[0], "k_scan_mm": n[1], "k_pq_scan": n[2]}
 
     def set_param(self, key: str, value: int) -> None:
         _chk(lib().rtams_set_param(self._h, key.encode(), value), "rtams_set_param")

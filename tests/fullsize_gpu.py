@@ -1,4 +1,4 @@
-"""Steps the two full-size parity files share: build the pair of indexes, compare lists, compare queries."""
+"""Steps the full-size parity files share: build the pair of indexes, compare lists, compare queries."""
 import numpy as np
 import pytest
 import torch
@@ -10,11 +10,11 @@ from tests.gpu_common import dev, scan_modes
 from tests.helpers import ATOL, RTOL, assert_topk_matches
 
 
-def build_pair(request, w, assign, cand, rearrange_threshold=0, spare_blocks=64):
+def build_pair(request, w, assign, cand, rearrange_threshold=0, spare_blocks=64, n_resources=5):
     n_all = len(w.base) + len(w.inserts)
     pool_blocks = n_all // w.block_vecs + 2 * w.nlist + spare_blocks
     g = rtams.Index(w.d, w.nlist, w.metric, w.block_vecs, pool_blocks=pool_blocks,
-                    rearrange_threshold=rearrange_threshold, n_resources=5, max_batch=256, max_k=64,
+                    rearrange_threshold=rearrange_threshold, n_resources=n_resources, max_batch=256, max_k=64,
                     max_nprobe=64, max_add_batch=65536, candidates_per_query=cand)
     g.set_centroids(dev(w.centroids))
     o = OracleIndex(w.d, w.nlist, w.metric, w.block_vecs, rearrange_threshold=0, pool_blocks=pool_blocks)
