@@ -500,7 +500,8 @@ def main() -> int:
         b.g.validate()
         st = b.g.pool_stats()
         result["pool"] = {"blocks_in_use": st.blocks_in_use, "blocks_total": st.blocks_total,
-                          "utilisation": st.utilisation, "ntotal": st.ntotal, "lists_exceeding": st.lists_exceeding}
+                          "utilisation": st.utilisation, "ntotal": st.ntotal, "lists_exceeding": st.lists_exceeding,
+                          "add_waits": st.add_waits}
         assert b.g.poll_error() == 0, "a kernel raised an error"
     b.close()
     if not args.no_extras and args.cpu_queries >= 0:

@@ -107,6 +107,8 @@ typedef struct rtams_stats {
   int64_t rearrangement_state;     /* of the last rearrangement round: 0 its list is contiguous (or nothing was to
                                       do), 1 another round is owed (a round moves as many blocks as the pool has
                                       spare blocks for, at most 4096), 2 stalled: no spare block at all */
+  int64_t add_waits;               /* times rtams_add waited for the data stream to learn how many blocks are left
+                                      (what the device reports at every publication did not do) */
 } rtams_stats;
 
 /* Bytes of pool needed for `blocks` blocks under this configuration (d_pool and
@@ -165,7 +167,13 @@ int rtams_set_codebooks(rtams_index *ix, const float *d_codebooks, void *hip_str
  * searches as a whole, after its last vector is written.  All adds (and
  * rearrangements) are ordered one after another: the paper's single data
  * stream; a call on another stream than the previous one is ordered behind it
- * with an event.  EPOOL (nothing enqueued) when the pool might overflow. */
+ * with an event.  EPOOL (nothing enqueued) when the pool might overflow:
+ * the call counts the blocks the batch may open at most (one per touched list
+ * plus the full ones) against the blocks left, which it takes from what the
+ * device reports to pinned host memory whenever a batch is published, less
+ * what the batches enqueued since may open.  Only when that estimate falls
+ * short does the call WAIT for the data stream and read the allocator's own
+ * counters (rtams_stats.add_waits counts these waits) before it says EPOOL. */
 int rtams_add(rtams_index *ix, int64_t n, const float *d_vecs, const int64_t *d_ids,
               void *hip_stream);
 

@@ -176,8 +176,15 @@ __global__ __launch_bounds__(256) void k_fill(Dev D, int64_t n, const float *__r
 // ---- publish: one thread per list makes the batch visible and evaluates
 // Exceed() (the equation defining it: vectors appended since the last
 // rearrangement, strictly greater than T_m').
-__global__ __launch_bounds__(256) void k_publish(Dev D) {
+__global__ __launch_bounds__(256) void k_publish(Dev D, uint32_t call_seq) {
   int list = blockIdx.x * blockDim.x + threadIdx.x;
+  // The allocator's counters are final for this batch (k_open has finished, and every rearrangement
+  // round enqueued before it has returned its spare blocks): the host learns the blocks in use.
+  if (list == 0) {
+    const int32_t f = D.ctrl->free_top;
+    const uint32_t in_use = D.ctrl->cur_P - (uint32_t)(f > 0 ? f : 0);
+    D.mirror->pool_word = ((unsigned long long)call_seq << 32) | in_use;
+  }
   if (list >= D.nlist) return;
   uint32_t newlen = D.reserved_len[list];
   uint32_t old = D.visible_len[list];
@@ -235,9 +242,9 @@ void launch_fill(const Dev &D, int64_t n, const float *Y, const int64_t *ids, in
   hipLaunchKernelGGL(k_fill, dim3(grid), dim3(256), 0, s, D, n, Y, ids, id_base, S.assign, S.did);
 }
 
-void launch_publish(const Dev &D, hipStream_t s) {
+void launch_publish(const Dev &D, uint32_t call_seq, hipStream_t s) {
   unsigned grid = (unsigned)((D.nlist + 255) / 256);
-  hipLaunchKernelGGL(k_publish, dim3(grid), dim3(256), 0, s, D);
+  hipLaunchKernelGGL(k_publish, dim3(grid), dim3(256), 0, s, D, call_seq);
 }
 
 }  // namespace rtams

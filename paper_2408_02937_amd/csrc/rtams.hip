@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <deque>
 #include <mutex>
 #include <new>
 #include <shared_mutex>
@@ -246,6 +247,13 @@ struct rtams_index {
   hipEvent_t fence_cur = nullptr;               // what a new search must wait for, or nullptr
   std::atomic<int64_t> ntotal_host{0};   // vectors handed to add so far (written under data_mutex; searches read it for estimates)
   int64_t avail_lb = 0;      // lower bound of the blocks still available in the pool
+  // Insertion calls enqueued whose publication the host has not seen yet, with the blocks each may open at most
+  // (under data_mutex).  The device reports (number of the last call published, blocks in use) in one word.
+  struct PendingAdd { uint32_t seq; int64_t need; };
+  std::deque<PendingAdd> pending_adds;
+  int64_t pending_need = 0;
+  uint32_t add_seq = 0;
+  int64_t add_waits = 0;     // times an add had to wait for the data stream to learn how many blocks are left
   std::atomic<int64_t> scan_items_per_pair{8};   // work items the plan may cut per (query, list) pair
   std::atomic<int64_t> scan_max_items{32768};    // ... and per request
   std::atomic<int64_t> profile_scan{0};
@@ -302,6 +310,21 @@ void coarse_and_plan(rtams_index *ix, int64_t nq, const float *Q, int nprobe, co
 int sync_data(rtams_index *ix) {
   if (ix->have_data_stream) HIP_TRY(hipStreamSynchronize(ix->data_stream));
   return RTAMS_OK;
+}
+
+// Blocks still available, from what the device last reported: the blocks in use after the insertion
+// call it names, less what the calls enqueued after that one may open.  Blocks in use never shrink
+// between two publications (a rearrangement round returns the spare blocks it took before the next
+// batch runs), so this is a lower bound whichever publication the word is from.  No waiting.
+void tighten_pool_bound(rtams_index *ix) {
+  const unsigned long long w = ix->mirror->pool_word;  // one aligned 64-bit load
+  const uint32_t seen = (uint32_t)(w >> 32), in_use = (uint32_t)w;
+  while (!ix->pending_adds.empty() && (int32_t)(seen - ix->pending_adds.front().seq) >= 0) {
+    ix->pending_need -= ix->pending_adds.front().need;
+    ix->pending_adds.pop_front();
+  }
+  const int64_t left = (int64_t)ix->dev.nblocks - (int64_t)in_use - ix->pending_need;
+  if (left > ix->avail_lb) ix->avail_lb = left;
 }
 
 // Orders this call behind the previous work of the data stream.
@@ -660,11 +683,15 @@ int rtams_add(rtams_index *ix, int64_t n, const float *d_vecs, const int64_t *d_
   // Upper bound of the blocks this batch can open: one partly filled block per
   // touched list plus the full ones.
   int64_t need = (n < D.nlist ? n : D.nlist) + n / D.T_m;
-  if (need > ix->avail_lb) {  // tighten the bound from the device's own counters
+  if (need > ix->avail_lb || ix->pending_adds.size() >= 4096) tighten_pool_bound(ix);
+  if (need > ix->avail_lb) {  // what the device has reported does not do: wait for it and read its counters
     int rc = sync_data(ix);
     if (rc) return rc;
     Ctrl c;
     if ((rc = read_ctrl(ix, &c))) return rc;
+    ++ix->add_waits;
+    ix->pending_adds.clear();
+    ix->pending_need = 0;
     ix->avail_lb = (int64_t)D.nblocks - (int64_t)c.cur_P + (c.free_top > 0 ? c.free_top : 0);
     if (need > ix->avail_lb)
       return fail(RTAMS_EPOOL, "add of %lld vectors may need %lld blocks, %lld left in the pool",
@@ -675,6 +702,7 @@ int rtams_add(rtams_index *ix, int64_t n, const float *d_vecs, const int64_t *d_
   DataStreamScope scope{ix, s};
   const int64_t round = ix->cfg.max_add_batch;
   const bool ordered = ix->ordered_add.load(std::memory_order_relaxed) != 0;
+  const uint32_t seq = ++ix->add_seq;
   for (int64_t o = 0; o < n; o += round) {
     int64_t m = n - o < round ? n - o : round;
     const float *Y = d_vecs + (size_t)o * D.d;
@@ -687,10 +715,13 @@ int rtams_add(rtams_index *ix, int64_t n, const float *d_vecs, const int64_t *d_
     launch_open(D, s);
     if (D.pq_m > 0) launch_pq_fill(D, m, Y, d_ids ? d_ids + o : nullptr, ix->ntotal_host + o, ix->ins, s);
     else launch_fill(D, m, Y, d_ids ? d_ids + o : nullptr, ix->ntotal_host + o, ix->ins, s);
-    launch_publish(D, s);
+    // only its last round completes the call: the rounds before it report under the call before
+    launch_publish(D, o + round >= n ? seq : seq - 1u, s);
   }
   HIP_TRY(hipGetLastError());
   ix->avail_lb -= need;
+  ix->pending_adds.push_back({seq, need});
+  ix->pending_need += need;
   ix->ntotal_host += n;
   // Exceed() held for some list when an earlier batch was published (the device
   // reports it through pinned memory): one rearrangement round behind this batch
@@ -1049,7 +1080,10 @@ int rtams_pool_stats(rtams_index *ix, rtams_stats *out) {
     HIP_TRY(hipMemcpy(leased, ix->ovf_leased, sizeof(uint32_t) * ix->ovf_chunks, hipMemcpyDeviceToHost));
     for (uint32_t e = 0; e < ix->ovf_chunks; ++e) out->overflow_chunks_leased += leased[e] != 0;
   }
+  out->add_waits = ix->add_waits;
   ix->avail_lb = out->blocks_total - out->blocks_in_use;
+  ix->pending_adds.clear();  // the data stream was waited for: every call is in those counters
+  ix->pending_need = 0;
   return RTAMS_OK;
 }
 

@@ -51,6 +51,9 @@ struct HostMirror {
   volatile uint32_t max_len;
   volatile int32_t search_error;
   volatile uint32_t rearr_state;  // of the last rearrangement round: 0 done, 1 another round owed, 2 stalled for lack of a spare block
+  // written by every publication, in one store: (number of the last insertion call published << 32) | blocks in
+  // use after it.  The host takes from it how many blocks are left without waiting for the data stream.
+  volatile unsigned long long pool_word;
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));

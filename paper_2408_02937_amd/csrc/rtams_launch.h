@@ -155,7 +155,7 @@ void launch_reserve_ordered(const Dev &D, int64_t n, const InsertScratch &S, hip
 void launch_open(const Dev &D, hipStream_t s);
 void launch_fill(const Dev &D, int64_t n, const float *Y, const int64_t *ids, int64_t id_base,
                  const InsertScratch &S, hipStream_t s);
-void launch_publish(const Dev &D, hipStream_t s);
+void launch_publish(const Dev &D, uint32_t call_seq, hipStream_t s);
 
 // probe.hip, group.hip, scan.hip, pq_scan.hip, select.hip ---------------------
 void launch_probe_plan(const Dev &D, int64_t nq, int nprobe, int max_nprobe, const SearchScratch &S,

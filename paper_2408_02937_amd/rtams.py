@@ -52,7 +52,7 @@ class Stats(C.Structure):
                 ("lists_exceeding", C.c_int64), ("table_entries_used", C.c_int64),
                 ("table_entries_total", C.c_int64), ("overflow_chunks", C.c_int64),
                 ("overflow_chunk_entries", C.c_int64), ("overflow_chunks_leased", C.c_int64),
-                ("rearrangement_state", C.c_int64)]
+                ("rearrangement_state", C.c_int64), ("add_waits", C.c_int64)]
 
 
 class RtamsError(RuntimeError):

@@ -558,3 +558,39 @@ def test_pool_exhaustion_is_refused_before_anything_is_enqueued():
     assert st.ntotal == T * (total - 2) and st.blocks_in_use == total - 2 and g.poll_error() == 0
     g.validate()
     g.close()
+
+
+def test_add_learns_the_blocks_left_from_the_device_s_reports_without_waiting():
+    """Every add counts the blocks it may open at most (one per list it might touch, plus the full
+    ones) against the blocks left.  Small batches over many lists open far fewer than that, so the
+    running count falls short long before the pool does; the blocks in use that the device reports
+    at every publication then put it right, and the call never has to wait for the data stream.
+    The lists are the oracle's afterwards; a pool that really is full is still refused."""
+    w = synth.gaussian_l2("pool-bound", 77, d=16, n_base=6400, n_centres=32, nlist=64, block_vecs=64,
+                          n_queries=8, n_inserts=64)
+    # 6,400 vectors over 64 lists fill about 130 blocks; 100 batches of 64 may open 65 each by the count
+    g, o = make_pair(w, pool_blocks=400, max_batch=8, max_k=16, max_nprobe=8, candidates_per_query=8192)
+    s = torch.cuda.Stream()
+    for lo in range(0, len(w.base), 64):
+        g.add(dev(w.base[lo:lo + 64]), stream=s)
+        s.synchronize()  # what the device reported is there for the next call to read
+    o.add(w.base)
+    st = g.pool_stats()
+    assert st.add_waits == 0, "an add waited for the data stream although the device had reported enough blocks left"
+    assert st.blocks_in_use == o.blocks_in_use and st.blocks_in_use < 200
+    assert_lists_equal(g, o)
+    g.validate()
+    # batches enqueued back to back: the calls not yet published count with what they may open, so the
+    # estimate can only fall short (a wait), never let a batch through that does not fit
+    more = synth.gaussian_l2("pool-bound-more", 78, d=16, n_base=64 * 40, n_centres=32, nlist=64, block_vecs=64,
+                             n_queries=8, n_inserts=64)
+    for lo in range(0, len(more.base), 64):  # 40 batches need some 40 blocks of the 250 left: none may be refused
+        g.add(dev(more.base[lo:lo + 64]), stream=s)
+    s.synchronize()
+    assert g.poll_error() == 0
+    o.add(more.base)
+    st2 = g.pool_stats()
+    assert st2.blocks_in_use == o.blocks_in_use
+    assert_lists_equal(g, o)
+    g.validate()
+    g.close()
