@@ -12,8 +12,8 @@ The default workload is the largest configuration: skewed growth (L2, d = 256,
 20 M base vectors whose lists follow a Zipf(1.1) law over 16,384 lists, blocks
 of 256 vectors, nprobe 64, k 50, query batch 256, inserts in batches of 1024
 with the rearrangement threshold armed, 7 search streams and the data stream).
-`--config 3` and `--config 2` run the inner-product and the byte-valued
-configuration the same way; the default run also carries a short block for
+`--config 3`, `--config 4` and `--config 2` run the inner-product and the
+byte-valued configurations the same way; the default run also carries a short block for
 configuration 2.
 
 Prints ONE JSON line on stdout (progress lines go to stderr).  `value` is
@@ -48,6 +48,9 @@ VALU_ISSUE_PEAK_T = 256 * 4 * 16 * 2.4e9 / 1e12  # fp32 vector instructions per 
 PROTOCOL = {
     2: {"batch": 256, "search_streams": 4, "insert_rate": 10_000.0, "threshold": 0, "latency_batches": (1, 32, 256)},
     3: {"batch": 128, "search_streams": 4, "insert_rate": 50_000.0, "threshold": 0, "latency_batches": (1, 128)},
+    # (the configuration's own protocol, open-loop mixed load, is `--study mixed`; here its largest query batch in
+    # closed loop beside 30 % of its highest offered rate of 50,000 operations/s as inserts)
+    4: {"batch": 64, "search_streams": 7, "insert_rate": 15_000.0, "threshold": 0, "latency_batches": (1, 64)},
     5: {"batch": 256, "search_streams": 7, "insert_rate": 100_000.0, "threshold": 10_000, "latency_batches": (1, 256)},
 }
 T_START = time.perf_counter()
@@ -59,7 +62,7 @@ def note(msg: str) -> None:
 
 # queries the CPU oracle answers for `cpu_baseline`: 5-15 s of work on the box's 16 cores (measured: 1,900
 # queries/s on configuration 2, 50 on configuration 5)
-CPU_SAMPLE_QUERIES = {2: 8192, 3: 512, 5: 768}
+CPU_SAMPLE_QUERIES = {2: 8192, 3: 512, 4: 512, 5: 768}
 
 
 def percentile(xs, p):
@@ -404,7 +407,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=5, choices=sorted(PROTOCOL),
-                    help="benchmark configuration: 5 skewed growth (default), 3 inner product, 2 byte-valued")
+                    help="benchmark configuration: 5 skewed growth (default), 4 wide inner product, 3 inner product, 2 byte-valued")
     ap.add_argument("--batch", type=int, default=0, help="queries per search batch (default: the configuration's)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrinks base/query/insert counts")
     ap.add_argument("--search-streams", type=int, default=0, help="default: the configuration's")

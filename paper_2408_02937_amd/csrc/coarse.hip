@@ -83,31 +83,101 @@ __global__ __launch_bounds__(kCoarseThreads) void k_coarse(
 #pragma unroll
   for (int v = 0; v < VT; ++v) { best_s[v] = worst; best_i[v] = 0x7fffffff; }
 
-  const float4 *C4 = reinterpret_cast<const float4 *>(D.centroids);
+  // The centroids stream in from their transposed copy: chunk j of 64 consecutive centroids is 1 KiB,
+  // one 16-byte load per lane.  A thread's chain of multiply-adds is sequential in the coordinates, so
+  // what hides the trips to memory is how far ahead of the chain the loads run: four sets of kSet
+  // chunks go round, three of them in flight while the fourth is used up (a single query against
+  // thousands of centroids is nothing but such chains, a few per CU).
+  constexpr int kSet = VT <= 2 ? 8 : 4;
+  const float4 *CT = reinterpret_cast<const float4 *>(D.centroids_t);
+  const size_t cstride = (size_t)D.nlist;
   for (int c = c_begin + threadIdx.x; c < c_end; c += kCoarseThreads) {
     double acc[VT];
 #pragma unroll
     for (int v = 0; v < VT; ++v) acc[v] = 0.0;
-    const float4 *row = C4 + (size_t)c * d4;
-    for (int j4 = 0; j4 < d4; ++j4) {
-      float4 cv = row[j4];
-      double c0 = (double)cv.x, c1 = (double)cv.y, c2 = (double)cv.z, c3 = (double)cv.w;
+    const float4 *col = CT + c;
+    auto load_set = [&](float4 *set, int j0) {
+#pragma unroll
+      for (int u = 0; u < kSet; ++u) set[u] = col[(size_t)(j0 + u) * cstride];
+      __builtin_amdgcn_sched_barrier(0);  // the loads go out here, not where they are used
+    };
+    // the vectors' coordinates of chunk j, out of LDS
+    auto read_y = [&](double (*y)[4], int j) {
 #pragma unroll
       for (int v = 0; v < VT; ++v) {
-        const double *y = ylds + v * d + 4 * j4;
+        const double *p = ylds + v * d + 4 * j;
+        y[v][0] = p[0]; y[v][1] = p[1]; y[v][2] = p[2]; y[v][3] = p[3];
+      }
+    };
+    auto fma_chunk = [&](const float4 &cv, const double (*y)[4]) {
+      const double c0 = (double)cv.x, c1 = (double)cv.y, c2 = (double)cv.z, c3 = (double)cv.w;
+#pragma unroll
+      for (int v = 0; v < VT; ++v) {
         if (METRIC == 0) {
-          double t0 = y[0] - c0; acc[v] = __builtin_fma(t0, t0, acc[v]);
-          double t1 = y[1] - c1; acc[v] = __builtin_fma(t1, t1, acc[v]);
-          double t2 = y[2] - c2; acc[v] = __builtin_fma(t2, t2, acc[v]);
-          double t3 = y[3] - c3; acc[v] = __builtin_fma(t3, t3, acc[v]);
+          double t0 = y[v][0] - c0; acc[v] = __builtin_fma(t0, t0, acc[v]);
+          double t1 = y[v][1] - c1; acc[v] = __builtin_fma(t1, t1, acc[v]);
+          double t2 = y[v][2] - c2; acc[v] = __builtin_fma(t2, t2, acc[v]);
+          double t3 = y[v][3] - c3; acc[v] = __builtin_fma(t3, t3, acc[v]);
         } else {
-          acc[v] = __builtin_fma(y[0], c0, acc[v]);
-          acc[v] = __builtin_fma(y[1], c1, acc[v]);
-          acc[v] = __builtin_fma(y[2], c2, acc[v]);
-          acc[v] = __builtin_fma(y[3], c3, acc[v]);
+          acc[v] = __builtin_fma(y[v][0], c0, acc[v]);
+          acc[v] = __builtin_fma(y[v][1], c1, acc[v]);
+          acc[v] = __builtin_fma(y[v][2], c2, acc[v]);
+          acc[v] = __builtin_fma(y[v][3], c3, acc[v]);
         }
       }
+    };
+    auto use_chunk = [&](const float4 &cv, int j) {
+      double y[VT][4];
+      read_y(y, j);
+      fma_chunk(cv, y);
+    };
+    // With one or two vectors to a thread a chunk is four or eight dependent multiply-adds, and a trip
+    // to LDS in front of each chunk would take longer than they do: the coordinates of the next
+    // chunk are asked for before this one is worked on.
+    constexpr bool kAhead = VT <= 2;
+    auto use_set = [&](const float4 *set, int j0) {
+      if (kAhead) {
+        double ya[VT][4], yb[VT][4];
+        read_y(ya, j0);
+#pragma unroll
+        for (int u = 0; u < kSet; u += 2) {
+          read_y(yb, j0 + u + 1);
+          fma_chunk(set[u], ya);
+          if (u + 2 < kSet) read_y(ya, j0 + u + 2);
+          fma_chunk(set[u + 1], yb);
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < kSet; ++u) use_chunk(set[u], j0 + u);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    constexpr int kRing = 4 * kSet;
+    const int d4_main = d4 / kRing * kRing;  // chunks that go through the four sets; the rest one at a time
+    if (d4_main) {  // uniform
+      float4 s0[kSet], s1[kSet], s2[kSet], s3[kSet];
+      load_set(s0, 0);
+      load_set(s1, kSet);
+      load_set(s2, 2 * kSet);
+      int j = 0;
+#pragma unroll 1
+      for (; j + kRing < d4_main; j += kRing) {
+        load_set(s3, j + 3 * kSet);
+        use_set(s0, j);
+        load_set(s0, j + kRing);
+        use_set(s1, j + kSet);
+        load_set(s1, j + kRing + kSet);
+        use_set(s2, j + 2 * kSet);
+        load_set(s2, j + kRing + 2 * kSet);
+        use_set(s3, j + 3 * kSet);
+      }
+      load_set(s3, j + 3 * kSet);
+      use_set(s0, j);
+      use_set(s1, j + kSet);
+      use_set(s2, j + 2 * kSet);
+      use_set(s3, j + 3 * kSet);
     }
+    for (int j = d4_main; j < d4; ++j) use_chunk(col[(size_t)j * cstride], j);
     if (ARGMIN) {
 #pragma unroll
       for (int v = 0; v < VT; ++v) {
@@ -145,6 +215,19 @@ __global__ __launch_bounds__(kCoarseThreads) void k_coarse(
       }
     }
   }
+}
+
+// once per set_centroids: the transposed copy the kernel above streams
+__global__ __launch_bounds__(256) void k_centroid_transpose(Dev D) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= (int64_t)D.nlist * D.d4) return;
+  const int j = (int)(t / D.nlist), c = (int)(t % D.nlist);  // consecutive threads write consecutive 16 bytes
+  reinterpret_cast<float4 *>(D.centroids_t)[t] = reinterpret_cast<const float4 *>(D.centroids)[(size_t)c * D.d4 + j];
+}
+
+void launch_centroid_transpose(const Dev &D, hipStream_t s) {
+  const int64_t items = (int64_t)D.nlist * D.d4;
+  hipLaunchKernelGGL(k_centroid_transpose, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, s, D);
 }
 
 template <bool ARGMIN>

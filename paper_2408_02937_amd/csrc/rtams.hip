@@ -39,7 +39,7 @@ inline size_t up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Byte offsets of everything in front of the blocks.
 struct Layout {
-  size_t ctrl, hook, centroids, cnorm, csplit, codebooks, codebooks_t, tc_min, tc_cnt, tc_col, tc_val, ins_ysplit, ins_ynorm, tile_rows, reserved_len, visible_len, online, nblk, exceed, seg_dir;
+  size_t ctrl, hook, centroids, centroids_t, cnorm, csplit, codebooks, codebooks_t, tc_min, tc_cnt, tc_col, tc_val, ins_ysplit, ins_ynorm, tile_rows, reserved_len, visible_len, online, nblk, exceed, seg_dir;
   size_t ins_assign, ins_did, ins_pscore, ins_pidx, part_cap;
   size_t rearr_head, rearr_arrays;
   size_t fixed_end;          // end of the part that does not depend on the block count
@@ -93,6 +93,7 @@ void lay_out(const rtams_config *c, int64_t blocks, size_t pool_bytes, Layout *L
   L->ctrl = take(sizeof(Ctrl));
   L->hook = take(kHookBytes);
   L->centroids = take(nl * c->d * sizeof(float));
+  L->centroids_t = take(nl * c->d * sizeof(float));
   L->cnorm = take(nl * sizeof(float));
   L->csplit = take(nl * (size_t)((c->d + 31) / 32) * 4 * 32);
   L->codebooks = take(c->pq_m > 0 ? (size_t)256 * c->d * sizeof(float) : 0);
@@ -473,6 +474,7 @@ int rtams_create(const rtams_config *cfg, rtams_index **out) {
   D.blocks = base + L.blocks;
   D.ctrl = reinterpret_cast<Ctrl *>(base + L.ctrl);
   D.centroids = reinterpret_cast<float *>(base + L.centroids);
+  D.centroids_t = reinterpret_cast<float *>(base + L.centroids_t);
   D.cnorm = reinterpret_cast<float *>(base + L.cnorm);
   D.csplit = reinterpret_cast<u32x4 *>(base + L.csplit);
   D.dgroups = (cfg->d + 31) / 32 * 4;
@@ -649,6 +651,7 @@ int rtams_set_centroids(rtams_index *ix, const float *d_centroids, void *hip_str
   HIP_TRY(hipMemcpyAsync(ix->dev.centroids, d_centroids, (size_t)ix->cfg.nlist * ix->cfg.d * 4,
                          hipMemcpyDeviceToDevice, s));
   launch_centroid_norms(ix->dev, s);
+  launch_centroid_transpose(ix->dev, s);
   HIP_TRY(hipGetLastError());
   ix->has_centroids = true;
   return RTAMS_OK;

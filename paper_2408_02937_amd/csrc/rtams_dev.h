@@ -79,6 +79,7 @@ struct Dev {
   Ctrl *ctrl;
   HostMirror *mirror;       // pinned host memory, device-visible
   float *centroids;         // [nlist][d]
+  float *centroids_t;       // the same numbers as [d / 4][nlist] chunks of 4 coordinates: chunk j of consecutive centroids side by side
   float *cnorm;             // [nlist] squared norms of the centroids (fp32)
   u32x4 *csplit;            // [nlist][dgroups][2] the centroids as bf16 halves: per group of 8 coordinates the 8 hi, then the 8 lo
   int32_t dgroups;          // groups of 8 coordinates of a split row, padded with zeros to whole steps of 32 coordinates: 4 ceil(d / 32)

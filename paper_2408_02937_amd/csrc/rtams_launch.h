@@ -138,6 +138,7 @@ __host__ __device__ inline float coarse_band(int d, float norms) {
   return (8.f * (float)(d + 4) * 5.9604645e-8f + 8.f * 1.52587890625e-5f) * norms;
 }
 void launch_centroid_norms(const Dev &D, hipStream_t s);  // and the centroids' split form
+void launch_centroid_transpose(const Dev &D, hipStream_t s);  // the copy the exact coarse kernel streams
 // (`split` takes the n rows as bf16 halves, [n][dgroups][2] 16-byte words; `norms` their n squared norms)
 void launch_coarse_mfma(const Dev &D, int64_t n, const float *Y, u32x4 *split, float *approx,
                         unsigned long long *cursor_to_clear, uint32_t *zero, int zero_n, hipStream_t s);
