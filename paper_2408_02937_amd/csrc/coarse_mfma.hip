@@ -344,28 +344,35 @@ __global__ __launch_bounds__(kMfmaThreads, kVB == 2 ? 3 : 2) void k_coarse_mfma(
 // scored in the fixed double arithmetic and the best is taken, ties to the
 // lowest index; then the next position of the list ("did = atomicAdd(nl_k, 1)").
 __device__ inline double exact_score(const Dev &D, const float *__restrict__ y, int c) {
-  // the fixed arithmetic of coarse.hip: one double FMA per dimension, dimensions in order
-  // (loaded four at a time)
+  // the fixed arithmetic of coarse.hip: one double FMA per dimension, dimensions in order; the
+  // 16-byte loads run eight chunks ahead of the chain (a load per turn of the chain, waited for each
+  // time, made the chain a sequence of trips to memory)
   const float4 *row4 = reinterpret_cast<const float4 *>(D.centroids + (size_t)c * D.d);
   const float4 *y4 = reinterpret_cast<const float4 *>(y);
+  const bool l2 = D.metric == 0;
   double acc = 0.0;
-  if (D.metric == 0) {
-    for (int j = 0; j < D.d4; ++j) {
-      const float4 a = y4[j], b = row4[j];
+  auto chain = [&](const float4 &a, const float4 &b) {
+    if (l2) {
       double t = (double)a.x - (double)b.x; acc = __builtin_fma(t, t, acc);
       t = (double)a.y - (double)b.y; acc = __builtin_fma(t, t, acc);
       t = (double)a.z - (double)b.z; acc = __builtin_fma(t, t, acc);
       t = (double)a.w - (double)b.w; acc = __builtin_fma(t, t, acc);
-    }
-  } else {
-    for (int j = 0; j < D.d4; ++j) {
-      const float4 a = y4[j], b = row4[j];
+    } else {
       acc = __builtin_fma((double)a.x, (double)b.x, acc);
       acc = __builtin_fma((double)a.y, (double)b.y, acc);
       acc = __builtin_fma((double)a.z, (double)b.z, acc);
       acc = __builtin_fma((double)a.w, (double)b.w, acc);
     }
+  };
+  int j = 0;
+  for (; j + 8 <= D.d4; j += 8) {
+    float4 a[8], b[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { a[u] = y4[j + u]; b[u] = row4[j + u]; }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) chain(a[u], b[u]);
   }
+  for (; j < D.d4; ++j) chain(y4[j], row4[j]);
   return acc;
 }
 
