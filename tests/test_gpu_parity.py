@@ -594,3 +594,57 @@ def test_add_learns_the_blocks_left_from_the_device_s_reports_without_waiting():
     assert_lists_equal(g, o)
     g.validate()
     g.close()
+
+
+def test_centroids_set_twice_replace_every_copy_the_kernels_read():
+    """Before the first vector is in, the centroids may be set again.  The library keeps them row by
+    row (exact rescoring), transposed (the exact coarse kernel), as bf16 halves and as squared norms
+    (the matrix-core filter): assignments and probe sets must follow the SECOND set on every path,
+    exact kernel alone and filter in front of it."""
+    w = synth.gaussian_l2("twice", 91, d=48, n_base=3000, n_centres=40, nlist=130, block_vecs=64,
+                          n_queries=64, n_inserts=64)
+    g, o = make_pair(w, max_batch=64, max_k=16, max_nprobe=16)
+    first = np.ascontiguousarray(w.base[::-1][:w.nlist] * 3.0 + 1.0)  # nothing like the real ones
+    g.set_centroids(dev(first))
+    g.set_centroids(dev(w.centroids))
+    ref_assign = o.assign(w.base[:2000])
+    ref_probe = o.probe(w.queries, 16)
+    for mfma in (0, 2):
+        g.set_param("use_mfma", mfma)
+        assert np.array_equal(g.assign(dev(w.base[:2000])).cpu().numpy(), ref_assign), f"use_mfma={mfma}: assignment"
+        assert np.array_equal(g.assign(dev(w.base[:3])).cpu().numpy(), ref_assign[:3]), f"use_mfma={mfma}: small batch"
+        assert np.array_equal(g.probe(dev(w.queries), 16).cpu().numpy(), ref_probe), f"use_mfma={mfma}: probes"
+        assert np.array_equal(g.probe(dev(w.queries[:1]), 16).cpu().numpy(), ref_probe[:1]), f"use_mfma={mfma}: one query"
+    g.set_param("use_mfma", 1)
+    g.add(dev(w.base))
+    o.add(w.base)
+    with pytest.raises(rtams.RtamsError) as e:  # once vectors are in, the centroids stay
+        g.set_centroids(dev(first))
+    assert e.value.code == rtams.ESTATE
+    assert_lists_equal(g, o)
+    g.close()
+
+
+def test_timed_scans_are_counted_by_the_kernel_that_ran(loaded):
+    """The benchmark names the scan kernel of its roofline from these counts."""
+    w, g, o, _ = loaded
+    q = dev(w.queries[:64])
+    g.scan_kernels(reset=True)
+    g.scan_time(reset=True)
+    g.set_param("profile_scan", 1)
+    try:
+        for mode, name in ((2, "k_scan_mm"), (0, "k_scan")):
+            g.set_param("scan_mfma", mode)
+            for _ in range(3):
+                g.search(q, w.k, w.nprobe)
+            torch.cuda.synchronize()
+            got = g.scan_kernels(reset=True)
+            assert got[name] == 3 and sum(got.values()) == 3, (mode, got)
+        ms, n = g.scan_time(reset=True)
+        assert n == 6 and ms > 0.0
+    finally:
+        g.set_param("profile_scan", 0)
+        g.set_param("scan_mfma", 1)
+    g.search(q, w.k, w.nprobe)  # not timed: not counted
+    torch.cuda.synchronize()
+    assert sum(g.scan_kernels().values()) == 0
