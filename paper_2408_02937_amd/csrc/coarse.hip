@@ -15,19 +15,31 @@ int coarse_vt(int d) { return d <= 768 ? 8 : d <= 1536 ? 4 : 2; }
 // centroid whether a vector sits in it or not, and a batch of a few tiles leaves most of the chip
 // idle (one workgroup per tile and centroid split).  The largest tile that still yields a
 // workgroup per compute unit, else single vectors.
-static int coarse_vt_for(const Dev &D, int64_t n) {
+// Every multiply-add takes one coordinate of a vector out of LDS, the same for the whole wavefront,
+// and with eight vectors to a thread the four wavefronts of a CU ask LDS for more than it returns
+// (measured: 64 x 8,192 x 768 in 65 us, 15 % of the double-precision rate).  So the largest shape is
+// four vectors against TWO centroids per thread: the same eight chains, the same number of
+// workgroups, half the reads of LDS per multiply-add.
+struct CoarseShape {
+  int vt;  // vectors of a workgroup's tile
+  int nc;  // centroids a thread takes at a time
+};
+static CoarseShape coarse_shape(const Dev &D, int64_t n) {
   const int64_t max_s = (D.nlist + kCoarseThreads - 1) / kCoarseThreads;
   for (int vt = coarse_vt(D.d); vt > 1; vt /= 2)
-    if ((n + vt - 1) / vt * max_s >= 256) return vt;
-  return 1;
+    if ((n + vt - 1) / vt * max_s >= 256) {
+      if (vt >= 4 && D.nlist >= 2 * kCoarseThreads) return {vt / 2, 2};
+      return {vt, 1};
+    }
+  return {1, 1};
 }
 
 // How many workgroups share the centroids of one vector tile, so that a small
 // batch still spreads over the chip.
 int coarse_splits(const Dev &D, int64_t n, size_t part_cap) {
-  int vt = coarse_vt_for(D, n);
-  int64_t tiles = (n + vt - 1) / vt;
-  int max_s = (D.nlist + kCoarseThreads - 1) / kCoarseThreads;
+  const CoarseShape sh = coarse_shape(D, n);
+  int64_t tiles = (n + sh.vt - 1) / sh.vt;
+  int max_s = (D.nlist + sh.nc * kCoarseThreads - 1) / (sh.nc * kCoarseThreads);
   int64_t want = (1024 + tiles - 1) / tiles;
   int64_t s = want < 1 ? 1 : want;
   if (s > max_s) s = max_s;
@@ -43,9 +55,9 @@ __device__ inline bool better_pair(int metric, double a, int ia, double b, int i
 }
 
 // One workgroup: VT vectors (converted to double in LDS) against a range of
-// centroids, one centroid row per thread at a time.  ARGMIN selects the
-// epilogue: the best centroid of the range per vector, or all scores.
-template <int METRIC, int VT, bool ARGMIN>
+// centroids, NC centroids per thread at a time (c and c + 256).  ARGMIN selects
+// the epilogue: the best centroid of the range per vector, or all scores.
+template <int METRIC, int VT, int NC, bool ARGMIN>
 __global__ __launch_bounds__(kCoarseThreads) void k_coarse(
     Dev D, int64_t n, const float *__restrict__ Y, int splits, double *__restrict__ scores,
     double *__restrict__ pscore, int32_t *__restrict__ pidx, unsigned long long *cursor_to_clear,
@@ -72,7 +84,8 @@ __global__ __launch_bounds__(kCoarseThreads) void k_coarse(
   __syncthreads();
 
   // centroid range of this split, in units of one row per thread
-  const int per = ((D.nlist + splits - 1) / splits + kCoarseThreads - 1) / kCoarseThreads * kCoarseThreads;
+  constexpr int kStep = NC * kCoarseThreads;  // centroids the workgroup takes at a time
+  const int per = ((D.nlist + splits - 1) / splits + kStep - 1) / kStep * kStep;
   const int c_begin = split * per;
   const int c_end = min(D.nlist, c_begin + per);
 
@@ -88,17 +101,24 @@ __global__ __launch_bounds__(kCoarseThreads) void k_coarse(
   // what hides the trips to memory is how far ahead of the chain the loads run: four sets of kSet
   // chunks go round, three of them in flight while the fourth is used up (a single query against
   // thousands of centroids is nothing but such chains, a few per CU).
-  constexpr int kSet = VT <= 2 ? 8 : 4;
+  constexpr int kSet = VT <= 2 && NC == 1 ? 8 : 4;
   const float4 *CT = reinterpret_cast<const float4 *>(D.centroids_t);
   const size_t cstride = (size_t)D.nlist;
-  for (int c = c_begin + threadIdx.x; c < c_end; c += kCoarseThreads) {
-    double acc[VT];
+  for (int c = c_begin + threadIdx.x; c < c_end; c += kStep) {
+    double acc[NC][VT];
 #pragma unroll
-    for (int v = 0; v < VT; ++v) acc[v] = 0.0;
-    const float4 *col = CT + c;
-    auto load_set = [&](float4 *set, int j0) {
+    for (int e = 0; e < NC; ++e)
 #pragma unroll
-      for (int u = 0; u < kSet; ++u) set[u] = col[(size_t)(j0 + u) * cstride];
+      for (int v = 0; v < VT; ++v) acc[e][v] = 0.0;
+    // (a second centroid past the range reads the last centroid: its scores are dropped below)
+    const float4 *col[NC];
+#pragma unroll
+    for (int e = 0; e < NC; ++e) col[e] = CT + min(c + e * kCoarseThreads, D.nlist - 1);
+    auto load_set = [&](float4 (*set)[kSet], int j0) {
+#pragma unroll
+      for (int e = 0; e < NC; ++e)
+#pragma unroll
+        for (int u = 0; u < kSet; ++u) set[e][u] = col[e][(size_t)(j0 + u) * cstride];
       __builtin_amdgcn_sched_barrier(0);  // the loads go out here, not where they are used
     };
     // the vectors' coordinates of chunk j, out of LDS
@@ -109,53 +129,55 @@ __global__ __launch_bounds__(kCoarseThreads) void k_coarse(
         y[v][0] = p[0]; y[v][1] = p[1]; y[v][2] = p[2]; y[v][3] = p[3];
       }
     };
-    auto fma_chunk = [&](const float4 &cv, const double (*y)[4]) {
+    auto fma_chunk = [&](int e, const float4 &cv, const double (*y)[4]) {
       const double c0 = (double)cv.x, c1 = (double)cv.y, c2 = (double)cv.z, c3 = (double)cv.w;
 #pragma unroll
       for (int v = 0; v < VT; ++v) {
         if (METRIC == 0) {
-          double t0 = y[v][0] - c0; acc[v] = __builtin_fma(t0, t0, acc[v]);
-          double t1 = y[v][1] - c1; acc[v] = __builtin_fma(t1, t1, acc[v]);
-          double t2 = y[v][2] - c2; acc[v] = __builtin_fma(t2, t2, acc[v]);
-          double t3 = y[v][3] - c3; acc[v] = __builtin_fma(t3, t3, acc[v]);
+          double t0 = y[v][0] - c0; acc[e][v] = __builtin_fma(t0, t0, acc[e][v]);
+          double t1 = y[v][1] - c1; acc[e][v] = __builtin_fma(t1, t1, acc[e][v]);
+          double t2 = y[v][2] - c2; acc[e][v] = __builtin_fma(t2, t2, acc[e][v]);
+          double t3 = y[v][3] - c3; acc[e][v] = __builtin_fma(t3, t3, acc[e][v]);
         } else {
-          acc[v] = __builtin_fma(y[v][0], c0, acc[v]);
-          acc[v] = __builtin_fma(y[v][1], c1, acc[v]);
-          acc[v] = __builtin_fma(y[v][2], c2, acc[v]);
-          acc[v] = __builtin_fma(y[v][3], c3, acc[v]);
+          acc[e][v] = __builtin_fma(y[v][0], c0, acc[e][v]);
+          acc[e][v] = __builtin_fma(y[v][1], c1, acc[e][v]);
+          acc[e][v] = __builtin_fma(y[v][2], c2, acc[e][v]);
+          acc[e][v] = __builtin_fma(y[v][3], c3, acc[e][v]);
         }
       }
-    };
-    auto use_chunk = [&](const float4 &cv, int j) {
-      double y[VT][4];
-      read_y(y, j);
-      fma_chunk(cv, y);
     };
     // With one or two vectors to a thread a chunk is four or eight dependent multiply-adds, and a trip
     // to LDS in front of each chunk would take longer than they do: the coordinates of the next
     // chunk are asked for before this one is worked on.
     constexpr bool kAhead = VT <= 2;
-    auto use_set = [&](const float4 *set, int j0) {
+    auto use_set = [&](const float4 (*set)[kSet], int j0) {
       if (kAhead) {
         double ya[VT][4], yb[VT][4];
         read_y(ya, j0);
 #pragma unroll
         for (int u = 0; u < kSet; u += 2) {
           read_y(yb, j0 + u + 1);
-          fma_chunk(set[u], ya);
+#pragma unroll
+          for (int e = 0; e < NC; ++e) fma_chunk(e, set[e][u], ya);
           if (u + 2 < kSet) read_y(ya, j0 + u + 2);
-          fma_chunk(set[u + 1], yb);
+#pragma unroll
+          for (int e = 0; e < NC; ++e) fma_chunk(e, set[e][u + 1], yb);
         }
       } else {
 #pragma unroll
-        for (int u = 0; u < kSet; ++u) use_chunk(set[u], j0 + u);
+        for (int u = 0; u < kSet; ++u) {
+          double y[VT][4];
+          read_y(y, j0 + u);  // once for the thread's centroids
+#pragma unroll
+          for (int e = 0; e < NC; ++e) fma_chunk(e, set[e][u], y);
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
     };
     constexpr int kRing = 4 * kSet;
     const int d4_main = d4 / kRing * kRing;  // chunks that go through the four sets; the rest one at a time
     if (d4_main) {  // uniform
-      float4 s0[kSet], s1[kSet], s2[kSet], s3[kSet];
+      float4 s0[NC][kSet], s1[NC][kSet], s2[NC][kSet], s3[NC][kSet];
       load_set(s0, 0);
       load_set(s1, kSet);
       load_set(s2, 2 * kSet);
@@ -177,18 +199,28 @@ __global__ __launch_bounds__(kCoarseThreads) void k_coarse(
       use_set(s2, j + 2 * kSet);
       use_set(s3, j + 3 * kSet);
     }
-    for (int j = d4_main; j < d4; ++j) use_chunk(col[(size_t)j * cstride], j);
-    if (ARGMIN) {
+    for (int j = d4_main; j < d4; ++j) {
+      double y[VT][4];
+      read_y(y, j);
 #pragma unroll
-      for (int v = 0; v < VT; ++v) {
-        const bool take = better_pair(METRIC, acc[v], c, best_s[v], best_i[v]);
-        best_s[v] = take ? acc[v] : best_s[v];
-        best_i[v] = take ? c : best_i[v];
+      for (int e = 0; e < NC; ++e) fma_chunk(e, col[e][(size_t)j * cstride], y);
+    }
+#pragma unroll
+    for (int e = 0; e < NC; ++e) {
+      const int ce = c + e * kCoarseThreads;
+      if (ce >= c_end) break;
+      if (ARGMIN) {
+#pragma unroll
+        for (int v = 0; v < VT; ++v) {
+          const bool take = better_pair(METRIC, acc[e][v], ce, best_s[v], best_i[v]);
+          best_s[v] = take ? acc[e][v] : best_s[v];
+          best_i[v] = take ? ce : best_i[v];
+        }
+      } else {
+#pragma unroll
+        for (int v = 0; v < VT; ++v)
+          if (v0 + v < n) scores[(size_t)(v0 + v) * D.nlist + ce] = acc[e][v];
       }
-    } else {
-#pragma unroll
-      for (int v = 0; v < VT; ++v)
-        if (v0 + v < n) scores[(size_t)(v0 + v) * D.nlist + c] = acc[v];
     }
   }
 
@@ -235,16 +267,19 @@ static void launch_coarse(const Dev &D, int64_t n, const float *Y, int splits, d
                           double *pscore, int32_t *pidx, unsigned long long *cursor, uint32_t *zero,
                           int zero_n, hipStream_t s) {
   if (n <= 0) return;
-  int vt = coarse_vt_for(D, n);
+  const CoarseShape sh = coarse_shape(D, n);
+  const int vt = sh.vt;
   dim3 grid((unsigned)((n + vt - 1) / vt), (unsigned)splits);
   size_t lds = (size_t)vt * D.d * sizeof(double);
-#define RTAMS_GO(M, V) \
-  hipLaunchKernelGGL((k_coarse<M, V, ARGMIN>), grid, dim3(kCoarseThreads), lds, s, D, n, Y, splits, \
+#define RTAMS_GO(M, V, N_) \
+  hipLaunchKernelGGL((k_coarse<M, V, N_, ARGMIN>), grid, dim3(kCoarseThreads), lds, s, D, n, Y, splits, \
                      scores, pscore, pidx, cursor, zero, zero_n)
   if (D.metric == 0) {
-    if (vt == 8) RTAMS_GO(0, 8); else if (vt == 4) RTAMS_GO(0, 4); else if (vt == 2) RTAMS_GO(0, 2); else RTAMS_GO(0, 1);
+    if (vt == 8) RTAMS_GO(0, 8, 1); else if (vt == 4 && sh.nc == 2) RTAMS_GO(0, 4, 2); else if (vt == 4) RTAMS_GO(0, 4, 1);
+    else if (vt == 2 && sh.nc == 2) RTAMS_GO(0, 2, 2); else if (vt == 2) RTAMS_GO(0, 2, 1); else RTAMS_GO(0, 1, 1);
   } else {
-    if (vt == 8) RTAMS_GO(1, 8); else if (vt == 4) RTAMS_GO(1, 4); else if (vt == 2) RTAMS_GO(1, 2); else RTAMS_GO(1, 1);
+    if (vt == 8) RTAMS_GO(1, 8, 1); else if (vt == 4 && sh.nc == 2) RTAMS_GO(1, 4, 2); else if (vt == 4) RTAMS_GO(1, 4, 1);
+    else if (vt == 2 && sh.nc == 2) RTAMS_GO(1, 2, 2); else if (vt == 2) RTAMS_GO(1, 2, 1); else RTAMS_GO(1, 1, 1);
   }
 #undef RTAMS_GO
 }
