@@ -128,10 +128,10 @@ void launch_coarse_argmin(const Dev &D, int64_t n, const float *Y, int splits, d
 // the refinement (measured crossovers on MI355X, d = 128 and 768: about 1 M (query,
 // centroid) pairs for a search and for an assignment alike).
 inline bool mfma_pays_for_search(int64_t nq, int64_t nlist) { return nq >= 32 && nq * nlist >= (int64_t)1 << 20; }
-// (with 8192 centroids or more, whose tiles alone fill the chip, an assignment pays from half as many pairs)
-inline bool mfma_pays_for_assign(int64_t m, int64_t nlist) {
-  return m >= 32 && m * nlist >= (nlist >= 8192 ? (int64_t)1 << 19 : (int64_t)1 << 20);
-}
+// (an assignment used to pay from half as many pairs where there are 8192 centroids or more; since the
+// exact kernel takes two centroids to a thread it does not: 64 vectors against 8,192 x 768 centroids
+// are assigned at 0.91 M vectors/s by the exact kernel alone and at 0.78 M through the filter)
+inline bool mfma_pays_for_assign(int64_t m, int64_t nlist) { return m >= 32 && m * nlist >= (int64_t)1 << 20; }
 // Twice the error bound of an approximate score, for a vector of squared norm |y|^2 (norms = |y|^2 + max |c|^2):
 // the exact best lies among the centroids whose approximation is within this of the smallest one.
 __host__ __device__ inline float coarse_band(int d, float norms) {
