@@ -17,9 +17,10 @@ int coarse_vt(int d) { return d <= 768 ? 8 : d <= 1536 ? 4 : 2; }
 // workgroup per compute unit, else single vectors.
 // Every multiply-add takes one coordinate of a vector out of LDS, the same for the whole wavefront,
 // and with eight vectors to a thread the four wavefronts of a CU ask LDS for more than it returns
-// (measured: 64 x 8,192 x 768 in 65 us, 15 % of the double-precision rate).  So the largest shape is
-// four vectors against TWO centroids per thread: the same eight chains, the same number of
-// workgroups, half the reads of LDS per multiply-add.
+// (measured: 64 x 8,192 x 768 in 65 us, 15 % of the double-precision rate).  So where that rule picks
+// eight or four vectors and there are 512 centroids or more, a thread takes half as many vectors
+// against TWO centroids: the same number of chains per thread and of workgroups, half the reads of
+// LDS per multiply-add (47 us for that batch).
 struct CoarseShape {
   int vt;  // vectors of a workgroup's tile
   int nc;  // centroids a thread takes at a time
